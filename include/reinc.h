@@ -1,0 +1,213 @@
+/*
+ * reinc.h -- C ABI of libreinc_hip.so: the single-GPU hot path of incremental dynamic-GNN training
+ * (ReInc, arXiv 2501.15348) written for AMD MI355X (gfx950).
+ *
+ * The method (paper Section 3.2): a dynamic graph is a series of snapshots G_t with node features
+ * F_t over a fixed node set.  Instead of aggregating every snapshot from scratch (Eq. 1,
+ * Agg_t = F_t *aggr G_t) the aggregate of snapshot t is derived from the cached aggregate of
+ * snapshot t-1 and two small delta graphs (Eq. 2, Agg_t = Agg_{t-1} - F_{t-1} *aggr G-_t + F_t *aggr G+_t).
+ * The aggregate feeds a GCN update (linear map + ReLU, Section 3.5 Listing 1) and, per node, a GRU
+ * or LSTM over the snapshots of a sliding window (Section 2.2).
+ *
+ * Conventions
+ *   - An edge (u -> v) goes from source u to target v and the TARGET aggregates the source's row.
+ *     Adjacency is stored as CSR by destination: row v lists the sources of v's in-edges, ascending.
+ *   - A snapshot is a SET of edges with u != v.  self_loop = 1 adds the identity to every snapshot.
+ *   - deg_t(v) = self_loop + in-degree of v in snapshot t.
+ *     Y_t = P_t X_t,  S_t = (A_t + self_loop I) Y_t,  Agg_t = Q_t S_t  with
+ *       SUM : P = Q = I        MEAN: P = I, Q = 1/deg        SYM : P = Q = deg^(-1/2)      (deg = 0 -> 0)
+ *   - All matrices are dense row-major.  Node ids are int32, 0 <= id < num_nodes <= 2^30.
+ *     Row pointers are int64.  Feature storage is fp32 or bf16 (raw 16-bit patterns); every
+ *     accumulator, aggregate, activation, weight and gradient is fp32.
+ *   - "device" pointers are HIP device memory of the context's GPU; "host" pointers are ordinary
+ *     host memory.  The caller owns every pointer it passes.  The library owns only what it carves
+ *     out of the caller-provided arena and its host-side bookkeeping (released by reinc_destroy).
+ *     No entry point calls hipMalloc or hipFree.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls marked ASYNC only
+ *     enqueue work on it; calls marked SYNC return after the device work has finished.
+ *   - Every function returns REINC_OK or a negative code and never throws or aborts;
+ *     reinc_last_error() gives the text of the last failure on that context.
+ *
+ * Flat parameter / gradient vector used by the window calls (fp32, device):
+ *   for l = 1..num_gcn_layers:  W_l [dims[l-1], dims[l]],  b_l [dims[l]]
+ *   then the recurrent cell:    W_i [dims[last], K*H],  W_h [H, K*H],  b_i [K*H],  b_h [K*H]
+ *   with K = 3 (GRU, gate order r,z,n) or 4 (LSTM, gate order i,f,g,o) and H = rnn_hidden.
+ */
+#ifndef REINC_H
+#define REINC_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define REINC_OK 0
+#define REINC_E_ARG (-1)         /* bad argument (null pointer, id out of range, bad size) */
+#define REINC_E_STATE (-2)       /* call out of order (snapshot not loaded, deltas not built, ...) */
+#define REINC_E_NOMEM (-3)       /* the arena is too small */
+#define REINC_E_HIP (-4)         /* a HIP call failed */
+#define REINC_E_UNSUPPORTED (-5) /* valid request that this build does not implement */
+
+#define REINC_AGG_SUM 0
+#define REINC_AGG_MEAN 1
+#define REINC_AGG_SYM 2
+
+#define REINC_RNN_GRU 0
+#define REINC_RNN_LSTM 1
+
+#define REINC_F32 0
+#define REINC_BF16 1
+
+#define REINC_MAX_GCN_LAYERS 3
+
+typedef struct reinc_ctx reinc_ctx; /* opaque */
+
+typedef struct reinc_config {
+    uint32_t struct_size;   /* sizeof(reinc_config): versions the struct */
+    int32_t device;         /* HIP device ordinal */
+    int64_t num_nodes;      /* N, fixed over the sequence (isolated nodes pad a varying node set, Section 3.2) */
+    int32_t num_snapshots;  /* T */
+    int32_t num_gcn_layers; /* 1..REINC_MAX_GCN_LAYERS */
+    int32_t dims[REINC_MAX_GCN_LAYERS + 1]; /* dims[0] = feature width, dims[l] = width after layer l */
+    int32_t rnn_kind;       /* REINC_RNN_* */
+    int32_t rnn_hidden;     /* H */
+    int32_t agg_kind;       /* REINC_AGG_* */
+    int32_t self_loop;      /* 0 or 1 */
+    int32_t feat_dtype;     /* REINC_F32 or REINC_BF16: storage type of the node features */
+    float fallback_ratio;   /* window driver: use the from-scratch path for step t when
+                               effective_delta_edges(t) / |E_t| exceeds this (Section 3.2, "user-defined
+                               threshold").  < 0: never fall back.  0: always from scratch. */
+    void *arena;            /* device memory owned by the caller, 256-byte aligned */
+    uint64_t arena_bytes;
+} reinc_config;
+
+/* Sizes of the delta structures of one step t-1 -> t (all counts of entries). */
+typedef struct reinc_delta_info {
+    int64_t num_edges_prev, num_edges_cur; /* |E_{t-1}|, |E_t| */
+    int64_t n_ins, n_del;                  /* |E_t \ E_{t-1}|, |E_{t-1} \ E_t| */
+    int64_t n_changed;                     /* |C_t|: nodes whose scaled feature row Y changed */
+    int64_t n_fchg_entries;                /* entries of (A_t + self_loop I) restricted to columns in C_t */
+    int64_t n_rows;                        /* |R_t|: rows of S that can differ from step t-1 */
+    int64_t n_entries;                     /* n_ins + n_del + n_fchg_entries: effective delta edges */
+} reinc_delta_info;
+
+typedef struct reinc_stats {
+    int64_t arena_used, arena_peak;      /* bytes */
+    int64_t global_hits, global_misses;  /* layer-1 aggregate cache (window driver) */
+    int64_t steps_incremental, steps_full, steps_fallback;
+    int64_t delta_entries_processed;     /* effective delta edges consumed by incremental steps */
+    int64_t local_bytes;                 /* bytes of per-window activations currently held */
+} reinc_stats;
+
+const char *reinc_version(void);
+
+/* Creates a context on cfg->device.  Nothing is allocated on the device: all device storage is carved
+ * out of cfg->arena.  SYNC. */
+int reinc_create(reinc_ctx **out, const reinc_config *cfg);
+int reinc_destroy(reinc_ctx *ctx);
+/* Text of the most recent failure on ctx (valid until the next call on ctx); "" if none. */
+const char *reinc_last_error(const reinc_ctx *ctx);
+/* Arena bytes still free. */
+int reinc_arena_free_bytes(const reinc_ctx *ctx, uint64_t *out);
+
+/* ---- load the snapshot sequence (Section 2.1: snapshots G_t with features F_t) --------------------------
+ * reinc_load_edges: src/dst are HOST arrays of nnz int32 endpoints in any order.  Duplicates and
+ * self-loops are removed; ids outside [0, N) give REINC_E_ARG.  The canonical CSR (by destination) and
+ * CSC (by source) of snapshot t are built on the host and copied into the arena.  SYNC.
+ * Each snapshot is loaded once. */
+int reinc_load_edges(reinc_ctx *ctx, int32_t t, const int32_t *src, const int32_t *dst, int64_t nnz);
+/* X_t = the given [N, dims[0]] matrix (fp32, or bf16 bit patterns when feat_dtype is bf16).
+ * on_device selects whether X is a device or a host pointer.  SYNC. */
+int reinc_load_features_full(reinc_ctx *ctx, int32_t t, const void *X, int on_device);
+/* X_t = X_{t-1} with `rows` (HOST, sorted, unique, nrows entries) replaced by the rows of `vals`
+ * (HOST, [nrows, dims[0]]).  Only the changed rows cross the host-device link (Section 4, delta mode).
+ * Needs X_{t-1}.  SYNC. */
+int reinc_load_features_delta(reinc_ctx *ctx, int32_t t, const int32_t *rows, int64_t nrows, const void *vals);
+
+/* ---- per-snapshot deltas (Section 3.2: delta graphs G-_t, G+_t) ------------------------------------------
+ * Builds, on the device, for step t (1 <= t < T; t < 0 = every step whose inputs are loaded):
+ *   - the insert CSR  E_t \ E_{t-1} and the delete CSR E_{t-1} \ E_t (by destination, ascending columns);
+ *   - the change set C_t = { u : X_t[u] != X_{t-1}[u] bitwise } (plus, for SYM, every u whose degree changed),
+ *     ascending, and dY = P_t X_t - P_{t-1} X_{t-1} on those rows;
+ *   - the merged signed delta rows used by reinc_aggregate_incremental: for each row v, first the inserted
+ *     sources, then the deleted sources, then the sources u in C_t of v's in-edges at t (and v itself when
+ *     self_loop is set and v is in C_t), each group ascending;
+ *   - R_t, the ascending list of rows with at least one entry.
+ * Needs edges and features of snapshots t-1 and t.  SYNC (sizes are read back to carve the arena). */
+int reinc_build_deltas(reinc_ctx *ctx, int32_t t, void *stream);
+int reinc_get_delta_info(reinc_ctx *ctx, int32_t t, reinc_delta_info *out);
+/* Copies the insert (kind 0) or delete (kind 1) CSR of step t to HOST buffers: row_ptr[N+1], col[nnz].
+ * Either buffer may be NULL; *nnz_out (may be NULL) receives the entry count, so a first call with NULL
+ * buffers sizes the second.  SYNC. */
+int reinc_get_delta_csr(reinc_ctx *ctx, int32_t t, int kind, int64_t *row_ptr, int32_t *col, int64_t *nnz_out);
+/* Copies the merged structures of step t to HOST buffers (each may be NULL): entry_ptr[N+1];
+ * entries[n_entries], each (kind << 30) | payload with kind 0 = inserted source id, 1 = deleted source id,
+ * 2 = position in `changed` of a changed source; rows[n_rows]; changed[n_changed].  SYNC. */
+int reinc_get_merged_delta(reinc_ctx *ctx, int32_t t, int64_t *entry_ptr, uint32_t *entries, int32_t *rows,
+                           int32_t *changed);
+/* Copies snapshot t's canonical CSR (transpose = 0) or CSC (transpose = 1) to HOST buffers.  SYNC. */
+int reinc_get_snapshot_csr(reinc_ctx *ctx, int32_t t, int transpose, int64_t *ptr, int32_t *idx, int64_t *nnz_out);
+
+/* ---- aggregation ------------------------------------------------------------------------------------------
+ * reinc_aggregate_full (Section 3.2, Eq. 1), ASYNC.  X: device [N, d] of x_dtype, or NULL for the stored X_t
+ * (then d and x_dtype must match the stored features).  out: device fp32 [N, d].
+ *   transpose = 0:  out = S_t = (A_t + sI) P_t X          (apply_q = 0)
+ *                   out = Agg_t = Q_t S_t                 (apply_q = 1)
+ *   transpose = 1:  out = P_t (A_t + sI)^T (Q_t X)  if apply_q, else P_t (A_t + sI)^T X: the adjoint used
+ *                   by the backward pass (X is then the gradient w.r.t. Agg or S).
+ * d * sizeof(element) must be a power of two between 16 and 1024 bytes. */
+int reinc_aggregate_full(reinc_ctx *ctx, int32_t t, int transpose, const void *X, int x_dtype, int32_t d,
+                         int apply_q, float *out, void *stream);
+/* reinc_aggregate_incremental (Section 3.2, Eq. 2), ASYNC.  Derives S_t of the stored features from
+ * S_{t-1}:  for every row r in R_t
+ *     S_t[r] = S_{t-1}[r] + sum_{inserted u} Y_{t-1}[u] - sum_{deleted u} Y_{t-1}[u] + sum_{changed u} dY[u]
+ * and S_t[r] = S_{t-1}[r] elsewhere.  S_prev, S_out: device fp32 [N, dims[0]].  S_out may be S_prev itself
+ * (in place: only rows in R_t are touched) or a disjoint buffer (all rows are written).  Needs
+ * reinc_build_deltas(t).  agg_out (may be NULL): device fp32 [N, dims[0]], receives Q_t S_t. */
+int reinc_aggregate_incremental(reinc_ctx *ctx, int32_t t, const float *S_prev, float *S_out, float *agg_out,
+                                void *stream);
+
+/* ---- dense steps ------------------------------------------------------------------------------------------
+ * reinc_gcn_transform (Section 3.5, Listing 1: update = ReLU(linear(aggregate))), ASYNC.
+ *   out[n, d_out] = act( (row_scale .* A)[n, d_in] * W[d_in, d_out] + b )
+ * A: device fp32 (a_dtype REINC_F32) or bf16; row_scale: device fp32 [n] or NULL; b: device [d_out] or NULL;
+ * relu: 0/1; out: device fp32. */
+int reinc_gcn_transform(reinc_ctx *ctx, const void *A, int a_dtype, int64_t n, int32_t d_in, int32_t d_out,
+                        const float *row_scale, const float *W, const float *b, int relu, float *out, void *stream);
+/* reinc_rnn_step: one GRU (3 gates) or LSTM (4 gates) step for n independent nodes (Section 2.1: the RNN
+ * runs per node over time; gate counts: Section 3.3), ASYNC.
+ *   GRU : r = sig(x W_ir + b_ir + h W_hr + b_hr), z likewise, n = tanh(x W_in + b_in + r .* (h W_hn + b_hn)),
+ *         h' = (1 - z) .* n + z .* h
+ *   LSTM: (i, f, g, o) = (sig, sig, tanh, sig)(x W_i + b_i + h W_h + b_h),  c' = f .* c + i .* g,  h' = o .* tanh(c')
+ * x [n, d_in], h_prev/h_out [n, H], c_prev/c_out [n, H] (LSTM only, else NULL), W_i [d_in, K*H], W_h [H, K*H],
+ * b_i, b_h [K*H]; all device fp32.  h_prev (and c_prev) may be NULL for a zero state.  h_out may not alias h_prev.
+ * saved (may be NULL): device fp32 [n, 4*H] (GRU: r, z, n, h W_hn + b_hn) or [n, 4*H] (LSTM: i, f, g, o),
+ * kept for the backward pass. */
+int reinc_rnn_step(reinc_ctx *ctx, int rnn_kind, const float *x, int64_t n, int32_t d_in, int32_t H,
+                   const float *h_prev, const float *c_prev, const float *W_i, const float *W_h, const float *b_i,
+                   const float *b_h, float *h_out, float *c_out, float *saved, void *stream);
+
+/* ---- window driver (Section 2.2: a window of L consecutive snapshots is one sample; Section 3.3: caches) -----
+ * reinc_forward_window, ASYNC: runs snapshots t0 .. t0+L-1 through the GCN layers and the recurrent cell
+ * from a zero state.  The layer-1 sums S_t of the stored features are weight-independent; they are kept in
+ * the global cache for every t once computed (by Eq. 2 from S_{t-1} when that is cached and the step is under
+ * fallback_ratio, else by Eq. 1) and reused by every later window.  Per-window activations go to the local
+ * cache and stay there until the next forward call.  target: device [N, H] or NULL;
+ * loss_out: device scalar = mean((h_last - target)^2) (ignored if target is NULL); h_last: device [N, H] or NULL. */
+int reinc_forward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *params, const float *target,
+                         float *loss_out, float *h_last, void *stream);
+/* reinc_backward_window, ASYNC: back-propagation through time for the window of the preceding
+ * reinc_forward_window call (same t0, L, params, target).  grads: device, same layout as params, overwritten. */
+int reinc_backward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *params, const float *target,
+                          float *grads, void *stream);
+/* Drops every cached layer-1 sum (the next windows recompute them). */
+int reinc_cache_clear(reinc_ctx *ctx);
+/* Device pointer of the cached layer-1 sums S_t ([N, dims[0]] fp32) or NULL if not cached. */
+int reinc_cache_peek(reinc_ctx *ctx, int32_t t, const float **S_out);
+int reinc_get_stats(reinc_ctx *ctx, reinc_stats *out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* REINC_H */

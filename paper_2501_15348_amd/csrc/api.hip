@@ -1,0 +1,445 @@
+// C-ABI entry points: context, snapshot store, delta builder, aggregation primitives.
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <new>
+
+#include "ctx.h"
+
+using namespace reinc;
+
+namespace {
+
+hipStream_t as_stream(void *s) { return static_cast<hipStream_t>(s); }
+
+int check_t(reinc_ctx *ctx, int32_t t)
+{
+    if (t < 0 || t >= ctx->cfg.num_snapshots)
+        return ctx->fail(REINC_E_ARG, "snapshot index %d outside [0, %d)", t, ctx->cfg.num_snapshots);
+    return REINC_OK;
+}
+
+template <typename T>
+int upload(reinc_ctx *ctx, T **dst, const T *host, int64_t count, const char *what)
+{
+    *dst = static_cast<T *>(ctx->alloc(uint64_t(std::max<int64_t>(count, 1)) * sizeof(T)));
+    if (!*dst) return ctx->fail(REINC_E_NOMEM, "arena exhausted while storing %s (%lld bytes)", what, (long long)(count * sizeof(T)));
+    if (count > 0) REINC_HIP(ctx, hipMemcpy(*dst, host, size_t(count) * sizeof(T), hipMemcpyHostToDevice));
+    return REINC_OK;
+}
+
+template <typename T>
+int read_back(reinc_ctx *ctx, T *host, const T *dev, int64_t count)
+{
+    if (host && count > 0) REINC_HIP(ctx, hipMemcpy(host, dev, size_t(count) * sizeof(T), hipMemcpyDeviceToHost));
+    return REINC_OK;
+}
+
+float scale_of(int agg, bool target_side, int64_t deg)
+{
+    if (agg == REINC_AGG_SUM) return 1.0f;
+    if (agg == REINC_AGG_MEAN && !target_side) return 1.0f;
+    if (deg <= 0) return 0.0f;
+    if (agg == REINC_AGG_MEAN) return float(1.0 / double(deg));
+    return float(1.0 / std::sqrt(double(deg)));
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *reinc_version(void) { return "reinc-hip 0.1 (gfx950)"; }
+
+int reinc_create(reinc_ctx **out, const reinc_config *cfg)
+{
+    if (!out || !cfg) return REINC_E_ARG;
+    *out = nullptr;
+    if (cfg->struct_size != sizeof(reinc_config)) return REINC_E_ARG;
+    reinc_ctx *ctx = new (std::nothrow) reinc_ctx();
+    if (!ctx) return REINC_E_NOMEM;
+    *out = ctx;  // returned even on failure so that reinc_last_error() can explain; the caller destroys it
+    ctx->cfg = *cfg;
+    const reinc_config &c = ctx->cfg;
+    if (c.num_nodes <= 0 || c.num_nodes > kMaxNodes) return ctx->fail(REINC_E_ARG, "num_nodes must be in [1, 2^30]");
+    if (c.num_snapshots <= 0) return ctx->fail(REINC_E_ARG, "num_snapshots must be positive");
+    if (c.num_gcn_layers < 1 || c.num_gcn_layers > REINC_MAX_GCN_LAYERS)
+        return ctx->fail(REINC_E_ARG, "num_gcn_layers must be in [1, %d]", REINC_MAX_GCN_LAYERS);
+    for (int l = 0; l <= c.num_gcn_layers; ++l)
+        if (c.dims[l] <= 0) return ctx->fail(REINC_E_ARG, "dims[%d] must be positive", l);
+    if (c.rnn_kind != REINC_RNN_GRU && c.rnn_kind != REINC_RNN_LSTM) return ctx->fail(REINC_E_ARG, "bad rnn_kind");
+    if (c.rnn_hidden <= 0) return ctx->fail(REINC_E_ARG, "rnn_hidden must be positive");
+    if (c.agg_kind < REINC_AGG_SUM || c.agg_kind > REINC_AGG_SYM) return ctx->fail(REINC_E_ARG, "bad agg_kind");
+    if (c.self_loop != 0 && c.self_loop != 1) return ctx->fail(REINC_E_ARG, "self_loop must be 0 or 1");
+    if (c.feat_dtype != REINC_F32 && c.feat_dtype != REINC_BF16) return ctx->fail(REINC_E_ARG, "bad feat_dtype");
+    if (!agg_width_supported(c.dims[0], c.feat_dtype == REINC_BF16))
+        return ctx->fail(REINC_E_UNSUPPORTED, "feature row of %d elements: row bytes must be a power of two in [16, 1024]",
+                         c.dims[0]);
+    if (!c.arena || (reinterpret_cast<uintptr_t>(c.arena) & 255)) return ctx->fail(REINC_E_ARG, "arena must be a 256-byte aligned device pointer");
+    REINC_HIP(ctx, hipSetDevice(c.device));
+    ctx->base = static_cast<char *>(c.arena);
+    ctx->size = c.arena_bytes & ~uint64_t(255);
+    ctx->bottom = 0;
+    ctx->top = ctx->size;
+    ctx->snaps.resize(c.num_snapshots);
+    ctx->deltas.resize(c.num_snapshots);
+    ctx->gcache.assign(c.num_snapshots, nullptr);
+    return REINC_OK;
+}
+
+int reinc_destroy(reinc_ctx *ctx)
+{
+    delete ctx;
+    return REINC_OK;
+}
+
+const char *reinc_last_error(const reinc_ctx *ctx) { return ctx ? ctx->err.c_str() : "null context"; }
+
+int reinc_arena_free_bytes(const reinc_ctx *ctx, uint64_t *out)
+{
+    if (!ctx || !out) return REINC_E_ARG;
+    *out = ctx->top - ctx->bottom;
+    return REINC_OK;
+}
+
+// ------------------------------------------------------------------------------------------------ loading
+
+int reinc_load_edges(reinc_ctx *ctx, int32_t t, const int32_t *src, const int32_t *dst, int64_t nnz)
+{
+    if (!ctx) return REINC_E_ARG;
+    REINC_TRY(check_t(ctx, t));
+    if (nnz < 0 || (nnz > 0 && (!src || !dst))) return ctx->fail(REINC_E_ARG, "null edge arrays");
+    Snapshot &sn = ctx->snaps[t];
+    if (sn.edges_loaded) return ctx->fail(REINC_E_STATE, "edges of snapshot %d already loaded", t);
+    const int64_t n = ctx->N();
+    REINC_HIP(ctx, hipSetDevice(ctx->cfg.device));
+    std::vector<uint64_t> keys;
+    keys.reserve(size_t(nnz));
+    for (int64_t i = 0; i < nnz; ++i) {
+        const int64_t u = src[i], v = dst[i];
+        if (u < 0 || u >= n || v < 0 || v >= n)
+            return ctx->fail(REINC_E_ARG, "edge %lld: (%lld -> %lld) outside [0, %lld)", (long long)i, (long long)u,
+                             (long long)v, (long long)n);
+        if (u != v) keys.push_back((uint64_t(v) << 32) | uint64_t(u));
+    }
+    std::sort(keys.begin(), keys.end());
+    keys.erase(std::unique(keys.begin(), keys.end()), keys.end());
+    const int64_t e = int64_t(keys.size());
+    std::vector<int64_t> row_ptr(n + 1, 0), col_ptr(n + 1, 0);
+    std::vector<int32_t> col(e), row(e);
+    for (int64_t i = 0; i < e; ++i) {
+        const int64_t v = int64_t(keys[i] >> 32), u = int64_t(keys[i] & 0xFFFFFFFFu);
+        col[i] = int32_t(u);
+        ++row_ptr[v + 1];
+        ++col_ptr[u + 1];
+    }
+    for (int64_t v = 0; v < n; ++v) {
+        row_ptr[v + 1] += row_ptr[v];
+        col_ptr[v + 1] += col_ptr[v];
+    }
+    {
+        std::vector<int64_t> cursor(col_ptr.begin(), col_ptr.end() - 1);
+        for (int64_t i = 0; i < e; ++i) {  // ascending (v, u): targets land ascending inside every source's list
+            const int64_t v = int64_t(keys[i] >> 32), u = int64_t(keys[i] & 0xFFFFFFFFu);
+            row[cursor[u]++] = int32_t(v);
+        }
+    }
+    std::vector<int32_t> long_rows, long_cols;
+    for (int64_t v = 0; v < n; ++v) {
+        if (row_ptr[v + 1] - row_ptr[v] > kLongRow) long_rows.push_back(int32_t(v));
+        if (col_ptr[v + 1] - col_ptr[v] > kLongRow) long_cols.push_back(int32_t(v));
+    }
+    sn.nnz = e;
+    REINC_TRY(upload(ctx, &sn.row_ptr, row_ptr.data(), n + 1, "row_ptr"));
+    REINC_TRY(upload(ctx, &sn.col, col.data(), e, "col"));
+    REINC_TRY(upload(ctx, &sn.col_ptr, col_ptr.data(), n + 1, "col_ptr"));
+    REINC_TRY(upload(ctx, &sn.row, row.data(), e, "row"));
+    sn.n_long_rows = int32_t(long_rows.size());
+    sn.n_long_cols = int32_t(long_cols.size());
+    REINC_TRY(upload(ctx, &sn.long_rows, long_rows.data(), sn.n_long_rows, "long_rows"));
+    REINC_TRY(upload(ctx, &sn.long_cols, long_cols.data(), sn.n_long_cols, "long_cols"));
+    const int agg = ctx->cfg.agg_kind;
+    if (agg != REINC_AGG_SUM) {
+        std::vector<float> q(n), p;
+        for (int64_t v = 0; v < n; ++v) q[v] = scale_of(agg, true, ctx->cfg.self_loop + row_ptr[v + 1] - row_ptr[v]);
+        REINC_TRY(upload(ctx, &sn.q, q.data(), n, "q"));
+        if (agg == REINC_AGG_SYM) sn.p = sn.q;  // same numbers on both sides
+    }
+    sn.edges_loaded = true;
+    return REINC_OK;
+}
+
+int reinc_load_features_full(reinc_ctx *ctx, int32_t t, const void *X, int on_device)
+{
+    if (!ctx) return REINC_E_ARG;
+    REINC_TRY(check_t(ctx, t));
+    if (!X) return ctx->fail(REINC_E_ARG, "null feature matrix");
+    Snapshot &sn = ctx->snaps[t];
+    if (sn.feats_loaded) return ctx->fail(REINC_E_STATE, "features of snapshot %d already loaded", t);
+    REINC_HIP(ctx, hipSetDevice(ctx->cfg.device));
+    const uint64_t bytes = uint64_t(ctx->N()) * ctx->cfg.dims[0] * ctx->elem_bytes();
+    sn.x = ctx->alloc(bytes);
+    if (!sn.x) return ctx->fail(REINC_E_NOMEM, "arena exhausted while storing features of snapshot %d", t);
+    REINC_HIP(ctx, hipMemcpy(sn.x, X, bytes, on_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice));
+    REINC_HIP(ctx, hipDeviceSynchronize());
+    sn.feats_loaded = true;
+    sn.feats_from_delta = false;
+    return REINC_OK;
+}
+
+int reinc_load_features_delta(reinc_ctx *ctx, int32_t t, const int32_t *rows, int64_t nrows, const void *vals)
+{
+    if (!ctx) return REINC_E_ARG;
+    REINC_TRY(check_t(ctx, t));
+    if (t == 0) return ctx->fail(REINC_E_ARG, "snapshot 0 has no predecessor: load it in full");
+    if (nrows < 0 || (nrows > 0 && (!rows || !vals))) return ctx->fail(REINC_E_ARG, "null row list or values");
+    Snapshot &sn = ctx->snaps[t];
+    const Snapshot &pv = ctx->snaps[t - 1];
+    if (sn.feats_loaded) return ctx->fail(REINC_E_STATE, "features of snapshot %d already loaded", t);
+    if (!pv.feats_loaded) return ctx->fail(REINC_E_STATE, "features of snapshot %d are needed first", t - 1);
+    for (int64_t i = 0; i < nrows; ++i) {
+        if (rows[i] < 0 || rows[i] >= ctx->N()) return ctx->fail(REINC_E_ARG, "feature row id %d out of range", rows[i]);
+        if (i && rows[i] <= rows[i - 1]) return ctx->fail(REINC_E_ARG, "feature row ids must be ascending and unique");
+    }
+    REINC_HIP(ctx, hipSetDevice(ctx->cfg.device));
+    const uint64_t row_bytes = uint64_t(ctx->cfg.dims[0]) * ctx->elem_bytes();
+    sn.x = ctx->alloc(uint64_t(ctx->N()) * row_bytes);
+    if (!sn.x) return ctx->fail(REINC_E_NOMEM, "arena exhausted while storing features of snapshot %d", t);
+    REINC_HIP(ctx, hipMemcpy(sn.x, pv.x, uint64_t(ctx->N()) * row_bytes, hipMemcpyDeviceToDevice));
+    // consecutive ids travel as one copy
+    const char *v = static_cast<const char *>(vals);
+    for (int64_t i = 0; i < nrows;) {
+        int64_t j = i + 1;
+        while (j < nrows && rows[j] == rows[j - 1] + 1) ++j;
+        REINC_HIP(ctx, hipMemcpy(static_cast<char *>(sn.x) + uint64_t(rows[i]) * row_bytes, v + uint64_t(i) * row_bytes,
+                                 uint64_t(j - i) * row_bytes, hipMemcpyHostToDevice));
+        i = j;
+    }
+    REINC_TRY(upload(ctx, &sn.feat_rows, rows, nrows, "feature row ids"));
+    sn.n_feat_rows = nrows;
+    REINC_HIP(ctx, hipDeviceSynchronize());
+    sn.feats_loaded = true;
+    sn.feats_from_delta = true;
+    return REINC_OK;
+}
+
+// ------------------------------------------------------------------------------------------------ deltas
+
+static int build_one(reinc_ctx *ctx, int32_t t, hipStream_t s)
+{
+    const int64_t n = ctx->N();
+    const int32_t d = ctx->cfg.dims[0];
+    const int bf16 = ctx->cfg.feat_dtype == REINC_BF16;
+    const Snapshot &a = ctx->snaps[t - 1];
+    const Snapshot &b = ctx->snaps[t];
+    Delta &dl = ctx->deltas[t];
+    if (dl.built) return REINC_OK;
+    if (!a.edges_loaded || !b.edges_loaded || !a.feats_loaded || !b.feats_loaded)
+        return ctx->fail(REINC_E_STATE, "step %d needs edges and features of snapshots %d and %d", t, t - 1, t);
+    ctx->scratch_reset();
+    const uint64_t mark = ctx->bottom;
+    auto nomem = [&](const char *what) {
+        ctx->bottom = mark;
+        ctx->scratch_reset();
+        return ctx->fail(REINC_E_NOMEM, "arena exhausted in build_deltas(%d): %s", t, what);
+    };
+    int32_t *cflags = static_cast<int32_t *>(ctx->scratch(uint64_t(n) * 4));
+    int32_t *cindex = static_cast<int32_t *>(ctx->scratch(uint64_t(n) * 4));
+    int32_t *cnt_ins = static_cast<int32_t *>(ctx->scratch(uint64_t(n) * 4));
+    int32_t *cnt_del = static_cast<int32_t *>(ctx->scratch(uint64_t(n) * 4));
+    int32_t *cnt_all = static_cast<int32_t *>(ctx->scratch(uint64_t(n) * 4));
+    int32_t *row_flag = static_cast<int32_t *>(ctx->scratch(uint64_t(n) * 4));
+    int64_t *coffs = static_cast<int64_t *>(ctx->scratch(uint64_t(n + 1) * 8));
+    int64_t *roffs = static_cast<int64_t *>(ctx->scratch(uint64_t(n + 1) * 8));
+    void *scan_tmp = ctx->scratch(scan_tmp_bytes(n));
+    if (!cflags || !cindex || !cnt_ins || !cnt_del || !cnt_all || !row_flag || !coffs || !roffs || !scan_tmp)
+        return nomem("scratch");
+
+    // change set C_t
+    launch_fill_i32(cflags, n, 0, s);
+    if (b.feats_from_delta)
+        launch_feature_flags_list(b.feat_rows, b.n_feat_rows, n, cflags, s);
+    else
+        launch_feature_flags_compare(a.x, b.x, n, d * ctx->elem_bytes(), cflags, s);
+    if (ctx->cfg.agg_kind == REINC_AGG_SYM) launch_degree_flags(a.row_ptr, b.row_ptr, n, cflags, s);
+    launch_scan(cflags, coffs, n, scan_tmp, s);
+    int64_t n_changed = 0;
+    REINC_HIP(ctx, hipMemcpyAsync(&n_changed, coffs + n, 8, hipMemcpyDeviceToHost, s));
+    REINC_HIP(ctx, hipStreamSynchronize(s));
+    dl.changed = static_cast<int32_t *>(ctx->alloc(uint64_t(std::max<int64_t>(n_changed, 1)) * 4));
+    dl.dY = static_cast<float *>(ctx->alloc(uint64_t(std::max<int64_t>(n_changed, 1)) * d * 4));
+    dl.ins_ptr = static_cast<int64_t *>(ctx->alloc(uint64_t(n + 1) * 8));
+    dl.del_ptr = static_cast<int64_t *>(ctx->alloc(uint64_t(n + 1) * 8));
+    dl.ent_ptr = static_cast<int64_t *>(ctx->alloc(uint64_t(n + 1) * 8));
+    if (!dl.changed || !dl.dY || !dl.ins_ptr || !dl.del_ptr || !dl.ent_ptr) return nomem("change set / row pointers");
+    launch_compact(cflags, coffs, n, dl.changed, cindex, s);
+    launch_dy(a.x, b.x, bf16, a.p, b.p, dl.changed, n_changed, d, dl.dY, s);
+
+    // per-row counts, row pointers
+    launch_delta_count(a.row_ptr, a.col, b.row_ptr, b.col, cflags, ctx->cfg.self_loop, n, cnt_ins, cnt_del, cnt_all,
+                       row_flag, s);
+    launch_scan(cnt_ins, dl.ins_ptr, n, scan_tmp, s);
+    launch_scan(cnt_del, dl.del_ptr, n, scan_tmp, s);
+    launch_scan(cnt_all, dl.ent_ptr, n, scan_tmp, s);
+    launch_scan(row_flag, roffs, n, scan_tmp, s);
+    int64_t totals[4] = {0, 0, 0, 0};
+    REINC_HIP(ctx, hipMemcpyAsync(&totals[0], dl.ins_ptr + n, 8, hipMemcpyDeviceToHost, s));
+    REINC_HIP(ctx, hipMemcpyAsync(&totals[1], dl.del_ptr + n, 8, hipMemcpyDeviceToHost, s));
+    REINC_HIP(ctx, hipMemcpyAsync(&totals[2], dl.ent_ptr + n, 8, hipMemcpyDeviceToHost, s));
+    REINC_HIP(ctx, hipMemcpyAsync(&totals[3], roffs + n, 8, hipMemcpyDeviceToHost, s));
+    REINC_HIP(ctx, hipStreamSynchronize(s));
+    dl.ins_col = static_cast<int32_t *>(ctx->alloc(uint64_t(std::max<int64_t>(totals[0], 1)) * 4));
+    dl.del_col = static_cast<int32_t *>(ctx->alloc(uint64_t(std::max<int64_t>(totals[1], 1)) * 4));
+    dl.ent = static_cast<uint32_t *>(ctx->alloc(uint64_t(std::max<int64_t>(totals[2], 1)) * 4));
+    dl.rows = static_cast<int32_t *>(ctx->alloc(uint64_t(std::max<int64_t>(totals[3], 1)) * 4));
+    if (!dl.ins_col || !dl.del_col || !dl.ent || !dl.rows) return nomem("delta entries");
+    launch_delta_fill(a.row_ptr, a.col, b.row_ptr, b.col, cindex, ctx->cfg.self_loop, n, dl.ins_ptr, dl.ins_col,
+                      dl.del_ptr, dl.del_col, dl.ent_ptr, dl.ent, s);
+    launch_compact(row_flag, roffs, n, dl.rows, nullptr, s);
+    REINC_HIP(ctx, hipGetLastError());
+    REINC_HIP(ctx, hipStreamSynchronize(s));
+    ctx->scratch_reset();
+    dl.info.num_edges_prev = a.nnz;
+    dl.info.num_edges_cur = b.nnz;
+    dl.info.n_ins = totals[0];
+    dl.info.n_del = totals[1];
+    dl.info.n_changed = n_changed;
+    dl.info.n_entries = totals[2];
+    dl.info.n_fchg_entries = totals[2] - totals[0] - totals[1];
+    dl.info.n_rows = totals[3];
+    dl.built = true;
+    return REINC_OK;
+}
+
+int reinc_build_deltas(reinc_ctx *ctx, int32_t t, void *stream)
+{
+    if (!ctx) return REINC_E_ARG;
+    REINC_HIP(ctx, hipSetDevice(ctx->cfg.device));
+    if (t < 0) {
+        for (int32_t k = 1; k < ctx->cfg.num_snapshots; ++k) {
+            const Snapshot &a = ctx->snaps[k - 1], &b = ctx->snaps[k];
+            if (a.edges_loaded && b.edges_loaded && a.feats_loaded && b.feats_loaded) REINC_TRY(build_one(ctx, k, as_stream(stream)));
+        }
+        return REINC_OK;
+    }
+    REINC_TRY(check_t(ctx, t));
+    if (t == 0) return ctx->fail(REINC_E_ARG, "step 0 has no predecessor");
+    return build_one(ctx, t, as_stream(stream));
+}
+
+static int need_delta(reinc_ctx *ctx, int32_t t)
+{
+    REINC_TRY(check_t(ctx, t));
+    if (t == 0 || !ctx->deltas[t].built) return ctx->fail(REINC_E_STATE, "deltas of step %d are not built", t);
+    return REINC_OK;
+}
+
+int reinc_get_delta_info(reinc_ctx *ctx, int32_t t, reinc_delta_info *out)
+{
+    if (!ctx || !out) return REINC_E_ARG;
+    REINC_TRY(need_delta(ctx, t));
+    *out = ctx->deltas[t].info;
+    return REINC_OK;
+}
+
+int reinc_get_delta_csr(reinc_ctx *ctx, int32_t t, int kind, int64_t *row_ptr, int32_t *col, int64_t *nnz_out)
+{
+    if (!ctx) return REINC_E_ARG;
+    REINC_TRY(need_delta(ctx, t));
+    if (kind != 0 && kind != 1) return ctx->fail(REINC_E_ARG, "kind must be 0 (insert) or 1 (delete)");
+    const Delta &dl = ctx->deltas[t];
+    const int64_t nnz = kind == 0 ? dl.info.n_ins : dl.info.n_del;
+    if (nnz_out) *nnz_out = nnz;
+    REINC_TRY(read_back(ctx, row_ptr, kind == 0 ? dl.ins_ptr : dl.del_ptr, ctx->N() + 1));
+    REINC_TRY(read_back(ctx, col, kind == 0 ? dl.ins_col : dl.del_col, nnz));
+    return REINC_OK;
+}
+
+int reinc_get_merged_delta(reinc_ctx *ctx, int32_t t, int64_t *entry_ptr, uint32_t *entries, int32_t *rows,
+                           int32_t *changed)
+{
+    if (!ctx) return REINC_E_ARG;
+    REINC_TRY(need_delta(ctx, t));
+    const Delta &dl = ctx->deltas[t];
+    REINC_TRY(read_back(ctx, entry_ptr, dl.ent_ptr, ctx->N() + 1));
+    REINC_TRY(read_back(ctx, entries, dl.ent, dl.info.n_entries));
+    REINC_TRY(read_back(ctx, rows, dl.rows, dl.info.n_rows));
+    REINC_TRY(read_back(ctx, changed, dl.changed, dl.info.n_changed));
+    return REINC_OK;
+}
+
+int reinc_get_snapshot_csr(reinc_ctx *ctx, int32_t t, int transpose, int64_t *ptr, int32_t *idx, int64_t *nnz_out)
+{
+    if (!ctx) return REINC_E_ARG;
+    REINC_TRY(check_t(ctx, t));
+    const Snapshot &sn = ctx->snaps[t];
+    if (!sn.edges_loaded) return ctx->fail(REINC_E_STATE, "edges of snapshot %d are not loaded", t);
+    if (nnz_out) *nnz_out = sn.nnz;
+    REINC_TRY(read_back(ctx, ptr, transpose ? sn.col_ptr : sn.row_ptr, ctx->N() + 1));
+    REINC_TRY(read_back(ctx, idx, transpose ? sn.row : sn.col, sn.nnz));
+    return REINC_OK;
+}
+
+// ------------------------------------------------------------------------------------------------ aggregation
+
+int reinc_aggregate_full(reinc_ctx *ctx, int32_t t, int transpose, const void *X, int x_dtype, int32_t d, int apply_q,
+                         float *out, void *stream)
+{
+    if (!ctx) return REINC_E_ARG;
+    REINC_TRY(check_t(ctx, t));
+    const Snapshot &sn = ctx->snaps[t];
+    if (!sn.edges_loaded) return ctx->fail(REINC_E_STATE, "edges of snapshot %d are not loaded", t);
+    if (!out) return ctx->fail(REINC_E_ARG, "null output");
+    if (x_dtype != REINC_F32 && x_dtype != REINC_BF16) return ctx->fail(REINC_E_ARG, "bad x_dtype");
+    if (!X) {
+        if (!sn.feats_loaded) return ctx->fail(REINC_E_STATE, "features of snapshot %d are not loaded", t);
+        if (d != ctx->cfg.dims[0] || x_dtype != ctx->cfg.feat_dtype)
+            return ctx->fail(REINC_E_ARG, "stored features are [N, %d] of dtype %d", ctx->cfg.dims[0], ctx->cfg.feat_dtype);
+        X = sn.x;
+    }
+    if (X == out) return ctx->fail(REINC_E_ARG, "output may not alias the input");
+    if (!agg_width_supported(d, x_dtype == REINC_BF16))
+        return ctx->fail(REINC_E_UNSUPPORTED, "row of %d elements: row bytes must be a power of two in [16, 1024]", d);
+    const int bf16 = x_dtype == REINC_BF16;
+    if (!transpose)
+        launch_aggregate(sn.row_ptr, sn.col, sn.long_rows, sn.n_long_rows, X, bf16, d, ctx->N(), ctx->cfg.self_loop, sn.p,
+                         apply_q ? sn.q : nullptr, out, as_stream(stream));
+    else
+        launch_aggregate(sn.col_ptr, sn.row, sn.long_cols, sn.n_long_cols, X, bf16, d, ctx->N(), ctx->cfg.self_loop,
+                         apply_q ? sn.q : nullptr, sn.p, out, as_stream(stream));
+    REINC_HIP(ctx, hipGetLastError());
+    return REINC_OK;
+}
+
+int reinc_aggregate_incremental(reinc_ctx *ctx, int32_t t, const float *S_prev, float *S_out, float *agg_out,
+                                void *stream)
+{
+    if (!ctx) return REINC_E_ARG;
+    REINC_TRY(need_delta(ctx, t));
+    if (!S_prev || !S_out) return ctx->fail(REINC_E_ARG, "null aggregate buffer");
+    const Delta &dl = ctx->deltas[t];
+    const Snapshot &pv = ctx->snaps[t - 1];
+    const Snapshot &sn = ctx->snaps[t];
+    const int32_t d = ctx->cfg.dims[0];
+    const uint64_t bytes = uint64_t(ctx->N()) * d * 4;
+    if (S_out != S_prev) {
+        const char *a = reinterpret_cast<const char *>(S_prev), *b = reinterpret_cast<const char *>(S_out);
+        if (a < b + bytes && b < a + bytes) return ctx->fail(REINC_E_ARG, "S_out must be S_prev itself or disjoint from it");
+        REINC_HIP(ctx, hipMemcpyAsync(S_out, S_prev, bytes, hipMemcpyDeviceToDevice, as_stream(stream)));
+    }
+    launch_incremental(dl.rows, dl.info.n_rows, dl.ent_ptr, dl.ent, pv.x, ctx->cfg.feat_dtype == REINC_BF16, pv.p, dl.dY, d,
+                       S_out, S_out, sn.q, agg_out, as_stream(stream));
+    REINC_HIP(ctx, hipGetLastError());
+    ctx->stats.delta_entries_processed += dl.info.n_entries;
+    return REINC_OK;
+}
+
+int reinc_get_stats(reinc_ctx *ctx, reinc_stats *out)
+{
+    if (!ctx || !out) return REINC_E_ARG;
+    ctx->stats.arena_used = int64_t(ctx->bottom);
+    ctx->stats.arena_peak = int64_t(ctx->peak);
+    *out = ctx->stats;
+    return REINC_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,169 @@
+// Internal state of libreinc_hip.so (not part of the ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdint>
+#include <cstdio>
+#include <string>
+#include <vector>
+
+#include "reinc.h"
+
+namespace reinc {
+
+constexpr uint32_t kKindShift = 30;  // merged delta entry = (kind << 30) | payload
+constexpr uint32_t kPayloadMask = (1u << kKindShift) - 1u;
+constexpr int64_t kMaxNodes = int64_t(1) << kKindShift;
+constexpr int kLongRow = 512;  // rows with more in-edges than this take the block-per-row path
+
+// One canonical snapshot on the device.
+struct Snapshot {
+    bool edges_loaded = false;
+    bool feats_loaded = false;
+    bool feats_from_delta = false;
+    int64_t nnz = 0;
+    // CSR by destination and CSC by source
+    int64_t *row_ptr = nullptr;
+    int32_t *col = nullptr;
+    int64_t *col_ptr = nullptr;
+    int32_t *row = nullptr;
+    // degree scalings: p (source side), q (target side), fp32 [N]
+    float *p = nullptr;
+    float *q = nullptr;
+    // rows / columns longer than kLongRow (ascending)
+    int32_t *long_rows = nullptr;
+    int32_t n_long_rows = 0;
+    int32_t *long_cols = nullptr;
+    int32_t n_long_cols = 0;
+    // features [N, d0] in feat_dtype
+    void *x = nullptr;
+    // rows replaced by load_features_delta (device copy, ascending)
+    int32_t *feat_rows = nullptr;
+    int64_t n_feat_rows = 0;
+};
+
+// Delta structures of step t-1 -> t.
+struct Delta {
+    bool built = false;
+    reinc_delta_info info{};
+    int64_t *ins_ptr = nullptr;
+    int32_t *ins_col = nullptr;
+    int64_t *del_ptr = nullptr;
+    int32_t *del_col = nullptr;
+    int64_t *ent_ptr = nullptr;  // [N+1]
+    uint32_t *ent = nullptr;     // [n_entries]
+    int32_t *rows = nullptr;     // R_t [n_rows]
+    int32_t *changed = nullptr;  // C_t [n_changed]
+    float *dY = nullptr;         // [n_changed, d0] fp32
+};
+
+struct LocalStep {  // per-window activations of one timestep (local cache)
+    float *S[REINC_MAX_GCN_LAYERS + 1] = {};  // S[l]: un-normalised sums feeding layer l (l >= 2; S[1] lives in the global cache)
+    float *H[REINC_MAX_GCN_LAYERS + 1] = {};  // H[l]: output of layer l
+    float *h = nullptr, *c = nullptr;         // recurrent state after this step
+    float *saved = nullptr;                   // gate values [N, 4H]
+};
+
+}  // namespace reinc
+
+struct reinc_ctx {
+    reinc_config cfg{};
+    std::string err;
+    // arena: persistent allocations grow from the bottom, per-call scratch from the top
+    char *base = nullptr;
+    uint64_t size = 0, bottom = 0, top = 0, peak = 0;
+    std::vector<reinc::Snapshot> snaps;
+    std::vector<reinc::Delta> deltas;
+    // global cache: S^1_t per snapshot
+    std::vector<float *> gcache;
+    // local cache
+    std::vector<reinc::LocalStep> local;
+    uint64_t local_mark = 0;  // arena bottom before the local cache was carved
+    bool local_valid = false;
+    int32_t local_t0 = -1, local_L = 0;
+    float *zero_state = nullptr;  // [N, H] zeros
+    reinc_stats stats{};
+
+    int fail(int code, const char *fmt, ...) {
+        char buf[512];
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(buf, sizeof buf, fmt, ap);
+        va_end(ap);
+        err = buf;
+        return code;
+    }
+    // persistent allocation (256-byte aligned); nullptr when the arena is exhausted
+    void *alloc(uint64_t bytes) {
+        uint64_t b = (bytes + 255) & ~uint64_t(255);
+        if (bottom + b > top) return nullptr;
+        void *p = base + bottom;
+        bottom += b;
+        if (bottom + (size - top) > peak) peak = bottom + (size - top);
+        return p;
+    }
+    // scratch allocation, released by scratch_reset()
+    void *scratch(uint64_t bytes) {
+        uint64_t b = (bytes + 255) & ~uint64_t(255);
+        if (bottom + b > top) return nullptr;
+        top -= b;
+        if (bottom + (size - top) > peak) peak = bottom + (size - top);
+        return base + top;
+    }
+    void scratch_reset() { top = size; }
+    int64_t N() const { return cfg.num_nodes; }
+    int elem_bytes() const { return cfg.feat_dtype == REINC_BF16 ? 2 : 4; }
+};
+
+#define REINC_HIP(ctx, expr)                                                                        \
+    do {                                                                                            \
+        hipError_t e_ = (expr);                                                                     \
+        if (e_ != hipSuccess) return (ctx)->fail(REINC_E_HIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+    } while (0)
+
+#define REINC_TRY(expr)           \
+    do {                          \
+        int rc_ = (expr);         \
+        if (rc_ != REINC_OK) return rc_; \
+    } while (0)
+
+namespace reinc {
+
+// ---- kernels_graph.hip
+// exclusive scan of int32 counts [n] into int64 offsets [n+1]; tmp: scratch of scan_tmp_bytes(n)
+uint64_t scan_tmp_bytes(int64_t n);
+void launch_scan(const int32_t *counts, int64_t *offsets, int64_t n, void *tmp, hipStream_t s);
+void launch_fill_i32(int32_t *p, int64_t n, int32_t v, hipStream_t s);
+void launch_feature_flags_compare(const void *x_prev, const void *x_cur, int64_t n, int32_t row_bytes, int32_t *flags,
+                                  hipStream_t s);
+void launch_feature_flags_list(const int32_t *rows, int64_t nrows, int64_t n, int32_t *flags, hipStream_t s);
+void launch_degree_flags(const int64_t *rp_prev, const int64_t *rp_cur, int64_t n, int32_t *flags, hipStream_t s);
+void launch_compact(const int32_t *flags, const int64_t *offsets, int64_t n, int32_t *list, int32_t *index_of,
+                    hipStream_t s);
+void launch_delta_count(const int64_t *rp_a, const int32_t *col_a, const int64_t *rp_b, const int32_t *col_b,
+                        const int32_t *cflags, int self_loop, int64_t n, int32_t *cnt_ins, int32_t *cnt_del,
+                        int32_t *cnt_all, int32_t *row_flag, hipStream_t s);
+void launch_delta_fill(const int64_t *rp_a, const int32_t *col_a, const int64_t *rp_b, const int32_t *col_b,
+                       const int32_t *cindex, int self_loop, int64_t n, const int64_t *ins_ptr, int32_t *ins_col,
+                       const int64_t *del_ptr, int32_t *del_col, const int64_t *ent_ptr, uint32_t *ent, hipStream_t s);
+void launch_dy(const void *x_prev, const void *x_cur, int bf16, const float *p_prev, const float *p_cur,
+               const int32_t *changed, int64_t n_changed, int32_t d, float *dY, hipStream_t s);
+
+// ---- kernels_agg.hip
+bool agg_width_supported(int32_t d, int bf16);
+// out[v] = out_scale[v] * ( self_loop * in_scale[v] X[v] + sum_{e in [ptr[v], ptr[v+1])} in_scale[idx[e]] X[idx[e]] )
+// in_scale / out_scale may be null (factor 1).
+void launch_aggregate(const int64_t *ptr, const int32_t *idx, const int32_t *long_rows, int32_t n_long, const void *X,
+                      int bf16, int32_t d, int64_t n, int self_loop, const float *in_scale, const float *out_scale,
+                      float *out, hipStream_t s);
+void launch_incremental(const int32_t *rows, int64_t n_rows, const int64_t *ent_ptr, const uint32_t *ent,
+                        const void *x_prev, int bf16, const float *p_prev, const float *dY, int32_t d,
+                        const float *S_prev, float *S_out, const float *q, float *agg_out, hipStream_t s);
+
+// ---- kernels_dense.hip
+int launch_gemm_rows(const void *A, int a_bf16, int64_t n, int32_t K, int32_t M, const float *row_scale,
+                     const float *W, int w_transposed, int32_t ldw, const float *bias, int relu,
+                     const float *out_row_scale, const float *relu_mask, float *out, int accumulate, hipStream_t s);
+}  // namespace reinc

@@ -1,0 +1,365 @@
+// Neighbourhood aggregation kernels (paper Section 3.2).
+//
+//   aggregate_rows / aggregate_long_rows : Eq. 1, from scratch.  One wavefront per output row; the
+//       wave loads 64 column indices at a time with one coalesced read and hands them round with
+//       lane shuffles; a row of d values is read by LPR = d*sizeof(elem)/16 lanes as one 16-byte
+//       load each, so 64/LPR source rows are in flight per load instruction and U of those
+//       instructions are issued back to back.  Rows with more than kLongRow entries are skipped
+//       and taken by a 4-wave block with an LDS reduction (power-law hubs).
+//   incremental_rows : Eq. 2 in the form  S_t[r] = S_{t-1}[r] + sum_ins Y_{t-1}[u] - sum_del Y_{t-1}[u]
+//       + sum_changed dY[u]  over the rows of R_t only, same lane layout, signed tagged entries.
+//
+// No atomics anywhere: every output row has one writer and a fixed summation order, so results are
+// bit-reproducible from run to run.
+#include "ctx.h"
+
+namespace reinc {
+
+namespace {
+
+constexpr int kWavesPerBlock = 4;
+constexpr int kUnroll = 4;
+
+template <bool BF16>
+struct Row;
+
+template <>
+struct Row<false> {
+    static constexpr int kVec = 4;
+    __device__ static inline void load(const void *base, int64_t row, int d, int li, float (&r)[4])
+    {
+        const float4 v = *reinterpret_cast<const float4 *>(static_cast<const float *>(base) + row * d + li * 4);
+        r[0] = v.x;
+        r[1] = v.y;
+        r[2] = v.z;
+        r[3] = v.w;
+    }
+};
+
+template <>
+struct Row<true> {
+    static constexpr int kVec = 8;
+    __device__ static inline void load(const void *base, int64_t row, int d, int li, float (&r)[8])
+    {
+        const uint4 v = *reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(base) + row * d + li * 8);
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            r[2 * i] = __uint_as_float(w[i] << 16);
+            r[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u);
+        }
+    }
+};
+
+template <int VEC>
+__device__ inline void load_f32(const float *base, int64_t row, int d, int li, float (&r)[VEC])
+{
+#pragma unroll
+    for (int i = 0; i < VEC; i += 4) {
+        const float4 v = *reinterpret_cast<const float4 *>(base + row * d + li * VEC + i);
+        r[i] = v.x;
+        r[i + 1] = v.y;
+        r[i + 2] = v.z;
+        r[i + 3] = v.w;
+    }
+}
+
+template <int VEC>
+__device__ inline void store_f32(float *base, int64_t row, int d, int li, const float (&r)[VEC])
+{
+#pragma unroll
+    for (int i = 0; i < VEC; i += 4)
+        *reinterpret_cast<float4 *>(base + row * d + li * VEC + i) = make_float4(r[i], r[i + 1], r[i + 2], r[i + 3]);
+}
+
+// Sums in_scale[u] * X[u] over the entries [beg, end) handled by this wave (entry e goes to lane group e % G).
+template <int LPR, bool BF16>
+__device__ inline void gather_segment(const int32_t *idx, int64_t beg, int64_t end, int64_t stride, const void *X,
+                                      const float *in_scale, int d, int lane, float (&acc)[Row<BF16>::kVec])
+{
+    constexpr int VEC = Row<BF16>::kVec;
+    constexpr int G = 64 / LPR;
+    const int g = lane / LPR, li = lane % LPR;
+    for (int64_t base = beg; base < end; base += stride) {
+        const int cnt = int(min(int64_t(64), end - base));
+        int32_t my_u = 0;
+        float my_sc = 1.0f;
+        if (lane < cnt) {
+            my_u = idx[base + lane];
+            if (in_scale) my_sc = in_scale[my_u];
+        }
+        for (int k = 0; k < cnt; k += G * kUnroll) {
+            float r[kUnroll][VEC];
+            float sc[kUnroll];
+#pragma unroll
+            for (int j = 0; j < kUnroll; ++j) {
+                const int e = k + j * G + g;
+                const int32_t u = __shfl(my_u, e & 63);
+                sc[j] = __shfl(my_sc, e & 63);
+                if (e < cnt) {
+                    Row<BF16>::load(X, u, d, li, r[j]);
+                } else {
+                    sc[j] = 0.0f;
+#pragma unroll
+                    for (int i = 0; i < VEC; ++i) r[j][i] = 0.0f;
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < kUnroll; ++j)
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) acc[i] += sc[j] * r[j][i];
+        }
+    }
+}
+
+template <int LPR, int VEC>
+__device__ inline void reduce_groups(float (&acc)[VEC])
+{
+#pragma unroll
+    for (int off = LPR; off < 64; off <<= 1)
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) acc[i] += __shfl_xor(acc[i], off);
+}
+
+template <int LPR, bool BF16>
+__global__ void __launch_bounds__(64 * kWavesPerBlock)
+aggregate_rows(const int64_t *__restrict__ ptr, const int32_t *__restrict__ idx, const void *__restrict__ X, int64_t n,
+               int self_loop, const float *__restrict__ in_scale, const float *__restrict__ out_scale,
+               float *__restrict__ out, int skip_long)
+{
+    constexpr int VEC = Row<BF16>::kVec;
+    constexpr int D = LPR * VEC;
+    const int lane = threadIdx.x & 63;
+    const int64_t v = int64_t(blockIdx.x) * kWavesPerBlock + (threadIdx.x >> 6);
+    if (v >= n) return;
+    const int64_t beg = ptr[v], end = ptr[v + 1];
+    if (skip_long && end - beg > kLongRow) return;
+    float acc[VEC];
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) acc[i] = 0.0f;
+    gather_segment<LPR, BF16>(idx, beg, end, 64, X, in_scale, D, lane, acc);
+    reduce_groups<LPR, VEC>(acc);
+    if (lane < LPR) {
+        if (self_loop) {
+            float r[VEC];
+            Row<BF16>::load(X, v, D, lane, r);
+            const float sc = in_scale ? in_scale[v] : 1.0f;
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) acc[i] += sc * r[i];
+        }
+        if (out_scale) {
+            const float q = out_scale[v];
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) acc[i] *= q;
+        }
+        store_f32<VEC>(out, v, D, lane, acc);
+    }
+}
+
+// one block of kWavesPerBlock waves per long row; wave w takes the 64-entry chunks w, w+4, ...
+template <int LPR, bool BF16>
+__global__ void __launch_bounds__(64 * kWavesPerBlock)
+aggregate_long_rows(const int32_t *__restrict__ long_rows, const int64_t *__restrict__ ptr,
+                    const int32_t *__restrict__ idx, const void *__restrict__ X, int self_loop,
+                    const float *__restrict__ in_scale, const float *__restrict__ out_scale, float *__restrict__ out)
+{
+    constexpr int VEC = Row<BF16>::kVec;
+    constexpr int D = LPR * VEC;
+    __shared__ float part[kWavesPerBlock][D];
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int64_t v = long_rows[blockIdx.x];
+    const int64_t beg = ptr[v], end = ptr[v + 1];
+    float acc[VEC];
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) acc[i] = 0.0f;
+    gather_segment<LPR, BF16>(idx, beg + 64 * w, end, 64 * kWavesPerBlock, X, in_scale, D, lane, acc);
+    reduce_groups<LPR, VEC>(acc);
+    if (lane < LPR)
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) part[w][lane * VEC + i] = acc[i];
+    __syncthreads();
+    if (w == 0 && lane < LPR) {
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) {
+            float s = part[0][lane * VEC + i];
+            for (int k = 1; k < kWavesPerBlock; ++k) s += part[k][lane * VEC + i];
+            acc[i] = s;
+        }
+        if (self_loop) {
+            float r[VEC];
+            Row<BF16>::load(X, v, D, lane, r);
+            const float sc = in_scale ? in_scale[v] : 1.0f;
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) acc[i] += sc * r[i];
+        }
+        if (out_scale) {
+            const float q = out_scale[v];
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) acc[i] *= q;
+        }
+        store_f32<VEC>(out, v, D, lane, acc);
+    }
+}
+
+template <int LPR, bool BF16>
+__global__ void __launch_bounds__(64 * kWavesPerBlock)
+incremental_rows(const int32_t *__restrict__ rows, int64_t n_rows, const int64_t *__restrict__ ent_ptr,
+                 const uint32_t *__restrict__ ent, const void *__restrict__ x_prev, const float *__restrict__ p_prev,
+                 const float *__restrict__ dY, const float *S_prev, float *S_out, const float *__restrict__ q,
+                 float *__restrict__ agg_out)
+{
+    constexpr int VEC = Row<BF16>::kVec;
+    constexpr int D = LPR * VEC;
+    constexpr int G = 64 / LPR;
+    const int lane = threadIdx.x & 63;
+    const int g = lane / LPR, li = lane % LPR;
+    const int64_t w = int64_t(blockIdx.x) * kWavesPerBlock + (threadIdx.x >> 6);
+    if (w >= n_rows) return;
+    const int64_t v = rows[w];
+    const int64_t beg = ent_ptr[v], end = ent_ptr[v + 1];
+    float acc[VEC];
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) acc[i] = 0.0f;
+    for (int64_t base = beg; base < end; base += 64) {
+        const int cnt = int(min(int64_t(64), end - base));
+        uint32_t my_e = 0;
+        float my_sc = 0.0f;
+        if (lane < cnt) {
+            my_e = ent[base + lane];
+            const uint32_t kind = my_e >> kKindShift;
+            if (kind == 2u) {
+                my_sc = 1.0f;
+            } else {
+                my_sc = p_prev ? p_prev[my_e & kPayloadMask] : 1.0f;
+                if (kind == 1u) my_sc = -my_sc;
+            }
+        }
+        for (int k = 0; k < cnt; k += G * kUnroll) {
+            float r[kUnroll][VEC];
+            float sc[kUnroll];
+#pragma unroll
+            for (int j = 0; j < kUnroll; ++j) {
+                const int e = k + j * G + g;
+                const uint32_t en = __shfl(my_e, e & 63);
+                sc[j] = __shfl(my_sc, e & 63);
+                if (e < cnt) {
+                    const int64_t u = en & kPayloadMask;
+                    if ((en >> kKindShift) == 2u)
+                        load_f32<VEC>(dY, u, D, li, r[j]);
+                    else
+                        Row<BF16>::load(x_prev, u, D, li, r[j]);
+                } else {
+                    sc[j] = 0.0f;
+#pragma unroll
+                    for (int i = 0; i < VEC; ++i) r[j][i] = 0.0f;
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < kUnroll; ++j)
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) acc[i] += sc[j] * r[j][i];
+        }
+    }
+    reduce_groups<LPR, VEC>(acc);
+    if (lane < LPR) {
+        float s[VEC];
+        load_f32<VEC>(S_prev, v, D, lane, s);
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) s[i] += acc[i];
+        store_f32<VEC>(S_out, v, D, lane, s);
+        if (agg_out) {
+            const float qq = q ? q[v] : 1.0f;
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) s[i] *= qq;
+            store_f32<VEC>(agg_out, v, D, lane, s);
+        }
+    }
+}
+
+inline int lanes_per_row(int32_t d, int bf16)
+{
+    int64_t bytes = int64_t(d) * (bf16 ? 2 : 4);
+    if (bytes < 16 || bytes > 1024 || (bytes & (bytes - 1))) return 0;
+    return int(bytes / 16);
+}
+
+template <bool BF16>
+void aggregate_dispatch(int lpr, const int64_t *ptr, const int32_t *idx, const int32_t *long_rows, int32_t n_long,
+                        const void *X, int64_t n, int self_loop, const float *in_scale, const float *out_scale, float *out,
+                        hipStream_t s)
+{
+    const unsigned blocks = unsigned((n + kWavesPerBlock - 1) / kWavesPerBlock);
+    const dim3 th(64 * kWavesPerBlock);
+    const int skip = n_long > 0;
+#define REINC_AGG_CASE(L)                                                                                          \
+    case L:                                                                                                        \
+        aggregate_rows<L, BF16><<<blocks, th, 0, s>>>(ptr, idx, X, n, self_loop, in_scale, out_scale, out, skip);  \
+        if (n_long > 0)                                                                                            \
+            aggregate_long_rows<L, BF16><<<unsigned(n_long), th, 0, s>>>(long_rows, ptr, idx, X, self_loop, in_scale, \
+                                                                         out_scale, out);                          \
+        break;
+    switch (lpr) {
+        REINC_AGG_CASE(1)
+        REINC_AGG_CASE(2)
+        REINC_AGG_CASE(4)
+        REINC_AGG_CASE(8)
+        REINC_AGG_CASE(16)
+        REINC_AGG_CASE(32)
+        REINC_AGG_CASE(64)
+    }
+#undef REINC_AGG_CASE
+}
+
+template <bool BF16>
+void incremental_dispatch(int lpr, const int32_t *rows, int64_t n_rows, const int64_t *ent_ptr, const uint32_t *ent,
+                          const void *x_prev, const float *p_prev, const float *dY, const float *S_prev, float *S_out,
+                          const float *q, float *agg_out, hipStream_t s)
+{
+    const unsigned blocks = unsigned((n_rows + kWavesPerBlock - 1) / kWavesPerBlock);
+    const dim3 th(64 * kWavesPerBlock);
+#define REINC_INC_CASE(L)                                                                                              \
+    case L:                                                                                                            \
+        incremental_rows<L, BF16><<<blocks, th, 0, s>>>(rows, n_rows, ent_ptr, ent, x_prev, p_prev, dY, S_prev, S_out, q, \
+                                                        agg_out);                                                      \
+        break;
+    switch (lpr) {
+        REINC_INC_CASE(1)
+        REINC_INC_CASE(2)
+        REINC_INC_CASE(4)
+        REINC_INC_CASE(8)
+        REINC_INC_CASE(16)
+        REINC_INC_CASE(32)
+        REINC_INC_CASE(64)
+    }
+#undef REINC_INC_CASE
+}
+
+}  // namespace
+
+bool agg_width_supported(int32_t d, int bf16) { return lanes_per_row(d, bf16) != 0; }
+
+void launch_aggregate(const int64_t *ptr, const int32_t *idx, const int32_t *long_rows, int32_t n_long, const void *X,
+                      int bf16, int32_t d, int64_t n, int self_loop, const float *in_scale, const float *out_scale,
+                      float *out, hipStream_t s)
+{
+    if (n <= 0) return;
+    const int lpr = lanes_per_row(d, bf16);
+    if (bf16)
+        aggregate_dispatch<true>(lpr, ptr, idx, long_rows, n_long, X, n, self_loop, in_scale, out_scale, out, s);
+    else
+        aggregate_dispatch<false>(lpr, ptr, idx, long_rows, n_long, X, n, self_loop, in_scale, out_scale, out, s);
+}
+
+void launch_incremental(const int32_t *rows, int64_t n_rows, const int64_t *ent_ptr, const uint32_t *ent,
+                        const void *x_prev, int bf16, const float *p_prev, const float *dY, int32_t d,
+                        const float *S_prev, float *S_out, const float *q, float *agg_out, hipStream_t s)
+{
+    if (n_rows <= 0) return;
+    const int lpr = lanes_per_row(d, bf16);
+    if (bf16)
+        incremental_dispatch<true>(lpr, rows, n_rows, ent_ptr, ent, x_prev, p_prev, dY, S_prev, S_out, q, agg_out, s);
+    else
+        incremental_dispatch<false>(lpr, rows, n_rows, ent_ptr, ent, x_prev, p_prev, dY, S_prev, S_out, q, agg_out, s);
+}
+
+}  // namespace reinc

@@ -1,0 +1,171 @@
+"""GPU parity, float side: from-scratch aggregation (paper Section 3.2, Eq. 1), its adjoint, and the
+incremental rule (Eq. 2) chained over snapshots, each against the from-scratch CPU reference."""
+import itertools
+
+import numpy as np
+import pytest
+
+import oracle
+from helpers import RTOL_BF16, RTOL_FP32, assert_close, oracle_feats, oracle_graphs
+from paper_2501_15348_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+def _ctx(wl, arena=512 << 20, **kw):
+    from paper_2501_15348_amd import reinc
+
+    return reinc.Context.for_workload(wl, arena_bytes=arena, **kw)
+
+
+def _dev(a, dtype=None):
+    import torch
+
+    t = torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    return t if dtype is None else t.to(dtype)
+
+
+@pytest.mark.parametrize("mode,self_loop", list(itertools.product(["sum", "mean", "sym"], [False, True])))
+def test_full_aggregation_tiny(tiny_seq, mode, self_loop):
+    import dataclasses
+
+    wl = dataclasses.replace(tiny_seq.workload, agg=mode, self_loop=self_loop)
+    seq = dataclasses.replace(tiny_seq, workload=wl)
+    ctx = _ctx(wl)
+    ctx.load_sequence(seq)
+    graphs = oracle_graphs(seq)
+    for t in (0, 3, 7):
+        s_ref, agg_ref = oracle.aggregate(graphs[t].row_ptr, graphs[t].col, oracle_feats(seq, t), mode, self_loop)
+        assert_close(ctx.aggregate_full(t).cpu().numpy(), s_ref, RTOL_FP32, f"S t={t}")
+        assert_close(ctx.aggregate_full(t, apply_q=True).cpu().numpy(), agg_ref, RTOL_FP32, f"Agg t={t}")
+        g = np.random.default_rng(t).standard_normal((wl.num_nodes, 16)).astype(np.float32)
+        adj = ctx.aggregate_full(t, _dev(g), transpose=True, apply_q=True).cpu().numpy()
+        assert_close(adj, oracle.aggregate_adjoint(graphs[t].row_ptr, graphs[t].col, g, mode, self_loop), RTOL_FP32, f"adjoint t={t}")
+    ctx.close()
+
+
+@pytest.mark.parametrize("d,bf16", [(4, False), (8, False), (32, False), (64, False), (128, False), (256, False),
+                                    (8, True), (64, True), (256, True), (512, True)])
+def test_row_widths(d, bf16):
+    import torch
+
+    wl = synth.Workload("w", 2111, 9.0, 1, "chunglu", 2.1, 0, 0, "fp32", "sym", True, (64, 64), "gru", 64, 1)
+    seq = synth.make_sequence(wl)
+    ctx = _ctx(wl)
+    ctx.load_edges(0, *seq.edges[0])
+    g = oracle_graphs(seq)[0]
+    x = np.random.default_rng(d).standard_normal((wl.num_nodes, d)).astype(np.float32)
+    if bf16:
+        x = synth.round_to_bf16(x)
+    xd = _dev(x, torch.bfloat16 if bf16 else None)
+    _, agg_ref = oracle.aggregate(g.row_ptr, g.col, x, "sym", True)
+    assert_close(ctx.aggregate_full(0, xd, apply_q=True).cpu().numpy(), agg_ref, RTOL_BF16 if bf16 else RTOL_FP32, f"d={d}")
+    adj_ref = oracle.aggregate_adjoint(g.row_ptr, g.col, x, "sym", True)
+    assert_close(ctx.aggregate_full(0, xd, transpose=True, apply_q=True).cpu().numpy(), adj_ref,
+                 RTOL_BF16 if bf16 else RTOL_FP32, f"adjoint d={d}")
+    ctx.close()
+
+
+def test_unsupported_width_is_an_error():
+    import torch
+    from paper_2501_15348_amd import reinc
+
+    wl = synth.WORKLOADS["tiny"].scaled(50, 1)
+    ctx = _ctx(wl, arena=8 << 20)
+    ctx.load_edges(0, np.array([0], dtype=np.int32), np.array([1], dtype=np.int32))
+    with pytest.raises(reinc.ReincError) as e:
+        ctx.aggregate_full(0, torch.zeros((50, 12), device="cuda"))
+    assert e.value.code == reinc.E_UNSUPPORTED
+    ctx.close()
+
+
+def test_hub_rows_take_the_block_path():
+    """Rows beyond 512 entries are reduced by a whole block; both CSR and CSC sides."""
+    n, d = 5000, 64
+    rng = np.random.default_rng(3)
+    src = np.concatenate([rng.choice(np.arange(1, n), 3000, replace=False), np.full(2500, 1), rng.integers(0, n, 20000)])
+    dst = np.concatenate([np.zeros(3000, dtype=np.int64), rng.choice(np.arange(2, n), 2500, replace=False), rng.integers(0, n, 20000)])
+    wl = synth.Workload("hub", n, 5.0, 1, "uniform", 0, 0, 0, "fp32", "mean", True, (d, d), "gru", d, 1)
+    ctx = _ctx(wl)
+    ctx.load_edges(0, src.astype(np.int32), dst.astype(np.int32))
+    g = oracle.Graph(oracle.canonicalise(src, dst, n), n)
+    assert np.diff(g.row_ptr).max() > 2500
+    x = rng.standard_normal((n, d)).astype(np.float32)
+    _, agg_ref = oracle.aggregate(g.row_ptr, g.col, x, "mean", True)
+    out1 = ctx.aggregate_full(0, _dev(x), apply_q=True)
+    out2 = ctx.aggregate_full(0, _dev(x), apply_q=True)
+    assert_close(out1.cpu().numpy(), agg_ref, RTOL_FP32, "hub forward")
+    assert bool((out1 == out2).all()), "aggregation must be bit-reproducible"
+    adj = ctx.aggregate_full(0, _dev(x), transpose=True, apply_q=True).cpu().numpy()
+    assert_close(adj, oracle.aggregate_adjoint(g.row_ptr, g.col, x, "mean", True), RTOL_FP32, "hub adjoint")
+    ctx.close()
+
+
+def _incremental_chain(seq, in_place, rtol=RTOL_FP32):
+    import torch
+
+    wl = seq.workload
+    ctx = _ctx(wl)
+    ctx.load_sequence(seq)
+    ctx.build_deltas(-1)
+    graphs = oracle_graphs(seq)
+    s = ctx.aggregate_full(0)
+    agg = ctx.aggregate_full(0, apply_q=True)
+    for t in range(1, seq.num_snapshots):
+        print(f"[{wl.name}] incremental step {t} in_place={in_place}", flush=True)
+        s_before = s.clone()
+        if in_place:
+            ctx.aggregate_incremental(t, s, s, agg)
+        else:
+            s = ctx.aggregate_incremental(t, s)
+        torch.cuda.synchronize()
+        s_ref, agg_ref = oracle.aggregate(graphs[t].row_ptr, graphs[t].col, oracle_feats(seq, t), wl.agg, wl.self_loop)
+        assert_close(s.cpu().numpy(), s_ref, rtol, f"S t={t}")
+        if in_place:
+            assert_close(agg.cpu().numpy(), agg_ref, rtol, f"Agg t={t}")
+        _, _, rows, _ = ctx.get_merged_delta(t)
+        untouched = np.setdiff1d(np.arange(wl.num_nodes), rows)
+        assert np.array_equal(s.cpu().numpy()[untouched], s_before.cpu().numpy()[untouched]), "rows outside R_t must keep their bits"
+        full = ctx.aggregate_full(t)
+        assert_close(s.cpu().numpy(), full.cpu().numpy(), rtol, f"incremental vs full t={t}")
+    st = ctx.get_stats()
+    assert st["delta_entries_processed"] == sum(ctx.get_delta_info(t)["n_entries"] for t in range(1, seq.num_snapshots))
+    ctx.close()
+
+
+@pytest.mark.parametrize("in_place", [True, False])
+def test_incremental_chain_tiny(tiny_seq, in_place):
+    _incremental_chain(tiny_seq, in_place)
+
+
+@pytest.mark.parametrize("name,n,kw", [
+    ("c2", 20011, {}),  # sym: degree changes widen the change set
+    ("c3", 6007, dict(num_snapshots=5)),  # mean, d = 128
+    ("c5_25", 9001, dict(num_snapshots=4)),  # sum, heavy churn
+    ("c4", 3001, dict(num_snapshots=3, feat_churn=0.02)),  # bf16 features, d = 256
+])
+def test_incremental_chain_power_law(name, n, kw):
+    wl = synth.WORKLOADS[name].scaled(n, kw.pop("num_snapshots", 4), **kw)
+    seq = synth.make_sequence(wl)
+    _incremental_chain(seq, in_place=True, rtol=RTOL_BF16 if wl.feat_dtype == "bf16" else RTOL_FP32)
+
+
+def test_incremental_is_bit_reproducible(tiny_seq):
+    ctx = _ctx(tiny_seq.workload)
+    ctx.load_sequence(tiny_seq)
+    ctx.build_deltas(-1)
+    s0 = ctx.aggregate_full(0)
+    a = ctx.aggregate_incremental(1, s0)
+    b = ctx.aggregate_incremental(1, s0)
+    assert bool((a == b).all())
+    from paper_2501_15348_amd import reinc
+
+    with pytest.raises(reinc.ReincError) as e:  # overlapping but not identical buffers
+        flat = s0.reshape(-1)
+        ctx.lib.reinc_aggregate_incremental  # noqa: B018
+        import torch
+
+        big = torch.empty(s0.numel() + 16, device="cuda")
+        ctx.aggregate_incremental(1, big[:s0.numel()].view_as(s0), big[16:].view_as(s0))
+    assert e.value.code == reinc.E_ARG
+    ctx.close()
