@@ -402,10 +402,10 @@ int reinc_aggregate_full(reinc_ctx *ctx, int32_t t, int transpose, const void *X
     const int bf16 = x_dtype == REINC_BF16;
     if (!transpose)
         launch_aggregate(sn.row_ptr, sn.col, sn.long_rows, sn.n_long_rows, X, bf16, d, ctx->N(), ctx->cfg.self_loop, sn.p,
-                         apply_q ? sn.q : nullptr, out, as_stream(stream));
+                         apply_q ? sn.q : nullptr, nullptr, out, as_stream(stream));
     else
         launch_aggregate(sn.col_ptr, sn.row, sn.long_cols, sn.n_long_cols, X, bf16, d, ctx->N(), ctx->cfg.self_loop,
-                         apply_q ? sn.q : nullptr, sn.p, out, as_stream(stream));
+                         apply_q ? sn.q : nullptr, sn.p, nullptr, out, as_stream(stream));
     REINC_HIP(ctx, hipGetLastError());
     return REINC_OK;
 }

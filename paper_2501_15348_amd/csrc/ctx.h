@@ -80,10 +80,11 @@ struct reinc_ctx {
     std::vector<float *> gcache;
     // local cache
     std::vector<reinc::LocalStep> local;
-    uint64_t local_mark = 0;  // arena bottom before the local cache was carved
+    uint64_t local_reserved = 0;  // bytes at the top of the arena held by the local cache
     bool local_valid = false;
     int32_t local_t0 = -1, local_L = 0;
     float *zero_state = nullptr;  // [N, H] zeros
+    float *loss_partial = nullptr;
     reinc_stats stats{};
 
     int fail(int code, const char *fmt, ...) {
@@ -108,11 +109,11 @@ struct reinc_ctx {
     void *scratch(uint64_t bytes) {
         uint64_t b = (bytes + 255) & ~uint64_t(255);
         if (bottom + b > top) return nullptr;
-        top -= b;
+        top -= b;  // scratch sits below the local cache, which holds the last local_reserved bytes
         if (bottom + (size - top) > peak) peak = bottom + (size - top);
         return base + top;
     }
-    void scratch_reset() { top = size; }
+    void scratch_reset() { top = size - local_reserved; }
     int64_t N() const { return cfg.num_nodes; }
     int elem_bytes() const { return cfg.feat_dtype == REINC_BF16 ? 2 : 4; }
 };
@@ -154,16 +155,32 @@ void launch_dy(const void *x_prev, const void *x_cur, int bf16, const float *p_p
 // ---- kernels_agg.hip
 bool agg_width_supported(int32_t d, int bf16);
 // out[v] = out_scale[v] * ( self_loop * in_scale[v] X[v] + sum_{e in [ptr[v], ptr[v+1])} in_scale[idx[e]] X[idx[e]] )
-// in_scale / out_scale may be null (factor 1).
+// in_scale / out_scale may be null (factor 1); mask [n,d] (may be null) zeroes the output where mask <= 0.
 void launch_aggregate(const int64_t *ptr, const int32_t *idx, const int32_t *long_rows, int32_t n_long, const void *X,
                       int bf16, int32_t d, int64_t n, int self_loop, const float *in_scale, const float *out_scale,
-                      float *out, hipStream_t s);
+                      const float *mask, float *out, hipStream_t s);
 void launch_incremental(const int32_t *rows, int64_t n_rows, const int64_t *ent_ptr, const uint32_t *ent,
                         const void *x_prev, int bf16, const float *p_prev, const float *dY, int32_t d,
                         const float *S_prev, float *S_out, const float *q, float *agg_out, hipStream_t s);
 
 // ---- kernels_dense.hip
-int launch_gemm_rows(const void *A, int a_bf16, int64_t n, int32_t K, int32_t M, const float *row_scale,
-                     const float *W, int w_transposed, int32_t ldw, const float *bias, int relu,
-                     const float *out_row_scale, const float *relu_mask, float *out, int accumulate, hipStream_t s);
+// out[n,M] = epilogue((row_scale .* A)[n,K] * B[K,M]); B = W (ldw = row stride) or W^T when w_transposed.
+// epilogue: + bias, relu, + add[n,M], zero where mask[n,M] <= 0 (each optional)
+int launch_gemm_rows(const void *A, int a_bf16, int64_t n, int32_t K, int32_t M, const float *row_scale, const float *W,
+                     int w_transposed, int32_t ldw, const float *bias, int relu, const float *add, const float *mask,
+                     float *out, hipStream_t s);
+void launch_rnn_fused(int lstm, const float *x, int64_t n, int32_t d_in, int32_t H, const float *h_prev,
+                      const float *c_prev, const float *W_i, const float *W_h, const float *b_i, const float *b_h,
+                      float *h_out, float *c_out, float *saved, hipStream_t s);
+uint64_t reduce_partial_bytes(int64_t n, int32_t K, int32_t M);
+// dW[K,M] += (row_scale .* A)^T G ; db[M] += column sums of G (db may be null)
+void launch_gemm_reduce(const float *A, int32_t lda, const float *row_scale, const float *G, int32_t ldg, int64_t n,
+                        int32_t K, int32_t M, float *partial, float *dW, float *db, hipStream_t s);
+void launch_rnn_backward_elem(int lstm, int64_t n, int32_t H, const float *dh, const float *dc, const float *saved,
+                              const float *h_prev, const float *c_prev, const float *c_new, float *dgi, float *dgh,
+                              float *dh_carry, float *dc_prev, hipStream_t s);
+uint64_t loss_partial_bytes();
+void launch_mse(const float *h, const float *y, int64_t total, float *partial, float *loss, hipStream_t s);
+void launch_mse_grad(const float *h, const float *y, int64_t total, float *dh, hipStream_t s);
+void launch_fill_f32(float *p, int64_t n, float v, hipStream_t s);
 }  // namespace reinc

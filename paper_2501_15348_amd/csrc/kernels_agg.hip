@@ -125,7 +125,7 @@ template <int LPR, bool BF16>
 __global__ void __launch_bounds__(64 * kWavesPerBlock)
 aggregate_rows(const int64_t *__restrict__ ptr, const int32_t *__restrict__ idx, const void *__restrict__ X, int64_t n,
                int self_loop, const float *__restrict__ in_scale, const float *__restrict__ out_scale,
-               float *__restrict__ out, int skip_long)
+               const float *__restrict__ mask, float *__restrict__ out, int skip_long)
 {
     constexpr int VEC = Row<BF16>::kVec;
     constexpr int D = LPR * VEC;
@@ -152,6 +152,13 @@ aggregate_rows(const int64_t *__restrict__ ptr, const int32_t *__restrict__ idx,
 #pragma unroll
             for (int i = 0; i < VEC; ++i) acc[i] *= q;
         }
+        if (mask) {
+            float m[VEC];
+            load_f32<VEC>(mask, v, D, lane, m);
+#pragma unroll
+            for (int i = 0; i < VEC; ++i)
+                if (!(m[i] > 0.0f)) acc[i] = 0.0f;
+        }
         store_f32<VEC>(out, v, D, lane, acc);
     }
 }
@@ -161,7 +168,8 @@ template <int LPR, bool BF16>
 __global__ void __launch_bounds__(64 * kWavesPerBlock)
 aggregate_long_rows(const int32_t *__restrict__ long_rows, const int64_t *__restrict__ ptr,
                     const int32_t *__restrict__ idx, const void *__restrict__ X, int self_loop,
-                    const float *__restrict__ in_scale, const float *__restrict__ out_scale, float *__restrict__ out)
+                    const float *__restrict__ in_scale, const float *__restrict__ out_scale,
+                    const float *__restrict__ mask, float *__restrict__ out)
 {
     constexpr int VEC = Row<BF16>::kVec;
     constexpr int D = LPR * VEC;
@@ -196,6 +204,13 @@ aggregate_long_rows(const int32_t *__restrict__ long_rows, const int64_t *__rest
             const float q = out_scale[v];
 #pragma unroll
             for (int i = 0; i < VEC; ++i) acc[i] *= q;
+        }
+        if (mask) {
+            float m[VEC];
+            load_f32<VEC>(mask, v, D, lane, m);
+#pragma unroll
+            for (int i = 0; i < VEC; ++i)
+                if (!(m[i] > 0.0f)) acc[i] = 0.0f;
         }
         store_f32<VEC>(out, v, D, lane, acc);
     }
@@ -285,18 +300,18 @@ inline int lanes_per_row(int32_t d, int bf16)
 
 template <bool BF16>
 void aggregate_dispatch(int lpr, const int64_t *ptr, const int32_t *idx, const int32_t *long_rows, int32_t n_long,
-                        const void *X, int64_t n, int self_loop, const float *in_scale, const float *out_scale, float *out,
-                        hipStream_t s)
+                        const void *X, int64_t n, int self_loop, const float *in_scale, const float *out_scale,
+                        const float *mask, float *out, hipStream_t s)
 {
     const unsigned blocks = unsigned((n + kWavesPerBlock - 1) / kWavesPerBlock);
     const dim3 th(64 * kWavesPerBlock);
     const int skip = n_long > 0;
 #define REINC_AGG_CASE(L)                                                                                          \
     case L:                                                                                                        \
-        aggregate_rows<L, BF16><<<blocks, th, 0, s>>>(ptr, idx, X, n, self_loop, in_scale, out_scale, out, skip);  \
+        aggregate_rows<L, BF16><<<blocks, th, 0, s>>>(ptr, idx, X, n, self_loop, in_scale, out_scale, mask, out, skip);  \
         if (n_long > 0)                                                                                            \
             aggregate_long_rows<L, BF16><<<unsigned(n_long), th, 0, s>>>(long_rows, ptr, idx, X, self_loop, in_scale, \
-                                                                         out_scale, out);                          \
+                                                                         out_scale, mask, out);                    \
         break;
     switch (lpr) {
         REINC_AGG_CASE(1)
@@ -340,14 +355,14 @@ bool agg_width_supported(int32_t d, int bf16) { return lanes_per_row(d, bf16) !=
 
 void launch_aggregate(const int64_t *ptr, const int32_t *idx, const int32_t *long_rows, int32_t n_long, const void *X,
                       int bf16, int32_t d, int64_t n, int self_loop, const float *in_scale, const float *out_scale,
-                      float *out, hipStream_t s)
+                      const float *mask, float *out, hipStream_t s)
 {
     if (n <= 0) return;
     const int lpr = lanes_per_row(d, bf16);
     if (bf16)
-        aggregate_dispatch<true>(lpr, ptr, idx, long_rows, n_long, X, n, self_loop, in_scale, out_scale, out, s);
+        aggregate_dispatch<true>(lpr, ptr, idx, long_rows, n_long, X, n, self_loop, in_scale, out_scale, mask, out, s);
     else
-        aggregate_dispatch<false>(lpr, ptr, idx, long_rows, n_long, X, n, self_loop, in_scale, out_scale, out, s);
+        aggregate_dispatch<false>(lpr, ptr, idx, long_rows, n_long, X, n, self_loop, in_scale, out_scale, mask, out, s);
 }
 
 void launch_incremental(const int32_t *rows, int64_t n_rows, const int64_t *ent_ptr, const uint32_t *ent,

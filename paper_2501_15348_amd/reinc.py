@@ -317,10 +317,17 @@ class Context:
     def cache_clear(self):
         self._ck(self.lib.reinc_cache_clear(self.handle))
 
-    def cache_peek(self, t: int) -> int:
+    def cache_peek(self, t: int):
+        """The cached layer-1 sums of snapshot t as a tensor view into the arena, or None."""
+        import torch
+
         ptr = ctypes.c_void_p()
         self._ck(self.lib.reinc_cache_peek(self.handle, t, ctypes.byref(ptr)))
-        return ptr.value or 0
+        if not ptr.value:
+            return None
+        off = ptr.value - self.arena.data_ptr()
+        nbytes = self.n * self.dims[0] * 4
+        return self.arena[off:off + nbytes].view(torch.float32).view(self.n, self.dims[0])
 
     def get_stats(self) -> dict:
         st = Stats()
