@@ -1,0 +1,275 @@
+#!/usr/bin/env python3
+"""Benchmark of the incremental dynamic-GNN hot path on one MI355X.
+
+One "step" is one cold pass of the whole path over one synthetic snapshot sequence that is already
+resident in HBM: build the per-step deltas, then slide a window of L snapshots over the sequence and
+run forward + backward + SGD for every window (the first epoch: the layer-1 sums are computed once,
+by the incremental rule or, above the change-ratio threshold, from scratch, and reused by every later
+window).  `value` is the number of effective delta edges of the sequence absorbed per second of that
+pass.  Prints one JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X HBM3E
+
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
+# command (profiles/aggregate_rows_c2_pmc.txt), scaled by the copy-kernel calibration; None = not measured.
+MEASURED_TRAFFIC = {}
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="c2")
+    ap.add_argument("--nodes", type=int, default=0, help="scale the workload down to this many nodes (debug)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="skip the per-kernel measurements after the timed region")
+    return ap.parse_args()
+
+
+def agg_bytes(num_edges: float, n: int, d: int, elem: int) -> float:
+    """Algorithmic bytes of one from-scratch aggregation launch: a column index and one source row per edge,
+    one row pointer pair and one fp32 output row per node."""
+    return num_edges * (4 + d * elem) + n * (d * 4 + 16)
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+
+    from paper_2501_15348_amd import reinc, synth
+
+    wl = synth.WORKLOADS[args.workload]
+    if args.nodes:
+        wl = wl.scaled(args.nodes)
+    n, T, L = wl.num_nodes, wl.num_snapshots, min(wl.window, wl.num_snapshots)
+    elem = 2 if wl.feat_dtype == "bf16" else 4
+    t_gen = time.perf_counter()
+    seq = synth.make_sequence(wl)
+    t_gen = time.perf_counter() - t_gen
+
+    # arena: snapshots + features + deltas + caches, with head-room
+    feat_bytes = T * n * wl.dims[0] * elem
+    edge_bytes = T * (wl.num_edges * 8 + n * 24)
+    cache_bytes = T * n * wl.dims[0] * 4
+    local_bytes = (L + 4) * n * (sum(wl.dims[1:]) * 2 + 6 * wl.hidden + 4 * max(wl.dims)) * 4
+    delta_bytes = T * (wl.num_edges * 8 + n * 40 + n * wl.dims[0] * 4)
+    arena = int(1.25 * (feat_bytes + edge_bytes + cache_bytes + local_bytes + delta_bytes)) + (256 << 20)
+    ctx = reinc.Context.for_workload(wl, arena_bytes=arena, fallback_ratio=0.5)
+    t_load = time.perf_counter()
+    ctx.load_sequence(seq)
+    torch.cuda.synchronize()
+    t_load = time.perf_counter() - t_load
+
+    params0 = torch.from_numpy(synth.make_params(wl)).cuda()
+    params = params0.clone()
+    target = torch.from_numpy(synth.make_target(wl)).cuda()
+    grads = torch.empty_like(params)
+    loss = torch.zeros(1, device="cuda")
+    windows = T - L + 1
+
+    def step():
+        ctx.reset_derived()
+        ctx.build_deltas(-1)
+        for t0 in range(windows):
+            ctx.forward_window(t0, L, params, target, loss)
+            ctx.backward_window(t0, L, params, target, grads)
+            ctx.sgd_step(params, grads, 1e-2)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    st0 = ctx.get_stats()
+    ctx.profile_begin(("agg_full",))
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    prof = ctx.profile_end()
+    st1 = ctx.get_stats()
+    ms_per_step = elapsed * 1e3 / args.steps
+    loss_value = float(loss.item())
+
+    infos = [ctx.get_delta_info(t) for t in range(1, T)]
+    delta_edges = sum(i["n_entries"] for i in infos)
+    value = delta_edges / (ms_per_step * 1e-3)
+
+    # ---- roofline of the dominant kernel (wave-per-row gather): algorithmic bytes / measured launch time
+    launches, total_ms = prof["agg_full"]
+    per_step_full = (st1["steps_full"] - st0["steps_full"]) / args.steps
+    e_mean = float(np.mean([len(s) for s, _ in seq.edges]))
+    layers = len(wl.dims) - 1
+    sched = [(per_step_full, agg_bytes(e_mean, n, wl.dims[0], elem))]
+    for l in range(2, layers + 1):  # forward aggregate and backward adjoint of layer l, per window timestep
+        sched.append((2 * windows * L, agg_bytes(e_mean, n, wl.dims[l - 1], 4)))
+    exp_launches = sum(c for c, _ in sched) * args.steps
+    bytes_per_launch = sum(c * b for c, b in sched) / max(sum(c for c, _ in sched), 1)
+    avg_ms = total_ms / max(launches, 1)
+    achieved = bytes_per_launch / (avg_ms * 1e-3) / 1e9 if launches else 0.0
+    roofline = {
+        "bound": "hbm", "kernel": "aggregate_rows", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC.get(wl.name),
+        "launches": int(launches), "expected_launches": int(exp_launches), "avg_us": round(avg_ms * 1e3, 2),
+        "algorithmic_bytes_per_launch": int(bytes_per_launch),
+        "share_of_step_time": round(total_ms / (elapsed * 1e3), 3),
+    }
+
+    out = {
+        "metric": "delta-edges/sec", "value": round(value, 1), "unit": "delta-edges/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32" if elem == 4 else "bf16-in/f32-acc", "data": "synthetic",
+        "config": {"workload": wl.name, "num_nodes": n, "num_edges": wl.num_edges, "snapshots": T, "window": L,
+                   "windows_per_step": windows, "edge_churn": wl.edge_churn, "feat_churn": wl.feat_churn, "agg": wl.agg,
+                   "dims": list(wl.dims), "rnn": wl.rnn, "hidden": wl.hidden, "fallback_ratio": 0.5,
+                   "step": "build deltas + cold epoch of forward/backward/SGD over all windows"},
+        "delta_edges_per_step": int(delta_edges), "snapshot_window_epoch_ms": round(ms_per_step, 3),
+        "layer1_steps": {"incremental": (st1["steps_incremental"] - st0["steps_incremental"]) // args.steps,
+                         "full": (st1["steps_full"] - st0["steps_full"]) // args.steps,
+                         "fallback": (st1["steps_fallback"] - st0["steps_fallback"]) // args.steps},
+        "loss": loss_value, "host_load_s": round(t_load, 3), "generate_s": round(t_gen, 3),
+        "roofline": roofline,
+    }
+
+    if not args.no_extras:
+        out["kernels"] = extras(ctx, wl, seq, infos, params0, target, step, elapsed / args.steps)
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl, seq, windows, L, delta_edges)
+    ctx.close()
+    print(json.dumps(out), flush=True)
+
+
+def extras(ctx, wl, seq, infos, params, target, step, step_s):
+    """Per-kernel figures measured after the timed region (not part of `value`)."""
+    import numpy as np
+    import torch
+
+    n, T, d = wl.num_nodes, wl.num_snapshots, wl.dims[0]
+    elem = 2 if wl.feat_dtype == "bf16" else 4
+    res = {}
+    # time share per kernel class over one more cold step
+    ctx.profile_begin(reinc_kinds())
+    step()
+    prof = ctx.profile_end()
+    res["breakdown_ms"] = {k: {"launches": int(c), "total_ms": round(ms, 3)} for k, (c, ms) in prof.items() if c}
+
+    def timed(fn, reps=10):
+        fn()
+        torch.cuda.synchronize()
+        evs = []
+        for _ in range(reps):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            fn()
+            b.record()
+            evs.append((a, b))
+        torch.cuda.synchronize()
+        ts = sorted(a.elapsed_time(b) for a, b in evs)
+        return ts[len(ts) // 2]
+
+    # incremental (forced) versus from-scratch layer-1 aggregation, per step, in place
+    s = ctx.aggregate_full(0)
+    work = s.clone()
+    out = torch.empty_like(s)
+    inc_ms, full_ms, inc_bytes = [], [], []
+    for t in range(1, T):
+        i = infos[t - 1]
+        inc_ms.append(timed(lambda: ctx.aggregate_incremental(t, work, work)))
+        full_ms.append(timed(lambda: ctx.aggregate_full(t, out=out)))
+        inc_bytes.append(i["n_entries"] * (4 + d * elem) + i["n_rows"] * (2 * d * 4 + 20))
+    e_mean = float(np.mean([len(a) for a, _ in seq.edges]))
+    ent = sum(i["n_entries"] for i in infos)
+    res["aggregate_incremental"] = {
+        "delta_edges_per_s": round(ent / (sum(inc_ms) * 1e-3), 1), "mean_us": round(1e3 * sum(inc_ms) / len(inc_ms), 2),
+        "algorithmic_GBps": round(sum(inc_bytes) / (sum(inc_ms) * 1e-3) / 1e9, 1),
+        "hbm_frac": round(sum(inc_bytes) / (sum(inc_ms) * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+        "mean_changed_row_fraction": round(float(np.mean([i["n_rows"] for i in infos])) / n, 4),
+        "mean_delta_to_edge_ratio": round(ent / (len(infos) * e_mean), 4),
+    }
+    fb = agg_bytes(e_mean, n, d, elem)
+    res["aggregate_full"] = {"mean_us": round(1e3 * sum(full_ms) / len(full_ms), 2),
+                             "algorithmic_GBps": round(fb * len(full_ms) / (sum(full_ms) * 1e-3) / 1e9, 1),
+                             "hbm_frac": round(fb * len(full_ms) / (sum(full_ms) * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+    res["incremental_speedup_over_full"] = round(sum(full_ms) / sum(inc_ms), 3)
+    # snapshot-diff builder
+    ctx.reset_derived()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ctx.build_deltas(-1)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    res["build_deltas"] = {"ms_per_step": round(dt * 1e3 / (T - 1), 3),
+                           "edges_per_s": round(sum(i["num_edges_prev"] + i["num_edges_cur"] for i in infos) / dt, 1)}
+    # warm epoch: every layer-1 sum comes from the global cache
+    L = min(wl.window, T)
+    loss = torch.zeros(1, device="cuda")
+    grads = torch.empty_like(params)
+    p = params.clone()
+
+    def epoch():
+        for t0_ in range(T - L + 1):
+            ctx.forward_window(t0_, L, p, target, loss)
+            ctx.backward_window(t0_, L, p, target, grads)
+            ctx.sgd_step(p, grads, 1e-2)
+
+    epoch()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    epoch()
+    torch.cuda.synchronize()
+    res["warm_epoch_ms"] = round((time.perf_counter() - t0) * 1e3, 3)
+    res["cold_epoch_ms"] = round(step_s * 1e3, 3)
+    return res
+
+
+def reinc_kinds():
+    from paper_2501_15348_amd import reinc
+
+    return reinc.KERNEL_KINDS
+
+
+def cpu_baseline(wl, seq, windows, L, delta_edges_epoch):
+    """The CPU reference as it stands (from-scratch fp64, every snapshot recomputed), timed on this host."""
+    import numpy as np
+
+    import oracle
+    from paper_2501_15348_amd import synth
+
+    n = wl.num_nodes
+    Ls = min(L, 2 if n > 300_000 else 4)
+    layers = len(wl.dims) - 1
+    graphs = oracle.graphs_of(seq.edges[:Ls], n)
+    feats = [oracle.features_at(seq.x0, seq.feat_rows, seq.feat_vals, t) for t in range(Ls)]
+    p = synth.split_params(wl, synth.make_params(wl).astype(np.float64))
+    target = synth.make_target(wl)
+    t0 = time.perf_counter()
+    _, h, saved = oracle.forward_window(graphs, feats, p, layers, wl.agg, wl.self_loop, wl.rnn, target, keep=True)
+    oracle.backward_window(graphs, saved, h, p, layers, wl.agg, wl.self_loop, wl.rnn, target)
+    dt = time.perf_counter() - t0
+    est_epoch = dt * (windows * L) / Ls  # the reference does the same work for every window timestep
+    return {"value": round(delta_edges_epoch / est_epoch, 1), "unit": "delta-edges/s", "cores": oracle.num_threads(),
+            "kind": "oracle",
+            "sample": f"forward+backward of one {Ls}-snapshot window of the same workload ({dt:.2f} s), scaled to the "
+                      f"{windows}x{L} window-timesteps of one step",
+            "sample_seconds": round(dt, 3)}
+
+
+if __name__ == "__main__":
+    main()

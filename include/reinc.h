@@ -132,7 +132,7 @@ int reinc_load_features_delta(reinc_ctx *ctx, int32_t t, const int32_t *rows, in
  *     ascending, and dY = P_t X_t - P_{t-1} X_{t-1} on those rows;
  *   - the merged signed delta rows used by reinc_aggregate_incremental: for each row v, first the inserted
  *     sources, then the deleted sources, then the sources u in C_t of v's in-edges at t (and v itself when
- *     self_loop is set and v is in C_t), each group ascending;
+ *     self_loop is set and v is in C_t, placed last), each group ascending;
  *   - R_t, the ascending list of rows with at least one entry.
  * Needs edges and features of snapshots t-1 and t.  SYNC (sizes are read back to carve the arena). */
 int reinc_build_deltas(reinc_ctx *ctx, int32_t t, void *stream);
@@ -164,7 +164,9 @@ int reinc_aggregate_full(reinc_ctx *ctx, int32_t t, int transpose, const void *X
  *     S_t[r] = S_{t-1}[r] + sum_{inserted u} Y_{t-1}[u] - sum_{deleted u} Y_{t-1}[u] + sum_{changed u} dY[u]
  * and S_t[r] = S_{t-1}[r] elsewhere.  S_prev, S_out: device fp32 [N, dims[0]].  S_out may be S_prev itself
  * (in place: only rows in R_t are touched) or a disjoint buffer (all rows are written).  Needs
- * reinc_build_deltas(t).  agg_out (may be NULL): device fp32 [N, dims[0]], receives Q_t S_t. */
+ * reinc_build_deltas(t).  agg_out (may be NULL): device fp32 [N, dims[0]]; its rows in R_t receive Q_t S_t and
+ * its other rows are left alone, so a buffer that held Agg_{t-1} holds Agg_t afterwards (a row outside R_t
+ * keeps both its sum and its degree). */
 int reinc_aggregate_incremental(reinc_ctx *ctx, int32_t t, const float *S_prev, float *S_out, float *agg_out,
                                 void *stream);
 
@@ -201,11 +203,34 @@ int reinc_forward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *par
  * reinc_forward_window call (same t0, L, params, target).  grads: device, same layout as params, overwritten. */
 int reinc_backward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *params, const float *target,
                           float *grads, void *stream);
+/* params[i] -= lr * grads[i] for count fp32 values (plain SGD; the paper names no optimiser), ASYNC. */
+int reinc_sgd_step(reinc_ctx *ctx, float *params, const float *grads, int64_t count, float lr, void *stream);
 /* Drops every cached layer-1 sum (the next windows recompute them). */
 int reinc_cache_clear(reinc_ctx *ctx);
+/* Drops everything derived from the loaded snapshots -- deltas, cached sums, the local cache -- and returns
+ * their arena space, so that the next reinc_build_deltas / window calls start cold.  Fails with REINC_E_STATE
+ * if a snapshot was loaded after the first derived structure was built.  SYNC. */
+int reinc_reset_derived(reinc_ctx *ctx);
 /* Device pointer of the cached layer-1 sums S_t ([N, dims[0]] fp32) or NULL if not cached. */
 int reinc_cache_peek(reinc_ctx *ctx, int32_t t, const float **S_out);
 int reinc_get_stats(reinc_ctx *ctx, reinc_stats *out);
+
+/* ---- kernel timing ------------------------------------------------------------------------------------------
+ * Between reinc_profile_begin and reinc_profile_end every launch of a kernel class selected in `mask`
+ * (bit REINC_K_*) is bracketed by a pair of HIP events on the stream it runs on.  reinc_profile_end waits for
+ * the device (SYNC) and fills launches[k] and total_ms[k] for k < REINC_K_COUNT.  At most
+ * REINC_PROFILE_MAX_LAUNCHES launches are recorded per session; later ones run untimed. */
+#define REINC_K_AGG_FULL 0   /* wave-per-row gather of reinc_aggregate_full (forward and adjoint) */
+#define REINC_K_AGG_INC 1    /* incremental row update */
+#define REINC_K_GEMM_ROWS 2  /* row-tile GEMM (GCN update, input gradients) */
+#define REINC_K_RNN 3        /* fused recurrent step */
+#define REINC_K_REDUCE 4     /* weight-gradient reduction GEMM */
+#define REINC_K_ELEM 5       /* elementwise recurrent backward */
+#define REINC_K_DIFF 6       /* snapshot-diff count + fill */
+#define REINC_K_COUNT 7
+#define REINC_PROFILE_MAX_LAUNCHES 16384
+int reinc_profile_begin(reinc_ctx *ctx, uint32_t mask);
+int reinc_profile_end(reinc_ctx *ctx, int64_t *launches, double *total_ms);
 
 #ifdef __cplusplus
 }

@@ -22,6 +22,7 @@ __all__ = [
     "csr_from_keys",
     "edge_deltas",
     "features_at",
+    "change_counts",
     "degrees",
     "aggregate",
     "aggregate_adjoint",
@@ -115,6 +116,30 @@ def features_at(x0: np.ndarray, feat_rows: Sequence[np.ndarray], feat_vals: Sequ
         if len(feat_rows[s]):
             x[feat_rows[s]] = feat_vals[s]
     return x
+
+
+def change_counts(g_prev: "Graph", g_cur: "Graph", x_prev, x_cur, mode: str, self_loop: bool) -> Dict[str, int]:
+    """Size of one step's change (Section 3.2): inserted and deleted edges, the nodes whose scaled feature row
+    differs (for "sym" a degree change alters the scaling), the current out-edges of those nodes (self-loop
+    included) -- together the effective delta edges -- and the number of target rows they touch."""
+    n = g_cur.n
+    ins = np.setdiff1d(g_cur.keys, g_prev.keys, assume_unique=True)
+    dele = np.setdiff1d(g_prev.keys, g_cur.keys, assume_unique=True)
+    changed = np.any(np.asarray(x_prev) != np.asarray(x_cur), axis=1)
+    if mode == "sym":
+        changed |= np.diff(g_prev.row_ptr) != np.diff(g_cur.row_ptr)
+    hit = changed[g_cur.col]
+    rows_cur = np.repeat(np.arange(n), np.diff(g_cur.row_ptr))
+    touched = np.zeros(n, dtype=bool)
+    touched[(ins >> np.uint64(32)).astype(np.int64)] = True
+    touched[(dele >> np.uint64(32)).astype(np.int64)] = True
+    touched[rows_cur[hit]] = True
+    n_f = int(hit.sum())
+    if self_loop:
+        touched |= changed
+        n_f += int(changed.sum())
+    return dict(n_ins=int(ins.size), n_del=int(dele.size), n_changed=int(changed.sum()), n_fchg_entries=n_f,
+                n_entries=int(ins.size + dele.size + n_f), n_rows=int(touched.sum()))
 
 
 def degrees(row_ptr: np.ndarray, self_loop: bool) -> np.ndarray:

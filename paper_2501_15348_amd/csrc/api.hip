@@ -88,6 +88,8 @@ int reinc_create(reinc_ctx **out, const reinc_config *cfg)
 
 int reinc_destroy(reinc_ctx *ctx)
 {
+    if (ctx)
+        for (hipEvent_t e : ctx->prof_events) (void)hipEventDestroy(e);
     delete ctx;
     return REINC_OK;
 }
@@ -165,6 +167,7 @@ int reinc_load_edges(reinc_ctx *ctx, int32_t t, const int32_t *src, const int32_
         if (agg == REINC_AGG_SYM) sn.p = sn.q;  // same numbers on both sides
     }
     sn.edges_loaded = true;
+    if (ctx->has_derived) ctx->load_after_derived = true;
     return REINC_OK;
 }
 
@@ -183,6 +186,7 @@ int reinc_load_features_full(reinc_ctx *ctx, int32_t t, const void *X, int on_de
     REINC_HIP(ctx, hipDeviceSynchronize());
     sn.feats_loaded = true;
     sn.feats_from_delta = false;
+    if (ctx->has_derived) ctx->load_after_derived = true;
     return REINC_OK;
 }
 
@@ -219,6 +223,7 @@ int reinc_load_features_delta(reinc_ctx *ctx, int32_t t, const int32_t *rows, in
     REINC_HIP(ctx, hipDeviceSynchronize());
     sn.feats_loaded = true;
     sn.feats_from_delta = true;
+    if (ctx->has_derived) ctx->load_after_derived = true;
     return REINC_OK;
 }
 
@@ -236,6 +241,7 @@ static int build_one(reinc_ctx *ctx, int32_t t, hipStream_t s)
     if (!a.edges_loaded || !b.edges_loaded || !a.feats_loaded || !b.feats_loaded)
         return ctx->fail(REINC_E_STATE, "step %d needs edges and features of snapshots %d and %d", t, t - 1, t);
     ctx->scratch_reset();
+    ctx->note_derived();
     const uint64_t mark = ctx->bottom;
     auto nomem = [&](const char *what) {
         ctx->bottom = mark;
@@ -275,8 +281,11 @@ static int build_one(reinc_ctx *ctx, int32_t t, hipStream_t s)
     launch_dy(a.x, b.x, bf16, a.p, b.p, dl.changed, n_changed, d, dl.dY, s);
 
     // per-row counts, row pointers
-    launch_delta_count(a.row_ptr, a.col, b.row_ptr, b.col, cflags, ctx->cfg.self_loop, n, cnt_ins, cnt_del, cnt_all,
-                       row_flag, s);
+    {
+        ProfScope prof(ctx, REINC_K_DIFF, s);
+        launch_delta_count(a.row_ptr, a.col, b.row_ptr, b.col, cflags, ctx->cfg.self_loop, n, cnt_ins, cnt_del, cnt_all,
+                           row_flag, s);
+    }
     launch_scan(cnt_ins, dl.ins_ptr, n, scan_tmp, s);
     launch_scan(cnt_del, dl.del_ptr, n, scan_tmp, s);
     launch_scan(cnt_all, dl.ent_ptr, n, scan_tmp, s);
@@ -292,8 +301,11 @@ static int build_one(reinc_ctx *ctx, int32_t t, hipStream_t s)
     dl.ent = static_cast<uint32_t *>(ctx->alloc(uint64_t(std::max<int64_t>(totals[2], 1)) * 4));
     dl.rows = static_cast<int32_t *>(ctx->alloc(uint64_t(std::max<int64_t>(totals[3], 1)) * 4));
     if (!dl.ins_col || !dl.del_col || !dl.ent || !dl.rows) return nomem("delta entries");
-    launch_delta_fill(a.row_ptr, a.col, b.row_ptr, b.col, cindex, ctx->cfg.self_loop, n, dl.ins_ptr, dl.ins_col,
-                      dl.del_ptr, dl.del_col, dl.ent_ptr, dl.ent, s);
+    {
+        ProfScope prof(ctx, REINC_K_DIFF, s);
+        launch_delta_fill(a.row_ptr, a.col, b.row_ptr, b.col, cindex, ctx->cfg.self_loop, n, dl.ins_ptr, dl.ins_col,
+                          dl.del_ptr, dl.del_col, dl.ent_ptr, dl.ent, s);
+    }
     launch_compact(row_flag, roffs, n, dl.rows, nullptr, s);
     REINC_HIP(ctx, hipGetLastError());
     REINC_HIP(ctx, hipStreamSynchronize(s));
@@ -401,11 +413,11 @@ int reinc_aggregate_full(reinc_ctx *ctx, int32_t t, int transpose, const void *X
         return ctx->fail(REINC_E_UNSUPPORTED, "row of %d elements: row bytes must be a power of two in [16, 1024]", d);
     const int bf16 = x_dtype == REINC_BF16;
     if (!transpose)
-        launch_aggregate(sn.row_ptr, sn.col, sn.long_rows, sn.n_long_rows, X, bf16, d, ctx->N(), ctx->cfg.self_loop, sn.p,
-                         apply_q ? sn.q : nullptr, nullptr, out, as_stream(stream));
+        aggregate_full(ctx, sn.row_ptr, sn.col, sn.long_rows, sn.n_long_rows, X, bf16, d, ctx->cfg.self_loop, sn.p,
+                       apply_q ? sn.q : nullptr, nullptr, out, as_stream(stream));
     else
-        launch_aggregate(sn.col_ptr, sn.row, sn.long_cols, sn.n_long_cols, X, bf16, d, ctx->N(), ctx->cfg.self_loop,
-                         apply_q ? sn.q : nullptr, sn.p, nullptr, out, as_stream(stream));
+        aggregate_full(ctx, sn.col_ptr, sn.row, sn.long_cols, sn.n_long_cols, X, bf16, d, ctx->cfg.self_loop,
+                       apply_q ? sn.q : nullptr, sn.p, nullptr, out, as_stream(stream));
     REINC_HIP(ctx, hipGetLastError());
     return REINC_OK;
 }
@@ -426,10 +438,73 @@ int reinc_aggregate_incremental(reinc_ctx *ctx, int32_t t, const float *S_prev, 
         if (a < b + bytes && b < a + bytes) return ctx->fail(REINC_E_ARG, "S_out must be S_prev itself or disjoint from it");
         REINC_HIP(ctx, hipMemcpyAsync(S_out, S_prev, bytes, hipMemcpyDeviceToDevice, as_stream(stream)));
     }
-    launch_incremental(dl.rows, dl.info.n_rows, dl.ent_ptr, dl.ent, pv.x, ctx->cfg.feat_dtype == REINC_BF16, pv.p, dl.dY, d,
-                       S_out, S_out, sn.q, agg_out, as_stream(stream));
+    {
+        ProfScope prof(ctx, REINC_K_AGG_INC, as_stream(stream));
+        launch_incremental(dl.rows, dl.info.n_rows, dl.ent_ptr, dl.ent, pv.x, ctx->cfg.feat_dtype == REINC_BF16, pv.p, dl.dY,
+                           d, S_out, S_out, sn.q, agg_out, as_stream(stream));
+    }
     REINC_HIP(ctx, hipGetLastError());
     ctx->stats.delta_entries_processed += dl.info.n_entries;
+    return REINC_OK;
+}
+
+int reinc_reset_derived(reinc_ctx *ctx)
+{
+    if (!ctx) return REINC_E_ARG;
+    if (!ctx->has_derived) return REINC_OK;
+    if (ctx->load_after_derived)
+        return ctx->fail(REINC_E_STATE, "a snapshot was loaded after deltas or caches were built: their space cannot be returned");
+    REINC_HIP(ctx, hipSetDevice(ctx->cfg.device));
+    REINC_HIP(ctx, hipDeviceSynchronize());
+    ctx->bottom = ctx->derived_mark;
+    ctx->has_derived = false;
+    for (Delta &d : ctx->deltas) d = Delta();
+    std::fill(ctx->gcache.begin(), ctx->gcache.end(), nullptr);
+    ctx->local.clear();
+    ctx->local_L = 0;
+    ctx->local_valid = false;
+    ctx->local_reserved = 0;
+    ctx->zero_state = nullptr;
+    ctx->loss_partial = nullptr;
+    ctx->stats.local_bytes = 0;
+    ctx->scratch_reset();
+    return REINC_OK;
+}
+
+int reinc_sgd_step(reinc_ctx *ctx, float *params, const float *grads, int64_t count, float lr, void *stream)
+{
+    if (!ctx) return REINC_E_ARG;
+    if (!params || !grads || count < 0) return ctx->fail(REINC_E_ARG, "null params or grads");
+    launch_sgd(params, grads, count, lr, as_stream(stream));
+    REINC_HIP(ctx, hipGetLastError());
+    return REINC_OK;
+}
+
+int reinc_profile_begin(reinc_ctx *ctx, uint32_t mask)
+{
+    if (!ctx) return REINC_E_ARG;
+    ctx->prof_kind.clear();
+    ctx->prof_mask = mask;
+    return REINC_OK;
+}
+
+int reinc_profile_end(reinc_ctx *ctx, int64_t *launches, double *total_ms)
+{
+    if (!ctx || !launches || !total_ms) return REINC_E_ARG;
+    ctx->prof_mask = 0;
+    REINC_HIP(ctx, hipSetDevice(ctx->cfg.device));
+    REINC_HIP(ctx, hipDeviceSynchronize());
+    for (int k = 0; k < REINC_K_COUNT; ++k) {
+        launches[k] = 0;
+        total_ms[k] = 0.0;
+    }
+    for (size_t i = 0; i < ctx->prof_kind.size(); ++i) {
+        float ms = 0.0f;
+        REINC_HIP(ctx, hipEventElapsedTime(&ms, ctx->prof_events[2 * i], ctx->prof_events[2 * i + 1]));
+        launches[ctx->prof_kind[i]] += 1;
+        total_ms[ctx->prof_kind[i]] += double(ms);
+    }
+    ctx->prof_kind.clear();
     return REINC_OK;
 }
 

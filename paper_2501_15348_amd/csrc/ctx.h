@@ -86,6 +86,19 @@ struct reinc_ctx {
     float *zero_state = nullptr;  // [N, H] zeros
     float *loss_partial = nullptr;
     reinc_stats stats{};
+    // arena bookkeeping for reinc_reset_derived
+    bool has_derived = false, load_after_derived = false;
+    uint64_t derived_mark = 0;
+    void note_derived() {
+        if (!has_derived) {
+            has_derived = true;
+            derived_mark = bottom;
+        }
+    }
+    // kernel timing (reinc_profile_begin / _end)
+    uint32_t prof_mask = 0;
+    std::vector<hipEvent_t> prof_events;  // pool, two per recorded launch
+    std::vector<int> prof_kind;           // kind of each recorded launch
 
     int fail(int code, const char *fmt, ...) {
         char buf[512];
@@ -117,6 +130,32 @@ struct reinc_ctx {
     int64_t N() const { return cfg.num_nodes; }
     int elem_bytes() const { return cfg.feat_dtype == REINC_BF16 ? 2 : 4; }
 };
+
+namespace reinc {
+// Brackets the launches issued during its lifetime with an event pair when their kind is being profiled.
+struct ProfScope {
+    reinc_ctx *ctx;
+    hipStream_t s;
+    int slot = -1;
+    ProfScope(reinc_ctx *c, int kind, hipStream_t st) : ctx(c), s(st) {
+        if (!(c->prof_mask & (1u << kind)) || c->prof_kind.size() >= REINC_PROFILE_MAX_LAUNCHES) return;
+        const size_t need = 2 * (c->prof_kind.size() + 1);
+        while (c->prof_events.size() < need) {
+            hipEvent_t e;
+            if (hipEventCreate(&e) != hipSuccess) return;
+            c->prof_events.push_back(e);
+        }
+        slot = int(c->prof_kind.size());
+        c->prof_kind.push_back(kind);
+        (void)hipEventRecord(c->prof_events[2 * slot], s);
+    }
+    ~ProfScope() {
+        if (slot >= 0) (void)hipEventRecord(ctx->prof_events[2 * slot + 1], s);
+    }
+    ProfScope(const ProfScope &) = delete;
+    ProfScope &operator=(const ProfScope &) = delete;
+};
+}  // namespace reinc
 
 #define REINC_HIP(ctx, expr)                                                                        \
     do {                                                                                            \
@@ -156,9 +195,18 @@ void launch_dy(const void *x_prev, const void *x_cur, int bf16, const float *p_p
 bool agg_width_supported(int32_t d, int bf16);
 // out[v] = out_scale[v] * ( self_loop * in_scale[v] X[v] + sum_{e in [ptr[v], ptr[v+1])} in_scale[idx[e]] X[idx[e]] )
 // in_scale / out_scale may be null (factor 1); mask [n,d] (may be null) zeroes the output where mask <= 0.
-void launch_aggregate(const int64_t *ptr, const int32_t *idx, const int32_t *long_rows, int32_t n_long, const void *X,
-                      int bf16, int32_t d, int64_t n, int self_loop, const float *in_scale, const float *out_scale,
-                      const float *mask, float *out, hipStream_t s);
+// launch_aggregate takes every row of at most kLongRow entries (all rows when n_long == 0); launch_aggregate_long
+// takes the listed long rows with one block each.
+void launch_aggregate(const int64_t *ptr, const int32_t *idx, int32_t n_long, const void *X, int bf16, int32_t d,
+                      int64_t n, int self_loop, const float *in_scale, const float *out_scale, const float *mask,
+                      float *out, hipStream_t s);
+void launch_aggregate_long(const int64_t *ptr, const int32_t *idx, const int32_t *long_rows, int32_t n_long, const void *X,
+                           int bf16, int32_t d, int self_loop, const float *in_scale, const float *out_scale,
+                           const float *mask, float *out, hipStream_t s);
+// both, with the main kernel timed as REINC_K_AGG_FULL
+void aggregate_full(reinc_ctx *ctx, const int64_t *ptr, const int32_t *idx, const int32_t *long_rows, int32_t n_long,
+                    const void *X, int bf16, int32_t d, int self_loop, const float *in_scale, const float *out_scale,
+                    const float *mask, float *out, hipStream_t s);
 void launch_incremental(const int32_t *rows, int64_t n_rows, const int64_t *ent_ptr, const uint32_t *ent,
                         const void *x_prev, int bf16, const float *p_prev, const float *dY, int32_t d,
                         const float *S_prev, float *S_out, const float *q, float *agg_out, hipStream_t s);
@@ -183,4 +231,5 @@ uint64_t loss_partial_bytes();
 void launch_mse(const float *h, const float *y, int64_t total, float *partial, float *loss, hipStream_t s);
 void launch_mse_grad(const float *h, const float *y, int64_t total, float *dh, hipStream_t s);
 void launch_fill_f32(float *p, int64_t n, float v, hipStream_t s);
+void launch_sgd(float *params, const float *grads, int64_t n, float lr, hipStream_t s);
 }  // namespace reinc

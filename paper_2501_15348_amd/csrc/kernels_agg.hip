@@ -299,19 +299,39 @@ inline int lanes_per_row(int32_t d, int bf16)
 }
 
 template <bool BF16>
-void aggregate_dispatch(int lpr, const int64_t *ptr, const int32_t *idx, const int32_t *long_rows, int32_t n_long,
-                        const void *X, int64_t n, int self_loop, const float *in_scale, const float *out_scale,
-                        const float *mask, float *out, hipStream_t s)
+void aggregate_dispatch(int lpr, const int64_t *ptr, const int32_t *idx, int32_t n_long, const void *X, int64_t n,
+                        int self_loop, const float *in_scale, const float *out_scale, const float *mask, float *out,
+                        hipStream_t s)
 {
     const unsigned blocks = unsigned((n + kWavesPerBlock - 1) / kWavesPerBlock);
     const dim3 th(64 * kWavesPerBlock);
     const int skip = n_long > 0;
+#define REINC_AGG_CASE(L)                                                                                                \
+    case L:                                                                                                              \
+        aggregate_rows<L, BF16><<<blocks, th, 0, s>>>(ptr, idx, X, n, self_loop, in_scale, out_scale, mask, out, skip);  \
+        break;
+    switch (lpr) {
+        REINC_AGG_CASE(1)
+        REINC_AGG_CASE(2)
+        REINC_AGG_CASE(4)
+        REINC_AGG_CASE(8)
+        REINC_AGG_CASE(16)
+        REINC_AGG_CASE(32)
+        REINC_AGG_CASE(64)
+    }
+#undef REINC_AGG_CASE
+}
+
+template <bool BF16>
+void aggregate_long_dispatch(int lpr, const int64_t *ptr, const int32_t *idx, const int32_t *long_rows, int32_t n_long,
+                             const void *X, int self_loop, const float *in_scale, const float *out_scale,
+                             const float *mask, float *out, hipStream_t s)
+{
+    const dim3 th(64 * kWavesPerBlock);
 #define REINC_AGG_CASE(L)                                                                                          \
     case L:                                                                                                        \
-        aggregate_rows<L, BF16><<<blocks, th, 0, s>>>(ptr, idx, X, n, self_loop, in_scale, out_scale, mask, out, skip);  \
-        if (n_long > 0)                                                                                            \
-            aggregate_long_rows<L, BF16><<<unsigned(n_long), th, 0, s>>>(long_rows, ptr, idx, X, self_loop, in_scale, \
-                                                                         out_scale, mask, out);                    \
+        aggregate_long_rows<L, BF16><<<unsigned(n_long), th, 0, s>>>(long_rows, ptr, idx, X, self_loop, in_scale,  \
+                                                                     out_scale, mask, out);                        \
         break;
     switch (lpr) {
         REINC_AGG_CASE(1)
@@ -353,16 +373,39 @@ void incremental_dispatch(int lpr, const int32_t *rows, int64_t n_rows, const in
 
 bool agg_width_supported(int32_t d, int bf16) { return lanes_per_row(d, bf16) != 0; }
 
-void launch_aggregate(const int64_t *ptr, const int32_t *idx, const int32_t *long_rows, int32_t n_long, const void *X,
-                      int bf16, int32_t d, int64_t n, int self_loop, const float *in_scale, const float *out_scale,
-                      const float *mask, float *out, hipStream_t s)
+void launch_aggregate(const int64_t *ptr, const int32_t *idx, int32_t n_long, const void *X, int bf16, int32_t d,
+                      int64_t n, int self_loop, const float *in_scale, const float *out_scale, const float *mask,
+                      float *out, hipStream_t s)
 {
     if (n <= 0) return;
     const int lpr = lanes_per_row(d, bf16);
     if (bf16)
-        aggregate_dispatch<true>(lpr, ptr, idx, long_rows, n_long, X, n, self_loop, in_scale, out_scale, mask, out, s);
+        aggregate_dispatch<true>(lpr, ptr, idx, n_long, X, n, self_loop, in_scale, out_scale, mask, out, s);
     else
-        aggregate_dispatch<false>(lpr, ptr, idx, long_rows, n_long, X, n, self_loop, in_scale, out_scale, mask, out, s);
+        aggregate_dispatch<false>(lpr, ptr, idx, n_long, X, n, self_loop, in_scale, out_scale, mask, out, s);
+}
+
+void launch_aggregate_long(const int64_t *ptr, const int32_t *idx, const int32_t *long_rows, int32_t n_long, const void *X,
+                           int bf16, int32_t d, int self_loop, const float *in_scale, const float *out_scale,
+                           const float *mask, float *out, hipStream_t s)
+{
+    if (n_long <= 0) return;
+    const int lpr = lanes_per_row(d, bf16);
+    if (bf16)
+        aggregate_long_dispatch<true>(lpr, ptr, idx, long_rows, n_long, X, self_loop, in_scale, out_scale, mask, out, s);
+    else
+        aggregate_long_dispatch<false>(lpr, ptr, idx, long_rows, n_long, X, self_loop, in_scale, out_scale, mask, out, s);
+}
+
+void aggregate_full(reinc_ctx *ctx, const int64_t *ptr, const int32_t *idx, const int32_t *long_rows, int32_t n_long,
+                    const void *X, int bf16, int32_t d, int self_loop, const float *in_scale, const float *out_scale,
+                    const float *mask, float *out, hipStream_t s)
+{
+    {
+        ProfScope prof(ctx, REINC_K_AGG_FULL, s);
+        launch_aggregate(ptr, idx, n_long, X, bf16, d, ctx->cfg.num_nodes, self_loop, in_scale, out_scale, mask, out, s);
+    }
+    launch_aggregate_long(ptr, idx, long_rows, n_long, X, bf16, d, self_loop, in_scale, out_scale, mask, out, s);
 }
 
 void launch_incremental(const int32_t *rows, int64_t n_rows, const int64_t *ent_ptr, const uint32_t *ent,

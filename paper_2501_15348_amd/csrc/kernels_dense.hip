@@ -156,6 +156,205 @@ __global__ void __launch_bounds__(256) gemm_rows_kernel(GemmArgs g)
     }
 }
 
+// 16 consecutive k values of row `row` (a valid row) starting at k0 + 16*(lane/32), as four 16-byte loads.
+template <bool BF16>
+__device__ inline void load_a16_fast(const void *A, int64_t row, int lda, int k0, float (&a)[16])
+{
+    const int kbase = k0 + 16 * ((threadIdx.x & 63) >> 5);
+    if (BF16) {
+        const uint16_t *p = static_cast<const uint16_t *>(A) + row * lda + kbase;
+        const uint4 v0 = *reinterpret_cast<const uint4 *>(p);
+        const uint4 v1 = *reinterpret_cast<const uint4 *>(p + 8);
+        const uint32_t w[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            a[2 * i] = __uint_as_float(w[i] << 16);
+            a[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u);
+        }
+    } else {
+        const float *p = static_cast<const float *>(A) + row * lda + kbase;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float4 v = *reinterpret_cast<const float4 *>(p + 4 * i);
+            a[4 * i] = v.x;
+            a[4 * i + 1] = v.y;
+            a[4 * i + 2] = v.z;
+            a[4 * i + 3] = v.w;
+        }
+    }
+}
+
+// 16 k-steps against B fragments in LDS.  bp points at this lane's column of the first of its 16 B rows;
+// tile t of NT sits at column offset tile_stride * t.  Fragments are read four steps ahead of their use so
+// that the matrix cores never wait for an LDS round trip.
+template <int NT, class Prefetch>
+__device__ inline void mfma_chunk(const float (&a)[16], const float *bp, int ld, int tile_stride, acc16 (&acc)[NT],
+                                  Prefetch prefetch)
+{
+    // groups of G steps: all B fragments of a group are read from LDS first, then its matrix instructions run
+    // back to back (the scheduling barriers keep the compiler from sinking each read next to its use, which
+    // would expose one LDS round trip per step)
+    constexpr int G = 8;
+#pragma unroll
+    for (int q = 0; q < 16 / G; ++q) {
+        float b[G][NT];
+#pragma unroll
+        for (int s = 0; s < G; ++s)
+#pragma unroll
+            for (int t = 0; t < NT; ++t) b[s][t] = bp[(G * q + s) * ld + t * tile_stride];
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int s = 0; s < G; ++s)
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+                acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[G * q + s], b[s][t], acc[t], 0, 0, 0);
+        if (q == 0) prefetch();
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
+struct NoPrefetch {
+    __device__ void operator()() const {}
+};
+
+// Same product with the whole weight slab [K, 32*NT] resident in LDS: it is staged once per block, after which
+// every wave streams its own 32-row tiles without any barrier.  The k chunks of all of a wave's tiles form one
+// stream; a ring of three register buffers keeps the loads two chunks (8 KB per wave) ahead of the matrix
+// cores, across tile boundaries and epilogues.  Needs K % 32 == 0 and 16-byte aligned rows; the row scale is
+// applied to the finished sums.
+template <int NT, bool BF16>
+__global__ void __launch_bounds__(256, NT <= 2 ? 3 : 2) gemm_rows_resident_kernel(GemmArgs g)
+{
+    extern __shared__ float Bs[];
+    constexpr int BN = 32 * NT;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int i = lane & 31, kk = lane >> 5;
+    const int col0 = blockIdx.y * BN;
+    for (int k0 = 0; k0 < g.K; k0 += kBK)
+        stage_b(Bs + k0 * BN, BN, BN, g.W, g.ldw, g.wT != 0, k0, g.K, [&](int c) { return col0 + c < g.M ? col0 + c : -1; });
+    __syncthreads();
+    const int64_t ntiles = (g.n + 31) / 32;
+    const int64_t first = int64_t(blockIdx.x) * 4 + w, stride = int64_t(gridDim.x) * 4;
+    if (first >= ntiles) return;
+    const int kch = g.K / kBK;
+    const int64_t total = ((ntiles - first + stride - 1) / stride) * kch;
+    const float *bp0 = Bs + (16 * kk) * BN + i;
+
+    // load cursor
+    int64_t ltile = first, issued = 0;
+    int lk = 0;
+    int64_t lrow = min(ltile * 32 + i, g.n - 1);
+    auto issue = [&](float(&buf)[16]) {
+        if (issued < total) {
+            load_a16_fast<BF16>(g.A, lrow, g.lda, lk * kBK, buf);
+            ++issued;
+            if (++lk == kch) {
+                lk = 0;
+                ltile += stride;
+                lrow = min(ltile * 32 + i, g.n - 1);
+            }
+        }
+    };
+    // compute cursor
+    int64_t tile = first;
+    int kc = 0;
+    acc16 acc[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[t][r] = 0.0f;
+
+    auto epilogue = [&]() {  // rows rbase + 8*(r/4) + r%4 of the finished tile
+        const int64_t rbase = tile * 32 + 4 * kk;
+        const bool full = tile * 32 + 32 <= g.n;
+        float rs[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) rs[r] = 1.0f;
+        if (g.row_scale) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) rs[r] = g.row_scale[min(rbase + 8 * (r / 4) + (r % 4), g.n - 1)];
+        }
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            const int c = col0 + 32 * t + i;
+            if (c < g.M) {
+                const float bias = g.bias ? g.bias[c] : 0.0f;
+                float v[16];
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    v[r] = acc[t][r] * rs[r] + bias;
+                    if (g.relu) v[r] = fmaxf(v[r], 0.0f);
+                }
+                if (g.add) {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) v[r] += g.add[min(rbase + 8 * (r / 4) + (r % 4), g.n - 1) * g.M + c];
+                }
+                if (g.mask) {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        if (!(g.mask[min(rbase + 8 * (r / 4) + (r % 4), g.n - 1) * g.M + c] > 0.0f)) v[r] = 0.0f;
+                }
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int64_t rr = rbase + 8 * (r / 4) + (r % 4);
+                    if (full || rr < g.n) g.out[rr * g.M + c] = v[r];
+                }
+            }
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[t][r] = 0.0f;
+        }
+    };
+    auto step = [&](float(&cur)[16], float(&nxt)[16]) {
+        issue(nxt);
+        __builtin_amdgcn_sched_barrier(0);  // the new loads go out before this chunk's matrix instructions
+        mfma_chunk<NT>(cur, bp0 + kc * kBK * BN, BN, 32, acc, NoPrefetch());
+        if (++kc == kch) {
+            epilogue();
+            kc = 0;
+            tile += stride;
+        }
+    };
+    float b0[16], b1[16], b2[16];
+    issue(b0);
+    issue(b1);
+    for (int64_t p = 0; p < total; p += 3) {
+        step(b0, b2);
+        if (p + 1 < total) step(b1, b0);
+        if (p + 2 < total) step(b2, b1);
+    }
+}
+
+constexpr int kNumCU = 256;
+constexpr size_t kLdsBytes = 160 * 1024;
+
+// blocks of this kernel that fit on one compute unit at once (registers and LDS); the persistent grids are
+// sized with it so that every block is resident from the start
+int resident_blocks(const void *kernel, int threads, size_t lds)
+{
+    int blocks = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks, kernel, threads, lds) != hipSuccess) return 0;
+    return blocks;
+}
+
+template <int NT>
+bool gemm_rows_resident_launch(const GemmArgs &g, int bf16, hipStream_t s)
+{
+    if (g.K % kBK != 0 || g.lda % 8 != 0) return false;
+    const size_t lds = size_t(g.K) * 32 * NT * sizeof(float);
+    if (lds > kLdsBytes - 1024) return false;
+    auto k = bf16 ? gemm_rows_resident_kernel<NT, true> : gemm_rows_resident_kernel<NT, false>;
+    if (lds > 48 * 1024 &&
+        hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, int(lds)) != hipSuccess)
+        return false;
+    const int per_cu = resident_blocks(reinterpret_cast<const void *>(k), 256, lds);
+    if (per_cu <= 0) return false;
+    const int64_t ntiles = (g.n + 31) / 32;
+    const unsigned gy = unsigned((g.M + 32 * NT - 1) / (32 * NT));
+    dim3 grid(unsigned(std::min<int64_t>((ntiles + 3) / 4, std::max<int64_t>(1, int64_t(kNumCU) * per_cu / gy))), gy);
+    k<<<grid, 256, lds, s>>>(g);
+    return true;
+}
+
 template <int NT, int WM, int WN>
 void gemm_rows_launch(const GemmArgs &g, int bf16, hipStream_t s)
 {
@@ -281,6 +480,176 @@ __global__ void __launch_bounds__(256) rnn_fused_kernel(RnnArgs g)
     }
 }
 
+// Same step with both weight matrices (the block's hidden-unit columns of every gate) resident in LDS:
+// staged once per block, then 8 waves (WM row tiles x WN groups of 32 hidden units) stream row tiles without
+// barriers.  Rows [0, d_in) of the slab hold W_i, rows [d_in, d_in + H) hold W_h.  Needs d_in % 64 == 0 and
+// H % 64 == 0.
+template <bool LSTM, int WN>
+__global__ void __launch_bounds__(512) rnn_fused_resident_kernel(RnnArgs g)
+{
+    extern __shared__ float Bs[];
+    constexpr int KG = LSTM ? 4 : 3;
+    constexpr int WM = 8 / WN;
+    constexpr int BH = 32 * WN;
+    constexpr int NC = KG * BH;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int wm = w / WN, wn = w % WN;
+    const int i = lane & 31, kk = lane >> 5;
+    const int h0 = blockIdx.y * BH;
+    const int H = g.H, ldw = KG * H, dpad = g.d_in;
+    auto col_of = [&](int c) {
+        const int gate = c / BH, j = c - gate * BH;
+        return h0 + j < H ? gate * H + h0 + j : -1;
+    };
+    for (int k0 = 0; k0 < g.d_in; k0 += kBK) stage_b(Bs + k0 * NC, NC, NC, g.W_i, ldw, false, k0, g.d_in, col_of);
+    for (int k0 = 0; k0 < H; k0 += kBK) stage_b(Bs + (dpad + k0) * NC, NC, NC, g.W_h, ldw, false, k0, H, col_of);
+    __syncthreads();
+    const int j = h0 + wn * 32 + i;
+    float bi[KG], bh[KG];
+#pragma unroll
+    for (int t = 0; t < KG; ++t) {
+        bi[t] = (g.b_i && j < H) ? g.b_i[t * H + j] : 0.0f;
+        bh[t] = (g.b_h && j < H) ? g.b_h[t * H + j] : 0.0f;
+    }
+    const int64_t ntiles = (g.n + 31) / 32;
+    const float *bp0 = Bs + (16 * kk) * NC + wn * 32 + i;
+    float a0[16], a1[16];
+    bool first = true;
+    for (int64_t tile = int64_t(blockIdx.x) * WM + wm; tile < ntiles; tile += int64_t(gridDim.x) * WM) {
+        const int64_t row = min(tile * 32 + i, g.n - 1);
+        acc16 acc[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[t][r] = 0.0f;
+        if (first) {
+            load_a16_fast<false>(g.x, row, g.d_in, 0, a0);
+            first = false;
+        }
+        const int64_t next_tile = tile + int64_t(gridDim.x) * WM;
+        const int64_t next_row = min(next_tile * 32 + i, g.n - 1);
+        const bool has_h = g.h_prev != nullptr;
+        acc16(&acc3)[3] = reinterpret_cast<acc16(&)[3]>(acc[0]);
+        acc16(&acc2)[2] = reinterpret_cast<acc16(&)[2]>(acc[0]);
+        acc16(&acc1)[1] = reinterpret_cast<acc16(&)[1]>(acc[3]);
+        // x part: gates land in accumulators 0 .. KG-1
+        for (int k0 = 0; k0 < g.d_in; k0 += 2 * kBK) {
+            auto pf1 = [&] { load_a16_fast<false>(g.x, row, g.d_in, k0 + kBK, a1); };
+            auto pf0 = [&] {
+                if (k0 + 2 * kBK < g.d_in)
+                    load_a16_fast<false>(g.x, row, g.d_in, k0 + 2 * kBK, a0);
+                else if (has_h)
+                    load_a16_fast<false>(g.h_prev, row, H, 0, a0);
+                else if (next_tile < ntiles)
+                    load_a16_fast<false>(g.x, next_row, g.d_in, 0, a0);
+            };
+            if (LSTM) {
+                mfma_chunk<4>(a0, bp0 + k0 * NC, NC, BH, acc, pf1);
+                mfma_chunk<4>(a1, bp0 + (k0 + kBK) * NC, NC, BH, acc, pf0);
+            } else {
+                mfma_chunk<3>(a0, bp0 + k0 * NC, NC, BH, acc3, pf1);
+                mfma_chunk<3>(a1, bp0 + (k0 + kBK) * NC, NC, BH, acc3, pf0);
+            }
+        }
+        // h part: GRU keeps h W_hn apart (accumulator 3) because the reset gate multiplies it
+        if (has_h) {
+            for (int k0 = 0; k0 < H; k0 += 2 * kBK) {
+                auto pf1 = [&] { load_a16_fast<false>(g.h_prev, row, H, k0 + kBK, a1); };
+                auto pf0 = [&] {
+                    if (k0 + 2 * kBK < H)
+                        load_a16_fast<false>(g.h_prev, row, H, k0 + 2 * kBK, a0);
+                    else if (next_tile < ntiles)
+                        load_a16_fast<false>(g.x, next_row, g.d_in, 0, a0);
+                };
+                const float *bp = bp0 + (dpad + k0) * NC;
+                if (LSTM) {
+                    mfma_chunk<4>(a0, bp, NC, BH, acc, pf1);
+                    mfma_chunk<4>(a1, bp + kBK * NC, NC, BH, acc, pf0);
+                } else {
+                    mfma_chunk<2>(a0, bp, NC, BH, acc2, pf1);
+                    mfma_chunk<1>(a0, bp + 2 * BH, NC, BH, acc1, NoPrefetch());
+                    mfma_chunk<2>(a1, bp + kBK * NC, NC, BH, acc2, pf0);
+                    mfma_chunk<1>(a1, bp + kBK * NC + 2 * BH, NC, BH, acc1, NoPrefetch());
+                }
+            }
+        }
+        if (j >= H) continue;
+        const int64_t rbase = tile * 32 + 4 * kk;
+        const bool full = tile * 32 + 32 <= g.n;
+        float prev[16];
+        const float *pstate = LSTM ? g.c_prev : g.h_prev;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int64_t rr = rbase + 8 * (r / 4) + (r % 4);
+            prev[r] = (pstate && (full || rr < g.n)) ? pstate[rr * H + j] : 0.0f;
+        }
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int64_t rr = rbase + 8 * (r / 4) + (r % 4);
+            if (!(full || rr < g.n)) continue;
+            const int64_t o = rr * H + j;
+            if (LSTM) {
+                const float gi = sigmoidf_(acc[0][r] + bi[0] + bh[0]);
+                const float gf = sigmoidf_(acc[1][r] + bi[1] + bh[1]);
+                const float gg = tanhf(acc[2][r] + bi[2] + bh[2]);
+                const float go = sigmoidf_(acc[3][r] + bi[3] + bh[3]);
+                const float cn = gf * prev[r] + gi * gg;
+                g.c_out[o] = cn;
+                g.h_out[o] = go * tanhf(cn);
+                if (g.saved) {
+                    float *sv = g.saved + rr * 4 * H + j;
+                    sv[0] = gi;
+                    sv[H] = gf;
+                    sv[2 * H] = gg;
+                    sv[3 * H] = go;
+                }
+            } else {
+                const float gr = sigmoidf_(acc[0][r] + bi[0] + bh[0]);
+                const float gz = sigmoidf_(acc[1][r] + bi[1] + bh[1]);
+                const float ghn = acc[3][r] + bh[2];
+                const float gn = tanhf(acc[2][r] + bi[2] + gr * ghn);
+                g.h_out[o] = (1.0f - gz) * gn + gz * prev[r];
+                if (g.saved) {
+                    float *sv = g.saved + rr * 4 * H + j;
+                    sv[0] = gr;
+                    sv[H] = gz;
+                    sv[2 * H] = gn;
+                    sv[3 * H] = ghn;
+                }
+            }
+        }
+    }
+}
+
+template <bool LSTM, int WN>
+bool rnn_fused_resident_launch(const RnnArgs &g, hipStream_t s)
+{
+    constexpr int KG = LSTM ? 4 : 3;
+    constexpr int WM = 8 / WN;
+    if (g.d_in % (2 * kBK) != 0 || g.H % (2 * kBK) != 0) return false;
+    const size_t lds = size_t(g.d_in + g.H) * KG * 32 * WN * sizeof(float);
+    if (lds > kLdsBytes - 1024) return false;
+    auto k = rnn_fused_resident_kernel<LSTM, WN>;
+    if (lds > 48 * 1024 &&
+        hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, int(lds)) != hipSuccess)
+        return false;
+    const int per_cu = resident_blocks(reinterpret_cast<const void *>(k), 512, lds);
+    if (per_cu <= 0) return false;
+    const int64_t ntiles = (g.n + 31) / 32;
+    const unsigned gy = unsigned((g.H + 32 * WN - 1) / (32 * WN));
+    dim3 grid(unsigned(std::min<int64_t>((ntiles + WM - 1) / WM, std::max<int64_t>(1, int64_t(kNumCU) * per_cu / gy))), gy);
+    k<<<grid, 512, lds, s>>>(g);
+    return true;
+}
+
+template <bool LSTM>
+bool rnn_fused_resident_dispatch(const RnnArgs &g, hipStream_t s)
+{
+    if (g.H > 64 && rnn_fused_resident_launch<LSTM, 4>(g, s)) return true;
+    if (g.H > 32 && rnn_fused_resident_launch<LSTM, 2>(g, s)) return true;
+    return rnn_fused_resident_launch<LSTM, 1>(g, s);
+}
+
 // ---- weight / bias gradient: C[K,M] = sum_rows (rs .* A)^T G ---------------------------------------------
 // grid (slab_i, slab_j, chunk); a block's 4 waves split its row chunk, each keeps a 64x64 output slab
 // (2x2 accumulators), and the four partial slabs are summed through LDS.  Row K of the partial holds the
@@ -297,6 +666,7 @@ struct ReduceArgs {
     float *partial;  // [chunks, K+1, M]
 };
 
+template <bool HAS_RS>
 __global__ void __launch_bounds__(256) gemm_reduce_kernel(ReduceArgs g)
 {
     __shared__ float red[3][64 * 65];
@@ -316,26 +686,70 @@ __global__ void __launch_bounds__(256) gemm_reduce_kernel(ReduceArgs g)
     float bsum[2] = {0.0f, 0.0f};
     const bool fa0 = f0 + i < g.K, fa1 = f0 + 32 + i < g.K;
     const bool cb0 = c0 + i < g.M, cb1 = c0 + 32 + i < g.M;
-    // wave w takes row pairs w, w+4, ... of the chunk
-    for (int64_t r = r_begin + 2 * w + kk; r < r_end + kk; r += 8) {
-        // (the loop bound keeps both half-waves in step: the kk = 1 half may see r == r_end and loads zeros)
-        const bool live = r < r_end;
-        float a0 = 0.0f, a1 = 0.0f, b0 = 0.0f, b1 = 0.0f;
-        if (live) {
-            const float sc = g.row_scale ? g.row_scale[r] : 1.0f;
-            const float *ap = g.A + r * g.lda + f0 + i;
-            const float *gp = g.G + r * g.ldg + c0 + i;
-            if (fa0) a0 = ap[0] * sc;
-            if (fa1) a1 = ap[32] * sc;
-            if (cb0) b0 = gp[0];
-            if (cb1) b1 = gp[32];
+    // wave w takes row pairs w, w+4, ... of the chunk, kRU pairs per trip.  Full trips over full 64x64 slabs run
+    // without a single branch: every load of the trip is issued before any arithmetic touches a loaded value.
+    constexpr int kRU = 8;
+    int64_t base = r_begin;
+    if (f0 + 64 <= g.K && c0 + 64 <= g.M) {
+        const float *ap = g.A + (base + 2 * w + kk) * g.lda + f0 + i;
+        const float *gp = g.G + (base + 2 * w + kk) * g.ldg + c0 + i;
+        const float *sp = HAS_RS ? g.row_scale + base + 2 * w + kk : nullptr;
+        for (; base + 8 * kRU <= r_end; base += 8 * kRU) {
+            float a0[kRU], a1[kRU], b0[kRU], b1[kRU], sc[kRU];
+#pragma unroll
+            for (int u = 0; u < kRU; ++u) {
+                a0[u] = ap[int64_t(8 * u) * g.lda];
+                a1[u] = ap[int64_t(8 * u) * g.lda + 32];
+                b0[u] = gp[int64_t(8 * u) * g.ldg];
+                b1[u] = gp[int64_t(8 * u) * g.ldg + 32];
+                sc[u] = HAS_RS ? sp[8 * u] : 1.0f;
+            }
+            ap += int64_t(8 * kRU) * g.lda;
+            gp += int64_t(8 * kRU) * g.ldg;
+            if (HAS_RS) sp += 8 * kRU;
+            __builtin_amdgcn_sched_barrier(0);  // keep every load of the trip ahead of the arithmetic
+#pragma unroll
+            for (int u = 0; u < kRU; ++u) {
+                if (HAS_RS) {
+                    a0[u] *= sc[u];
+                    a1[u] *= sc[u];
+                }
+                acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0[u], b0[u], acc[0][0], 0, 0, 0);
+                acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0[u], b1[u], acc[0][1], 0, 0, 0);
+                acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[u], b0[u], acc[1][0], 0, 0, 0);
+                acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[u], b1[u], acc[1][1], 0, 0, 0);
+                bsum[0] += b0[u];
+                bsum[1] += b1[u];
+            }
         }
-        acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
-        acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
-        acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
-        acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
-        bsum[0] += b0;
-        bsum[1] += b1;
+    }
+    // ragged slabs and the last rows of the chunk: guarded loads
+    for (int64_t r0 = base + 2 * w + kk; r0 < r_end + kk; r0 += 8 * kRU) {
+        // (the bound keeps both half-waves in step: a half that runs past r_end loads zeros)
+        float a0[kRU], a1[kRU], b0[kRU], b1[kRU];
+#pragma unroll
+        for (int u = 0; u < kRU; ++u) {
+            const int64_t r = r0 + 8 * u;
+            a0[u] = a1[u] = b0[u] = b1[u] = 0.0f;
+            if (r < r_end) {
+                const float sc = HAS_RS ? g.row_scale[r] : 1.0f;
+                const float *ap = g.A + r * g.lda + f0 + i;
+                const float *gp = g.G + r * g.ldg + c0 + i;
+                if (fa0) a0[u] = ap[0] * sc;
+                if (fa1) a1[u] = ap[32] * sc;
+                if (cb0) b0[u] = gp[0];
+                if (cb1) b1[u] = gp[32];
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kRU; ++u) {
+            acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0[u], b0[u], acc[0][0], 0, 0, 0);
+            acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0[u], b1[u], acc[0][1], 0, 0, 0);
+            acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[u], b0[u], acc[1][0], 0, 0, 0);
+            acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[u], b1[u], acc[1][1], 0, 0, 0);
+            bsum[0] += b0[u];
+            bsum[1] += b1[u];
+        }
     }
     // combine the four waves: waves 1..3 park their slabs in LDS, wave 0 adds them in order
 #pragma unroll
@@ -372,13 +786,27 @@ __global__ void __launch_bounds__(256) gemm_reduce_kernel(ReduceArgs g)
 }
 
 // dst_w[K*M] += sum_c partial[c][0..K*M);  dst_b[M] += sum_c partial[c][K*M ..)
-__global__ void reduce_partials_kernel(const float *partial, int chunks, int K, int M, float *dst_w, float *dst_b)
+// A block owns 64 consecutive outputs; its 4 waves split the chunks, then add their sums in wave order.
+__global__ void __launch_bounds__(256)
+reduce_partials_kernel(const float *partial, int chunks, int K, int M, float *dst_w, float *dst_b)
 {
-    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    __shared__ float red[4][64];
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int total = (K + 1) * M;
-    if (idx >= total) return;
-    float s = 0.0f;
-    for (int c = 0; c < chunks; ++c) s += partial[int64_t(c) * total + idx];
+    const int idx = blockIdx.x * 64 + lane;
+    float s0 = 0.0f, s1 = 0.0f;
+    if (idx < total) {
+        int c = w;
+        for (; c + 4 < chunks; c += 8) {
+            s0 += partial[int64_t(c) * total + idx];
+            s1 += partial[int64_t(c + 4) * total + idx];
+        }
+        if (c < chunks) s0 += partial[int64_t(c) * total + idx];
+    }
+    red[w][lane] = s0 + s1;
+    __syncthreads();
+    if (w != 0 || idx >= total) return;
+    const float s = ((red[0][lane] + red[1][lane]) + red[2][lane]) + red[3][lane];
     if (idx < K * M)
         dst_w[idx] += s;
     else if (dst_b)
@@ -476,6 +904,12 @@ __global__ void mse_grad_kernel(const float *h, const float *y, int64_t total, f
     if (i < total) dh[i] = 2.0f * (h[i] - y[i]) / float(total);
 }
 
+__global__ void sgd_kernel(float *p, const float *g, int64_t n, float lr)
+{
+    const int64_t i = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
+    if (i < n) p[i] -= lr * g[i];
+}
+
 __global__ void fill_f32_kernel(float *p, int64_t n, float v)
 {
     const int64_t i = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
@@ -490,6 +924,11 @@ int launch_gemm_rows(const void *A, int a_bf16, int64_t n, int32_t K, int32_t M,
 {
     if (n <= 0) return 0;
     GemmArgs g{A, n, K, M, K, row_scale, W, ldw, w_transposed, bias, relu, mask, add, out};
+    // preferred: weight slab resident in LDS, as wide as fits
+    if (M > 64 && gemm_rows_resident_launch<4>(g, a_bf16, s)) return 0;
+    if (M > 32 && gemm_rows_resident_launch<2>(g, a_bf16, s)) return 0;
+    if (gemm_rows_resident_launch<1>(g, a_bf16, s)) return 0;
+    // very deep products: stage the weights 32 k values at a time
     if (M <= 32)
         gemm_rows_launch<1, 4, 1>(g, a_bf16, s);
     else if (M <= 64)
@@ -507,6 +946,7 @@ void launch_rnn_fused(int lstm, const float *x, int64_t n, int32_t d_in, int32_t
 {
     if (n <= 0) return;
     RnnArgs g{x, n, d_in, H, h_prev, c_prev, W_i, W_h, b_i, b_h, h_out, c_out, saved};
+    if (lstm ? rnn_fused_resident_dispatch<true>(g, s) : rnn_fused_resident_dispatch<false>(g, s)) return;
 #define REINC_RNN_LAUNCH(WM, WN)                                                                    \
     do {                                                                                            \
         dim3 grid(unsigned((n + 32 * WM - 1) / (32 * WM)), unsigned((H + 32 * WN - 1) / (32 * WN))); \
@@ -526,8 +966,9 @@ void launch_rnn_fused(int lstm, const float *x, int64_t n, int32_t d_in, int32_t
 
 int reduce_chunks(int64_t n, int32_t K, int32_t M)
 {
+    // about three blocks per compute unit, at least 256 rows each
     const int64_t slabs = int64_t((K + 63) / 64) * ((M + 63) / 64);
-    int64_t chunks = std::max<int64_t>(1, 1024 / slabs);
+    int64_t chunks = std::max<int64_t>(1, (768 + slabs - 1) / slabs);
     chunks = std::min<int64_t>(chunks, (n + 255) / 256);
     return int(std::max<int64_t>(chunks, 1));
 }
@@ -543,12 +984,15 @@ void launch_gemm_reduce(const float *A, int32_t lda, const float *row_scale, con
     if (n <= 0) return;
     const int chunks = reduce_chunks(n, K, M);
     int64_t rpc = (n + chunks - 1) / chunks;
-    rpc = (rpc + 7) & ~int64_t(7);  // whole row-pair groups per wave
+    rpc = (rpc + 63) & ~int64_t(63);  // whole 64-row trips; no row pair straddles two chunks
     ReduceArgs g{A, lda, row_scale, G, ldg, n, K, M, rpc, partial};
     dim3 grid(unsigned((K + 63) / 64), unsigned((M + 63) / 64), unsigned(chunks));
-    gemm_reduce_kernel<<<grid, 256, 0, s>>>(g);
+    if (row_scale)
+        gemm_reduce_kernel<true><<<grid, 256, 0, s>>>(g);
+    else
+        gemm_reduce_kernel<false><<<grid, 256, 0, s>>>(g);
     const int total = (K + 1) * M;
-    reduce_partials_kernel<<<(total + 255) / 256, 256, 0, s>>>(partial, chunks, K, M, dW, db);
+    reduce_partials_kernel<<<(total + 63) / 64, 256, 0, s>>>(partial, chunks, K, M, dW, db);
 }
 
 void launch_rnn_backward_elem(int lstm, int64_t n, int32_t H, const float *dh, const float *dc, const float *saved,
@@ -576,6 +1020,11 @@ void launch_mse(const float *h, const float *y, int64_t total, float *partial, f
 void launch_mse_grad(const float *h, const float *y, int64_t total, float *dh, hipStream_t s)
 {
     if (total > 0) mse_grad_kernel<<<unsigned((total + 255) / 256), 256, 0, s>>>(h, y, total, dh);
+}
+
+void launch_sgd(float *params, const float *grads, int64_t n, float lr, hipStream_t s)
+{
+    if (n > 0) sgd_kernel<<<unsigned((n + 255) / 256), 256, 0, s>>>(params, grads, n, lr);
 }
 
 void launch_fill_f32(float *p, int64_t n, float v, hipStream_t s)

@@ -11,6 +11,28 @@ namespace {
 
 hipStream_t as_stream(void *s) { return static_cast<hipStream_t>(s); }
 
+// launch wrappers that time the kernel class when profiling is on; `ctx` and the stream are in scope at every use
+#define PROF_GEMM(...)                                        \
+    do {                                                      \
+        ProfScope prof_(ctx, REINC_K_GEMM_ROWS, prof_stream); \
+        launch_gemm_rows(__VA_ARGS__);                        \
+    } while (0)
+#define PROF_RNN(...)                                   \
+    do {                                                \
+        ProfScope prof_(ctx, REINC_K_RNN, prof_stream); \
+        launch_rnn_fused(__VA_ARGS__);                  \
+    } while (0)
+#define PROF_REDUCE(...)                                   \
+    do {                                                   \
+        ProfScope prof_(ctx, REINC_K_REDUCE, prof_stream); \
+        launch_gemm_reduce(__VA_ARGS__);                   \
+    } while (0)
+#define PROF_ELEM(...)                                   \
+    do {                                                 \
+        ProfScope prof_(ctx, REINC_K_ELEM, prof_stream); \
+        launch_rnn_backward_elem(__VA_ARGS__);           \
+    } while (0)
+
 struct Params {
     const float *W[REINC_MAX_GCN_LAYERS + 1] = {};
     const float *b[REINC_MAX_GCN_LAYERS + 1] = {};
@@ -111,6 +133,7 @@ int ensure_layer1(reinc_ctx *ctx, int32_t t, hipStream_t s)
     const int32_t d = c.dims[0];
     const int bf16 = c.feat_dtype == REINC_BF16;
     const uint64_t bytes = uint64_t(c.num_nodes) * d * 4;
+    ctx->note_derived();
     float *slot = static_cast<float *>(ctx->alloc(bytes));
     if (!slot) return ctx->fail(REINC_E_NOMEM, "arena exhausted: no room for the cached aggregate of snapshot %d", t);
     ++ctx->stats.global_misses;
@@ -128,13 +151,16 @@ int ensure_layer1(reinc_ctx *ctx, int32_t t, hipStream_t s)
         const Delta &dl = ctx->deltas[t];
         const Snapshot &pv = ctx->snaps[t - 1];
         REINC_HIP(ctx, hipMemcpyAsync(slot, ctx->gcache[t - 1], bytes, hipMemcpyDeviceToDevice, s));
-        launch_incremental(dl.rows, dl.info.n_rows, dl.ent_ptr, dl.ent, pv.x, bf16, pv.p, dl.dY, d, slot, slot, nullptr,
-                           nullptr, s);
+        {
+            ProfScope prof(ctx, REINC_K_AGG_INC, s);
+            launch_incremental(dl.rows, dl.info.n_rows, dl.ent_ptr, dl.ent, pv.x, bf16, pv.p, dl.dY, d, slot, slot, nullptr,
+                               nullptr, s);
+        }
         ++ctx->stats.steps_incremental;
         ctx->stats.delta_entries_processed += dl.info.n_entries;
     } else {
-        launch_aggregate(sn.row_ptr, sn.col, sn.long_rows, sn.n_long_rows, sn.x, bf16, d, c.num_nodes, c.self_loop, sn.p,
-                         nullptr, nullptr, slot, s);
+        aggregate_full(ctx, sn.row_ptr, sn.col, sn.long_rows, sn.n_long_rows, sn.x, bf16, d, c.self_loop, sn.p, nullptr,
+                       nullptr, slot, s);
         ++ctx->stats.steps_full;
     }
     REINC_HIP(ctx, hipGetLastError());
@@ -161,7 +187,8 @@ int reinc_gcn_transform(reinc_ctx *ctx, const void *A, int a_dtype, int64_t n, i
     if (n < 0 || d_in <= 0 || d_out <= 0) return ctx->fail(REINC_E_ARG, "bad shape");
     if (a_dtype != REINC_F32 && a_dtype != REINC_BF16) return ctx->fail(REINC_E_ARG, "bad a_dtype");
     if (A == out) return ctx->fail(REINC_E_ARG, "output may not alias the input");
-    launch_gemm_rows(A, a_dtype == REINC_BF16, n, d_in, d_out, row_scale, W, 0, d_out, b, relu, nullptr, nullptr, out,
+    hipStream_t prof_stream = as_stream(stream);
+    PROF_GEMM(A, a_dtype == REINC_BF16, n, d_in, d_out, row_scale, W, 0, d_out, b, relu, nullptr, nullptr, out,
                      as_stream(stream));
     REINC_HIP(ctx, hipGetLastError());
     return REINC_OK;
@@ -177,7 +204,8 @@ int reinc_rnn_step(reinc_ctx *ctx, int rnn_kind, const float *x, int64_t n, int3
     if (rnn_kind == REINC_RNN_LSTM && !c_out) return ctx->fail(REINC_E_ARG, "an LSTM step needs c_out");
     if (n < 0 || d_in <= 0 || H <= 0) return ctx->fail(REINC_E_ARG, "bad shape");
     if (h_out == h_prev || (c_out && c_out == c_prev)) return ctx->fail(REINC_E_ARG, "state outputs may not alias the previous state");
-    launch_rnn_fused(rnn_kind == REINC_RNN_LSTM, x, n, d_in, H, h_prev, c_prev, W_i, W_h, b_i, b_h, h_out, c_out, saved,
+    hipStream_t prof_stream = as_stream(stream);
+    PROF_RNN(rnn_kind == REINC_RNN_LSTM, x, n, d_in, H, h_prev, c_prev, W_i, W_h, b_i, b_h, h_out, c_out, saved,
                      as_stream(stream));
     REINC_HIP(ctx, hipGetLastError());
     return REINC_OK;
@@ -195,6 +223,7 @@ int reinc_forward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *par
         if (!agg_width_supported(c.dims[l], 0))
             return ctx->fail(REINC_E_UNSUPPORTED, "layer width %d: row bytes must be a power of two in [16, 1024]", c.dims[l]);
     hipStream_t s = as_stream(stream);
+    hipStream_t prof_stream = s;
     REINC_HIP(ctx, hipSetDevice(c.device));
     ctx->local_valid = false;
     REINC_TRY(ensure_local(ctx, L, s));
@@ -208,16 +237,16 @@ int reinc_forward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *par
         REINC_TRY(ensure_layer1(ctx, t, s));
         const Snapshot &sn = ctx->snaps[t];
         LocalStep &st = ctx->local[i];
-        launch_gemm_rows(ctx->gcache[t], 0, n, c.dims[0], c.dims[1], sn.q, p.W[1], 0, c.dims[1], p.b[1], 1, nullptr, nullptr,
+        PROF_GEMM(ctx->gcache[t], 0, n, c.dims[0], c.dims[1], sn.q, p.W[1], 0, c.dims[1], p.b[1], 1, nullptr, nullptr,
                          st.H[1], s);
         for (int l = 2; l <= Lg; ++l) {
-            launch_aggregate(sn.row_ptr, sn.col, sn.long_rows, sn.n_long_rows, st.H[l - 1], 0, c.dims[l - 1], n, c.self_loop,
-                             sn.p, nullptr, nullptr, st.S[l], s);
-            launch_gemm_rows(st.S[l], 0, n, c.dims[l - 1], c.dims[l], sn.q, p.W[l], 0, c.dims[l], p.b[l], 1, nullptr, nullptr,
+            aggregate_full(ctx, sn.row_ptr, sn.col, sn.long_rows, sn.n_long_rows, st.H[l - 1], 0, c.dims[l - 1], c.self_loop,
+                           sn.p, nullptr, nullptr, st.S[l], s);
+            PROF_GEMM(st.S[l], 0, n, c.dims[l - 1], c.dims[l], sn.q, p.W[l], 0, c.dims[l], p.b[l], 1, nullptr, nullptr,
                              st.H[l], s);
         }
         const LocalStep *pv = i ? &ctx->local[i - 1] : nullptr;
-        launch_rnn_fused(lstm, st.H[Lg], n, c.dims[Lg], H, pv ? pv->h : nullptr, pv ? pv->c : nullptr, p.W_i, p.W_h, p.b_i,
+        PROF_RNN(lstm, st.H[Lg], n, c.dims[Lg], H, pv ? pv->h : nullptr, pv ? pv->c : nullptr, p.W_i, p.W_h, p.b_i,
                          p.b_h, st.h, st.c, st.saved, s);
     }
     const LocalStep &last = ctx->local[L - 1];
@@ -239,6 +268,7 @@ int reinc_backward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *pa
         return ctx->fail(REINC_E_STATE, "backward needs the forward pass of the same window [%d, %d) first", t0, t0 + L);
     const reinc_config &c = ctx->cfg;
     hipStream_t s = as_stream(stream);
+    hipStream_t prof_stream = s;
     REINC_HIP(ctx, hipSetDevice(c.device));
     const Params p = split_params(c, params);
     Params gp = split_params(c, grads);
@@ -272,18 +302,18 @@ int reinc_backward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *pa
         const Snapshot &sn = ctx->snaps[t];
         const LocalStep &st = ctx->local[i];
         const LocalStep *pv = i ? &ctx->local[i - 1] : nullptr;
-        launch_rnn_backward_elem(lstm, n, H, dh, dc_in, st.saved, pv ? pv->h : nullptr, pv ? pv->c : nullptr, st.c, dgi, dgh,
+        PROF_ELEM(lstm, n, H, dh, dc_in, st.saved, pv ? pv->h : nullptr, pv ? pv->c : nullptr, st.c, dgi, dgh,
                                  dh2, dc2, s);
         const float *x = st.H[Lg];
         const int dl = c.dims[Lg];
-        launch_gemm_reduce(x, dl, nullptr, dgi, KH, n, dl, KH, partial, const_cast<float *>(gp.W_i),
+        PROF_REDUCE(x, dl, nullptr, dgi, KH, n, dl, KH, partial, const_cast<float *>(gp.W_i),
                            const_cast<float *>(gp.b_i), s);
-        launch_gemm_reduce(pv ? pv->h : ctx->zero_state, H, nullptr, dgh, KH, n, H, KH, partial, const_cast<float *>(gp.W_h),
+        PROF_REDUCE(pv ? pv->h : ctx->zero_state, H, nullptr, dgh, KH, n, H, KH, partial, const_cast<float *>(gp.W_h),
                            const_cast<float *>(gp.b_h), s);
         // gradient w.r.t. the last GCN layer's pre-activation
-        launch_gemm_rows(dgi, 0, n, KH, dl, nullptr, p.W_i, 1, KH, nullptr, 0, nullptr, x, dz, s);
+        PROF_GEMM(dgi, 0, n, KH, dl, nullptr, p.W_i, 1, KH, nullptr, 0, nullptr, x, dz, s);
         if (i > 0) {  // gradient w.r.t. h_{t-1}
-            launch_gemm_rows(dgh, 0, n, KH, H, nullptr, p.W_h, 1, KH, nullptr, 0, lstm ? nullptr : dh2, nullptr, dh, s);
+            PROF_GEMM(dgh, 0, n, KH, H, nullptr, p.W_h, 1, KH, nullptr, 0, lstm ? nullptr : dh2, nullptr, dh, s);
             if (lstm) {
                 std::swap(dc, dc2);  // dc now holds the gradient w.r.t. c_{t-1}
                 dc_in = dc;
@@ -292,13 +322,13 @@ int reinc_backward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *pa
         }
         for (int l = Lg; l >= 1; --l) {
             const float *S = l == 1 ? ctx->gcache[t] : st.S[l];
-            launch_gemm_reduce(S, c.dims[l - 1], sn.q, dz, c.dims[l], n, c.dims[l - 1], c.dims[l], partial,
+            PROF_REDUCE(S, c.dims[l - 1], sn.q, dz, c.dims[l], n, c.dims[l - 1], c.dims[l], partial,
                                const_cast<float *>(gp.W[l]), const_cast<float *>(gp.b[l]), s);
             if (l > 1) {
-                launch_gemm_rows(dz, 0, n, c.dims[l], c.dims[l - 1], nullptr, p.W[l], 1, c.dims[l], nullptr, 0, nullptr,
+                PROF_GEMM(dz, 0, n, c.dims[l], c.dims[l - 1], nullptr, p.W[l], 1, c.dims[l], nullptr, 0, nullptr,
                                  nullptr, dagg, s);
-                launch_aggregate(sn.col_ptr, sn.row, sn.long_cols, sn.n_long_cols, dagg, 0, c.dims[l - 1], n, c.self_loop,
-                                 sn.q, sn.p, st.H[l - 1], dz2, s);
+                aggregate_full(ctx, sn.col_ptr, sn.row, sn.long_cols, sn.n_long_cols, dagg, 0, c.dims[l - 1], c.self_loop, sn.q,
+                               sn.p, st.H[l - 1], dz2, s);
                 std::swap(dz, dz2);
             }
         }

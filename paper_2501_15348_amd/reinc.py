@@ -20,6 +20,7 @@ AGG = {"sum": 0, "mean": 1, "sym": 2}
 RNN = {"gru": 0, "lstm": 1}
 DTYPE = {"fp32": 0, "bf16": 1}
 MAX_GCN_LAYERS = 3
+KERNEL_KINDS = ("agg_full", "agg_inc", "gemm_rows", "rnn", "reduce", "elem", "diff")
 
 
 class Config(ctypes.Structure):
@@ -89,6 +90,10 @@ def load_library() -> ctypes.CDLL:
         "reinc_rnn_step": [p, ci, p, i64, i32, i32, p, p, p, p, p, p, p, p, p, p],
         "reinc_forward_window": [p, i32, i32, p, p, p, p, p],
         "reinc_backward_window": [p, i32, i32, p, p, p, p],
+        "reinc_sgd_step": [p, p, p, i64, ctypes.c_float, p],
+        "reinc_reset_derived": [p],
+        "reinc_profile_begin": [p, ctypes.c_uint32],
+        "reinc_profile_end": [p, ctypes.POINTER(i64), ctypes.POINTER(ctypes.c_double)],
         "reinc_cache_clear": [p],
         "reinc_cache_peek": [p, i32, ctypes.POINTER(p)],
         "reinc_get_stats": [p, ctypes.POINTER(Stats)],
@@ -313,6 +318,25 @@ class Context:
     def backward_window(self, t0: int, length: int, params, target, grads):
         self._ck(self.lib.reinc_backward_window(self.handle, t0, length, _dev_ptr(params), _dev_ptr(target),
                                                 _dev_ptr(grads), _stream()))
+
+    def sgd_step(self, params, grads, lr: float):
+        self._ck(self.lib.reinc_sgd_step(self.handle, _dev_ptr(params), _dev_ptr(grads), params.numel(), lr, _stream()))
+
+    def reset_derived(self):
+        self._ck(self.lib.reinc_reset_derived(self.handle))
+
+    def profile_begin(self, kinds=("agg_full",)):
+        mask = 0
+        for k in kinds:
+            mask |= 1 << KERNEL_KINDS.index(k)
+        self._ck(self.lib.reinc_profile_begin(self.handle, mask))
+
+    def profile_end(self) -> dict:
+        n = len(KERNEL_KINDS)
+        launches = (ctypes.c_int64 * n)()
+        total = (ctypes.c_double * n)()
+        self._ck(self.lib.reinc_profile_end(self.handle, launches, total))
+        return {k: (launches[i], total[i]) for i, k in enumerate(KERNEL_KINDS)}
 
     def cache_clear(self):
         self._ck(self.lib.reinc_cache_clear(self.handle))

@@ -64,3 +64,26 @@ def test_degenerate():
     assert icol.size == 0 and _pairs(drp, dcol) == [(0, 1), (1, 2)]
     (irp, icol), (drp, dcol) = oracle.edge_deltas(e, a, n)
     assert dcol.size == 0 and _pairs(irp, icol) == [(0, 1), (1, 2)]
+
+
+def test_change_counts_against_set_based_delta_graphs(tiny_seq):
+    """The vectorised counts equal the sizes of the literal delta graphs of Section 3.2."""
+    from oracle import incremental as inc
+
+    n = tiny_seq.workload.num_nodes
+    graphs = oracle.graphs_of(tiny_seq.edges, n)
+    for mode, sl in (("sum", True), ("sym", True), ("mean", False)):
+        for t in (1, 4):
+            xp = oracle.features_at(tiny_seq.x0, tiny_seq.feat_rows, tiny_seq.feat_vals, t - 1)
+            xc = oracle.features_at(tiny_seq.x0, tiny_seq.feat_rows, tiny_seq.feat_vals, t)
+            c = oracle.change_counts(graphs[t - 1], graphs[t], xp, xc, mode, sl)
+            assert c["n_ins"] == len(tiny_seq.truth_inserted[t]) and c["n_del"] == len(tiny_seq.truth_deleted[t])
+            e_prev, e_cur = inc.edge_set(*tiny_seq.edges[t - 1]), inc.edge_set(*tiny_seq.edges[t])
+            changed = set(np.nonzero(np.any(xp != xc, axis=1))[0].tolist())
+            if mode == "sym":
+                changed |= set(np.nonzero(np.diff(graphs[t - 1].row_ptr) != np.diff(graphs[t].row_ptr))[0].tolist())
+            assert c["n_changed"] == len(changed)
+            fchg = {e for e in inc.with_self_loops(e_cur, n, sl) if e[0] in changed}
+            assert c["n_fchg_entries"] == len(fchg)
+            assert c["n_entries"] == c["n_ins"] + c["n_del"] + len(fchg)
+            assert c["n_rows"] == len(inc.touched_rows(e_prev, e_cur, changed, n, sl))
