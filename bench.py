@@ -24,8 +24,8 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E
 
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
-# command (profiles/aggregate_rows_c2_pmc.txt), scaled by the copy-kernel calibration; None = not measured.
-MEASURED_TRAFFIC = {}
+# command (profiles/bench_c2_hbm_traffic_pmc.txt), scaled by the copy-kernel calibration; None = not measured.
+MEASURED_TRAFFIC = {"c2": 209.3e6}
 
 
 def parse_args():
@@ -37,6 +37,8 @@ def parse_args():
     ap.add_argument("--nodes", type=int, default=0, help="scale the workload down to this many nodes (debug)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the per-kernel measurements after the timed region")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one 256 MiB device copy (a kernel of known traffic, for scaling rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE)")
     return ap.parse_args()
 
 
@@ -93,6 +95,12 @@ def main():
             ctx.backward_window(t0, L, params, target, grads)
             ctx.sgd_step(params, grads, 1e-2)
 
+    if args.calibrate_copy:
+        src = torch.empty(64 << 20, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)  # reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()

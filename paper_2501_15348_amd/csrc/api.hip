@@ -209,18 +209,19 @@ int reinc_load_features_delta(reinc_ctx *ctx, int32_t t, const int32_t *rows, in
     sn.x = ctx->alloc(uint64_t(ctx->N()) * row_bytes);
     if (!sn.x) return ctx->fail(REINC_E_NOMEM, "arena exhausted while storing features of snapshot %d", t);
     REINC_HIP(ctx, hipMemcpy(sn.x, pv.x, uint64_t(ctx->N()) * row_bytes, hipMemcpyDeviceToDevice));
-    // consecutive ids travel as one copy
-    const char *v = static_cast<const char *>(vals);
-    for (int64_t i = 0; i < nrows;) {
-        int64_t j = i + 1;
-        while (j < nrows && rows[j] == rows[j - 1] + 1) ++j;
-        REINC_HIP(ctx, hipMemcpy(static_cast<char *>(sn.x) + uint64_t(rows[i]) * row_bytes, v + uint64_t(i) * row_bytes,
-                                 uint64_t(j - i) * row_bytes, hipMemcpyHostToDevice));
-        i = j;
-    }
     REINC_TRY(upload(ctx, &sn.feat_rows, rows, nrows, "feature row ids"));
+    // the changed rows travel as one block into scratch and are scattered by a kernel
+    ctx->scratch_reset();
+    void *staged = ctx->scratch(uint64_t(std::max<int64_t>(nrows, 1)) * row_bytes);
+    if (!staged) return ctx->fail(REINC_E_NOMEM, "arena exhausted while staging the feature rows of snapshot %d", t);
+    if (nrows > 0) {
+        REINC_HIP(ctx, hipMemcpy(staged, vals, uint64_t(nrows) * row_bytes, hipMemcpyHostToDevice));
+        launch_scatter_rows(staged, sn.feat_rows, nrows, int32_t(row_bytes), sn.x, nullptr);
+        REINC_HIP(ctx, hipGetLastError());
+    }
     sn.n_feat_rows = nrows;
     REINC_HIP(ctx, hipDeviceSynchronize());
+    ctx->scratch_reset();
     sn.feats_loaded = true;
     sn.feats_from_delta = true;
     if (ctx->has_derived) ctx->load_after_derived = true;

@@ -188,6 +188,7 @@ void launch_delta_count(const int64_t *rp_a, const int32_t *col_a, const int64_t
 void launch_delta_fill(const int64_t *rp_a, const int32_t *col_a, const int64_t *rp_b, const int32_t *col_b,
                        const int32_t *cindex, int self_loop, int64_t n, const int64_t *ins_ptr, int32_t *ins_col,
                        const int64_t *del_ptr, int32_t *del_col, const int64_t *ent_ptr, uint32_t *ent, hipStream_t s);
+void launch_scatter_rows(const void *vals, const int32_t *rows, int64_t nrows, int32_t row_bytes, void *x, hipStream_t s);
 void launch_dy(const void *x_prev, const void *x_cur, int bf16, const float *p_prev, const float *p_cur,
                const int32_t *changed, int64_t n_changed, int32_t d, float *dY, hipStream_t s);
 

@@ -134,6 +134,23 @@ __device__ inline bool row_find(const int32_t *col, int64_t beg, int64_t end, in
     return lo < end && col[lo] == key;
 }
 
+// Membership of this lane's two values in the other list of a row that fits one group (both lists <= kGroup
+// long): the group's lanes hand their values round with shuffles, so no dependent global reads are needed.
+// A lane without a value passes -1, which never matches a node id.
+__device__ inline void group_membership(int32_t av, int32_t bv, int lane, bool &a_in_b, bool &b_in_a)
+{
+    const int gbase = lane & ~(kGroup - 1);
+    a_in_b = false;
+    b_in_a = false;
+#pragma unroll
+    for (int j = 0; j < kGroup; ++j) {
+        const int32_t bj = __shfl(bv, gbase + j);
+        const int32_t aj = __shfl(av, gbase + j);
+        a_in_b |= (bj == av);
+        b_in_a |= (aj == bv);
+    }
+}
+
 __device__ inline int wave_max(int v)
 {
     for (int off = 32; off > 0; off >>= 1) v = max(v, __shfl_xor(v, off));
@@ -160,15 +177,20 @@ delta_count(const int64_t *rp_a, const int32_t *col_a, const int64_t *rp_b, cons
     int la = int(a1 - a0), lb = int(b1 - b0);
     int iters = (wave_max(max(la, lb)) + kGroup - 1) / kGroup;
     int n_ins = 0, n_del = 0, n_f = 0;
+    const bool short_row = la <= kGroup && lb <= kGroup;
     for (int it = 0; it < iters; ++it) {
         int k = it * kGroup + li;
-        bool is_del = false, is_ins = false, is_f = false;
-        if (k < la) is_del = !row_find(col_b, b0, b1, col_a[a0 + k]);
-        if (k < lb) {
-            int32_t u = col_b[b0 + k];
-            is_ins = !row_find(col_a, a0, a1, u);
-            is_f = cflags[u] != 0;
+        const int32_t av = k < la ? col_a[a0 + k] : -1;
+        const int32_t bv = k < lb ? col_b[b0 + k] : -1;
+        bool a_in_b, b_in_a;
+        group_membership(av, bv, lane, a_in_b, b_in_a);
+        if (!short_row) {
+            a_in_b = k < la && row_find(col_b, b0, b1, av);
+            b_in_a = k < lb && row_find(col_a, a0, a1, bv);
         }
+        const bool is_del = k < la && !a_in_b;
+        const bool is_ins = k < lb && !b_in_a;
+        const bool is_f = k < lb && cflags[bv] != 0;
         n_del += __popcll(__ballot(is_del) & gmask);
         n_ins += __popcll(__ballot(is_ins) & gmask);
         n_f += __popcll(__ballot(is_f) & gmask);
@@ -208,20 +230,21 @@ delta_fill(const int64_t *rp_a, const int32_t *col_a, const int64_t *rp_b, const
     }
     int la = int(a1 - a0), lb = int(b1 - b0);
     int iters = (wave_max(max(la, lb)) + kGroup - 1) / kGroup;
+    const bool short_row = la <= kGroup && lb <= kGroup;
     for (int it = 0; it < iters; ++it) {
         int k = it * kGroup + li;
-        bool is_del = false, is_ins = false, is_f = false;
-        int32_t ua = 0, ub = 0, ci = -1;
-        if (k < la) {
-            ua = col_a[a0 + k];
-            is_del = !row_find(col_b, b0, b1, ua);
+        const int32_t ua = k < la ? col_a[a0 + k] : -1;
+        const int32_t ub = k < lb ? col_b[b0 + k] : -1;
+        bool a_in_b, b_in_a;
+        group_membership(ua, ub, lane, a_in_b, b_in_a);
+        if (!short_row) {
+            a_in_b = k < la && row_find(col_b, b0, b1, ua);
+            b_in_a = k < lb && row_find(col_a, a0, a1, ub);
         }
-        if (k < lb) {
-            ub = col_b[b0 + k];
-            is_ins = !row_find(col_a, a0, a1, ub);
-            ci = cindex[ub];
-            is_f = ci >= 0;
-        }
+        const bool is_del = k < la && !a_in_b;
+        const bool is_ins = k < lb && !b_in_a;
+        const int32_t ci = k < lb ? cindex[ub] : -1;
+        const bool is_f = ci >= 0;
         uint64_t m_del = __ballot(is_del) & gmask, m_ins = __ballot(is_ins) & gmask, m_f = __ballot(is_f) & gmask;
         if (is_del) {
             int r = __popcll(m_del & below);
@@ -248,6 +271,15 @@ delta_fill(const int64_t *rp_a, const int32_t *col_a, const int64_t *rp_b, const
         int ci = cindex[v];
         if (ci >= 0) ent[e_f] = (2u << kKindShift) | uint32_t(ci);
     }
+}
+
+// X[rows[r]] = vals[r], rows of `chunks` 16-byte pieces
+__global__ void scatter_rows(const uint4 *vals, const int32_t *rows, int64_t nrows, int32_t chunks, uint4 *x)
+{
+    int64_t i = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
+    if (i >= nrows * chunks) return;
+    int64_t r = i / chunks;
+    x[int64_t(rows[r]) * chunks + (i - r * chunks)] = vals[i];
 }
 
 __device__ inline float bf16_to_f32(uint16_t b) { return __uint_as_float(uint32_t(b) << 16); }
@@ -344,6 +376,15 @@ void launch_delta_fill(const int64_t *rp_a, const int32_t *col_a, const int64_t 
     if (n > 0)
         delta_fill<<<blocks_for(n, kRowsPerBlock), kDiffThreads, 0, s>>>(rp_a, col_a, rp_b, col_b, cindex, self_loop, n,
                                                                          ins_ptr, ins_col, del_ptr, del_col, ent_ptr, ent);
+}
+
+void launch_scatter_rows(const void *vals, const int32_t *rows, int64_t nrows, int32_t row_bytes, void *x, hipStream_t s)
+{
+    const int32_t chunks = row_bytes / 16;
+    const int64_t total = nrows * chunks;
+    if (total > 0)
+        scatter_rows<<<blocks_for(total, 256), 256, 0, s>>>(static_cast<const uint4 *>(vals), rows, nrows, chunks,
+                                                            static_cast<uint4 *>(x));
 }
 
 void launch_dy(const void *x_prev, const void *x_cur, int bf16, const float *p_prev, const float *p_cur,
