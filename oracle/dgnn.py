@@ -26,6 +26,7 @@ __all__ = [
     "degrees",
     "aggregate",
     "aggregate_adjoint",
+    "aggregate_rows",
     "dense_layer",
     "gru_cell",
     "lstm_cell",
@@ -176,6 +177,30 @@ def aggregate_adjoint(row_ptr, col, g, mode: str, self_loop: bool) -> np.ndarray
     if rc:
         raise ValueError("column index out of range")
     return dx
+
+
+def aggregate_rows(row_ptr, col, x, rows, mode: str, self_loop: bool) -> Tuple[np.ndarray, np.ndarray]:
+    """Eq. 1 for a sample of target rows only, one row at a time from the definition (for graphs too large
+    to aggregate in full on the host).  x may be fp32; sums are fp64.  Returns (S[rows], Agg[rows])."""
+    deg = np.diff(row_ptr).astype(np.float64) + (1.0 if self_loop else 0.0)
+    with np.errstate(divide="ignore"):
+        if mode == "sym":
+            p = np.where(deg > 0, 1.0 / np.sqrt(deg), 0.0)
+            q = p
+        elif mode == "mean":
+            p = np.ones_like(deg)
+            q = np.where(deg > 0, 1.0 / deg, 0.0)
+        else:
+            p = q = np.ones_like(deg)
+    d = x.shape[1]
+    s = np.zeros((len(rows), d), dtype=np.float64)
+    for k, v in enumerate(rows):
+        u = col[row_ptr[v]:row_ptr[v + 1]]
+        acc = (p[u, None] * x[u].astype(np.float64)).sum(axis=0) if u.size else np.zeros(d)
+        if self_loop:
+            acc = acc + p[v] * x[v].astype(np.float64)
+        s[k] = acc
+    return s, s * q[np.asarray(rows)][:, None]
 
 
 # ----------------------------------------------------------------------------- dense side

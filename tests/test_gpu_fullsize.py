@@ -1,0 +1,137 @@
+"""GPU parity at the full sizes of the benchmark workloads, in the launch configuration bench.py times:
+integer outputs in full, float outputs in full where the host can recompute them in seconds and on
+sampled rows otherwise (paper Section 3.2 for the aggregation, Sections 2.2 / 3.3 for the window)."""
+import numpy as np
+import pytest
+
+import oracle
+from helpers import RTOL_BF16, RTOL_FP32, assert_close, oracle_feats
+from paper_2501_15348_amd import synth
+
+pytestmark = [pytest.mark.gpu, pytest.mark.timeout(900)]
+
+
+def _setup(name, T, arena_gb, **kw):
+    from paper_2501_15348_amd import reinc
+
+    base = synth.WORKLOADS[name]
+    wl = base.scaled(base.num_nodes, T, **kw)
+    print(f"[{wl.name}] generating {wl.num_nodes} nodes, {wl.num_edges} edges, {T} snapshots", flush=True)
+    seq = synth.make_sequence(wl, shuffle_edges=False)
+    ctx = reinc.Context.for_workload(wl, arena_bytes=int(arena_gb * (1 << 30)))
+    print(f"[{wl.name}] loading", flush=True)
+    ctx.load_sequence(seq)
+    ctx.build_deltas(-1)
+    return wl, seq, ctx
+
+
+def _check_deltas(ctx, seq, graphs, t):
+    n = seq.workload.num_nodes
+    (irp, icol), (drp, dcol) = oracle.edge_deltas(graphs[t - 1].keys, graphs[t].keys, n)
+    for kind, (erp, ecol) in enumerate(((irp, icol), (drp, dcol))):
+        rp, col = ctx.get_delta_csr(t, kind)
+        assert np.array_equal(rp, erp) and np.array_equal(col, ecol), f"delta CSR kind {kind} step {t}"
+    # the generator's own lists are the ground truth of the diff
+    ts, td = seq.truth_pairs(t, "ins")
+    assert irp[-1] == ts.size
+    counts = oracle.change_counts(graphs[t - 1], graphs[t], oracle_feats(seq, t - 1), oracle_feats(seq, t),
+                                  seq.workload.agg, seq.workload.self_loop)
+    info = ctx.get_delta_info(t)
+    for k in ("n_ins", "n_del", "n_changed", "n_fchg_entries", "n_entries", "n_rows"):
+        assert info[k] == counts[k], (k, info[k], counts[k])
+
+
+def test_bench_workload_c2_full():
+    """100k nodes, 1M edges, sym normalisation: deltas, both aggregation paths, and a 3-snapshot window."""
+    import torch
+
+    wl, seq, ctx = _setup("c2", 4, 2)
+    graphs = oracle.graphs_of(seq.edges, wl.num_nodes)
+    for t in (1, 3):
+        _check_deltas(ctx, seq, graphs, t)
+    s = ctx.aggregate_full(0)
+    for t in range(1, 4):
+        s = ctx.aggregate_incremental(t, s)
+        s_ref, agg_ref = oracle.aggregate(graphs[t].row_ptr, graphs[t].col, oracle_feats(seq, t), wl.agg, wl.self_loop)
+        assert_close(s.cpu().numpy(), s_ref, RTOL_FP32, f"incremental S t={t}")
+        assert_close(ctx.aggregate_full(t, apply_q=True).cpu().numpy(), agg_ref, RTOL_FP32, f"full Agg t={t}")
+    flat = synth.make_params(wl, bias_scale=0.1)
+    target = synth.make_target(wl)
+    params, tgt = torch.from_numpy(flat).cuda(), torch.from_numpy(target).cuda()
+    loss = torch.zeros(1, device="cuda")
+    h = torch.empty((wl.num_nodes, wl.hidden), device="cuda")
+    grads = torch.empty_like(params)
+    ctx.forward_window(1, 3, params, tgt, loss, h)
+    ctx.backward_window(1, 3, params, tgt, grads)
+    feats = [oracle_feats(seq, t) for t in range(1, 4)]
+    p = synth.split_params(wl, flat.astype(np.float64))
+    ref_loss, ref_h, saved = oracle.forward_window(graphs[1:4], feats, p, 2, wl.agg, wl.self_loop, wl.rnn, target, keep=True)
+    assert_close(h.cpu().numpy(), ref_h, RTOL_FP32, "h_last")
+    assert abs(loss.item() - ref_loss) <= RTOL_FP32 * abs(ref_loss)
+    ref_g = oracle.backward_window(graphs[1:4], saved, ref_h, p, 2, wl.agg, wl.self_loop, wl.rnn, target)
+    got = synth.split_params(wl, grads.cpu().numpy())
+    for name, _ in synth.param_shapes(wl):
+        assert_close(got[name], ref_g[name], 5 * RTOL_FP32, f"grad {name}")
+    ctx.close()
+
+
+def test_churn_sweep_workload_c5_full():
+    """500k nodes, 6M edges, sum aggregation, 10 % churn: incremental chain against the from-scratch reference."""
+    wl, seq, ctx = _setup("c5_10", 3, 4)
+    graphs = oracle.graphs_of(seq.edges, wl.num_nodes)
+    _check_deltas(ctx, seq, graphs, 2)
+    s = ctx.aggregate_full(0)
+    for t in (1, 2):
+        ctx.aggregate_incremental(t, s, s)
+        s_ref, _ = oracle.aggregate(graphs[t].row_ptr, graphs[t].col, oracle_feats(seq, t), wl.agg, wl.self_loop)
+        assert_close(s.cpu().numpy(), s_ref, RTOL_FP32, f"S t={t}")
+    ctx.close()
+
+
+def test_window_workload_c3_full():
+    """1M nodes, 16M edges, d = 128, mean aggregation: deltas in full, aggregates on sampled rows (hubs included)."""
+    wl, seq, ctx = _setup("c3", 2, 12)
+    n = wl.num_nodes
+    graphs = oracle.graphs_of(seq.edges, n)
+    _check_deltas(ctx, seq, graphs, 1)
+    rng = np.random.default_rng(0)
+    s0 = ctx.aggregate_full(0)
+    s1 = ctx.aggregate_incremental(1, s0)
+    full1 = ctx.aggregate_full(1, apply_q=True)
+    _, _, rows_changed, _ = ctx.get_merged_delta(1)
+    deg = np.diff(graphs[1].row_ptr)
+    sample = np.unique(np.concatenate([rng.integers(0, n, 300), rng.choice(rows_changed, 300), np.argsort(deg)[-20:], [0, n - 1]]))
+    x1 = oracle_feats(seq, 1)
+    s_ref, agg_ref = oracle.aggregate_rows(graphs[1].row_ptr, graphs[1].col, x1, sample, wl.agg, wl.self_loop)
+    assert_close(s1.cpu().numpy()[sample], s_ref, RTOL_FP32, "incremental S (sampled rows)")
+    assert_close(full1.cpu().numpy()[sample], agg_ref, RTOL_FP32, "full Agg (sampled rows)")
+    untouched = np.setdiff1d(sample, rows_changed)
+    assert np.array_equal(s1.cpu().numpy()[untouched], s0.cpu().numpy()[untouched])
+    ctx.close()
+
+
+def test_bf16_workload_c4_full():
+    """2.5M nodes, 50M edges, bf16 features of width 256, 10 % churn: deltas in full, aggregates on sampled rows."""
+    wl, seq, ctx = _setup("c4", 2, 40)
+    n = wl.num_nodes
+    graphs = oracle.graphs_of(seq.edges, n)
+    _check_deltas(ctx, seq, graphs, 1)
+    rng = np.random.default_rng(1)
+    s0 = ctx.aggregate_full(0)
+    s1 = ctx.aggregate_incremental(1, s0, s0)
+    _, _, rows_changed, _ = ctx.get_merged_delta(1)
+    deg = np.diff(graphs[1].row_ptr)
+    sample = np.unique(np.concatenate([rng.integers(0, n, 200), rng.choice(rows_changed, 200), np.argsort(deg)[-10:]]))
+    x1 = seq.x0.copy()
+    x1[seq.feat_rows[1]] = seq.feat_vals[1]
+    s_ref, _ = oracle.aggregate_rows(graphs[1].row_ptr, graphs[1].col, x1, sample, wl.agg, wl.self_loop)
+    assert_close(s1[torch_index(sample)].cpu().numpy(), s_ref, RTOL_BF16, "incremental S (sampled rows)")
+    full = ctx.aggregate_full(1)
+    assert_close(full[torch_index(sample)].cpu().numpy(), s_ref, RTOL_BF16, "full S (sampled rows)")
+    ctx.close()
+
+
+def torch_index(rows):
+    import torch
+
+    return torch.from_numpy(np.asarray(rows, dtype=np.int64)).cuda()

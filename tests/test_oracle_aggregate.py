@@ -136,3 +136,16 @@ def test_adjoint_is_transpose():
         x = rng.standard_normal((n, d))  # <A x, g> == <x, A^T g>
         _, ax = oracle.aggregate(rp, col, x, mode, sl)
         assert np.isclose((ax * g).sum(), (x * oracle.aggregate_adjoint(rp, col, g, mode, sl)).sum())
+
+
+def test_row_sampled_form_equals_full():
+    rng = np.random.default_rng(11)
+    n, d = 60, 4
+    keys = oracle.canonicalise(rng.integers(0, n, 300), rng.integers(0, n, 300), n)
+    rp, col = oracle.csr_from_keys(keys, n)
+    x = rng.standard_normal((n, d))
+    rows = np.array([0, 7, 33, 59])
+    for mode, sl in itertools.product(["sum", "mean", "sym"], [False, True]):
+        s_full, agg_full = oracle.aggregate(rp, col, x, mode, sl)
+        s, agg = oracle.aggregate_rows(rp, col, x, rows, mode, sl)
+        assert np.allclose(s, s_full[rows], atol=1e-13) and np.allclose(agg, agg_full[rows], atol=1e-13)
