@@ -127,10 +127,11 @@ int reinc_load_edges(reinc_ctx *ctx, int32_t t, const int32_t *src, const int32_
     keys.erase(std::unique(keys.begin(), keys.end()), keys.end());
     const int64_t e = int64_t(keys.size());
     std::vector<int64_t> row_ptr(n + 1, 0), col_ptr(n + 1, 0);
-    std::vector<int32_t> col(e), row(e);
+    std::vector<int32_t> col(e), row(e), rowid(e);
     for (int64_t i = 0; i < e; ++i) {
         const int64_t v = int64_t(keys[i] >> 32), u = int64_t(keys[i] & 0xFFFFFFFFu);
         col[i] = int32_t(u);
+        rowid[i] = int32_t(v);
         ++row_ptr[v + 1];
         ++col_ptr[u + 1];
     }
@@ -153,6 +154,7 @@ int reinc_load_edges(reinc_ctx *ctx, int32_t t, const int32_t *src, const int32_
     sn.nnz = e;
     REINC_TRY(upload(ctx, &sn.row_ptr, row_ptr.data(), n + 1, "row_ptr"));
     REINC_TRY(upload(ctx, &sn.col, col.data(), e, "col"));
+    REINC_TRY(upload(ctx, &sn.rowid, rowid.data(), e, "rowid"));
     REINC_TRY(upload(ctx, &sn.col_ptr, col_ptr.data(), n + 1, "col_ptr"));
     REINC_TRY(upload(ctx, &sn.row, row.data(), e, "row"));
     sn.n_long_rows = int32_t(long_rows.size());
@@ -249,16 +251,16 @@ static int build_one(reinc_ctx *ctx, int32_t t, hipStream_t s)
         ctx->scratch_reset();
         return ctx->fail(REINC_E_NOMEM, "arena exhausted in build_deltas(%d): %s", t, what);
     };
-    int32_t *cflags = static_cast<int32_t *>(ctx->scratch(uint64_t(n) * 4));
-    int32_t *cindex = static_cast<int32_t *>(ctx->scratch(uint64_t(n) * 4));
-    int32_t *cnt_ins = static_cast<int32_t *>(ctx->scratch(uint64_t(n) * 4));
-    int32_t *cnt_del = static_cast<int32_t *>(ctx->scratch(uint64_t(n) * 4));
-    int32_t *cnt_all = static_cast<int32_t *>(ctx->scratch(uint64_t(n) * 4));
-    int32_t *row_flag = static_cast<int32_t *>(ctx->scratch(uint64_t(n) * 4));
-    int64_t *coffs = static_cast<int64_t *>(ctx->scratch(uint64_t(n + 1) * 8));
-    int64_t *roffs = static_cast<int64_t *>(ctx->scratch(uint64_t(n + 1) * 8));
-    void *scan_tmp = ctx->scratch(scan_tmp_bytes(n));
-    if (!cflags || !cindex || !cnt_ins || !cnt_del || !cnt_all || !row_flag || !coffs || !roffs || !scan_tmp)
+    const int64_t na = a.nnz, nb = b.nnz;
+    auto i32s = [&](int64_t c) { return static_cast<int32_t *>(ctx->scratch(uint64_t(std::max<int64_t>(c, 1)) * 4)); };
+    auto i64s = [&](int64_t c) { return static_cast<int64_t *>(ctx->scratch(uint64_t(std::max<int64_t>(c, 1)) * 8)); };
+    int32_t *cflags = i32s(n), *cindex = i32s(n), *row_flag = i32s(n);
+    int32_t *absent_a = i32s(na), *absent_b = i32s(nb), *hit_b = i32s(nb);
+    int64_t *coffs = i64s(n + 1), *roffs = i64s(n + 1);
+    int64_t *pos_del = i64s(na + 1), *pos_ins = i64s(nb + 1), *pos_hit = i64s(nb + 1);
+    void *scan_tmp = ctx->scratch(scan_tmp_bytes(std::max(std::max(na, nb), n)));
+    if (!cflags || !cindex || !row_flag || !absent_a || !absent_b || !hit_b || !coffs || !roffs || !pos_del || !pos_ins ||
+        !pos_hit || !scan_tmp)
         return nomem("scratch");
 
     // change set C_t
@@ -269,43 +271,44 @@ static int build_one(reinc_ctx *ctx, int32_t t, hipStream_t s)
         launch_feature_flags_compare(a.x, b.x, n, d * ctx->elem_bytes(), cflags, s);
     if (ctx->cfg.agg_kind == REINC_AGG_SYM) launch_degree_flags(a.row_ptr, b.row_ptr, n, cflags, s);
     launch_scan(cflags, coffs, n, scan_tmp, s);
-    int64_t n_changed = 0;
-    REINC_HIP(ctx, hipMemcpyAsync(&n_changed, coffs + n, 8, hipMemcpyDeviceToHost, s));
-    REINC_HIP(ctx, hipStreamSynchronize(s));
-    dl.changed = static_cast<int32_t *>(ctx->alloc(uint64_t(std::max<int64_t>(n_changed, 1)) * 4));
-    dl.dY = static_cast<float *>(ctx->alloc(uint64_t(std::max<int64_t>(n_changed, 1)) * d * 4));
+    // per-edge flags (one thread per edge) and their prefix sums: the prefix sums are the output positions
+    {
+        ProfScope prof(ctx, REINC_K_DIFF, s);
+        launch_edge_flags(a.rowid, a.col, na, b.row_ptr, b.col, nullptr, absent_a, nullptr, s);
+        launch_edge_flags(b.rowid, b.col, nb, a.row_ptr, a.col, cflags, absent_b, hit_b, s);
+    }
+    launch_scan(absent_a, pos_del, na, scan_tmp, s);
+    launch_scan(absent_b, pos_ins, nb, scan_tmp, s);
+    launch_scan(hit_b, pos_hit, nb, scan_tmp, s);
     dl.ins_ptr = static_cast<int64_t *>(ctx->alloc(uint64_t(n + 1) * 8));
     dl.del_ptr = static_cast<int64_t *>(ctx->alloc(uint64_t(n + 1) * 8));
     dl.ent_ptr = static_cast<int64_t *>(ctx->alloc(uint64_t(n + 1) * 8));
-    if (!dl.changed || !dl.dY || !dl.ins_ptr || !dl.del_ptr || !dl.ent_ptr) return nomem("change set / row pointers");
-    launch_compact(cflags, coffs, n, dl.changed, cindex, s);
-    launch_dy(a.x, b.x, bf16, a.p, b.p, dl.changed, n_changed, d, dl.dY, s);
-
-    // per-row counts, row pointers
-    {
-        ProfScope prof(ctx, REINC_K_DIFF, s);
-        launch_delta_count(a.row_ptr, a.col, b.row_ptr, b.col, cflags, ctx->cfg.self_loop, n, cnt_ins, cnt_del, cnt_all,
-                           row_flag, s);
-    }
-    launch_scan(cnt_ins, dl.ins_ptr, n, scan_tmp, s);
-    launch_scan(cnt_del, dl.del_ptr, n, scan_tmp, s);
-    launch_scan(cnt_all, dl.ent_ptr, n, scan_tmp, s);
+    if (!dl.ins_ptr || !dl.del_ptr || !dl.ent_ptr) return nomem("row pointers");
+    launch_delta_row_ptrs(a.row_ptr, b.row_ptr, pos_del, pos_ins, pos_hit, coffs, ctx->cfg.self_loop, n, dl.ins_ptr,
+                          dl.del_ptr, dl.ent_ptr, row_flag, s);
     launch_scan(row_flag, roffs, n, scan_tmp, s);
-    int64_t totals[4] = {0, 0, 0, 0};
+    int64_t totals[5] = {0, 0, 0, 0, 0};
     REINC_HIP(ctx, hipMemcpyAsync(&totals[0], dl.ins_ptr + n, 8, hipMemcpyDeviceToHost, s));
     REINC_HIP(ctx, hipMemcpyAsync(&totals[1], dl.del_ptr + n, 8, hipMemcpyDeviceToHost, s));
     REINC_HIP(ctx, hipMemcpyAsync(&totals[2], dl.ent_ptr + n, 8, hipMemcpyDeviceToHost, s));
     REINC_HIP(ctx, hipMemcpyAsync(&totals[3], roffs + n, 8, hipMemcpyDeviceToHost, s));
+    REINC_HIP(ctx, hipMemcpyAsync(&totals[4], coffs + n, 8, hipMemcpyDeviceToHost, s));
     REINC_HIP(ctx, hipStreamSynchronize(s));
+    const int64_t n_changed = totals[4];
+    dl.changed = static_cast<int32_t *>(ctx->alloc(uint64_t(std::max<int64_t>(n_changed, 1)) * 4));
+    dl.dY = static_cast<float *>(ctx->alloc(uint64_t(std::max<int64_t>(n_changed, 1)) * d * 4));
     dl.ins_col = static_cast<int32_t *>(ctx->alloc(uint64_t(std::max<int64_t>(totals[0], 1)) * 4));
     dl.del_col = static_cast<int32_t *>(ctx->alloc(uint64_t(std::max<int64_t>(totals[1], 1)) * 4));
     dl.ent = static_cast<uint32_t *>(ctx->alloc(uint64_t(std::max<int64_t>(totals[2], 1)) * 4));
     dl.rows = static_cast<int32_t *>(ctx->alloc(uint64_t(std::max<int64_t>(totals[3], 1)) * 4));
-    if (!dl.ins_col || !dl.del_col || !dl.ent || !dl.rows) return nomem("delta entries");
+    if (!dl.changed || !dl.dY || !dl.ins_col || !dl.del_col || !dl.ent || !dl.rows) return nomem("delta entries");
+    launch_compact(cflags, coffs, n, dl.changed, cindex, s);
+    launch_dy(a.x, b.x, bf16, a.p, b.p, dl.changed, n_changed, d, dl.dY, s);
     {
         ProfScope prof(ctx, REINC_K_DIFF, s);
-        launch_delta_fill(a.row_ptr, a.col, b.row_ptr, b.col, cindex, ctx->cfg.self_loop, n, dl.ins_ptr, dl.ins_col,
-                          dl.del_ptr, dl.del_col, dl.ent_ptr, dl.ent, s);
+        launch_delta_fill(a.rowid, a.col, na, b.rowid, b.col, nb, b.row_ptr, absent_a, absent_b, hit_b, pos_del, pos_ins,
+                          pos_hit, cindex, ctx->cfg.self_loop, n, dl.ins_ptr, dl.ins_col, dl.del_ptr, dl.del_col, dl.ent_ptr,
+                          dl.ent, s);
     }
     launch_compact(row_flag, roffs, n, dl.rows, nullptr, s);
     REINC_HIP(ctx, hipGetLastError());

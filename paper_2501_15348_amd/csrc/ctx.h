@@ -27,6 +27,7 @@ struct Snapshot {
     // CSR by destination and CSC by source
     int64_t *row_ptr = nullptr;
     int32_t *col = nullptr;
+    int32_t *rowid = nullptr;  // target of every CSR entry (the expanded row pointer)
     int64_t *col_ptr = nullptr;
     int32_t *row = nullptr;
     // degree scalings: p (source side), q (target side), fp32 [N]
@@ -182,12 +183,17 @@ void launch_feature_flags_list(const int32_t *rows, int64_t nrows, int64_t n, in
 void launch_degree_flags(const int64_t *rp_prev, const int64_t *rp_cur, int64_t n, int32_t *flags, hipStream_t s);
 void launch_compact(const int32_t *flags, const int64_t *offsets, int64_t n, int32_t *list, int32_t *index_of,
                     hipStream_t s);
-void launch_delta_count(const int64_t *rp_a, const int32_t *col_a, const int64_t *rp_b, const int32_t *col_b,
-                        const int32_t *cflags, int self_loop, int64_t n, int32_t *cnt_ins, int32_t *cnt_del,
-                        int32_t *cnt_all, int32_t *row_flag, hipStream_t s);
-void launch_delta_fill(const int64_t *rp_a, const int32_t *col_a, const int64_t *rp_b, const int32_t *col_b,
-                       const int32_t *cindex, int self_loop, int64_t n, const int64_t *ins_ptr, int32_t *ins_col,
-                       const int64_t *del_ptr, int32_t *del_col, const int64_t *ent_ptr, uint32_t *ent, hipStream_t s);
+void launch_edge_flags(const int32_t *rowid, const int32_t *col, int64_t nnz, const int64_t *other_ptr,
+                       const int32_t *other_col, const int32_t *cflags, int32_t *absent, int32_t *hit, hipStream_t s);
+void launch_delta_row_ptrs(const int64_t *rp_a, const int64_t *rp_b, const int64_t *pos_del, const int64_t *pos_ins,
+                           const int64_t *pos_hit, const int64_t *pos_self, int self_loop, int64_t n, int64_t *ins_ptr,
+                           int64_t *del_ptr, int64_t *ent_ptr, int32_t *row_flag, hipStream_t s);
+void launch_delta_fill(const int32_t *rowid_a, const int32_t *col_a, int64_t nnz_a, const int32_t *rowid_b,
+                       const int32_t *col_b, int64_t nnz_b, const int64_t *rp_b, const int32_t *absent_a,
+                       const int32_t *absent_b, const int32_t *hit_b, const int64_t *pos_del, const int64_t *pos_ins,
+                       const int64_t *pos_hit, const int32_t *cindex, int self_loop, int64_t n, const int64_t *ins_ptr,
+                       int32_t *ins_col, const int64_t *del_ptr, int32_t *del_col, const int64_t *ent_ptr, uint32_t *ent,
+                       hipStream_t s);
 void launch_scatter_rows(const void *vals, const int32_t *rows, int64_t nrows, int32_t row_bytes, void *x, hipStream_t s);
 void launch_dy(const void *x_prev, const void *x_cur, int bf16, const float *p_prev, const float *p_cur,
                const int32_t *changed, int64_t n_changed, int32_t d, float *dY, hipStream_t s);

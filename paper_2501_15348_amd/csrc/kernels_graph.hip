@@ -1,5 +1,5 @@
 // Integer kernels: exclusive scan, change-set flags, and the snapshot-diff builder that turns two
-// consecutive canonical CSRs into the insert / delete CSRs and the merged signed delta rows
+// consecutive canonical CSRs (sorted edge keys) into the insert / delete CSRs and the merged signed delta rows
 // (paper Section 3.2: delta graphs of edge deletions and insertions, with a node's feature change
 // folded in through its out-edges).  All outputs are unique, so they can be compared bit for bit.
 #include "ctx.h"
@@ -116,11 +116,10 @@ __global__ void compact(const int32_t *flags, const int64_t *offsets, int64_t n,
     if (index_of) index_of[i] = f ? int32_t(offsets[i]) : -1;
 }
 
-// ---- snapshot diff: a group of kGroup lanes walks one row ------------------------------------------------
-constexpr int kGroup = 16;
-constexpr int kDiffThreads = 256;
-constexpr int kRowsPerBlock = kDiffThreads / kGroup;
-
+// ---- snapshot diff, one thread per edge -----------------------------------------------------------------
+// Every edge of one snapshot looks itself up in the same row of the other snapshot (binary search over that
+// row's sorted columns).  Work is per edge, so a hub row costs no more per element than a short one and the
+// launch has no long tail; consecutive threads share a row, so the row bounds and the top probes hit in cache.
 __device__ inline bool row_find(const int32_t *col, int64_t beg, int64_t end, int32_t key)
 {
     int64_t lo = beg, hi = end;
@@ -134,143 +133,78 @@ __device__ inline bool row_find(const int32_t *col, int64_t beg, int64_t end, in
     return lo < end && col[lo] == key;
 }
 
-// Membership of this lane's two values in the other list of a row that fits one group (both lists <= kGroup
-// long): the group's lanes hand their values round with shuffles, so no dependent global reads are needed.
-// A lane without a value passes -1, which never matches a node id.
-__device__ inline void group_membership(int32_t av, int32_t bv, int lane, bool &a_in_b, bool &b_in_a)
+// absent[e] = 1 if edge e of `self` is not in `other`; hit[e] = cflags[col[e]] != 0 (optional)
+__global__ void edge_flags(const int32_t *rowid, const int32_t *col, int64_t nnz, const int64_t *other_ptr,
+                           const int32_t *other_col, const int32_t *cflags, int32_t *absent, int32_t *hit)
 {
-    const int gbase = lane & ~(kGroup - 1);
-    a_in_b = false;
-    b_in_a = false;
-#pragma unroll
-    for (int j = 0; j < kGroup; ++j) {
-        const int32_t bj = __shfl(bv, gbase + j);
-        const int32_t aj = __shfl(av, gbase + j);
-        a_in_b |= (bj == av);
-        b_in_a |= (aj == bv);
+    const int64_t e = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
+    if (e >= nnz) return;
+    const int32_t v = rowid[e], u = col[e];
+    absent[e] = !row_find(other_col, other_ptr[v], other_ptr[v + 1], u);
+    if (hit) hit[e] = cflags[u] != 0;
+}
+
+// Row pointers of the three outputs from the per-edge prefix sums:
+//   ins_ptr[v] = pos_ins[rp_b[v]], del_ptr[v] = pos_del[rp_a[v]],
+//   ent_ptr[v] = ins_ptr[v] + del_ptr[v] + pos_hit[rp_b[v]] + (self_loop ? pos_self[v] : 0)
+__global__ void delta_row_ptrs(const int64_t *rp_a, const int64_t *rp_b, const int64_t *pos_del, const int64_t *pos_ins,
+                               const int64_t *pos_hit, const int64_t *pos_self, int self_loop, int64_t n,
+                               int64_t *ins_ptr, int64_t *del_ptr, int64_t *ent_ptr)
+{
+    const int64_t v = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
+    if (v > n) return;
+    const int64_t i = pos_ins[rp_b[v]], d = pos_del[rp_a[v]];
+    ins_ptr[v] = i;
+    del_ptr[v] = d;
+    ent_ptr[v] = i + d + pos_hit[rp_b[v]] + (self_loop ? pos_self[v] : 0);
+}
+
+__global__ void row_nonempty(const int64_t *ent_ptr, int64_t n, int32_t *flag)
+{
+    const int64_t v = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
+    if (v < n) flag[v] = ent_ptr[v + 1] > ent_ptr[v];
+}
+
+// Inserted edges (kind 0) and changed-source entries (kind 2) come from snapshot t's edges.
+__global__ void fill_from_cur(const int32_t *rowid, const int32_t *col, int64_t nnz, const int64_t *rp_b,
+                              const int32_t *absent, const int32_t *hit, const int64_t *pos_ins, const int64_t *pos_hit,
+                              const int32_t *cindex, const int64_t *ins_ptr, const int64_t *del_ptr,
+                              const int64_t *ent_ptr, int32_t *ins_col, uint32_t *ent)
+{
+    const int64_t e = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
+    if (e >= nnz) return;
+    const int32_t v = rowid[e], u = col[e];
+    if (absent[e]) {
+        const int64_t r = pos_ins[e];
+        ins_col[r] = u;
+        ent[ent_ptr[v] + (r - ins_ptr[v])] = uint32_t(u);
+    }
+    if (hit[e]) {
+        const int64_t base = ent_ptr[v] + (ins_ptr[v + 1] - ins_ptr[v]) + (del_ptr[v + 1] - del_ptr[v]);
+        ent[base + (pos_hit[e] - pos_hit[rp_b[v]])] = (2u << kKindShift) | uint32_t(cindex[u]);
     }
 }
 
-__device__ inline int wave_max(int v)
+// Deleted edges (kind 1) come from snapshot t-1's edges.
+__global__ void fill_from_prev(const int32_t *rowid, const int32_t *col, int64_t nnz, const int32_t *absent,
+                               const int64_t *pos_del, const int64_t *ins_ptr, const int64_t *del_ptr,
+                               const int64_t *ent_ptr, int32_t *del_col, uint32_t *ent)
 {
-    for (int off = 32; off > 0; off >>= 1) v = max(v, __shfl_xor(v, off));
-    return v;
+    const int64_t e = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
+    if (e >= nnz || !absent[e]) return;
+    const int32_t v = rowid[e], u = col[e];
+    const int64_t r = pos_del[e];
+    del_col[r] = u;
+    ent[ent_ptr[v] + (ins_ptr[v + 1] - ins_ptr[v]) + (r - del_ptr[v])] = (1u << kKindShift) | uint32_t(u);
 }
 
-// A = snapshot t-1, B = snapshot t.  Per row: |B \ A|, |A \ B|, and the size of the merged delta row.
-__global__ void __launch_bounds__(kDiffThreads)
-delta_count(const int64_t *rp_a, const int32_t *col_a, const int64_t *rp_b, const int32_t *col_b, const int32_t *cflags,
-            int self_loop, int64_t n, int32_t *cnt_ins, int32_t *cnt_del, int32_t *cnt_all, int32_t *row_flag)
+// The row's own entry (self-loop of a changed node) is the last entry of its row.
+__global__ void fill_self(const int32_t *cindex, int64_t n, const int64_t *ent_ptr, uint32_t *ent)
 {
-    const int lane = threadIdx.x & 63;
-    const int g = lane / kGroup, li = lane % kGroup;
-    const uint64_t gmask = ((uint64_t(1) << kGroup) - 1) << (g * kGroup);
-    int64_t v = int64_t(blockIdx.x) * kRowsPerBlock + threadIdx.x / kGroup;
-    bool live = v < n;
-    int64_t a0 = 0, a1 = 0, b0 = 0, b1 = 0;
-    if (live) {
-        a0 = rp_a[v];
-        a1 = rp_a[v + 1];
-        b0 = rp_b[v];
-        b1 = rp_b[v + 1];
-    }
-    int la = int(a1 - a0), lb = int(b1 - b0);
-    int iters = (wave_max(max(la, lb)) + kGroup - 1) / kGroup;
-    int n_ins = 0, n_del = 0, n_f = 0;
-    const bool short_row = la <= kGroup && lb <= kGroup;
-    for (int it = 0; it < iters; ++it) {
-        int k = it * kGroup + li;
-        const int32_t av = k < la ? col_a[a0 + k] : -1;
-        const int32_t bv = k < lb ? col_b[b0 + k] : -1;
-        bool a_in_b, b_in_a;
-        group_membership(av, bv, lane, a_in_b, b_in_a);
-        if (!short_row) {
-            a_in_b = k < la && row_find(col_b, b0, b1, av);
-            b_in_a = k < lb && row_find(col_a, a0, a1, bv);
-        }
-        const bool is_del = k < la && !a_in_b;
-        const bool is_ins = k < lb && !b_in_a;
-        const bool is_f = k < lb && cflags[bv] != 0;
-        n_del += __popcll(__ballot(is_del) & gmask);
-        n_ins += __popcll(__ballot(is_ins) & gmask);
-        n_f += __popcll(__ballot(is_f) & gmask);
-    }
-    if (live && li == 0) {
-        if (self_loop && cflags[v]) n_f += 1;
-        cnt_ins[v] = n_ins;
-        cnt_del[v] = n_del;
-        int all = n_ins + n_del + n_f;
-        cnt_all[v] = all;
-        row_flag[v] = all > 0;
-    }
-}
-
-__global__ void __launch_bounds__(kDiffThreads)
-delta_fill(const int64_t *rp_a, const int32_t *col_a, const int64_t *rp_b, const int32_t *col_b, const int32_t *cindex,
-           int self_loop, int64_t n, const int64_t *ins_ptr, int32_t *ins_col, const int64_t *del_ptr, int32_t *del_col,
-           const int64_t *ent_ptr, uint32_t *ent)
-{
-    const int lane = threadIdx.x & 63;
-    const int g = lane / kGroup, li = lane % kGroup;
-    const uint64_t gmask = ((uint64_t(1) << kGroup) - 1) << (g * kGroup);
-    const uint64_t below = (uint64_t(1) << lane) - 1;
-    int64_t v = int64_t(blockIdx.x) * kRowsPerBlock + threadIdx.x / kGroup;
-    bool live = v < n;
-    int64_t a0 = 0, a1 = 0, b0 = 0, b1 = 0, o_ins = 0, o_del = 0, e_ins = 0, e_del = 0, e_f = 0;
-    if (live) {
-        a0 = rp_a[v];
-        a1 = rp_a[v + 1];
-        b0 = rp_b[v];
-        b1 = rp_b[v + 1];
-        o_ins = ins_ptr[v];
-        o_del = del_ptr[v];
-        e_ins = ent_ptr[v];
-        e_del = e_ins + (ins_ptr[v + 1] - o_ins);
-        e_f = e_del + (del_ptr[v + 1] - o_del);
-    }
-    int la = int(a1 - a0), lb = int(b1 - b0);
-    int iters = (wave_max(max(la, lb)) + kGroup - 1) / kGroup;
-    const bool short_row = la <= kGroup && lb <= kGroup;
-    for (int it = 0; it < iters; ++it) {
-        int k = it * kGroup + li;
-        const int32_t ua = k < la ? col_a[a0 + k] : -1;
-        const int32_t ub = k < lb ? col_b[b0 + k] : -1;
-        bool a_in_b, b_in_a;
-        group_membership(ua, ub, lane, a_in_b, b_in_a);
-        if (!short_row) {
-            a_in_b = k < la && row_find(col_b, b0, b1, ua);
-            b_in_a = k < lb && row_find(col_a, a0, a1, ub);
-        }
-        const bool is_del = k < la && !a_in_b;
-        const bool is_ins = k < lb && !b_in_a;
-        const int32_t ci = k < lb ? cindex[ub] : -1;
-        const bool is_f = ci >= 0;
-        uint64_t m_del = __ballot(is_del) & gmask, m_ins = __ballot(is_ins) & gmask, m_f = __ballot(is_f) & gmask;
-        if (is_del) {
-            int r = __popcll(m_del & below);
-            del_col[o_del + r] = ua;
-            ent[e_del + r] = (1u << kKindShift) | uint32_t(ua);
-        }
-        if (is_ins) {
-            int r = __popcll(m_ins & below);
-            ins_col[o_ins + r] = ub;
-            ent[e_ins + r] = uint32_t(ub);
-        }
-        if (is_f) {
-            int r = __popcll(m_f & below);
-            ent[e_f + r] = (2u << kKindShift) | uint32_t(ci);
-        }
-        int c_del = __popcll(m_del), c_ins = __popcll(m_ins), c_f = __popcll(m_f);
-        o_del += c_del;
-        e_del += c_del;
-        o_ins += c_ins;
-        e_ins += c_ins;
-        e_f += c_f;
-    }
-    if (live && li == 0 && self_loop) {
-        int ci = cindex[v];
-        if (ci >= 0) ent[e_f] = (2u << kKindShift) | uint32_t(ci);
-    }
+    const int64_t v = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
+    if (v >= n) return;
+    const int32_t ci = cindex[v];
+    if (ci >= 0) ent[ent_ptr[v + 1] - 1] = (2u << kKindShift) | uint32_t(ci);
 }
 
 // X[rows[r]] = vals[r], rows of `chunks` 16-byte pieces
@@ -360,22 +294,36 @@ void launch_compact(const int32_t *flags, const int64_t *offsets, int64_t n, int
     if (n > 0) compact<<<blocks_for(n, 256), 256, 0, s>>>(flags, offsets, n, list, index_of);
 }
 
-void launch_delta_count(const int64_t *rp_a, const int32_t *col_a, const int64_t *rp_b, const int32_t *col_b,
-                        const int32_t *cflags, int self_loop, int64_t n, int32_t *cnt_ins, int32_t *cnt_del,
-                        int32_t *cnt_all, int32_t *row_flag, hipStream_t s)
+void launch_edge_flags(const int32_t *rowid, const int32_t *col, int64_t nnz, const int64_t *other_ptr,
+                       const int32_t *other_col, const int32_t *cflags, int32_t *absent, int32_t *hit, hipStream_t s)
 {
-    if (n > 0)
-        delta_count<<<blocks_for(n, kRowsPerBlock), kDiffThreads, 0, s>>>(rp_a, col_a, rp_b, col_b, cflags, self_loop, n,
-                                                                          cnt_ins, cnt_del, cnt_all, row_flag);
+    if (nnz > 0)
+        edge_flags<<<blocks_for(nnz, 256), 256, 0, s>>>(rowid, col, nnz, other_ptr, other_col, cflags, absent, hit);
 }
 
-void launch_delta_fill(const int64_t *rp_a, const int32_t *col_a, const int64_t *rp_b, const int32_t *col_b,
-                       const int32_t *cindex, int self_loop, int64_t n, const int64_t *ins_ptr, int32_t *ins_col,
-                       const int64_t *del_ptr, int32_t *del_col, const int64_t *ent_ptr, uint32_t *ent, hipStream_t s)
+void launch_delta_row_ptrs(const int64_t *rp_a, const int64_t *rp_b, const int64_t *pos_del, const int64_t *pos_ins,
+                           const int64_t *pos_hit, const int64_t *pos_self, int self_loop, int64_t n, int64_t *ins_ptr,
+                           int64_t *del_ptr, int64_t *ent_ptr, int32_t *row_flag, hipStream_t s)
 {
-    if (n > 0)
-        delta_fill<<<blocks_for(n, kRowsPerBlock), kDiffThreads, 0, s>>>(rp_a, col_a, rp_b, col_b, cindex, self_loop, n,
-                                                                         ins_ptr, ins_col, del_ptr, del_col, ent_ptr, ent);
+    delta_row_ptrs<<<blocks_for(n + 1, 256), 256, 0, s>>>(rp_a, rp_b, pos_del, pos_ins, pos_hit, pos_self, self_loop, n,
+                                                          ins_ptr, del_ptr, ent_ptr);
+    if (n > 0) row_nonempty<<<blocks_for(n, 256), 256, 0, s>>>(ent_ptr, n, row_flag);
+}
+
+void launch_delta_fill(const int32_t *rowid_a, const int32_t *col_a, int64_t nnz_a, const int32_t *rowid_b,
+                       const int32_t *col_b, int64_t nnz_b, const int64_t *rp_b, const int32_t *absent_a,
+                       const int32_t *absent_b, const int32_t *hit_b, const int64_t *pos_del, const int64_t *pos_ins,
+                       const int64_t *pos_hit, const int32_t *cindex, int self_loop, int64_t n, const int64_t *ins_ptr,
+                       int32_t *ins_col, const int64_t *del_ptr, int32_t *del_col, const int64_t *ent_ptr, uint32_t *ent,
+                       hipStream_t s)
+{
+    if (nnz_b > 0)
+        fill_from_cur<<<blocks_for(nnz_b, 256), 256, 0, s>>>(rowid_b, col_b, nnz_b, rp_b, absent_b, hit_b, pos_ins, pos_hit,
+                                                             cindex, ins_ptr, del_ptr, ent_ptr, ins_col, ent);
+    if (nnz_a > 0)
+        fill_from_prev<<<blocks_for(nnz_a, 256), 256, 0, s>>>(rowid_a, col_a, nnz_a, absent_a, pos_del, ins_ptr, del_ptr,
+                                                              ent_ptr, del_col, ent);
+    if (self_loop && n > 0) fill_self<<<blocks_for(n, 256), 256, 0, s>>>(cindex, n, ent_ptr, ent);
 }
 
 void launch_scatter_rows(const void *vals, const int32_t *rows, int64_t nrows, int32_t row_bytes, void *x, hipStream_t s)
