@@ -287,6 +287,15 @@ static int build_one(reinc_ctx *ctx, int32_t t, hipStream_t s)
     launch_delta_row_ptrs(a.row_ptr, b.row_ptr, pos_del, pos_ins, pos_hit, coffs, ctx->cfg.self_loop, n, dl.ins_ptr,
                           dl.del_ptr, dl.ent_ptr, row_flag, s);
     launch_scan(row_flag, roffs, n, scan_tmp, s);
+    int32_t *long_flag = nullptr;
+    int64_t *loffs = i64s(n + 1);
+    int32_t *long_flag_own = i32s(n);
+    if (!loffs || !long_flag_own) return nomem("scratch");
+    long_flag = long_flag_own;
+    launch_row_long_flags(dl.ent_ptr, n, long_flag, s);
+    launch_scan(long_flag, loffs, n, scan_tmp, s);
+    int64_t n_long = 0;
+    REINC_HIP(ctx, hipMemcpyAsync(&n_long, loffs + n, 8, hipMemcpyDeviceToHost, s));
     int64_t totals[5] = {0, 0, 0, 0, 0};
     REINC_HIP(ctx, hipMemcpyAsync(&totals[0], dl.ins_ptr + n, 8, hipMemcpyDeviceToHost, s));
     REINC_HIP(ctx, hipMemcpyAsync(&totals[1], dl.del_ptr + n, 8, hipMemcpyDeviceToHost, s));
@@ -301,7 +310,11 @@ static int build_one(reinc_ctx *ctx, int32_t t, hipStream_t s)
     dl.del_col = static_cast<int32_t *>(ctx->alloc(uint64_t(std::max<int64_t>(totals[1], 1)) * 4));
     dl.ent = static_cast<uint32_t *>(ctx->alloc(uint64_t(std::max<int64_t>(totals[2], 1)) * 4));
     dl.rows = static_cast<int32_t *>(ctx->alloc(uint64_t(std::max<int64_t>(totals[3], 1)) * 4));
-    if (!dl.changed || !dl.dY || !dl.ins_col || !dl.del_col || !dl.ent || !dl.rows) return nomem("delta entries");
+    dl.long_rows = static_cast<int32_t *>(ctx->alloc(uint64_t(std::max<int64_t>(n_long, 1)) * 4));
+    dl.n_long_rows = n_long;
+    if (!dl.changed || !dl.dY || !dl.ins_col || !dl.del_col || !dl.ent || !dl.rows || !dl.long_rows)
+        return nomem("delta entries");
+    launch_compact(long_flag, loffs, n, dl.long_rows, nullptr, s);
     launch_compact(cflags, coffs, n, dl.changed, cindex, s);
     launch_dy(a.x, b.x, bf16, a.p, b.p, dl.changed, n_changed, d, dl.dY, s);
     {
@@ -444,8 +457,8 @@ int reinc_aggregate_incremental(reinc_ctx *ctx, int32_t t, const float *S_prev, 
     }
     {
         ProfScope prof(ctx, REINC_K_AGG_INC, as_stream(stream));
-        launch_incremental(dl.rows, dl.info.n_rows, dl.ent_ptr, dl.ent, pv.x, ctx->cfg.feat_dtype == REINC_BF16, pv.p, dl.dY,
-                           d, S_out, S_out, sn.q, agg_out, as_stream(stream));
+        launch_incremental(dl.rows, dl.info.n_rows, dl.long_rows, dl.n_long_rows, dl.ent_ptr, dl.ent, pv.x,
+                           ctx->cfg.feat_dtype == REINC_BF16, pv.p, dl.dY, d, S_out, S_out, sn.q, agg_out, as_stream(stream));
     }
     REINC_HIP(ctx, hipGetLastError());
     ctx->stats.delta_entries_processed += dl.info.n_entries;

@@ -16,7 +16,7 @@ namespace reinc {
 constexpr uint32_t kKindShift = 30;  // merged delta entry = (kind << 30) | payload
 constexpr uint32_t kPayloadMask = (1u << kKindShift) - 1u;
 constexpr int64_t kMaxNodes = int64_t(1) << kKindShift;
-constexpr int kLongRow = 512;  // rows with more in-edges than this take the block-per-row path
+constexpr int kLongRow = 64;  // rows with more in-edges than this take the block-per-row path
 
 // One canonical snapshot on the device.
 struct Snapshot {
@@ -56,6 +56,8 @@ struct Delta {
     int64_t *ent_ptr = nullptr;  // [N+1]
     uint32_t *ent = nullptr;     // [n_entries]
     int32_t *rows = nullptr;     // R_t [n_rows]
+    int32_t *long_rows = nullptr;  // rows of R_t with more than kLongRow entries
+    int64_t n_long_rows = 0;
     int32_t *changed = nullptr;  // C_t [n_changed]
     float *dY = nullptr;         // [n_changed, d0] fp32
 };
@@ -214,9 +216,13 @@ void launch_aggregate_long(const int64_t *ptr, const int32_t *idx, const int32_t
 void aggregate_full(reinc_ctx *ctx, const int64_t *ptr, const int32_t *idx, const int32_t *long_rows, int32_t n_long,
                     const void *X, int bf16, int32_t d, int self_loop, const float *in_scale, const float *out_scale,
                     const float *mask, float *out, hipStream_t s);
-void launch_incremental(const int32_t *rows, int64_t n_rows, const int64_t *ent_ptr, const uint32_t *ent,
-                        const void *x_prev, int bf16, const float *p_prev, const float *dY, int32_t d,
-                        const float *S_prev, float *S_out, const float *q, float *agg_out, hipStream_t s);
+// rows: every changed row (those of at most kLongRow entries are taken one per lane group); long_rows: the
+// changed rows with more entries (one wavefront each)
+void launch_incremental(const int32_t *rows, int64_t n_rows, const int32_t *long_rows, int64_t n_long,
+                        const int64_t *ent_ptr, const uint32_t *ent, const void *x_prev, int bf16, const float *p_prev,
+                        const float *dY, int32_t d, const float *S_prev, float *S_out, const float *q, float *agg_out,
+                        hipStream_t s);
+void launch_row_long_flags(const int64_t *ent_ptr, int64_t n, int32_t *flag, hipStream_t s);
 
 // ---- kernels_dense.hip
 // out[n,M] = epilogue((row_scale .* A)[n,K] * B[K,M]); B = W (ldw = row stride) or W^T when w_transposed.

@@ -6,6 +6,8 @@
 //       load each, so 64/LPR source rows are in flight per load instruction and U of those
 //       instructions are issued back to back.  Rows with more than kLongRow entries are skipped
 //       and taken by a 4-wave block with an LDS reduction (power-law hubs).
+//   aggregate_rows_grouped / incremental_rows_grouped : the same sums with one row per group of LPR lanes, for
+//       rows of at most kLongRow entries (the bulk of a power-law graph): more independent chains per wave.
 //   incremental_rows : Eq. 2 in the form  S_t[r] = S_{t-1}[r] + sum_ins Y_{t-1}[u] - sum_del Y_{t-1}[u]
 //       + sum_changed dY[u]  over the rows of R_t only, same lane layout, signed tagged entries.
 //
@@ -91,18 +93,23 @@ __device__ inline void gather_segment(const int32_t *idx, int64_t beg, int64_t e
         for (int k = 0; k < cnt; k += G * kUnroll) {
             float r[kUnroll][VEC];
             float sc[kUnroll];
+            // the row gathers depend only on the column ids: issue them before touching the gathered scales
 #pragma unroll
             for (int j = 0; j < kUnroll; ++j) {
                 const int e = k + j * G + g;
                 const int32_t u = __shfl(my_u, e & 63);
-                sc[j] = __shfl(my_sc, e & 63);
                 if (e < cnt) {
                     Row<BF16>::load(X, u, d, li, r[j]);
                 } else {
-                    sc[j] = 0.0f;
 #pragma unroll
                     for (int i = 0; i < VEC; ++i) r[j][i] = 0.0f;
                 }
+            }
+#pragma unroll
+            for (int j = 0; j < kUnroll; ++j) {
+                const int e = k + j * G + g;
+                sc[j] = __shfl(my_sc, e & 63);
+                if (e >= cnt) sc[j] = 0.0f;
             }
 #pragma unroll
             for (int j = 0; j < kUnroll; ++j)
@@ -160,6 +167,100 @@ aggregate_rows(const int64_t *__restrict__ ptr, const int32_t *__restrict__ idx,
                 if (!(m[i] > 0.0f)) acc[i] = 0.0f;
         }
         store_f32<VEC>(out, v, D, lane, acc);
+    }
+}
+
+// Short rows: every group of LPR lanes owns one output row, so a wave keeps 64/LPR independent
+// row-pointer -> column-id -> source-row chains in flight and writes with all 64 lanes.  Rows longer than
+// kLongRow are left to the block path.
+template <int LPR, bool BF16>
+__global__ void __launch_bounds__(64 * kWavesPerBlock)
+aggregate_rows_grouped(const int64_t *__restrict__ ptr, const int32_t *__restrict__ idx, const void *__restrict__ X,
+                       int64_t n, int self_loop, const float *__restrict__ in_scale,
+                       const float *__restrict__ out_scale, const float *__restrict__ mask, float *__restrict__ out,
+                       int skip_long)
+{
+    constexpr int VEC = Row<BF16>::kVec;
+    constexpr int D = LPR * VEC;
+    constexpr int G = 64 / LPR;
+    const int lane = threadIdx.x & 63;
+    const int g = lane / LPR, li = lane % LPR, gbase = g * LPR;
+    const int64_t v = (int64_t(blockIdx.x) * kWavesPerBlock + (threadIdx.x >> 6)) * G + g;
+    const bool live = v < n;
+    int64_t beg = 0, end = 0;
+    if (live) {
+        beg = ptr[v];
+        end = ptr[v + 1];
+    }
+    bool skipped = false;
+    if (skip_long && end - beg > kLongRow) {
+        skipped = true;
+        end = beg;
+    }
+    float acc[VEC];
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) acc[i] = 0.0f;
+    // wave-uniform trip counts: the longest row of the wave decides
+    int len = int(end - beg);
+    int maxlen = len;
+#pragma unroll
+    for (int off = LPR; off < 64; off <<= 1) maxlen = max(maxlen, __shfl_xor(maxlen, off));
+    for (int base = 0; base < maxlen; base += LPR) {
+        const int cnt = min(LPR, max(len - base, 0));
+        int32_t my_u = 0;
+        float my_sc = 1.0f;
+        if (li < cnt) {
+            my_u = idx[beg + base + li];
+            if (in_scale) my_sc = in_scale[my_u];
+        }
+        const int cmax = min(LPR, maxlen - base);
+        for (int k = 0; k < cmax; k += kUnroll) {
+            float r[kUnroll][VEC];
+            float sc[kUnroll];
+#pragma unroll
+            for (int j = 0; j < kUnroll; ++j) {
+                const int e = k + j;
+                const int32_t u = __shfl(my_u, gbase + (e & (LPR - 1)));
+                if (e < cnt) {
+                    Row<BF16>::load(X, u, D, li, r[j]);
+                } else {
+#pragma unroll
+                    for (int i = 0; i < VEC; ++i) r[j][i] = 0.0f;
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < kUnroll; ++j) {
+                const int e = k + j;
+                sc[j] = __shfl(my_sc, gbase + (e & (LPR - 1)));
+                if (e >= cnt) sc[j] = 0.0f;
+            }
+#pragma unroll
+            for (int j = 0; j < kUnroll; ++j)
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) acc[i] += sc[j] * r[j][i];
+        }
+    }
+    if (live && !skipped) {
+        if (self_loop) {
+            float r[VEC];
+            Row<BF16>::load(X, v, D, li, r);
+            const float sc = in_scale ? in_scale[v] : 1.0f;
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) acc[i] += sc * r[i];
+        }
+        if (out_scale) {
+            const float q = out_scale[v];
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) acc[i] *= q;
+        }
+        if (mask) {
+            float m[VEC];
+            load_f32<VEC>(mask, v, D, li, m);
+#pragma unroll
+            for (int i = 0; i < VEC; ++i)
+                if (!(m[i] > 0.0f)) acc[i] = 0.0f;
+        }
+        store_f32<VEC>(out, v, D, li, acc);
     }
 }
 
@@ -291,6 +392,96 @@ incremental_rows(const int32_t *__restrict__ rows, int64_t n_rows, const int64_t
     }
 }
 
+// Changed rows with at most kLongRow entries, one row per group of LPR lanes (see aggregate_rows_grouped).
+template <int LPR, bool BF16>
+__global__ void __launch_bounds__(64 * kWavesPerBlock)
+incremental_rows_grouped(const int32_t *__restrict__ rows, int64_t n_rows, const int64_t *__restrict__ ent_ptr,
+                         const uint32_t *__restrict__ ent, const void *__restrict__ x_prev,
+                         const float *__restrict__ p_prev, const float *__restrict__ dY, const float *S_prev, float *S_out,
+                         const float *__restrict__ q, float *__restrict__ agg_out)
+{
+    constexpr int VEC = Row<BF16>::kVec;
+    constexpr int D = LPR * VEC;
+    constexpr int G = 64 / LPR;
+    const int lane = threadIdx.x & 63;
+    const int g = lane / LPR, li = lane % LPR, gbase = g * LPR;
+    const int64_t w = (int64_t(blockIdx.x) * kWavesPerBlock + (threadIdx.x >> 6)) * G + g;
+    const bool live = w < n_rows;
+    int64_t v = 0, beg = 0, end = 0;
+    if (live) {
+        v = rows[w];
+        beg = ent_ptr[v];
+        end = ent_ptr[v + 1];
+    }
+    const bool mine = live && end - beg <= kLongRow;  // longer rows belong to the wave-per-row pass
+    if (!mine) end = beg;
+    float s_old[VEC];
+    if (mine) load_f32<VEC>(S_prev, v, D, li, s_old);  // issued early: independent of the entry chain
+    float acc[VEC];
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) acc[i] = 0.0f;
+    const int len = int(end - beg);
+    int maxlen = len;
+#pragma unroll
+    for (int off = LPR; off < 64; off <<= 1) maxlen = max(maxlen, __shfl_xor(maxlen, off));
+    for (int base = 0; base < maxlen; base += LPR) {
+        const int cnt = min(LPR, max(len - base, 0));
+        uint32_t my_e = 0;
+        float my_sc = 0.0f;
+        if (li < cnt) {
+            my_e = ent[beg + base + li];
+            const uint32_t kind = my_e >> kKindShift;
+            if (kind == 2u) {
+                my_sc = 1.0f;
+            } else {
+                my_sc = p_prev ? p_prev[my_e & kPayloadMask] : 1.0f;
+                if (kind == 1u) my_sc = -my_sc;
+            }
+        }
+        const int cmax = min(LPR, maxlen - base);
+        for (int k = 0; k < cmax; k += kUnroll) {
+            float r[kUnroll][VEC];
+            float sc[kUnroll];
+#pragma unroll
+            for (int j = 0; j < kUnroll; ++j) {
+                const int e = k + j;
+                const uint32_t en = __shfl(my_e, gbase + (e & (LPR - 1)));
+                if (e < cnt) {
+                    const int64_t u = en & kPayloadMask;
+                    if ((en >> kKindShift) == 2u)
+                        load_f32<VEC>(dY, u, D, li, r[j]);
+                    else
+                        Row<BF16>::load(x_prev, u, D, li, r[j]);
+                } else {
+#pragma unroll
+                    for (int i = 0; i < VEC; ++i) r[j][i] = 0.0f;
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < kUnroll; ++j) {
+                const int e = k + j;
+                sc[j] = __shfl(my_sc, gbase + (e & (LPR - 1)));
+                if (e >= cnt) sc[j] = 0.0f;
+            }
+#pragma unroll
+            for (int j = 0; j < kUnroll; ++j)
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) acc[i] += sc[j] * r[j][i];
+        }
+    }
+    if (mine) {
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) s_old[i] += acc[i];
+        store_f32<VEC>(S_out, v, D, li, s_old);
+        if (agg_out) {
+            const float qq = q ? q[v] : 1.0f;
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) s_old[i] *= qq;
+            store_f32<VEC>(agg_out, v, D, li, s_old);
+        }
+    }
+}
+
 inline int lanes_per_row(int32_t d, int bf16)
 {
     int64_t bytes = int64_t(d) * (bf16 ? 2 : 4);
@@ -303,13 +494,16 @@ void aggregate_dispatch(int lpr, const int64_t *ptr, const int32_t *idx, int32_t
                         int self_loop, const float *in_scale, const float *out_scale, const float *mask, float *out,
                         hipStream_t s)
 {
-    const unsigned blocks = unsigned((n + kWavesPerBlock - 1) / kWavesPerBlock);
     const dim3 th(64 * kWavesPerBlock);
     const int skip = n_long > 0;
-#define REINC_AGG_CASE(L)                                                                                                \
-    case L:                                                                                                              \
-        aggregate_rows<L, BF16><<<blocks, th, 0, s>>>(ptr, idx, X, n, self_loop, in_scale, out_scale, mask, out, skip);  \
-        break;
+#define REINC_AGG_CASE(L)                                                                                           \
+    case L: {                                                                                                       \
+        const int64_t rows_per_block = int64_t(kWavesPerBlock) * (64 / L);                                          \
+        const unsigned blocks = unsigned((n + rows_per_block - 1) / rows_per_block);                                \
+        aggregate_rows_grouped<L, BF16><<<blocks, th, 0, s>>>(ptr, idx, X, n, self_loop, in_scale, out_scale, mask, \
+                                                              out, skip);                                           \
+        break;                                                                                                      \
+    }
     switch (lpr) {
         REINC_AGG_CASE(1)
         REINC_AGG_CASE(2)
@@ -346,17 +540,24 @@ void aggregate_long_dispatch(int lpr, const int64_t *ptr, const int32_t *idx, co
 }
 
 template <bool BF16>
-void incremental_dispatch(int lpr, const int32_t *rows, int64_t n_rows, const int64_t *ent_ptr, const uint32_t *ent,
-                          const void *x_prev, const float *p_prev, const float *dY, const float *S_prev, float *S_out,
-                          const float *q, float *agg_out, hipStream_t s)
+void incremental_dispatch(int lpr, const int32_t *rows, int64_t n_rows, const int32_t *long_rows, int64_t n_long,
+                          const int64_t *ent_ptr, const uint32_t *ent, const void *x_prev, const float *p_prev,
+                          const float *dY, const float *S_prev, float *S_out, const float *q, float *agg_out,
+                          hipStream_t s)
 {
-    const unsigned blocks = unsigned((n_rows + kWavesPerBlock - 1) / kWavesPerBlock);
     const dim3 th(64 * kWavesPerBlock);
-#define REINC_INC_CASE(L)                                                                                              \
-    case L:                                                                                                            \
-        incremental_rows<L, BF16><<<blocks, th, 0, s>>>(rows, n_rows, ent_ptr, ent, x_prev, p_prev, dY, S_prev, S_out, q, \
-                                                        agg_out);                                                      \
-        break;
+    const unsigned long_blocks = unsigned((n_long + kWavesPerBlock - 1) / kWavesPerBlock);
+#define REINC_INC_CASE(L)                                                                                           \
+    case L: {                                                                                                       \
+        const int64_t rows_per_block = int64_t(kWavesPerBlock) * (64 / L);                                          \
+        const unsigned blocks = unsigned((n_rows + rows_per_block - 1) / rows_per_block);                           \
+        incremental_rows_grouped<L, BF16><<<blocks, th, 0, s>>>(rows, n_rows, ent_ptr, ent, x_prev, p_prev, dY, S_prev, \
+                                                                S_out, q, agg_out);                                 \
+        if (n_long > 0)                                                                                             \
+            incremental_rows<L, BF16><<<long_blocks, th, 0, s>>>(long_rows, n_long, ent_ptr, ent, x_prev, p_prev, dY, \
+                                                                 S_prev, S_out, q, agg_out);                        \
+        break;                                                                                                      \
+    }
     switch (lpr) {
         REINC_INC_CASE(1)
         REINC_INC_CASE(2)
@@ -408,16 +609,19 @@ void aggregate_full(reinc_ctx *ctx, const int64_t *ptr, const int32_t *idx, cons
     launch_aggregate_long(ptr, idx, long_rows, n_long, X, bf16, d, self_loop, in_scale, out_scale, mask, out, s);
 }
 
-void launch_incremental(const int32_t *rows, int64_t n_rows, const int64_t *ent_ptr, const uint32_t *ent,
-                        const void *x_prev, int bf16, const float *p_prev, const float *dY, int32_t d,
-                        const float *S_prev, float *S_out, const float *q, float *agg_out, hipStream_t s)
+void launch_incremental(const int32_t *rows, int64_t n_rows, const int32_t *long_rows, int64_t n_long,
+                        const int64_t *ent_ptr, const uint32_t *ent, const void *x_prev, int bf16, const float *p_prev,
+                        const float *dY, int32_t d, const float *S_prev, float *S_out, const float *q, float *agg_out,
+                        hipStream_t s)
 {
     if (n_rows <= 0) return;
     const int lpr = lanes_per_row(d, bf16);
     if (bf16)
-        incremental_dispatch<true>(lpr, rows, n_rows, ent_ptr, ent, x_prev, p_prev, dY, S_prev, S_out, q, agg_out, s);
+        incremental_dispatch<true>(lpr, rows, n_rows, long_rows, n_long, ent_ptr, ent, x_prev, p_prev, dY, S_prev, S_out, q,
+                                   agg_out, s);
     else
-        incremental_dispatch<false>(lpr, rows, n_rows, ent_ptr, ent, x_prev, p_prev, dY, S_prev, S_out, q, agg_out, s);
+        incremental_dispatch<false>(lpr, rows, n_rows, long_rows, n_long, ent_ptr, ent, x_prev, p_prev, dY, S_prev, S_out, q,
+                                    agg_out, s);
 }
 
 }  // namespace reinc

@@ -165,6 +165,12 @@ __global__ void row_nonempty(const int64_t *ent_ptr, int64_t n, int32_t *flag)
     if (v < n) flag[v] = ent_ptr[v + 1] > ent_ptr[v];
 }
 
+__global__ void row_long(const int64_t *ent_ptr, int64_t n, int32_t *flag)
+{
+    const int64_t v = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
+    if (v < n) flag[v] = ent_ptr[v + 1] - ent_ptr[v] > kLongRow;
+}
+
 // Inserted edges (kind 0) and changed-source entries (kind 2) come from snapshot t's edges.
 __global__ void fill_from_cur(const int32_t *rowid, const int32_t *col, int64_t nnz, const int64_t *rp_b,
                               const int32_t *absent, const int32_t *hit, const int64_t *pos_ins, const int64_t *pos_hit,
@@ -308,6 +314,11 @@ void launch_delta_row_ptrs(const int64_t *rp_a, const int64_t *rp_b, const int64
     delta_row_ptrs<<<blocks_for(n + 1, 256), 256, 0, s>>>(rp_a, rp_b, pos_del, pos_ins, pos_hit, pos_self, self_loop, n,
                                                           ins_ptr, del_ptr, ent_ptr);
     if (n > 0) row_nonempty<<<blocks_for(n, 256), 256, 0, s>>>(ent_ptr, n, row_flag);
+}
+
+void launch_row_long_flags(const int64_t *ent_ptr, int64_t n, int32_t *flag, hipStream_t s)
+{
+    if (n > 0) row_long<<<blocks_for(n, 256), 256, 0, s>>>(ent_ptr, n, flag);
 }
 
 void launch_delta_fill(const int32_t *rowid_a, const int32_t *col_a, int64_t nnz_a, const int32_t *rowid_b,

@@ -153,8 +153,8 @@ int ensure_layer1(reinc_ctx *ctx, int32_t t, hipStream_t s)
         REINC_HIP(ctx, hipMemcpyAsync(slot, ctx->gcache[t - 1], bytes, hipMemcpyDeviceToDevice, s));
         {
             ProfScope prof(ctx, REINC_K_AGG_INC, s);
-            launch_incremental(dl.rows, dl.info.n_rows, dl.ent_ptr, dl.ent, pv.x, bf16, pv.p, dl.dY, d, slot, slot, nullptr,
-                               nullptr, s);
+            launch_incremental(dl.rows, dl.info.n_rows, dl.long_rows, dl.n_long_rows, dl.ent_ptr, dl.ent, pv.x, bf16, pv.p,
+                               dl.dY, d, slot, slot, nullptr, nullptr, s);
         }
         ++ctx->stats.steps_incremental;
         ctx->stats.delta_entries_processed += dl.info.n_entries;
