@@ -22,6 +22,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E
+LONG_ROW = 64  # rows with more entries than this are aggregated by the block-per-row kernel
 
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
 # command (profiles/bench_c2_hbm_traffic_pmc.txt), scaled by the copy-kernel calibration; None = not measured.
@@ -120,21 +121,39 @@ def main():
     delta_edges = sum(i["n_entries"] for i in infos)
     value = delta_edges / (ms_per_step * 1e-3)
 
-    # ---- roofline of the dominant kernel (wave-per-row gather): algorithmic bytes / measured launch time
+    # ---- roofline of the dominant HBM-bound kernel, aggregate_rows_grouped (it takes every row of at most
+    # LONG_ROW entries; longer rows go to a second, block-per-row kernel that is not part of this figure):
+    # algorithmic bytes of exactly the rows it handles / its measured launch time
     launches, total_ms = prof["agg_full"]
     per_step_full = (st1["steps_full"] - st0["steps_full"]) / args.steps
-    e_mean = float(np.mean([len(s) for s, _ in seq.edges]))
     layers = len(wl.dims) - 1
-    sched = [(per_step_full, agg_bytes(e_mean, n, wl.dims[0], elem))]
-    for l in range(2, layers + 1):  # forward aggregate and backward adjoint of layer l, per window timestep
-        sched.append((2 * windows * L, agg_bytes(e_mean, n, wl.dims[l - 1], 4)))
-    exp_launches = sum(c for c, _ in sched) * args.steps
-    bytes_per_launch = sum(c * b for c, b in sched) / max(sum(c for c, _ in sched), 1)
+    fwd_short, adj_short = [], []  # per snapshot: (edges, rows) handled by the grouped kernel, CSR and CSC side
+    for src, dst in seq.edges:
+        for ids, acc in ((dst, fwd_short), (src, adj_short)):
+            deg = np.bincount(ids, minlength=n)
+            short = deg <= LONG_ROW
+            acc.append((float(deg[short].sum()), float(short.sum())))
+
+    def short_bytes(t, side, d, el):
+        e_s, n_s = (fwd_short if side == "fwd" else adj_short)[t]
+        return e_s * (4 + d * el) + n * 16 + n_s * d * 4
+
+    total_bytes, count = 0.0, 0.0
+    mean_l1 = float(np.mean([short_bytes(t, "fwd", wl.dims[0], elem) for t in range(T)]))
+    total_bytes += per_step_full * mean_l1
+    count += per_step_full
+    for t0_ in range(windows):
+        for t in range(t0_, t0_ + L):
+            for l in range(2, layers + 1):  # forward aggregate and backward adjoint of layer l
+                total_bytes += short_bytes(t, "fwd", wl.dims[l - 1], 4) + short_bytes(t, "adj", wl.dims[l - 1], 4)
+                count += 2
+    exp_launches = count * args.steps
+    bytes_per_launch = total_bytes / max(count, 1)
     avg_ms = total_ms / max(launches, 1)
     achieved = bytes_per_launch / (avg_ms * 1e-3) / 1e9 if launches else 0.0
     roofline = {
-        "bound": "hbm", "kernel": "aggregate_rows", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-        "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC.get(wl.name),
+        "bound": "hbm", "kernel": "aggregate_rows_grouped", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+        "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC.get(wl.name),
         "launches": int(launches), "expected_launches": int(exp_launches), "avg_us": round(avg_ms * 1e3, 2),
         "algorithmic_bytes_per_launch": int(bytes_per_launch),
         "share_of_step_time": round(total_ms / (elapsed * 1e3), 3),

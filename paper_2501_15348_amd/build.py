@@ -25,7 +25,7 @@ def build_library(verbose: bool = False) -> str:
         "-std=c++17",
         "-fPIC",
         "-Wall",
-        "-Wno-unused-function",
+        "-Wno-unused-function", *os.environ.get("REINC_EXTRA_FLAGS", "").split(),
         # keep the compiler from emitting packed-fp32 instructions
         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
         "-I", os.path.join(ROOT, "include"),

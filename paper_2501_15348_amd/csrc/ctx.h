@@ -234,9 +234,11 @@ void launch_rnn_fused(int lstm, const float *x, int64_t n, int32_t d_in, int32_t
                       const float *c_prev, const float *W_i, const float *W_h, const float *b_i, const float *b_h,
                       float *h_out, float *c_out, float *saved, hipStream_t s);
 uint64_t reduce_partial_bytes(int64_t n, int32_t K, int32_t M);
-// dW[K,M] += (row_scale .* A)^T G ; db[M] += column sums of G (db may be null)
+// partial[chunk] (+)= (row_scale .* A)^T G over the chunk's rows, with the column sums of G in row K; `accumulate`
+// adds to what the slabs hold.  launch_reduce_partials then does dW[K,M] += sum of slabs, db[M] += sum of rows K.
 void launch_gemm_reduce(const float *A, int32_t lda, const float *row_scale, const float *G, int32_t ldg, int64_t n,
-                        int32_t K, int32_t M, float *partial, float *dW, float *db, hipStream_t s);
+                        int32_t K, int32_t M, float *partial, int accumulate, hipStream_t s);
+void launch_reduce_partials(const float *partial, int64_t n, int32_t K, int32_t M, float *dW, float *db, hipStream_t s);
 void launch_rnn_backward_elem(int lstm, int64_t n, int32_t H, const float *dh, const float *dc, const float *saved,
                               const float *h_prev, const float *c_prev, const float *c_new, float *dgi, float *dgh,
                               float *dh_carry, float *dc_prev, hipStream_t s);

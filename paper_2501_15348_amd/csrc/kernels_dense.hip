@@ -664,6 +664,8 @@ struct ReduceArgs {
     int K, M;
     int64_t rows_per_chunk;
     float *partial;  // [chunks, K+1, M]
+    int chunks;
+    int accumulate;  // add to the partial slabs instead of overwriting them (later timesteps of a window)
 };
 
 template <bool HAS_RS>
@@ -673,8 +675,19 @@ __global__ void __launch_bounds__(256) gemm_reduce_kernel(ReduceArgs g)
     __shared__ float bred[4][64];
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int i = lane & 31, kk = lane >> 5;
-    const int f0 = blockIdx.x * 64, c0 = blockIdx.y * 64;
-    const int64_t r_begin = int64_t(blockIdx.z) * g.rows_per_chunk;
+    // 1-D grid; consecutive block ids go round the 8 XCDs, so id % 8 picks the XCD.  All slabs of one row chunk
+    // are given to the same XCD (and to neighbouring ids), so that chunk's rows are fetched from HBM once and the
+    // other slabs find them in that XCD's L2.
+    const int slabs_x = (g.K + 63) / 64, slabs = slabs_x * ((g.M + 63) / 64);
+#ifdef REINC_REDUCE_SIMPLE_MAP
+    const int slab = blockIdx.x % slabs, chunk = blockIdx.x / slabs;
+#else
+    const int xcd = blockIdx.x % 8, qid = blockIdx.x / 8;
+    const int slab = qid % slabs, chunk = (qid / slabs) * 8 + xcd;
+#endif
+    if (chunk >= g.chunks) return;
+    const int f0 = (slab % slabs_x) * 64, c0 = (slab / slabs_x) * 64;
+    const int64_t r_begin = int64_t(chunk) * g.rows_per_chunk;
     const int64_t r_end = min(g.n, r_begin + g.rows_per_chunk);
     acc16 acc[2][2];
 #pragma unroll
@@ -770,19 +783,34 @@ __global__ void __launch_bounds__(256) gemm_reduce_kernel(ReduceArgs g)
     }
     __syncthreads();
     if (w != 0) return;
-    float *out = g.partial + int64_t(blockIdx.z) * (g.K + 1) * g.M;
+    float *out = g.partial + int64_t(chunk) * (g.K + 1) * g.M;
 #pragma unroll
     for (int a = 0; a < 2; ++a)
 #pragma unroll
-        for (int b = 0; b < 2; ++b)
+        for (int b = 0; b < 2; ++b) {
+            const int cc = 32 * b + i;
+            float old[16];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) old[r] = 0.0f;
+            if (g.accumulate) {  // all 16 reads of the tile go out together
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int fr = 32 * a + 8 * (r / 4) + 4 * kk + (r % 4);
+                    if (f0 + fr < g.K && c0 + cc < g.M) old[r] = out[int64_t(f0 + fr) * g.M + c0 + cc];
+                }
+            }
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const int fr = 32 * a + 8 * (r / 4) + 4 * kk + (r % 4), cc = 32 * b + i;
+                const int fr = 32 * a + 8 * (r / 4) + 4 * kk + (r % 4);
                 const float v = ((acc[a][b][r] + red[0][fr * 65 + cc]) + red[1][fr * 65 + cc]) + red[2][fr * 65 + cc];
-                if (f0 + fr < g.K && c0 + cc < g.M) out[int64_t(f0 + fr) * g.M + c0 + cc] = v;
+                if (f0 + fr < g.K && c0 + cc < g.M) out[int64_t(f0 + fr) * g.M + c0 + cc] = old[r] + v;
             }
-    if (blockIdx.x == 0 && c0 + lane < g.M)
-        out[int64_t(g.K) * g.M + c0 + lane] = ((bred[0][lane] + bred[1][lane]) + bred[2][lane]) + bred[3][lane];
+        }
+    if (f0 == 0 && c0 + lane < g.M) {
+        float *o = out + int64_t(g.K) * g.M + c0 + lane;
+        const float v = ((bred[0][lane] + bred[1][lane]) + bred[2][lane]) + bred[3][lane];
+        *o = g.accumulate ? *o + v : v;
+    }
 }
 
 // dst_w[K*M] += sum_c partial[c][0..K*M);  dst_b[M] += sum_c partial[c][K*M ..)
@@ -979,20 +1007,26 @@ uint64_t reduce_partial_bytes(int64_t n, int32_t K, int32_t M)
 }
 
 void launch_gemm_reduce(const float *A, int32_t lda, const float *row_scale, const float *G, int32_t ldg, int64_t n,
-                        int32_t K, int32_t M, float *partial, float *dW, float *db, hipStream_t s)
+                        int32_t K, int32_t M, float *partial, int accumulate, hipStream_t s)
 {
     if (n <= 0) return;
     const int chunks = reduce_chunks(n, K, M);
     int64_t rpc = (n + chunks - 1) / chunks;
     rpc = (rpc + 63) & ~int64_t(63);  // whole 64-row trips; no row pair straddles two chunks
-    ReduceArgs g{A, lda, row_scale, G, ldg, n, K, M, rpc, partial};
-    dim3 grid(unsigned((K + 63) / 64), unsigned((M + 63) / 64), unsigned(chunks));
+    ReduceArgs g{A, lda, row_scale, G, ldg, n, K, M, rpc, partial, chunks, accumulate};
+    const int slabs = ((K + 63) / 64) * ((M + 63) / 64);
+    const unsigned blocks = unsigned(slabs) * unsigned((chunks + 7) / 8) * 8u;
     if (row_scale)
-        gemm_reduce_kernel<true><<<grid, 256, 0, s>>>(g);
+        gemm_reduce_kernel<true><<<blocks, 256, 0, s>>>(g);
     else
-        gemm_reduce_kernel<false><<<grid, 256, 0, s>>>(g);
+        gemm_reduce_kernel<false><<<blocks, 256, 0, s>>>(g);
+}
+
+void launch_reduce_partials(const float *partial, int64_t n, int32_t K, int32_t M, float *dW, float *db, hipStream_t s)
+{
+    if (n <= 0) return;
     const int total = (K + 1) * M;
-    reduce_partials_kernel<<<(total + 63) / 64, 256, 0, s>>>(partial, chunks, K, M, dW, db);
+    reduce_partials_kernel<<<(total + 63) / 64, 256, 0, s>>>(partial, reduce_chunks(n, K, M), K, M, dW, db);
 }
 
 void launch_rnn_backward_elem(int lstm, int64_t n, int32_t H, const float *dh, const float *dc, const float *saved,

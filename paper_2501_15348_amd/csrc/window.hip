@@ -278,8 +278,6 @@ int reinc_backward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *pa
     const int KH = (lstm ? 4 : 3) * H;
     int maxd = H;
     for (int l = 0; l <= Lg; ++l) maxd = std::max(maxd, c.dims[l]);
-    uint64_t pbytes = std::max(reduce_partial_bytes(n, c.dims[Lg], KH), reduce_partial_bytes(n, H, KH));
-    for (int l = 1; l <= Lg; ++l) pbytes = std::max(pbytes, reduce_partial_bytes(n, c.dims[l - 1], c.dims[l]));
 
     ctx->scratch_reset();
     auto f32 = [&](uint64_t count) { return static_cast<float *>(ctx->scratch(count * 4)); };
@@ -288,8 +286,16 @@ int reinc_backward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *pa
     float *dgi = f32(uint64_t(n) * KH);
     float *dgh = lstm ? dgi : f32(uint64_t(n) * KH);
     float *dz = f32(uint64_t(n) * maxd), *dz2 = f32(uint64_t(n) * maxd), *dagg = f32(uint64_t(n) * maxd);
-    float *partial = static_cast<float *>(ctx->scratch(pbytes));
-    if (!dh || !dh2 || (lstm && (!dc || !dc2)) || !dgi || !dgh || !dz || !dz2 || !dagg || !partial) {
+    // one set of partial slabs per weight matrix: they collect all timesteps and are reduced once at the end
+    float *part_wi = static_cast<float *>(ctx->scratch(reduce_partial_bytes(n, c.dims[Lg], KH)));
+    float *part_wh = static_cast<float *>(ctx->scratch(reduce_partial_bytes(n, H, KH)));
+    float *part_w[REINC_MAX_GCN_LAYERS + 1] = {};
+    bool part_ok = part_wi && part_wh;
+    for (int l = 1; l <= Lg; ++l) {
+        part_w[l] = static_cast<float *>(ctx->scratch(reduce_partial_bytes(n, c.dims[l - 1], c.dims[l])));
+        part_ok = part_ok && part_w[l];
+    }
+    if (!dh || !dh2 || (lstm && (!dc || !dc2)) || !dgi || !dgh || !dz || !dz2 || !dagg || !part_ok) {
         ctx->scratch_reset();
         return ctx->fail(REINC_E_NOMEM, "arena exhausted: no room for the backward scratch buffers");
     }
@@ -306,10 +312,9 @@ int reinc_backward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *pa
                                  dh2, dc2, s);
         const float *x = st.H[Lg];
         const int dl = c.dims[Lg];
-        PROF_REDUCE(x, dl, nullptr, dgi, KH, n, dl, KH, partial, const_cast<float *>(gp.W_i),
-                           const_cast<float *>(gp.b_i), s);
-        PROF_REDUCE(pv ? pv->h : ctx->zero_state, H, nullptr, dgh, KH, n, H, KH, partial, const_cast<float *>(gp.W_h),
-                           const_cast<float *>(gp.b_h), s);
+        const int later = i != L - 1;
+        PROF_REDUCE(x, dl, nullptr, dgi, KH, n, dl, KH, part_wi, later, s);
+        PROF_REDUCE(pv ? pv->h : ctx->zero_state, H, nullptr, dgh, KH, n, H, KH, part_wh, later, s);
         // gradient w.r.t. the last GCN layer's pre-activation
         PROF_GEMM(dgi, 0, n, KH, dl, nullptr, p.W_i, 1, KH, nullptr, 0, nullptr, x, dz, s);
         if (i > 0) {  // gradient w.r.t. h_{t-1}
@@ -322,8 +327,7 @@ int reinc_backward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *pa
         }
         for (int l = Lg; l >= 1; --l) {
             const float *S = l == 1 ? ctx->gcache[t] : st.S[l];
-            PROF_REDUCE(S, c.dims[l - 1], sn.q, dz, c.dims[l], n, c.dims[l - 1], c.dims[l], partial,
-                               const_cast<float *>(gp.W[l]), const_cast<float *>(gp.b[l]), s);
+            PROF_REDUCE(S, c.dims[l - 1], sn.q, dz, c.dims[l], n, c.dims[l - 1], c.dims[l], part_w[l], later, s);
             if (l > 1) {
                 PROF_GEMM(dz, 0, n, c.dims[l], c.dims[l - 1], nullptr, p.W[l], 1, c.dims[l], nullptr, 0, nullptr,
                                  nullptr, dagg, s);
@@ -333,6 +337,11 @@ int reinc_backward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *pa
             }
         }
     }
+    launch_reduce_partials(part_wi, n, c.dims[Lg], KH, const_cast<float *>(gp.W_i), const_cast<float *>(gp.b_i), s);
+    launch_reduce_partials(part_wh, n, H, KH, const_cast<float *>(gp.W_h), const_cast<float *>(gp.b_h), s);
+    for (int l = 1; l <= Lg; ++l)
+        launch_reduce_partials(part_w[l], n, c.dims[l - 1], c.dims[l], const_cast<float *>(gp.W[l]),
+                               const_cast<float *>(gp.b[l]), s);
     REINC_HIP(ctx, hipGetLastError());
     return REINC_OK;
 }
