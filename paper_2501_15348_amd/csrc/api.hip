@@ -88,8 +88,12 @@ int reinc_create(reinc_ctx **out, const reinc_config *cfg)
 
 int reinc_destroy(reinc_ctx *ctx)
 {
-    if (ctx)
+    if (ctx) {
         for (hipEvent_t e : ctx->prof_events) (void)hipEventDestroy(e);
+        for (hipEvent_t e : ctx->order_events) (void)hipEventDestroy(e);
+        for (hipStream_t st : ctx->side)
+            if (st) (void)hipStreamDestroy(st);
+    }
     delete ctx;
     return REINC_OK;
 }

@@ -98,6 +98,10 @@ struct reinc_ctx {
             derived_mark = bottom;
         }
     }
+    // side streams of the window driver (default priority, created on first use) and a ring of ordering events
+    hipStream_t side[3] = {nullptr, nullptr, nullptr};
+    std::vector<hipEvent_t> order_events;
+    size_t order_next = 0;
     // kernel timing (reinc_profile_begin / _end)
     uint32_t prof_mask = 0;
     std::vector<hipEvent_t> prof_events;  // pool, two per recorded launch

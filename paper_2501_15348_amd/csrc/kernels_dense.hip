@@ -19,6 +19,10 @@ namespace {
 
 typedef float acc16 __attribute__((ext_vector_type(16)));
 
+#ifndef REINC_GEMM64_NT
+#define REINC_GEMM64_NT 1  // accumulator tiles per wave for outputs of 33..64 columns (1: two waves share a row tile)
+#endif
+
 constexpr int kBK = 32;  // k values staged per LDS chunk
 
 __device__ inline float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
@@ -222,23 +226,27 @@ struct NoPrefetch {
 // stream; a ring of three register buffers keeps the loads two chunks (8 KB per wave) ahead of the matrix
 // cores, across tile boundaries and epilogues.  Needs K % 32 == 0 and 16-byte aligned rows; the row scale is
 // applied to the finished sums.
-template <int NT, bool BF16>
-__global__ void __launch_bounds__(256, NT <= 2 ? 3 : 2) gemm_rows_resident_kernel(GemmArgs g)
+template <int NT, int WN, bool BF16>
+__global__ void __launch_bounds__(256, NT == 1 ? 4 : (NT == 2 ? 3 : 2)) gemm_rows_resident_kernel(GemmArgs g)
 {
+    // 4 waves = (4 / WN) row tiles x WN column groups of 32*NT columns; the slab holds all 32*NT*WN columns
     extern __shared__ float Bs[];
-    constexpr int BN = 32 * NT;
+    constexpr int BN = 32 * NT * WN;
+    constexpr int WR = 4 / WN;
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int wn = w % WN, wr = w / WN;
     const int i = lane & 31, kk = lane >> 5;
     const int col0 = blockIdx.y * BN;
     for (int k0 = 0; k0 < g.K; k0 += kBK)
         stage_b(Bs + k0 * BN, BN, BN, g.W, g.ldw, g.wT != 0, k0, g.K, [&](int c) { return col0 + c < g.M ? col0 + c : -1; });
     __syncthreads();
     const int64_t ntiles = (g.n + 31) / 32;
-    const int64_t first = int64_t(blockIdx.x) * 4 + w, stride = int64_t(gridDim.x) * 4;
+    const int64_t first = int64_t(blockIdx.x) * WR + wr, stride = int64_t(gridDim.x) * WR;
     if (first >= ntiles) return;
     const int kch = g.K / kBK;
     const int64_t total = ((ntiles - first + stride - 1) / stride) * kch;
-    const float *bp0 = Bs + (16 * kk) * BN + i;
+    const float *bp0 = Bs + (16 * kk) * BN + wn * 32 * NT + i;
+    const int wcol0 = col0 + wn * 32 * NT;
 
     // load cursor
     int64_t ltile = first, issued = 0;
@@ -276,7 +284,7 @@ __global__ void __launch_bounds__(256, NT <= 2 ? 3 : 2) gemm_rows_resident_kerne
         }
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
-            const int c = col0 + 32 * t + i;
+            const int c = wcol0 + 32 * t + i;
             if (c < g.M) {
                 const float bias = g.bias ? g.bias[c] : 0.0f;
                 float v[16];
@@ -336,21 +344,23 @@ int resident_blocks(const void *kernel, int threads, size_t lds)
     return blocks;
 }
 
-template <int NT>
+template <int NT, int WN>
 bool gemm_rows_resident_launch(const GemmArgs &g, int bf16, hipStream_t s)
 {
     if (g.K % kBK != 0 || g.lda % 8 != 0) return false;
-    const size_t lds = size_t(g.K) * 32 * NT * sizeof(float);
+    constexpr int BN = 32 * NT * WN;
+    const size_t lds = size_t(g.K) * BN * sizeof(float);
     if (lds > kLdsBytes - 1024) return false;
-    auto k = bf16 ? gemm_rows_resident_kernel<NT, true> : gemm_rows_resident_kernel<NT, false>;
+    auto k = bf16 ? gemm_rows_resident_kernel<NT, WN, true> : gemm_rows_resident_kernel<NT, WN, false>;
     if (lds > 48 * 1024 &&
         hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, int(lds)) != hipSuccess)
         return false;
     const int per_cu = resident_blocks(reinterpret_cast<const void *>(k), 256, lds);
     if (per_cu <= 0) return false;
     const int64_t ntiles = (g.n + 31) / 32;
-    const unsigned gy = unsigned((g.M + 32 * NT - 1) / (32 * NT));
-    dim3 grid(unsigned(std::min<int64_t>((ntiles + 3) / 4, std::max<int64_t>(1, int64_t(kNumCU) * per_cu / gy))), gy);
+    const int wr = 4 / WN;
+    const unsigned gy = unsigned((g.M + BN - 1) / BN);
+    dim3 grid(unsigned(std::min<int64_t>((ntiles + wr - 1) / wr, std::max<int64_t>(1, int64_t(kNumCU) * per_cu / gy))), gy);
     k<<<grid, 256, lds, s>>>(g);
     return true;
 }
@@ -953,9 +963,9 @@ int launch_gemm_rows(const void *A, int a_bf16, int64_t n, int32_t K, int32_t M,
     if (n <= 0) return 0;
     GemmArgs g{A, n, K, M, K, row_scale, W, ldw, w_transposed, bias, relu, mask, add, out};
     // preferred: weight slab resident in LDS, as wide as fits
-    if (M > 64 && gemm_rows_resident_launch<4>(g, a_bf16, s)) return 0;
-    if (M > 32 && gemm_rows_resident_launch<2>(g, a_bf16, s)) return 0;
-    if (gemm_rows_resident_launch<1>(g, a_bf16, s)) return 0;
+    if (M > 64 && gemm_rows_resident_launch<4, 1>(g, a_bf16, s)) return 0;
+    if (M > 32 && gemm_rows_resident_launch<REINC_GEMM64_NT, 2 / REINC_GEMM64_NT>(g, a_bf16, s)) return 0;
+    if (gemm_rows_resident_launch<1, 1>(g, a_bf16, s)) return 0;
     // very deep products: stage the weights 32 k values at a time
     if (M <= 32)
         gemm_rows_launch<1, 4, 1>(g, a_bf16, s);

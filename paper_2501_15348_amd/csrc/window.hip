@@ -11,27 +11,52 @@ namespace {
 
 hipStream_t as_stream(void *s) { return static_cast<hipStream_t>(s); }
 
-// launch wrappers that time the kernel class when profiling is on; `ctx` and the stream are in scope at every use
-#define PROF_GEMM(...)                                        \
-    do {                                                      \
-        ProfScope prof_(ctx, REINC_K_GEMM_ROWS, prof_stream); \
-        launch_gemm_rows(__VA_ARGS__);                        \
-    } while (0)
-#define PROF_RNN(...)                                   \
-    do {                                                \
-        ProfScope prof_(ctx, REINC_K_RNN, prof_stream); \
-        launch_rnn_fused(__VA_ARGS__);                  \
-    } while (0)
-#define PROF_REDUCE(...)                                   \
-    do {                                                   \
-        ProfScope prof_(ctx, REINC_K_REDUCE, prof_stream); \
-        launch_gemm_reduce(__VA_ARGS__);                   \
-    } while (0)
-#define PROF_ELEM(...)                                   \
-    do {                                                 \
-        ProfScope prof_(ctx, REINC_K_ELEM, prof_stream); \
-        launch_rnn_backward_elem(__VA_ARGS__);           \
-    } while (0)
+// launch wrappers that time the kernel class when profiling is on
+template <class... A>
+void gemm_rows(reinc_ctx *ctx, hipStream_t st, A... a)
+{
+    ProfScope prof(ctx, REINC_K_GEMM_ROWS, st);
+    launch_gemm_rows(a..., st);
+}
+template <class... A>
+void rnn_fused(reinc_ctx *ctx, hipStream_t st, A... a)
+{
+    ProfScope prof(ctx, REINC_K_RNN, st);
+    launch_rnn_fused(a..., st);
+}
+template <class... A>
+void gemm_reduce(reinc_ctx *ctx, hipStream_t st, A... a)
+{
+    ProfScope prof(ctx, REINC_K_REDUCE, st);
+    launch_gemm_reduce(a..., st);
+}
+template <class... A>
+void rnn_backward_elem(reinc_ctx *ctx, hipStream_t st, A... a)
+{
+    ProfScope prof(ctx, REINC_K_ELEM, st);
+    launch_rnn_backward_elem(a..., st);
+}
+
+// The window driver spreads independent kernels over up to three side streams (all at the default priority)
+// and orders them with events: `to` waits for everything enqueued on `from` so far.
+int ensure_side_streams(reinc_ctx *ctx)
+{
+    for (hipStream_t &st : ctx->side)
+        if (!st) REINC_HIP(ctx, hipStreamCreateWithFlags(&st, hipStreamNonBlocking));
+    if (ctx->order_events.empty()) {
+        ctx->order_events.resize(512);
+        for (hipEvent_t &e : ctx->order_events) REINC_HIP(ctx, hipEventCreateWithFlags(&e, hipEventDisableTiming));
+    }
+    return REINC_OK;
+}
+
+int order_after(reinc_ctx *ctx, hipStream_t from, hipStream_t to)
+{
+    hipEvent_t e = ctx->order_events[ctx->order_next++ % ctx->order_events.size()];
+    REINC_HIP(ctx, hipEventRecord(e, from));
+    REINC_HIP(ctx, hipStreamWaitEvent(to, e, 0));
+    return REINC_OK;
+}
 
 struct Params {
     const float *W[REINC_MAX_GCN_LAYERS + 1] = {};
@@ -187,9 +212,8 @@ int reinc_gcn_transform(reinc_ctx *ctx, const void *A, int a_dtype, int64_t n, i
     if (n < 0 || d_in <= 0 || d_out <= 0) return ctx->fail(REINC_E_ARG, "bad shape");
     if (a_dtype != REINC_F32 && a_dtype != REINC_BF16) return ctx->fail(REINC_E_ARG, "bad a_dtype");
     if (A == out) return ctx->fail(REINC_E_ARG, "output may not alias the input");
-    hipStream_t prof_stream = as_stream(stream);
-    PROF_GEMM(A, a_dtype == REINC_BF16, n, d_in, d_out, row_scale, W, 0, d_out, b, relu, nullptr, nullptr, out,
-                     as_stream(stream));
+    gemm_rows(ctx, as_stream(stream), A, int(a_dtype == REINC_BF16), n, d_in, d_out, row_scale, W, 0, d_out, b, relu,
+              (const float *)nullptr, (const float *)nullptr, out);
     REINC_HIP(ctx, hipGetLastError());
     return REINC_OK;
 }
@@ -204,9 +228,8 @@ int reinc_rnn_step(reinc_ctx *ctx, int rnn_kind, const float *x, int64_t n, int3
     if (rnn_kind == REINC_RNN_LSTM && !c_out) return ctx->fail(REINC_E_ARG, "an LSTM step needs c_out");
     if (n < 0 || d_in <= 0 || H <= 0) return ctx->fail(REINC_E_ARG, "bad shape");
     if (h_out == h_prev || (c_out && c_out == c_prev)) return ctx->fail(REINC_E_ARG, "state outputs may not alias the previous state");
-    hipStream_t prof_stream = as_stream(stream);
-    PROF_RNN(rnn_kind == REINC_RNN_LSTM, x, n, d_in, H, h_prev, c_prev, W_i, W_h, b_i, b_h, h_out, c_out, saved,
-                     as_stream(stream));
+    rnn_fused(ctx, as_stream(stream), int(rnn_kind == REINC_RNN_LSTM), x, n, d_in, H, h_prev, c_prev, W_i, W_h, b_i, b_h,
+              h_out, c_out, saved);
     REINC_HIP(ctx, hipGetLastError());
     return REINC_OK;
 }
@@ -223,31 +246,37 @@ int reinc_forward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *par
         if (!agg_width_supported(c.dims[l], 0))
             return ctx->fail(REINC_E_UNSUPPORTED, "layer width %d: row bytes must be a power of two in [16, 1024]", c.dims[l]);
     hipStream_t s = as_stream(stream);
-    hipStream_t prof_stream = s;
     REINC_HIP(ctx, hipSetDevice(c.device));
     ctx->local_valid = false;
+    REINC_TRY(ensure_side_streams(ctx));
     REINC_TRY(ensure_local(ctx, L, s));
     ctx->scratch_reset();
     const Params p = split_params(c, params);
     const int64_t n = c.num_nodes;
     const int Lg = c.num_gcn_layers, H = c.rnn_hidden;
     const int lstm = c.rnn_kind == REINC_RNN_LSTM;
+    const float *nof = nullptr;
+    // The GCN part of a timestep does not depend on the recurrent state, so it runs ahead on a side stream while
+    // the caller's stream steps the recurrent cell: the cell of snapshot t overlaps the GCN layers of t+1.
+    hipStream_t g = ctx->side[0];
+    REINC_TRY(order_after(ctx, s, g));
     for (int32_t i = 0; i < L; ++i) {
         const int32_t t = t0 + i;
-        REINC_TRY(ensure_layer1(ctx, t, s));
+        REINC_TRY(ensure_layer1(ctx, t, g));
         const Snapshot &sn = ctx->snaps[t];
         LocalStep &st = ctx->local[i];
-        PROF_GEMM(ctx->gcache[t], 0, n, c.dims[0], c.dims[1], sn.q, p.W[1], 0, c.dims[1], p.b[1], 1, nullptr, nullptr,
-                         st.H[1], s);
+        gemm_rows(ctx, g, (const void *)ctx->gcache[t], 0, n, c.dims[0], c.dims[1], (const float *)sn.q, p.W[1], 0, c.dims[1],
+                  p.b[1], 1, nof, nof, st.H[1]);
         for (int l = 2; l <= Lg; ++l) {
             aggregate_full(ctx, sn.row_ptr, sn.col, sn.long_rows, sn.n_long_rows, st.H[l - 1], 0, c.dims[l - 1], c.self_loop,
-                           sn.p, nullptr, nullptr, st.S[l], s);
-            PROF_GEMM(st.S[l], 0, n, c.dims[l - 1], c.dims[l], sn.q, p.W[l], 0, c.dims[l], p.b[l], 1, nullptr, nullptr,
-                             st.H[l], s);
+                           sn.p, nullptr, nullptr, st.S[l], g);
+            gemm_rows(ctx, g, (const void *)st.S[l], 0, n, c.dims[l - 1], c.dims[l], (const float *)sn.q, p.W[l], 0,
+                      c.dims[l], p.b[l], 1, nof, nof, st.H[l]);
         }
+        REINC_TRY(order_after(ctx, g, s));
         const LocalStep *pv = i ? &ctx->local[i - 1] : nullptr;
-        PROF_RNN(lstm, st.H[Lg], n, c.dims[Lg], H, pv ? pv->h : nullptr, pv ? pv->c : nullptr, p.W_i, p.W_h, p.b_i,
-                         p.b_h, st.h, st.c, st.saved, s);
+        rnn_fused(ctx, s, lstm, (const float *)st.H[Lg], n, c.dims[Lg], H, pv ? (const float *)pv->h : nof,
+                  pv ? (const float *)pv->c : nof, p.W_i, p.W_h, p.b_i, p.b_h, st.h, st.c, st.saved);
     }
     const LocalStep &last = ctx->local[L - 1];
     if (target) launch_mse(last.h, target, n * H, ctx->loss_partial, loss_out, s);
@@ -268,8 +297,8 @@ int reinc_backward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *pa
         return ctx->fail(REINC_E_STATE, "backward needs the forward pass of the same window [%d, %d) first", t0, t0 + L);
     const reinc_config &c = ctx->cfg;
     hipStream_t s = as_stream(stream);
-    hipStream_t prof_stream = s;
     REINC_HIP(ctx, hipSetDevice(c.device));
+    REINC_TRY(ensure_side_streams(ctx));
     const Params p = split_params(c, params);
     Params gp = split_params(c, grads);
     const int64_t n = c.num_nodes;
@@ -303,39 +332,60 @@ int reinc_backward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *pa
     launch_fill_f32(g, p.count, 0.0f, s);
     launch_mse_grad(ctx->local[L - 1].h, target, n * H, dh, s);
     const float *dc_in = nullptr;  // zero at the last step
+    const float *nof = nullptr;
+    // Per timestep, after the elementwise gate gradients: the caller's stream carries the recurrent chain
+    // (gradient w.r.t. h_{t-1}); side 0 and side 1 take the weight-gradient reductions (each weight always on the
+    // same stream, so its partial slabs are updated in timestep order); side 2 takes the GCN backward chain.
+    hipStream_t s0 = ctx->side[0], s1 = ctx->side[1], s2 = ctx->side[2];
     for (int32_t i = L - 1; i >= 0; --i) {
         const int32_t t = t0 + i;
         const Snapshot &sn = ctx->snaps[t];
         const LocalStep &st = ctx->local[i];
         const LocalStep *pv = i ? &ctx->local[i - 1] : nullptr;
-        PROF_ELEM(lstm, n, H, dh, dc_in, st.saved, pv ? pv->h : nullptr, pv ? pv->c : nullptr, st.c, dgi, dgh,
-                                 dh2, dc2, s);
+        rnn_backward_elem(ctx, s, lstm, n, H, (const float *)dh, dc_in, (const float *)st.saved,
+                          pv ? (const float *)pv->h : nof, pv ? (const float *)pv->c : nof, (const float *)st.c, dgi, dgh, dh2,
+                          dc2);
+        REINC_TRY(order_after(ctx, s, s0));
+        REINC_TRY(order_after(ctx, s, s1));
+        REINC_TRY(order_after(ctx, s, s2));
         const float *x = st.H[Lg];
         const int dl = c.dims[Lg];
         const int later = i != L - 1;
-        PROF_REDUCE(x, dl, nullptr, dgi, KH, n, dl, KH, part_wi, later, s);
-        PROF_REDUCE(pv ? pv->h : ctx->zero_state, H, nullptr, dgh, KH, n, H, KH, part_wh, later, s);
+        gemm_reduce(ctx, s0, x, dl, nof, (const float *)dgi, KH, n, dl, KH, part_wi, later);
+        gemm_reduce(ctx, s1, pv ? (const float *)pv->h : (const float *)ctx->zero_state, H, nof, (const float *)dgh, KH, n, H, KH,
+                    part_wh, later);
         // gradient w.r.t. the last GCN layer's pre-activation
-        PROF_GEMM(dgi, 0, n, KH, dl, nullptr, p.W_i, 1, KH, nullptr, 0, nullptr, x, dz, s);
+        gemm_rows(ctx, s2, (const void *)dgi, 0, n, KH, dl, nof, p.W_i, 1, KH, nof, 0, nof, x, dz);
         if (i > 0) {  // gradient w.r.t. h_{t-1}
-            PROF_GEMM(dgh, 0, n, KH, H, nullptr, p.W_h, 1, KH, nullptr, 0, lstm ? nullptr : dh2, nullptr, dh, s);
+            gemm_rows(ctx, s, (const void *)dgh, 0, n, KH, H, nof, p.W_h, 1, KH, nof, 0, lstm ? nof : (const float *)dh2, nof,
+                      dh);
             if (lstm) {
                 std::swap(dc, dc2);  // dc now holds the gradient w.r.t. c_{t-1}
                 dc_in = dc;
                 // dc2 is free again; rnn_backward_elem writes the next dc_prev there
             }
         }
+        hipStream_t reader_dz2 = nullptr;  // side stream that may still read the buffer behind dz2
         for (int l = Lg; l >= 1; --l) {
             const float *S = l == 1 ? ctx->gcache[t] : st.S[l];
-            PROF_REDUCE(S, c.dims[l - 1], sn.q, dz, c.dims[l], n, c.dims[l - 1], c.dims[l], part_w[l], later, s);
+            hipStream_t sr = (l & 1) ? s1 : s0;  // the reduction of layer l always runs on the same side stream
+            REINC_TRY(order_after(ctx, s2, sr));
+            gemm_reduce(ctx, sr, S, c.dims[l - 1], (const float *)sn.q, (const float *)dz, c.dims[l], n, c.dims[l - 1],
+                        c.dims[l], part_w[l], later);
             if (l > 1) {
-                PROF_GEMM(dz, 0, n, c.dims[l], c.dims[l - 1], nullptr, p.W[l], 1, c.dims[l], nullptr, 0, nullptr,
-                                 nullptr, dagg, s);
+                gemm_rows(ctx, s2, (const void *)dz, 0, n, c.dims[l], c.dims[l - 1], nof, p.W[l], 1, c.dims[l], nof, 0, nof,
+                          nof, dagg);
+                if (reader_dz2) REINC_TRY(order_after(ctx, reader_dz2, s2));
                 aggregate_full(ctx, sn.col_ptr, sn.row, sn.long_cols, sn.n_long_cols, dagg, 0, c.dims[l - 1], c.self_loop, sn.q,
-                               sn.p, st.H[l - 1], dz2, s);
+                               sn.p, st.H[l - 1], dz2, s2);
                 std::swap(dz, dz2);
+                reader_dz2 = sr;  // this layer's reduction reads what is now dz2
             }
         }
+        // the next timestep overwrites the gate gradients and the layer scratch: everything joins first
+        REINC_TRY(order_after(ctx, s0, s));
+        REINC_TRY(order_after(ctx, s1, s));
+        REINC_TRY(order_after(ctx, s2, s));
     }
     launch_reduce_partials(part_wi, n, c.dims[Lg], KH, const_cast<float *>(gp.W_i), const_cast<float *>(gp.b_i), s);
     launch_reduce_partials(part_wh, n, H, KH, const_cast<float *>(gp.W_h), const_cast<float *>(gp.b_h), s);

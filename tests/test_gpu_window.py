@@ -44,6 +44,7 @@ CASES = [
     ("c2", 3001, 6, {}),
     ("c3", 2003, 5, dict(dims=(128, 128, 128))),
     ("c5_10", 2500, 4, {}),
+    ("c3", 1201, 4, dict(dims=(32, 64, 32, 16), hidden=32, agg="sym")),  # three GCN layers, LSTM
 ]
 
 
