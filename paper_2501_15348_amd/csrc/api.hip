@@ -1,6 +1,7 @@
 // C-ABI entry points: context, snapshot store, delta builder, aggregation primitives.
 #include <algorithm>
 #include <cmath>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 
@@ -83,6 +84,9 @@ int reinc_create(reinc_ctx **out, const reinc_config *cfg)
     ctx->snaps.resize(c.num_snapshots);
     ctx->deltas.resize(c.num_snapshots);
     ctx->gcache.assign(c.num_snapshots, nullptr);
+    // measured on MI355X: overlapping the independent kernels of a timestep on side streams gains nothing (every
+    // kernel already fills the register file), so the default keeps all work on the caller's stream
+    if (const char *e = std::getenv("REINC_OVERLAP")) ctx->overlap = e[0] == '1';
     return REINC_OK;
 }
 

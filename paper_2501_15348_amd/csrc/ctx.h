@@ -100,6 +100,7 @@ struct reinc_ctx {
     }
     // side streams of the window driver (default priority, created on first use) and a ring of ordering events
     hipStream_t side[3] = {nullptr, nullptr, nullptr};
+    bool overlap = false;  // true (REINC_OVERLAP=1): the window driver spreads independent kernels over the side streams
     std::vector<hipEvent_t> order_events;
     size_t order_next = 0;
     // kernel timing (reinc_profile_begin / _end)

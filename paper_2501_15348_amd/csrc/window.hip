@@ -52,6 +52,7 @@ int ensure_side_streams(reinc_ctx *ctx)
 
 int order_after(reinc_ctx *ctx, hipStream_t from, hipStream_t to)
 {
+    if (from == to) return REINC_OK;
     hipEvent_t e = ctx->order_events[ctx->order_next++ % ctx->order_events.size()];
     REINC_HIP(ctx, hipEventRecord(e, from));
     REINC_HIP(ctx, hipStreamWaitEvent(to, e, 0));
@@ -256,9 +257,10 @@ int reinc_forward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *par
     const int Lg = c.num_gcn_layers, H = c.rnn_hidden;
     const int lstm = c.rnn_kind == REINC_RNN_LSTM;
     const float *nof = nullptr;
-    // The GCN part of a timestep does not depend on the recurrent state, so it runs ahead on a side stream while
-    // the caller's stream steps the recurrent cell: the cell of snapshot t overlaps the GCN layers of t+1.
-    hipStream_t g = ctx->side[0];
+    // The GCN part of a timestep does not depend on the recurrent state; with overlap enabled it runs ahead on a
+    // side stream while the caller's stream steps the recurrent cell (the cell of snapshot t beside the GCN layers
+    // of t+1).  By default both share the caller's stream.
+    hipStream_t g = ctx->overlap ? ctx->side[0] : s;
     REINC_TRY(order_after(ctx, s, g));
     for (int32_t i = 0; i < L; ++i) {
         const int32_t t = t0 + i;
@@ -333,10 +335,10 @@ int reinc_backward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *pa
     launch_mse_grad(ctx->local[L - 1].h, target, n * H, dh, s);
     const float *dc_in = nullptr;  // zero at the last step
     const float *nof = nullptr;
-    // Per timestep, after the elementwise gate gradients: the caller's stream carries the recurrent chain
+    // With overlap enabled, per timestep, after the elementwise gate gradients: the caller's stream carries the recurrent chain
     // (gradient w.r.t. h_{t-1}); side 0 and side 1 take the weight-gradient reductions (each weight always on the
     // same stream, so its partial slabs are updated in timestep order); side 2 takes the GCN backward chain.
-    hipStream_t s0 = ctx->side[0], s1 = ctx->side[1], s2 = ctx->side[2];
+    hipStream_t s0 = ctx->overlap ? ctx->side[0] : s, s1 = ctx->overlap ? ctx->side[1] : s, s2 = ctx->overlap ? ctx->side[2] : s;
     for (int32_t i = L - 1; i >= 0; --i) {
         const int32_t t = t0 + i;
         const Snapshot &sn = ctx->snaps[t];

@@ -163,3 +163,25 @@ def test_window_errors():
         small.forward_window(0, 4, params, tgt, loss)
     assert e.value.code == reinc.E_NOMEM
     small.close()
+
+
+def test_overlap_on_side_streams_gives_the_same_answer(monkeypatch):
+    """REINC_OVERLAP=1 spreads independent kernels of a timestep over side streams; results must not change."""
+    import torch
+
+    wl = synth.WORKLOADS["c2"].scaled(2000, 5)
+    outs = []
+    for flag in ("0", "1"):
+        monkeypatch.setenv("REINC_OVERLAP", flag)
+        seq, ctx, flat, target = _setup(wl)
+        params, tgt = _dev(flat), _dev(target)
+        loss = torch.zeros(1, device="cuda")
+        h = torch.empty((wl.num_nodes, wl.hidden), device="cuda")
+        grads = torch.empty_like(params)
+        for t0 in (0, 1):
+            ctx.forward_window(t0, 4, params, tgt, loss, h)
+            ctx.backward_window(t0, 4, params, tgt, grads)
+        torch.cuda.synchronize()
+        outs.append((h.cpu().numpy(), grads.cpu().numpy(), loss.item()))
+        ctx.close()
+    assert np.array_equal(outs[0][0], outs[1][0]) and np.array_equal(outs[0][1], outs[1][1]) and outs[0][2] == outs[1][2]
