@@ -164,9 +164,9 @@ int reinc_aggregate_full(reinc_ctx *ctx, int32_t t, int transpose, const void *X
  *     S_t[r] = S_{t-1}[r] + sum_{inserted u} Y_{t-1}[u] - sum_{deleted u} Y_{t-1}[u] + sum_{changed u} dY[u]
  * and S_t[r] = S_{t-1}[r] elsewhere.  S_prev, S_out: device fp32 [N, dims[0]].  S_out may be S_prev itself
  * (in place: only rows in R_t are touched) or a disjoint buffer (all rows are written).  Needs
- * reinc_build_deltas(t).  agg_out (may be NULL): device fp32 [N, dims[0]]; its rows in R_t receive Q_t S_t and
- * its other rows are left alone, so a buffer that held Agg_{t-1} holds Agg_t afterwards (a row outside R_t
- * keeps both its sum and its degree). */
+ * reinc_build_deltas(t).  agg_out (may be NULL; in-place calls only): device fp32 [N, dims[0]]; its rows in R_t
+ * receive Q_t S_t and its other rows are left alone, so a buffer that held Agg_{t-1} holds Agg_t afterwards (a
+ * row outside R_t keeps both its sum and its degree). */
 int reinc_aggregate_incremental(reinc_ctx *ctx, int32_t t, const float *S_prev, float *S_out, float *agg_out,
                                 void *stream);
 

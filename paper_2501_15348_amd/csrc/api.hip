@@ -458,15 +458,18 @@ int reinc_aggregate_incremental(reinc_ctx *ctx, int32_t t, const float *S_prev, 
     const Snapshot &sn = ctx->snaps[t];
     const int32_t d = ctx->cfg.dims[0];
     const uint64_t bytes = uint64_t(ctx->N()) * d * 4;
-    if (S_out != S_prev) {
+    const bool in_place = S_out == S_prev;
+    if (!in_place) {
         const char *a = reinterpret_cast<const char *>(S_prev), *b = reinterpret_cast<const char *>(S_out);
         if (a < b + bytes && b < a + bytes) return ctx->fail(REINC_E_ARG, "S_out must be S_prev itself or disjoint from it");
-        REINC_HIP(ctx, hipMemcpyAsync(S_out, S_prev, bytes, hipMemcpyDeviceToDevice, as_stream(stream)));
+        if (agg_out) return ctx->fail(REINC_E_ARG, "agg_out is only updated in place: pass S_out == S_prev with it");
     }
     {
+        // in place: the rows of R_t; to a new buffer: one pass over every row (rows without entries are copied)
         ProfScope prof(ctx, REINC_K_AGG_INC, as_stream(stream));
-        launch_incremental(dl.rows, dl.info.n_rows, dl.long_rows, dl.n_long_rows, dl.ent_ptr, dl.ent, pv.x,
-                           ctx->cfg.feat_dtype == REINC_BF16, pv.p, dl.dY, d, S_out, S_out, sn.q, agg_out, as_stream(stream));
+        launch_incremental(in_place ? dl.rows : nullptr, in_place ? dl.info.n_rows : ctx->N(), dl.long_rows, dl.n_long_rows,
+                           dl.ent_ptr, dl.ent, pv.x, ctx->cfg.feat_dtype == REINC_BF16, pv.p, dl.dY, d, S_prev, S_out, sn.q,
+                           agg_out, as_stream(stream));
     }
     REINC_HIP(ctx, hipGetLastError());
     ctx->stats.delta_entries_processed += dl.info.n_entries;

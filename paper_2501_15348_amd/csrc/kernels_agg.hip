@@ -20,7 +20,8 @@ namespace reinc {
 namespace {
 
 constexpr int kWavesPerBlock = 4;
-constexpr int kUnroll = 4;
+constexpr int kUnroll = 8;        // source rows in flight per lane in the wave-per-row kernels
+constexpr int kUnrollGrouped = 8;  // in the group-per-row kernels (16 lowers occupancy and measured slower)
 
 template <bool BF16>
 struct Row;
@@ -214,11 +215,11 @@ aggregate_rows_grouped(const int64_t *__restrict__ ptr, const int32_t *__restric
             if (in_scale) my_sc = in_scale[my_u];
         }
         const int cmax = min(LPR, maxlen - base);
-        for (int k = 0; k < cmax; k += kUnroll) {
-            float r[kUnroll][VEC];
-            float sc[kUnroll];
+        for (int k = 0; k < cmax; k += kUnrollGrouped) {
+            float r[kUnrollGrouped][VEC];
+            float sc[kUnrollGrouped];
 #pragma unroll
-            for (int j = 0; j < kUnroll; ++j) {
+            for (int j = 0; j < kUnrollGrouped; ++j) {
                 const int e = k + j;
                 const int32_t u = __shfl(my_u, gbase + (e & (LPR - 1)));
                 if (e < cnt) {
@@ -229,13 +230,13 @@ aggregate_rows_grouped(const int64_t *__restrict__ ptr, const int32_t *__restric
                 }
             }
 #pragma unroll
-            for (int j = 0; j < kUnroll; ++j) {
+            for (int j = 0; j < kUnrollGrouped; ++j) {
                 const int e = k + j;
                 sc[j] = __shfl(my_sc, gbase + (e & (LPR - 1)));
                 if (e >= cnt) sc[j] = 0.0f;
             }
 #pragma unroll
-            for (int j = 0; j < kUnroll; ++j)
+            for (int j = 0; j < kUnrollGrouped; ++j)
 #pragma unroll
                 for (int i = 0; i < VEC; ++i) acc[i] += sc[j] * r[j][i];
         }
@@ -409,7 +410,7 @@ incremental_rows_grouped(const int32_t *__restrict__ rows, int64_t n_rows, const
     const bool live = w < n_rows;
     int64_t v = 0, beg = 0, end = 0;
     if (live) {
-        v = rows[w];
+        v = rows ? rows[w] : w;  // no row list: every row, so that rows without entries are copied through
         beg = ent_ptr[v];
         end = ent_ptr[v + 1];
     }
@@ -439,11 +440,11 @@ incremental_rows_grouped(const int32_t *__restrict__ rows, int64_t n_rows, const
             }
         }
         const int cmax = min(LPR, maxlen - base);
-        for (int k = 0; k < cmax; k += kUnroll) {
-            float r[kUnroll][VEC];
-            float sc[kUnroll];
+        for (int k = 0; k < cmax; k += kUnrollGrouped) {
+            float r[kUnrollGrouped][VEC];
+            float sc[kUnrollGrouped];
 #pragma unroll
-            for (int j = 0; j < kUnroll; ++j) {
+            for (int j = 0; j < kUnrollGrouped; ++j) {
                 const int e = k + j;
                 const uint32_t en = __shfl(my_e, gbase + (e & (LPR - 1)));
                 if (e < cnt) {
@@ -458,13 +459,13 @@ incremental_rows_grouped(const int32_t *__restrict__ rows, int64_t n_rows, const
                 }
             }
 #pragma unroll
-            for (int j = 0; j < kUnroll; ++j) {
+            for (int j = 0; j < kUnrollGrouped; ++j) {
                 const int e = k + j;
                 sc[j] = __shfl(my_sc, gbase + (e & (LPR - 1)));
                 if (e >= cnt) sc[j] = 0.0f;
             }
 #pragma unroll
-            for (int j = 0; j < kUnroll; ++j)
+            for (int j = 0; j < kUnrollGrouped; ++j)
 #pragma unroll
                 for (int i = 0; i < VEC; ++i) acc[i] += sc[j] * r[j][i];
         }

@@ -176,11 +176,11 @@ int ensure_layer1(reinc_ctx *ctx, int32_t t, hipStream_t s)
     if (incremental) {
         const Delta &dl = ctx->deltas[t];
         const Snapshot &pv = ctx->snaps[t - 1];
-        REINC_HIP(ctx, hipMemcpyAsync(slot, ctx->gcache[t - 1], bytes, hipMemcpyDeviceToDevice, s));
         {
+            // one pass over every row: changed rows get their delta, the others are copied into the new slot
             ProfScope prof(ctx, REINC_K_AGG_INC, s);
-            launch_incremental(dl.rows, dl.info.n_rows, dl.long_rows, dl.n_long_rows, dl.ent_ptr, dl.ent, pv.x, bf16, pv.p,
-                               dl.dY, d, slot, slot, nullptr, nullptr, s);
+            launch_incremental(nullptr, c.num_nodes, dl.long_rows, dl.n_long_rows, dl.ent_ptr, dl.ent, pv.x, bf16, pv.p, dl.dY,
+                               d, ctx->gcache[t - 1], slot, nullptr, nullptr, s);
         }
         ++ctx->stats.steps_incremental;
         ctx->stats.delta_entries_processed += dl.info.n_entries;
