@@ -2,6 +2,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 
 #include <cstdarg>
 #include <cstdint>
@@ -140,12 +141,15 @@ struct reinc_ctx {
 };
 
 namespace reinc {
-// Brackets the launches issued during its lifetime with an event pair when their kind is being profiled.
+// Times launches of a kernel class when that class is being profiled.  Default: an event pair recorded around
+// everything launched during the scope's lifetime.  With `attached`, nothing is recorded here; the caller hands
+// start() / stop() to hipExtLaunchKernelGGL, which stamps them with the kernel's own begin and end.
 struct ProfScope {
     reinc_ctx *ctx;
     hipStream_t s;
     int slot = -1;
-    ProfScope(reinc_ctx *c, int kind, hipStream_t st) : ctx(c), s(st) {
+    bool attached;
+    ProfScope(reinc_ctx *c, int kind, hipStream_t st, bool attach = false) : ctx(c), s(st), attached(attach) {
         if (!(c->prof_mask & (1u << kind)) || c->prof_kind.size() >= REINC_PROFILE_MAX_LAUNCHES) return;
         const size_t need = 2 * (c->prof_kind.size() + 1);
         while (c->prof_events.size() < need) {
@@ -155,11 +159,13 @@ struct ProfScope {
         }
         slot = int(c->prof_kind.size());
         c->prof_kind.push_back(kind);
-        (void)hipEventRecord(c->prof_events[2 * slot], s);
+        if (!attached) (void)hipEventRecord(c->prof_events[2 * slot], s);
     }
     ~ProfScope() {
-        if (slot >= 0) (void)hipEventRecord(ctx->prof_events[2 * slot + 1], s);
+        if (slot >= 0 && !attached) (void)hipEventRecord(ctx->prof_events[2 * slot + 1], s);
     }
+    hipEvent_t start() const { return slot >= 0 ? ctx->prof_events[2 * slot] : nullptr; }
+    hipEvent_t stop() const { return slot >= 0 ? ctx->prof_events[2 * slot + 1] : nullptr; }
     ProfScope(const ProfScope &) = delete;
     ProfScope &operator=(const ProfScope &) = delete;
 };
@@ -213,7 +219,7 @@ bool agg_width_supported(int32_t d, int bf16);
 // takes the listed long rows with one block each.
 void launch_aggregate(const int64_t *ptr, const int32_t *idx, int32_t n_long, const void *X, int bf16, int32_t d,
                       int64_t n, int self_loop, const float *in_scale, const float *out_scale, const float *mask,
-                      float *out, hipStream_t s);
+                      float *out, hipStream_t s, hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr);
 void launch_aggregate_long(const int64_t *ptr, const int32_t *idx, const int32_t *long_rows, int32_t n_long, const void *X,
                            int bf16, int32_t d, int self_loop, const float *in_scale, const float *out_scale,
                            const float *mask, float *out, hipStream_t s);
