@@ -122,60 +122,88 @@ int reinc_load_edges(reinc_ctx *ctx, int32_t t, const int32_t *src, const int32_
     if (sn.edges_loaded) return ctx->fail(REINC_E_STATE, "edges of snapshot %d already loaded", t);
     const int64_t n = ctx->N();
     REINC_HIP(ctx, hipSetDevice(ctx->cfg.device));
-    std::vector<uint64_t> keys;
-    keys.reserve(size_t(nnz));
-    for (int64_t i = 0; i < nnz; ++i) {
-        const int64_t u = src[i], v = dst[i];
-        if (u < 0 || u >= n || v < 0 || v >= n)
-            return ctx->fail(REINC_E_ARG, "edge %lld: (%lld -> %lld) outside [0, %lld)", (long long)i, (long long)u,
-                             (long long)v, (long long)n);
-        if (u != v) keys.push_back((uint64_t(v) << 32) | uint64_t(u));
+    hipStream_t s = nullptr;
+    // the raw list goes to scratch; everything else happens on the device
+    ctx->scratch_reset();
+    const uint64_t mark = ctx->bottom;
+    auto fail_nomem = [&](const char *what) {
+        ctx->bottom = mark;
+        ctx->scratch_reset();
+        return ctx->fail(REINC_E_NOMEM, "arena exhausted while canonicalising snapshot %d: %s", t, what);
+    };
+    const int64_t m = std::max<int64_t>(nnz, 1);
+    int32_t *d_src = static_cast<int32_t *>(ctx->scratch(uint64_t(m) * 4));
+    int32_t *d_dst = static_cast<int32_t *>(ctx->scratch(uint64_t(m) * 4));
+    uint64_t *keys0 = static_cast<uint64_t *>(ctx->scratch(uint64_t(m) * 8));
+    uint64_t *keys1 = static_cast<uint64_t *>(ctx->scratch(uint64_t(m) * 8));
+    int32_t *flag = static_cast<int32_t *>(ctx->scratch(uint64_t(std::max(m, n)) * 4));
+    int64_t *offs = static_cast<int64_t *>(ctx->scratch(uint64_t(std::max(m, n) + 1) * 8));
+    int32_t *err = static_cast<int32_t *>(ctx->scratch(256));
+    const size_t sort_bytes = sort_keys_tmp_bytes(m);
+    void *sort_tmp = ctx->scratch(sort_bytes);
+    void *scan_tmp = ctx->scratch(scan_tmp_bytes(std::max(m, n)));
+    if (!d_src || !d_dst || !keys0 || !keys1 || !flag || !offs || !err || !sort_tmp || !scan_tmp) return fail_nomem("scratch");
+    if (nnz > 0) {
+        REINC_HIP(ctx, hipMemcpy(d_src, src, size_t(nnz) * 4, hipMemcpyHostToDevice));
+        REINC_HIP(ctx, hipMemcpy(d_dst, dst, size_t(nnz) * 4, hipMemcpyHostToDevice));
     }
-    std::sort(keys.begin(), keys.end());
-    keys.erase(std::unique(keys.begin(), keys.end()), keys.end());
-    const int64_t e = int64_t(keys.size());
-    std::vector<int64_t> row_ptr(n + 1, 0), col_ptr(n + 1, 0);
-    std::vector<int32_t> col(e), row(e), rowid(e);
-    for (int64_t i = 0; i < e; ++i) {
-        const int64_t v = int64_t(keys[i] >> 32), u = int64_t(keys[i] & 0xFFFFFFFFu);
-        col[i] = int32_t(u);
-        rowid[i] = int32_t(v);
-        ++row_ptr[v + 1];
-        ++col_ptr[u + 1];
-    }
-    for (int64_t v = 0; v < n; ++v) {
-        row_ptr[v + 1] += row_ptr[v];
-        col_ptr[v + 1] += col_ptr[v];
-    }
-    {
-        std::vector<int64_t> cursor(col_ptr.begin(), col_ptr.end() - 1);
-        for (int64_t i = 0; i < e; ++i) {  // ascending (v, u): targets land ascending inside every source's list
-            const int64_t v = int64_t(keys[i] >> 32), u = int64_t(keys[i] & 0xFFFFFFFFu);
-            row[cursor[u]++] = int32_t(v);
-        }
-    }
-    std::vector<int32_t> long_rows, long_cols;
-    for (int64_t v = 0; v < n; ++v) {
-        if (row_ptr[v + 1] - row_ptr[v] > kLongRow) long_rows.push_back(int32_t(v));
-        if (col_ptr[v + 1] - col_ptr[v] > kLongRow) long_cols.push_back(int32_t(v));
+    launch_fill_i32(err, 1, 0, s);
+    unsigned node_bits = 1;
+    while ((int64_t(1) << node_bits) <= n) ++node_bits;  // the sentinel row id n must sort correctly too
+    launch_make_keys(d_src, d_dst, nnz, n, keys0, err, s);
+    REINC_HIP(ctx, sort_keys(sort_tmp, sort_bytes, keys0, keys1, nnz, 32 + node_bits, s));
+    launch_unique_flags(keys1, nnz, n, flag, s);
+    launch_scan(flag, offs, nnz, scan_tmp, s);
+    int64_t e = 0;
+    int32_t bad = 0;
+    REINC_HIP(ctx, hipMemcpy(&e, offs + std::max<int64_t>(nnz, 0), 8, hipMemcpyDeviceToHost));
+    REINC_HIP(ctx, hipMemcpy(&bad, err, 4, hipMemcpyDeviceToHost));
+    if (bad) {
+        ctx->scratch_reset();
+        return ctx->fail(REINC_E_ARG, "snapshot %d: an edge endpoint is outside [0, %lld)", t, (long long)n);
     }
     sn.nnz = e;
-    REINC_TRY(upload(ctx, &sn.row_ptr, row_ptr.data(), n + 1, "row_ptr"));
-    REINC_TRY(upload(ctx, &sn.col, col.data(), e, "col"));
-    REINC_TRY(upload(ctx, &sn.rowid, rowid.data(), e, "rowid"));
-    REINC_TRY(upload(ctx, &sn.col_ptr, col_ptr.data(), n + 1, "col_ptr"));
-    REINC_TRY(upload(ctx, &sn.row, row.data(), e, "row"));
-    sn.n_long_rows = int32_t(long_rows.size());
-    sn.n_long_cols = int32_t(long_cols.size());
-    REINC_TRY(upload(ctx, &sn.long_rows, long_rows.data(), sn.n_long_rows, "long_rows"));
-    REINC_TRY(upload(ctx, &sn.long_cols, long_cols.data(), sn.n_long_cols, "long_cols"));
+    const uint64_t ee = uint64_t(std::max<int64_t>(e, 1));
+    sn.row_ptr = static_cast<int64_t *>(ctx->alloc(uint64_t(n + 1) * 8));
+    sn.col = static_cast<int32_t *>(ctx->alloc(ee * 4));
+    sn.rowid = static_cast<int32_t *>(ctx->alloc(ee * 4));
+    sn.col_ptr = static_cast<int64_t *>(ctx->alloc(uint64_t(n + 1) * 8));
+    sn.row = static_cast<int32_t *>(ctx->alloc(ee * 4));
+    if (!sn.row_ptr || !sn.col || !sn.rowid || !sn.col_ptr || !sn.row) return fail_nomem("CSR / CSC");
+    // CSR by destination from the sorted unique keys; the same edges keyed by source give the CSC
+    launch_scatter_unique(keys1, flag, offs, nnz, sn.col, sn.rowid, keys0, s);
+    launch_ptr_from_rowid(sn.rowid, e, n, sn.row_ptr, s);
+    REINC_HIP(ctx, sort_keys(sort_tmp, sort_bytes, keys0, keys1, e, 32 + node_bits, s));
+    launch_low_halves(keys1, e, sn.row, s);
+    launch_ptr_from_sorted(keys1, e, n, sn.col_ptr, s);
     const int agg = ctx->cfg.agg_kind;
     if (agg != REINC_AGG_SUM) {
-        std::vector<float> q(n), p;
-        for (int64_t v = 0; v < n; ++v) q[v] = scale_of(agg, true, ctx->cfg.self_loop + row_ptr[v + 1] - row_ptr[v]);
-        REINC_TRY(upload(ctx, &sn.q, q.data(), n, "q"));
+        sn.q = static_cast<float *>(ctx->alloc(uint64_t(n) * 4));
+        if (!sn.q) return fail_nomem("degree scales");
+        launch_degree_scales(sn.row_ptr, n, agg == REINC_AGG_SYM, ctx->cfg.self_loop, sn.q, s);
         if (agg == REINC_AGG_SYM) sn.p = sn.q;  // same numbers on both sides
     }
+    // rows / columns that take the block-per-row aggregation path
+    for (int side = 0; side < 2; ++side) {
+        const int64_t *ptr = side == 0 ? sn.row_ptr : sn.col_ptr;
+        launch_long_flags(ptr, n, flag, s);
+        launch_scan(flag, offs, n, scan_tmp, s);
+        int64_t cnt = 0;
+        REINC_HIP(ctx, hipMemcpy(&cnt, offs + n, 8, hipMemcpyDeviceToHost));
+        int32_t *list = static_cast<int32_t *>(ctx->alloc(uint64_t(std::max<int64_t>(cnt, 1)) * 4));
+        if (!list) return fail_nomem("long row list");
+        launch_compact(flag, offs, n, list, nullptr, s);
+        if (side == 0) {
+            sn.long_rows = list;
+            sn.n_long_rows = int32_t(cnt);
+        } else {
+            sn.long_cols = list;
+            sn.n_long_cols = int32_t(cnt);
+        }
+    }
+    REINC_HIP(ctx, hipGetLastError());
+    REINC_HIP(ctx, hipDeviceSynchronize());
+    ctx->scratch_reset();
     sn.edges_loaded = true;
     if (ctx->has_derived) ctx->load_after_derived = true;
     return REINC_OK;

@@ -196,6 +196,20 @@ void launch_feature_flags_list(const int32_t *rows, int64_t nrows, int64_t n, in
 void launch_degree_flags(const int64_t *rp_prev, const int64_t *rp_cur, int64_t n, int32_t *flags, hipStream_t s);
 void launch_compact(const int32_t *flags, const int64_t *offsets, int64_t n, int32_t *list, int32_t *index_of,
                     hipStream_t s);
+// canonicalisation of a raw edge list
+size_t sort_keys_tmp_bytes(int64_t n);
+hipError_t sort_keys(void *tmp, size_t tmp_bytes, const uint64_t *in, uint64_t *out, int64_t n, unsigned end_bit,
+                     hipStream_t s);
+void launch_make_keys(const int32_t *src, const int32_t *dst, int64_t nnz, int64_t n, uint64_t *keys, int32_t *err,
+                      hipStream_t s);
+void launch_unique_flags(const uint64_t *keys, int64_t nnz, int64_t n, int32_t *flag, hipStream_t s);
+void launch_scatter_unique(const uint64_t *keys, const int32_t *flag, const int64_t *offs, int64_t nnz, int32_t *col,
+                           int32_t *rowid, uint64_t *swapped, hipStream_t s);
+void launch_low_halves(const uint64_t *keys, int64_t e, int32_t *out, hipStream_t s);
+void launch_ptr_from_sorted(const uint64_t *keys, int64_t e, int64_t n, int64_t *ptr, hipStream_t s);
+void launch_ptr_from_rowid(const int32_t *rowid, int64_t e, int64_t n, int64_t *ptr, hipStream_t s);
+void launch_degree_scales(const int64_t *ptr, int64_t n, int sym, int self_loop, float *q, hipStream_t s);
+void launch_long_flags(const int64_t *ptr, int64_t n, int32_t *flag, hipStream_t s);
 void launch_edge_flags(const int32_t *rowid, const int32_t *col, int64_t nnz, const int64_t *other_ptr,
                        const int32_t *other_col, const int32_t *cflags, int32_t *absent, int32_t *hit, hipStream_t s);
 void launch_delta_row_ptrs(const int64_t *rp_a, const int64_t *rp_b, const int64_t *pos_del, const int64_t *pos_ins,

@@ -116,6 +116,93 @@ __global__ void compact(const int32_t *flags, const int64_t *offsets, int64_t n,
     if (index_of) index_of[i] = f ? int32_t(offsets[i]) : -1;
 }
 
+// ---- canonicalisation of a raw edge list (set semantics) -----------------------------------------------------
+// key = target * 2^32 + source; a self-loop or an endpoint outside [0, n) gets the key n * 2^32, which sorts behind
+// every valid key and is dropped; an endpoint outside the range also raises the error flag.
+__global__ void make_keys(const int32_t *src, const int32_t *dst, int64_t nnz, int64_t n, uint64_t *keys, int32_t *err)
+{
+    const int64_t i = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
+    if (i >= nnz) return;
+    const int64_t u = src[i], v = dst[i];
+    const bool bad = u < 0 || u >= n || v < 0 || v >= n;
+    if (bad) atomicOr(err, 1);
+    keys[i] = (bad || u == v) ? (uint64_t(n) << 32) : ((uint64_t(v) << 32) | uint64_t(u));
+}
+
+// flag[i] = 1 for the first copy of every valid key of the sorted list
+__global__ void unique_flags(const uint64_t *keys, int64_t nnz, int64_t n, int32_t *flag)
+{
+    const int64_t i = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
+    if (i >= nnz) return;
+    const uint64_t k = keys[i];
+    flag[i] = int64_t(k >> 32) < n && (i == 0 || keys[i - 1] != k);
+}
+
+// col[j] = low half, rowid[j] = high half of the j-th kept key; swapped[j] = the key with its halves exchanged
+__global__ void scatter_unique(const uint64_t *keys, const int32_t *flag, const int64_t *offs, int64_t nnz, int32_t *col,
+                               int32_t *rowid, uint64_t *swapped)
+{
+    const int64_t i = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
+    if (i >= nnz || !flag[i]) return;
+    const uint64_t k = keys[i];
+    const int64_t j = offs[i];
+    col[j] = int32_t(k & 0xFFFFFFFFu);
+    rowid[j] = int32_t(k >> 32);
+    swapped[j] = (k << 32) | (k >> 32);
+}
+
+__global__ void low_halves(const uint64_t *keys, int64_t e, int32_t *out)
+{
+    const int64_t i = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
+    if (i < e) out[i] = int32_t(keys[i] & 0xFFFFFFFFu);
+}
+
+// ptr[v] = number of sorted keys whose high half is below v, for v = 0 .. n (binary search per row)
+__global__ void ptr_from_sorted(const uint64_t *keys, int64_t e, int64_t n, int64_t *ptr)
+{
+    const int64_t v = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
+    if (v > n) return;
+    int64_t lo = 0, hi = e;
+    while (lo < hi) {
+        const int64_t mid = (lo + hi) >> 1;
+        if (int64_t(keys[mid] >> 32) < v)
+            lo = mid + 1;
+        else
+            hi = mid;
+    }
+    ptr[v] = lo;
+}
+
+__global__ void ptr_from_rowid(const int32_t *rowid, int64_t e, int64_t n, int64_t *ptr)
+{
+    const int64_t v = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
+    if (v > n) return;
+    int64_t lo = 0, hi = e;
+    while (lo < hi) {
+        const int64_t mid = (lo + hi) >> 1;
+        if (rowid[mid] < v)
+            lo = mid + 1;
+        else
+            hi = mid;
+    }
+    ptr[v] = lo;
+}
+
+// q[v] = 1/deg (mean) or deg^-1/2 (sym), deg = self_loop + row length; 0 for deg = 0
+__global__ void degree_scales(const int64_t *ptr, int64_t n, int sym, int self_loop, float *q)
+{
+    const int64_t v = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
+    if (v >= n) return;
+    const double deg = double(ptr[v + 1] - ptr[v] + self_loop);
+    q[v] = deg <= 0.0 ? 0.0f : float(sym ? 1.0 / sqrt(deg) : 1.0 / deg);
+}
+
+__global__ void long_flags(const int64_t *ptr, int64_t n, int32_t *flag)
+{
+    const int64_t v = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
+    if (v < n) flag[v] = ptr[v + 1] - ptr[v] > kLongRow;
+}
+
 // ---- snapshot diff, one thread per edge -----------------------------------------------------------------
 // Every edge of one snapshot looks itself up in the same row of the other snapshot (binary search over that
 // row's sorted columns).  Work is per edge, so a hub row costs no more per element than a short one and the
@@ -298,6 +385,48 @@ void launch_compact(const int32_t *flags, const int64_t *offsets, int64_t n, int
                     hipStream_t s)
 {
     if (n > 0) compact<<<blocks_for(n, 256), 256, 0, s>>>(flags, offsets, n, list, index_of);
+}
+
+void launch_make_keys(const int32_t *src, const int32_t *dst, int64_t nnz, int64_t n, uint64_t *keys, int32_t *err,
+                      hipStream_t s)
+{
+    if (nnz > 0) make_keys<<<blocks_for(nnz, 256), 256, 0, s>>>(src, dst, nnz, n, keys, err);
+}
+
+void launch_unique_flags(const uint64_t *keys, int64_t nnz, int64_t n, int32_t *flag, hipStream_t s)
+{
+    if (nnz > 0) unique_flags<<<blocks_for(nnz, 256), 256, 0, s>>>(keys, nnz, n, flag);
+}
+
+void launch_scatter_unique(const uint64_t *keys, const int32_t *flag, const int64_t *offs, int64_t nnz, int32_t *col,
+                           int32_t *rowid, uint64_t *swapped, hipStream_t s)
+{
+    if (nnz > 0) scatter_unique<<<blocks_for(nnz, 256), 256, 0, s>>>(keys, flag, offs, nnz, col, rowid, swapped);
+}
+
+void launch_low_halves(const uint64_t *keys, int64_t e, int32_t *out, hipStream_t s)
+{
+    if (e > 0) low_halves<<<blocks_for(e, 256), 256, 0, s>>>(keys, e, out);
+}
+
+void launch_ptr_from_sorted(const uint64_t *keys, int64_t e, int64_t n, int64_t *ptr, hipStream_t s)
+{
+    ptr_from_sorted<<<blocks_for(n + 1, 256), 256, 0, s>>>(keys, e, n, ptr);
+}
+
+void launch_ptr_from_rowid(const int32_t *rowid, int64_t e, int64_t n, int64_t *ptr, hipStream_t s)
+{
+    ptr_from_rowid<<<blocks_for(n + 1, 256), 256, 0, s>>>(rowid, e, n, ptr);
+}
+
+void launch_degree_scales(const int64_t *ptr, int64_t n, int sym, int self_loop, float *q, hipStream_t s)
+{
+    if (n > 0) degree_scales<<<blocks_for(n, 256), 256, 0, s>>>(ptr, n, sym, self_loop, q);
+}
+
+void launch_long_flags(const int64_t *ptr, int64_t n, int32_t *flag, hipStream_t s)
+{
+    if (n > 0) long_flags<<<blocks_for(n, 256), 256, 0, s>>>(ptr, n, flag);
 }
 
 void launch_edge_flags(const int32_t *rowid, const int32_t *col, int64_t nnz, const int64_t *other_ptr,
