@@ -19,10 +19,6 @@ namespace {
 
 typedef float acc16 __attribute__((ext_vector_type(16)));
 
-#ifndef REINC_GEMM64_NT
-#define REINC_GEMM64_NT 1  // accumulator tiles per wave for outputs of 33..64 columns (1: two waves share a row tile)
-#endif
-
 constexpr int kBK = 32;  // k values staged per LDS chunk
 
 __device__ inline float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
@@ -91,6 +87,66 @@ __device__ inline void stage_b(float *Bs, int ldb, int ncols, const float *W, in
             const int wc = col_of(c);
             const int k = k0 + kk;
             Bs[kk * ldb + c] = (wc >= 0 && k < K) ? W[int64_t(wc) * ldw + k] : 0.0f;
+        }
+    }
+}
+
+// Whole-slab staging for the LDS-resident kernels: Bs[k][c] (row length NC) for k in [0, K), where the NC
+// staged columns are runs of RUN consecutive columns of W and run r starts at W column run_col(r).  A thread
+// owns one 16-byte column position and walks down the rows with a fixed pointer stride, so a load costs two
+// or three instructions; kStageDepth loads are in flight per thread and nothing is conditional (a row index
+// past the end is clamped, which repeats a load and its store).  Needs 16-byte aligned rows of W (ldw % 4 == 0, aligned base,
+// run starts % 4 == 0) and TPB >= NC / 4 threads.
+constexpr int kStageDepth = 4;
+
+template <int NC, int RUN, int TPB, class RunCol>
+__device__ inline void stage_slab(float *Bs, const float *W, int ldw, int K, RunCol run_col)
+{
+    constexpr int V = NC / 4, RV = RUN / 4;
+    constexpr int RPS = TPB / V;  // slab rows covered per step by the first RPS * V threads
+    static_assert(RPS >= 1, "block too small for the slab width");
+    const int tid = threadIdx.x;
+    const int k0 = tid / V, c4 = tid - k0 * V;
+    if (k0 >= RPS || k0 >= K) return;
+    const int run = c4 / RV, off = c4 - run * RV;
+    const float *src = W + int64_t(k0) * ldw + run_col(run) + 4 * off;
+    float *dst = Bs + 4 * tid;
+    const int last = (K - k0 - 1) / RPS;  // this thread stages rows k0 + RPS * (0 .. last)
+    const int sstep = RPS * ldw;
+    // rows beyond `last` repeat row `last`: duplicate loads and stores of one value instead of branches
+    for (int b = 0; b <= last; b += kStageDepth) {
+        float4 v[kStageDepth];
+#pragma unroll
+        for (int u = 0; u < kStageDepth; ++u) v[u] = *reinterpret_cast<const float4 *>(src + int64_t(min(b + u, last)) * sstep);
+#pragma unroll
+        for (int u = 0; u < kStageDepth; ++u) *reinterpret_cast<float4 *>(dst + min(b + u, last) * (4 * RPS * V)) = v[u];
+    }
+}
+
+// The same for a transposed operand: Bs[k][j] = W[col0 + j][k] for j in [0, NC), W row-major [M, ldw].
+// Lanes run along j, so the LDS stores of a wave fall into consecutive banks.  Needs K % 4 == 0.
+template <int NC, int TPB>
+__device__ inline void stage_slab_transposed(float *Bs, const float *W, int ldw, int K, int col0)
+{
+    constexpr int QPS = TPB / NC;  // k quads covered per step by the first QPS * NC threads
+    static_assert(QPS >= 1, "block too small for the slab width");
+    const int tid = threadIdx.x;
+    const int q0 = tid / NC, j = tid - q0 * NC;
+    if (q0 >= QPS || 4 * q0 >= K) return;
+    const float *src = W + int64_t(col0 + j) * ldw + 4 * q0;
+    float *dst = Bs + 4 * q0 * NC + j;
+    const int last = (K / 4 - q0 - 1) / QPS;
+    for (int b = 0; b <= last; b += kStageDepth) {
+        float4 v[kStageDepth];
+#pragma unroll
+        for (int u = 0; u < kStageDepth; ++u) v[u] = *reinterpret_cast<const float4 *>(src + min(b + u, last) * (4 * QPS));
+#pragma unroll
+        for (int u = 0; u < kStageDepth; ++u) {
+            float *d = dst + min(b + u, last) * (4 * QPS * NC);
+            d[0] = v[u].x;
+            d[NC] = v[u].y;
+            d[2 * NC] = v[u].z;
+            d[3 * NC] = v[u].w;
         }
     }
 }
@@ -188,17 +244,40 @@ __device__ inline void load_a16_fast(const void *A, int64_t row, int lda, int k0
     }
 }
 
-// 16 k-steps against B fragments in LDS.  bp points at this lane's column of the first of its 16 B rows;
-// tile t of NT sits at column offset tile_stride * t.  Fragments are read four steps ahead of their use so
-// that the matrix cores never wait for an LDS round trip.
-template <int NT, class Prefetch>
-__device__ inline void mfma_chunk(const float (&a)[16], const float *bp, int ld, int tile_stride, acc16 (&acc)[NT],
-                                  Prefetch prefetch)
+// The same from a ready pointer to the lane's first value.
+template <bool BF16>
+__device__ inline void load_a16_ptr(const char *p, float (&a)[16])
 {
-    // groups of G steps: all B fragments of a group are read from LDS first, then its matrix instructions run
-    // back to back (the scheduling barriers keep the compiler from sinking each read next to its use, which
-    // would expose one LDS round trip per step)
-    constexpr int G = 8;
+    if (BF16) {
+        const uint4 v0 = *reinterpret_cast<const uint4 *>(p);
+        const uint4 v1 = *reinterpret_cast<const uint4 *>(p + 16);
+        const uint32_t w[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            a[2 * i] = __uint_as_float(w[i] << 16);
+            a[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u);
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float4 v = *reinterpret_cast<const float4 *>(p + 16 * i);
+            a[4 * i] = v.x;
+            a[4 * i + 1] = v.y;
+            a[4 * i + 2] = v.z;
+            a[4 * i + 3] = v.w;
+        }
+    }
+}
+
+// 16 k-steps against B fragments in LDS.  bp points at this lane's column of the first of its 16 B rows;
+// tile t of NT sits at column offset tile_stride * t and accumulates into acc[t], except that the last tile
+// accumulates into acc[LAST] (the recurrent step keeps one gate's two halves apart).  Fragments are read in
+// groups of G steps ahead of their matrix instructions: the scheduling barriers keep the compiler from
+// sinking each read next to its use, which would expose one LDS round trip per step.
+template <int NT, int LAST, int G, int NACC, class Prefetch>
+__device__ inline void mfma_chunk_map(const float (&a)[16], const float *bp, int ld, int tile_stride, acc16 (&acc)[NACC],
+                                      Prefetch prefetch)
+{
 #pragma unroll
     for (int q = 0; q < 16 / G; ++q) {
         float b[G][NT];
@@ -210,111 +289,147 @@ __device__ inline void mfma_chunk(const float (&a)[16], const float *bp, int ld,
 #pragma unroll
         for (int s = 0; s < G; ++s)
 #pragma unroll
-            for (int t = 0; t < NT; ++t)
-                acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[G * q + s], b[s][t], acc[t], 0, 0, 0);
+            for (int t = 0; t < NT; ++t) {
+                constexpr int dummy = 0;
+                (void)dummy;
+                acc16 &dst = acc[t == NT - 1 ? LAST : t];
+                dst = __builtin_amdgcn_mfma_f32_32x32x2f32(a[G * q + s], b[s][t], dst, 0, 0, 0);
+            }
         if (q == 0) prefetch();
         __builtin_amdgcn_sched_barrier(0);
     }
+}
+
+template <int NT, class Prefetch>
+__device__ inline void mfma_chunk(const float (&a)[16], const float *bp, int ld, int tile_stride, acc16 (&acc)[NT],
+                                  Prefetch prefetch)
+{
+    mfma_chunk_map<NT, NT - 1, 8>(a, bp, ld, tile_stride, acc, prefetch);
 }
 
 struct NoPrefetch {
     __device__ void operator()() const {}
 };
 
-// Same product with the whole weight slab [K, 32*NT] resident in LDS: it is staged once per block, after which
-// every wave streams its own 32-row tiles without any barrier.  The k chunks of all of a wave's tiles form one
-// stream; a ring of three register buffers keeps the loads two chunks (8 KB per wave) ahead of the matrix
-// cores, across tile boundaries and epilogues.  Needs K % 32 == 0 and 16-byte aligned rows; the row scale is
-// applied to the finished sums.
-template <int NT, int WN, bool BF16>
-__global__ void __launch_bounds__(256, NT == 1 ? 4 : (NT == 2 ? 3 : 2)) gemm_rows_resident_kernel(GemmArgs g)
+// Same product with the whole weight slab [K, 32*NT*WN] resident in LDS: it is staged once per block, after
+// which every wave streams its own 32-row tiles without any barrier.  A block is as many waves as the
+// register budget of the variant allows (one block per compute unit), so the slab is fetched once per compute
+// unit and even a slab that fills the LDS leaves the unit fully occupied.  The k chunks of all of a wave's
+// tiles form one stream; a ring of three register buffers keeps the loads two chunks (8 KB per wave) ahead of
+// the matrix cores, across tile boundaries and epilogues.  Needs K % 32 == 0 and 16-byte aligned rows; the
+// row scale is applied to the finished sums.
+template <int NT, int WN, int WAVES, bool BF16>
+__global__ void __launch_bounds__(64 * WAVES) gemm_rows_resident_kernel(GemmArgs g)
 {
-    // 4 waves = (4 / WN) row tiles x WN column groups of 32*NT columns; the slab holds all 32*NT*WN columns
+    // WAVES waves = (WAVES / WN) row tiles x WN column groups of 32*NT columns; the slab holds all 32*NT*WN columns
     extern __shared__ float Bs[];
     constexpr int BN = 32 * NT * WN;
-    constexpr int WR = 4 / WN;
+    constexpr int WR = WAVES / WN;
+    static_assert(WAVES % WN == 0, "column groups must divide the block");
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int wn = w % WN, wr = w / WN;
     const int i = lane & 31, kk = lane >> 5;
     const int col0 = blockIdx.y * BN;
-    for (int k0 = 0; k0 < g.K; k0 += kBK)
-        stage_b(Bs + k0 * BN, BN, BN, g.W, g.ldw, g.wT != 0, k0, g.K, [&](int c) { return col0 + c < g.M ? col0 + c : -1; });
-    __syncthreads();
-    const int64_t ntiles = (g.n + 31) / 32;
-    const int64_t first = int64_t(blockIdx.x) * WR + wr, stride = int64_t(gridDim.x) * WR;
-    if (first >= ntiles) return;
+    // tile indices fit 32 bits (n < 2^31 rows); all cursor arithmetic is wave-uniform
+    const int ntiles = int((g.n + 31) / 32);
+    const int first = __builtin_amdgcn_readfirstlane(int(blockIdx.x) * WR + wr), stride = int(gridDim.x) * WR;
     const int kch = g.K / kBK;
-    const int64_t total = ((ntiles - first + stride - 1) / stride) * kch;
     const float *bp0 = Bs + (16 * kk) * BN + wn * 32 * NT + i;
     const int wcol0 = col0 + wn * 32 * NT;
+    constexpr int ES = BF16 ? 2 : 4;
+    auto row_ptr = [&](int t) __attribute__((always_inline)) {  // this lane's 16 k values of chunk 0 in tile t
+        return static_cast<const char *>(g.A) + (min(int64_t(t) * 32 + i, g.n - 1) * g.lda + 16 * kk) * ES;
+    };
 
-    // load cursor
-    int64_t ltile = first, issued = 0;
-    int lk = 0;
-    int64_t lrow = min(ltile * 32 + i, g.n - 1);
-    auto issue = [&](float(&buf)[16]) {
-        if (issued < total) {
-            load_a16_fast<BF16>(g.A, lrow, g.lda, lk * kBK, buf);
-            ++issued;
+    // load cursor: chunk lk of tile ltile
+    int ltile = first, lk = 0;
+    const char *lptr = row_ptr(ltile < ntiles ? ltile : 0);
+    auto issue = [&](float(&buf)[16]) __attribute__((always_inline)) {
+        if (ltile < ntiles) {
+            load_a16_ptr<BF16>(lptr, buf);
+            lptr += kBK * ES;
             if (++lk == kch) {
                 lk = 0;
                 ltile += stride;
-                lrow = min(ltile * 32 + i, g.n - 1);
+                if (ltile < ntiles) lptr = row_ptr(ltile);
             }
         }
     };
+    auto issue_always = [&](float(&buf)[16]) __attribute__((always_inline)) {  // the caller knows that the chunk exists
+        load_a16_ptr<BF16>(lptr, buf);
+        lptr += kBK * ES;
+        if (++lk == kch) {
+            lk = 0;
+            ltile += stride;
+            lptr = row_ptr(ltile);
+        }
+    };
+    // the first two chunks of A are requested before the weight slab is staged: both fetches overlap
+    float b0[16], b1[16], b2[16];
+    issue(b0);
+    issue(b1);
+    const bool fast_stage = col0 + BN <= g.M && g.ldw % 4 == 0 && (reinterpret_cast<uintptr_t>(g.W) & 15) == 0;
+    if (fast_stage && !g.wT) {
+        stage_slab<BN, BN, 64 * WAVES>(Bs, g.W, g.ldw, g.K, [&](int) { return col0; });
+    } else if (fast_stage) {
+        stage_slab_transposed<BN, 64 * WAVES>(Bs, g.W, g.ldw, g.K, col0);
+    } else {
+        for (int k0 = 0; k0 < g.K; k0 += kBK)
+            stage_b(Bs + k0 * BN, BN, BN, g.W, g.ldw, g.wT != 0, k0, g.K, [&](int c) { return col0 + c < g.M ? col0 + c : -1; });
+    }
+    __syncthreads();
+    // everything requested so far has landed by now; saying so keeps the waits inside the loops exact
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
     // compute cursor
-    int64_t tile = first;
-    int kc = 0;
+    int tile = first, kc = 0;
+    float bias[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) bias[t] = (g.bias && wcol0 + 32 * t + i < g.M) ? g.bias[wcol0 + 32 * t + i] : 0.0f;
     acc16 acc[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[t][r] = 0.0f;
 
-    auto epilogue = [&]() {  // rows rbase + 8*(r/4) + r%4 of the finished tile
-        const int64_t rbase = tile * 32 + 4 * kk;
-        const bool full = tile * 32 + 32 <= g.n;
-        float rs[16];
-#pragma unroll
-        for (int r = 0; r < 16; ++r) rs[r] = 1.0f;
-        if (g.row_scale) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) rs[r] = g.row_scale[min(rbase + 8 * (r / 4) + (r % 4), g.n - 1)];
-        }
+    auto epilogue = [&]() __attribute__((always_inline)) {  // rows rbase + 8*q + e (q, e in 0..3) of the finished tile, four rows at a time
+        const int64_t rbase = int64_t(tile) * 32 + 4 * kk;
+        const bool full = int64_t(tile) * 32 + 32 <= g.n;
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
             const int c = wcol0 + 32 * t + i;
             if (c < g.M) {
-                const float bias = g.bias ? g.bias[c] : 0.0f;
-                float v[16];
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    v[r] = acc[t][r] * rs[r] + bias;
-                    if (g.relu) v[r] = fmaxf(v[r], 0.0f);
-                }
-                if (g.add) {
+                for (int q = 0; q < 4; ++q) {
+                    int64_t o[4];
+                    float v[4];
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) v[r] += g.add[min(rbase + 8 * (r / 4) + (r % 4), g.n - 1) * g.M + c];
-                }
-                if (g.mask) {
+                    for (int e = 0; e < 4; ++e) {
+                        const int64_t rr = min(rbase + 8 * q + e, g.n - 1);
+                        o[e] = rr * g.M + c;
+                        v[e] = acc[t][4 * q + e];
+                        if (g.row_scale) v[e] *= g.row_scale[rr];
+                        v[e] += bias[t];
+                        if (g.relu) v[e] = fmaxf(v[e], 0.0f);
+                    }
+                    if (g.add) {
 #pragma unroll
-                    for (int r = 0; r < 16; ++r)
-                        if (!(g.mask[min(rbase + 8 * (r / 4) + (r % 4), g.n - 1) * g.M + c] > 0.0f)) v[r] = 0.0f;
-                }
+                        for (int e = 0; e < 4; ++e) v[e] += g.add[o[e]];
+                    }
+                    if (g.mask) {
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int64_t rr = rbase + 8 * (r / 4) + (r % 4);
-                    if (full || rr < g.n) g.out[rr * g.M + c] = v[r];
+                        for (int e = 0; e < 4; ++e)
+                            if (!(g.mask[o[e]] > 0.0f)) v[e] = 0.0f;
+                    }
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (full || rbase + 8 * q + e < g.n) g.out[o[e]] = v[e];
                 }
             }
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[t][r] = 0.0f;
         }
     };
-    auto step = [&](float(&cur)[16], float(&nxt)[16]) {
-        issue(nxt);
-        __builtin_amdgcn_sched_barrier(0);  // the new loads go out before this chunk's matrix instructions
+    auto multiply = [&](float(&cur)[16]) __attribute__((always_inline)) {
         mfma_chunk<NT>(cur, bp0 + kc * kBK * BN, BN, 32, acc, NoPrefetch());
         if (++kc == kch) {
             epilogue();
@@ -322,13 +437,32 @@ __global__ void __launch_bounds__(256, NT == 1 ? 4 : (NT == 2 ? 3 : 2)) gemm_row
             tile += stride;
         }
     };
-    float b0[16], b1[16], b2[16];
-    issue(b0);
-    issue(b1);
-    for (int64_t p = 0; p < total; p += 3) {
+    // Steady state: while the chunk two ahead of the one being multiplied exists, its load is unconditional,
+    // so the wait in front of a chunk's matrix instructions covers exactly the loads older than the last two.
+    // (A load that may or may not have been issued forces a wait for everything.)
+    const int my_tiles = first < ntiles ? (ntiles - first + stride - 1) / stride : 0;
+    const int steady = max(my_tiles * kch - 2, 0) / 3;
+    for (int j = 0; j < steady; ++j) {
+        issue_always(b2);
+        __builtin_amdgcn_sched_barrier(0);  // the new loads go out before this chunk's matrix instructions
+        multiply(b0);
+        issue_always(b0);
+        __builtin_amdgcn_sched_barrier(0);
+        multiply(b1);
+        issue_always(b1);
+        __builtin_amdgcn_sched_barrier(0);
+        multiply(b2);
+    }
+    // the last chunks: loads only while chunks remain
+    auto step = [&](float(&cur)[16], float(&nxt)[16]) __attribute__((always_inline)) {
+        issue(nxt);
+        __builtin_amdgcn_sched_barrier(0);
+        multiply(cur);
+    };
+    while (tile < ntiles) {
         step(b0, b2);
-        if (p + 1 < total) step(b1, b0);
-        if (p + 2 < total) step(b2, b1);
+        if (tile < ntiles) step(b1, b0);
+        if (tile < ntiles) step(b2, b1);
     }
 }
 
@@ -344,25 +478,36 @@ int resident_blocks(const void *kernel, int threads, size_t lds)
     return blocks;
 }
 
-template <int NT, int WN>
+template <int NT, int WN, int WAVES>
 bool gemm_rows_resident_launch(const GemmArgs &g, int bf16, hipStream_t s)
 {
     if (g.K % kBK != 0 || g.lda % 8 != 0) return false;
     constexpr int BN = 32 * NT * WN;
     const size_t lds = size_t(g.K) * BN * sizeof(float);
     if (lds > kLdsBytes - 1024) return false;
-    auto k = bf16 ? gemm_rows_resident_kernel<NT, WN, true> : gemm_rows_resident_kernel<NT, WN, false>;
+    auto k = bf16 ? gemm_rows_resident_kernel<NT, WN, WAVES, true> : gemm_rows_resident_kernel<NT, WN, WAVES, false>;
     if (lds > 48 * 1024 &&
         hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, int(lds)) != hipSuccess)
         return false;
-    const int per_cu = resident_blocks(reinterpret_cast<const void *>(k), 256, lds);
+    const int per_cu = resident_blocks(reinterpret_cast<const void *>(k), 64 * WAVES, lds);
     if (per_cu <= 0) return false;
     const int64_t ntiles = (g.n + 31) / 32;
-    const int wr = 4 / WN;
+    constexpr int wr = WAVES / WN;
     const unsigned gy = unsigned((g.M + BN - 1) / BN);
     dim3 grid(unsigned(std::min<int64_t>((ntiles + wr - 1) / wr, std::max<int64_t>(1, int64_t(kNumCU) * per_cu / gy))), gy);
-    k<<<grid, 256, lds, s>>>(g);
+    k<<<grid, 64 * WAVES, lds, s>>>(g);
     return true;
+}
+
+// Variant choice (measured on 1e5 .. 2.5e6 rows, K and M in 64 .. 512): the widest accumulator tile whose slab
+// fits wins for outputs of more than 64 columns; when the slab of 128 columns does not fit, 64-column slabs
+// with the column groups on blockIdx.y follow (A is then re-read out of L2).
+bool gemm_rows_resident_dispatch(const GemmArgs &g, int bf16, hipStream_t s)
+{
+    if (g.M > 64 && gemm_rows_resident_launch<4, 1, 8>(g, bf16, s)) return true;
+    if (g.M > 64 && gemm_rows_resident_launch<2, 1, 12>(g, bf16, s)) return true;
+    if (g.M > 32 && g.M <= 64 && gemm_rows_resident_launch<2, 1, 16>(g, bf16, s)) return true;
+    return gemm_rows_resident_launch<1, 1, 16>(g, bf16, s);
 }
 
 template <int NT, int WM, int WN>
@@ -386,7 +531,10 @@ struct RnnArgs {
     float *h_out, *c_out, *saved;
 };
 
-__device__ inline float sigmoidf_(float v) { return 1.0f / (1.0f + expf(-v)); }
+// Gate activations on the hardware exp2 / reciprocal instructions (about 1 ulp each): absolute error below
+// 3e-7, far inside the 1e-4 tolerance on the step's outputs, at a fifth of the instructions of expf/tanhf.
+__device__ inline float sigmoidf_(float v) { return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.44269504f * v)); }
+__device__ inline float tanhf_(float v) { return 1.0f - 2.0f * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(2.88539008f * v)); }
 
 // 4 waves as WM x WN; each wave owns 32 rows x 32 hidden units and four 32x32 accumulators:
 //   LSTM: gates i, f, g, o (x and h parts summed);   GRU: r, z (summed), x-part of n, h-part of n.
@@ -459,12 +607,12 @@ __global__ void __launch_bounds__(256) rnn_fused_kernel(RnnArgs g)
         if (LSTM) {
             const float gi = sigmoidf_(acc[0][r] + bi[0] + bh[0]);
             const float gf = sigmoidf_(acc[1][r] + bi[1] + bh[1]);
-            const float gg = tanhf(acc[2][r] + bi[2] + bh[2]);
+            const float gg = tanhf_(acc[2][r] + bi[2] + bh[2]);
             const float go = sigmoidf_(acc[3][r] + bi[3] + bh[3]);
             const float cp = g.c_prev ? g.c_prev[o] : 0.0f;
             const float cn = gf * cp + gi * gg;
             g.c_out[o] = cn;
-            g.h_out[o] = go * tanhf(cn);
+            g.h_out[o] = go * tanhf_(cn);
             if (g.saved) {
                 float *sv = g.saved + rr * 4 * H + j;
                 sv[0] = gi;
@@ -476,7 +624,7 @@ __global__ void __launch_bounds__(256) rnn_fused_kernel(RnnArgs g)
             const float gr = sigmoidf_(acc[0][r] + bi[0] + bh[0]);
             const float gz = sigmoidf_(acc[1][r] + bi[1] + bh[1]);
             const float ghn = acc[3][r] + bh[2];
-            const float gn = tanhf(acc[2][r] + bi[2] + gr * ghn);
+            const float gn = tanhf_(acc[2][r] + bi[2] + gr * ghn);
             const float hp = g.h_prev ? g.h_prev[o] : 0.0f;
             g.h_out[o] = (1.0f - gz) * gn + gz * hp;
             if (g.saved) {
@@ -491,173 +639,226 @@ __global__ void __launch_bounds__(256) rnn_fused_kernel(RnnArgs g)
 }
 
 // Same step with both weight matrices (the block's hidden-unit columns of every gate) resident in LDS:
-// staged once per block, then 8 waves (WM row tiles x WN groups of 32 hidden units) stream row tiles without
-// barriers.  Rows [0, d_in) of the slab hold W_i, rows [d_in, d_in + H) hold W_h.  Needs d_in % 64 == 0 and
-// H % 64 == 0.
-template <bool LSTM, int WN>
-__global__ void __launch_bounds__(512) rnn_fused_resident_kernel(RnnArgs g)
+// staged once per block (one block per compute unit), then every wave streams 32-row tiles for its 32 hidden
+// units without barriers.  Rows [0, d_in) of the slab hold W_i, rows [d_in, d_in + H) hold W_h, so the k
+// chunks of x and of h_prev form one stream per tile, and the chunks of all of a wave's tiles one stream
+// overall; a ring of three register buffers keeps the loads two chunks ahead of the matrix cores.  Needs
+// d_in % 32 == 0, H % 32 == 0 and 16-byte aligned rows.
+template <bool LSTM, int WN, int WAVES>
+__global__ void __launch_bounds__(64 * WAVES) rnn_fused_resident_kernel(RnnArgs g)
 {
     extern __shared__ float Bs[];
     constexpr int KG = LSTM ? 4 : 3;
-    constexpr int WM = 8 / WN;
+    constexpr int WM = WAVES / WN;
     constexpr int BH = 32 * WN;
     constexpr int NC = KG * BH;
+    constexpr int G = 4;  // B fragments are read four steps (12 or 16 registers) ahead
+    static_assert(WAVES % WN == 0, "column groups must divide the block");
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int wm = w / WN, wn = w % WN;
     const int i = lane & 31, kk = lane >> 5;
     const int h0 = blockIdx.y * BH;
-    const int H = g.H, ldw = KG * H, dpad = g.d_in;
-    auto col_of = [&](int c) {
-        const int gate = c / BH, j = c - gate * BH;
-        return h0 + j < H ? gate * H + h0 + j : -1;
+    const int H = g.H, ldw = KG * H;
+    const int ntiles = int((g.n + 31) / 32);
+    const int first = __builtin_amdgcn_readfirstlane(int(blockIdx.x) * WM + wm), stride = int(gridDim.x) * WM;
+    const int kx = g.d_in / kBK, kh = g.h_prev ? H / kBK : 0, kch = kx + kh;
+    auto x_ptr = [&](int t) __attribute__((always_inline)) {
+        return reinterpret_cast<const char *>(g.x) + (min(int64_t(t) * 32 + i, g.n - 1) * g.d_in + 16 * kk) * 4;
     };
-    for (int k0 = 0; k0 < g.d_in; k0 += kBK) stage_b(Bs + k0 * NC, NC, NC, g.W_i, ldw, false, k0, g.d_in, col_of);
-    for (int k0 = 0; k0 < H; k0 += kBK) stage_b(Bs + (dpad + k0) * NC, NC, NC, g.W_h, ldw, false, k0, H, col_of);
+    auto h_ptr = [&](int t) __attribute__((always_inline)) {
+        return reinterpret_cast<const char *>(g.h_prev) + (min(int64_t(t) * 32 + i, g.n - 1) * H + 16 * kk) * 4;
+    };
+    // load cursor: chunk lk of tile ltile (chunks 0 .. kx-1 come from x, the rest from h_prev)
+    int ltile = first, lk = 0;
+    const char *lptr = x_ptr(ltile < ntiles ? ltile : 0);
+    auto advance = [&](bool more) __attribute__((always_inline)) {
+        lptr += kBK * 4;
+        ++lk;
+        if (lk == kx && kh > 0) lptr = h_ptr(ltile);
+        if (lk == kch) {
+            lk = 0;
+            ltile += stride;
+            if (more) lptr = x_ptr(ltile);
+        }
+    };
+    auto issue = [&](float(&buf)[16]) __attribute__((always_inline)) {
+        if (ltile < ntiles) {
+            load_a16_ptr<false>(lptr, buf);
+            advance(ltile + stride < ntiles || lk + 1 < kch);
+        }
+    };
+    auto issue_always = [&](float(&buf)[16]) __attribute__((always_inline)) {  // the caller knows that the chunk exists
+        load_a16_ptr<false>(lptr, buf);
+        advance(true);
+    };
+    // the first two chunks are requested before the slabs are staged: the fetches overlap
+    float b0[16], b1[16], b2[16];
+    issue(b0);
+    issue(b1);
+    const bool fast_stage = h0 + BH <= H && H % 4 == 0 && (reinterpret_cast<uintptr_t>(g.W_i) & 15) == 0 &&
+                            (reinterpret_cast<uintptr_t>(g.W_h) & 15) == 0;
+    if (fast_stage) {
+        stage_slab<NC, BH, 64 * WAVES>(Bs, g.W_i, ldw, g.d_in, [&](int gate) { return gate * H + h0; });
+        stage_slab<NC, BH, 64 * WAVES>(Bs + int64_t(g.d_in) * NC, g.W_h, ldw, H, [&](int gate) { return gate * H + h0; });
+    } else {
+        auto col_of = [&](int c) {
+            const int gate = c / BH, j = c - gate * BH;
+            return h0 + j < H ? gate * H + h0 + j : -1;
+        };
+        for (int k0 = 0; k0 < g.d_in; k0 += kBK) stage_b(Bs + k0 * NC, NC, NC, g.W_i, ldw, false, k0, g.d_in, col_of);
+        for (int k0 = 0; k0 < H; k0 += kBK) stage_b(Bs + (g.d_in + k0) * NC, NC, NC, g.W_h, ldw, false, k0, H, col_of);
+    }
     __syncthreads();
+    // everything requested so far has landed by now; saying so keeps the waits inside the loops exact
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
     const int j = h0 + wn * 32 + i;
-    float bi[KG], bh[KG];
+    float bsum[KG], bhn = 0.0f;  // gate biases: b_i + b_h, except that GRU keeps b_hn apart (the reset gate scales it)
 #pragma unroll
     for (int t = 0; t < KG; ++t) {
-        bi[t] = (g.b_i && j < H) ? g.b_i[t * H + j] : 0.0f;
-        bh[t] = (g.b_h && j < H) ? g.b_h[t * H + j] : 0.0f;
+        const float bi = (g.b_i && j < H) ? g.b_i[t * H + j] : 0.0f;
+        const float bh = (g.b_h && j < H) ? g.b_h[t * H + j] : 0.0f;
+        if (!LSTM && t == 2) {
+            bsum[t] = bi;
+            bhn = bh;
+        } else {
+            bsum[t] = bi + bh;
+        }
     }
-    const int64_t ntiles = (g.n + 31) / 32;
     const float *bp0 = Bs + (16 * kk) * NC + wn * 32 + i;
-    float a0[16], a1[16];
-    bool first = true;
-    for (int64_t tile = int64_t(blockIdx.x) * WM + wm; tile < ntiles; tile += int64_t(gridDim.x) * WM) {
-        const int64_t row = min(tile * 32 + i, g.n - 1);
-        acc16 acc[4];
+    const float *pstate = LSTM ? g.c_prev : g.h_prev;
+    // compute cursor; accumulators: LSTM i, f, g, o (x and h parts summed); GRU r, z (summed), h part of n, x part of n
+    int tile = first, kc = 0;
+    acc16 acc[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[t][r] = 0.0f;
+
+    auto epilogue = [&]() __attribute__((always_inline)) {  // rows rbase + 8*q + e of the finished tile, four at a time
+        const int64_t rbase = int64_t(tile) * 32 + 4 * kk;
+        const bool full = int64_t(tile) * 32 + 32 <= g.n;
+        if (j < H) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                int64_t rr[4];
+                float prev[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    rr[e] = min(rbase + 8 * q + e, g.n - 1);
+                    prev[e] = pstate ? pstate[rr[e] * H + j] : 0.0f;
+                }
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    if (!(full || rbase + 8 * q + e < g.n)) continue;
+                    const int r = 4 * q + e;
+                    const int64_t o = rr[e] * H + j;
+                    if (LSTM) {
+                        const float gi = sigmoidf_(acc[0][r] + bsum[0]);
+                        const float gf = sigmoidf_(acc[1][r] + bsum[1]);
+                        const float gg = tanhf_(acc[2][r] + bsum[2]);
+                        const float go = sigmoidf_(acc[3][r] + bsum[LSTM ? 3 : 0]);
+                        const float cn = gf * prev[e] + gi * gg;
+                        g.c_out[o] = cn;
+                        g.h_out[o] = go * tanhf_(cn);
+                        if (g.saved) {
+                            float *sv = g.saved + rr[e] * 4 * H + j;
+                            sv[0] = gi;
+                            sv[H] = gf;
+                            sv[2 * H] = gg;
+                            sv[3 * H] = go;
+                        }
+                    } else {
+                        const float gr = sigmoidf_(acc[0][r] + bsum[0]);
+                        const float gz = sigmoidf_(acc[1][r] + bsum[1]);
+                        const float ghn = acc[2][r] + bhn;
+                        const float gn = tanhf_(acc[3][r] + bsum[2] + gr * ghn);
+                        g.h_out[o] = (1.0f - gz) * gn + gz * prev[e];
+                        if (g.saved) {
+                            float *sv = g.saved + rr[e] * 4 * H + j;
+                            sv[0] = gr;
+                            sv[H] = gz;
+                            sv[2 * H] = gn;
+                            sv[3 * H] = ghn;
+                        }
+                    }
+                }
+            }
+        }
 #pragma unroll
         for (int t = 0; t < 4; ++t)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[t][r] = 0.0f;
-        if (first) {
-            load_a16_fast<false>(g.x, row, g.d_in, 0, a0);
-            first = false;
-        }
-        const int64_t next_tile = tile + int64_t(gridDim.x) * WM;
-        const int64_t next_row = min(next_tile * 32 + i, g.n - 1);
-        const bool has_h = g.h_prev != nullptr;
-        acc16(&acc3)[3] = reinterpret_cast<acc16(&)[3]>(acc[0]);
-        acc16(&acc2)[2] = reinterpret_cast<acc16(&)[2]>(acc[0]);
-        acc16(&acc1)[1] = reinterpret_cast<acc16(&)[1]>(acc[3]);
-        // x part: gates land in accumulators 0 .. KG-1
-        for (int k0 = 0; k0 < g.d_in; k0 += 2 * kBK) {
-            auto pf1 = [&] { load_a16_fast<false>(g.x, row, g.d_in, k0 + kBK, a1); };
-            auto pf0 = [&] {
-                if (k0 + 2 * kBK < g.d_in)
-                    load_a16_fast<false>(g.x, row, g.d_in, k0 + 2 * kBK, a0);
-                else if (has_h)
-                    load_a16_fast<false>(g.h_prev, row, H, 0, a0);
-                else if (next_tile < ntiles)
-                    load_a16_fast<false>(g.x, next_row, g.d_in, 0, a0);
-            };
-            if (LSTM) {
-                mfma_chunk<4>(a0, bp0 + k0 * NC, NC, BH, acc, pf1);
-                mfma_chunk<4>(a1, bp0 + (k0 + kBK) * NC, NC, BH, acc, pf0);
-            } else {
-                mfma_chunk<3>(a0, bp0 + k0 * NC, NC, BH, acc3, pf1);
-                mfma_chunk<3>(a1, bp0 + (k0 + kBK) * NC, NC, BH, acc3, pf0);
-            }
-        }
-        // h part: GRU keeps h W_hn apart (accumulator 3) because the reset gate multiplies it
-        if (has_h) {
-            for (int k0 = 0; k0 < H; k0 += 2 * kBK) {
-                auto pf1 = [&] { load_a16_fast<false>(g.h_prev, row, H, k0 + kBK, a1); };
-                auto pf0 = [&] {
-                    if (k0 + 2 * kBK < H)
-                        load_a16_fast<false>(g.h_prev, row, H, k0 + 2 * kBK, a0);
-                    else if (next_tile < ntiles)
-                        load_a16_fast<false>(g.x, next_row, g.d_in, 0, a0);
-                };
-                const float *bp = bp0 + (dpad + k0) * NC;
-                if (LSTM) {
-                    mfma_chunk<4>(a0, bp, NC, BH, acc, pf1);
-                    mfma_chunk<4>(a1, bp + kBK * NC, NC, BH, acc, pf0);
-                } else {
-                    mfma_chunk<2>(a0, bp, NC, BH, acc2, pf1);
-                    mfma_chunk<1>(a0, bp + 2 * BH, NC, BH, acc1, NoPrefetch());
-                    mfma_chunk<2>(a1, bp + kBK * NC, NC, BH, acc2, pf0);
-                    mfma_chunk<1>(a1, bp + kBK * NC + 2 * BH, NC, BH, acc1, NoPrefetch());
-                }
-            }
-        }
-        if (j >= H) continue;
-        const int64_t rbase = tile * 32 + 4 * kk;
-        const bool full = tile * 32 + 32 <= g.n;
-        float prev[16];
-        const float *pstate = LSTM ? g.c_prev : g.h_prev;
+    };
+    auto multiply = [&](float(&cur)[16]) __attribute__((always_inline)) {
+        const float *bp = bp0 + kc * kBK * NC;
+        mfma_chunk_map<KG, KG - 1, G>(cur, bp, NC, BH, acc, NoPrefetch());
+        ++kc;
+        if (!LSTM && kc == kx) {  // GRU: the x part of the n gate is complete; the h part starts from zero
+            acc[3] = acc[2];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int64_t rr = rbase + 8 * (r / 4) + (r % 4);
-            prev[r] = (pstate && (full || rr < g.n)) ? pstate[rr * H + j] : 0.0f;
+            for (int r = 0; r < 16; ++r) acc[2][r] = 0.0f;
         }
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int64_t rr = rbase + 8 * (r / 4) + (r % 4);
-            if (!(full || rr < g.n)) continue;
-            const int64_t o = rr * H + j;
-            if (LSTM) {
-                const float gi = sigmoidf_(acc[0][r] + bi[0] + bh[0]);
-                const float gf = sigmoidf_(acc[1][r] + bi[1] + bh[1]);
-                const float gg = tanhf(acc[2][r] + bi[2] + bh[2]);
-                const float go = sigmoidf_(acc[3][r] + bi[3] + bh[3]);
-                const float cn = gf * prev[r] + gi * gg;
-                g.c_out[o] = cn;
-                g.h_out[o] = go * tanhf(cn);
-                if (g.saved) {
-                    float *sv = g.saved + rr * 4 * H + j;
-                    sv[0] = gi;
-                    sv[H] = gf;
-                    sv[2 * H] = gg;
-                    sv[3 * H] = go;
-                }
-            } else {
-                const float gr = sigmoidf_(acc[0][r] + bi[0] + bh[0]);
-                const float gz = sigmoidf_(acc[1][r] + bi[1] + bh[1]);
-                const float ghn = acc[3][r] + bh[2];
-                const float gn = tanhf(acc[2][r] + bi[2] + gr * ghn);
-                g.h_out[o] = (1.0f - gz) * gn + gz * prev[r];
-                if (g.saved) {
-                    float *sv = g.saved + rr * 4 * H + j;
-                    sv[0] = gr;
-                    sv[H] = gz;
-                    sv[2 * H] = gn;
-                    sv[3 * H] = ghn;
-                }
-            }
+        if (kc == kch) {
+            epilogue();
+            kc = 0;
+            tile += stride;
         }
+    };
+    // steady state (unconditional loads, exact waits), then the last chunks: see gemm_rows_resident_kernel
+    const int my_tiles = first < ntiles ? (ntiles - first + stride - 1) / stride : 0;
+    const int steady = max(my_tiles * kch - 2, 0) / 3;
+    for (int it = 0; it < steady; ++it) {
+        issue_always(b2);
+        __builtin_amdgcn_sched_barrier(0);
+        multiply(b0);
+        issue_always(b0);
+        __builtin_amdgcn_sched_barrier(0);
+        multiply(b1);
+        issue_always(b1);
+        __builtin_amdgcn_sched_barrier(0);
+        multiply(b2);
+    }
+    auto step = [&](float(&cur)[16], float(&nxt)[16]) __attribute__((always_inline)) {
+        issue(nxt);
+        __builtin_amdgcn_sched_barrier(0);
+        multiply(cur);
+    };
+    while (tile < ntiles) {
+        step(b0, b2);
+        if (tile < ntiles) step(b1, b0);
+        if (tile < ntiles) step(b2, b1);
     }
 }
 
-template <bool LSTM, int WN>
+template <bool LSTM, int WN, int WAVES>
 bool rnn_fused_resident_launch(const RnnArgs &g, hipStream_t s)
 {
     constexpr int KG = LSTM ? 4 : 3;
-    constexpr int WM = 8 / WN;
-    if (g.d_in % (2 * kBK) != 0 || g.H % (2 * kBK) != 0) return false;
+    constexpr int WM = WAVES / WN;
+    if (g.d_in % kBK != 0 || g.H % kBK != 0 || g.d_in % 4 != 0) return false;
     const size_t lds = size_t(g.d_in + g.H) * KG * 32 * WN * sizeof(float);
     if (lds > kLdsBytes - 1024) return false;
-    auto k = rnn_fused_resident_kernel<LSTM, WN>;
+    auto k = rnn_fused_resident_kernel<LSTM, WN, WAVES>;
     if (lds > 48 * 1024 &&
         hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, int(lds)) != hipSuccess)
         return false;
-    const int per_cu = resident_blocks(reinterpret_cast<const void *>(k), 512, lds);
+    const int per_cu = resident_blocks(reinterpret_cast<const void *>(k), 64 * WAVES, lds);
     if (per_cu <= 0) return false;
     const int64_t ntiles = (g.n + 31) / 32;
     const unsigned gy = unsigned((g.H + 32 * WN - 1) / (32 * WN));
     dim3 grid(unsigned(std::min<int64_t>((ntiles + WM - 1) / WM, std::max<int64_t>(1, int64_t(kNumCU) * per_cu / gy))), gy);
-    k<<<grid, 512, lds, s>>>(g);
+    k<<<grid, 64 * WAVES, lds, s>>>(g);
     return true;
 }
+
+constexpr int kRnnWaves = 12;  // three waves per SIMD: the kernel needs at most 168 registers
 
 template <bool LSTM>
 bool rnn_fused_resident_dispatch(const RnnArgs &g, hipStream_t s)
 {
-    if (g.H > 64 && rnn_fused_resident_launch<LSTM, 4>(g, s)) return true;
-    if (g.H > 32 && rnn_fused_resident_launch<LSTM, 2>(g, s)) return true;
-    return rnn_fused_resident_launch<LSTM, 1>(g, s);
+    if (g.H % 128 == 0 && rnn_fused_resident_launch<LSTM, 4, kRnnWaves>(g, s)) return true;
+    if (g.H % 64 == 0 && rnn_fused_resident_launch<LSTM, 2, kRnnWaves>(g, s)) return true;
+    return rnn_fused_resident_launch<LSTM, 1, kRnnWaves>(g, s);
 }
 
 // ---- weight / bias gradient: C[K,M] = sum_rows (rs .* A)^T G ---------------------------------------------
@@ -877,7 +1078,7 @@ __global__ void rnn_backward_elem_kernel(RnnBwdArgs g)
     const float dh = g.dh[idx];
     if (LSTM) {
         const float gi = sv[0], gf = sv[H], gg = sv[2 * H], go = sv[3 * H];
-        const float tc = tanhf(g.c_new[idx]);
+        const float tc = tanhf_(g.c_new[idx]);
         const float dcc = (g.dc ? g.dc[idx] : 0.0f) + dh * go * (1.0f - tc * tc);
         const float cp = g.c_prev ? g.c_prev[idx] : 0.0f;
         float *o = g.dgi + r * 4 * H + j;
@@ -963,9 +1164,7 @@ int launch_gemm_rows(const void *A, int a_bf16, int64_t n, int32_t K, int32_t M,
     if (n <= 0) return 0;
     GemmArgs g{A, n, K, M, K, row_scale, W, ldw, w_transposed, bias, relu, mask, add, out};
     // preferred: weight slab resident in LDS, as wide as fits
-    if (M > 64 && gemm_rows_resident_launch<4, 1>(g, a_bf16, s)) return 0;
-    if (M > 32 && gemm_rows_resident_launch<REINC_GEMM64_NT, 2 / REINC_GEMM64_NT>(g, a_bf16, s)) return 0;
-    if (gemm_rows_resident_launch<1, 1>(g, a_bf16, s)) return 0;
+    if (gemm_rows_resident_dispatch(g, a_bf16, s)) return 0;
     // very deep products: stage the weights 32 k values at a time
     if (M <= 32)
         gemm_rows_launch<1, 4, 1>(g, a_bf16, s);
