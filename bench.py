@@ -23,6 +23,7 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E
 LONG_ROW = 64  # rows with more entries than this are aggregated by the block-per-row kernel
+MAX_BATCH = 8  # timesteps of a window that the driver hands to one launch
 
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
 # command (profiles/bench_c2_hbm_traffic_pmc.txt), scaled by the copy-kernel calibration; None = not measured.
@@ -142,11 +143,12 @@ def main():
     mean_l1 = float(np.mean([short_bytes(t, "fwd", wl.dims[0], elem) for t in range(T)]))
     total_bytes += per_step_full * mean_l1
     count += per_step_full
+    batches = -(-L // MAX_BATCH)  # above layer 1 one launch aggregates up to MAX_BATCH snapshots of a window
     for t0_ in range(windows):
-        for t in range(t0_, t0_ + L):
-            for l in range(2, layers + 1):  # forward aggregate and backward adjoint of layer l
+        for l in range(2, layers + 1):  # forward aggregate and backward adjoint of layer l
+            count += 2 * batches
+            for t in range(t0_, t0_ + L):
                 total_bytes += short_bytes(t, "fwd", wl.dims[l - 1], 4) + short_bytes(t, "adj", wl.dims[l - 1], 4)
-                count += 2
     exp_launches = count * args.steps
     bytes_per_launch = total_bytes / max(count, 1)
     avg_ms = total_ms / max(launches, 1)

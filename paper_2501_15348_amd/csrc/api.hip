@@ -84,9 +84,11 @@ int reinc_create(reinc_ctx **out, const reinc_config *cfg)
     ctx->snaps.resize(c.num_snapshots);
     ctx->deltas.resize(c.num_snapshots);
     ctx->gcache.assign(c.num_snapshots, nullptr);
-    // measured on MI355X: overlapping the independent kernels of a timestep on side streams gains nothing (every
-    // kernel already fills the register file), so the default keeps all work on the caller's stream
-    if (const char *e = std::getenv("REINC_OVERLAP")) ctx->overlap = e[0] == '1';
+    if (const char *e = std::getenv("REINC_BATCH")) ctx->max_batch = std::min(std::max(std::atoi(e), 1), int(kMaxAggBatch));
+    if (c.agg_kind != REINC_AGG_SUM) {
+        ctx->q_block = static_cast<float *>(ctx->alloc(uint64_t(c.num_snapshots) * uint64_t(c.num_nodes) * 4));
+        if (!ctx->q_block) return ctx->fail(REINC_E_NOMEM, "arena exhausted: no room for the degree scales");
+    }
     return REINC_OK;
 }
 
@@ -94,9 +96,6 @@ int reinc_destroy(reinc_ctx *ctx)
 {
     if (ctx) {
         for (hipEvent_t e : ctx->prof_events) (void)hipEventDestroy(e);
-        for (hipEvent_t e : ctx->order_events) (void)hipEventDestroy(e);
-        for (hipStream_t st : ctx->side)
-            if (st) (void)hipStreamDestroy(st);
     }
     delete ctx;
     return REINC_OK;
@@ -178,8 +177,7 @@ int reinc_load_edges(reinc_ctx *ctx, int32_t t, const int32_t *src, const int32_
     launch_ptr_from_sorted(keys1, e, n, sn.col_ptr, s);
     const int agg = ctx->cfg.agg_kind;
     if (agg != REINC_AGG_SUM) {
-        sn.q = static_cast<float *>(ctx->alloc(uint64_t(n) * 4));
-        if (!sn.q) return fail_nomem("degree scales");
+        sn.q = ctx->q_block + int64_t(t) * n;  // one [T, N] block: the scales of consecutive snapshots are adjacent
         launch_degree_scales(sn.row_ptr, n, agg == REINC_AGG_SYM, ctx->cfg.self_loop, sn.q, s);
         if (agg == REINC_AGG_SYM) sn.p = sn.q;  // same numbers on both sides
     }

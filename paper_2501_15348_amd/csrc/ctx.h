@@ -63,6 +63,23 @@ struct Delta {
     float *dY = nullptr;         // [n_changed, d0] fp32
 };
 
+// One aggregation problem: CSR-like (ptr, idx) over n rows, input rows X, optional source / target scalings and
+// output mask, output rows, and the list of rows longer than kLongRow.
+constexpr int kMaxAggBatch = 8;
+struct AggItem {
+    const int64_t *ptr;
+    const int32_t *idx;
+    const void *X;
+    const float *in_scale, *out_scale, *mask;
+    float *out;
+    const int32_t *long_rows;
+    int32_t n_long;
+};
+struct AggBatch {
+    int count = 0;
+    AggItem item[kMaxAggBatch];
+};
+
 struct LocalStep {  // per-window activations of one timestep (local cache)
     float *S[REINC_MAX_GCN_LAYERS + 1] = {};  // S[l]: un-normalised sums feeding layer l (l >= 2; S[1] lives in the global cache)
     float *H[REINC_MAX_GCN_LAYERS + 1] = {};  // H[l]: output of layer l
@@ -87,7 +104,9 @@ struct reinc_ctx {
     uint64_t local_reserved = 0;  // bytes at the top of the arena held by the local cache
     bool local_valid = false;
     int32_t local_t0 = -1, local_L = 0;
-    float *zero_state = nullptr;  // [N, H] zeros
+    float *zero_state = nullptr;  // [N, H] zeros: the recurrent state before the first timestep of a window
+    float *q_block = nullptr;     // [T, N] target-side degree scales of all snapshots (null for SUM)
+    int max_batch = reinc::kMaxAggBatch;  // timesteps the window driver handles per launch (REINC_BATCH=1..8 lowers it)
     float *loss_partial = nullptr;
     reinc_stats stats{};
     // arena bookkeeping for reinc_reset_derived
@@ -99,11 +118,6 @@ struct reinc_ctx {
             derived_mark = bottom;
         }
     }
-    // side streams of the window driver (default priority, created on first use) and a ring of ordering events
-    hipStream_t side[3] = {nullptr, nullptr, nullptr};
-    bool overlap = false;  // true (REINC_OVERLAP=1): the window driver spreads independent kernels over the side streams
-    std::vector<hipEvent_t> order_events;
-    size_t order_next = 0;
     // kernel timing (reinc_profile_begin / _end)
     uint32_t prof_mask = 0;
     std::vector<hipEvent_t> prof_events;  // pool, two per recorded launch
@@ -229,15 +243,15 @@ void launch_dy(const void *x_prev, const void *x_cur, int bf16, const float *p_p
 bool agg_width_supported(int32_t d, int bf16);
 // out[v] = out_scale[v] * ( self_loop * in_scale[v] X[v] + sum_{e in [ptr[v], ptr[v+1])} in_scale[idx[e]] X[idx[e]] )
 // in_scale / out_scale may be null (factor 1); mask [n,d] (may be null) zeroes the output where mask <= 0.
-// launch_aggregate takes every row of at most kLongRow entries (all rows when n_long == 0); launch_aggregate_long
-// takes the listed long rows with one block each.
-void launch_aggregate(const int64_t *ptr, const int32_t *idx, int32_t n_long, const void *X, int bf16, int32_t d,
-                      int64_t n, int self_loop, const float *in_scale, const float *out_scale, const float *mask,
-                      float *out, hipStream_t s, hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr);
-void launch_aggregate_long(const int64_t *ptr, const int32_t *idx, const int32_t *long_rows, int32_t n_long, const void *X,
-                           int bf16, int32_t d, int self_loop, const float *in_scale, const float *out_scale,
-                           const float *mask, float *out, hipStream_t s);
+// One launch serves a batch of up to kMaxAggBatch snapshots (blockIdx.y picks the item): the layers above the
+// first aggregate every timestep of a window in one go.  launch_aggregate_batch takes every row of at most kLongRow
+// entries (all rows of an item with n_long == 0); launch_aggregate_long_batch takes the listed long rows with one
+// block each.
+void launch_aggregate_batch(const AggBatch &batch, int bf16, int32_t d, int64_t n, int self_loop, hipStream_t s,
+                            hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr);
+void launch_aggregate_long_batch(const AggBatch &batch, int bf16, int32_t d, int self_loop, hipStream_t s);
 // both, with the main kernel timed as REINC_K_AGG_FULL
+void aggregate_full_batch(reinc_ctx *ctx, const AggBatch &batch, int bf16, int32_t d, int self_loop, hipStream_t s);
 void aggregate_full(reinc_ctx *ctx, const int64_t *ptr, const int32_t *idx, const int32_t *long_rows, int32_t n_long,
                     const void *X, int bf16, int32_t d, int self_loop, const float *in_scale, const float *out_scale,
                     const float *mask, float *out, hipStream_t s);
@@ -260,9 +274,11 @@ void launch_rnn_fused(int lstm, const float *x, int64_t n, int32_t d_in, int32_t
                       float *h_out, float *c_out, float *saved, hipStream_t s);
 uint64_t reduce_partial_bytes(int64_t n, int32_t K, int32_t M);
 // partial[chunk] (+)= (row_scale .* A)^T G over the chunk's rows, with the column sums of G in row K; `accumulate`
-// adds to what the slabs hold.  launch_reduce_partials then does dW[K,M] += sum of slabs, db[M] += sum of rows K.
+// adds to what the slabs hold.  The slab geometry is that of n_geom >= n rows, so that calls over different row
+// counts can add into one set of slabs (sized by reduce_partial_bytes(n_geom, K, M)).  launch_reduce_partials
+// (with the same n_geom) then does dW[K,M] += sum of slabs, db[M] += sum of rows K.
 void launch_gemm_reduce(const float *A, int32_t lda, const float *row_scale, const float *G, int32_t ldg, int64_t n,
-                        int32_t K, int32_t M, float *partial, int accumulate, hipStream_t s);
+                        int64_t n_geom, int32_t K, int32_t M, float *partial, int accumulate, hipStream_t s);
 void launch_reduce_partials(const float *partial, int64_t n, int32_t K, int32_t M, float *dW, float *db, hipStream_t s);
 void launch_rnn_backward_elem(int lstm, int64_t n, int32_t H, const float *dh, const float *dc, const float *saved,
                               const float *h_prev, const float *c_prev, const float *c_new, float *dgi, float *dgh,

@@ -13,6 +13,8 @@
 //
 // No atomics anywhere: every output row has one writer and a fixed summation order, so results are
 // bit-reproducible from run to run.
+#include <algorithm>
+
 #include "ctx.h"
 
 namespace reinc {
@@ -176,14 +178,21 @@ aggregate_rows(const int64_t *__restrict__ ptr, const int32_t *__restrict__ idx,
 // kLongRow are left to the block path.
 template <int LPR, bool BF16>
 __global__ void __launch_bounds__(64 * kWavesPerBlock)
-aggregate_rows_grouped(const int64_t *__restrict__ ptr, const int32_t *__restrict__ idx, const void *__restrict__ X,
-                       int64_t n, int self_loop, const float *__restrict__ in_scale,
-                       const float *__restrict__ out_scale, const float *__restrict__ mask, float *__restrict__ out,
-                       int skip_long)
+aggregate_rows_grouped(AggBatch batch, int64_t n, int self_loop)
 {
     constexpr int VEC = Row<BF16>::kVec;
     constexpr int D = LPR * VEC;
     constexpr int G = 64 / LPR;
+    // blockIdx.y picks the snapshot of the batch: its graph, its input and its output
+    const AggItem &it = batch.item[blockIdx.y];
+    const int64_t *__restrict__ ptr = it.ptr;
+    const int32_t *__restrict__ idx = it.idx;
+    const void *__restrict__ X = it.X;
+    const float *__restrict__ in_scale = it.in_scale;
+    const float *__restrict__ out_scale = it.out_scale;
+    const float *__restrict__ mask = it.mask;
+    float *__restrict__ out = it.out;
+    const int skip_long = it.n_long > 0;
     const int lane = threadIdx.x & 63;
     const int g = lane / LPR, li = lane % LPR, gbase = g * LPR;
     const int64_t v = (int64_t(blockIdx.x) * kWavesPerBlock + (threadIdx.x >> 6)) * G + g;
@@ -268,16 +277,22 @@ aggregate_rows_grouped(const int64_t *__restrict__ ptr, const int32_t *__restric
 // one block of kWavesPerBlock waves per long row; wave w takes the 64-entry chunks w, w+4, ...
 template <int LPR, bool BF16>
 __global__ void __launch_bounds__(64 * kWavesPerBlock)
-aggregate_long_rows(const int32_t *__restrict__ long_rows, const int64_t *__restrict__ ptr,
-                    const int32_t *__restrict__ idx, const void *__restrict__ X, int self_loop,
-                    const float *__restrict__ in_scale, const float *__restrict__ out_scale,
-                    const float *__restrict__ mask, float *__restrict__ out)
+aggregate_long_rows(AggBatch batch, int self_loop)
 {
     constexpr int VEC = Row<BF16>::kVec;
     constexpr int D = LPR * VEC;
     __shared__ float part[kWavesPerBlock][D];
+    const AggItem &it = batch.item[blockIdx.y];
+    if (int(blockIdx.x) >= it.n_long) return;  // the grid is as wide as the batch's longest list
+    const int64_t *__restrict__ ptr = it.ptr;
+    const int32_t *__restrict__ idx = it.idx;
+    const void *__restrict__ X = it.X;
+    const float *__restrict__ in_scale = it.in_scale;
+    const float *__restrict__ out_scale = it.out_scale;
+    const float *__restrict__ mask = it.mask;
+    float *__restrict__ out = it.out;
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    const int64_t v = long_rows[blockIdx.x];
+    const int64_t v = it.long_rows[blockIdx.x];
     const int64_t beg = ptr[v], end = ptr[v + 1];
     float acc[VEC];
 #pragma unroll
@@ -491,19 +506,17 @@ inline int lanes_per_row(int32_t d, int bf16)
 }
 
 template <bool BF16>
-void aggregate_dispatch(int lpr, const int64_t *ptr, const int32_t *idx, int32_t n_long, const void *X, int64_t n,
-                        int self_loop, const float *in_scale, const float *out_scale, const float *mask, float *out,
-                        hipStream_t s, hipEvent_t ev_start, hipEvent_t ev_stop)
+void aggregate_dispatch(int lpr, const AggBatch &batch, int64_t n, int self_loop, hipStream_t s, hipEvent_t ev_start,
+                        hipEvent_t ev_stop)
 {
     const dim3 th(64 * kWavesPerBlock);
-    const int skip = n_long > 0;
-#define REINC_AGG_CASE(L)                                                                                           \
-    case L: {                                                                                                       \
-        const int64_t rows_per_block = int64_t(kWavesPerBlock) * (64 / L);                                          \
-        const unsigned blocks = unsigned((n + rows_per_block - 1) / rows_per_block);                                \
-        hipExtLaunchKernelGGL((aggregate_rows_grouped<L, BF16>), dim3(blocks), th, 0, s, ev_start, ev_stop, 0, ptr, \
-                              idx, X, n, self_loop, in_scale, out_scale, mask, out, skip);                          \
-        break;                                                                                                      \
+#define REINC_AGG_CASE(L)                                                                                          \
+    case L: {                                                                                                      \
+        const int64_t rows_per_block = int64_t(kWavesPerBlock) * (64 / L);                                         \
+        const unsigned blocks = unsigned((n + rows_per_block - 1) / rows_per_block);                               \
+        hipExtLaunchKernelGGL((aggregate_rows_grouped<L, BF16>), dim3(blocks, unsigned(batch.count)), th, 0, s,    \
+                              ev_start, ev_stop, 0, batch, n, self_loop);                                          \
+        break;                                                                                                     \
     }
     switch (lpr) {
         REINC_AGG_CASE(1)
@@ -518,15 +531,13 @@ void aggregate_dispatch(int lpr, const int64_t *ptr, const int32_t *idx, int32_t
 }
 
 template <bool BF16>
-void aggregate_long_dispatch(int lpr, const int64_t *ptr, const int32_t *idx, const int32_t *long_rows, int32_t n_long,
-                             const void *X, int self_loop, const float *in_scale, const float *out_scale,
-                             const float *mask, float *out, hipStream_t s)
+void aggregate_long_dispatch(int lpr, const AggBatch &batch, int32_t max_long, int self_loop, hipStream_t s)
 {
     const dim3 th(64 * kWavesPerBlock);
-#define REINC_AGG_CASE(L)                                                                                          \
-    case L:                                                                                                        \
-        aggregate_long_rows<L, BF16><<<unsigned(n_long), th, 0, s>>>(long_rows, ptr, idx, X, self_loop, in_scale,  \
-                                                                     out_scale, mask, out);                        \
+    const dim3 grid(unsigned(max_long), unsigned(batch.count));
+#define REINC_AGG_CASE(L)                                                         \
+    case L:                                                                       \
+        aggregate_long_rows<L, BF16><<<grid, th, 0, s>>>(batch, self_loop);       \
         break;
     switch (lpr) {
         REINC_AGG_CASE(1)
@@ -575,43 +586,47 @@ void incremental_dispatch(int lpr, const int32_t *rows, int64_t n_rows, const in
 
 bool agg_width_supported(int32_t d, int bf16) { return lanes_per_row(d, bf16) != 0; }
 
-void launch_aggregate(const int64_t *ptr, const int32_t *idx, int32_t n_long, const void *X, int bf16, int32_t d,
-                      int64_t n, int self_loop, const float *in_scale, const float *out_scale, const float *mask,
-                      float *out, hipStream_t s, hipEvent_t ev_start, hipEvent_t ev_stop)
+void launch_aggregate_batch(const AggBatch &batch, int bf16, int32_t d, int64_t n, int self_loop, hipStream_t s,
+                            hipEvent_t ev_start, hipEvent_t ev_stop)
 {
-    if (n <= 0) return;
+    if (n <= 0 || batch.count <= 0) return;
     const int lpr = lanes_per_row(d, bf16);
     if (bf16)
-        aggregate_dispatch<true>(lpr, ptr, idx, n_long, X, n, self_loop, in_scale, out_scale, mask, out, s, ev_start,
-                                 ev_stop);
+        aggregate_dispatch<true>(lpr, batch, n, self_loop, s, ev_start, ev_stop);
     else
-        aggregate_dispatch<false>(lpr, ptr, idx, n_long, X, n, self_loop, in_scale, out_scale, mask, out, s, ev_start,
-                                  ev_stop);
+        aggregate_dispatch<false>(lpr, batch, n, self_loop, s, ev_start, ev_stop);
 }
 
-void launch_aggregate_long(const int64_t *ptr, const int32_t *idx, const int32_t *long_rows, int32_t n_long, const void *X,
-                           int bf16, int32_t d, int self_loop, const float *in_scale, const float *out_scale,
-                           const float *mask, float *out, hipStream_t s)
+void launch_aggregate_long_batch(const AggBatch &batch, int bf16, int32_t d, int self_loop, hipStream_t s)
 {
-    if (n_long <= 0) return;
+    int32_t max_long = 0;
+    for (int i = 0; i < batch.count; ++i) max_long = std::max(max_long, batch.item[i].n_long);
+    if (max_long <= 0) return;
     const int lpr = lanes_per_row(d, bf16);
     if (bf16)
-        aggregate_long_dispatch<true>(lpr, ptr, idx, long_rows, n_long, X, self_loop, in_scale, out_scale, mask, out, s);
+        aggregate_long_dispatch<true>(lpr, batch, max_long, self_loop, s);
     else
-        aggregate_long_dispatch<false>(lpr, ptr, idx, long_rows, n_long, X, self_loop, in_scale, out_scale, mask, out, s);
+        aggregate_long_dispatch<false>(lpr, batch, max_long, self_loop, s);
+}
+
+void aggregate_full_batch(reinc_ctx *ctx, const AggBatch &batch, int bf16, int32_t d, int self_loop, hipStream_t s)
+{
+    {
+        // the timing events ride on the launch itself, so they carry the kernel's own begin and end
+        ProfScope prof(ctx, REINC_K_AGG_FULL, s, true);
+        launch_aggregate_batch(batch, bf16, d, ctx->cfg.num_nodes, self_loop, s, prof.start(), prof.stop());
+    }
+    launch_aggregate_long_batch(batch, bf16, d, self_loop, s);
 }
 
 void aggregate_full(reinc_ctx *ctx, const int64_t *ptr, const int32_t *idx, const int32_t *long_rows, int32_t n_long,
                     const void *X, int bf16, int32_t d, int self_loop, const float *in_scale, const float *out_scale,
                     const float *mask, float *out, hipStream_t s)
 {
-    {
-        // the timing events ride on the launch itself, so they carry the kernel's own begin and end
-        ProfScope prof(ctx, REINC_K_AGG_FULL, s, true);
-        launch_aggregate(ptr, idx, n_long, X, bf16, d, ctx->cfg.num_nodes, self_loop, in_scale, out_scale, mask, out, s,
-                         prof.start(), prof.stop());
-    }
-    launch_aggregate_long(ptr, idx, long_rows, n_long, X, bf16, d, self_loop, in_scale, out_scale, mask, out, s);
+    AggBatch batch;
+    batch.count = 1;
+    batch.item[0] = AggItem{ptr, idx, X, in_scale, out_scale, mask, out, long_rows, n_long};
+    aggregate_full_batch(ctx, batch, bf16, d, self_loop, s);
 }
 
 void launch_incremental(const int32_t *rows, int64_t n_rows, const int32_t *long_rows, int64_t n_long,

@@ -882,7 +882,9 @@ struct ReduceArgs {
 template <bool HAS_RS>
 __global__ void __launch_bounds__(256) gemm_reduce_kernel(ReduceArgs g)
 {
-    __shared__ float red[3][64 * 65];
+    // wave w finishes accumulator tile w of the 2x2: the other waves park their share of it here (two tiles at
+    // a time, to keep the block's LDS at 25 KB)
+    __shared__ float red[2][3][32 * 33];
     __shared__ float bred[4][64];
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int i = lane & 31, kk = lane >> 5;
@@ -890,16 +892,12 @@ __global__ void __launch_bounds__(256) gemm_reduce_kernel(ReduceArgs g)
     // are given to the same XCD (and to neighbouring ids), so that chunk's rows are fetched from HBM once and the
     // other slabs find them in that XCD's L2.
     const int slabs_x = (g.K + 63) / 64, slabs = slabs_x * ((g.M + 63) / 64);
-#ifdef REINC_REDUCE_SIMPLE_MAP
-    const int slab = blockIdx.x % slabs, chunk = blockIdx.x / slabs;
-#else
     const int xcd = blockIdx.x % 8, qid = blockIdx.x / 8;
     const int slab = qid % slabs, chunk = (qid / slabs) * 8 + xcd;
-#endif
     if (chunk >= g.chunks) return;
     const int f0 = (slab % slabs_x) * 64, c0 = (slab / slabs_x) * 64;
     const int64_t r_begin = int64_t(chunk) * g.rows_per_chunk;
-    const int64_t r_end = min(g.n, r_begin + g.rows_per_chunk);
+    const int64_t r_end = max(r_begin, min(g.n, r_begin + g.rows_per_chunk));  // a chunk past the last row is empty
     acc16 acc[2][2];
 #pragma unroll
     for (int a = 0; a < 2; ++a)
@@ -910,42 +908,68 @@ __global__ void __launch_bounds__(256) gemm_reduce_kernel(ReduceArgs g)
     float bsum[2] = {0.0f, 0.0f};
     const bool fa0 = f0 + i < g.K, fa1 = f0 + 32 + i < g.K;
     const bool cb0 = c0 + i < g.M, cb1 = c0 + 32 + i < g.M;
-    // wave w takes row pairs w, w+4, ... of the chunk, kRU pairs per trip.  Full trips over full 64x64 slabs run
-    // without a single branch: every load of the trip is issued before any arithmetic touches a loaded value.
+    // Wave w takes row pairs w, w+4, ... of the chunk, kRU pairs (64 rows of the block) per trip.  Full trips
+    // over full 64x64 slabs run without a branch and double-buffered: the loads of the next trip are issued
+    // before the matrix instructions of the current one, and while a next trip exists they are unconditional
+    // (a load that may or may not have been issued would force a wait for everything).
     constexpr int kRU = 8;
     int64_t base = r_begin;
     if (f0 + 64 <= g.K && c0 + 64 <= g.M) {
-        const float *ap = g.A + (base + 2 * w + kk) * g.lda + f0 + i;
-        const float *gp = g.G + (base + 2 * w + kk) * g.ldg + c0 + i;
-        const float *sp = HAS_RS ? g.row_scale + base + 2 * w + kk : nullptr;
-        for (; base + 8 * kRU <= r_end; base += 8 * kRU) {
-            float a0[kRU], a1[kRU], b0[kRU], b1[kRU], sc[kRU];
+        // wave-uniform row pointers plus one fixed 32-bit lane offset per operand: the addresses of a trip cost
+        // scalar arithmetic only
+        const int wu = __builtin_amdgcn_readfirstlane(w);
+        const float *ap = g.A + (base + 2 * wu) * g.lda + f0;
+        const float *gp = g.G + (base + 2 * wu) * g.ldg + c0;
+        const float *sp = HAS_RS ? g.row_scale + base + 2 * wu : nullptr;
+        const unsigned aoff = unsigned(kk) * unsigned(g.lda) + i, goff = unsigned(kk) * unsigned(g.ldg) + i;
+        // a trip's operands: [0] [1] = the two 32-column halves of the A rows, [2] [3] = of the G rows, [4] = row scale
+        auto load = [&](float(&t)[5][kRU]) __attribute__((always_inline)) {
 #pragma unroll
             for (int u = 0; u < kRU; ++u) {
-                a0[u] = ap[int64_t(8 * u) * g.lda];
-                a1[u] = ap[int64_t(8 * u) * g.lda + 32];
-                b0[u] = gp[int64_t(8 * u) * g.ldg];
-                b1[u] = gp[int64_t(8 * u) * g.ldg + 32];
-                sc[u] = HAS_RS ? sp[8 * u] : 1.0f;
+                const float *au = ap + int64_t(8 * u) * g.lda, *gu = gp + int64_t(8 * u) * g.ldg;
+                t[0][u] = au[aoff];
+                t[1][u] = au[aoff + 32];
+                t[2][u] = gu[goff];
+                t[3][u] = gu[goff + 32];
+                t[4][u] = HAS_RS ? sp[8 * u + kk] : 1.0f;
             }
             ap += int64_t(8 * kRU) * g.lda;
             gp += int64_t(8 * kRU) * g.ldg;
             if (HAS_RS) sp += 8 * kRU;
-            __builtin_amdgcn_sched_barrier(0);  // keep every load of the trip ahead of the arithmetic
+        };
+        auto multiply = [&](float(&t)[5][kRU]) __attribute__((always_inline)) {
 #pragma unroll
             for (int u = 0; u < kRU; ++u) {
-                if (HAS_RS) {
-                    a0[u] *= sc[u];
-                    a1[u] *= sc[u];
-                }
-                acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0[u], b0[u], acc[0][0], 0, 0, 0);
-                acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0[u], b1[u], acc[0][1], 0, 0, 0);
-                acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[u], b0[u], acc[1][0], 0, 0, 0);
-                acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[u], b1[u], acc[1][1], 0, 0, 0);
-                bsum[0] += b0[u];
-                bsum[1] += b1[u];
+                const float a0 = HAS_RS ? t[0][u] * t[4][u] : t[0][u], a1 = HAS_RS ? t[1][u] * t[4][u] : t[1][u];
+                acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, t[2][u], acc[0][0], 0, 0, 0);
+                acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, t[3][u], acc[0][1], 0, 0, 0);
+                acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, t[2][u], acc[1][0], 0, 0, 0);
+                acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, t[3][u], acc[1][1], 0, 0, 0);
+                bsum[0] += t[2][u];
+                bsum[1] += t[3][u];
             }
+        };
+        const int trips = int((r_end - r_begin) / (8 * kRU));
+        float ta[5][kRU], tb[5][kRU];
+        int t = 0;
+        if (trips > 0) load(ta);
+        for (; t + 2 < trips; t += 2) {
+            load(tb);
+            __builtin_amdgcn_sched_barrier(0);  // the loads go out ahead of the arithmetic
+            multiply(ta);
+            load(ta);
+            __builtin_amdgcn_sched_barrier(0);
+            multiply(tb);
         }
+        if (t + 1 < trips) {
+            load(tb);
+            __builtin_amdgcn_sched_barrier(0);
+            multiply(ta);
+            multiply(tb);
+        } else if (t < trips) {
+            multiply(ta);
+        }
+        base += int64_t(trips) * (8 * kRU);
     }
     // ragged slabs and the last rows of the chunk: guarded loads
     for (int64_t r0 = base + 2 * w + kk; r0 < r_end + kk; r0 += 8 * kRU) {
@@ -975,16 +999,9 @@ __global__ void __launch_bounds__(256) gemm_reduce_kernel(ReduceArgs g)
             bsum[1] += b1[u];
         }
     }
-    // combine the four waves: waves 1..3 park their slabs in LDS, wave 0 adds them in order
-#pragma unroll
-    for (int a = 0; a < 2; ++a)
-#pragma unroll
-        for (int b = 0; b < 2; ++b)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int fr = 32 * a + 8 * (r / 4) + 4 * kk + (r % 4), cc = 32 * b + i;
-                if (w > 0) red[w - 1][fr * 65 + cc] = acc[a][b][r];
-            }
+    // Combine the four waves.  Tile (a, b) is finished by wave 2a+b: the other three park their share in LDS
+    // (slot = their rank among the other waves) and the owner adds the four shares in wave order, then adds
+    // the result to the partial slab (or overwrites it).  Tiles (0, *) go first, then tiles (1, *).
     {
         const float s0 = bsum[0] + __shfl_xor(bsum[0], 32), s1 = bsum[1] + __shfl_xor(bsum[1], 32);
         if (kk == 0) {
@@ -992,32 +1009,49 @@ __global__ void __launch_bounds__(256) gemm_reduce_kernel(ReduceArgs g)
             bred[w][32 + i] = s1;
         }
     }
-    __syncthreads();
-    if (w != 0) return;
     float *out = g.partial + int64_t(chunk) * (g.K + 1) * g.M;
+    auto park = [&](const acc16 &t, int owner) __attribute__((always_inline)) {
+        float *dst = red[owner & 1][w < owner ? w : w - 1];
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+        for (int r = 0; r < 16; ++r) dst[(8 * (r / 4) + 4 * kk + (r % 4)) * 33 + i] = t[r];
+    };
+    auto finish = [&](const acc16 &mine, int a, int b) __attribute__((always_inline)) {
+        const int cc = c0 + 32 * b + i;
+        const int owner = 2 * a + b;
 #pragma unroll
-        for (int b = 0; b < 2; ++b) {
-            const int cc = 32 * b + i;
-            float old[16];
+        for (int q = 0; q < 4; ++q) {  // four rows at a time keeps the register count of the tail low
+            float old[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+            if (g.accumulate) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) old[r] = 0.0f;
-            if (g.accumulate) {  // all 16 reads of the tile go out together
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int fr = 32 * a + 8 * (r / 4) + 4 * kk + (r % 4);
-                    if (f0 + fr < g.K && c0 + cc < g.M) old[r] = out[int64_t(f0 + fr) * g.M + c0 + cc];
+                for (int e = 0; e < 4; ++e) {
+                    const int fr = f0 + 32 * a + 8 * q + 4 * kk + e;
+                    if (fr < g.K && cc < g.M) old[e] = out[int64_t(fr) * g.M + cc];
                 }
             }
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int fr = 32 * a + 8 * (r / 4) + 4 * kk + (r % 4);
-                const float v = ((acc[a][b][r] + red[0][fr * 65 + cc]) + red[1][fr * 65 + cc]) + red[2][fr * 65 + cc];
-                if (f0 + fr < g.K && c0 + cc < g.M) out[int64_t(f0 + fr) * g.M + c0 + cc] = old[r] + v;
+            for (int e = 0; e < 4; ++e) {
+                const int lr = 8 * q + 4 * kk + e;
+                float v = 0.0f;
+#pragma unroll
+                for (int ww = 0; ww < 4; ++ww)  // shares in wave order: a fixed summation order
+                    v += ww == owner ? mine[4 * q + e] : red[b][ww < owner ? ww : ww - 1][lr * 33 + i];
+                const int fr = f0 + 32 * a + lr;
+                if (fr < g.K && cc < g.M) out[int64_t(fr) * g.M + cc] = old[e] + v;
             }
         }
-    if (f0 == 0 && c0 + lane < g.M) {
+    };
+    if (w != 0) park(acc[0][0], 0);
+    if (w != 1) park(acc[0][1], 1);
+    __syncthreads();
+    if (w == 0) finish(acc[0][0], 0, 0);
+    if (w == 1) finish(acc[0][1], 0, 1);
+    __syncthreads();
+    if (w != 2) park(acc[1][0], 2);
+    if (w != 3) park(acc[1][1], 3);
+    __syncthreads();
+    if (w == 2) finish(acc[1][0], 1, 0);
+    if (w == 3) finish(acc[1][1], 1, 1);
+    if (w == 0 && f0 == 0 && c0 + lane < g.M) {
         float *o = out + int64_t(g.K) * g.M + c0 + lane;
         const float v = ((bred[0][lane] + bred[1][lane]) + bred[2][lane]) + bred[3][lane];
         *o = g.accumulate ? *o + v : v;
@@ -1203,9 +1237,13 @@ void launch_rnn_fused(int lstm, const float *x, int64_t n, int32_t d_in, int32_t
 
 int reduce_chunks(int64_t n, int32_t K, int32_t M)
 {
-    // about three blocks per compute unit, at least 256 rows each
+    // as many blocks as are resident at once (registers and LDS decide how many fit a compute unit), at least
+    // 256 rows each
+    static const int per_cu = std::max(1, std::min(resident_blocks(reinterpret_cast<const void *>(gemm_reduce_kernel<false>), 256, 0),
+                                                   resident_blocks(reinterpret_cast<const void *>(gemm_reduce_kernel<true>), 256, 0)));
     const int64_t slabs = int64_t((K + 63) / 64) * ((M + 63) / 64);
-    int64_t chunks = std::max<int64_t>(1, (768 + slabs - 1) / slabs);
+    int64_t chunks = std::max<int64_t>(1, int64_t(kNumCU) * per_cu / slabs);
+    if (chunks >= 8) chunks &= ~int64_t(7);  // the grid is padded to whole groups of 8 chunks (one per XCD): stay resident
     chunks = std::min<int64_t>(chunks, (n + 255) / 256);
     return int(std::max<int64_t>(chunks, 1));
 }
@@ -1216,11 +1254,13 @@ uint64_t reduce_partial_bytes(int64_t n, int32_t K, int32_t M)
 }
 
 void launch_gemm_reduce(const float *A, int32_t lda, const float *row_scale, const float *G, int32_t ldg, int64_t n,
-                        int32_t K, int32_t M, float *partial, int accumulate, hipStream_t s)
+                        int64_t n_geom, int32_t K, int32_t M, float *partial, int accumulate, hipStream_t s)
 {
-    if (n <= 0) return;
-    const int chunks = reduce_chunks(n, K, M);
-    int64_t rpc = (n + chunks - 1) / chunks;
+    if (n <= 0 || n_geom < n) return;
+    // the chunk geometry (how many slabs, how many rows each) belongs to n_geom rows: calls with fewer rows fill
+    // the same slabs (their last chunks see no rows and contribute zeros)
+    const int chunks = reduce_chunks(n_geom, K, M);
+    int64_t rpc = (n_geom + chunks - 1) / chunks;
     rpc = (rpc + 63) & ~int64_t(63);  // whole 64-row trips; no row pair straddles two chunks
     ReduceArgs g{A, lda, row_scale, G, ldg, n, K, M, rpc, partial, chunks, accumulate};
     const int slabs = ((K + 63) / 64) * ((M + 63) / 64);

@@ -2,6 +2,8 @@
 // consecutive snapshots is one training sample with back-propagation through time; Section 3.3: a global
 // cache for the aggregates of the input features, a local cache for per-layer intermediates).
 #include <algorithm>
+#include <initializer_list>
+#include <vector>
 
 #include "ctx.h"
 
@@ -37,28 +39,6 @@ void rnn_backward_elem(reinc_ctx *ctx, hipStream_t st, A... a)
     launch_rnn_backward_elem(a..., st);
 }
 
-// The window driver spreads independent kernels over up to three side streams (all at the default priority)
-// and orders them with events: `to` waits for everything enqueued on `from` so far.
-int ensure_side_streams(reinc_ctx *ctx)
-{
-    for (hipStream_t &st : ctx->side)
-        if (!st) REINC_HIP(ctx, hipStreamCreateWithFlags(&st, hipStreamNonBlocking));
-    if (ctx->order_events.empty()) {
-        ctx->order_events.resize(512);
-        for (hipEvent_t &e : ctx->order_events) REINC_HIP(ctx, hipEventCreateWithFlags(&e, hipEventDisableTiming));
-    }
-    return REINC_OK;
-}
-
-int order_after(reinc_ctx *ctx, hipStream_t from, hipStream_t to)
-{
-    if (from == to) return REINC_OK;
-    hipEvent_t e = ctx->order_events[ctx->order_next++ % ctx->order_events.size()];
-    REINC_HIP(ctx, hipEventRecord(e, from));
-    REINC_HIP(ctx, hipStreamWaitEvent(to, e, 0));
-    return REINC_OK;
-}
-
 struct Params {
     const float *W[REINC_MAX_GCN_LAYERS + 1] = {};
     const float *b[REINC_MAX_GCN_LAYERS + 1] = {};
@@ -92,17 +72,23 @@ Params split_params(const reinc_config &c, const float *flat)
 
 uint64_t align256(uint64_t b) { return (b + 255) & ~uint64_t(255); }
 
-uint64_t local_step_bytes(const reinc_config &c)
+// The local cache keeps every quantity as one array over the window's timesteps, so that the rows of consecutive
+// timesteps are adjacent and the dense kernels can take a whole batch of timesteps as one tall matrix.  A
+// timestep's slice is exactly n*d floats when that keeps slices 16-byte aligned, else it is padded (and the
+// driver falls back to one launch per timestep for that quantity).
+uint64_t slice_floats(uint64_t n, uint64_t d) { return (n * d) % 4 == 0 ? n * d : align256(n * d * 4) / 4; }
+
+uint64_t local_bytes(const reinc_config &c, int32_t L)
 {
-    const uint64_t n = uint64_t(c.num_nodes);
+    const uint64_t n = uint64_t(c.num_nodes), H = uint64_t(c.rnn_hidden);
     uint64_t b = 0;
     for (int l = 1; l <= c.num_gcn_layers; ++l) {
-        b += align256(n * c.dims[l] * 4);
-        if (l >= 2) b += align256(n * c.dims[l - 1] * 4);
+        b += align256(uint64_t(L) * slice_floats(n, c.dims[l]) * 4);
+        if (l >= 2) b += align256(uint64_t(L) * slice_floats(n, c.dims[l - 1]) * 4);
     }
-    b += align256(n * c.rnn_hidden * 4);                                     // h
-    if (c.rnn_kind == REINC_RNN_LSTM) b += align256(n * c.rnn_hidden * 4);   // c
-    b += align256(n * 4 * c.rnn_hidden * 4);                                 // gate values
+    b += align256(uint64_t(L + 1) * slice_floats(n, H) * 4);                                  // h, with the zero state in front
+    if (c.rnn_kind == REINC_RNN_LSTM) b += align256(uint64_t(L) * slice_floats(n, H) * 4);    // c
+    b += align256(uint64_t(L) * slice_floats(n, 4 * H) * 4);                                  // gate values
     return b;
 }
 
@@ -111,9 +97,8 @@ int ensure_local(reinc_ctx *ctx, int32_t L, hipStream_t s)
 {
     const reinc_config &c = ctx->cfg;
     if (ctx->local_L >= L && !ctx->local.empty()) return REINC_OK;
-    const uint64_t n = uint64_t(c.num_nodes);
-    const uint64_t fixed = align256(n * c.rnn_hidden * 4) + align256(loss_partial_bytes());
-    const uint64_t need = fixed + uint64_t(L) * local_step_bytes(c);
+    const uint64_t n = uint64_t(c.num_nodes), H = uint64_t(c.rnn_hidden);
+    const uint64_t need = align256(loss_partial_bytes()) + local_bytes(c, L);
     if (ctx->bottom + need > ctx->size)
         return ctx->fail(REINC_E_NOMEM, "arena exhausted: the local cache of a %d-step window needs %llu bytes", L,
                          (unsigned long long)need);
@@ -125,18 +110,30 @@ int ensure_local(reinc_ctx *ctx, int32_t L, hipStream_t s)
         p += align256(bytes);
         return reinterpret_cast<float *>(r);
     };
-    ctx->zero_state = take(n * c.rnn_hidden * 4);
     ctx->loss_partial = take(loss_partial_bytes());
     ctx->local.assign(L, LocalStep());
-    for (int32_t i = 0; i < L; ++i) {
-        LocalStep &st = ctx->local[i];
-        for (int l = 1; l <= c.num_gcn_layers; ++l) {
-            st.H[l] = take(n * c.dims[l] * 4);
-            if (l >= 2) st.S[l] = take(n * c.dims[l - 1] * 4);
+    for (int l = 1; l <= c.num_gcn_layers; ++l) {
+        const uint64_t sh = slice_floats(n, c.dims[l]);
+        float *Hl = take(uint64_t(L) * sh * 4);
+        for (int32_t i = 0; i < L; ++i) ctx->local[i].H[l] = Hl + i * sh;
+        if (l >= 2) {
+            const uint64_t ss = slice_floats(n, c.dims[l - 1]);
+            float *Sl = take(uint64_t(L) * ss * 4);
+            for (int32_t i = 0; i < L; ++i) ctx->local[i].S[l] = Sl + i * ss;
         }
-        st.h = take(n * c.rnn_hidden * 4);
-        if (c.rnn_kind == REINC_RNN_LSTM) st.c = take(n * c.rnn_hidden * 4);
-        st.saved = take(n * 4 * c.rnn_hidden * 4);
+    }
+    {
+        const uint64_t sh = slice_floats(n, H);
+        float *h = take(uint64_t(L + 1) * sh * 4);
+        ctx->zero_state = h;  // the state before timestep 0: h_{t-1} of timestep i is slice i
+        for (int32_t i = 0; i < L; ++i) ctx->local[i].h = h + (i + 1) * sh;
+        if (c.rnn_kind == REINC_RNN_LSTM) {
+            float *cs = take(uint64_t(L) * sh * 4);
+            for (int32_t i = 0; i < L; ++i) ctx->local[i].c = cs + i * sh;
+        }
+        const uint64_t sg = slice_floats(n, 4 * H);
+        float *sv = take(uint64_t(L) * sg * 4);
+        for (int32_t i = 0; i < L; ++i) ctx->local[i].saved = sv + i * sg;
     }
     ctx->local_L = L;
     ctx->local_valid = false;
@@ -201,6 +198,32 @@ int check_window(reinc_ctx *ctx, int32_t t0, int32_t L)
     return REINC_OK;
 }
 
+// Calls fn(i0, len) for every maximal run of timesteps [i0, i0 + len) of [lo, hi] whose rows are adjacent in memory in
+// each of the given per-timestep arrays: such a run is one tall matrix of n * len rows.
+struct Strip {
+    const float *const *each;  // start of every timestep's [n, row_floats] array, indexed by timestep; null: ignore
+    int64_t row_floats;
+};
+
+template <class F>
+int for_runs(int lo, int hi, int64_t n, std::initializer_list<Strip> strips, F fn)
+{
+    int i0 = lo;
+    while (i0 <= hi) {
+        int len = 1;
+        for (; i0 + len <= hi; ++len) {
+            bool adjacent = true;
+            for (const Strip &st : strips)
+                if (st.each && st.each[i0 + len] != st.each[i0 + len - 1] + n * st.row_floats) adjacent = false;
+            if (!adjacent) break;
+        }
+        const int rc = fn(i0, len);
+        if (rc != REINC_OK) return rc;
+        i0 += len;
+    }
+    return REINC_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -249,7 +272,6 @@ int reinc_forward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *par
     hipStream_t s = as_stream(stream);
     REINC_HIP(ctx, hipSetDevice(c.device));
     ctx->local_valid = false;
-    REINC_TRY(ensure_side_streams(ctx));
     REINC_TRY(ensure_local(ctx, L, s));
     ctx->scratch_reset();
     const Params p = split_params(c, params);
@@ -257,28 +279,49 @@ int reinc_forward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *par
     const int Lg = c.num_gcn_layers, H = c.rnn_hidden;
     const int lstm = c.rnn_kind == REINC_RNN_LSTM;
     const float *nof = nullptr;
-    // The GCN part of a timestep does not depend on the recurrent state; with overlap enabled it runs ahead on a
-    // side stream while the caller's stream steps the recurrent cell (the cell of snapshot t beside the GCN layers
-    // of t+1).  By default both share the caller's stream.
-    hipStream_t g = ctx->overlap ? ctx->side[0] : s;
-    REINC_TRY(order_after(ctx, s, g));
-    for (int32_t i = 0; i < L; ++i) {
-        const int32_t t = t0 + i;
-        REINC_TRY(ensure_layer1(ctx, t, g));
-        const Snapshot &sn = ctx->snaps[t];
-        LocalStep &st = ctx->local[i];
-        gemm_rows(ctx, g, (const void *)ctx->gcache[t], 0, n, c.dims[0], c.dims[1], (const float *)sn.q, p.W[1], 0, c.dims[1],
-                  p.b[1], 1, nof, nof, st.H[1]);
-        for (int l = 2; l <= Lg; ++l) {
-            aggregate_full(ctx, sn.row_ptr, sn.col, sn.long_rows, sn.n_long_rows, st.H[l - 1], 0, c.dims[l - 1], c.self_loop,
-                           sn.p, nullptr, nullptr, st.S[l], g);
-            gemm_rows(ctx, g, (const void *)st.S[l], 0, n, c.dims[l - 1], c.dims[l], (const float *)sn.q, p.W[l], 0,
-                      c.dims[l], p.b[l], 1, nof, nof, st.H[l]);
+    // Layer by layer over batches of timesteps: the dense steps see all timesteps of a batch as one tall matrix
+    // (one launch instead of one per timestep), the aggregation of a layer takes the batch's snapshots in one
+    // launch; only the layer-1 sums (a chain over snapshots) and the recurrent cell (a chain over time) go
+    // timestep by timestep.
+    std::vector<const float *> s1(L), q(L), Hp(L), Sp(L), Hout(L);
+    for (int32_t lo = 0; lo < L; lo += ctx->max_batch) {
+        const int32_t hi = std::min(L, lo + ctx->max_batch) - 1;
+        for (int32_t i = lo; i <= hi; ++i) {
+            REINC_TRY(ensure_layer1(ctx, t0 + i, s));
+            s1[i] = ctx->gcache[t0 + i];
+            q[i] = ctx->snaps[t0 + i].q;
         }
-        REINC_TRY(order_after(ctx, g, s));
-        const LocalStep *pv = i ? &ctx->local[i - 1] : nullptr;
-        rnn_fused(ctx, s, lstm, (const float *)st.H[Lg], n, c.dims[Lg], H, pv ? (const float *)pv->h : nof,
-                  pv ? (const float *)pv->c : nof, p.W_i, p.W_h, p.b_i, p.b_h, st.h, st.c, st.saved);
+        for (int l = 1; l <= Lg; ++l) {
+            if (l >= 2) {
+                AggBatch batch;
+                batch.count = hi - lo + 1;
+                for (int32_t i = lo; i <= hi; ++i) {
+                    const Snapshot &sn = ctx->snaps[t0 + i];
+                    LocalStep &st = ctx->local[i];
+                    batch.item[i - lo] = AggItem{sn.row_ptr, sn.col, st.H[l - 1], sn.p, nullptr, nullptr, st.S[l], sn.long_rows,
+                                                 sn.n_long_rows};
+                }
+                aggregate_full_batch(ctx, batch, 0, c.dims[l - 1], c.self_loop, s);
+            }
+            for (int32_t i = lo; i <= hi; ++i) {
+                Sp[i] = l == 1 ? s1[i] : ctx->local[i].S[l];
+                Hout[i] = ctx->local[i].H[l];
+            }
+            const bool has_q = q[lo] != nullptr;
+            REINC_TRY(for_runs(lo, hi, n, {Strip{Sp.data(), c.dims[l - 1]}, Strip{Hout.data(), c.dims[l]},
+                                           Strip{has_q ? q.data() : nullptr, 1}},
+                               [&](int i0, int len) {
+                                   gemm_rows(ctx, s, (const void *)Sp[i0], 0, n * len, c.dims[l - 1], c.dims[l], q[i0], p.W[l], 0,
+                                             c.dims[l], p.b[l], 1, nof, nof, const_cast<float *>(Hout[i0]));
+                                   return REINC_OK;
+                               }));
+        }
+        for (int32_t i = lo; i <= hi; ++i) {
+            LocalStep &st = ctx->local[i];
+            const LocalStep *pv = i ? &ctx->local[i - 1] : nullptr;
+            rnn_fused(ctx, s, lstm, (const float *)st.H[Lg], n, c.dims[Lg], H, pv ? (const float *)pv->h : nof,
+                      pv ? (const float *)pv->c : nof, p.W_i, p.W_h, p.b_i, p.b_h, st.h, st.c, st.saved);
+        }
     }
     const LocalStep &last = ctx->local[L - 1];
     if (target) launch_mse(last.h, target, n * H, ctx->loss_partial, loss_out, s);
@@ -300,7 +343,6 @@ int reinc_backward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *pa
     const reinc_config &c = ctx->cfg;
     hipStream_t s = as_stream(stream);
     REINC_HIP(ctx, hipSetDevice(c.device));
-    REINC_TRY(ensure_side_streams(ctx));
     const Params p = split_params(c, params);
     Params gp = split_params(c, grads);
     const int64_t n = c.num_nodes;
@@ -310,89 +352,135 @@ int reinc_backward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *pa
     int maxd = H;
     for (int l = 0; l <= Lg; ++l) maxd = std::max(maxd, c.dims[l]);
 
+    // Scratch.  The recurrent chain runs timestep by timestep; everything else of the backward pass is done for a
+    // batch of B timesteps at a time (tall matrices, one aggregation launch per layer), which needs the gate and
+    // layer gradients of B timesteps at once.  B is the largest depth (at most the window, at most kMaxAggBatch)
+    // whose buffers fit the free part of the arena.
     ctx->scratch_reset();
     auto f32 = [&](uint64_t count) { return static_cast<float *>(ctx->scratch(count * 4)); };
     float *dh = f32(uint64_t(n) * H), *dh2 = f32(uint64_t(n) * H);
     float *dc = lstm ? f32(uint64_t(n) * H) : nullptr, *dc2 = lstm ? f32(uint64_t(n) * H) : nullptr;
-    float *dgi = f32(uint64_t(n) * KH);
-    float *dgh = lstm ? dgi : f32(uint64_t(n) * KH);
-    float *dz = f32(uint64_t(n) * maxd), *dz2 = f32(uint64_t(n) * maxd), *dagg = f32(uint64_t(n) * maxd);
-    // one set of partial slabs per weight matrix: they collect all timesteps and are reduced once at the end
-    float *part_wi = static_cast<float *>(ctx->scratch(reduce_partial_bytes(n, c.dims[Lg], KH)));
-    float *part_wh = static_cast<float *>(ctx->scratch(reduce_partial_bytes(n, H, KH)));
-    float *part_w[REINC_MAX_GCN_LAYERS + 1] = {};
-    bool part_ok = part_wi && part_wh;
-    for (int l = 1; l <= Lg; ++l) {
-        part_w[l] = static_cast<float *>(ctx->scratch(reduce_partial_bytes(n, c.dims[l - 1], c.dims[l])));
-        part_ok = part_ok && part_w[l];
-    }
-    if (!dh || !dh2 || (lstm && (!dc || !dc2)) || !dgi || !dgh || !dz || !dz2 || !dagg || !part_ok) {
+    bool ok = dh && dh2 && (!lstm || (dc && dc2));
+    const uint64_t free_bytes = ok ? ctx->top - ctx->bottom : 0;
+    auto batch_bytes = [&](int B) {
+        const uint64_t rows = uint64_t(B) * uint64_t(n);
+        uint64_t b = align256(rows * KH * 4) * (lstm ? 1 : 2) + 3 * align256(rows * maxd * 4);
+        b += align256(reduce_partial_bytes(int64_t(rows), c.dims[Lg], KH)) + align256(reduce_partial_bytes(int64_t(rows), H, KH));
+        for (int l = 1; l <= Lg; ++l) b += align256(reduce_partial_bytes(int64_t(rows), c.dims[l - 1], c.dims[l]));
+        return b;
+    };
+    int B = std::min<int>(L, ctx->max_batch);
+    while (B > 1 && batch_bytes(B) > free_bytes) --B;
+    if (!ok || batch_bytes(B) > free_bytes) {
         ctx->scratch_reset();
         return ctx->fail(REINC_E_NOMEM, "arena exhausted: no room for the backward scratch buffers");
     }
-    float *g = grads;
-    launch_fill_f32(g, p.count, 0.0f, s);
+    const int64_t rowsB = int64_t(B) * n;
+    float *dgi = f32(uint64_t(rowsB) * KH);
+    float *dgh = lstm ? dgi : f32(uint64_t(rowsB) * KH);
+    float *dz = f32(uint64_t(rowsB) * maxd), *dz2 = f32(uint64_t(rowsB) * maxd), *dagg = f32(uint64_t(rowsB) * maxd);
+    // one set of partial slabs per weight matrix: they collect all batches and are reduced once at the end
+    float *part_wi = static_cast<float *>(ctx->scratch(reduce_partial_bytes(rowsB, c.dims[Lg], KH)));
+    float *part_wh = static_cast<float *>(ctx->scratch(reduce_partial_bytes(rowsB, H, KH)));
+    float *part_w[REINC_MAX_GCN_LAYERS + 1] = {};
+    bool part_ok = part_wi && part_wh;
+    for (int l = 1; l <= Lg; ++l) {
+        part_w[l] = static_cast<float *>(ctx->scratch(reduce_partial_bytes(rowsB, c.dims[l - 1], c.dims[l])));
+        part_ok = part_ok && part_w[l];
+    }
+    if (!dgi || !dgh || !dz || !dz2 || !dagg || !part_ok) {
+        ctx->scratch_reset();
+        return ctx->fail(REINC_E_NOMEM, "arena exhausted: no room for the backward scratch buffers");
+    }
+    launch_fill_f32(grads, p.count, 0.0f, s);
     launch_mse_grad(ctx->local[L - 1].h, target, n * H, dh, s);
     const float *dc_in = nullptr;  // zero at the last step
     const float *nof = nullptr;
-    // With overlap enabled, per timestep, after the elementwise gate gradients: the caller's stream carries the recurrent chain
-    // (gradient w.r.t. h_{t-1}); side 0 and side 1 take the weight-gradient reductions (each weight always on the
-    // same stream, so its partial slabs are updated in timestep order); side 2 takes the GCN backward chain.
-    hipStream_t s0 = ctx->overlap ? ctx->side[0] : s, s1 = ctx->overlap ? ctx->side[1] : s, s2 = ctx->overlap ? ctx->side[2] : s;
-    for (int32_t i = L - 1; i >= 0; --i) {
-        const int32_t t = t0 + i;
-        const Snapshot &sn = ctx->snaps[t];
-        const LocalStep &st = ctx->local[i];
-        const LocalStep *pv = i ? &ctx->local[i - 1] : nullptr;
-        rnn_backward_elem(ctx, s, lstm, n, H, (const float *)dh, dc_in, (const float *)st.saved,
-                          pv ? (const float *)pv->h : nof, pv ? (const float *)pv->c : nof, (const float *)st.c, dgi, dgh, dh2,
-                          dc2);
-        REINC_TRY(order_after(ctx, s, s0));
-        REINC_TRY(order_after(ctx, s, s1));
-        REINC_TRY(order_after(ctx, s, s2));
-        const float *x = st.H[Lg];
+    std::vector<const float *> s1(L), q(L), Ap(L), Mp(L);
+    // The partial slabs of a weight always belong to the same number of rows (B timesteps): a shorter last batch
+    // uses the chunk geometry of a full one, so that every batch adds into the same slabs.
+    auto reduce = [&](const float *A, int lda, const float *rs, const float *G, int ldg, int64_t rows, int K, int M, float *part,
+                      int accumulate) { gemm_reduce(ctx, s, A, lda, rs, G, ldg, rows, rowsB, K, M, part, accumulate); };
+    bool first_batch = true;
+    for (int32_t hi = L - 1; hi >= 0;) {
+        const int32_t lo = std::max(0, hi - B + 1);
+        const int nb = hi - lo + 1;
+        // the recurrent chain of the batch, last timestep first
+        for (int32_t i = hi; i >= lo; --i) {
+            const LocalStep &st = ctx->local[i];
+            const LocalStep *pv = i ? &ctx->local[i - 1] : nullptr;
+            float *dgi_i = dgi + int64_t(i - lo) * n * KH, *dgh_i = dgh + int64_t(i - lo) * n * KH;
+            rnn_backward_elem(ctx, s, lstm, n, H, (const float *)dh, dc_in, (const float *)st.saved,
+                              pv ? (const float *)pv->h : nof, pv ? (const float *)pv->c : nof, (const float *)st.c, dgi_i, dgh_i,
+                              dh2, dc2);
+            if (i > 0) {  // gradient w.r.t. h_{t-1}
+                gemm_rows(ctx, s, (const void *)dgh_i, 0, n, KH, H, nof, p.W_h, 1, KH, nof, 0, lstm ? nof : (const float *)dh2,
+                          nof, dh);
+                if (lstm) {
+                    std::swap(dc, dc2);  // dc now holds the gradient w.r.t. c_{t-1}; dc2 is free for the next step
+                    dc_in = dc;
+                }
+            }
+        }
+        for (int32_t i = lo; i <= hi; ++i) {
+            s1[i] = ctx->gcache[t0 + i];
+            q[i] = ctx->snaps[t0 + i].q;
+        }
+        const bool has_q = q[lo] != nullptr;
+        const int acc0 = first_batch ? 0 : 1;
         const int dl = c.dims[Lg];
-        const int later = i != L - 1;
-        gemm_reduce(ctx, s0, x, dl, nof, (const float *)dgi, KH, n, dl, KH, part_wi, later);
-        gemm_reduce(ctx, s1, pv ? (const float *)pv->h : (const float *)ctx->zero_state, H, nof, (const float *)dgh, KH, n, H, KH,
-                    part_wh, later);
-        // gradient w.r.t. the last GCN layer's pre-activation
-        gemm_rows(ctx, s2, (const void *)dgi, 0, n, KH, dl, nof, p.W_i, 1, KH, nof, 0, nof, x, dz);
-        if (i > 0) {  // gradient w.r.t. h_{t-1}
-            gemm_rows(ctx, s, (const void *)dgh, 0, n, KH, H, nof, p.W_h, 1, KH, nof, 0, lstm ? nof : (const float *)dh2, nof,
-                      dh);
-            if (lstm) {
-                std::swap(dc, dc2);  // dc now holds the gradient w.r.t. c_{t-1}
-                dc_in = dc;
-                // dc2 is free again; rnn_backward_elem writes the next dc_prev there
-            }
+        // recurrent weights: x_t = H^{Lg}_t against the x-side gate gradients, h_{t-1} against the h-side ones
+        for (int32_t i = lo; i <= hi; ++i) {
+            Ap[i] = ctx->local[i].H[Lg];
+            Mp[i] = i ? ctx->local[i - 1].h : ctx->zero_state;
         }
-        hipStream_t reader_dz2 = nullptr;  // side stream that may still read the buffer behind dz2
+        int calls = 0;
+        REINC_TRY(for_runs(lo, hi, n, {Strip{Ap.data(), dl}}, [&](int i0, int len) {
+            reduce(Ap[i0], dl, nof, dgi + int64_t(i0 - lo) * n * KH, KH, n * len, dl, KH, part_wi, acc0 | (calls++ > 0));
+            return REINC_OK;
+        }));
+        calls = 0;
+        REINC_TRY(for_runs(lo, hi, n, {Strip{Mp.data(), H}}, [&](int i0, int len) {
+            reduce(Mp[i0], H, nof, dgh + int64_t(i0 - lo) * n * KH, KH, n * len, H, KH, part_wh, acc0 | (calls++ > 0));
+            return REINC_OK;
+        }));
+        // gradient w.r.t. the last GCN layer's pre-activation, all timesteps of the batch
+        REINC_TRY(for_runs(lo, hi, n, {Strip{Ap.data(), dl}}, [&](int i0, int len) {
+            gemm_rows(ctx, s, (const void *)(dgi + int64_t(i0 - lo) * n * KH), 0, n * len, KH, dl, nof, p.W_i, 1, KH, nof, 0, nof,
+                      Ap[i0], dz + int64_t(i0 - lo) * n * dl);
+            return REINC_OK;
+        }));
         for (int l = Lg; l >= 1; --l) {
-            const float *S = l == 1 ? ctx->gcache[t] : st.S[l];
-            hipStream_t sr = (l & 1) ? s1 : s0;  // the reduction of layer l always runs on the same side stream
-            REINC_TRY(order_after(ctx, s2, sr));
-            gemm_reduce(ctx, sr, S, c.dims[l - 1], (const float *)sn.q, (const float *)dz, c.dims[l], n, c.dims[l - 1],
-                        c.dims[l], part_w[l], later);
+            const int din = c.dims[l - 1], dout = c.dims[l];
+            for (int32_t i = lo; i <= hi; ++i) Ap[i] = l == 1 ? s1[i] : ctx->local[i].S[l];
+            calls = 0;
+            REINC_TRY(for_runs(lo, hi, n, {Strip{Ap.data(), din}, Strip{has_q ? q.data() : nullptr, 1}},
+                               [&](int i0, int len) {
+                                   reduce(Ap[i0], din, q[i0], dz + int64_t(i0 - lo) * n * dout, dout, n * len, din, dout, part_w[l],
+                                          acc0 | (calls++ > 0));
+                                   return REINC_OK;
+                               }));
             if (l > 1) {
-                gemm_rows(ctx, s2, (const void *)dz, 0, n, c.dims[l], c.dims[l - 1], nof, p.W[l], 1, c.dims[l], nof, 0, nof,
-                          nof, dagg);
-                if (reader_dz2) REINC_TRY(order_after(ctx, reader_dz2, s2));
-                aggregate_full(ctx, sn.col_ptr, sn.row, sn.long_cols, sn.n_long_cols, dagg, 0, c.dims[l - 1], c.self_loop, sn.q,
-                               sn.p, st.H[l - 1], dz2, s2);
+                gemm_rows(ctx, s, (const void *)dz, 0, n * nb, dout, din, nof, p.W[l], 1, dout, nof, 0, nof, nof, dagg);
+                AggBatch batch;
+                batch.count = nb;
+                for (int32_t i = lo; i <= hi; ++i) {
+                    const Snapshot &sn = ctx->snaps[t0 + i];
+                    batch.item[i - lo] = AggItem{sn.col_ptr, sn.row, dagg + int64_t(i - lo) * n * din, sn.q, sn.p,
+                                                 ctx->local[i].H[l - 1], dz2 + int64_t(i - lo) * n * din, sn.long_cols,
+                                                 sn.n_long_cols};
+                }
+                aggregate_full_batch(ctx, batch, 0, din, c.self_loop, s);
                 std::swap(dz, dz2);
-                reader_dz2 = sr;  // this layer's reduction reads what is now dz2
             }
         }
-        // the next timestep overwrites the gate gradients and the layer scratch: everything joins first
-        REINC_TRY(order_after(ctx, s0, s));
-        REINC_TRY(order_after(ctx, s1, s));
-        REINC_TRY(order_after(ctx, s2, s));
+        first_batch = false;
+        hi = lo - 1;
     }
-    launch_reduce_partials(part_wi, n, c.dims[Lg], KH, const_cast<float *>(gp.W_i), const_cast<float *>(gp.b_i), s);
-    launch_reduce_partials(part_wh, n, H, KH, const_cast<float *>(gp.W_h), const_cast<float *>(gp.b_h), s);
+    launch_reduce_partials(part_wi, rowsB, c.dims[Lg], KH, const_cast<float *>(gp.W_i), const_cast<float *>(gp.b_i), s);
+    launch_reduce_partials(part_wh, rowsB, H, KH, const_cast<float *>(gp.W_h), const_cast<float *>(gp.b_h), s);
     for (int l = 1; l <= Lg; ++l)
-        launch_reduce_partials(part_w[l], n, c.dims[l - 1], c.dims[l], const_cast<float *>(gp.W[l]),
+        launch_reduce_partials(part_w[l], rowsB, c.dims[l - 1], c.dims[l], const_cast<float *>(gp.W[l]),
                                const_cast<float *>(gp.b[l]), s);
     REINC_HIP(ctx, hipGetLastError());
     return REINC_OK;
