@@ -21,6 +21,10 @@ typedef float acc16 __attribute__((ext_vector_type(16)));
 
 constexpr int kBK = 32;  // k values staged per LDS chunk
 
+// a float known to sit in global memory (a pointer that went through an asm barrier would otherwise be loaded with
+// address-space-generic instructions, whose completion the compiler cannot order against other loads)
+typedef float __attribute__((address_space(1))) GlobalFloat;
+
 __device__ inline float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
 
 // 16 consecutive k values of row `row` starting at k0 + 16*(lane/32); zero beyond n / K
@@ -317,7 +321,7 @@ struct NoPrefetch {
 // unit and even a slab that fills the LDS leaves the unit fully occupied.  The k chunks of all of a wave's
 // tiles form one stream; a ring of three register buffers keeps the loads two chunks (8 KB per wave) ahead of
 // the matrix cores, across tile boundaries and epilogues.  Needs K % 32 == 0 and 16-byte aligned rows; the
-// row scale is applied to the finished sums.
+// row scale is applied to the rows of A as they are consumed.
 template <int NT, int WN, int WAVES, bool BF16>
 __global__ void __launch_bounds__(64 * WAVES) gemm_rows_resident_kernel(GemmArgs g)
 {
@@ -341,33 +345,51 @@ __global__ void __launch_bounds__(64 * WAVES) gemm_rows_resident_kernel(GemmArgs
         return static_cast<const char *>(g.A) + (min(int64_t(t) * 32 + i, g.n - 1) * g.lda + 16 * kk) * ES;
     };
 
+    // The row scale travels with the chunk: every lane loads the scale of its row next to its 16 k values and
+    // multiplies them before the matrix instructions (a load in the epilogue would make the wave wait for
+    // everything in flight, once per tile).  Without a row scale the same load reads a valid dummy address and
+    // the factor is 1: the load stays unconditional, which keeps the waits on the ring exact.
+    const bool has_rs = g.row_scale != nullptr;
+    auto scale_ptr = [&](int t) __attribute__((always_inline)) {
+        return has_rs ? g.row_scale + min(int64_t(t) * 32 + i, g.n - 1) : static_cast<const float *>(g.A);
+    };
+
     // load cursor: chunk lk of tile ltile
     int ltile = first, lk = 0;
     const char *lptr = row_ptr(ltile < ntiles ? ltile : 0);
-    auto issue = [&](float(&buf)[16]) __attribute__((always_inline)) {
+    const float *lsp = scale_ptr(ltile < ntiles ? ltile : 0);
+    auto issue = [&](float(&buf)[16], float &sc) __attribute__((always_inline)) {
         if (ltile < ntiles) {
             load_a16_ptr<BF16>(lptr, buf);
+            asm volatile("" : "+v"(lsp));  // one scale load per chunk, never merged into a per-tile (conditional) one
+            sc = *(const GlobalFloat *)lsp;
             lptr += kBK * ES;
             if (++lk == kch) {
                 lk = 0;
                 ltile += stride;
-                if (ltile < ntiles) lptr = row_ptr(ltile);
+                if (ltile < ntiles) {
+                    lptr = row_ptr(ltile);
+                    lsp = scale_ptr(ltile);
+                }
             }
         }
     };
-    auto issue_always = [&](float(&buf)[16]) __attribute__((always_inline)) {  // the caller knows that the chunk exists
+    auto issue_always = [&](float(&buf)[16], float &sc) __attribute__((always_inline)) {  // the caller knows that the chunk exists
         load_a16_ptr<BF16>(lptr, buf);
+        asm volatile("" : "+v"(lsp));
+        sc = *(const GlobalFloat *)lsp;
         lptr += kBK * ES;
         if (++lk == kch) {
             lk = 0;
             ltile += stride;
             lptr = row_ptr(ltile);
+            lsp = scale_ptr(ltile);
         }
     };
     // the first two chunks of A are requested before the weight slab is staged: both fetches overlap
-    float b0[16], b1[16], b2[16];
-    issue(b0);
-    issue(b1);
+    float b0[16], b1[16], b2[16], s0 = 1.0f, s1 = 1.0f, s2 = 1.0f;
+    issue(b0, s0);
+    issue(b1, s1);
     const bool fast_stage = col0 + BN <= g.M && g.ldw % 4 == 0 && (reinterpret_cast<uintptr_t>(g.W) & 15) == 0;
     if (fast_stage && !g.wT) {
         stage_slab<BN, BN, 64 * WAVES>(Bs, g.W, g.ldw, g.K, [&](int) { return col0; });
@@ -406,9 +428,7 @@ __global__ void __launch_bounds__(64 * WAVES) gemm_rows_resident_kernel(GemmArgs
                     for (int e = 0; e < 4; ++e) {
                         const int64_t rr = min(rbase + 8 * q + e, g.n - 1);
                         o[e] = rr * g.M + c;
-                        v[e] = acc[t][4 * q + e];
-                        if (g.row_scale) v[e] *= g.row_scale[rr];
-                        v[e] += bias[t];
+                        v[e] = acc[t][4 * q + e] + bias[t];
                         if (g.relu) v[e] = fmaxf(v[e], 0.0f);
                     }
                     if (g.add) {
@@ -429,7 +449,10 @@ __global__ void __launch_bounds__(64 * WAVES) gemm_rows_resident_kernel(GemmArgs
             for (int r = 0; r < 16; ++r) acc[t][r] = 0.0f;
         }
     };
-    auto multiply = [&](float(&cur)[16]) __attribute__((always_inline)) {
+    auto multiply = [&](float(&cur)[16], float sc) __attribute__((always_inline)) {
+        const float f = has_rs ? sc : 1.0f;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) cur[e] *= f;
         mfma_chunk<NT>(cur, bp0 + kc * kBK * BN, BN, 32, acc, NoPrefetch());
         if (++kc == kch) {
             epilogue();
@@ -443,26 +466,27 @@ __global__ void __launch_bounds__(64 * WAVES) gemm_rows_resident_kernel(GemmArgs
     const int my_tiles = first < ntiles ? (ntiles - first + stride - 1) / stride : 0;
     const int steady = max(my_tiles * kch - 2, 0) / 3;
     for (int j = 0; j < steady; ++j) {
-        issue_always(b2);
+        issue_always(b2, s2);
         __builtin_amdgcn_sched_barrier(0);  // the new loads go out before this chunk's matrix instructions
-        multiply(b0);
-        issue_always(b0);
+        multiply(b0, s0);
+        issue_always(b0, s0);
         __builtin_amdgcn_sched_barrier(0);
-        multiply(b1);
-        issue_always(b1);
+        multiply(b1, s1);
+        issue_always(b1, s1);
         __builtin_amdgcn_sched_barrier(0);
-        multiply(b2);
+        multiply(b2, s2);
     }
     // the last chunks: loads only while chunks remain
-    auto step = [&](float(&cur)[16], float(&nxt)[16]) __attribute__((always_inline)) {
-        issue(nxt);
+    auto step = [&](float(&cur)[16], float &csc, float(&nxt)[16], float &nsc) __attribute__((always_inline)) {
+        const float sc = csc;
+        issue(nxt, nsc);
         __builtin_amdgcn_sched_barrier(0);
-        multiply(cur);
+        multiply(cur, sc);
     };
     while (tile < ntiles) {
-        step(b0, b2);
-        if (tile < ntiles) step(b1, b0);
-        if (tile < ntiles) step(b2, b1);
+        step(b0, s0, b2, s2);
+        if (tile < ntiles) step(b1, s1, b0, s0);
+        if (tile < ntiles) step(b2, s2, b1, s1);
     }
 }
 
@@ -1140,17 +1164,50 @@ __global__ void rnn_backward_elem_kernel(RnnBwdArgs g)
 }
 
 // ---- loss ----------------------------------------------------------------------------------------------------
-constexpr int kLossBlocks = 256;
+constexpr int kLossBlocks = 1024;
 
+// Partial sums of squared errors, one per block, in a fixed order.  VEC = 4 reads 16 bytes per lane (needs aligned
+// pointers); four independent loads per lane are in flight.
+template <int VEC>
 __global__ void __launch_bounds__(256) mse_partial_kernel(const float *h, const float *y, int64_t total, float *partial)
 {
     __shared__ float red[256];
-    float s = 0.0f;
-    for (int64_t i = blockIdx.x * int64_t(256) + threadIdx.x; i < total; i += int64_t(gridDim.x) * 256) {
-        const float e = h[i] - y[i];
-        s += e * e;
+    constexpr int U = 4;
+    const int64_t nv = total / VEC;  // whole vectors; the tail is taken by block 0 below
+    const int64_t stride = int64_t(gridDim.x) * 256;
+    float s[U] = {0.0f, 0.0f, 0.0f, 0.0f};
+    for (int64_t i0 = blockIdx.x * int64_t(256) + threadIdx.x; i0 < nv; i0 += U * stride) {
+        float a[U][VEC], b[U][VEC];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t i = min(i0 + u * stride, nv - 1);
+            if (VEC == 4) {
+                const float4 va = reinterpret_cast<const float4 *>(h)[i], vb = reinterpret_cast<const float4 *>(y)[i];
+                a[u][0] = va.x, a[u][1 % VEC] = va.y, a[u][2 % VEC] = va.z, a[u][3 % VEC] = va.w;
+                b[u][0] = vb.x, b[u][1 % VEC] = vb.y, b[u][2 % VEC] = vb.z, b[u][3 % VEC] = vb.w;
+            } else {
+                a[u][0] = h[i];
+                b[u][0] = y[i];
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (i0 + u * stride < nv) {
+#pragma unroll
+                for (int k = 0; k < VEC; ++k) {
+                    const float e = a[u][k] - b[u][k];
+                    s[u] += e * e;
+                }
+            }
+        }
     }
-    red[threadIdx.x] = s;
+    float t = (s[0] + s[1]) + (s[2] + s[3]);
+    if (blockIdx.x == 0 && threadIdx.x == 0)
+        for (int64_t i = nv * VEC; i < total; ++i) {
+            const float e = h[i] - y[i];
+            t += e * e;
+        }
+    red[threadIdx.x] = t;
     __syncthreads();
     for (int off = 128; off > 0; off >>= 1) {
         if (threadIdx.x < off) red[threadIdx.x] += red[threadIdx.x + off];
@@ -1162,13 +1219,15 @@ __global__ void __launch_bounds__(256) mse_partial_kernel(const float *h, const 
 __global__ void __launch_bounds__(256) mse_final_kernel(const float *partial, int nparts, int64_t total, float *loss)
 {
     __shared__ float red[256];
-    red[threadIdx.x] = int(threadIdx.x) < nparts ? partial[threadIdx.x] : 0.0f;
+    float t = 0.0f;
+    for (int i = threadIdx.x; i < nparts; i += 256) t += partial[i];
+    red[threadIdx.x] = t;
     __syncthreads();
     for (int off = 128; off > 0; off >>= 1) {
         if (threadIdx.x < off) red[threadIdx.x] += red[threadIdx.x + off];
         __syncthreads();
     }
-    if (threadIdx.x == 0) loss[0] = red[0] / float(total);
+    if (threadIdx.x == 0) *loss = total > 0 ? red[0] / float(total) : 0.0f;
 }
 
 __global__ void mse_grad_kernel(const float *h, const float *y, int64_t total, float *dh)
@@ -1296,7 +1355,10 @@ uint64_t loss_partial_bytes() { return kLossBlocks * sizeof(float); }
 
 void launch_mse(const float *h, const float *y, int64_t total, float *partial, float *loss, hipStream_t s)
 {
-    mse_partial_kernel<<<kLossBlocks, 256, 0, s>>>(h, y, total, partial);
+    if (((reinterpret_cast<uintptr_t>(h) | reinterpret_cast<uintptr_t>(y)) & 15) == 0)
+        mse_partial_kernel<4><<<kLossBlocks, 256, 0, s>>>(h, y, total, partial);
+    else
+        mse_partial_kernel<1><<<kLossBlocks, 256, 0, s>>>(h, y, total, partial);
     mse_final_kernel<<<1, 256, 0, s>>>(partial, kLossBlocks, total, loss);
 }
 
