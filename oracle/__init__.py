@@ -13,9 +13,13 @@ invariant; the generator's own insert/delete lists and brute force for the edge 
 torch.nn.GRUCell / LSTMCell and closed forms for the recurrent cells; finite differences and
 torch.autograd on a dense-adjacency model for the backward pass.
 
+The max / min aggregators (`oracle.minmax`) are pinned to a dense masked-adjacency formula, the max/min
+duality, closed-form special cases and the chained incremental == from-scratch invariant.
+
 Parity unpinned by the paper (pinned only to this package's own definition): the symmetric
 degree normalisation (absent from the paper), and the loss (mean squared error on a synthetic
 target instead of the paper's forecasting MAE on datasets that are not available).
 """
 from .dgnn import *  # noqa: F401,F403
 from . import incremental  # noqa: F401
+from . import minmax  # noqa: F401
