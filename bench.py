@@ -237,6 +237,42 @@ def extras(ctx, wl, seq, infos, params, target, step, step_s):
                              "algorithmic_GBps": round(fb * len(full_ms) / (sum(full_ms) * 1e-3) / 1e9, 1),
                              "hbm_frac": round(fb * len(full_ms) / (sum(full_ms) * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
     res["incremental_speedup_over_full"] = round(sum(full_ms) / sum(inc_ms), 3)
+    # max aggregation with contributing source ids (Section 3.2): from scratch versus the incremental procedure
+    # (in place; rows whose contributor was lost are aggregated from scratch inside the same call)
+    mm, cc = ctx.aggregate_full_minmax(0, "max")
+    mo, co = torch.empty_like(mm), torch.empty_like(cc)
+    tm, tc = torch.empty_like(mm), torch.empty_like(cc)
+    wk = torch.empty(2 * n + 4, dtype=torch.int32, device="cuda")
+    mm_inc, mm_full, redone = [], [], []
+
+    def timed_step_in_place(t, reps=5):
+        ts = []
+        for _ in range(reps + 1):
+            tm.copy_(mm)  # the state of step t-1, restored outside the timed region
+            tc.copy_(cc)
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            ctx.aggregate_incremental_minmax(t, "max", tm, tc, tm, tc, wk)
+            b.record()
+            torch.cuda.synchronize()
+            ts.append(a.elapsed_time(b))
+        ts = sorted(ts[1:])
+        return ts[len(ts) // 2]
+
+    for t in range(1, T):
+        mm_full.append(timed(lambda: ctx.aggregate_full_minmax(t, "max", out=mo, contrib=co)))
+        mm_inc.append(timed_step_in_place(t))
+        ctx.aggregate_incremental_minmax(t, "max", mm, cc, mm, cc, wk)  # advance the chain
+        redone.append(int(wk[0].item()))
+    mm_bytes = e_mean * (4 + d * elem) + n * (16 + 2 * d * 4)
+    res["aggregate_max"] = {
+        "full_mean_us": round(1e3 * sum(mm_full) / len(mm_full), 2),
+        "full_algorithmic_GBps": round(mm_bytes * len(mm_full) / (sum(mm_full) * 1e-3) / 1e9, 1),
+        "incremental_mean_us_in_place": round(1e3 * sum(mm_inc) / len(mm_inc), 2),
+        "rows_reaggregated_fraction_of_changed_rows": round(sum(redone) / max(sum(i["n_rows"] for i in infos), 1), 4),
+        "rows_reaggregated_fraction_of_all_rows": round(sum(redone) / (n * len(redone)), 4),
+        "incremental_speedup_over_full": round(sum(mm_full) / sum(mm_inc), 3),
+    }
     # snapshot-diff builder
     ctx.reset_derived()
     torch.cuda.synchronize()

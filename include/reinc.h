@@ -170,6 +170,32 @@ int reinc_aggregate_full(reinc_ctx *ctx, int32_t t, int transpose, const void *X
 int reinc_aggregate_incremental(reinc_ctx *ctx, int32_t t, const float *S_prev, float *S_out, float *agg_out,
                                 void *stream);
 
+/* ---- max / min aggregation (Section 3.2: aggregators that cannot be updated by subtraction) ----------------
+ * For target v and feature j, over the sources u of v's in-edges at snapshot t (and v itself when self_loop is
+ * set):  M[v, j] = max_u X[u, j] (REINC_OP_MAX) or min_u X[u, j] (REINC_OP_MIN), and C[v, j] = the source that
+ * attains it -- it names the contributing edge (C[v, j] -> v); among equal values the smallest id.  A target
+ * without any source gets M = 0 and C = -1.  No degree scaling is applied.
+ *
+ * reinc_aggregate_full_minmax, ASYNC: from scratch.  X, x_dtype, d as for reinc_aggregate_full (NULL = the stored
+ * features); out: device fp32 [N, d]; contrib: device int32 [N, d].
+ *
+ * reinc_aggregate_incremental_minmax, ASYNC: (M_t, C_t) of the stored features from (M_{t-1}, C_{t-1}), the
+ * paper's procedure: for every row of R_t, if a deleted edge or a changed source is the recorded contributor of
+ * any feature of the row, the row is aggregated from scratch; otherwise the previous result is combined with the
+ * values that arrive over inserted edges and from changed sources.  (A contributor that an arriving value has
+ * already replaced does not count as lost; rows with more than 64 delta entries are aggregated from scratch
+ * without looking.)  The outputs may be the previous buffers themselves (in place: only rows of
+ * R_t are touched) or disjoint buffers (every row is written); values and contributors must agree on that.
+ * work: device int32 [2 N + 4] scratch; on completion work[0] = number of rows aggregated from scratch.
+ * Needs reinc_build_deltas(t); the context's agg_kind only matters in that SYM adds the degree-changed nodes to
+ * the change set (more rows are then re-examined; results are the same). */
+#define REINC_OP_MAX 0
+#define REINC_OP_MIN 1
+int reinc_aggregate_full_minmax(reinc_ctx *ctx, int32_t t, int op, const void *X, int x_dtype, int32_t d, float *out,
+                                int32_t *contrib, void *stream);
+int reinc_aggregate_incremental_minmax(reinc_ctx *ctx, int32_t t, int op, const float *M_prev, const int32_t *C_prev,
+                                       float *M_out, int32_t *C_out, int32_t *work, void *stream);
+
 /* ---- dense steps ------------------------------------------------------------------------------------------
  * reinc_gcn_transform (Section 3.5, Listing 1: update = ReLU(linear(aggregate))), ASYNC.
  *   out[n, d_out] = act( (row_scale .* A)[n, d_in] * W[d_in, d_out] + b )
@@ -227,7 +253,8 @@ int reinc_get_stats(reinc_ctx *ctx, reinc_stats *out);
 #define REINC_K_REDUCE 4     /* weight-gradient reduction GEMM */
 #define REINC_K_ELEM 5       /* elementwise recurrent backward */
 #define REINC_K_DIFF 6       /* snapshot-diff count + fill */
-#define REINC_K_COUNT 7
+#define REINC_K_AGG_MINMAX 7 /* max / min aggregation (from scratch or incremental: all kernels of a call) */
+#define REINC_K_COUNT 8
 #define REINC_PROFILE_MAX_LAUNCHES 16384
 int reinc_profile_begin(reinc_ctx *ctx, uint32_t mask);
 int reinc_profile_end(reinc_ctx *ctx, int64_t *launches, double *total_ms);

@@ -66,8 +66,15 @@ def _row_from_scratch(v: int, row_ptr, col, x, op: str, self_loop: bool, m, c) -
                 c[v, j] = u
 
 
-def incremental_minmax_step(m_prev, c_prev, prev_ptr, prev_col, cur_ptr, cur_col, x_prev, x_cur, op: str, self_loop: bool):
-    """One snapshot step of the paper's procedure.  Returns (M, C, rows recomputed from scratch, rows touched)."""
+def incremental_minmax_step(m_prev, c_prev, prev_ptr, prev_col, cur_ptr, cur_col, x_prev, x_cur, op: str, self_loop: bool,
+                            arrivals_first: bool = False):
+    """One snapshot step of the paper's procedure.  Returns (M, C, rows recomputed from scratch, rows touched).
+
+    arrivals_first = False is the procedure as the paper words it: any lost contributing edge sends the target to
+    the from-scratch path.  arrivals_first = True is the refinement the HIP kernel uses: the arriving values are
+    combined first (inserted edges in ascending source order, then nothing else), and a lost source only forces
+    the from-scratch path if it is still the recorded contributor afterwards -- a contributor that an arrival has
+    already beaten (or tied with a smaller id) cannot matter any more.  Both give the from-scratch result."""
     n, d = x_cur.shape
     m, c = m_prev.copy(), c_prev.copy()
     changed: Set[int] = {int(i) for i in np.nonzero(np.any(x_prev != x_cur, axis=1))[0]}
@@ -83,6 +90,27 @@ def incremental_minmax_step(m_prev, c_prev, prev_ptr, prev_col, cur_ptr, cur_col
         if not removed and not arrived:
             continue
         touched.add(v)
+        if arrivals_first:
+            # the kernel's order: values over inserted edges first, then the lost sources are looked up (deleted
+            # edges, then changed sources, each changed source also contributing its new value as it is met)
+            mv, cv = m[v].copy(), c[v].copy()
+            for u in sorted(new - old):
+                for j in range(d):
+                    if _better(op, x_cur[u, j], u, mv[j], int(cv[j])):
+                        mv[j], cv[j] = x_cur[u, j], u
+            lost = any(int(cv[j]) in (old - new) for j in range(d))
+            for u in sorted((new & changed) - {v}) + ([v] if v in (new & changed) else []):
+                if u in old and any(int(cv[j]) == u for j in range(d)):
+                    lost = True
+                for j in range(d):
+                    if _better(op, x_cur[u, j], u, mv[j], int(cv[j])):
+                        mv[j], cv[j] = x_cur[u, j], u
+            if lost:
+                _row_from_scratch(v, cur_ptr, cur_col, x_cur, op, self_loop, m, c)
+                recomputed.add(v)
+            else:
+                m[v], c[v] = mv, cv
+            continue
         if any(int(c[v, j]) in removed for j in range(d)):
             _row_from_scratch(v, cur_ptr, cur_col, x_cur, op, self_loop, m, c)
             recomputed.add(v)

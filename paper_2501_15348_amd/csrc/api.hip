@@ -502,6 +502,69 @@ int reinc_aggregate_incremental(reinc_ctx *ctx, int32_t t, const float *S_prev, 
     return REINC_OK;
 }
 
+int reinc_aggregate_full_minmax(reinc_ctx *ctx, int32_t t, int op, const void *X, int x_dtype, int32_t d, float *out,
+                                int32_t *contrib, void *stream)
+{
+    if (!ctx) return REINC_E_ARG;
+    REINC_TRY(check_t(ctx, t));
+    const Snapshot &sn = ctx->snaps[t];
+    if (!sn.edges_loaded) return ctx->fail(REINC_E_STATE, "edges of snapshot %d are not loaded", t);
+    if (op != REINC_OP_MAX && op != REINC_OP_MIN) return ctx->fail(REINC_E_ARG, "op must be REINC_OP_MAX or REINC_OP_MIN");
+    if (!out || !contrib) return ctx->fail(REINC_E_ARG, "null output");
+    if (x_dtype != REINC_F32 && x_dtype != REINC_BF16) return ctx->fail(REINC_E_ARG, "bad x_dtype");
+    if (!X) {
+        if (!sn.feats_loaded) return ctx->fail(REINC_E_STATE, "features of snapshot %d are not loaded", t);
+        if (d != ctx->cfg.dims[0] || x_dtype != ctx->cfg.feat_dtype)
+            return ctx->fail(REINC_E_ARG, "stored features are [N, %d] of dtype %d", ctx->cfg.dims[0], ctx->cfg.feat_dtype);
+        X = sn.x;
+    }
+    if (X == out) return ctx->fail(REINC_E_ARG, "output may not alias the input");
+    if (!agg_width_supported(d, x_dtype == REINC_BF16))
+        return ctx->fail(REINC_E_UNSUPPORTED, "row of %d elements: row bytes must be a power of two in [16, 1024]", d);
+    {
+        ProfScope prof(ctx, REINC_K_AGG_MINMAX, as_stream(stream));
+        launch_minmax_full(sn.row_ptr, sn.col, sn.long_rows, sn.n_long_rows, X, x_dtype == REINC_BF16, d, ctx->N(),
+                           ctx->cfg.self_loop, op == REINC_OP_MAX, out, contrib, as_stream(stream));
+    }
+    REINC_HIP(ctx, hipGetLastError());
+    return REINC_OK;
+}
+
+int reinc_aggregate_incremental_minmax(reinc_ctx *ctx, int32_t t, int op, const float *M_prev, const int32_t *C_prev,
+                                       float *M_out, int32_t *C_out, int32_t *work, void *stream)
+{
+    if (!ctx) return REINC_E_ARG;
+    REINC_TRY(need_delta(ctx, t));
+    if (op != REINC_OP_MAX && op != REINC_OP_MIN) return ctx->fail(REINC_E_ARG, "op must be REINC_OP_MAX or REINC_OP_MIN");
+    if (!M_prev || !C_prev || !M_out || !C_out || !work) return ctx->fail(REINC_E_ARG, "null buffer");
+    const Delta &dl = ctx->deltas[t];
+    const Snapshot &sn = ctx->snaps[t];
+    const int32_t d = ctx->cfg.dims[0];
+    const uint64_t bytes = uint64_t(ctx->N()) * d * 4;
+    const bool in_place = M_out == M_prev;
+    if (in_place != (C_out == C_prev))
+        return ctx->fail(REINC_E_ARG, "values and contributors must both be updated in place or both go to new buffers");
+    if (!in_place) {
+        const char *a = reinterpret_cast<const char *>(M_prev), *b = reinterpret_cast<const char *>(M_out);
+        const char *e = reinterpret_cast<const char *>(C_prev), *f = reinterpret_cast<const char *>(C_out);
+        if ((a < b + bytes && b < a + bytes) || (e < f + bytes && f < e + bytes))
+            return ctx->fail(REINC_E_ARG, "output buffers must be the previous ones themselves or disjoint from them");
+    }
+    hipStream_t s = as_stream(stream);
+    // work: [0] rows aggregated from scratch, [1] spare, [2, N+2) hub-row marks by row id, then per-block counts
+    launch_fill_f32(reinterpret_cast<float *>(work), ctx->N() + 2, 0.0f, s);  // (bit pattern 0)
+    {
+        ProfScope prof(ctx, REINC_K_AGG_MINMAX, s);
+        const int64_t n_rows = in_place ? dl.info.n_rows : ctx->N();
+        launch_minmax_incremental(in_place ? dl.rows : nullptr, n_rows, sn.long_rows, sn.n_long_rows, dl.ent_ptr, dl.ent,
+                                  dl.changed, sn.row_ptr, sn.col, sn.x, ctx->cfg.feat_dtype == REINC_BF16, d,
+                                  ctx->cfg.self_loop, op == REINC_OP_MAX, M_prev, C_prev, M_out, C_out, work + 2,
+                                  work + 2 + ctx->N(), work, s);
+    }
+    REINC_HIP(ctx, hipGetLastError());
+    return REINC_OK;
+}
+
 int reinc_reset_derived(reinc_ctx *ctx)
 {
     if (!ctx) return REINC_E_ARG;

@@ -255,6 +255,16 @@ void aggregate_full_batch(reinc_ctx *ctx, const AggBatch &batch, int bf16, int32
 void aggregate_full(reinc_ctx *ctx, const int64_t *ptr, const int32_t *idx, const int32_t *long_rows, int32_t n_long,
                     const void *X, int bf16, int32_t d, int self_loop, const float *in_scale, const float *out_scale,
                     const float *mask, float *out, hipStream_t s);
+// max / min aggregation with contributing source ids (Section 3.2): from scratch, and the incremental step whose
+// hub rows with a lost contributor are marked in hub_flags [N] (zeroed by the caller) for the block-per-row kernel;
+// block_counts needs one int per 4 rows; *stat_out receives the number of rows aggregated from scratch
+void launch_minmax_full(const int64_t *ptr, const int32_t *idx, const int32_t *long_rows, int32_t n_long, const void *X,
+                        int bf16, int32_t d, int64_t n, int self_loop, int is_max, float *out, int32_t *contrib, hipStream_t s);
+void launch_minmax_incremental(const int32_t *rows, int64_t n_rows, const int32_t *long_rows, int32_t n_long,
+                               const int64_t *ent_ptr, const uint32_t *ent, const int32_t *changed, const int64_t *ptr,
+                               const int32_t *idx, const void *x_cur, int bf16, int32_t d, int self_loop, int is_max,
+                               const float *M_prev, const int32_t *C_prev, float *M_out, int32_t *C_out, int32_t *hub_flags,
+                               int32_t *block_counts, int32_t *stat_out, hipStream_t s);
 // rows: every changed row (those of at most kLongRow entries are taken one per lane group); long_rows: the
 // changed rows with more entries (one wavefront each)
 void launch_incremental(const int32_t *rows, int64_t n_rows, const int32_t *long_rows, int64_t n_long,

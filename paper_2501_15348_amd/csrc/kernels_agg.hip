@@ -498,6 +498,363 @@ incremental_rows_grouped(const int32_t *__restrict__ rows, int64_t n_rows, const
     }
 }
 
+// ---- max / min aggregators (Section 3.2) ----------------------------------------------------------------
+// M[v, j] = max over the sources u of v (and v itself with a self-loop) of X[u, j], C[v, j] = the source that
+// attains it (the smallest id among equals), 0 / -1 for a target without any source.  min is computed as the max
+// of the negated values (sign = -1; negation is exact), so both share one code path and one tie rule.
+// Inside the kernels "no source yet" is (m, c) = (-inf, kNoSource), which makes the update one branch-free
+// comparison chain; it is turned into the stored (0, -1) at the end.
+constexpr int32_t kNoSource = 0x7fffffff;
+
+__device__ inline void mm_update(float x, int32_t u, float &m, int32_t &c)
+{
+    const bool better = (x > m) | ((x == m) & (u < c));
+    m = better ? x : m;
+    c = better ? u : c;
+}
+
+template <int VEC>
+__device__ inline void mm_store(float *out, int32_t *contrib, int64_t v, int d, int li, float sign, float (&m)[VEC],
+                                const int32_t (&c)[VEC])
+{
+    int32_t cs[VEC];
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) {
+        const bool none = c[i] == kNoSource;
+        m[i] = none ? 0.0f : sign * m[i];
+        cs[i] = none ? -1 : c[i];
+    }
+    store_f32<VEC>(out, v, d, li, m);
+#pragma unroll
+    for (int i = 0; i < VEC; i += 4)
+        *reinterpret_cast<int4 *>(contrib + v * d + li * VEC + i) = make_int4(cs[i], cs[i + 1], cs[i + 2], cs[i + 3]);
+}
+
+// From scratch, rows of at most kLongRow entries: one row per group of LPR lanes (see aggregate_rows_grouped).
+// list == nullptr: rows 0 .. count_host-1; else the listed rows (count_dev, if given, points at their number on the
+// device: the rows that the incremental pass handed back).  Longer rows are left to minmax_long_rows.
+// The gathers of a trip are unconditional: a position past the end of the row repeats the row's last entry, which
+// a maximum does not notice.
+template <int LPR, bool BF16>
+__global__ void __launch_bounds__(64 * kWavesPerBlock)
+minmax_rows_grouped(const int32_t *__restrict__ list, const int32_t *__restrict__ count_dev, int64_t count_host,
+                    const int64_t *__restrict__ ptr, const int32_t *__restrict__ idx, const void *__restrict__ X,
+                    int self_loop, float sign, float *__restrict__ out, int32_t *__restrict__ contrib)
+{
+    constexpr int VEC = Row<BF16>::kVec;
+    constexpr int D = LPR * VEC;
+    constexpr int G = 64 / LPR;
+    const int lane = threadIdx.x & 63;
+    const int g = lane / LPR, li = lane % LPR, gbase = g * LPR;
+    const int64_t w = (int64_t(blockIdx.x) * kWavesPerBlock + (threadIdx.x >> 6)) * G + g;
+    const int64_t count = count_dev ? int64_t(*count_dev) : count_host;
+    bool live = w < count;
+    int64_t v = 0, beg = 0, end = 0;
+    if (live) {
+        v = list ? list[w] : w;
+        beg = ptr[v];
+        end = ptr[v + 1];
+    }
+    if (end - beg > kLongRow) {
+        live = false;
+        end = beg;
+    }
+    float m[VEC];
+    int32_t c[VEC];
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) {
+        m[i] = -INFINITY;
+        c[i] = kNoSource;
+    }
+    const int len = int(end - beg);
+    int maxlen = len;
+#pragma unroll
+    for (int off = LPR; off < 64; off <<= 1) maxlen = max(maxlen, __shfl_xor(maxlen, off));
+    for (int base = 0; base < maxlen; base += LPR) {
+        const int cnt = min(LPR, max(len - base, 0));
+        int32_t my_u = 0;
+        if (li < cnt) my_u = idx[beg + base + li];
+        const int cmax = min(LPR, maxlen - base);
+        const int last = max(cnt - 1, 0);
+        for (int k = 0; k < cmax; k += kUnrollGrouped) {
+            float r[kUnrollGrouped][VEC];
+            int32_t us[kUnrollGrouped];
+#pragma unroll
+            for (int j = 0; j < kUnrollGrouped; ++j) {
+                us[j] = __shfl(my_u, gbase + min(k + j, last));  // (row 0 for a group without entries: ignored below)
+                Row<BF16>::load(X, us[j], D, li, r[j]);
+            }
+            if (cnt > 0) {
+#pragma unroll
+                for (int j = 0; j < kUnrollGrouped; ++j)
+#pragma unroll
+                    for (int i = 0; i < VEC; ++i) mm_update(sign * r[j][i], us[j], m[i], c[i]);
+            }
+        }
+    }
+    if (live) {
+        if (self_loop) {
+            float r[VEC];
+            Row<BF16>::load(X, v, D, li, r);
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) mm_update(sign * r[i], int32_t(v), m[i], c[i]);
+        }
+        mm_store<VEC>(out, contrib, v, D, li, sign, m, c);
+    }
+}
+
+// From scratch, one block of kWavesPerBlock waves per listed row of any length: the long rows of a snapshot; with
+// `flags` (indexed by row id) only those that the incremental pass marked.
+// Wave w takes the 64-entry chunks w, w + kWavesPerBlock, ...; groups and waves hold disjoint subsets of the
+// sources and are combined at the end (the rule does not depend on the order).
+template <int LPR, bool BF16>
+__global__ void __launch_bounds__(64 * kWavesPerBlock)
+minmax_long_rows(const int32_t *__restrict__ list, const int32_t *__restrict__ flags,
+                 const int64_t *__restrict__ ptr, const int32_t *__restrict__ idx, const void *__restrict__ X, int self_loop,
+                 float sign, float *__restrict__ out, int32_t *__restrict__ contrib)
+{
+    constexpr int VEC = Row<BF16>::kVec;
+    constexpr int D = LPR * VEC;
+    constexpr int G = 64 / LPR;
+    __shared__ float pm[kWavesPerBlock][D];
+    __shared__ int32_t pc[kWavesPerBlock][D];
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int g = lane / LPR, li = lane % LPR;
+    const int64_t v = list[blockIdx.x];
+    if (flags && !flags[v]) return;  // the incremental pass did not ask for this row
+    const int64_t beg = ptr[v], end = ptr[v + 1];
+    float m[VEC];
+    int32_t c[VEC];
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) {
+        m[i] = -INFINITY;
+        c[i] = kNoSource;
+    }
+    for (int64_t base = beg + 64 * w; base < end; base += 64 * kWavesPerBlock) {
+        const int cnt = int(min(int64_t(64), end - base));
+        int32_t my_u = 0;
+        if (lane < cnt) my_u = idx[base + lane];
+        for (int k = 0; k < cnt; k += G * kUnroll) {
+            float r[kUnroll][VEC];
+            int32_t us[kUnroll];
+#pragma unroll
+            for (int j = 0; j < kUnroll; ++j) {  // a position past the end repeats the chunk's last entry
+                us[j] = __shfl(my_u, min(k + j * G + g, cnt - 1));
+                Row<BF16>::load(X, us[j], D, li, r[j]);
+            }
+#pragma unroll
+            for (int j = 0; j < kUnroll; ++j)
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) mm_update(sign * r[j][i], us[j], m[i], c[i]);
+        }
+    }
+    if (self_loop && w == 0 && g == 0) {
+        float r[VEC];
+        Row<BF16>::load(X, v, D, li, r);
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) mm_update(sign * r[i], int32_t(v), m[i], c[i]);
+    }
+#pragma unroll
+    for (int off = LPR; off < 64; off <<= 1)
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) {
+            const float xm = __shfl_xor(m[i], off);
+            const int32_t xc = __shfl_xor(c[i], off);
+            mm_update(xm, xc, m[i], c[i]);
+        }
+    if (lane < LPR)
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) {
+            pm[w][lane * VEC + i] = m[i];
+            pc[w][lane * VEC + i] = c[i];
+        }
+    __syncthreads();
+    if (w == 0 && lane < LPR) {
+#pragma unroll
+        for (int k = 1; k < kWavesPerBlock; ++k)
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) mm_update(pm[k][lane * VEC + i], pc[k][lane * VEC + i], m[i], c[i]);
+        mm_store<VEC>(out, contrib, v, D, li, sign, m, c);
+    }
+}
+
+// Incremental step (the paper's procedure): one changed row per group of LPR lanes.  The row's merged delta entries
+// name the sources whose contribution disappeared (deleted edges, changed sources) and those whose value is new
+// (inserted edges, changed sources), inserted edges first.  If a disappeared source is still the recorded
+// contributor of any feature when it is met (an arriving value that has already replaced it makes the loss
+// harmless), the row is aggregated from scratch: by the same lane group right away when the row has at most
+// kLongRow sources, else by the block-per-row kernel (the row is marked in `hub_flags`).  Otherwise the old result
+// combined with the new values is the answer.  Rows with more than kLongRow delta entries are aggregated from
+// scratch without looking.  rows == nullptr: every row of the graph (rows without entries are copied to the new
+// buffers).  block_counts[blockIdx.x] receives the block's number of rows aggregated from scratch.
+template <int LPR, bool BF16>
+__global__ void __launch_bounds__(64 * kWavesPerBlock)
+minmax_incremental_grouped(const int32_t *__restrict__ rows, int64_t n_rows, const int64_t *__restrict__ ent_ptr,
+                           const uint32_t *__restrict__ ent, const int32_t *__restrict__ changed,
+                           const int64_t *__restrict__ ptr, const int32_t *__restrict__ idx, const void *__restrict__ x_cur,
+                           int self_loop, float sign, const float *M_prev, const int32_t *C_prev, float *M_out, int32_t *C_out,
+                           int32_t *__restrict__ hub_flags, int32_t *__restrict__ block_counts)
+{
+    constexpr int VEC = Row<BF16>::kVec;
+    constexpr int D = LPR * VEC;
+    constexpr int G = 64 / LPR;
+    __shared__ int blk_redone;
+    if (threadIdx.x == 0) blk_redone = 0;
+    __syncthreads();
+    const int lane = threadIdx.x & 63;
+    const int g = lane / LPR, li = lane % LPR, gbase = g * LPR;
+    const int64_t w = (int64_t(blockIdx.x) * kWavesPerBlock + (threadIdx.x >> 6)) * G + g;
+    const bool live = w < n_rows;
+    int64_t v = 0, beg = 0, end = 0;
+    if (live) {
+        v = rows ? rows[w] : w;
+        beg = ent_ptr[v];
+        end = ent_ptr[v + 1];
+    }
+    const bool too_long = end - beg > kLongRow;
+    if (too_long) end = beg;
+    float m[VEC];
+    int32_t c[VEC], c0[VEC];
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) {
+        m[i] = -INFINITY;
+        c[i] = kNoSource;
+    }
+    if (live) {
+        load_f32<VEC>(M_prev, v, D, li, m);
+#pragma unroll
+        for (int i = 0; i < VEC; i += 4) {
+            const int4 t = *reinterpret_cast<const int4 *>(C_prev + v * D + li * VEC + i);
+            c[i] = t.x, c[i + 1] = t.y, c[i + 2] = t.z, c[i + 3] = t.w;
+        }
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) {  // back to the "max of sign * x" form
+            m[i] = c[i] < 0 ? -INFINITY : sign * m[i];
+            c[i] = c[i] < 0 ? kNoSource : c[i];
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) c0[i] = c[i];  // the contributors recorded before this step
+    int hit = 0;
+    const int len = int(end - beg);
+    int maxlen = len;
+#pragma unroll
+    for (int off = LPR; off < 64; off <<= 1) maxlen = max(maxlen, __shfl_xor(maxlen, off));
+    for (int base = 0; base < maxlen; base += LPR) {
+        const int cnt = min(LPR, max(len - base, 0));
+        int32_t my_u = 0, my_kind = 1;
+        if (li < cnt) {
+            const uint32_t e = ent[beg + base + li];
+            my_kind = int32_t(e >> kKindShift);
+            my_u = int32_t(e & kPayloadMask);
+            if (my_kind == 2) my_u = changed[my_u];
+        }
+        const int cmax = min(LPR, maxlen - base);
+        const int last = max(cnt - 1, 0);
+        for (int k = 0; k < cmax; k += kUnrollGrouped) {
+            float r[kUnrollGrouped][VEC];
+            int32_t us[kUnrollGrouped], kinds[kUnrollGrouped];
+#pragma unroll
+            for (int j = 0; j < kUnrollGrouped; ++j) {  // unconditional gathers; a position past the end repeats the last entry
+                us[j] = __shfl(my_u, gbase + min(k + j, last));
+                kinds[j] = __shfl(my_kind, gbase + min(k + j, last));
+                Row<BF16>::load(x_cur, us[j], D, li, r[j]);
+            }
+            if (cnt > 0) {
+#pragma unroll
+                for (int j = 0; j < kUnrollGrouped; ++j) {
+                    // a deleted edge or a changed source: its old contribution is gone; that matters if it was the
+                    // recorded contributor and no arriving value has replaced it yet
+                    // (a repeated last entry may bring its value again, but is looked up only once)
+                    const bool gone = (kinds[j] != 0) & (k + j < cnt), arrives = kinds[j] != 1;
+#pragma unroll
+                    for (int i = 0; i < VEC; ++i) {
+                        hit |= int(gone & (c0[i] == us[j]) & (c[i] == us[j]));
+                        // a deleted edge brings nothing: (-inf, kNoSource) never wins
+                        mm_update(arrives ? sign * r[j][i] : -INFINITY, arrives ? us[j] : kNoSource, m[i], c[i]);
+                    }
+                }
+            }
+        }
+    }
+    // any lane of the group may have seen the hit
+#pragma unroll
+    for (int off = 1; off < LPR; off <<= 1) hit |= __shfl_xor(hit, off);
+    const bool redo_row = live && (hit || too_long);
+    // from scratch, by the same group, when the whole row is short
+    int64_t fbeg = 0, fend = 0;
+    if (redo_row) {
+        fbeg = ptr[v];
+        fend = ptr[v + 1];
+    }
+    const bool hub = fend - fbeg > kLongRow;
+    if (hub) fend = fbeg;
+    if (redo_row) {
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) {
+            m[i] = -INFINITY;
+            c[i] = kNoSource;
+        }
+    }
+    const int flen = int(fend - fbeg);
+    int fmax = flen;
+#pragma unroll
+    for (int off = LPR; off < 64; off <<= 1) fmax = max(fmax, __shfl_xor(fmax, off));
+    for (int base = 0; base < fmax; base += LPR) {
+        const int cnt = min(LPR, max(flen - base, 0));
+        int32_t my_u = 0;
+        if (li < cnt) my_u = idx[fbeg + base + li];
+        const int cmax = min(LPR, fmax - base);
+        const int last = max(cnt - 1, 0);
+        for (int k = 0; k < cmax; k += kUnrollGrouped) {
+            float r[kUnrollGrouped][VEC];
+            int32_t us[kUnrollGrouped];
+#pragma unroll
+            for (int j = 0; j < kUnrollGrouped; ++j) {
+                us[j] = __shfl(my_u, gbase + min(k + j, last));
+                Row<BF16>::load(x_cur, us[j], D, li, r[j]);
+            }
+            if (cnt > 0) {
+#pragma unroll
+                for (int j = 0; j < kUnrollGrouped; ++j)
+#pragma unroll
+                    for (int i = 0; i < VEC; ++i) mm_update(sign * r[j][i], us[j], m[i], c[i]);
+            }
+        }
+    }
+    if (live) {
+        if (redo_row && hub) {
+            if (li == 0) hub_flags[v] = 1;  // (a plain store: thousands of atomics on one counter would serialise)
+        } else {
+            if (redo_row && self_loop) {
+                float r[VEC];
+                Row<BF16>::load(x_cur, v, D, li, r);
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) mm_update(sign * r[i], int32_t(v), m[i], c[i]);
+            }
+            if (redo_row || len > 0 || M_out != M_prev) mm_store<VEC>(M_out, C_out, v, D, li, sign, m, c);
+        }
+        if (redo_row && li == 0) atomicAdd(&blk_redone, 1);
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) block_counts[blockIdx.x] = blk_redone;
+}
+
+// work[0] = sum of the per-block counts, in a fixed order
+__global__ void __launch_bounds__(256) sum_counts_kernel(const int32_t *__restrict__ counts, int64_t n, int32_t *__restrict__ out)
+{
+    __shared__ int red[256];
+    int t = 0;
+    for (int64_t i = threadIdx.x; i < n; i += 256) t += counts[i];
+    red[threadIdx.x] = t;
+    __syncthreads();
+    for (int off = 128; off > 0; off >>= 1) {
+        if (int(threadIdx.x) < off) red[threadIdx.x] += red[threadIdx.x + off];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) *out = red[0];
+}
+
 inline int lanes_per_row(int32_t d, int bf16)
 {
     int64_t bytes = int64_t(d) * (bf16 ? 2 : 4);
@@ -582,6 +939,61 @@ void incremental_dispatch(int lpr, const int32_t *rows, int64_t n_rows, const in
 #undef REINC_INC_CASE
 }
 
+#define REINC_LPR_SWITCH(lpr, CASE) \
+    switch (lpr) {                  \
+        CASE(1)                     \
+        CASE(2)                     \
+        CASE(4)                     \
+        CASE(8)                     \
+        CASE(16)                    \
+        CASE(32)                    \
+        CASE(64)                    \
+    }
+
+template <bool BF16>
+void minmax_full_dispatch(int lpr, const int64_t *ptr, const int32_t *idx, const int32_t *long_rows, int32_t n_long,
+                          const void *X, int64_t n, int self_loop, float sign, float *out, int32_t *contrib, hipStream_t s)
+{
+    const dim3 th(64 * kWavesPerBlock);
+#define REINC_CASE(L)                                                                                                  \
+    case L: {                                                                                                          \
+        const int64_t rows_per_block = int64_t(kWavesPerBlock) * (64 / L);                                             \
+        const unsigned blocks = unsigned((n + rows_per_block - 1) / rows_per_block);                                   \
+        minmax_rows_grouped<L, BF16><<<blocks, th, 0, s>>>(nullptr, nullptr, n, ptr, idx, X, self_loop, sign, out, contrib); \
+        if (n_long > 0)                                                                                                \
+            minmax_long_rows<L, BF16><<<unsigned(n_long), th, 0, s>>>(long_rows, nullptr, ptr, idx, X, self_loop, sign,    \
+                                                                      out, contrib);                                   \
+        break;                                                                                                         \
+    }
+    REINC_LPR_SWITCH(lpr, REINC_CASE)
+#undef REINC_CASE
+}
+
+template <bool BF16>
+void minmax_incremental_dispatch(int lpr, const int32_t *rows, int64_t n_rows, const int32_t *long_rows, int32_t n_long,
+                                 const int64_t *ent_ptr, const uint32_t *ent, const int32_t *changed, const int64_t *ptr,
+                                 const int32_t *idx, const void *x_cur, int self_loop, float sign, const float *M_prev,
+                                 const int32_t *C_prev, float *M_out, int32_t *C_out, int32_t *hub_flags, int32_t *block_counts,
+                                 int32_t *stat_out, hipStream_t s)
+{
+    const dim3 th(64 * kWavesPerBlock);
+#define REINC_CASE(L)                                                                                                   \
+    case L: {                                                                                                           \
+        const int64_t rows_per_block = int64_t(kWavesPerBlock) * (64 / L);                                              \
+        const unsigned blocks = unsigned((n_rows + rows_per_block - 1) / rows_per_block);                               \
+        minmax_incremental_grouped<L, BF16><<<blocks, th, 0, s>>>(rows, n_rows, ent_ptr, ent, changed, ptr, idx, x_cur, \
+                                                                  self_loop, sign, M_prev, C_prev, M_out, C_out,        \
+                                                                  hub_flags, block_counts);                             \
+        if (n_long > 0)                                                                                                 \
+            minmax_long_rows<L, BF16><<<unsigned(n_long), th, 0, s>>>(long_rows, hub_flags, ptr, idx, x_cur, self_loop, \
+                                                                      sign, M_out, C_out);                              \
+        sum_counts_kernel<<<1, 256, 0, s>>>(block_counts, blocks, stat_out);                                            \
+        break;                                                                                                          \
+    }
+    REINC_LPR_SWITCH(lpr, REINC_CASE)
+#undef REINC_CASE
+}
+
 }  // namespace
 
 bool agg_width_supported(int32_t d, int bf16) { return lanes_per_row(d, bf16) != 0; }
@@ -642,6 +1054,35 @@ void launch_incremental(const int32_t *rows, int64_t n_rows, const int32_t *long
     else
         incremental_dispatch<false>(lpr, rows, n_rows, long_rows, n_long, ent_ptr, ent, x_prev, p_prev, dY, S_prev, S_out, q,
                                     agg_out, s);
+}
+
+void launch_minmax_full(const int64_t *ptr, const int32_t *idx, const int32_t *long_rows, int32_t n_long, const void *X,
+                        int bf16, int32_t d, int64_t n, int self_loop, int is_max, float *out, int32_t *contrib, hipStream_t s)
+{
+    if (n <= 0) return;
+    const int lpr = lanes_per_row(d, bf16);
+    const float sign = is_max ? 1.0f : -1.0f;
+    if (bf16)
+        minmax_full_dispatch<true>(lpr, ptr, idx, long_rows, n_long, X, n, self_loop, sign, out, contrib, s);
+    else
+        minmax_full_dispatch<false>(lpr, ptr, idx, long_rows, n_long, X, n, self_loop, sign, out, contrib, s);
+}
+
+void launch_minmax_incremental(const int32_t *rows, int64_t n_rows, const int32_t *long_rows, int32_t n_long,
+                               const int64_t *ent_ptr, const uint32_t *ent, const int32_t *changed, const int64_t *ptr,
+                               const int32_t *idx, const void *x_cur, int bf16, int32_t d, int self_loop, int is_max,
+                               const float *M_prev, const int32_t *C_prev, float *M_out, int32_t *C_out, int32_t *hub_flags,
+                               int32_t *block_counts, int32_t *stat_out, hipStream_t s)
+{
+    if (n_rows <= 0) return;
+    const int lpr = lanes_per_row(d, bf16);
+    const float sign = is_max ? 1.0f : -1.0f;
+    if (bf16)
+        minmax_incremental_dispatch<true>(lpr, rows, n_rows, long_rows, n_long, ent_ptr, ent, changed, ptr, idx, x_cur,
+                                          self_loop, sign, M_prev, C_prev, M_out, C_out, hub_flags, block_counts, stat_out, s);
+    else
+        minmax_incremental_dispatch<false>(lpr, rows, n_rows, long_rows, n_long, ent_ptr, ent, changed, ptr, idx, x_cur,
+                                           self_loop, sign, M_prev, C_prev, M_out, C_out, hub_flags, block_counts, stat_out, s);
 }
 
 }  // namespace reinc

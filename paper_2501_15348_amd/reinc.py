@@ -20,7 +20,8 @@ AGG = {"sum": 0, "mean": 1, "sym": 2}
 RNN = {"gru": 0, "lstm": 1}
 DTYPE = {"fp32": 0, "bf16": 1}
 MAX_GCN_LAYERS = 3
-KERNEL_KINDS = ("agg_full", "agg_inc", "gemm_rows", "rnn", "reduce", "elem", "diff")
+KERNEL_KINDS = ("agg_full", "agg_inc", "gemm_rows", "rnn", "reduce", "elem", "diff", "agg_minmax")
+OPS = {"max": 0, "min": 1}
 
 
 class Config(ctypes.Structure):
@@ -86,6 +87,8 @@ def load_library() -> ctypes.CDLL:
         "reinc_get_snapshot_csr": [p, i32, ci, p, p, ctypes.POINTER(i64)],
         "reinc_aggregate_full": [p, i32, ci, p, ci, i32, ci, p, p],
         "reinc_aggregate_incremental": [p, i32, p, p, p, p],
+        "reinc_aggregate_full_minmax": [p, i32, ci, p, ci, i32, p, p, p],
+        "reinc_aggregate_incremental_minmax": [p, i32, ci, p, p, p, p, p, p],
         "reinc_gcn_transform": [p, p, ci, i64, i32, i32, p, p, p, ci, p, p],
         "reinc_rnn_step": [p, ci, p, i64, i32, i32, p, p, p, p, p, p, p, p, p, p],
         "reinc_forward_window": [p, i32, i32, p, p, p, p, p],
@@ -284,6 +287,40 @@ class Context:
         self._ck(self.lib.reinc_aggregate_incremental(self.handle, t, _dev_ptr(s_prev), _dev_ptr(s_out),
                                                       _dev_ptr(agg_out), _stream()))
         return s_out
+
+    def aggregate_full_minmax(self, t: int, op: str, x=None, out=None, contrib=None):
+        """Max / min over the in-neighbourhood with the contributing source ids (paper Section 3.2)."""
+        import torch
+
+        if x is None:
+            d, dt = self.dims[0], DTYPE[self.feat_dtype]
+        else:
+            d = x.shape[1]
+            dt = 1 if x.dtype == torch.bfloat16 else 0
+            if x.dtype not in (torch.float32, torch.bfloat16) or x.shape[0] != self.n:
+                raise ValueError("x must be fp32 or bf16 [N, d]")
+        if out is None:
+            out = torch.empty((self.n, d), dtype=torch.float32, device=self.device)
+        if contrib is None:
+            contrib = torch.empty((self.n, d), dtype=torch.int32, device=self.device)
+        self._ck(self.lib.reinc_aggregate_full_minmax(self.handle, t, OPS[op], _dev_ptr(x), dt, d, _dev_ptr(out),
+                                                      _dev_ptr(contrib), _stream()))
+        return out, contrib
+
+    def aggregate_incremental_minmax(self, t: int, op: str, m_prev, c_prev, m_out=None, c_out=None, work=None):
+        """(M_t, C_t) from (M_{t-1}, C_{t-1}); returns (M, C, work) with work[0] = rows aggregated from scratch."""
+        import torch
+
+        shape = (self.n, self.dims[0])
+        if m_prev.dtype != torch.float32 or tuple(m_prev.shape) != shape or c_prev.dtype != torch.int32 or tuple(c_prev.shape) != shape:
+            raise ValueError("M_prev must be fp32 and C_prev int32, both [N, dims[0]]")
+        if m_out is None:
+            m_out, c_out = torch.empty_like(m_prev), torch.empty_like(c_prev)
+        if work is None:
+            work = torch.empty(2 * self.n + 4, dtype=torch.int32, device=self.device)
+        self._ck(self.lib.reinc_aggregate_incremental_minmax(self.handle, t, OPS[op], _dev_ptr(m_prev), _dev_ptr(c_prev),
+                                                             _dev_ptr(m_out), _dev_ptr(c_out), _dev_ptr(work), _stream()))
+        return m_out, c_out, work
 
     # ---- dense steps
     def gcn_transform(self, a, w, b=None, row_scale=None, relu: bool = True, out=None):

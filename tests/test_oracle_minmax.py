@@ -105,8 +105,9 @@ def test_deleting_a_non_contributor_changes_nothing_and_a_contributor_forces_a_r
     assert m4[3, 0] == 9.0 and k4[3, 0] == 0 and redo == set()
 
 
+@pytest.mark.parametrize("arrivals_first", [False, True])
 @pytest.mark.parametrize("op,self_loop,ties", [("max", True, False), ("min", False, True), ("max", False, True)])
-def test_incremental_chain_equals_from_scratch(op, self_loop, ties):
+def test_incremental_chain_equals_from_scratch(op, self_loop, ties, arrivals_first):
     wl = synth.WORKLOADS["tiny"].scaled(300, 6, edge_churn=0.05, feat_churn=0.05)
     seq = synth.make_sequence(wl)
     n = wl.num_nodes
@@ -119,7 +120,8 @@ def test_incremental_chain_equals_from_scratch(op, self_loop, ties):
     for t in range(1, wl.num_snapshots):
         before = m.copy()
         m, c, redo, touched = minmax.incremental_minmax_step(m, c, graphs[t - 1].row_ptr, graphs[t - 1].col, graphs[t].row_ptr,
-                                                             graphs[t].col, feats[t - 1], feats[t], op, self_loop)
+                                                             graphs[t].col, feats[t - 1], feats[t], op, self_loop,
+                                                             arrivals_first=arrivals_first)
         mf, cf = minmax.aggregate_minmax(graphs[t].row_ptr, graphs[t].col, feats[t], op, self_loop)
         assert np.array_equal(m, mf) and np.array_equal(c, cf), f"snapshot {t}"
         assert redo <= touched
@@ -128,3 +130,20 @@ def test_incremental_chain_equals_from_scratch(op, self_loop, ties):
         total_redo += len(redo)
         total_touched += len(touched)
     assert 0 < total_redo < total_touched  # both the fallback and the purely incremental path were exercised
+
+
+def test_applying_arrivals_first_never_recomputes_more():
+    wl = synth.WORKLOADS["tiny"].scaled(400, 5, edge_churn=0.10, feat_churn=0.05)
+    seq = synth.make_sequence(wl)
+    graphs = oracle.graphs_of(seq.edges, wl.num_nodes)
+    feats = [np.round(oracle.features_at(seq.x0, seq.feat_rows, seq.feat_vals, t).astype(np.float64) * 2) for t in range(5)]
+    m, c = minmax.aggregate_minmax(graphs[0].row_ptr, graphs[0].col, feats[0], "max", True)
+    fewer = 0
+    for t in range(1, 5):
+        args = (m, c, graphs[t - 1].row_ptr, graphs[t - 1].col, graphs[t].row_ptr, graphs[t].col, feats[t - 1], feats[t], "max", True)
+        m1, c1, redo1, _ = minmax.incremental_minmax_step(*args)
+        m2, c2, redo2, _ = minmax.incremental_minmax_step(*args, arrivals_first=True)
+        assert np.array_equal(m1, m2) and np.array_equal(c1, c2) and redo2 <= redo1
+        fewer += len(redo1) - len(redo2)
+        m, c = m1, c1
+    assert fewer > 0
