@@ -34,6 +34,8 @@ __all__ = [
     "graphs_of",
     "forward_window",
     "backward_window",
+    "forward_window_integrated",
+    "backward_window_integrated",
     "AGG_MODES",
 ]
 
@@ -365,4 +367,97 @@ def backward_window(
                 dagg = dz @ p[f"W{l}"].T
                 dhl = aggregate_adjoint(g.row_ptr, g.col, dagg, mode, self_loop)
         dh = dh_prev
+    return grads
+
+
+# ----------------------------------------------------------------------------- the integrated model
+
+
+def forward_window_integrated(
+    graphs: Sequence[Graph],
+    feats: Sequence[np.ndarray],
+    params: Dict[str, np.ndarray],
+    mode: str,
+    self_loop: bool,
+    rnn: str,
+    target: Optional[np.ndarray] = None,
+    keep: bool = False,
+):
+    """Forward over one window of the integrated model (Section 2.1: a GraphRNN replaces the matrix products of
+    the recurrent gates by graph operations on x_t and h_{t-1}; Section 3.1, reuse across gates: the inputs are
+    aggregated once and the hidden states once, and all gates share the two aggregates).  Per timestep
+        ax = Agg(X_t; G_t),   ah = Agg(h_{t-1}; G_t),
+        h_t = cell(x = ax, h = ah)  with the carry term taken from the un-aggregated state:
+        GRU:  h_t = (1 - z) * n + z * h_{t-1};    LSTM:  c_t = f * c_{t-1} + i * g,  h_t = o * tanh(c_t).
+    params: W_i [d0, K*H], W_h [H, K*H], b_i, b_h.  Zero initial state; loss = mean((h_last - target)^2)."""
+    p = _f64(params)
+    n = graphs[0].n
+    hd = p["W_h"].shape[0]
+    h = np.zeros((n, hd))
+    c = np.zeros((n, hd))
+    saved = []
+    for g, x in zip(graphs, feats):
+        _, ax = aggregate(g.row_ptr, g.col, np.asarray(x, dtype=np.float64), mode, self_loop)
+        _, ah = aggregate(g.row_ptr, g.col, h, mode, self_loop)
+        if rnn == "gru":
+            h_cell, gates = gru_cell(ax, ah, p["W_i"], p["W_h"], p["b_i"], p["b_h"])
+            z = gates[1]
+            h_new = h_cell - z * ah + z * h  # the cell's carry z * (its h input) replaced by z * h_{t-1}
+            c_new = c
+        else:
+            h_new, c_new, gates = lstm_cell(ax, ah, c, p["W_i"], p["W_h"], p["b_i"], p["b_h"])
+        if keep:
+            saved.append(dict(ax=ax, ah=ah, h_prev=h, c_prev=c, c_new=c_new, gates=gates))
+        h, c = h_new, c_new
+    loss = None
+    if target is not None:
+        loss = float(np.mean((h - np.asarray(target, dtype=np.float64)) ** 2))
+    return loss, h, saved
+
+
+def backward_window_integrated(
+    graphs: Sequence[Graph],
+    saved,
+    h_last: np.ndarray,
+    params: Dict[str, np.ndarray],
+    mode: str,
+    self_loop: bool,
+    rnn: str,
+    target: np.ndarray,
+) -> Dict[str, np.ndarray]:
+    """Back-propagation through time for forward_window_integrated.  The gradient reaches h_{t-1} over two paths:
+    the carry term, and the aggregate ah through the adjoint of the aggregation."""
+    p = _f64(params)
+    grads = {k: np.zeros_like(v) for k, v in p.items()}
+    tgt = np.asarray(target, dtype=np.float64)
+    dh = 2.0 * (h_last - tgt) / tgt.size
+    dc = np.zeros_like(dh)
+    for g, sv in zip(reversed(list(graphs)), reversed(saved)):
+        ax, ah, h_prev = sv["ax"], sv["ah"], sv["h_prev"]
+        if rnn == "gru":
+            r, z, nn, ghn = sv["gates"]
+            dn_pre = dh * (1.0 - z) * (1.0 - nn * nn)
+            dz_pre = dh * (h_prev - nn) * z * (1.0 - z)
+            dr_pre = dn_pre * ghn * r * (1.0 - r)
+            dgi = np.concatenate([dr_pre, dz_pre, dn_pre], axis=1)
+            dgh = np.concatenate([dr_pre, dz_pre, dn_pre * r], axis=1)
+            carry = dh * z
+        else:
+            i, f, gg, o = sv["gates"]
+            tc = np.tanh(sv["c_new"])
+            dcc = dc + dh * o * (1.0 - tc * tc)
+            do_pre = dh * tc * o * (1.0 - o)
+            di_pre = dcc * gg * i * (1.0 - i)
+            df_pre = dcc * sv["c_prev"] * f * (1.0 - f)
+            dg_pre = dcc * i * (1.0 - gg * gg)
+            dgi = np.concatenate([di_pre, df_pre, dg_pre, do_pre], axis=1)
+            dgh = dgi
+            carry = 0.0
+            dc = dcc * f
+        grads["W_i"] += ax.T @ dgi
+        grads["W_h"] += ah.T @ dgh
+        grads["b_i"] += dgi.sum(axis=0)
+        grads["b_h"] += dgh.sum(axis=0)
+        dah = dgh @ p["W_h"].T
+        dh = carry + aggregate_adjoint(g.row_ptr, g.col, dah, mode, self_loop)
     return grads
