@@ -301,6 +301,27 @@ def extras(ctx, wl, seq, infos, params, target, step, step_s):
     torch.cuda.synchronize()
     res["warm_epoch_ms"] = round((time.perf_counter() - t0) * 1e3, 3)
     res["cold_epoch_ms"] = round(step_s * 1e3, 3)
+    # the integrated model (graph operations inside the recurrent gates): warm epoch, same windows
+    import dataclasses
+
+    from paper_2501_15348_amd import synth
+
+    wli = dataclasses.replace(wl, dims=(wl.dims[0],))
+    pi = torch.from_numpy(synth.make_params(wli)).cuda()
+    gi = torch.empty_like(pi)
+
+    def epoch_integrated():
+        for t0_ in range(T - L + 1):
+            ctx.forward_window_integrated(t0_, L, pi, target, loss)
+            ctx.backward_window_integrated(t0_, L, pi, target, gi)
+            ctx.sgd_step(pi, gi, 1e-2)
+
+    epoch_integrated()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    epoch_integrated()
+    torch.cuda.synchronize()
+    res["integrated_model_warm_epoch_ms"] = round((time.perf_counter() - t0) * 1e3, 3)
     return res
 
 

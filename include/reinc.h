@@ -229,6 +229,21 @@ int reinc_forward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *par
  * reinc_forward_window call (same t0, L, params, target).  grads: device, same layout as params, overwritten. */
 int reinc_backward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *params, const float *target,
                           float *grads, void *stream);
+/* The integrated model (Section 2.1: a GraphRNN replaces the matrix products inside the recurrent gates by graph
+ * operations on x_t and h_{t-1}; Section 3.1, reuse across gates: both are aggregated once per timestep and all
+ * gates share the two aggregates).  Per timestep
+ *     ax = Agg(X_t; G_t)      -- the layer-1 aggregate of the stored features: global cache / Eq. 2, as above
+ *     ah = Agg(h_{t-1}; G_t)  -- from scratch (the state changes everywhere), kept in the local cache
+ *     gates from ax W_i + b_i and ah W_h + b_h with the cell equations of reinc_rnn_step, the carry term on the
+ *     un-aggregated state:  GRU h_t = (1 - z) n + z h_{t-1};  LSTM c_t = f c_{t-1} + i g, h_t = o tanh(c_t).
+ * The GCN layer fields of the configuration are not used (dims[0] is the feature width).  params / grads: W_i
+ * [dims[0], K*H], W_h [H, K*H], b_i [K*H], b_h [K*H], flat in this order.  rnn_hidden * 4 must be a power of two
+ * between 16 and 1024 bytes.  Other arguments and the ASYNC / state rules as for reinc_forward_window /
+ * reinc_backward_window (the backward call needs the integrated forward call of the same window). */
+int reinc_forward_window_integrated(reinc_ctx *ctx, int32_t t0, int32_t L, const float *params, const float *target,
+                                    float *loss_out, float *h_last, void *stream);
+int reinc_backward_window_integrated(reinc_ctx *ctx, int32_t t0, int32_t L, const float *params, const float *target,
+                                     float *grads, void *stream);
 /* params[i] -= lr * grads[i] for count fp32 values (plain SGD; the paper names no optimiser), ASYNC. */
 int reinc_sgd_step(reinc_ctx *ctx, float *params, const float *grads, int64_t count, float lr, void *stream);
 /* Drops every cached layer-1 sum (the next windows recompute them). */

@@ -579,6 +579,7 @@ int reinc_reset_derived(reinc_ctx *ctx)
     std::fill(ctx->gcache.begin(), ctx->gcache.end(), nullptr);
     ctx->local.clear();
     ctx->local_L = 0;
+    ctx->local_kind = 0;
     ctx->local_valid = false;
     ctx->local_reserved = 0;
     ctx->zero_state = nullptr;

@@ -71,6 +71,7 @@ struct AggItem {
     const int32_t *idx;
     const void *X;
     const float *in_scale, *out_scale, *mask;
+    const float *add;  // [n, d] or null: added to the finished row (after scaling and masking)
     float *out;
     const int32_t *long_rows;
     int32_t n_long;
@@ -104,6 +105,7 @@ struct reinc_ctx {
     uint64_t local_reserved = 0;  // bytes at the top of the arena held by the local cache
     bool local_valid = false;
     int32_t local_t0 = -1, local_L = 0;
+    int local_kind = 0;  // which model carved the local cache: 0 = stacked (GCN layers, then the cell), 1 = integrated
     float *zero_state = nullptr;  // [N, H] zeros: the recurrent state before the first timestep of a window
     float *q_block = nullptr;     // [T, N] target-side degree scales of all snapshots (null for SUM)
     int max_batch = reinc::kMaxAggBatch;  // timesteps the window driver handles per launch (REINC_BATCH=1..8 lowers it)
@@ -279,9 +281,11 @@ void launch_row_long_flags(const int64_t *ent_ptr, int64_t n, int32_t *flag, hip
 int launch_gemm_rows(const void *A, int a_bf16, int64_t n, int32_t K, int32_t M, const float *row_scale, const float *W,
                      int w_transposed, int32_t ldw, const float *bias, int relu, const float *add, const float *mask,
                      float *out, hipStream_t s);
-void launch_rnn_fused(int lstm, const float *x, int64_t n, int32_t d_in, int32_t H, const float *h_prev,
-                      const float *c_prev, const float *W_i, const float *W_h, const float *b_i, const float *b_h,
-                      float *h_out, float *c_out, float *saved, hipStream_t s);
+// x_scale [n] (or null) multiplies the rows of x; h_prev is the recurrent GEMM operand, h_carry the state of the GRU
+// carry term z .* h (the stacked model passes the same pointer for both)
+void launch_rnn_fused(int lstm, const float *x, const float *x_scale, int64_t n, int32_t d_in, int32_t H, const float *h_prev,
+                      const float *h_carry, const float *c_prev, const float *W_i, const float *W_h, const float *b_i,
+                      const float *b_h, float *h_out, float *c_out, float *saved, hipStream_t s);
 uint64_t reduce_partial_bytes(int64_t n, int32_t K, int32_t M);
 // partial[chunk] (+)= (row_scale .* A)^T G over the chunk's rows, with the column sums of G in row K; `accumulate`
 // adds to what the slabs hold.  The slab geometry is that of n_geom >= n rows, so that calls over different row

@@ -1,11 +1,10 @@
 // Neighbourhood aggregation kernels (paper Section 3.2).
 //
-//   aggregate_rows / aggregate_long_rows : Eq. 1, from scratch.  One wavefront per output row; the
-//       wave loads 64 column indices at a time with one coalesced read and hands them round with
-//       lane shuffles; a row of d values is read by LPR = d*sizeof(elem)/16 lanes as one 16-byte
-//       load each, so 64/LPR source rows are in flight per load instruction and U of those
-//       instructions are issued back to back.  Rows with more than kLongRow entries are skipped
-//       and taken by a 4-wave block with an LDS reduction (power-law hubs).
+//   aggregate_long_rows : Eq. 1, from scratch, rows with more than kLongRow entries (power-law hubs): a 4-wave
+//       block per row with an LDS reduction.  A wave loads 64 column indices at a time with one coalesced
+//       read and hands them round with lane shuffles; a row of d values is read by LPR = d*sizeof(elem)/16
+//       lanes as one 16-byte load each, so 64/LPR source rows are in flight per load instruction and U of
+//       those instructions are issued back to back.
 //   aggregate_rows_grouped / incremental_rows_grouped : the same sums with one row per group of LPR lanes, for
 //       rows of at most kLongRow entries (the bulk of a power-law graph): more independent chains per wave.
 //   incremental_rows : Eq. 2 in the form  S_t[r] = S_{t-1}[r] + sum_ins Y_{t-1}[u] - sum_del Y_{t-1}[u]
@@ -131,48 +130,6 @@ __device__ inline void reduce_groups(float (&acc)[VEC])
         for (int i = 0; i < VEC; ++i) acc[i] += __shfl_xor(acc[i], off);
 }
 
-template <int LPR, bool BF16>
-__global__ void __launch_bounds__(64 * kWavesPerBlock)
-aggregate_rows(const int64_t *__restrict__ ptr, const int32_t *__restrict__ idx, const void *__restrict__ X, int64_t n,
-               int self_loop, const float *__restrict__ in_scale, const float *__restrict__ out_scale,
-               const float *__restrict__ mask, float *__restrict__ out, int skip_long)
-{
-    constexpr int VEC = Row<BF16>::kVec;
-    constexpr int D = LPR * VEC;
-    const int lane = threadIdx.x & 63;
-    const int64_t v = int64_t(blockIdx.x) * kWavesPerBlock + (threadIdx.x >> 6);
-    if (v >= n) return;
-    const int64_t beg = ptr[v], end = ptr[v + 1];
-    if (skip_long && end - beg > kLongRow) return;
-    float acc[VEC];
-#pragma unroll
-    for (int i = 0; i < VEC; ++i) acc[i] = 0.0f;
-    gather_segment<LPR, BF16>(idx, beg, end, 64, X, in_scale, D, lane, acc);
-    reduce_groups<LPR, VEC>(acc);
-    if (lane < LPR) {
-        if (self_loop) {
-            float r[VEC];
-            Row<BF16>::load(X, v, D, lane, r);
-            const float sc = in_scale ? in_scale[v] : 1.0f;
-#pragma unroll
-            for (int i = 0; i < VEC; ++i) acc[i] += sc * r[i];
-        }
-        if (out_scale) {
-            const float q = out_scale[v];
-#pragma unroll
-            for (int i = 0; i < VEC; ++i) acc[i] *= q;
-        }
-        if (mask) {
-            float m[VEC];
-            load_f32<VEC>(mask, v, D, lane, m);
-#pragma unroll
-            for (int i = 0; i < VEC; ++i)
-                if (!(m[i] > 0.0f)) acc[i] = 0.0f;
-        }
-        store_f32<VEC>(out, v, D, lane, acc);
-    }
-}
-
 // Short rows: every group of LPR lanes owns one output row, so a wave keeps 64/LPR independent
 // row-pointer -> column-id -> source-row chains in flight and writes with all 64 lanes.  Rows longer than
 // kLongRow are left to the block path.
@@ -191,6 +148,7 @@ aggregate_rows_grouped(AggBatch batch, int64_t n, int self_loop)
     const float *__restrict__ in_scale = it.in_scale;
     const float *__restrict__ out_scale = it.out_scale;
     const float *__restrict__ mask = it.mask;
+    const float *__restrict__ add = it.add;
     float *__restrict__ out = it.out;
     const int skip_long = it.n_long > 0;
     const int lane = threadIdx.x & 63;
@@ -270,6 +228,12 @@ aggregate_rows_grouped(AggBatch batch, int64_t n, int self_loop)
             for (int i = 0; i < VEC; ++i)
                 if (!(m[i] > 0.0f)) acc[i] = 0.0f;
         }
+        if (add) {
+            float a[VEC];
+            load_f32<VEC>(add, v, D, li, a);
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) acc[i] += a[i];
+        }
         store_f32<VEC>(out, v, D, li, acc);
     }
 }
@@ -290,6 +254,7 @@ aggregate_long_rows(AggBatch batch, int self_loop)
     const float *__restrict__ in_scale = it.in_scale;
     const float *__restrict__ out_scale = it.out_scale;
     const float *__restrict__ mask = it.mask;
+    const float *__restrict__ add = it.add;
     float *__restrict__ out = it.out;
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int64_t v = it.long_rows[blockIdx.x];
@@ -328,6 +293,12 @@ aggregate_long_rows(AggBatch batch, int self_loop)
 #pragma unroll
             for (int i = 0; i < VEC; ++i)
                 if (!(m[i] > 0.0f)) acc[i] = 0.0f;
+        }
+        if (add) {
+            float a[VEC];
+            load_f32<VEC>(add, v, D, lane, a);
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) acc[i] += a[i];
         }
         store_f32<VEC>(out, v, D, lane, acc);
     }
@@ -1037,7 +1008,7 @@ void aggregate_full(reinc_ctx *ctx, const int64_t *ptr, const int32_t *idx, cons
 {
     AggBatch batch;
     batch.count = 1;
-    batch.item[0] = AggItem{ptr, idx, X, in_scale, out_scale, mask, out, long_rows, n_long};
+    batch.item[0] = AggItem{ptr, idx, X, in_scale, out_scale, mask, nullptr, out, long_rows, n_long};
     aggregate_full_batch(ctx, batch, bf16, d, self_loop, s);
 }
 

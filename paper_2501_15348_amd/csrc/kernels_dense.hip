@@ -551,6 +551,8 @@ struct RnnArgs {
     int64_t n;
     int d_in, H;
     const float *h_prev, *c_prev;  // may be null (zero state)
+    const float *x_scale;          // [n] or null: every row of x is multiplied by its scale first
+    const float *h_carry;          // GRU: the state in the carry term z .* h (normally h_prev itself; null = zero)
     const float *W_i, *W_h, *b_i, *b_h;
     float *h_out, *c_out, *saved;
 };
@@ -593,7 +595,8 @@ __global__ void __launch_bounds__(256) rnn_fused_kernel(RnnArgs g)
         const bool vec_ok = (K % 4) == 0;
         for (int k0 = 0; k0 < K; k0 += kBK) {
             float a[16];
-            load_a16<false>(A, row, g.n, K, k0, K, vec_ok, 1.0f, a);
+            const float sc = (part == 0 && g.x_scale && row < g.n) ? g.x_scale[row] : 1.0f;
+            load_a16<false>(A, row, g.n, K, k0, K, vec_ok, sc, a);
             __syncthreads();
             stage_b(Bs, LDB, NC, W, ldw, false, k0, K, col_of);
             __syncthreads();
@@ -649,7 +652,7 @@ __global__ void __launch_bounds__(256) rnn_fused_kernel(RnnArgs g)
             const float gz = sigmoidf_(acc[1][r] + bi[1] + bh[1]);
             const float ghn = acc[3][r] + bh[2];
             const float gn = tanhf_(acc[2][r] + bi[2] + gr * ghn);
-            const float hp = g.h_prev ? g.h_prev[o] : 0.0f;
+            const float hp = g.h_carry ? g.h_carry[o] : 0.0f;
             g.h_out[o] = (1.0f - gz) * gn + gz * hp;
             if (g.saved) {
                 float *sv = g.saved + rr * 4 * H + j;
@@ -692,9 +695,15 @@ __global__ void __launch_bounds__(64 * WAVES) rnn_fused_resident_kernel(RnnArgs 
     auto h_ptr = [&](int t) __attribute__((always_inline)) {
         return reinterpret_cast<const char *>(g.h_prev) + (min(int64_t(t) * 32 + i, g.n - 1) * H + 16 * kk) * 4;
     };
+    // the row scale of x travels with its chunks (see gemm_rows_resident_kernel); chunks of h_prev carry a 1
+    const bool has_xs = g.x_scale != nullptr;
+    auto xs_ptr = [&](int t) __attribute__((always_inline)) {
+        return has_xs ? g.x_scale + min(int64_t(t) * 32 + i, g.n - 1) : g.x;
+    };
     // load cursor: chunk lk of tile ltile (chunks 0 .. kx-1 come from x, the rest from h_prev)
     int ltile = first, lk = 0;
     const char *lptr = x_ptr(ltile < ntiles ? ltile : 0);
+    const float *lsp = xs_ptr(ltile < ntiles ? ltile : 0);
     auto advance = [&](bool more) __attribute__((always_inline)) {
         lptr += kBK * 4;
         ++lk;
@@ -702,23 +711,30 @@ __global__ void __launch_bounds__(64 * WAVES) rnn_fused_resident_kernel(RnnArgs 
         if (lk == kch) {
             lk = 0;
             ltile += stride;
-            if (more) lptr = x_ptr(ltile);
+            if (more) {
+                lptr = x_ptr(ltile);
+                lsp = xs_ptr(ltile);
+            }
         }
     };
-    auto issue = [&](float(&buf)[16]) __attribute__((always_inline)) {
+    auto issue = [&](float(&buf)[16], float &sc) __attribute__((always_inline)) {
         if (ltile < ntiles) {
             load_a16_ptr<false>(lptr, buf);
+            asm volatile("" : "+v"(lsp));  // one scale load per chunk, never merged into a conditional one
+            sc = *(const GlobalFloat *)lsp;
             advance(ltile + stride < ntiles || lk + 1 < kch);
         }
     };
-    auto issue_always = [&](float(&buf)[16]) __attribute__((always_inline)) {  // the caller knows that the chunk exists
+    auto issue_always = [&](float(&buf)[16], float &sc) __attribute__((always_inline)) {  // the caller knows that the chunk exists
         load_a16_ptr<false>(lptr, buf);
+        asm volatile("" : "+v"(lsp));
+        sc = *(const GlobalFloat *)lsp;
         advance(true);
     };
     // the first two chunks are requested before the slabs are staged: the fetches overlap
-    float b0[16], b1[16], b2[16];
-    issue(b0);
-    issue(b1);
+    float b0[16], b1[16], b2[16], s0 = 1.0f, s1 = 1.0f, s2 = 1.0f;
+    issue(b0, s0);
+    issue(b1, s1);
     const bool fast_stage = h0 + BH <= H && H % 4 == 0 && (reinterpret_cast<uintptr_t>(g.W_i) & 15) == 0 &&
                             (reinterpret_cast<uintptr_t>(g.W_h) & 15) == 0;
     if (fast_stage) {
@@ -749,7 +765,7 @@ __global__ void __launch_bounds__(64 * WAVES) rnn_fused_resident_kernel(RnnArgs 
         }
     }
     const float *bp0 = Bs + (16 * kk) * NC + wn * 32 + i;
-    const float *pstate = LSTM ? g.c_prev : g.h_prev;
+    const float *pstate = LSTM ? g.c_prev : g.h_carry;
     // compute cursor; accumulators: LSTM i, f, g, o (x and h parts summed); GRU r, z (summed), h part of n, x part of n
     int tile = first, kc = 0;
     acc16 acc[4];
@@ -813,8 +829,11 @@ __global__ void __launch_bounds__(64 * WAVES) rnn_fused_resident_kernel(RnnArgs 
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[t][r] = 0.0f;
     };
-    auto multiply = [&](float(&cur)[16]) __attribute__((always_inline)) {
+    auto multiply = [&](float(&cur)[16], float sc) __attribute__((always_inline)) {
         const float *bp = bp0 + kc * kBK * NC;
+        const float f = (has_xs && kc < kx) ? sc : 1.0f;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) cur[e] *= f;
         mfma_chunk_map<KG, KG - 1, G>(cur, bp, NC, BH, acc, NoPrefetch());
         ++kc;
         if (!LSTM && kc == kx) {  // GRU: the x part of the n gate is complete; the h part starts from zero
@@ -832,25 +851,26 @@ __global__ void __launch_bounds__(64 * WAVES) rnn_fused_resident_kernel(RnnArgs 
     const int my_tiles = first < ntiles ? (ntiles - first + stride - 1) / stride : 0;
     const int steady = max(my_tiles * kch - 2, 0) / 3;
     for (int it = 0; it < steady; ++it) {
-        issue_always(b2);
+        issue_always(b2, s2);
         __builtin_amdgcn_sched_barrier(0);
-        multiply(b0);
-        issue_always(b0);
+        multiply(b0, s0);
+        issue_always(b0, s0);
         __builtin_amdgcn_sched_barrier(0);
-        multiply(b1);
-        issue_always(b1);
+        multiply(b1, s1);
+        issue_always(b1, s1);
         __builtin_amdgcn_sched_barrier(0);
-        multiply(b2);
+        multiply(b2, s2);
     }
-    auto step = [&](float(&cur)[16], float(&nxt)[16]) __attribute__((always_inline)) {
-        issue(nxt);
+    auto step = [&](float(&cur)[16], float &csc, float(&nxt)[16], float &nsc) __attribute__((always_inline)) {
+        const float sc = csc;
+        issue(nxt, nsc);
         __builtin_amdgcn_sched_barrier(0);
-        multiply(cur);
+        multiply(cur, sc);
     };
     while (tile < ntiles) {
-        step(b0, b2);
-        if (tile < ntiles) step(b1, b0);
-        if (tile < ntiles) step(b2, b1);
+        step(b0, s0, b2, s2);
+        if (tile < ntiles) step(b1, s1, b0, s0);
+        if (tile < ntiles) step(b2, s2, b1, s1);
     }
 }
 
@@ -1270,12 +1290,12 @@ int launch_gemm_rows(const void *A, int a_bf16, int64_t n, int32_t K, int32_t M,
     return 0;
 }
 
-void launch_rnn_fused(int lstm, const float *x, int64_t n, int32_t d_in, int32_t H, const float *h_prev,
-                      const float *c_prev, const float *W_i, const float *W_h, const float *b_i, const float *b_h,
-                      float *h_out, float *c_out, float *saved, hipStream_t s)
+void launch_rnn_fused(int lstm, const float *x, const float *x_scale, int64_t n, int32_t d_in, int32_t H, const float *h_prev,
+                      const float *h_carry, const float *c_prev, const float *W_i, const float *W_h, const float *b_i,
+                      const float *b_h, float *h_out, float *c_out, float *saved, hipStream_t s)
 {
     if (n <= 0) return;
-    RnnArgs g{x, n, d_in, H, h_prev, c_prev, W_i, W_h, b_i, b_h, h_out, c_out, saved};
+    RnnArgs g{x, n, d_in, H, h_prev, c_prev, x_scale, h_carry, W_i, W_h, b_i, b_h, h_out, c_out, saved};
     if (lstm ? rnn_fused_resident_dispatch<true>(g, s) : rnn_fused_resident_dispatch<false>(g, s)) return;
 #define REINC_RNN_LAUNCH(WM, WN)                                                                    \
     do {                                                                                            \

@@ -96,7 +96,7 @@ uint64_t local_bytes(const reinc_config &c, int32_t L)
 int ensure_local(reinc_ctx *ctx, int32_t L, hipStream_t s)
 {
     const reinc_config &c = ctx->cfg;
-    if (ctx->local_L >= L && !ctx->local.empty()) return REINC_OK;
+    if (ctx->local_kind == 0 && ctx->local_L >= L && !ctx->local.empty()) return REINC_OK;
     const uint64_t n = uint64_t(c.num_nodes), H = uint64_t(c.rnn_hidden);
     const uint64_t need = align256(loss_partial_bytes()) + local_bytes(c, L);
     if (ctx->bottom + need > ctx->size)
@@ -136,9 +136,53 @@ int ensure_local(reinc_ctx *ctx, int32_t L, hipStream_t s)
         for (int32_t i = 0; i < L; ++i) ctx->local[i].saved = sv + i * sg;
     }
     ctx->local_L = L;
+    ctx->local_kind = 0;
     ctx->local_valid = false;
     ctx->stats.local_bytes = int64_t(need);
     launch_fill_f32(ctx->zero_state, int64_t(n) * c.rnn_hidden, 0.0f, s);
+    return REINC_OK;
+}
+
+// Local cache of the integrated model: per timestep the aggregated hidden state Agg(h_{t-1}) (kept in LocalStep::S[1];
+// slice 0 stays zero: the state before the window is zero), the state h (zero state in front), c, the gate values.
+int ensure_local_integrated(reinc_ctx *ctx, int32_t L, hipStream_t s)
+{
+    const reinc_config &c = ctx->cfg;
+    if (ctx->local_kind == 1 && ctx->local_L >= L && !ctx->local.empty()) return REINC_OK;
+    const uint64_t n = uint64_t(c.num_nodes), H = uint64_t(c.rnn_hidden);
+    const uint64_t sh = slice_floats(n, H), sg = slice_floats(n, 4 * H);
+    const bool lstm = c.rnn_kind == REINC_RNN_LSTM;
+    const uint64_t need = align256(loss_partial_bytes()) + align256(uint64_t(L) * sh * 4) + align256(uint64_t(L + 1) * sh * 4) +
+                          (lstm ? align256(uint64_t(L) * sh * 4) : 0) + align256(uint64_t(L) * sg * 4);
+    if (ctx->bottom + need > ctx->size)
+        return ctx->fail(REINC_E_NOMEM, "arena exhausted: the local cache of a %d-step window needs %llu bytes", L,
+                         (unsigned long long)need);
+    ctx->local_reserved = need;
+    ctx->scratch_reset();
+    char *p = ctx->base + (ctx->size - need);
+    auto take = [&](uint64_t bytes) {
+        char *r = p;
+        p += align256(bytes);
+        return reinterpret_cast<float *>(r);
+    };
+    ctx->loss_partial = take(loss_partial_bytes());
+    ctx->local.assign(L, LocalStep());
+    float *ah = take(uint64_t(L) * sh * 4), *h = take(uint64_t(L + 1) * sh * 4);
+    float *cs = lstm ? take(uint64_t(L) * sh * 4) : nullptr;
+    float *sv = take(uint64_t(L) * sg * 4);
+    ctx->zero_state = h;
+    for (int32_t i = 0; i < L; ++i) {
+        ctx->local[i].S[1] = ah + i * sh;
+        ctx->local[i].h = h + (i + 1) * sh;
+        ctx->local[i].c = cs ? cs + i * sh : nullptr;
+        ctx->local[i].saved = sv + i * sg;
+    }
+    ctx->local_L = L;
+    ctx->local_kind = 1;
+    ctx->local_valid = false;
+    ctx->stats.local_bytes = int64_t(need);
+    launch_fill_f32(ctx->zero_state, int64_t(n) * c.rnn_hidden, 0.0f, s);
+    launch_fill_f32(ah, int64_t(n) * c.rnn_hidden, 0.0f, s);
     return REINC_OK;
 }
 
@@ -252,8 +296,8 @@ int reinc_rnn_step(reinc_ctx *ctx, int rnn_kind, const float *x, int64_t n, int3
     if (rnn_kind == REINC_RNN_LSTM && !c_out) return ctx->fail(REINC_E_ARG, "an LSTM step needs c_out");
     if (n < 0 || d_in <= 0 || H <= 0) return ctx->fail(REINC_E_ARG, "bad shape");
     if (h_out == h_prev || (c_out && c_out == c_prev)) return ctx->fail(REINC_E_ARG, "state outputs may not alias the previous state");
-    rnn_fused(ctx, as_stream(stream), int(rnn_kind == REINC_RNN_LSTM), x, n, d_in, H, h_prev, c_prev, W_i, W_h, b_i, b_h,
-              h_out, c_out, saved);
+    rnn_fused(ctx, as_stream(stream), int(rnn_kind == REINC_RNN_LSTM), x, static_cast<const float *>(nullptr), n, d_in, H, h_prev,
+              h_prev, c_prev, W_i, W_h, b_i, b_h, h_out, c_out, saved);
     REINC_HIP(ctx, hipGetLastError());
     return REINC_OK;
 }
@@ -298,7 +342,7 @@ int reinc_forward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *par
                 for (int32_t i = lo; i <= hi; ++i) {
                     const Snapshot &sn = ctx->snaps[t0 + i];
                     LocalStep &st = ctx->local[i];
-                    batch.item[i - lo] = AggItem{sn.row_ptr, sn.col, st.H[l - 1], sn.p, nullptr, nullptr, st.S[l], sn.long_rows,
+                    batch.item[i - lo] = AggItem{sn.row_ptr, sn.col, st.H[l - 1], sn.p, nullptr, nullptr, nullptr, st.S[l], sn.long_rows,
                                                  sn.n_long_rows};
                 }
                 aggregate_full_batch(ctx, batch, 0, c.dims[l - 1], c.self_loop, s);
@@ -319,8 +363,9 @@ int reinc_forward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *par
         for (int32_t i = lo; i <= hi; ++i) {
             LocalStep &st = ctx->local[i];
             const LocalStep *pv = i ? &ctx->local[i - 1] : nullptr;
-            rnn_fused(ctx, s, lstm, (const float *)st.H[Lg], n, c.dims[Lg], H, pv ? (const float *)pv->h : nof,
-                      pv ? (const float *)pv->c : nof, p.W_i, p.W_h, p.b_i, p.b_h, st.h, st.c, st.saved);
+            const float *hp = pv ? (const float *)pv->h : nof;
+            rnn_fused(ctx, s, lstm, (const float *)st.H[Lg], nof, n, c.dims[Lg], H, hp, hp, pv ? (const float *)pv->c : nof,
+                      p.W_i, p.W_h, p.b_i, p.b_h, st.h, st.c, st.saved);
         }
     }
     const LocalStep &last = ctx->local[L - 1];
@@ -338,7 +383,7 @@ int reinc_backward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *pa
     if (!ctx) return REINC_E_ARG;
     REINC_TRY(check_window(ctx, t0, L));
     if (!params || !target || !grads) return ctx->fail(REINC_E_ARG, "null params, target or grads");
-    if (!ctx->local_valid || ctx->local_t0 != t0 || int32_t(ctx->local.size()) < L)
+    if (!ctx->local_valid || ctx->local_kind != 0 || ctx->local_t0 != t0 || int32_t(ctx->local.size()) < L)
         return ctx->fail(REINC_E_STATE, "backward needs the forward pass of the same window [%d, %d) first", t0, t0 + L);
     const reinc_config &c = ctx->cfg;
     hipStream_t s = as_stream(stream);
@@ -467,7 +512,7 @@ int reinc_backward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *pa
                 for (int32_t i = lo; i <= hi; ++i) {
                     const Snapshot &sn = ctx->snaps[t0 + i];
                     batch.item[i - lo] = AggItem{sn.col_ptr, sn.row, dagg + int64_t(i - lo) * n * din, sn.q, sn.p,
-                                                 ctx->local[i].H[l - 1], dz2 + int64_t(i - lo) * n * din, sn.long_cols,
+                                                 ctx->local[i].H[l - 1], nullptr, dz2 + int64_t(i - lo) * n * din, sn.long_cols,
                                                  sn.n_long_cols};
                 }
                 aggregate_full_batch(ctx, batch, 0, din, c.self_loop, s);
@@ -482,6 +527,154 @@ int reinc_backward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *pa
     for (int l = 1; l <= Lg; ++l)
         launch_reduce_partials(part_w[l], rowsB, c.dims[l - 1], c.dims[l], const_cast<float *>(gp.W[l]),
                                const_cast<float *>(gp.b[l]), s);
+    REINC_HIP(ctx, hipGetLastError());
+    return REINC_OK;
+}
+
+// ---- the integrated model (Section 2.1: graph operations on x_t and h_{t-1} inside the recurrent gates; Section 3.1:
+// both are aggregated once per timestep and shared by all gates).  params: W_i [dims[0], K*H], W_h [H, K*H], b_i, b_h.
+int reinc_forward_window_integrated(reinc_ctx *ctx, int32_t t0, int32_t L, const float *params, const float *target,
+                                    float *loss_out, float *h_last, void *stream)
+{
+    if (!ctx) return REINC_E_ARG;
+    REINC_TRY(check_window(ctx, t0, L));
+    if (!params) return ctx->fail(REINC_E_ARG, "null parameter vector");
+    if (target && !loss_out) return ctx->fail(REINC_E_ARG, "a target needs loss_out");
+    const reinc_config &c = ctx->cfg;
+    const int H = c.rnn_hidden;
+    if (!agg_width_supported(H, 0))
+        return ctx->fail(REINC_E_UNSUPPORTED, "hidden width %d: row bytes must be a power of two in [16, 1024]", H);
+    hipStream_t s = as_stream(stream);
+    REINC_HIP(ctx, hipSetDevice(c.device));
+    ctx->local_valid = false;
+    REINC_TRY(ensure_local_integrated(ctx, L, s));
+    ctx->scratch_reset();
+    const int64_t n = c.num_nodes;
+    const int lstm = c.rnn_kind == REINC_RNN_LSTM;
+    const int64_t KH = int64_t(lstm ? 4 : 3) * H;
+    const float *W_i = params, *W_h = W_i + int64_t(c.dims[0]) * KH, *b_i = W_h + int64_t(H) * KH, *b_h = b_i + KH;
+    const float *nof = nullptr;
+    for (int32_t i = 0; i < L; ++i) {
+        const int32_t t = t0 + i;
+        REINC_TRY(ensure_layer1(ctx, t, s));  // Agg(X_t): from the global cache, by Eq. 2, or from scratch
+        const Snapshot &sn = ctx->snaps[t];
+        LocalStep &st = ctx->local[i];
+        const LocalStep *pv = i ? &ctx->local[i - 1] : nullptr;
+        if (pv)  // Agg(h_{t-1}) over snapshot t; at the first timestep the state, and with it the aggregate, is zero
+            aggregate_full(ctx, sn.row_ptr, sn.col, sn.long_rows, sn.n_long_rows, pv->h, 0, H, c.self_loop, sn.p, sn.q, nullptr,
+                           st.S[1], s);
+        rnn_fused(ctx, s, lstm, (const float *)ctx->gcache[t], (const float *)sn.q, n, c.dims[0], H,
+                  pv ? (const float *)st.S[1] : nof, pv ? (const float *)pv->h : nof, pv ? (const float *)pv->c : nof, W_i, W_h,
+                  b_i, b_h, st.h, st.c, st.saved);
+    }
+    const LocalStep &last = ctx->local[L - 1];
+    if (target) launch_mse(last.h, target, n * H, ctx->loss_partial, loss_out, s);
+    if (h_last) REINC_HIP(ctx, hipMemcpyAsync(h_last, last.h, uint64_t(n) * H * 4, hipMemcpyDeviceToDevice, s));
+    REINC_HIP(ctx, hipGetLastError());
+    ctx->local_valid = true;
+    ctx->local_t0 = t0;
+    return REINC_OK;
+}
+
+int reinc_backward_window_integrated(reinc_ctx *ctx, int32_t t0, int32_t L, const float *params, const float *target,
+                                     float *grads, void *stream)
+{
+    if (!ctx) return REINC_E_ARG;
+    REINC_TRY(check_window(ctx, t0, L));
+    if (!params || !target || !grads) return ctx->fail(REINC_E_ARG, "null params, target or grads");
+    if (!ctx->local_valid || ctx->local_kind != 1 || ctx->local_t0 != t0 || int32_t(ctx->local.size()) < L)
+        return ctx->fail(REINC_E_STATE, "backward needs the integrated forward pass of the same window [%d, %d) first", t0, t0 + L);
+    const reinc_config &c = ctx->cfg;
+    hipStream_t s = as_stream(stream);
+    REINC_HIP(ctx, hipSetDevice(c.device));
+    const int64_t n = c.num_nodes;
+    const int H = c.rnn_hidden, d0 = c.dims[0];
+    const int lstm = c.rnn_kind == REINC_RNN_LSTM;
+    const int KH = (lstm ? 4 : 3) * H;
+    const float *W_h = params + int64_t(d0) * KH;
+    float *gW_i = grads, *gW_h = gW_i + int64_t(d0) * KH, *gb_i = gW_h + int64_t(H) * KH, *gb_h = gb_i + KH;
+    const int64_t count = int64_t(d0 + H + 2) * KH;
+
+    ctx->scratch_reset();
+    auto f32 = [&](uint64_t cnt) { return static_cast<float *>(ctx->scratch(cnt * 4)); };
+    float *dh = f32(uint64_t(n) * H), *dh2 = f32(uint64_t(n) * H), *dah = f32(uint64_t(n) * H);
+    float *dc = lstm ? f32(uint64_t(n) * H) : nullptr, *dc2 = lstm ? f32(uint64_t(n) * H) : nullptr;
+    bool ok = dh && dh2 && dah && (!lstm || (dc && dc2));
+    const uint64_t free_bytes = ok ? ctx->top - ctx->bottom : 0;
+    auto batch_bytes = [&](int B) {
+        const uint64_t rows = uint64_t(B) * uint64_t(n);
+        return align256(rows * KH * 4) * (lstm ? 1 : 2) + align256(reduce_partial_bytes(int64_t(rows), d0, KH)) +
+               align256(reduce_partial_bytes(int64_t(rows), H, KH));
+    };
+    int B = std::min<int>(L, ctx->max_batch);
+    while (B > 1 && batch_bytes(B) > free_bytes) --B;
+    if (!ok || batch_bytes(B) > free_bytes) {
+        ctx->scratch_reset();
+        return ctx->fail(REINC_E_NOMEM, "arena exhausted: no room for the backward scratch buffers");
+    }
+    const int64_t rowsB = int64_t(B) * n;
+    float *dgi = f32(uint64_t(rowsB) * KH);
+    float *dgh = lstm ? dgi : f32(uint64_t(rowsB) * KH);
+    float *part_wi = static_cast<float *>(ctx->scratch(reduce_partial_bytes(rowsB, d0, KH)));
+    float *part_wh = static_cast<float *>(ctx->scratch(reduce_partial_bytes(rowsB, H, KH)));
+    if (!dgi || !dgh || !part_wi || !part_wh) {
+        ctx->scratch_reset();
+        return ctx->fail(REINC_E_NOMEM, "arena exhausted: no room for the backward scratch buffers");
+    }
+    launch_fill_f32(grads, count, 0.0f, s);
+    launch_mse_grad(ctx->local[L - 1].h, target, n * H, dh, s);
+    const float *dc_in = nullptr;
+    const float *nof = nullptr;
+    std::vector<const float *> s1(L), q(L), ah(L);
+    bool first_batch = true;
+    for (int32_t hi = L - 1; hi >= 0;) {
+        const int32_t lo = std::max(0, hi - B + 1);
+        for (int32_t i = hi; i >= lo; --i) {
+            const Snapshot &sn = ctx->snaps[t0 + i];
+            const LocalStep &st = ctx->local[i];
+            const LocalStep *pv = i ? &ctx->local[i - 1] : nullptr;
+            float *dgi_i = dgi + int64_t(i - lo) * n * KH, *dgh_i = dgh + int64_t(i - lo) * n * KH;
+            rnn_backward_elem(ctx, s, lstm, n, H, (const float *)dh, dc_in, (const float *)st.saved,
+                              pv ? (const float *)pv->h : nof, pv ? (const float *)pv->c : nof, (const float *)st.c, dgi_i, dgh_i,
+                              dh2, dc2);
+            if (i > 0) {
+                // gradient w.r.t. Agg(h_{t-1}), then through the adjoint of the aggregation, plus the carry path
+                gemm_rows(ctx, s, (const void *)dgh_i, 0, n, KH, H, nof, W_h, 1, KH, nof, 0, nof, nof, dah);
+                AggBatch batch;
+                batch.count = 1;
+                batch.item[0] = AggItem{sn.col_ptr, sn.row, dah, sn.q, sn.p, nullptr, lstm ? nof : (const float *)dh2, dh,
+                                        sn.long_cols, sn.n_long_cols};
+                aggregate_full_batch(ctx, batch, 0, H, c.self_loop, s);
+                if (lstm) {
+                    std::swap(dc, dc2);
+                    dc_in = dc;
+                }
+            }
+        }
+        for (int32_t i = lo; i <= hi; ++i) {
+            s1[i] = ctx->gcache[t0 + i];
+            q[i] = ctx->snaps[t0 + i].q;
+            ah[i] = ctx->local[i].S[1];
+        }
+        const bool has_q = q[lo] != nullptr;
+        const int acc0 = first_batch ? 0 : 1;
+        int calls = 0;
+        REINC_TRY(for_runs(lo, hi, n, {Strip{s1.data(), d0}, Strip{has_q ? q.data() : nullptr, 1}}, [&](int i0, int len) {
+            gemm_reduce(ctx, s, s1[i0], d0, q[i0], (const float *)(dgi + int64_t(i0 - lo) * n * KH), KH, n * len, rowsB, d0, KH,
+                        part_wi, acc0 | (calls++ > 0));
+            return REINC_OK;
+        }));
+        calls = 0;
+        REINC_TRY(for_runs(lo, hi, n, {Strip{ah.data(), H}}, [&](int i0, int len) {
+            gemm_reduce(ctx, s, ah[i0], H, nof, (const float *)(dgh + int64_t(i0 - lo) * n * KH), KH, n * len, rowsB, H, KH, part_wh,
+                        acc0 | (calls++ > 0));
+            return REINC_OK;
+        }));
+        first_batch = false;
+        hi = lo - 1;
+    }
+    launch_reduce_partials(part_wi, rowsB, d0, KH, gW_i, gb_i, s);
+    launch_reduce_partials(part_wh, rowsB, H, KH, gW_h, gb_h, s);
     REINC_HIP(ctx, hipGetLastError());
     return REINC_OK;
 }

@@ -93,6 +93,8 @@ def load_library() -> ctypes.CDLL:
         "reinc_rnn_step": [p, ci, p, i64, i32, i32, p, p, p, p, p, p, p, p, p, p],
         "reinc_forward_window": [p, i32, i32, p, p, p, p, p],
         "reinc_backward_window": [p, i32, i32, p, p, p, p],
+        "reinc_forward_window_integrated": [p, i32, i32, p, p, p, p, p],
+        "reinc_backward_window_integrated": [p, i32, i32, p, p, p, p],
         "reinc_sgd_step": [p, p, p, i64, ctypes.c_float, p],
         "reinc_reset_derived": [p],
         "reinc_profile_begin": [p, ctypes.c_uint32],
@@ -355,6 +357,15 @@ class Context:
     def backward_window(self, t0: int, length: int, params, target, grads):
         self._ck(self.lib.reinc_backward_window(self.handle, t0, length, _dev_ptr(params), _dev_ptr(target),
                                                 _dev_ptr(grads), _stream()))
+
+    def forward_window_integrated(self, t0: int, length: int, params, target=None, loss_out=None, h_last=None):
+        """Integrated model (graph operations inside the gates); params = W_i [dims[0], K*H], W_h, b_i, b_h."""
+        self._ck(self.lib.reinc_forward_window_integrated(self.handle, t0, length, _dev_ptr(params), _dev_ptr(target),
+                                                          _dev_ptr(loss_out), _dev_ptr(h_last), _stream()))
+
+    def backward_window_integrated(self, t0: int, length: int, params, target, grads):
+        self._ck(self.lib.reinc_backward_window_integrated(self.handle, t0, length, _dev_ptr(params), _dev_ptr(target),
+                                                           _dev_ptr(grads), _stream()))
 
     def sgd_step(self, params, grads, lr: float):
         self._ck(self.lib.reinc_sgd_step(self.handle, _dev_ptr(params), _dev_ptr(grads), params.numel(), lr, _stream()))
