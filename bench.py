@@ -50,6 +50,11 @@ def agg_bytes(num_edges: float, n: int, d: int, elem: int) -> float:
     return num_edges * (4 + d * elem) + n * (d * 4 + 16)
 
 
+def _progress(stage, t, total):
+    """Progress lines on stderr: generating and loading the largest workloads takes minutes of host time."""
+    print(f"[bench] {stage} {t + 1}/{total}", file=sys.stderr, flush=True)
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -66,7 +71,7 @@ def main():
     n, T, L = wl.num_nodes, wl.num_snapshots, min(wl.window, wl.num_snapshots)
     elem = 2 if wl.feat_dtype == "bf16" else 4
     t_gen = time.perf_counter()
-    seq = synth.make_sequence(wl)
+    seq = synth.make_sequence(wl, progress=_progress)
     t_gen = time.perf_counter() - t_gen
 
     # arena: snapshots + features + deltas + caches, with head-room
@@ -76,9 +81,13 @@ def main():
     local_bytes = (L + 4) * n * (sum(wl.dims[1:]) * 2 + 6 * wl.hidden + 4 * max(wl.dims)) * 4
     delta_bytes = T * (wl.num_edges * 8 + n * 40 + n * wl.dims[0] * 4)
     arena = int(1.25 * (feat_bytes + edge_bytes + cache_bytes + local_bytes + delta_bytes)) + (256 << 20)
+    # the estimate is generous; at the largest workload it exceeds the card, where everything still fits: take what
+    # is free and let the library size its scratch (it lowers the time-batch depth) or report that it ran out
+    free_bytes, _ = torch.cuda.mem_get_info()
+    arena = min(arena, free_bytes - (8 << 30))
     ctx = reinc.Context.for_workload(wl, arena_bytes=arena, fallback_ratio=0.5)
     t_load = time.perf_counter()
-    ctx.load_sequence(seq)
+    ctx.load_sequence(seq, progress=_progress)
     torch.cuda.synchronize()
     t_load = time.perf_counter() - t_load
 
@@ -103,8 +112,11 @@ def main():
         dst.copy_(src)  # reads 256 MiB, writes 256 MiB
         torch.cuda.synchronize()
         del src, dst
-    for _ in range(args.warmup):
+    print(f"[bench] loaded in {t_load:.1f} s; warm-up", file=sys.stderr, flush=True)
+    for i in range(args.warmup):
         step()
+        torch.cuda.synchronize()
+        _progress("warm-up step", i, args.warmup)
     torch.cuda.synchronize()
     st0 = ctx.get_stats()
     ctx.profile_begin(("agg_full",))
@@ -114,6 +126,7 @@ def main():
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     prof = ctx.profile_end()
+    print(f"[bench] {args.steps} timed steps in {elapsed:.2f} s", file=sys.stderr, flush=True)
     st1 = ctx.get_stats()
     ms_per_step = elapsed * 1e3 / args.steps
     loss_value = float(loss.item())

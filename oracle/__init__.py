@@ -16,6 +16,11 @@ torch.autograd on a dense-adjacency model for the backward pass.
 The max / min aggregators (`oracle.minmax`) are pinned to a dense masked-adjacency formula, the max/min
 duality, closed-form special cases and the chained incremental == from-scratch invariant.
 
+The cache-policy simulator (`oracle.cache_policy`: score = future accesses / size - imminence with expiration,
+LRU, LFU) is pinned to a textbook page-replacement example, exhaustive search for the optimal policy, closed forms
+for cyclic access and the shape of the paper's policy comparison; the paper's printed hit rates themselves are
+unpinned (the model and the cache-size normalisation behind them are not given).
+
 Parity unpinned by the paper (pinned only to this package's own definition): the symmetric
 degree normalisation (absent from the paper), and the loss (mean squared error on a synthetic
 target instead of the paper's forecasting MAE on datasets that are not available).
@@ -23,3 +28,4 @@ target instead of the paper's forecasting MAE on datasets that are not available
 from .dgnn import *  # noqa: F401,F403
 from . import incremental  # noqa: F401
 from . import minmax  # noqa: F401
+from . import cache_policy  # noqa: F401

@@ -412,12 +412,14 @@ class Context:
         return out.value
 
     # ---- convenience (marshalling only): load a whole generated sequence
-    def load_sequence(self, seq, delta_features: bool = True):
+    def load_sequence(self, seq, delta_features: bool = True, progress=None):
         from . import synth
 
         conv = (lambda a: synth.bf16_bits(a)) if self.feat_dtype == "bf16" else (lambda a: a)
         for t, (s, d) in enumerate(seq.edges):
             self.load_edges(t, s, d)
+            if progress is not None:
+                progress("load", t, seq.num_snapshots)
         self.load_features_full(0, conv(seq.x0))
         x = seq.x0
         for t in range(1, seq.num_snapshots):

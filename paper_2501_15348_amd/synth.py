@@ -203,8 +203,14 @@ def bf16_bits(x: np.ndarray) -> np.ndarray:
     return (u >> np.uint32(16)).astype(np.uint16)
 
 
-def make_sequence(wl: Workload, shuffle_edges: bool = True) -> SnapshotSequence:
+def make_sequence(wl: Workload, shuffle_edges: bool = True, progress=None) -> SnapshotSequence:
+    """Generate the seeded snapshot sequence of a workload.
+
+    `progress`, if given, is called as progress(stage, t, T) after each snapshot's edges ("edges") and
+    feature rows ("features") are drawn; it does not influence the generated values.
+    """
     n, e0, T, d = wl.num_nodes, wl.num_edges, wl.num_snapshots, wl.feat_dim
+    tell = progress if progress is not None else (lambda stage, t, total: None)
     sampler = _EndpointSampler(wl)
     keys = _draw_new_edges(_rng(wl.seed, _S_GRAPH), sampler, e0, np.empty(0, dtype=np.uint64))
 
@@ -214,6 +220,7 @@ def make_sequence(wl: Workload, shuffle_edges: bool = True) -> SnapshotSequence:
         return _unpack(k)
 
     edges = [emit(keys, 0)]
+    tell("edges", 0, T)
     t_ins: List[np.ndarray] = [np.empty(0, dtype=np.uint64)]
     t_del: List[np.ndarray] = [np.empty(0, dtype=np.uint64)]
     for t in range(1, T):
@@ -227,6 +234,7 @@ def make_sequence(wl: Workload, shuffle_edges: bool = True) -> SnapshotSequence:
         t_ins.append(ins)
         keys = np.sort(np.concatenate([keys[keep], ins]))
         edges.append(emit(keys, t))
+        tell("edges", t, T)
 
     x0 = _rng(wl.seed, _S_FEAT0).standard_normal((n, d), dtype=np.float32)
     if wl.feat_dtype == "bf16":
@@ -242,6 +250,7 @@ def make_sequence(wl: Workload, shuffle_edges: bool = True) -> SnapshotSequence:
             vals = round_to_bf16(vals)
         rows_l.append(rows)
         vals_l.append(vals)
+        tell("features", t, T)
     return SnapshotSequence(wl, edges, t_ins, t_del, x0, rows_l, vals_l)
 
 
