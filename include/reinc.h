@@ -98,6 +98,9 @@ typedef struct reinc_stats {
     int64_t steps_incremental, steps_full, steps_fallback;
     int64_t delta_entries_processed;     /* effective delta edges consumed by incremental steps */
     int64_t local_bytes;                 /* bytes of per-window activations currently held */
+    /* budgeted layer-1 cache (reinc_cache_configure; all zero while every aggregate is kept) */
+    int64_t global_admitted, global_refused, global_evicted, global_expired;
+    int64_t global_bytes, global_peak_bytes; /* bytes the retained aggregates take now / at most so far */
 } reinc_stats;
 
 const char *reinc_version(void);
@@ -252,8 +255,58 @@ int reinc_cache_clear(reinc_ctx *ctx);
  * their arena space, so that the next reinc_build_deltas / window calls start cold.  Fails with REINC_E_STATE
  * if a snapshot was loaded after the first derived structure was built.  SYNC. */
 int reinc_reset_derived(reinc_ctx *ctx);
-/* Device pointer of the cached layer-1 sums S_t ([N, dims[0]] fp32) or NULL if not cached. */
+/* Device pointer of the cached layer-1 sums S_t ([N, dims[0]] fp32) or NULL if not cached.  With a cache budget
+ * the pointer is good until the next forward-window call (an aggregate the policy does not keep lives that long). */
 int reinc_cache_peek(reinc_ctx *ctx, int32_t t, const float **S_out);
+
+/* ---- cache budget and eviction policy (Section 3.3, "Eviction Policy"; compared with LRU / LFU in Section 5) ----
+ * By default every layer-1 aggregate stays cached (REINC_POLICY_KEEP_ALL: T * N * dims[0] * 4 bytes in the end).
+ * reinc_cache_configure limits what is RETAINED BETWEEN WINDOWS to budget_bytes and chooses who leaves:
+ *   REINC_POLICY_SCORE  the paper's rule: score = F / S - I, lowest score leaves first, and an aggregate that no
+ *                       later window needs (F = 0) leaves at once.  For the aggregate of snapshot t computed by the
+ *                       window that starts at t0, in an epoch of windows t0 = 0, stride, 2*stride, ... of length
+ *                       `window` over the T snapshots:
+ *                         F = min((t - t0) / stride, (T - window - t0) / stride)   later windows that contain t
+ *                         I = window - stride                                     the paper's encoder imminence
+ *                         S = N * dims[0] * 4 bytes
+ *                       (the paper prints F for its encoder-decoder model and stride 1; this is the same count for a
+ *                       model without a decoder).  A newcomer that scores no higher than what it would displace is
+ *                       not kept.
+ *   REINC_POLICY_LRU / REINC_POLICY_LFU   always keep the newcomer; the least recently / least frequently (since
+ *                       it entered; ties: least recently) used aggregate leaves.
+ * Mechanics: a window looks up its snapshots in order; what it has to compute lives in a buffer of its own until the
+ * next forward-window call begins, and is offered to the policy then, in snapshot order (so the backward pass of the
+ * window still finds it).  Device memory: (budget_bytes / S + window) buffers of S bytes, taken from the arena at
+ * the first window; no copies are made.  Windows longer than `window` are refused while a budget is set.
+ * The call drops every cached aggregate.  Results do not depend on the policy beyond rounding (an aggregate that
+ * was not kept is recomputed, from scratch or from its predecessor); the counters in reinc_stats do. */
+#define REINC_POLICY_KEEP_ALL 0
+#define REINC_POLICY_SCORE 1
+#define REINC_POLICY_LRU 2
+#define REINC_POLICY_LFU 3
+int reinc_cache_configure(reinc_ctx *ctx, int32_t policy, int64_t budget_bytes, int32_t window, int32_t stride);
+
+/* The same policies as a stand-alone store of (key, size, F, I) records, HOST only, no device and no context needed:
+ * a trace of look-ups and offers can be replayed to size a budget before training.
+ *   access:  *hit = 1 and one future access consumed (recency / frequency refreshed; under REINC_POLICY_SCORE the
+ *            entry leaves when its F reaches 0), or *hit = 0 and nothing changes.
+ *   offer:   after a miss.  *admitted tells whether the record was kept; the keys that left for it are written to
+ *            evicted[0 .. min(*n_evicted, evicted_cap)) (NULL / 0 to ignore).  A refused offer evicts nothing.  An
+ *            offer of a present key only replaces its F and I.  size > 0.
+ *   rescore: replaces F and I of a present key (under REINC_POLICY_SCORE, F <= 0 expires it).
+ *   counters: out[REINC_POLICY_COUNTERS] = hits, misses, admitted, refused, evicted, expired, used, peak_used.
+ * Ties: the older last use leaves first, then the smaller key.  Scores are compared exactly (no floating point);
+ * sizes, F and I must stay below 2^40. */
+typedef struct reinc_policy reinc_policy;
+#define REINC_POLICY_COUNTERS 8
+int reinc_policy_create(reinc_policy **out, int32_t policy, int64_t budget);
+int reinc_policy_destroy(reinc_policy *p);
+int reinc_policy_access(reinc_policy *p, int64_t key, int32_t *hit);
+int reinc_policy_offer(reinc_policy *p, int64_t key, int64_t size, int64_t future, int64_t imminence, int32_t *admitted,
+                       int64_t *evicted, int32_t evicted_cap, int32_t *n_evicted);
+int reinc_policy_rescore(reinc_policy *p, int64_t key, int64_t future, int64_t imminence);
+int reinc_policy_contains(const reinc_policy *p, int64_t key, int32_t *present);
+int reinc_policy_counters(const reinc_policy *p, int64_t *out);
 int reinc_get_stats(reinc_ctx *ctx, reinc_stats *out);
 
 /* ---- kernel timing ------------------------------------------------------------------------------------------

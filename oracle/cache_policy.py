@@ -178,8 +178,9 @@ def sliding_window_future(t: int, q: int, T: int, L: int, stride: int) -> int:
     return count
 
 
-def sliding_window_flow(T: int, L: int, stride: int, epochs: int = 1):
-    """Events of `epochs` passes of the window driver over T snapshots (Section 2.2: one window is one sample)."""
+def sliding_window_flow(T: int, L: int, stride: int, epochs: int = 1, size: int = 1):
+    """Events of `epochs` passes of the window driver over T snapshots (Section 2.2: one window is one sample);
+    every aggregate has the given size (the unit of the budget)."""
     events = []
     for _ in range(epochs):
         for q in range((T - L) // stride + 1):
@@ -187,7 +188,7 @@ def sliding_window_flow(T: int, L: int, stride: int, epochs: int = 1):
             for t in range(t0, t0 + L):
                 events.append(("access", t))
             for t in range(t0, t0 + L):
-                events.append(("offer", t, 1, sliding_window_future(t, q, T, L, stride), L - stride))
+                events.append(("offer", t, size, sliding_window_future(t, q, T, L, stride), L - stride))
     return events
 
 

@@ -577,6 +577,12 @@ int reinc_reset_derived(reinc_ctx *ctx)
     ctx->has_derived = false;
     for (Delta &d : ctx->deltas) d = Delta();
     std::fill(ctx->gcache.begin(), ctx->gcache.end(), nullptr);
+    // the cache buffers went back to the arena with everything else; a configured budget stays in force
+    ctx->pool.clear();
+    ctx->pool_free.clear();
+    ctx->pending.clear();
+    ctx->expired_pending.clear();
+    if (ctx->gpolicy) ctx->gpolicy->clear();
     ctx->local.clear();
     ctx->local_L = 0;
     ctx->local_kind = 0;

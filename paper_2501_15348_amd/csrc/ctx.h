@@ -7,10 +7,12 @@
 #include <cstdarg>
 #include <cstdint>
 #include <cstdio>
+#include <memory>
 #include <string>
 #include <vector>
 
 #include "reinc.h"
+#include "cache_policy.h"
 
 namespace reinc {
 
@@ -98,8 +100,16 @@ struct reinc_ctx {
     uint64_t size = 0, bottom = 0, top = 0, peak = 0;
     std::vector<reinc::Snapshot> snaps;
     std::vector<reinc::Delta> deltas;
-    // global cache: S^1_t per snapshot
+    // global cache: where the layer-1 sums S^1_t of each snapshot are right now (null: nowhere)
     std::vector<float *> gcache;
+    // budgeted global cache (reinc_cache_configure); gpolicy is null while every aggregate is kept
+    std::unique_ptr<reinc::CachePolicy> gpolicy;
+    int64_t budget_slots = 0;                 // buffers the policy may keep between windows
+    int32_t plan_window = 0, plan_stride = 1; // the epoch the future access counts are derived from
+    std::vector<float *> pool, pool_free;     // budget_slots + plan_window buffers of one aggregate each, and the free ones
+    std::vector<int32_t> pending;             // snapshots the last window computed: offered when the next one begins
+    std::vector<int32_t> expired_pending;     // hits of the last window that expired: their buffers return then too
+    int32_t pending_t0 = 0, pending_L = 0;    // the window that computed `pending`
     // local cache
     std::vector<reinc::LocalStep> local;
     uint64_t local_reserved = 0;  // bytes at the top of the arena held by the local cache

@@ -186,11 +186,89 @@ int ensure_local_integrated(reinc_ctx *ctx, int32_t L, hipStream_t s)
     return REINC_OK;
 }
 
-// Makes sure the layer-1 sums of snapshot t are in the global cache.
+uint64_t aggregate_bytes(const reinc_config &c) { return align256(uint64_t(c.num_nodes) * c.dims[0] * 4); }
+
+void sync_policy_stats(reinc_ctx *ctx)
+{
+    const CachePolicy::Counters &k = ctx->gpolicy->counters();
+    ctx->stats.global_admitted = k.admitted;
+    ctx->stats.global_refused = k.refused;
+    ctx->stats.global_evicted = k.evicted;
+    ctx->stats.global_expired = k.expired;
+    ctx->stats.global_bytes = k.used;
+    ctx->stats.global_peak_bytes = k.peak_used;
+}
+
+// Budgeted cache: takes the buffers (what may be retained plus one window's worth) from the arena, once.
+int ensure_pool(reinc_ctx *ctx)
+{
+    const uint64_t want = uint64_t(ctx->budget_slots) + uint64_t(ctx->plan_window);
+    if (ctx->pool.size() >= want) return REINC_OK;
+    const uint64_t bytes = aggregate_bytes(ctx->cfg);
+    ctx->note_derived();
+    while (ctx->pool.size() < want) {
+        float *b = static_cast<float *>(ctx->alloc(bytes));
+        if (!b)
+            return ctx->fail(REINC_E_NOMEM, "arena exhausted: the cache budget needs %llu buffers of %llu bytes",
+                             (unsigned long long)want, (unsigned long long)bytes);
+        ctx->pool.push_back(b);
+        ctx->pool_free.push_back(b);
+    }
+    return REINC_OK;
+}
+
+// Budgeted cache: the previous window is over.  Buffers of its expired hits return to the pool, and what it computed
+// is offered to the policy in snapshot order (Section 3.3, eviction policy: F / S - I with expiration, or LRU / LFU).
+void retire_window(reinc_ctx *ctx)
+{
+    if (!ctx->gpolicy) return;
+    auto release = [&](int32_t t) {
+        if (ctx->gcache[t]) ctx->pool_free.push_back(ctx->gcache[t]);
+        ctx->gcache[t] = nullptr;
+    };
+    for (int32_t t : ctx->expired_pending) release(t);
+    ctx->expired_pending.clear();
+    const int64_t T = ctx->cfg.num_snapshots, S = ctx->plan_stride, t0 = ctx->pending_t0, L = ctx->pending_L;
+    const int64_t size = int64_t(aggregate_bytes(ctx->cfg));
+    std::vector<int64_t> gone;
+    for (int32_t t : ctx->pending) {
+        // later windows of the epoch (starts t0 + S, t0 + 2S, ... up to T - L) that still contain snapshot t
+        const int64_t future = std::max<int64_t>(std::min((t - t0) / S, (T - L - t0) / S), 0);
+        gone.clear();
+        const bool kept = ctx->gpolicy->offer(t, size, future, L - S, &gone);
+        for (int64_t k : gone) release(int32_t(k));
+        if (!kept) release(t);
+    }
+    ctx->pending.clear();
+    sync_policy_stats(ctx);
+}
+
+// Budgeted cache, start of a forward window: settle the previous window, then note the new one.
+int begin_budgeted_window(reinc_ctx *ctx, int32_t t0, int32_t L)
+{
+    if (!ctx->gpolicy) return REINC_OK;
+    if (L > ctx->plan_window)
+        return ctx->fail(REINC_E_ARG, "window of %d steps, but the cache budget was configured for at most %d", L, ctx->plan_window);
+    ctx->scratch_reset();  // scratch of the previous call is dead: the buffers may use that room
+    REINC_TRY(ensure_pool(ctx));
+    retire_window(ctx);
+    ctx->pending_t0 = t0;
+    ctx->pending_L = L;
+    return REINC_OK;
+}
+
+// Makes sure the layer-1 sums of snapshot t are available: ctx->gcache[t] points at them afterwards.
 int ensure_layer1(reinc_ctx *ctx, int32_t t, hipStream_t s)
 {
     const reinc_config &c = ctx->cfg;
-    if (ctx->gcache[t]) {
+    if (ctx->gpolicy) {
+        bool expired = false;
+        if (ctx->gpolicy->access(t, &expired)) {
+            ++ctx->stats.global_hits;
+            if (expired) ctx->expired_pending.push_back(t);  // the buffer stays ours until this window is retired
+            return REINC_OK;
+        }
+    } else if (ctx->gcache[t]) {
         ++ctx->stats.global_hits;
         return REINC_OK;
     }
@@ -200,9 +278,18 @@ int ensure_layer1(reinc_ctx *ctx, int32_t t, hipStream_t s)
     const int32_t d = c.dims[0];
     const int bf16 = c.feat_dtype == REINC_BF16;
     const uint64_t bytes = uint64_t(c.num_nodes) * d * 4;
-    ctx->note_derived();
-    float *slot = static_cast<float *>(ctx->alloc(bytes));
-    if (!slot) return ctx->fail(REINC_E_NOMEM, "arena exhausted: no room for the cached aggregate of snapshot %d", t);
+    float *slot = nullptr;
+    if (ctx->gpolicy) {
+        if (ctx->pool_free.empty()) return ctx->fail(REINC_E_STATE, "cache buffers exhausted (window longer than configured?)");
+        slot = ctx->pool_free.back();
+        ctx->pool_free.pop_back();
+        ctx->gcache[t] = slot;  // recorded before anything can fail, so that the buffer always finds its way back
+        ctx->pending.push_back(t);
+    } else {
+        ctx->note_derived();
+        slot = static_cast<float *>(ctx->alloc(bytes));
+        if (!slot) return ctx->fail(REINC_E_NOMEM, "arena exhausted: no room for the cached aggregate of snapshot %d", t);
+    }
     ++ctx->stats.global_misses;
     const bool chain = t > 0 && ctx->gcache[t - 1] && ctx->deltas[t].built && c.fallback_ratio != 0.0f;
     bool incremental = chain;
@@ -316,6 +403,7 @@ int reinc_forward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *par
     hipStream_t s = as_stream(stream);
     REINC_HIP(ctx, hipSetDevice(c.device));
     ctx->local_valid = false;
+    REINC_TRY(begin_budgeted_window(ctx, t0, L));
     REINC_TRY(ensure_local(ctx, L, s));
     ctx->scratch_reset();
     const Params p = split_params(c, params);
@@ -547,6 +635,7 @@ int reinc_forward_window_integrated(reinc_ctx *ctx, int32_t t0, int32_t L, const
     hipStream_t s = as_stream(stream);
     REINC_HIP(ctx, hipSetDevice(c.device));
     ctx->local_valid = false;
+    REINC_TRY(begin_budgeted_window(ctx, t0, L));
     REINC_TRY(ensure_local_integrated(ctx, L, s));
     ctx->scratch_reset();
     const int64_t n = c.num_nodes;
@@ -682,6 +771,17 @@ int reinc_backward_window_integrated(reinc_ctx *ctx, int32_t t0, int32_t L, cons
 int reinc_cache_clear(reinc_ctx *ctx)
 {
     if (!ctx) return REINC_E_ARG;
+    if (ctx->gpolicy) {
+        // every buffer returns to the pool; the pool itself stays
+        ctx->gpolicy->clear();
+        ctx->pool_free = ctx->pool;
+        ctx->pending.clear();
+        ctx->expired_pending.clear();
+        std::fill(ctx->gcache.begin(), ctx->gcache.end(), nullptr);
+        ctx->local_valid = false;
+        sync_policy_stats(ctx);
+        return REINC_OK;
+    }
     // cached sums live in the persistent region and cannot be returned piecemeal: forget them and let the
     // next windows recompute into fresh slots only if every slot sits at the end of the region
     uint64_t lowest = ctx->bottom;
@@ -700,6 +800,32 @@ int reinc_cache_clear(reinc_ctx *ctx)
     }
     std::fill(ctx->gcache.begin(), ctx->gcache.end(), nullptr);
     ctx->local_valid = false;
+    return REINC_OK;
+}
+
+int reinc_cache_configure(reinc_ctx *ctx, int32_t policy, int64_t budget_bytes, int32_t window, int32_t stride)
+{
+    if (!ctx) return REINC_E_ARG;
+    if (policy < REINC_POLICY_KEEP_ALL || policy > REINC_POLICY_LFU) return ctx->fail(REINC_E_ARG, "unknown cache policy %d", policy);
+    REINC_TRY(reinc_cache_clear(ctx));
+    if (policy == REINC_POLICY_KEEP_ALL) {
+        // buffers taken for an earlier budget stay in the arena until reinc_reset_derived
+        ctx->gpolicy.reset();
+        ctx->budget_slots = 0;
+        ctx->plan_window = 0;
+        ctx->plan_stride = 1;
+        return REINC_OK;
+    }
+    if (budget_bytes < 0 || window < 1 || window > ctx->cfg.num_snapshots || stride < 1)
+        return ctx->fail(REINC_E_ARG, "cache budget: need budget_bytes >= 0, 1 <= window <= %d snapshots, stride >= 1",
+                         ctx->cfg.num_snapshots);
+    const int64_t size = int64_t(aggregate_bytes(ctx->cfg));
+    ctx->budget_slots = std::min<int64_t>(budget_bytes / size, ctx->cfg.num_snapshots);  // more can never be held
+    ctx->plan_window = window;
+    ctx->plan_stride = stride;
+    ctx->gpolicy.reset(new CachePolicy(policy, ctx->budget_slots * size));
+    ctx->pool_free = ctx->pool;  // buffers of an earlier budget are reused; more are taken at the next window if needed
+    sync_policy_stats(ctx);
     return REINC_OK;
 }
 

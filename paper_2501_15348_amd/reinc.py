@@ -51,7 +51,12 @@ class DeltaInfo(ctypes.Structure):
 class Stats(ctypes.Structure):
     _fields_ = [(k, ctypes.c_int64) for k in (
         "arena_used", "arena_peak", "global_hits", "global_misses", "steps_incremental", "steps_full",
-        "steps_fallback", "delta_entries_processed", "local_bytes")]
+        "steps_fallback", "delta_entries_processed", "local_bytes", "global_admitted", "global_refused",
+        "global_evicted", "global_expired", "global_bytes", "global_peak_bytes")]
+
+
+POLICIES = ("keep_all", "score", "lru", "lfu")  # REINC_POLICY_*
+POLICY_COUNTERS = ("hits", "misses", "admitted", "refused", "evicted", "expired", "used", "peak_used")
 
 
 class ReincError(RuntimeError):
@@ -101,6 +106,14 @@ def load_library() -> ctypes.CDLL:
         "reinc_profile_end": [p, ctypes.POINTER(i64), ctypes.POINTER(ctypes.c_double)],
         "reinc_cache_clear": [p],
         "reinc_cache_peek": [p, i32, ctypes.POINTER(p)],
+        "reinc_cache_configure": [p, i32, i64, i32, i32],
+        "reinc_policy_create": [ctypes.POINTER(p), i32, i64],
+        "reinc_policy_destroy": [p],
+        "reinc_policy_access": [p, i64, ctypes.POINTER(i32)],
+        "reinc_policy_offer": [p, i64, i64, i64, i64, ctypes.POINTER(i32), ctypes.POINTER(i64), i32, ctypes.POINTER(i32)],
+        "reinc_policy_rescore": [p, i64, i64, i64],
+        "reinc_policy_contains": [p, i64, ctypes.POINTER(i32)],
+        "reinc_policy_counters": [p, ctypes.POINTER(i64)],
         "reinc_get_stats": [p, ctypes.POINTER(Stats)],
     }
     for name, args in sig.items():
@@ -389,6 +402,14 @@ class Context:
     def cache_clear(self):
         self._ck(self.lib.reinc_cache_clear(self.handle))
 
+    def cache_configure(self, policy: str, budget_bytes: int = 0, window: int = 1, stride: int = 1):
+        """Limits what the layer-1 cache retains between windows; policy is one of POLICIES."""
+        self._ck(self.lib.reinc_cache_configure(self.handle, POLICIES.index(policy), int(budget_bytes), window, stride))
+
+    def aggregate_bytes(self) -> int:
+        """Size of one cached layer-1 aggregate (the unit a budget is counted in)."""
+        return (self.n * self.dims[0] * 4 + 255) & ~255
+
     def cache_peek(self, t: int):
         """The cached layer-1 sums of snapshot t as a tensor view into the arena, or None."""
         import torch
@@ -429,3 +450,53 @@ class Context:
                 x = x.copy()
                 x[seq.feat_rows[t]] = seq.feat_vals[t]
                 self.load_features_full(t, conv(x))
+
+
+class PolicyStore:
+    """The cache policies as a stand-alone host-side store of (key, size, F, I) records (no GPU needed)."""
+
+    def __init__(self, policy: str, budget: int):
+        self.lib = load_library()
+        self.handle = ctypes.c_void_p()
+        code = self.lib.reinc_policy_create(ctypes.byref(self.handle), POLICIES.index(policy), int(budget))
+        if code != 0:
+            raise ReincError(code, "reinc_policy_create failed")
+
+    def close(self):
+        if self.handle:
+            self.lib.reinc_policy_destroy(self.handle)
+            self.handle = ctypes.c_void_p()
+
+    def __del__(self):
+        self.close()
+
+    def _ck(self, code: int):
+        if code != 0:
+            raise ReincError(code, "policy store call failed")
+
+    def access(self, key: int) -> bool:
+        hit = ctypes.c_int32()
+        self._ck(self.lib.reinc_policy_access(self.handle, key, ctypes.byref(hit)))
+        return bool(hit.value)
+
+    def offer(self, key: int, size: int, future: int, imminence: int, cap: int = 64):
+        admitted, n_out = ctypes.c_int32(), ctypes.c_int32()
+        buf = (ctypes.c_int64 * cap)()
+        self._ck(self.lib.reinc_policy_offer(self.handle, key, size, future, imminence, ctypes.byref(admitted), buf, cap,
+                                             ctypes.byref(n_out)))
+        if n_out.value > cap:
+            raise ReincError(-1, f"{n_out.value} keys were evicted, room for {cap}")
+        return bool(admitted.value), list(buf[:n_out.value])
+
+    def rescore(self, key: int, future: int, imminence: int):
+        self._ck(self.lib.reinc_policy_rescore(self.handle, key, future, imminence))
+
+    def __contains__(self, key: int) -> bool:
+        present = ctypes.c_int32()
+        self._ck(self.lib.reinc_policy_contains(self.handle, key, ctypes.byref(present)))
+        return bool(present.value)
+
+    def counters(self) -> dict:
+        out = (ctypes.c_int64 * len(POLICY_COUNTERS))()
+        self._ck(self.lib.reinc_policy_counters(self.handle, out))
+        return dict(zip(POLICY_COUNTERS, out))

@@ -1,0 +1,180 @@
+"""GPU tests of the budgeted layer-1 cache (paper Section 3.3, eviction policy): with a budget and any of the three
+policies the window driver still matches the from-scratch CPU reference, and its hits, misses, evictions and
+expirations are exactly those the reference policy simulator predicts for the same epoch of windows."""
+import dataclasses
+
+import numpy as np
+import pytest
+
+import oracle
+from oracle.cache_policy import CacheSim, sliding_window_flow
+from helpers import RTOL_FP32, assert_close, oracle_feats, oracle_graphs
+from paper_2501_15348_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+def _dev(a):
+    import torch
+
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def _setup(wl, arena=1 << 30):
+    from paper_2501_15348_amd import reinc
+
+    seq = synth.make_sequence(wl)
+    ctx = reinc.Context.for_workload(wl, arena_bytes=arena, fallback_ratio=0.5)
+    ctx.load_sequence(seq)
+    ctx.build_deltas(-1)
+    return seq, ctx, synth.make_params(wl, bias_scale=0.2), synth.make_target(wl)
+
+
+def _predicted(policy, slots, size, T, L, stride, epochs):
+    """Per window: (hits, misses) of the reference simulator, and the simulator itself."""
+    sim = CacheSim(policy, slots * size)
+    events = sliding_window_flow(T, L, stride, epochs=epochs, size=size)
+    per_window, hits, misses = [], 0, 0
+    missed = set()
+    for ev in events:
+        if ev[0] == "access":
+            hit = sim.access(ev[1])
+            hits += hit
+            misses += not hit
+            (missed.discard if hit else missed.add)(ev[1])
+            if hits + misses == L:
+                per_window.append((hits, misses))
+                hits = misses = 0
+        elif ev[1] in missed and ev[1] not in sim:
+            sim.offer(*ev[1:])
+    return per_window, sim
+
+
+@pytest.mark.parametrize("policy", ["score", "lru", "lfu"])
+@pytest.mark.parametrize("slots,stride", [(0, 1), (2, 1), (5, 1), (12, 1), (3, 2)])
+def test_counters_follow_the_reference_simulator(policy, slots, stride):
+    import torch
+
+    wl = synth.WORKLOADS["tiny"].scaled(700, 12)
+    T, L, epochs = wl.num_snapshots, 6, 2
+    seq, ctx, flat, target = _setup(wl, arena=256 << 20)
+    size = ctx.aggregate_bytes()
+    ctx.cache_configure(policy, slots * size + size // 2, window=L, stride=stride)  # a fraction of a buffer buys nothing
+    params, tgt = _dev(flat), _dev(target)
+    loss = torch.zeros(1, device="cuda")
+    grads = torch.empty_like(params)
+    want, sim = _predicted(policy, slots, size, T, L, stride, epochs)
+    got = []
+    for _ in range(epochs):
+        for t0 in range(0, T - L + 1, stride):
+            before = ctx.get_stats()
+            ctx.forward_window(t0, L, params, tgt, loss)
+            ctx.backward_window(t0, L, params, tgt, grads)
+            after = ctx.get_stats()
+            got.append((after["global_hits"] - before["global_hits"], after["global_misses"] - before["global_misses"]))
+    torch.cuda.synchronize()
+    assert got == want
+    # the last window's aggregates are offered when the next window begins: settle them with one more window, on
+    # both sides (the simulator's flow has offered them already; the extra window is replayed there too)
+    ctx.forward_window(0, L, params, tgt, loss)
+    st = ctx.get_stats()
+    for t in range(L):
+        sim.access(t)
+    assert st["global_admitted"] == sim.admitted and st["global_refused"] == sim.refused
+    assert st["global_evicted"] == sim.evicted and st["global_expired"] == sim.expired
+    assert st["global_peak_bytes"] == sim.peak_used <= slots * size
+    ctx.close()
+
+
+@pytest.mark.parametrize("policy,slots", [("score", 2), ("lru", 1), ("lfu", 3), ("score", 0)])
+def test_results_match_the_reference_under_a_budget(policy, slots):
+    import torch
+
+    wl = synth.WORKLOADS["c2"].scaled(3001, 9)
+    T, L = wl.num_snapshots, 4
+    seq, ctx, flat, target = _setup(wl)
+    ctx.cache_configure(policy, slots * ctx.aggregate_bytes(), window=L, stride=1)
+    params, tgt = _dev(flat), _dev(target)
+    loss = torch.zeros(1, device="cuda")
+    h_last = torch.empty((wl.num_nodes, wl.hidden), device="cuda")
+    grads = torch.empty_like(params)
+    graphs_all = oracle_graphs(seq)
+    p = synth.split_params(wl, flat.astype(np.float64))
+    layers = len(wl.dims) - 1
+    for t0 in range(T - L + 1):
+        print(f"[{policy} {slots}] window t0={t0}", flush=True)
+        ctx.forward_window(t0, L, params, tgt, loss, h_last)
+        ctx.backward_window(t0, L, params, tgt, grads)
+        torch.cuda.synchronize()
+        graphs = graphs_all[t0:t0 + L]
+        feats = [oracle_feats(seq, t) for t in range(t0, t0 + L)]
+        ref_loss, ref_h, saved = oracle.forward_window(graphs, feats, p, layers, wl.agg, wl.self_loop, wl.rnn, target, keep=True)
+        assert_close(h_last.cpu().numpy(), ref_h, RTOL_FP32, f"h_last (t0={t0})")
+        assert abs(loss.item() - ref_loss) <= RTOL_FP32 * abs(ref_loss)
+        ref_g = oracle.backward_window(graphs, saved, ref_h, p, layers, wl.agg, wl.self_loop, wl.rnn, target)
+        got = synth.split_params(wl, grads.cpu().numpy())
+        for name, _ in synth.param_shapes(wl):
+            assert_close(got[name], ref_g[name], 5 * RTOL_FP32, f"grad {name} (t0={t0})")
+        # every aggregate the window used is still where the driver says it is, and correct
+        for t in (t0, t0 + L - 1):
+            S = ctx.cache_peek(t)
+            assert S is not None
+            ref_S, _ = oracle.aggregate(graphs_all[t].row_ptr, graphs_all[t].col, oracle_feats(seq, t), wl.agg, wl.self_loop)
+            assert_close(S.cpu().numpy(), ref_S, RTOL_FP32, f"S_{t}")
+    st = ctx.get_stats()
+    assert st["global_bytes"] <= slots * ctx.aggregate_bytes()
+    ctx.close()
+
+
+def test_integrated_model_under_a_budget():
+    import torch
+
+    wl = synth.WORKLOADS["c2"].scaled(2001, 8)
+    T, L = wl.num_snapshots, 4
+    seq, ctx, _, target = _setup(wl)
+    wli = dataclasses.replace(wl, dims=(wl.dims[0],))  # parameter shapes of the integrated model: the cell only
+    flat = synth.make_params(wli, bias_scale=0.2)
+    params, tgt = _dev(flat), _dev(target)
+    loss = torch.zeros(1, device="cuda")
+    h_a = torch.empty((wl.num_nodes, wl.hidden), device="cuda")
+    h_b = torch.empty_like(h_a)
+    g_a, g_b = torch.empty_like(params), torch.empty_like(params)
+    losses = {}
+    for mode, h, g in (("keep_all", h_a, g_a), ("score", h_b, g_b)):
+        ctx.cache_configure(mode, 2 * ctx.aggregate_bytes(), window=L, stride=1)
+        for t0 in range(T - L + 1):
+            ctx.forward_window_integrated(t0, L, params, tgt, loss, h)
+            ctx.backward_window_integrated(t0, L, params, tgt, g)
+        torch.cuda.synchronize()
+        losses[mode] = loss.item()
+    # same arithmetic, except that an aggregate that was not retained is rebuilt from scratch instead of updated
+    assert_close(h_b.cpu().numpy(), h_a.cpu().numpy().astype(np.float64), RTOL_FP32, "h_last")
+    assert_close(g_b.cpu().numpy(), g_a.cpu().numpy().astype(np.float64), 5 * RTOL_FP32, "grads")
+    assert abs(losses["score"] - losses["keep_all"]) <= RTOL_FP32 * abs(losses["keep_all"])
+    st = ctx.get_stats()
+    assert st["global_expired"] > 0 and st["global_peak_bytes"] <= 2 * ctx.aggregate_bytes()
+    ctx.close()
+
+
+def test_configuration_errors():
+    from paper_2501_15348_amd import reinc
+    import torch
+
+    wl = synth.WORKLOADS["tiny"]
+    seq, ctx, flat, target = _setup(wl, arena=64 << 20)
+    with pytest.raises(reinc.ReincError):
+        ctx.cache_configure("score", -1, window=4)
+    with pytest.raises(reinc.ReincError):
+        ctx.cache_configure("score", 0, window=0)
+    with pytest.raises(reinc.ReincError):
+        ctx.cache_configure("lru", 0, window=4, stride=0)
+    ctx.cache_configure("score", 0, window=3)
+    params, tgt = _dev(flat), _dev(target)
+    loss = torch.zeros(1, device="cuda")
+    with pytest.raises(reinc.ReincError):
+        ctx.forward_window(0, 4, params, tgt, loss)  # longer than configured
+    ctx.forward_window(0, 3, params, tgt, loss)
+    ctx.cache_configure("keep_all")
+    ctx.forward_window(0, 4, params, tgt, loss)
+    torch.cuda.synchronize()
+    ctx.close()
