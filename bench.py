@@ -335,6 +335,24 @@ def extras(ctx, wl, seq, infos, params, target, step, step_s):
     epoch_integrated()
     torch.cuda.synchronize()
     res["integrated_model_warm_epoch_ms"] = round((time.perf_counter() - t0) * 1e3, 3)
+    # budgeted layer-1 cache: one cold epoch (deltas built, no aggregate cached) per policy and budget
+    size = ctx.aggregate_bytes()
+    rows = []
+    for policy, slots in (("keep_all", T), ("score", L - 1), ("lru", L - 1), ("score", L // 2), ("lru", L // 2), ("score", 0)):
+        ctx.cache_configure(policy, slots * size, window=L, stride=1)
+        torch.cuda.synchronize()
+        st0 = ctx.get_stats()
+        t0 = time.perf_counter()
+        epoch()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3
+        st1 = ctx.get_stats()
+        hits, misses = st1["global_hits"] - st0["global_hits"], st1["global_misses"] - st0["global_misses"]
+        rows.append({"policy": policy, "budget_aggregates": slots, "cold_epoch_ms": round(ms, 3), "hits": hits, "misses": misses,
+                     "full": st1["steps_full"] - st0["steps_full"],
+                     "retained_peak_MB": round((T * size if policy == "keep_all" else st1["global_peak_bytes"]) / 1e6, 1)})
+    ctx.cache_configure("keep_all")
+    res["cache_budget"] = rows
     return res
 
 

@@ -637,6 +637,7 @@ int reinc_get_stats(reinc_ctx *ctx, reinc_stats *out)
     if (!ctx || !out) return REINC_E_ARG;
     ctx->stats.arena_used = int64_t(ctx->bottom);
     ctx->stats.arena_peak = int64_t(ctx->peak);
+    ctx->sync_policy_stats();
     *out = ctx->stats;
     return REINC_OK;
 }

@@ -110,6 +110,16 @@ struct reinc_ctx {
     std::vector<int32_t> pending;             // snapshots the last window computed: offered when the next one begins
     std::vector<int32_t> expired_pending;     // hits of the last window that expired: their buffers return then too
     int32_t pending_t0 = 0, pending_L = 0;    // the window that computed `pending`
+    void sync_policy_stats() {
+        if (!gpolicy) return;
+        const reinc::CachePolicy::Counters &k = gpolicy->counters();
+        stats.global_admitted = k.admitted;
+        stats.global_refused = k.refused;
+        stats.global_evicted = k.evicted;
+        stats.global_expired = k.expired;
+        stats.global_bytes = k.used;
+        stats.global_peak_bytes = k.peak_used;
+    }
     // local cache
     std::vector<reinc::LocalStep> local;
     uint64_t local_reserved = 0;  // bytes at the top of the arena held by the local cache

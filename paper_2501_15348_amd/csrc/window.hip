@@ -188,17 +188,6 @@ int ensure_local_integrated(reinc_ctx *ctx, int32_t L, hipStream_t s)
 
 uint64_t aggregate_bytes(const reinc_config &c) { return align256(uint64_t(c.num_nodes) * c.dims[0] * 4); }
 
-void sync_policy_stats(reinc_ctx *ctx)
-{
-    const CachePolicy::Counters &k = ctx->gpolicy->counters();
-    ctx->stats.global_admitted = k.admitted;
-    ctx->stats.global_refused = k.refused;
-    ctx->stats.global_evicted = k.evicted;
-    ctx->stats.global_expired = k.expired;
-    ctx->stats.global_bytes = k.used;
-    ctx->stats.global_peak_bytes = k.peak_used;
-}
-
 // Budgeted cache: takes the buffers (what may be retained plus one window's worth) from the arena, once.
 int ensure_pool(reinc_ctx *ctx)
 {
@@ -240,7 +229,7 @@ void retire_window(reinc_ctx *ctx)
         if (!kept) release(t);
     }
     ctx->pending.clear();
-    sync_policy_stats(ctx);
+    ctx->sync_policy_stats();
 }
 
 // Budgeted cache, start of a forward window: settle the previous window, then note the new one.
@@ -779,7 +768,7 @@ int reinc_cache_clear(reinc_ctx *ctx)
         ctx->expired_pending.clear();
         std::fill(ctx->gcache.begin(), ctx->gcache.end(), nullptr);
         ctx->local_valid = false;
-        sync_policy_stats(ctx);
+        ctx->sync_policy_stats();
         return REINC_OK;
     }
     // cached sums live in the persistent region and cannot be returned piecemeal: forget them and let the
@@ -825,7 +814,7 @@ int reinc_cache_configure(reinc_ctx *ctx, int32_t policy, int64_t budget_bytes, 
     ctx->plan_stride = stride;
     ctx->gpolicy.reset(new CachePolicy(policy, ctx->budget_slots * size));
     ctx->pool_free = ctx->pool;  // buffers of an earlier budget are reused; more are taken at the next window if needed
-    sync_policy_stats(ctx);
+    ctx->sync_policy_stats();
     return REINC_OK;
 }
 
