@@ -270,8 +270,17 @@ int ensure_layer1(reinc_ctx *ctx, int32_t t, hipStream_t s)
     float *slot = nullptr;
     if (ctx->gpolicy) {
         if (ctx->pool_free.empty()) return ctx->fail(REINC_E_STATE, "cache buffers exhausted (window longer than configured?)");
-        slot = ctx->pool_free.back();
-        ctx->pool_free.pop_back();
+        // the dense kernels take consecutive timesteps as one tall matrix when their sums are adjacent in memory:
+        // prefer the buffer right behind the previous snapshot's, else the lowest free address (the retained
+        // window then moves through the pool like a ring)
+        auto pick = std::min_element(ctx->pool_free.begin(), ctx->pool_free.end());
+        if (t > 0 && ctx->gcache[t - 1]) {
+            float *next = reinterpret_cast<float *>(reinterpret_cast<char *>(ctx->gcache[t - 1]) + aggregate_bytes(c));
+            auto it = std::find(ctx->pool_free.begin(), ctx->pool_free.end(), next);
+            if (it != ctx->pool_free.end()) pick = it;
+        }
+        slot = *pick;
+        ctx->pool_free.erase(pick);
         ctx->gcache[t] = slot;  // recorded before anything can fail, so that the buffer always finds its way back
         ctx->pending.push_back(t);
     } else {
