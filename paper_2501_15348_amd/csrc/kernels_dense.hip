@@ -13,6 +13,9 @@
 // reads row 16*(l/32)+s of the staged weight chunk: each 128-byte line of A is fetched by one lane pair.
 #include "ctx.h"
 
+#include <cstdlib>
+#include <cstring>
+
 namespace reinc {
 
 namespace {
@@ -315,14 +318,121 @@ struct NoPrefetch {
     __device__ void operator()() const {}
 };
 
+// ---- fp32 products on the bf16 matrix cores ---------------------------------------------------------------------
+// An fp32 value is the sum of three bfloat16 terms, v = hi + mid + lo with |v - (hi + mid + lo)| <= 2^-24 |v|
+// (each term is the round-to-nearest bfloat16 of what the terms before it leave over; the remainders are exact in
+// fp32).  A product of two such sums, kept to the terms of relative size 2^-16 and above -- hi*hi, hi*mid, mid*hi,
+// hi*lo, mid*mid, lo*hi -- is exact to about 2^-23 of |a*b|, and every one of the six is a bf16 x bf16 product that
+// the matrix core forms exactly and adds in fp32.  Six bf16 instructions of depth 16 do the work of eight fp32
+// instructions of depth 2 in 3/8 of the cycles.
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+__device__ inline uint32_t pack_bf16(float a, float b)  // a in the low half; one v_cvt_pk_bf16_f32
+{
+    bf16x2 p;
+    p[0] = static_cast<__bf16>(a);
+    p[1] = static_cast<__bf16>(b);
+    return __builtin_bit_cast(uint32_t, p);
+}
+
+// Splits eight consecutive values into their three bfloat16 planes (pairs packed low half first).
+__device__ inline void split8(const float *v, u32x4 &hi, u32x4 &mid, u32x4 &lo)
+{
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const float a0 = v[2 * j], a1 = v[2 * j + 1];
+        const uint32_t h = pack_bf16(a0, a1);
+        const float r0 = a0 - __uint_as_float(h << 16), r1 = a1 - __uint_as_float(h & 0xFFFF0000u);
+        const uint32_t m = pack_bf16(r0, r1);
+        const float q0 = r0 - __uint_as_float(m << 16), q1 = r1 - __uint_as_float(m & 0xFFFF0000u);
+        hi[j] = h;
+        mid[j] = m;
+        lo[j] = pack_bf16(q0, q1);
+    }
+}
+
+__device__ inline acc16 mfma_bf16(u32x4 a, u32x4 b, acc16 c)
+{
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+
+// Stages columns [col0, col0 + NC) of W (or of W^T) for the split product: for every group of eight k values and
+// every column one 16-byte record per plane, planes[p][k / 8][column].  Columns at or beyond M are zero.
+template <int NC, int TPB>
+__device__ inline void stage_split(u32x4 *Bq, const float *W, int ldw, int K, bool wT, int col0, int M)
+{
+    const int groups = K / 8, plane = groups * NC;
+    const bool vec = wT && ldw % 4 == 0 && (reinterpret_cast<uintptr_t>(W) & 15) == 0;
+    for (int item = threadIdx.x; item < plane; item += TPB) {
+        const int g8 = item / NC, c = col0 + item % NC;
+        float v[8];
+        if (c >= M) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] = 0.0f;
+        } else if (!wT) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] = W[int64_t(8 * g8 + e) * ldw + c];
+        } else if (vec) {
+            const float4 x = *reinterpret_cast<const float4 *>(W + int64_t(c) * ldw + 8 * g8);
+            const float4 y = *reinterpret_cast<const float4 *>(W + int64_t(c) * ldw + 8 * g8 + 4);
+            v[0] = x.x, v[1] = x.y, v[2] = x.z, v[3] = x.w, v[4] = y.x, v[5] = y.y, v[6] = y.z, v[7] = y.w;
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] = W[int64_t(c) * ldw + 8 * g8 + e];
+        }
+        u32x4 h, m, l;
+        split8(v, h, m, l);
+        Bq[item] = h;
+        Bq[plane + item] = m;
+        Bq[2 * plane + item] = l;
+    }
+}
+
+// One 32-deep chunk of the split product: the lane's 16 values of A are two groups of eight k values, each split into
+// three planes and multiplied with the staged planes of W, smallest terms first.  bq points at this lane's record of
+// the chunk's first group of plane 0; consecutive groups are `ld` records apart, planes `plane` records.
+template <int NT>
+__device__ inline void mfma_chunk_split(const float (&a)[16], const u32x4 *bq, int ld, int plane, acc16 (&acc)[NT])
+{
+#pragma unroll
+    for (int m = 0; m < 2; ++m) {
+        u32x4 b0[NT], b1[NT], b2[NT];
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            b0[t] = bq[m * ld + 32 * t];
+            b1[t] = bq[plane + m * ld + 32 * t];
+            b2[t] = bq[2 * plane + m * ld + 32 * t];
+        }
+        u32x4 ah, am, al;
+        split8(a + 8 * m, ah, am, al);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int t = 0; t < NT; ++t) acc[t] = mfma_bf16(al, b0[t], acc[t]);
+#pragma unroll
+        for (int t = 0; t < NT; ++t) acc[t] = mfma_bf16(am, b1[t], acc[t]);
+#pragma unroll
+        for (int t = 0; t < NT; ++t) acc[t] = mfma_bf16(ah, b2[t], acc[t]);
+#pragma unroll
+        for (int t = 0; t < NT; ++t) acc[t] = mfma_bf16(am, b0[t], acc[t]);
+#pragma unroll
+        for (int t = 0; t < NT; ++t) acc[t] = mfma_bf16(ah, b1[t], acc[t]);
+#pragma unroll
+        for (int t = 0; t < NT; ++t) acc[t] = mfma_bf16(ah, b0[t], acc[t]);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
 // Same product with the whole weight slab [K, 32*NT*WN] resident in LDS: it is staged once per block, after
 // which every wave streams its own 32-row tiles without any barrier.  A block is as many waves as the
 // register budget of the variant allows (one block per compute unit), so the slab is fetched once per compute
 // unit and even a slab that fills the LDS leaves the unit fully occupied.  The k chunks of all of a wave's
 // tiles form one stream; a ring of three register buffers keeps the loads two chunks (8 KB per wave) ahead of
 // the matrix cores, across tile boundaries and epilogues.  Needs K % 32 == 0 and 16-byte aligned rows; the
-// row scale is applied to the rows of A as they are consumed.
-template <int NT, int WN, int WAVES, bool BF16>
+// row scale is applied to the rows of A as they are consumed.  SPLIT: the slab holds the three bfloat16 planes of
+// the weights (6 bytes per value instead of 4) and the product runs on the bf16 matrix cores, see above.
+template <int NT, int WN, int WAVES, bool BF16, bool SPLIT>
 __global__ void __launch_bounds__(64 * WAVES) gemm_rows_resident_kernel(GemmArgs g)
 {
     // WAVES waves = (WAVES / WN) row tiles x WN column groups of 32*NT columns; the slab holds all 32*NT*WN columns
@@ -339,6 +449,9 @@ __global__ void __launch_bounds__(64 * WAVES) gemm_rows_resident_kernel(GemmArgs
     const int first = __builtin_amdgcn_readfirstlane(int(blockIdx.x) * WR + wr), stride = int(gridDim.x) * WR;
     const int kch = g.K / kBK;
     const float *bp0 = Bs + (16 * kk) * BN + wn * 32 * NT + i;
+    u32x4 *Bq = reinterpret_cast<u32x4 *>(Bs);
+    const int plane = g.K / 8 * BN;                         // records per plane of the split slab
+    const u32x4 *bq0 = Bq + (2 * kk) * BN + wn * 32 * NT + i;  // this lane's record of group 2*kk (chunk 0), plane 0
     const int wcol0 = col0 + wn * 32 * NT;
     constexpr int ES = BF16 ? 2 : 4;
     auto row_ptr = [&](int t) __attribute__((always_inline)) {  // this lane's 16 k values of chunk 0 in tile t
@@ -391,7 +504,9 @@ __global__ void __launch_bounds__(64 * WAVES) gemm_rows_resident_kernel(GemmArgs
     issue(b0, s0);
     issue(b1, s1);
     const bool fast_stage = col0 + BN <= g.M && g.ldw % 4 == 0 && (reinterpret_cast<uintptr_t>(g.W) & 15) == 0;
-    if (fast_stage && !g.wT) {
+    if (SPLIT) {
+        stage_split<BN, 64 * WAVES>(Bq, g.W, g.ldw, g.K, g.wT != 0, col0, g.M);
+    } else if (fast_stage && !g.wT) {
         stage_slab<BN, BN, 64 * WAVES>(Bs, g.W, g.ldw, g.K, [&](int) { return col0; });
     } else if (fast_stage) {
         stage_slab_transposed<BN, 64 * WAVES>(Bs, g.W, g.ldw, g.K, col0);
@@ -453,7 +568,10 @@ __global__ void __launch_bounds__(64 * WAVES) gemm_rows_resident_kernel(GemmArgs
         const float f = has_rs ? sc : 1.0f;
 #pragma unroll
         for (int e = 0; e < 16; ++e) cur[e] *= f;
-        mfma_chunk<NT>(cur, bp0 + kc * kBK * BN, BN, 32, acc, NoPrefetch());
+        if (SPLIT)
+            mfma_chunk_split<NT>(cur, bq0 + kc * 4 * BN, BN, plane, acc);
+        else
+            mfma_chunk<NT>(cur, bp0 + kc * kBK * BN, BN, 32, acc, NoPrefetch());
         if (++kc == kch) {
             epilogue();
             kc = 0;
@@ -502,14 +620,14 @@ int resident_blocks(const void *kernel, int threads, size_t lds)
     return blocks;
 }
 
-template <int NT, int WN, int WAVES>
+template <int NT, int WN, int WAVES, bool SPLIT>
 bool gemm_rows_resident_launch(const GemmArgs &g, int bf16, hipStream_t s)
 {
     if (g.K % kBK != 0 || g.lda % 8 != 0) return false;
     constexpr int BN = 32 * NT * WN;
-    const size_t lds = size_t(g.K) * BN * sizeof(float);
+    const size_t lds = size_t(g.K) * BN * (SPLIT ? 6 : sizeof(float));
     if (lds > kLdsBytes - 1024) return false;
-    auto k = bf16 ? gemm_rows_resident_kernel<NT, WN, WAVES, true> : gemm_rows_resident_kernel<NT, WN, WAVES, false>;
+    auto k = bf16 ? gemm_rows_resident_kernel<NT, WN, WAVES, true, SPLIT> : gemm_rows_resident_kernel<NT, WN, WAVES, false, SPLIT>;
     if (lds > 48 * 1024 &&
         hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, int(lds)) != hipSuccess)
         return false;
@@ -523,15 +641,32 @@ bool gemm_rows_resident_launch(const GemmArgs &g, int bf16, hipStream_t s)
     return true;
 }
 
+// REINC_DENSE=fp32 keeps every dense product on the fp32 matrix instructions (the split-bf16 kernels are the default)
+bool dense_split_enabled()
+{
+    static const bool on = [] {
+        const char *v = getenv("REINC_DENSE");
+        return !(v && strcmp(v, "fp32") == 0);
+    }();
+    return on;
+}
+
 // Variant choice (measured on 1e5 .. 2.5e6 rows, K and M in 64 .. 512): the widest accumulator tile whose slab
 // fits wins for outputs of more than 64 columns; when the slab of 128 columns does not fit, 64-column slabs
-// with the column groups on blockIdx.y follow (A is then re-read out of L2).
+// with the column groups on blockIdx.y follow (A is then re-read out of L2).  The split-bf16 variants come first;
+// shapes whose three-plane slab does not fit (K * columns * 6 bytes) stay on the fp32 instructions.
 bool gemm_rows_resident_dispatch(const GemmArgs &g, int bf16, hipStream_t s)
 {
-    if (g.M > 64 && gemm_rows_resident_launch<4, 1, 8>(g, bf16, s)) return true;
-    if (g.M > 64 && gemm_rows_resident_launch<2, 1, 12>(g, bf16, s)) return true;
-    if (g.M > 32 && g.M <= 64 && gemm_rows_resident_launch<2, 1, 16>(g, bf16, s)) return true;
-    return gemm_rows_resident_launch<1, 1, 16>(g, bf16, s);
+    if (dense_split_enabled()) {
+        if (g.M > 64 && gemm_rows_resident_launch<4, 1, 8, true>(g, bf16, s)) return true;
+        if (g.M > 64 && gemm_rows_resident_launch<2, 1, 12, true>(g, bf16, s)) return true;
+        if (g.M > 32 && g.M <= 64 && gemm_rows_resident_launch<2, 1, 12, true>(g, bf16, s)) return true;  // 16 waves would spill
+        if (g.M <= 32 && gemm_rows_resident_launch<1, 1, 16, true>(g, bf16, s)) return true;
+    }
+    if (g.M > 64 && gemm_rows_resident_launch<4, 1, 8, false>(g, bf16, s)) return true;
+    if (g.M > 64 && gemm_rows_resident_launch<2, 1, 12, false>(g, bf16, s)) return true;
+    if (g.M > 32 && g.M <= 64 && gemm_rows_resident_launch<2, 1, 16, false>(g, bf16, s)) return true;
+    return gemm_rows_resident_launch<1, 1, 16, false>(g, bf16, s);
 }
 
 template <int NT, int WM, int WN>
