@@ -390,20 +390,40 @@ __device__ inline void stage_split(u32x4 *Bq, const float *W, int ldw, int K, bo
     }
 }
 
+// The same for K rows of a row-major W whose slab columns are picked by col_of(c) (a source column, or -1 for a
+// column of zeros); the rows become groups group0 .. group0 + K/8 - 1 of a slab of `plane` records per plane.
+template <int NC, int TPB, class ColOf>
+__device__ inline void stage_split_cols(u32x4 *Bq, int plane, int group0, const float *W, int ldw, int K, ColOf col_of)
+{
+    for (int item = threadIdx.x; item < K / 8 * NC; item += TPB) {
+        const int g8 = item / NC, c = col_of(item % NC);
+        float v[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = c >= 0 ? W[int64_t(8 * g8 + e) * ldw + c] : 0.0f;
+        u32x4 h, m, l;
+        split8(v, h, m, l);
+        u32x4 *dst = Bq + group0 * NC + item;
+        dst[0] = h;
+        dst[plane] = m;
+        dst[2 * plane] = l;
+    }
+}
+
 // One 32-deep chunk of the split product: the lane's 16 values of A are two groups of eight k values, each split into
 // three planes and multiplied with the staged planes of W, smallest terms first.  bq points at this lane's record of
-// the chunk's first group of plane 0; consecutive groups are `ld` records apart, planes `plane` records.
-template <int NT>
-__device__ inline void mfma_chunk_split(const float (&a)[16], const u32x4 *bq, int ld, int plane, acc16 (&acc)[NT])
+// the chunk's first group of plane 0; consecutive groups are `ld` records apart, planes `plane` records, the wave's
+// NT column tiles `tile_stride` records; tile t accumulates into acc[t].
+template <int NT, int NACC>
+__device__ inline void mfma_chunk_split(const float (&a)[16], const u32x4 *bq, int ld, int plane, int tile_stride, acc16 (&acc)[NACC])
 {
 #pragma unroll
     for (int m = 0; m < 2; ++m) {
         u32x4 b0[NT], b1[NT], b2[NT];
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
-            b0[t] = bq[m * ld + 32 * t];
-            b1[t] = bq[plane + m * ld + 32 * t];
-            b2[t] = bq[2 * plane + m * ld + 32 * t];
+            b0[t] = bq[m * ld + tile_stride * t];
+            b1[t] = bq[plane + m * ld + tile_stride * t];
+            b2[t] = bq[2 * plane + m * ld + tile_stride * t];
         }
         u32x4 ah, am, al;
         split8(a + 8 * m, ah, am, al);
@@ -569,7 +589,7 @@ __global__ void __launch_bounds__(64 * WAVES) gemm_rows_resident_kernel(GemmArgs
 #pragma unroll
         for (int e = 0; e < 16; ++e) cur[e] *= f;
         if (SPLIT)
-            mfma_chunk_split<NT>(cur, bq0 + kc * 4 * BN, BN, plane, acc);
+            mfma_chunk_split<NT, NT>(cur, bq0 + kc * 4 * BN, BN, plane, 32, acc);
         else
             mfma_chunk<NT>(cur, bp0 + kc * kBK * BN, BN, 32, acc, NoPrefetch());
         if (++kc == kch) {
@@ -805,8 +825,9 @@ __global__ void __launch_bounds__(256) rnn_fused_kernel(RnnArgs g)
 // units without barriers.  Rows [0, d_in) of the slab hold W_i, rows [d_in, d_in + H) hold W_h, so the k
 // chunks of x and of h_prev form one stream per tile, and the chunks of all of a wave's tiles one stream
 // overall; a ring of three register buffers keeps the loads two chunks ahead of the matrix cores.  Needs
-// d_in % 32 == 0, H % 32 == 0 and 16-byte aligned rows.
-template <bool LSTM, int WN, int WAVES>
+// d_in % 32 == 0, H % 32 == 0 and 16-byte aligned rows.  SPLIT: the slab holds the three bfloat16 planes of the
+// weights and the products run on the bf16 matrix cores (see the note on fp32 products above).
+template <bool LSTM, int WN, int WAVES, bool SPLIT>
 __global__ void __launch_bounds__(64 * WAVES) rnn_fused_resident_kernel(RnnArgs g)
 {
     extern __shared__ float Bs[];
@@ -872,7 +893,16 @@ __global__ void __launch_bounds__(64 * WAVES) rnn_fused_resident_kernel(RnnArgs 
     issue(b1, s1);
     const bool fast_stage = h0 + BH <= H && H % 4 == 0 && (reinterpret_cast<uintptr_t>(g.W_i) & 15) == 0 &&
                             (reinterpret_cast<uintptr_t>(g.W_h) & 15) == 0;
-    if (fast_stage) {
+    u32x4 *Bq = reinterpret_cast<u32x4 *>(Bs);
+    const int plane = (g.d_in + H) / 8 * NC;  // records per plane of the split slab
+    if (SPLIT) {
+        auto col_of = [&](int c) {
+            const int gate = c / BH, jj = c - gate * BH;
+            return h0 + jj < H ? gate * H + h0 + jj : -1;
+        };
+        stage_split_cols<NC, 64 * WAVES>(Bq, plane, 0, g.W_i, ldw, g.d_in, col_of);
+        stage_split_cols<NC, 64 * WAVES>(Bq, plane, g.d_in / 8, g.W_h, ldw, H, col_of);
+    } else if (fast_stage) {
         stage_slab<NC, BH, 64 * WAVES>(Bs, g.W_i, ldw, g.d_in, [&](int gate) { return gate * H + h0; });
         stage_slab<NC, BH, 64 * WAVES>(Bs + int64_t(g.d_in) * NC, g.W_h, ldw, H, [&](int gate) { return gate * H + h0; });
     } else {
@@ -969,7 +999,10 @@ __global__ void __launch_bounds__(64 * WAVES) rnn_fused_resident_kernel(RnnArgs 
         const float f = (has_xs && kc < kx) ? sc : 1.0f;
 #pragma unroll
         for (int e = 0; e < 16; ++e) cur[e] *= f;
-        mfma_chunk_map<KG, KG - 1, G>(cur, bp, NC, BH, acc, NoPrefetch());
+        if (SPLIT)
+            mfma_chunk_split<KG, 4>(cur, Bq + (4 * kc + 2 * kk) * NC + wn * 32 + i, NC, plane, BH, acc);
+        else
+            mfma_chunk_map<KG, KG - 1, G>(cur, bp, NC, BH, acc, NoPrefetch());
         ++kc;
         if (!LSTM && kc == kx) {  // GRU: the x part of the n gate is complete; the h part starts from zero
             acc[3] = acc[2];
@@ -1009,15 +1042,15 @@ __global__ void __launch_bounds__(64 * WAVES) rnn_fused_resident_kernel(RnnArgs 
     }
 }
 
-template <bool LSTM, int WN, int WAVES>
+template <bool LSTM, int WN, int WAVES, bool SPLIT>
 bool rnn_fused_resident_launch(const RnnArgs &g, hipStream_t s)
 {
     constexpr int KG = LSTM ? 4 : 3;
     constexpr int WM = WAVES / WN;
     if (g.d_in % kBK != 0 || g.H % kBK != 0 || g.d_in % 4 != 0) return false;
-    const size_t lds = size_t(g.d_in + g.H) * KG * 32 * WN * sizeof(float);
+    const size_t lds = size_t(g.d_in + g.H) * KG * 32 * WN * (SPLIT ? 6 : sizeof(float));
     if (lds > kLdsBytes - 1024) return false;
-    auto k = rnn_fused_resident_kernel<LSTM, WN, WAVES>;
+    auto k = rnn_fused_resident_kernel<LSTM, WN, WAVES, SPLIT>;
     if (lds > 48 * 1024 &&
         hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, int(lds)) != hipSuccess)
         return false;
@@ -1032,12 +1065,19 @@ bool rnn_fused_resident_launch(const RnnArgs &g, hipStream_t s)
 
 constexpr int kRnnWaves = 12;  // three waves per SIMD: the kernel needs at most 168 registers
 
+constexpr int kRnnSplitWaves = 8;  // the split variant holds three planes of every fragment: two waves per SIMD
+
 template <bool LSTM>
 bool rnn_fused_resident_dispatch(const RnnArgs &g, hipStream_t s)
 {
-    if (g.H % 128 == 0 && rnn_fused_resident_launch<LSTM, 4, kRnnWaves>(g, s)) return true;
-    if (g.H % 64 == 0 && rnn_fused_resident_launch<LSTM, 2, kRnnWaves>(g, s)) return true;
-    return rnn_fused_resident_launch<LSTM, 1, kRnnWaves>(g, s);
+    if (dense_split_enabled()) {  // shapes whose three-plane slab does not fit stay on the fp32 instructions
+        if (g.H % 128 == 0 && rnn_fused_resident_launch<LSTM, 4, kRnnSplitWaves, true>(g, s)) return true;
+        if (g.H % 64 == 0 && rnn_fused_resident_launch<LSTM, 2, kRnnSplitWaves, true>(g, s)) return true;
+        if (rnn_fused_resident_launch<LSTM, 1, kRnnSplitWaves, true>(g, s)) return true;
+    }
+    if (g.H % 128 == 0 && rnn_fused_resident_launch<LSTM, 4, kRnnWaves, false>(g, s)) return true;
+    if (g.H % 64 == 0 && rnn_fused_resident_launch<LSTM, 2, kRnnWaves, false>(g, s)) return true;
+    return rnn_fused_resident_launch<LSTM, 1, kRnnWaves, false>(g, s);
 }
 
 // ---- weight / bias gradient: C[K,M] = sum_rows (rs .* A)^T G ---------------------------------------------
@@ -1058,8 +1098,30 @@ struct ReduceArgs {
     int accumulate;  // add to the partial slabs instead of overwriting them (later timesteps of a window)
 };
 
-template <bool HAS_RS>
-__global__ void __launch_bounds__(256) gemm_reduce_kernel(ReduceArgs g)
+// One trip of a wave on the bf16 matrix cores: the lane's eight values per operand are eight rows of the trip
+// (the contraction runs over rows), each operand is split into its three bfloat16 planes and the six products of
+// relative size 2^-16 and above are accumulated, smallest first (see the note on fp32 products above).
+__device__ inline void reduce_trip_split(const float (&a0)[8], const float (&a1)[8], const float (&g0)[8], const float (&g1)[8],
+                                         acc16 (&acc)[2][2])
+{
+    u32x4 A0[3], A1[3], G0[3], G1[3];
+    split8(g0, G0[0], G0[1], G0[2]);
+    split8(g1, G1[0], G1[1], G1[2]);
+    split8(a0, A0[0], A0[1], A0[2]);
+    split8(a1, A1[0], A1[1], A1[2]);
+    constexpr int order[6][2] = {{2, 0}, {1, 1}, {0, 2}, {1, 0}, {0, 1}, {0, 0}};
+#pragma unroll
+    for (int o = 0; o < 6; ++o) {
+        const int p = order[o][0], q = order[o][1];
+        acc[0][0] = mfma_bf16(A0[p], G0[q], acc[0][0]);
+        acc[0][1] = mfma_bf16(A0[p], G1[q], acc[0][1]);
+        acc[1][0] = mfma_bf16(A1[p], G0[q], acc[1][0]);
+        acc[1][1] = mfma_bf16(A1[p], G1[q], acc[1][1]);
+    }
+}
+
+template <bool HAS_RS, bool SPLIT>
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) gemm_reduce_kernel(ReduceArgs g)
 {
     // wave w finishes accumulator tile w of the 2x2: the other waves park their share of it here (two tiles at
     // a time, to keep the block's LDS at 25 KB)
@@ -1117,6 +1179,23 @@ __global__ void __launch_bounds__(256) gemm_reduce_kernel(ReduceArgs g)
             if (HAS_RS) sp += 8 * kRU;
         };
         auto multiply = [&](float(&t)[5][kRU]) __attribute__((always_inline)) {
+            if (SPLIT) {
+                static_assert(kRU == 8, "a trip is one depth-16 matrix instruction per tile: eight rows per lane");
+                if (HAS_RS) {
+#pragma unroll
+                    for (int u = 0; u < kRU; ++u) {
+                        t[0][u] *= t[4][u];
+                        t[1][u] *= t[4][u];
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < kRU; ++u) {
+                    bsum[0] += t[2][u];
+                    bsum[1] += t[3][u];
+                }
+                reduce_trip_split(t[0], t[1], t[2], t[3], acc);
+                return;
+            }
 #pragma unroll
             for (int u = 0; u < kRU; ++u) {
                 const float a0 = HAS_RS ? t[0][u] * t[4][u] : t[0][u], a1 = HAS_RS ? t[1][u] * t[4][u] : t[1][u];
@@ -1167,6 +1246,15 @@ __global__ void __launch_bounds__(256) gemm_reduce_kernel(ReduceArgs g)
                 if (cb0) b0[u] = gp[0];
                 if (cb1) b1[u] = gp[32];
             }
+        }
+        if (SPLIT) {
+#pragma unroll
+            for (int u = 0; u < kRU; ++u) {
+                bsum[0] += b0[u];
+                bsum[1] += b1[u];
+            }
+            reduce_trip_split(a0, a1, b0, b1, acc);
+            continue;
         }
 #pragma unroll
         for (int u = 0; u < kRU; ++u) {
@@ -1453,8 +1541,12 @@ int reduce_chunks(int64_t n, int32_t K, int32_t M)
 {
     // as many blocks as are resident at once (registers and LDS decide how many fit a compute unit), at least
     // 256 rows each
-    static const int per_cu = std::max(1, std::min(resident_blocks(reinterpret_cast<const void *>(gemm_reduce_kernel<false>), 256, 0),
-                                                   resident_blocks(reinterpret_cast<const void *>(gemm_reduce_kernel<true>), 256, 0)));
+    static const int per_cu =
+        dense_split_enabled()
+            ? std::max(1, std::min(resident_blocks(reinterpret_cast<const void *>(gemm_reduce_kernel<false, true>), 256, 0),
+                                   resident_blocks(reinterpret_cast<const void *>(gemm_reduce_kernel<true, true>), 256, 0)))
+            : std::max(1, std::min(resident_blocks(reinterpret_cast<const void *>(gemm_reduce_kernel<false, false>), 256, 0),
+                                   resident_blocks(reinterpret_cast<const void *>(gemm_reduce_kernel<true, false>), 256, 0)));
     const int64_t slabs = int64_t((K + 63) / 64) * ((M + 63) / 64);
     int64_t chunks = std::max<int64_t>(1, int64_t(kNumCU) * per_cu / slabs);
     if (chunks >= 8) chunks &= ~int64_t(7);  // the grid is padded to whole groups of 8 chunks (one per XCD): stay resident
@@ -1479,10 +1571,11 @@ void launch_gemm_reduce(const float *A, int32_t lda, const float *row_scale, con
     ReduceArgs g{A, lda, row_scale, G, ldg, n, K, M, rpc, partial, chunks, accumulate};
     const int slabs = ((K + 63) / 64) * ((M + 63) / 64);
     const unsigned blocks = unsigned(slabs) * unsigned((chunks + 7) / 8) * 8u;
+    const bool split = dense_split_enabled();
     if (row_scale)
-        gemm_reduce_kernel<true><<<blocks, 256, 0, s>>>(g);
+        (split ? gemm_reduce_kernel<true, true> : gemm_reduce_kernel<true, false>)<<<blocks, 256, 0, s>>>(g);
     else
-        gemm_reduce_kernel<false><<<blocks, 256, 0, s>>>(g);
+        (split ? gemm_reduce_kernel<false, true> : gemm_reduce_kernel<false, false>)<<<blocks, 256, 0, s>>>(g);
 }
 
 void launch_reduce_partials(const float *partial, int64_t n, int32_t K, int32_t M, float *dW, float *db, hipStream_t s)
