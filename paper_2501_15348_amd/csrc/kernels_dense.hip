@@ -682,6 +682,8 @@ bool gemm_rows_resident_dispatch(const GemmArgs &g, int bf16, hipStream_t s)
         if (g.M > 64 && gemm_rows_resident_launch<2, 1, 12, true>(g, bf16, s)) return true;
         if (g.M > 32 && g.M <= 64 && gemm_rows_resident_launch<2, 1, 12, true>(g, bf16, s)) return true;  // 16 waves would spill
         if (g.M <= 32 && gemm_rows_resident_launch<1, 1, 16, true>(g, bf16, s)) return true;
+        // (deep products such as K = 512 -> 128 would fit a 32-column split slab only; four column groups re-splitting
+        // the same rows were measured no faster than the fp32 instructions with a 64-column slab)
     }
     if (g.M > 64 && gemm_rows_resident_launch<4, 1, 8, false>(g, bf16, s)) return true;
     if (g.M > 64 && gemm_rows_resident_launch<2, 1, 12, false>(g, bf16, s)) return true;
