@@ -266,110 +266,209 @@ int reinc_load_features_delta(reinc_ctx *ctx, int32_t t, const int32_t *rows, in
 
 // ------------------------------------------------------------------------------------------------ deltas
 
-static int build_one(reinc_ctx *ctx, int32_t t, hipStream_t s)
+// Scratch one step needs while its deltas are being built (bytes, with the allocator's rounding).
+static uint64_t step_scratch_bytes(int64_t n, int64_t na, int64_t nb)
+{
+    auto r = [](int64_t count, int64_t elem) { return (uint64_t(std::max<int64_t>(count, 1)) * elem + 255) & ~uint64_t(255); };
+    return 5 * r(n, 4) + r(na, 4) + 2 * r(nb, 4) + 3 * r(n + 1, 8) + r(na + 1, 8) + 2 * r(nb + 1, 8);
+}
+
+// Builds the deltas of a group of steps.  Every stage runs for all steps of the group before the next stage begins,
+// all prefix sums of a stage are one launch, and the host waits twice per group (for the sizes of the outputs, and at
+// the end): on small graphs a step's kernels last microseconds, and step-by-step building was bound by launches and
+// round trips to the host.
+static int build_group(reinc_ctx *ctx, const std::vector<int32_t> &steps, hipStream_t s)
 {
     const int64_t n = ctx->N();
     const int32_t d = ctx->cfg.dims[0];
     const int bf16 = ctx->cfg.feat_dtype == REINC_BF16;
-    const Snapshot &a = ctx->snaps[t - 1];
-    const Snapshot &b = ctx->snaps[t];
-    Delta &dl = ctx->deltas[t];
-    if (dl.built) return REINC_OK;
-    if (!a.edges_loaded || !b.edges_loaded || !a.feats_loaded || !b.feats_loaded)
-        return ctx->fail(REINC_E_STATE, "step %d needs edges and features of snapshots %d and %d", t, t - 1, t);
+    const int G = int(steps.size());
+    if (G == 0) return REINC_OK;
     ctx->scratch_reset();
     ctx->note_derived();
     const uint64_t mark = ctx->bottom;
     auto nomem = [&](const char *what) {
         ctx->bottom = mark;
         ctx->scratch_reset();
-        return ctx->fail(REINC_E_NOMEM, "arena exhausted in build_deltas(%d): %s", t, what);
+        for (int32_t t : steps) ctx->deltas[t] = Delta();
+        return ctx->fail(REINC_E_NOMEM, "arena exhausted in build_deltas(%d..%d): %s", steps.front(), steps.back(), what);
     };
-    const int64_t na = a.nnz, nb = b.nnz;
     auto i32s = [&](int64_t c) { return static_cast<int32_t *>(ctx->scratch(uint64_t(std::max<int64_t>(c, 1)) * 4)); };
     auto i64s = [&](int64_t c) { return static_cast<int64_t *>(ctx->scratch(uint64_t(std::max<int64_t>(c, 1)) * 8)); };
-    int32_t *cflags = i32s(n), *cindex = i32s(n), *row_flag = i32s(n);
-    int32_t *absent_a = i32s(na), *absent_b = i32s(nb), *hit_b = i32s(nb);
-    int64_t *coffs = i64s(n + 1), *roffs = i64s(n + 1);
-    int64_t *pos_del = i64s(na + 1), *pos_ins = i64s(nb + 1), *pos_hit = i64s(nb + 1);
-    void *scan_tmp = ctx->scratch(scan_tmp_bytes(std::max(std::max(na, nb), n)));
-    if (!cflags || !cindex || !row_flag || !absent_a || !absent_b || !hit_b || !coffs || !roffs || !pos_del || !pos_ins ||
-        !pos_hit || !scan_tmp)
-        return nomem("scratch");
+    struct Work {
+        int32_t *cflags, *cindex, *row_flag, *long_flag, *absent_a, *absent_b, *hit_b;
+        int64_t *coffs, *roffs, *loffs, *pos_del, *pos_ins, *pos_hit;
+    };
+    std::vector<Work> work(G);
+    // job tables of the three scan stages and the table of totals, built up front (every address is known once the
+    // scratch and the row pointers are allocated) and uploaded in one copy
+    std::vector<ScanJob> jobs;
+    jobs.reserve(size_t(6) * G);
+    int64_t tiles[3] = {0, 0, 0};
+    int first_job[4] = {0, 0, 0, 0};
+    bool ok = true;
+    for (int g = 0; g < G; ++g) {
+        const Snapshot &a = ctx->snaps[steps[g] - 1], &b = ctx->snaps[steps[g]];
+        Work &w = work[g];
+        w.cflags = i32s(n), w.cindex = i32s(n), w.row_flag = i32s(n), w.long_flag = i32s(n);
+        w.absent_a = i32s(a.nnz), w.absent_b = i32s(b.nnz), w.hit_b = i32s(b.nnz);
+        w.coffs = i64s(n + 1), w.roffs = i64s(n + 1), w.loffs = i64s(n + 1);
+        w.pos_del = i64s(a.nnz + 1), w.pos_ins = i64s(b.nnz + 1), w.pos_hit = i64s(b.nnz + 1);
+        ok = ok && w.cflags && w.cindex && w.row_flag && w.long_flag && w.absent_a && w.absent_b && w.hit_b && w.coffs && w.roffs &&
+             w.loffs && w.pos_del && w.pos_ins && w.pos_hit;
+        Delta &dl = ctx->deltas[steps[g]];
+        dl.ins_ptr = static_cast<int64_t *>(ctx->alloc(uint64_t(n + 1) * 8));
+        dl.del_ptr = static_cast<int64_t *>(ctx->alloc(uint64_t(n + 1) * 8));
+        dl.ent_ptr = static_cast<int64_t *>(ctx->alloc(uint64_t(n + 1) * 8));
+        ok = ok && dl.ins_ptr && dl.del_ptr && dl.ent_ptr;
+    }
+    if (!ok) return nomem("scratch and row pointers");
+    auto add_job = [&](int stage, const int32_t *in, int64_t *out, int64_t count) {
+        jobs.push_back(ScanJob{in, out, count, tiles[stage]});
+        tiles[stage] += scan_tiles(count);
+    };
+    for (int g = 0; g < G; ++g) add_job(0, work[g].cflags, work[g].coffs, n);
+    first_job[1] = int(jobs.size());
+    for (int g = 0; g < G; ++g) {
+        const Snapshot &a = ctx->snaps[steps[g] - 1], &b = ctx->snaps[steps[g]];
+        add_job(1, work[g].absent_a, work[g].pos_del, a.nnz);
+        add_job(1, work[g].absent_b, work[g].pos_ins, b.nnz);
+        add_job(1, work[g].hit_b, work[g].pos_hit, b.nnz);
+    }
+    first_job[2] = int(jobs.size());
+    for (int g = 0; g < G; ++g) {
+        add_job(2, work[g].row_flag, work[g].roffs, n);
+        add_job(2, work[g].long_flag, work[g].loffs, n);
+    }
+    first_job[3] = int(jobs.size());
+    constexpr int kTotals = 6;  // per step: inserted, deleted, entries, changed rows of S, changed nodes, long rows
+    std::vector<const int64_t *> total_ptrs(size_t(kTotals) * G);
+    for (int g = 0; g < G; ++g) {
+        const Delta &dl = ctx->deltas[steps[g]];
+        const int64_t *p[kTotals] = {dl.ins_ptr + n, dl.del_ptr + n, dl.ent_ptr + n, work[g].roffs + n, work[g].coffs + n, work[g].loffs + n};
+        std::copy(p, p + kTotals, total_ptrs.begin() + size_t(kTotals) * g);
+    }
+    const int64_t max_tiles = std::max(tiles[0], std::max(tiles[1], tiles[2]));
+    ScanJob *jobs_dev = static_cast<ScanJob *>(ctx->scratch(jobs.size() * sizeof(ScanJob)));
+    const int64_t **ptrs_dev = static_cast<const int64_t **>(ctx->scratch(total_ptrs.size() * sizeof(int64_t *)));
+    int64_t *totals_dev = i64s(int64_t(kTotals) * G);
+    int64_t *tile_sums = i64s(max_tiles);
+    if (!jobs_dev || !ptrs_dev || !totals_dev || !tile_sums) return nomem("scan tables");
+    REINC_HIP(ctx, hipMemcpyAsync(jobs_dev, jobs.data(), jobs.size() * sizeof(ScanJob), hipMemcpyHostToDevice, s));
+    REINC_HIP(ctx, hipMemcpyAsync(ptrs_dev, total_ptrs.data(), total_ptrs.size() * sizeof(int64_t *), hipMemcpyHostToDevice, s));
 
-    // change set C_t
-    launch_fill_i32(cflags, n, 0, s);
-    if (b.feats_from_delta)
-        launch_feature_flags_list(b.feat_rows, b.n_feat_rows, n, cflags, s);
-    else
-        launch_feature_flags_compare(a.x, b.x, n, d * ctx->elem_bytes(), cflags, s);
-    if (ctx->cfg.agg_kind == REINC_AGG_SYM) launch_degree_flags(a.row_ptr, b.row_ptr, n, cflags, s);
-    launch_scan(cflags, coffs, n, scan_tmp, s);
-    // per-edge flags (one thread per edge) and their prefix sums: the prefix sums are the output positions
+    // stage 1: change sets C_t
+    for (int g = 0; g < G; ++g) {
+        const Snapshot &a = ctx->snaps[steps[g] - 1], &b = ctx->snaps[steps[g]];
+        launch_fill_i32(work[g].cflags, n, 0, s);
+        if (b.feats_from_delta)
+            launch_feature_flags_list(b.feat_rows, b.n_feat_rows, n, work[g].cflags, s);
+        else
+            launch_feature_flags_compare(a.x, b.x, n, d * ctx->elem_bytes(), work[g].cflags, s);
+        if (ctx->cfg.agg_kind == REINC_AGG_SYM) launch_degree_flags(a.row_ptr, b.row_ptr, n, work[g].cflags, s);
+    }
+    launch_multi_scan(jobs_dev + first_job[0], first_job[1] - first_job[0], tiles[0], tile_sums, s);
+    // stage 2: per-edge flags (one thread per edge); their prefix sums are the output positions
     {
         ProfScope prof(ctx, REINC_K_DIFF, s);
-        launch_edge_flags(a.rowid, a.col, na, b.row_ptr, b.col, nullptr, absent_a, nullptr, s);
-        launch_edge_flags(b.rowid, b.col, nb, a.row_ptr, a.col, cflags, absent_b, hit_b, s);
+        for (int g = 0; g < G; ++g) {
+            const Snapshot &a = ctx->snaps[steps[g] - 1], &b = ctx->snaps[steps[g]];
+            launch_edge_flags(a.rowid, a.col, a.nnz, b.row_ptr, b.col, nullptr, work[g].absent_a, nullptr, s);
+            launch_edge_flags(b.rowid, b.col, b.nnz, a.row_ptr, a.col, work[g].cflags, work[g].absent_b, work[g].hit_b, s);
+        }
     }
-    launch_scan(absent_a, pos_del, na, scan_tmp, s);
-    launch_scan(absent_b, pos_ins, nb, scan_tmp, s);
-    launch_scan(hit_b, pos_hit, nb, scan_tmp, s);
-    dl.ins_ptr = static_cast<int64_t *>(ctx->alloc(uint64_t(n + 1) * 8));
-    dl.del_ptr = static_cast<int64_t *>(ctx->alloc(uint64_t(n + 1) * 8));
-    dl.ent_ptr = static_cast<int64_t *>(ctx->alloc(uint64_t(n + 1) * 8));
-    if (!dl.ins_ptr || !dl.del_ptr || !dl.ent_ptr) return nomem("row pointers");
-    launch_delta_row_ptrs(a.row_ptr, b.row_ptr, pos_del, pos_ins, pos_hit, coffs, ctx->cfg.self_loop, n, dl.ins_ptr,
-                          dl.del_ptr, dl.ent_ptr, row_flag, s);
-    launch_scan(row_flag, roffs, n, scan_tmp, s);
-    int32_t *long_flag = nullptr;
-    int64_t *loffs = i64s(n + 1);
-    int32_t *long_flag_own = i32s(n);
-    if (!loffs || !long_flag_own) return nomem("scratch");
-    long_flag = long_flag_own;
-    launch_row_long_flags(dl.ent_ptr, n, long_flag, s);
-    launch_scan(long_flag, loffs, n, scan_tmp, s);
-    int64_t n_long = 0;
-    REINC_HIP(ctx, hipMemcpyAsync(&n_long, loffs + n, 8, hipMemcpyDeviceToHost, s));
-    int64_t totals[5] = {0, 0, 0, 0, 0};
-    REINC_HIP(ctx, hipMemcpyAsync(&totals[0], dl.ins_ptr + n, 8, hipMemcpyDeviceToHost, s));
-    REINC_HIP(ctx, hipMemcpyAsync(&totals[1], dl.del_ptr + n, 8, hipMemcpyDeviceToHost, s));
-    REINC_HIP(ctx, hipMemcpyAsync(&totals[2], dl.ent_ptr + n, 8, hipMemcpyDeviceToHost, s));
-    REINC_HIP(ctx, hipMemcpyAsync(&totals[3], roffs + n, 8, hipMemcpyDeviceToHost, s));
-    REINC_HIP(ctx, hipMemcpyAsync(&totals[4], coffs + n, 8, hipMemcpyDeviceToHost, s));
+    launch_multi_scan(jobs_dev + first_job[1], first_job[2] - first_job[1], tiles[1], tile_sums, s);
+    // stage 3: row pointers of the three outputs, rows that change, rows with many entries
+    for (int g = 0; g < G; ++g) {
+        const Snapshot &a = ctx->snaps[steps[g] - 1], &b = ctx->snaps[steps[g]];
+        const Delta &dl = ctx->deltas[steps[g]];
+        launch_delta_row_ptrs(a.row_ptr, b.row_ptr, work[g].pos_del, work[g].pos_ins, work[g].pos_hit, work[g].coffs,
+                              ctx->cfg.self_loop, n, dl.ins_ptr, dl.del_ptr, dl.ent_ptr, work[g].row_flag, s);
+        launch_row_long_flags(dl.ent_ptr, n, work[g].long_flag, s);
+    }
+    launch_multi_scan(jobs_dev + first_job[2], first_job[3] - first_job[2], tiles[2], tile_sums, s);
+    launch_gather_i64(ptrs_dev, kTotals * G, totals_dev, s);
+    std::vector<int64_t> totals(size_t(kTotals) * G);
+    REINC_HIP(ctx, hipMemcpyAsync(totals.data(), totals_dev, totals.size() * 8, hipMemcpyDeviceToHost, s));
     REINC_HIP(ctx, hipStreamSynchronize(s));
-    const int64_t n_changed = totals[4];
-    dl.changed = static_cast<int32_t *>(ctx->alloc(uint64_t(std::max<int64_t>(n_changed, 1)) * 4));
-    dl.dY = static_cast<float *>(ctx->alloc(uint64_t(std::max<int64_t>(n_changed, 1)) * d * 4));
-    dl.ins_col = static_cast<int32_t *>(ctx->alloc(uint64_t(std::max<int64_t>(totals[0], 1)) * 4));
-    dl.del_col = static_cast<int32_t *>(ctx->alloc(uint64_t(std::max<int64_t>(totals[1], 1)) * 4));
-    dl.ent = static_cast<uint32_t *>(ctx->alloc(uint64_t(std::max<int64_t>(totals[2], 1)) * 4));
-    dl.rows = static_cast<int32_t *>(ctx->alloc(uint64_t(std::max<int64_t>(totals[3], 1)) * 4));
-    dl.long_rows = static_cast<int32_t *>(ctx->alloc(uint64_t(std::max<int64_t>(n_long, 1)) * 4));
-    dl.n_long_rows = n_long;
-    if (!dl.changed || !dl.dY || !dl.ins_col || !dl.del_col || !dl.ent || !dl.rows || !dl.long_rows)
-        return nomem("delta entries");
-    launch_compact(long_flag, loffs, n, dl.long_rows, nullptr, s);
-    launch_compact(cflags, coffs, n, dl.changed, cindex, s);
-    launch_dy(a.x, b.x, bf16, a.p, b.p, dl.changed, n_changed, d, dl.dY, s);
-    {
-        ProfScope prof(ctx, REINC_K_DIFF, s);
-        launch_delta_fill(a.rowid, a.col, na, b.rowid, b.col, nb, b.row_ptr, absent_a, absent_b, hit_b, pos_del, pos_ins,
-                          pos_hit, cindex, ctx->cfg.self_loop, n, dl.ins_ptr, dl.ins_col, dl.del_ptr, dl.del_col, dl.ent_ptr,
-                          dl.ent, s);
+    // stage 4: outputs of the sizes just learnt
+    for (int g = 0; g < G; ++g) {
+        const int64_t *tt = &totals[size_t(kTotals) * g];
+        Delta &dl = ctx->deltas[steps[g]];
+        auto take = [&](int64_t count, int64_t elem) { return ctx->alloc(uint64_t(std::max<int64_t>(count, 1)) * elem); };
+        dl.changed = static_cast<int32_t *>(take(tt[4], 4));
+        dl.dY = static_cast<float *>(take(tt[4], int64_t(d) * 4));
+        dl.ins_col = static_cast<int32_t *>(take(tt[0], 4));
+        dl.del_col = static_cast<int32_t *>(take(tt[1], 4));
+        dl.ent = static_cast<uint32_t *>(take(tt[2], 4));
+        dl.rows = static_cast<int32_t *>(take(tt[3], 4));
+        dl.long_rows = static_cast<int32_t *>(take(tt[5], 4));
+        dl.n_long_rows = tt[5];
+        if (!dl.changed || !dl.dY || !dl.ins_col || !dl.del_col || !dl.ent || !dl.rows || !dl.long_rows)
+            return nomem("delta entries");
     }
-    launch_compact(row_flag, roffs, n, dl.rows, nullptr, s);
+    for (int g = 0; g < G; ++g) {
+        const Snapshot &a = ctx->snaps[steps[g] - 1], &b = ctx->snaps[steps[g]];
+        const int64_t *tt = &totals[size_t(kTotals) * g];
+        Delta &dl = ctx->deltas[steps[g]];
+        const Work &w = work[g];
+        launch_compact(w.long_flag, w.loffs, n, dl.long_rows, nullptr, s);
+        launch_compact(w.cflags, w.coffs, n, dl.changed, w.cindex, s);
+        launch_dy(a.x, b.x, bf16, a.p, b.p, dl.changed, tt[4], d, dl.dY, s);
+        {
+            ProfScope prof(ctx, REINC_K_DIFF, s);
+            launch_delta_fill(a.rowid, a.col, a.nnz, b.rowid, b.col, b.nnz, b.row_ptr, w.absent_a, w.absent_b, w.hit_b, w.pos_del,
+                              w.pos_ins, w.pos_hit, w.cindex, ctx->cfg.self_loop, n, dl.ins_ptr, dl.ins_col, dl.del_ptr,
+                              dl.del_col, dl.ent_ptr, dl.ent, s);
+        }
+        launch_compact(w.row_flag, w.roffs, n, dl.rows, nullptr, s);
+    }
     REINC_HIP(ctx, hipGetLastError());
     REINC_HIP(ctx, hipStreamSynchronize(s));
     ctx->scratch_reset();
-    dl.info.num_edges_prev = a.nnz;
-    dl.info.num_edges_cur = b.nnz;
-    dl.info.n_ins = totals[0];
-    dl.info.n_del = totals[1];
-    dl.info.n_changed = n_changed;
-    dl.info.n_entries = totals[2];
-    dl.info.n_fchg_entries = totals[2] - totals[0] - totals[1];
-    dl.info.n_rows = totals[3];
-    dl.built = true;
+    for (int g = 0; g < G; ++g) {
+        const Snapshot &a = ctx->snaps[steps[g] - 1], &b = ctx->snaps[steps[g]];
+        const int64_t *tt = &totals[size_t(kTotals) * g];
+        Delta &dl = ctx->deltas[steps[g]];
+        dl.info.num_edges_prev = a.nnz;
+        dl.info.num_edges_cur = b.nnz;
+        dl.info.n_ins = tt[0];
+        dl.info.n_del = tt[1];
+        dl.info.n_changed = tt[4];
+        dl.info.n_entries = tt[2];
+        dl.info.n_fchg_entries = tt[2] - tt[0] - tt[1];
+        dl.info.n_rows = tt[3];
+        dl.built = true;
+    }
+    return REINC_OK;
+}
+
+// Builds the given steps in groups as large as the free scratch allows (at least one step at a time).
+static int build_steps(reinc_ctx *ctx, const std::vector<int32_t> &todo, hipStream_t s)
+{
+    const int64_t n = ctx->N();
+    size_t i = 0;
+    while (i < todo.size()) {
+        ctx->scratch_reset();
+        // room: what is free now, less the persistent outputs this group will take (row pointers now; entries bounded
+        // by the edges of both snapshots, the changed rows and their features)
+        const uint64_t room = ctx->top > ctx->bottom ? ctx->top - ctx->bottom : 0;
+        uint64_t used = 0;
+        std::vector<int32_t> group;
+        while (i + group.size() < todo.size()) {
+            const int32_t t = todo[i + group.size()];
+            const Snapshot &a = ctx->snaps[t - 1], &b = ctx->snaps[t];
+            const uint64_t persistent = 3 * uint64_t(n + 1) * 8 + uint64_t(2 * a.nnz + 3 * b.nnz + 4 * n) * 4 +
+                                        uint64_t(n) * ctx->cfg.dims[0] * 4 + 16 * 256;
+            const uint64_t tables = uint64_t(a.nnz + 2 * b.nnz + 2 * n) / 256 + 4096;  // tile sums, job and pointer tables
+            const uint64_t need = step_scratch_bytes(n, a.nnz, b.nnz) + persistent + tables;
+            if (!group.empty() && used + need > room) break;
+            used += need;
+            group.push_back(t);
+        }
+        REINC_TRY(build_group(ctx, group, s));
+        i += group.size();
+    }
     return REINC_OK;
 }
 
@@ -377,16 +476,22 @@ int reinc_build_deltas(reinc_ctx *ctx, int32_t t, void *stream)
 {
     if (!ctx) return REINC_E_ARG;
     REINC_HIP(ctx, hipSetDevice(ctx->cfg.device));
+    std::vector<int32_t> todo;
     if (t < 0) {
         for (int32_t k = 1; k < ctx->cfg.num_snapshots; ++k) {
             const Snapshot &a = ctx->snaps[k - 1], &b = ctx->snaps[k];
-            if (a.edges_loaded && b.edges_loaded && a.feats_loaded && b.feats_loaded) REINC_TRY(build_one(ctx, k, as_stream(stream)));
+            if (a.edges_loaded && b.edges_loaded && a.feats_loaded && b.feats_loaded && !ctx->deltas[k].built) todo.push_back(k);
         }
-        return REINC_OK;
+        return build_steps(ctx, todo, as_stream(stream));
     }
     REINC_TRY(check_t(ctx, t));
     if (t == 0) return ctx->fail(REINC_E_ARG, "step 0 has no predecessor");
-    return build_one(ctx, t, as_stream(stream));
+    if (ctx->deltas[t].built) return REINC_OK;
+    const Snapshot &a = ctx->snaps[t - 1], &b = ctx->snaps[t];
+    if (!a.edges_loaded || !b.edges_loaded || !a.feats_loaded || !b.feats_loaded)
+        return ctx->fail(REINC_E_STATE, "step %d needs edges and features of snapshots %d and %d", t, t - 1, t);
+    todo.push_back(t);
+    return build_steps(ctx, todo, as_stream(stream));
 }
 
 static int need_delta(reinc_ctx *ctx, int32_t t)

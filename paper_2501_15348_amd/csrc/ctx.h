@@ -225,6 +225,17 @@ namespace reinc {
 // exclusive scan of int32 counts [n] into int64 offsets [n+1]; tmp: scratch of scan_tmp_bytes(n)
 uint64_t scan_tmp_bytes(int64_t n);
 void launch_scan(const int32_t *counts, int64_t *offsets, int64_t n, void *tmp, hipStream_t s);
+// Many exclusive scans in one launch.  Job j scans in[0, n) into out[0, n]; tile0 = scan_tiles() of all jobs before
+// it.  jobs_dev: the job table in device memory; tile_sums: scratch of total_tiles int64.
+struct ScanJob {
+    const int32_t *in;
+    int64_t *out;
+    int64_t n, tile0;
+};
+int64_t scan_tiles(int64_t n);
+void launch_multi_scan(const ScanJob *jobs_dev, int njobs, int64_t total_tiles, int64_t *tile_sums, hipStream_t s);
+// dst[i] = *src_dev[i] for i < count (src_dev: pointer table in device memory)
+void launch_gather_i64(const int64_t *const *src_dev, int count, int64_t *dst, hipStream_t s);
 void launch_fill_i32(int32_t *p, int64_t n, int32_t v, hipStream_t s);
 void launch_feature_flags_compare(const void *x_prev, const void *x_cur, int64_t n, int32_t row_bytes, int32_t *flags,
                                   hipStream_t s);

@@ -85,6 +85,84 @@ scan_finish(const int32_t *counts, int64_t n, const int64_t *tile_offsets, int64
 
 __global__ void write_zero_i64(int64_t *p) { p[0] = 0; }
 
+// ---- many scans in one launch ---------------------------------------------------------------------------------
+// The tiles of all jobs are numbered consecutively (job j owns tiles [tile0, tile0 + ceil(n / tile))); a block finds
+// its job by bisection over tile0.  Same arithmetic as the single scan, so the results are identical.
+__device__ inline int find_job(const ScanJob *jobs, int njobs, int64_t tile)
+{
+    int lo = 0, hi = njobs - 1;  // last job whose tile0 <= tile (jobs without tiles share their successor's tile0 and lose)
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (jobs[mid].tile0 <= tile)
+            lo = mid;
+        else
+            hi = mid - 1;
+    }
+    return lo;
+}
+
+__global__ void __launch_bounds__(kScanThreads) multi_scan_tile_sums(const ScanJob *jobs, int njobs, int64_t *tile_sums)
+{
+    __shared__ int64_t lds[kScanThreads];
+    const ScanJob job = jobs[find_job(jobs, njobs, blockIdx.x)];
+    int64_t base = (int64_t(blockIdx.x) - job.tile0) * kScanTile + int64_t(threadIdx.x) * kScanItems;
+    int64_t s = 0;
+    for (int k = 0; k < kScanItems; ++k)
+        if (base + k < job.n) s += job.in[base + k];
+    int64_t total;
+    block_exclusive_scan(s, lds, &total);
+    if (threadIdx.x == 0) tile_sums[blockIdx.x] = total;
+}
+
+// one block per job: exclusive scan of the job's tile sums in place; an empty job gets its single output here
+__global__ void __launch_bounds__(kScanThreads) multi_scan_tile_offsets(const ScanJob *jobs, int64_t *tile_sums)
+{
+    __shared__ int64_t lds[kScanThreads];
+    const ScanJob job = jobs[blockIdx.x];
+    if (job.n <= 0) {
+        if (threadIdx.x == 0) job.out[0] = 0;
+        return;
+    }
+    const int64_t ntiles = (job.n + kScanTile - 1) / kScanTile;
+    int64_t *mine = tile_sums + job.tile0;
+    int64_t running = 0;
+    for (int64_t base = 0; base < ntiles; base += kScanThreads) {
+        int64_t i = base + threadIdx.x;
+        int64_t v = i < ntiles ? mine[i] : 0;
+        int64_t total;
+        int64_t ex = block_exclusive_scan(v, lds, &total);
+        if (i < ntiles) mine[i] = running + ex;
+        running += total;
+    }
+}
+
+__global__ void __launch_bounds__(kScanThreads) multi_scan_finish(const ScanJob *jobs, int njobs, const int64_t *tile_offsets)
+{
+    __shared__ int64_t lds[kScanThreads];
+    const ScanJob job = jobs[find_job(jobs, njobs, blockIdx.x)];
+    int64_t base = (int64_t(blockIdx.x) - job.tile0) * kScanTile + int64_t(threadIdx.x) * kScanItems;
+    int32_t c[kScanItems];
+    int64_t s = 0;
+    for (int k = 0; k < kScanItems; ++k) {
+        c[k] = base + k < job.n ? job.in[base + k] : 0;
+        s += c[k];
+    }
+    int64_t total;
+    int64_t ex = block_exclusive_scan(s, lds, &total) + tile_offsets[blockIdx.x];
+    for (int k = 0; k < kScanItems; ++k) {
+        if (base + k < job.n) job.out[base + k] = ex;
+        ex += c[k];
+        if (base + k == job.n - 1) job.out[job.n] = ex;
+    }
+}
+
+// dst[i] = *src[i]: the totals of many scans gathered for one copy to the host
+__global__ void gather_i64(const int64_t *const *src, int count, int64_t *dst)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count) dst[i] = *src[i];
+}
+
 // ---- change-set flags ------------------------------------------------------------------------------------
 __global__ void flags_compare(const uint4 *a, const uint4 *b, int64_t nchunks, int32_t chunks_per_row, int32_t *flags)
 {
@@ -353,6 +431,21 @@ void launch_scan(const int32_t *counts, int64_t *offsets, int64_t n, void *tmp, 
     scan_tile_sums<<<unsigned(tiles), kScanThreads, 0, s>>>(counts, n, tile_sums);
     scan_tile_offsets<<<1, kScanThreads, 0, s>>>(tile_sums, tiles);
     scan_finish<<<unsigned(tiles), kScanThreads, 0, s>>>(counts, n, tile_sums, offsets);
+}
+
+int64_t scan_tiles(int64_t n) { return n > 0 ? (n + kScanTile - 1) / kScanTile : 0; }
+
+void launch_multi_scan(const ScanJob *jobs_dev, int njobs, int64_t total_tiles, int64_t *tile_sums, hipStream_t s)
+{
+    if (njobs <= 0) return;
+    if (total_tiles > 0) multi_scan_tile_sums<<<unsigned(total_tiles), kScanThreads, 0, s>>>(jobs_dev, njobs, tile_sums);
+    multi_scan_tile_offsets<<<unsigned(njobs), kScanThreads, 0, s>>>(jobs_dev, tile_sums);
+    if (total_tiles > 0) multi_scan_finish<<<unsigned(total_tiles), kScanThreads, 0, s>>>(jobs_dev, njobs, tile_sums);
+}
+
+void launch_gather_i64(const int64_t *const *src_dev, int count, int64_t *dst, hipStream_t s)
+{
+    if (count > 0) gather_i64<<<(count + 255) / 256, 256, 0, s>>>(src_dev, count, dst);
 }
 
 void launch_fill_i32(int32_t *p, int64_t n, int32_t v, hipStream_t s)
