@@ -1328,31 +1328,36 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
 }
 
 // dst_w[K*M] += sum_c partial[c][0..K*M);  dst_b[M] += sum_c partial[c][K*M ..)
-// A block owns 64 consecutive outputs; its 4 waves split the chunks, then add their sums in wave order.
-__global__ void __launch_bounds__(256)
+// A block owns 64 consecutive outputs; its 16 waves split the chunks (four independent sums each, so that the
+// loads of a wave overlap), then wave 0 adds the 16 sums in wave order: a fixed summation order.
+constexpr int kPartialWaves = 16;
+
+__global__ void __launch_bounds__(64 * kPartialWaves)
 reduce_partials_kernel(const float *partial, int chunks, int K, int M, float *dst_w, float *dst_b)
 {
-    __shared__ float red[4][64];
+    __shared__ float red[kPartialWaves][64];
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int total = (K + 1) * M;
     const int idx = blockIdx.x * 64 + lane;
-    float s0 = 0.0f, s1 = 0.0f;
+    float s[4] = {0.0f, 0.0f, 0.0f, 0.0f};
     if (idx < total) {
         int c = w;
-        for (; c + 4 < chunks; c += 8) {
-            s0 += partial[int64_t(c) * total + idx];
-            s1 += partial[int64_t(c + 4) * total + idx];
+        for (; c + 3 * kPartialWaves < chunks; c += 4 * kPartialWaves) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) s[u] += partial[int64_t(c + u * kPartialWaves) * total + idx];
         }
-        if (c < chunks) s0 += partial[int64_t(c) * total + idx];
+        for (int u = 0; c < chunks; c += kPartialWaves, ++u) s[u] += partial[int64_t(c) * total + idx];
     }
-    red[w][lane] = s0 + s1;
+    red[w][lane] = (s[0] + s[1]) + (s[2] + s[3]);
     __syncthreads();
     if (w != 0 || idx >= total) return;
-    const float s = ((red[0][lane] + red[1][lane]) + red[2][lane]) + red[3][lane];
+    float v = red[0][lane];
+#pragma unroll
+    for (int ww = 1; ww < kPartialWaves; ++ww) v += red[ww][lane];
     if (idx < K * M)
-        dst_w[idx] += s;
+        dst_w[idx] += v;
     else if (dst_b)
-        dst_b[idx - K * M] += s;
+        dst_b[idx - K * M] += v;
 }
 
 // ---- recurrent backward, elementwise part ------------------------------------------------------------------
@@ -1584,7 +1589,7 @@ void launch_reduce_partials(const float *partial, int64_t n, int32_t K, int32_t 
 {
     if (n <= 0) return;
     const int total = (K + 1) * M;
-    reduce_partials_kernel<<<(total + 63) / 64, 256, 0, s>>>(partial, reduce_chunks(n, K, M), K, M, dW, db);
+    reduce_partials_kernel<<<(total + 63) / 64, 64 * kPartialWaves, 0, s>>>(partial, reduce_chunks(n, K, M), K, M, dW, db);
 }
 
 void launch_rnn_backward_elem(int lstm, int64_t n, int32_t H, const float *dh, const float *dc, const float *saved,

@@ -101,14 +101,26 @@ __device__ inline int find_job(const ScanJob *jobs, int njobs, int64_t tile)
     return lo;
 }
 
+// a thread's eight consecutive counts: two 16-byte loads where all eight exist and the array is aligned
+__device__ inline void load_items(const int32_t *in, int64_t n, int64_t base, int32_t (&c)[kScanItems])
+{
+    if (base + kScanItems <= n && (reinterpret_cast<uintptr_t>(in) & 15) == 0) {
+        const int4 a = *reinterpret_cast<const int4 *>(in + base), b = *reinterpret_cast<const int4 *>(in + base + 4);
+        c[0] = a.x, c[1] = a.y, c[2] = a.z, c[3] = a.w, c[4] = b.x, c[5] = b.y, c[6] = b.z, c[7] = b.w;
+        return;
+    }
+    for (int k = 0; k < kScanItems; ++k) c[k] = base + k < n ? in[base + k] : 0;
+}
+
 __global__ void __launch_bounds__(kScanThreads) multi_scan_tile_sums(const ScanJob *jobs, int njobs, int64_t *tile_sums)
 {
     __shared__ int64_t lds[kScanThreads];
     const ScanJob job = jobs[find_job(jobs, njobs, blockIdx.x)];
     int64_t base = (int64_t(blockIdx.x) - job.tile0) * kScanTile + int64_t(threadIdx.x) * kScanItems;
+    int32_t c[kScanItems];
+    load_items(job.in, job.n, base, c);
     int64_t s = 0;
-    for (int k = 0; k < kScanItems; ++k)
-        if (base + k < job.n) s += job.in[base + k];
+    for (int k = 0; k < kScanItems; ++k) s += c[k];
     int64_t total;
     block_exclusive_scan(s, lds, &total);
     if (threadIdx.x == 0) tile_sums[blockIdx.x] = total;
@@ -142,13 +154,24 @@ __global__ void __launch_bounds__(kScanThreads) multi_scan_finish(const ScanJob 
     const ScanJob job = jobs[find_job(jobs, njobs, blockIdx.x)];
     int64_t base = (int64_t(blockIdx.x) - job.tile0) * kScanTile + int64_t(threadIdx.x) * kScanItems;
     int32_t c[kScanItems];
+    load_items(job.in, job.n, base, c);
     int64_t s = 0;
-    for (int k = 0; k < kScanItems; ++k) {
-        c[k] = base + k < job.n ? job.in[base + k] : 0;
-        s += c[k];
-    }
+    for (int k = 0; k < kScanItems; ++k) s += c[k];
     int64_t total;
     int64_t ex = block_exclusive_scan(s, lds, &total) + tile_offsets[blockIdx.x];
+    if (base + kScanItems < job.n && (reinterpret_cast<uintptr_t>(job.out) & 15) == 0) {
+        // a thread's eight outputs are 64 consecutive bytes: four 16-byte stores
+        longlong2 *o = reinterpret_cast<longlong2 *>(job.out + base);
+#pragma unroll
+        for (int k = 0; k < kScanItems; k += 2) {
+            longlong2 v;
+            v.x = ex;
+            v.y = ex + c[k];
+            ex += c[k] + c[k + 1];
+            o[k / 2] = v;
+        }
+        return;
+    }
     for (int k = 0; k < kScanItems; ++k) {
         if (base + k < job.n) job.out[base + k] = ex;
         ex += c[k];
