@@ -16,9 +16,9 @@ def _ctx(wl, arena=256 << 20, **kw):
     return reinc.Context.for_workload(wl, arena_bytes=arena, **kw)
 
 
-def _check_all_steps(seq, delta_features=True):
+def _check_all_steps(seq, delta_features=True, arena=256 << 20):
     wl = seq.workload
-    ctx = _ctx(wl)
+    ctx = _ctx(wl, arena=arena)
     ctx.load_sequence(seq, delta_features=delta_features)
     ctx.build_deltas(-1)
     graphs = oracle_graphs(seq)
@@ -115,6 +115,38 @@ def test_long_rows_in_the_diff():
     b = rng.choice(np.arange(1, n), 1400, replace=False)
     steps = [(a.tolist(), [0] * a.size, []), (b.tolist(), [0] * b.size, [7])]
     _check_all_steps(_manual_seq(n, steps))
+
+
+def test_steps_built_in_several_groups_and_arena_exhaustion():
+    """The builder takes as many steps per pass as the free arena allows: a generous arena (one group), one that
+    forces several groups, and one that cannot hold the deltas at all (clean error, nothing half-built)."""
+    from paper_2501_15348_amd import reinc
+
+    wl = synth.WORKLOADS["c2"].scaled(6001, 9)
+    seq = synth.make_sequence(wl)
+    probe = _ctx(wl)
+    probe.load_sequence(seq)
+    loaded = probe.get_stats()["arena_used"]  # snapshots and features
+    probe.build_deltas(-1)
+    deltas = probe.get_stats()["arena_used"] - loaded
+    probe.close()
+    print(f"loaded {loaded >> 20} MiB, deltas {deltas >> 20} MiB", flush=True)
+    _check_all_steps(seq, arena=256 << 20)
+    _check_all_steps(seq, arena=loaded + deltas + (6 << 20))  # a step needs about 2.3 MiB of scratch: groups of one or two
+    ctx = _ctx(wl, arena=loaded + deltas // 2)
+    ctx.load_sequence(seq)
+    with pytest.raises(reinc.ReincError) as e:
+        ctx.build_deltas(-1)
+    assert e.value.code == reinc.E_NOMEM
+    built = 0
+    for t in range(1, wl.num_snapshots):
+        try:
+            ctx.get_delta_info(t)
+            built += 1
+        except reinc.ReincError as err:
+            assert err.code == reinc.E_STATE
+    assert built < wl.num_snapshots - 1
+    ctx.close()
 
 
 def test_error_paths():
