@@ -323,6 +323,35 @@ static int build_group(reinc_ctx *ctx, const std::vector<int32_t> &steps, hipStr
         ok = ok && dl.ins_ptr && dl.del_ptr && dl.ent_ptr;
     }
     if (!ok) return nomem("scratch and row pointers");
+    // the per-step table for the batched stage kernels
+    std::vector<DiffStep> table(G);
+    int64_t max_a = 0, max_b = 0, max_list = 0;
+    bool compare_features = false;
+    for (int g = 0; g < G; ++g) {
+        const Snapshot &a = ctx->snaps[steps[g] - 1], &b = ctx->snaps[steps[g]];
+        const Work &w = work[g];
+        const Delta &dl = ctx->deltas[steps[g]];
+        DiffStep &st = table[g];
+        st = DiffStep{};
+        st.rowid_a = a.rowid, st.col_a = a.col, st.rowid_b = b.rowid, st.col_b = b.col;
+        st.rp_a = a.row_ptr, st.rp_b = b.row_ptr;
+        st.na = a.nnz, st.nb = b.nnz;
+        st.x_a = a.x, st.x_b = b.x, st.p_a = a.p, st.p_b = b.p;
+        st.feat_rows = b.feats_from_delta ? b.feat_rows : nullptr;
+        st.n_feat_rows = b.feats_from_delta ? b.n_feat_rows : 0;
+        st.cflags = w.cflags, st.cindex = w.cindex, st.row_flag = w.row_flag, st.long_flag = w.long_flag;
+        st.absent_a = w.absent_a, st.absent_b = w.absent_b, st.hit_b = w.hit_b;
+        st.coffs = w.coffs, st.roffs = w.roffs, st.loffs = w.loffs;
+        st.pos_del = w.pos_del, st.pos_ins = w.pos_ins, st.pos_hit = w.pos_hit;
+        st.ins_ptr = dl.ins_ptr, st.del_ptr = dl.del_ptr, st.ent_ptr = dl.ent_ptr;
+        max_a = std::max(max_a, a.nnz);
+        max_b = std::max(max_b, b.nnz);
+        max_list = std::max(max_list, st.n_feat_rows);
+        compare_features = compare_features || !b.feats_from_delta;
+    }
+    DiffStep *table_dev = static_cast<DiffStep *>(ctx->scratch(table.size() * sizeof(DiffStep)));
+    if (!table_dev) return nomem("step table");
+    const int sym = ctx->cfg.agg_kind == REINC_AGG_SYM;
     auto add_job = [&](int stage, const int32_t *in, int64_t *out, int64_t count) {
         jobs.push_back(ScanJob{in, out, count, tiles[stage]});
         tiles[stage] += scan_tiles(count);
@@ -357,35 +386,26 @@ static int build_group(reinc_ctx *ctx, const std::vector<int32_t> &steps, hipStr
     REINC_HIP(ctx, hipMemcpyAsync(jobs_dev, jobs.data(), jobs.size() * sizeof(ScanJob), hipMemcpyHostToDevice, s));
     REINC_HIP(ctx, hipMemcpyAsync(ptrs_dev, total_ptrs.data(), total_ptrs.size() * sizeof(int64_t *), hipMemcpyHostToDevice, s));
 
-    // stage 1: change sets C_t
-    for (int g = 0; g < G; ++g) {
-        const Snapshot &a = ctx->snaps[steps[g] - 1], &b = ctx->snaps[steps[g]];
-        launch_fill_i32(work[g].cflags, n, 0, s);
-        if (b.feats_from_delta)
-            launch_feature_flags_list(b.feat_rows, b.n_feat_rows, n, work[g].cflags, s);
-        else
-            launch_feature_flags_compare(a.x, b.x, n, d * ctx->elem_bytes(), work[g].cflags, s);
-        if (ctx->cfg.agg_kind == REINC_AGG_SYM) launch_degree_flags(a.row_ptr, b.row_ptr, n, work[g].cflags, s);
-    }
+    REINC_HIP(ctx, hipMemcpyAsync(table_dev, table.data(), table.size() * sizeof(DiffStep), hipMemcpyHostToDevice, s));
+    auto stage = [&](int which, int64_t max_changed) {
+        launch_diff_stage(which, table_dev, G, n, max_a, max_b, max_list, max_changed, sym, ctx->cfg.self_loop, bf16, d, s);
+    };
+    // stage 1: change sets C_t (steps whose features were loaded whole are compared row by row)
+    stage(0, 0);
+    if (compare_features)
+        for (int g = 0; g < G; ++g) {
+            const Snapshot &a = ctx->snaps[steps[g] - 1], &b = ctx->snaps[steps[g]];
+            if (!b.feats_from_delta) launch_feature_flags_compare(a.x, b.x, n, d * ctx->elem_bytes(), work[g].cflags, s);
+        }
     launch_multi_scan(jobs_dev + first_job[0], first_job[1] - first_job[0], tiles[0], tile_sums, s);
     // stage 2: per-edge flags (one thread per edge); their prefix sums are the output positions
     {
         ProfScope prof(ctx, REINC_K_DIFF, s);
-        for (int g = 0; g < G; ++g) {
-            const Snapshot &a = ctx->snaps[steps[g] - 1], &b = ctx->snaps[steps[g]];
-            launch_edge_flags(a.rowid, a.col, a.nnz, b.row_ptr, b.col, nullptr, work[g].absent_a, nullptr, s);
-            launch_edge_flags(b.rowid, b.col, b.nnz, a.row_ptr, a.col, work[g].cflags, work[g].absent_b, work[g].hit_b, s);
-        }
+        stage(1, 0);
     }
     launch_multi_scan(jobs_dev + first_job[1], first_job[2] - first_job[1], tiles[1], tile_sums, s);
     // stage 3: row pointers of the three outputs, rows that change, rows with many entries
-    for (int g = 0; g < G; ++g) {
-        const Snapshot &a = ctx->snaps[steps[g] - 1], &b = ctx->snaps[steps[g]];
-        const Delta &dl = ctx->deltas[steps[g]];
-        launch_delta_row_ptrs(a.row_ptr, b.row_ptr, work[g].pos_del, work[g].pos_ins, work[g].pos_hit, work[g].coffs,
-                              ctx->cfg.self_loop, n, dl.ins_ptr, dl.del_ptr, dl.ent_ptr, work[g].row_flag, s);
-        launch_row_long_flags(dl.ent_ptr, n, work[g].long_flag, s);
-    }
+    stage(2, 0);
     launch_multi_scan(jobs_dev + first_job[2], first_job[3] - first_job[2], tiles[2], tile_sums, s);
     launch_gather_i64(ptrs_dev, kTotals * G, totals_dev, s);
     std::vector<int64_t> totals(size_t(kTotals) * G);
@@ -407,21 +427,19 @@ static int build_group(reinc_ctx *ctx, const std::vector<int32_t> &steps, hipStr
         if (!dl.changed || !dl.dY || !dl.ins_col || !dl.del_col || !dl.ent || !dl.rows || !dl.long_rows)
             return nomem("delta entries");
     }
+    int64_t max_changed = 0;
     for (int g = 0; g < G; ++g) {
-        const Snapshot &a = ctx->snaps[steps[g] - 1], &b = ctx->snaps[steps[g]];
-        const int64_t *tt = &totals[size_t(kTotals) * g];
-        Delta &dl = ctx->deltas[steps[g]];
-        const Work &w = work[g];
-        launch_compact(w.long_flag, w.loffs, n, dl.long_rows, nullptr, s);
-        launch_compact(w.cflags, w.coffs, n, dl.changed, w.cindex, s);
-        launch_dy(a.x, b.x, bf16, a.p, b.p, dl.changed, tt[4], d, dl.dY, s);
-        {
-            ProfScope prof(ctx, REINC_K_DIFF, s);
-            launch_delta_fill(a.rowid, a.col, a.nnz, b.rowid, b.col, b.nnz, b.row_ptr, w.absent_a, w.absent_b, w.hit_b, w.pos_del,
-                              w.pos_ins, w.pos_hit, w.cindex, ctx->cfg.self_loop, n, dl.ins_ptr, dl.ins_col, dl.del_ptr,
-                              dl.del_col, dl.ent_ptr, dl.ent, s);
-        }
-        launch_compact(w.row_flag, w.roffs, n, dl.rows, nullptr, s);
+        const Delta &dl = ctx->deltas[steps[g]];
+        DiffStep &st = table[g];
+        st.ins_col = dl.ins_col, st.del_col = dl.del_col, st.ent = dl.ent;
+        st.rows = dl.rows, st.long_rows = dl.long_rows, st.changed = dl.changed, st.dY = dl.dY;
+        st.n_changed = totals[size_t(kTotals) * g + 4];
+        max_changed = std::max(max_changed, st.n_changed);
+    }
+    REINC_HIP(ctx, hipMemcpyAsync(table_dev, table.data(), table.size() * sizeof(DiffStep), hipMemcpyHostToDevice, s));
+    {
+        ProfScope prof(ctx, REINC_K_DIFF, s);
+        stage(3, max_changed);
     }
     REINC_HIP(ctx, hipGetLastError());
     REINC_HIP(ctx, hipStreamSynchronize(s));

@@ -234,13 +234,34 @@ struct ScanJob {
 };
 int64_t scan_tiles(int64_t n);
 void launch_multi_scan(const ScanJob *jobs_dev, int njobs, int64_t total_tiles, int64_t *tile_sums, hipStream_t s);
+// Everything the diff builder needs for one pair of consecutive snapshots (a = t-1, b = t): inputs, scratch, outputs.
+// A table of these in device memory lets one launch work on many pairs (blockIdx.y picks the pair).
+struct DiffStep {
+    const int32_t *rowid_a, *col_a, *rowid_b, *col_b;
+    const int64_t *rp_a, *rp_b;
+    int64_t na, nb;
+    const void *x_a, *x_b;
+    const float *p_a, *p_b;
+    const int32_t *feat_rows;  // rows re-assigned at t (delta-mode loading), or null
+    int64_t n_feat_rows;
+    int32_t *cflags, *cindex, *row_flag, *long_flag, *absent_a, *absent_b, *hit_b;
+    int64_t *coffs, *roffs, *loffs, *pos_del, *pos_ins, *pos_hit;
+    int64_t *ins_ptr, *del_ptr, *ent_ptr;
+    int32_t *ins_col, *del_col;
+    uint32_t *ent;
+    int32_t *rows, *long_rows, *changed;
+    float *dY;
+    int64_t n_changed;
+};
+// stage 0: change-set flags; 1: per-edge flags; 2: row pointers and row flags; 3: lists, dY, entries.  The prefix sums
+// between the stages are the caller's.  max_*: the largest count of any pair (the grid covers it).
+void launch_diff_stage(int stage, const DiffStep *steps_dev, int count, int64_t n, int64_t max_a, int64_t max_b, int64_t max_list,
+                       int64_t max_changed, int sym, int self_loop, int bf16, int32_t d, hipStream_t s);
 // dst[i] = *src_dev[i] for i < count (src_dev: pointer table in device memory)
 void launch_gather_i64(const int64_t *const *src_dev, int count, int64_t *dst, hipStream_t s);
 void launch_fill_i32(int32_t *p, int64_t n, int32_t v, hipStream_t s);
 void launch_feature_flags_compare(const void *x_prev, const void *x_cur, int64_t n, int32_t row_bytes, int32_t *flags,
                                   hipStream_t s);
-void launch_feature_flags_list(const int32_t *rows, int64_t nrows, int64_t n, int32_t *flags, hipStream_t s);
-void launch_degree_flags(const int64_t *rp_prev, const int64_t *rp_cur, int64_t n, int32_t *flags, hipStream_t s);
 void launch_compact(const int32_t *flags, const int64_t *offsets, int64_t n, int32_t *list, int32_t *index_of,
                     hipStream_t s);
 // canonicalisation of a raw edge list
@@ -257,20 +278,7 @@ void launch_ptr_from_sorted(const uint64_t *keys, int64_t e, int64_t n, int64_t 
 void launch_ptr_from_rowid(const int32_t *rowid, int64_t e, int64_t n, int64_t *ptr, hipStream_t s);
 void launch_degree_scales(const int64_t *ptr, int64_t n, int sym, int self_loop, float *q, hipStream_t s);
 void launch_long_flags(const int64_t *ptr, int64_t n, int32_t *flag, hipStream_t s);
-void launch_edge_flags(const int32_t *rowid, const int32_t *col, int64_t nnz, const int64_t *other_ptr,
-                       const int32_t *other_col, const int32_t *cflags, int32_t *absent, int32_t *hit, hipStream_t s);
-void launch_delta_row_ptrs(const int64_t *rp_a, const int64_t *rp_b, const int64_t *pos_del, const int64_t *pos_ins,
-                           const int64_t *pos_hit, const int64_t *pos_self, int self_loop, int64_t n, int64_t *ins_ptr,
-                           int64_t *del_ptr, int64_t *ent_ptr, int32_t *row_flag, hipStream_t s);
-void launch_delta_fill(const int32_t *rowid_a, const int32_t *col_a, int64_t nnz_a, const int32_t *rowid_b,
-                       const int32_t *col_b, int64_t nnz_b, const int64_t *rp_b, const int32_t *absent_a,
-                       const int32_t *absent_b, const int32_t *hit_b, const int64_t *pos_del, const int64_t *pos_ins,
-                       const int64_t *pos_hit, const int32_t *cindex, int self_loop, int64_t n, const int64_t *ins_ptr,
-                       int32_t *ins_col, const int64_t *del_ptr, int32_t *del_col, const int64_t *ent_ptr, uint32_t *ent,
-                       hipStream_t s);
 void launch_scatter_rows(const void *vals, const int32_t *rows, int64_t nrows, int32_t row_bytes, void *x, hipStream_t s);
-void launch_dy(const void *x_prev, const void *x_cur, int bf16, const float *p_prev, const float *p_cur,
-               const int32_t *changed, int64_t n_changed, int32_t d, float *dY, hipStream_t s);
 
 // ---- kernels_agg.hip
 bool agg_width_supported(int32_t d, int bf16);
@@ -304,7 +312,6 @@ void launch_incremental(const int32_t *rows, int64_t n_rows, const int32_t *long
                         const int64_t *ent_ptr, const uint32_t *ent, const void *x_prev, int bf16, const float *p_prev,
                         const float *dY, int32_t d, const float *S_prev, float *S_out, const float *q, float *agg_out,
                         hipStream_t s);
-void launch_row_long_flags(const int64_t *ent_ptr, int64_t n, int32_t *flag, hipStream_t s);
 
 // ---- kernels_dense.hip
 // out[n,M] = epilogue((row_scale .* A)[n,K] * B[K,M]); B = W (ldw = row stride) or W^T when w_transposed.

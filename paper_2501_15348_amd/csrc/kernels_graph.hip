@@ -4,6 +4,8 @@
 // folded in through its out-edges).  All outputs are unique, so they can be compared bit for bit.
 #include "ctx.h"
 
+#include <algorithm>
+
 namespace reinc {
 
 namespace {
@@ -195,18 +197,6 @@ __global__ void flags_compare(const uint4 *a, const uint4 *b, int64_t nchunks, i
     if (x.x != y.x || x.y != y.y || x.z != y.z || x.w != y.w) flags[i / chunks_per_row] = 1;
 }
 
-__global__ void flags_list(const int32_t *rows, int64_t nrows, int32_t *flags)
-{
-    int64_t i = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
-    if (i < nrows) flags[rows[i]] = 1;
-}
-
-__global__ void flags_degree(const int64_t *rp_a, const int64_t *rp_b, int64_t n, int32_t *flags)
-{
-    int64_t v = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
-    if (v < n && (rp_a[v + 1] - rp_a[v]) != (rp_b[v + 1] - rp_b[v])) flags[v] = 1;
-}
-
 // list[offsets[i]] = i for flagged i; index_of[i] = offsets[i] or -1
 __global__ void compact(const int32_t *flags, const int64_t *offsets, int64_t n, int32_t *list, int32_t *index_of)
 {
@@ -321,86 +311,6 @@ __device__ inline bool row_find(const int32_t *col, int64_t beg, int64_t end, in
     return lo < end && col[lo] == key;
 }
 
-// absent[e] = 1 if edge e of `self` is not in `other`; hit[e] = cflags[col[e]] != 0 (optional)
-__global__ void edge_flags(const int32_t *rowid, const int32_t *col, int64_t nnz, const int64_t *other_ptr,
-                           const int32_t *other_col, const int32_t *cflags, int32_t *absent, int32_t *hit)
-{
-    const int64_t e = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
-    if (e >= nnz) return;
-    const int32_t v = rowid[e], u = col[e];
-    absent[e] = !row_find(other_col, other_ptr[v], other_ptr[v + 1], u);
-    if (hit) hit[e] = cflags[u] != 0;
-}
-
-// Row pointers of the three outputs from the per-edge prefix sums:
-//   ins_ptr[v] = pos_ins[rp_b[v]], del_ptr[v] = pos_del[rp_a[v]],
-//   ent_ptr[v] = ins_ptr[v] + del_ptr[v] + pos_hit[rp_b[v]] + (self_loop ? pos_self[v] : 0)
-__global__ void delta_row_ptrs(const int64_t *rp_a, const int64_t *rp_b, const int64_t *pos_del, const int64_t *pos_ins,
-                               const int64_t *pos_hit, const int64_t *pos_self, int self_loop, int64_t n,
-                               int64_t *ins_ptr, int64_t *del_ptr, int64_t *ent_ptr)
-{
-    const int64_t v = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
-    if (v > n) return;
-    const int64_t i = pos_ins[rp_b[v]], d = pos_del[rp_a[v]];
-    ins_ptr[v] = i;
-    del_ptr[v] = d;
-    ent_ptr[v] = i + d + pos_hit[rp_b[v]] + (self_loop ? pos_self[v] : 0);
-}
-
-__global__ void row_nonempty(const int64_t *ent_ptr, int64_t n, int32_t *flag)
-{
-    const int64_t v = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
-    if (v < n) flag[v] = ent_ptr[v + 1] > ent_ptr[v];
-}
-
-__global__ void row_long(const int64_t *ent_ptr, int64_t n, int32_t *flag)
-{
-    const int64_t v = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
-    if (v < n) flag[v] = ent_ptr[v + 1] - ent_ptr[v] > kLongRow;
-}
-
-// Inserted edges (kind 0) and changed-source entries (kind 2) come from snapshot t's edges.
-__global__ void fill_from_cur(const int32_t *rowid, const int32_t *col, int64_t nnz, const int64_t *rp_b,
-                              const int32_t *absent, const int32_t *hit, const int64_t *pos_ins, const int64_t *pos_hit,
-                              const int32_t *cindex, const int64_t *ins_ptr, const int64_t *del_ptr,
-                              const int64_t *ent_ptr, int32_t *ins_col, uint32_t *ent)
-{
-    const int64_t e = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
-    if (e >= nnz) return;
-    const int32_t v = rowid[e], u = col[e];
-    if (absent[e]) {
-        const int64_t r = pos_ins[e];
-        ins_col[r] = u;
-        ent[ent_ptr[v] + (r - ins_ptr[v])] = uint32_t(u);
-    }
-    if (hit[e]) {
-        const int64_t base = ent_ptr[v] + (ins_ptr[v + 1] - ins_ptr[v]) + (del_ptr[v + 1] - del_ptr[v]);
-        ent[base + (pos_hit[e] - pos_hit[rp_b[v]])] = (2u << kKindShift) | uint32_t(cindex[u]);
-    }
-}
-
-// Deleted edges (kind 1) come from snapshot t-1's edges.
-__global__ void fill_from_prev(const int32_t *rowid, const int32_t *col, int64_t nnz, const int32_t *absent,
-                               const int64_t *pos_del, const int64_t *ins_ptr, const int64_t *del_ptr,
-                               const int64_t *ent_ptr, int32_t *del_col, uint32_t *ent)
-{
-    const int64_t e = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
-    if (e >= nnz || !absent[e]) return;
-    const int32_t v = rowid[e], u = col[e];
-    const int64_t r = pos_del[e];
-    del_col[r] = u;
-    ent[ent_ptr[v] + (ins_ptr[v + 1] - ins_ptr[v]) + (r - del_ptr[v])] = (1u << kKindShift) | uint32_t(u);
-}
-
-// The row's own entry (self-loop of a changed node) is the last entry of its row.
-__global__ void fill_self(const int32_t *cindex, int64_t n, const int64_t *ent_ptr, uint32_t *ent)
-{
-    const int64_t v = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
-    if (v >= n) return;
-    const int32_t ci = cindex[v];
-    if (ci >= 0) ent[ent_ptr[v + 1] - 1] = (2u << kKindShift) | uint32_t(ci);
-}
-
 // X[rows[r]] = vals[r], rows of `chunks` 16-byte pieces
 __global__ void scatter_rows(const uint4 *vals, const int32_t *rows, int64_t nrows, int32_t chunks, uint4 *x)
 {
@@ -412,30 +322,163 @@ __global__ void scatter_rows(const uint4 *vals, const int32_t *rows, int64_t nro
 
 __device__ inline float bf16_to_f32(uint16_t b) { return __uint_as_float(uint32_t(b) << 16); }
 
-// dY[i] = p_cur[u] X_cur[u] - p_prev[u] X_prev[u],  u = changed[i]
-__global__ void dy_rows(const void *x_prev, const void *x_cur, int bf16, const float *p_prev, const float *p_cur,
-                        const int32_t *changed, int64_t n_changed, int32_t d, float *dY)
-{
-    int64_t i = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
-    if (i >= n_changed * d) return;
-    int64_t r = i / d;
-    int32_t j = int32_t(i - r * d);
-    int64_t u = changed[r];
-    float a, b;
-    if (bf16) {
-        a = bf16_to_f32(static_cast<const uint16_t *>(x_prev)[u * d + j]);
-        b = bf16_to_f32(static_cast<const uint16_t *>(x_cur)[u * d + j]);
-    } else {
-        a = static_cast<const float *>(x_prev)[u * d + j];
-        b = static_cast<const float *>(x_cur)[u * d + j];
-    }
-    float pa = p_prev ? p_prev[u] : 1.0f, pb = p_cur ? p_cur[u] : 1.0f;
-    dY[i] = pb * b - pa * a;
-}
-
 inline unsigned blocks_for(int64_t n, int threads) { return unsigned((n + threads - 1) / threads); }
 
+// ---- the diff builder's stages, for many snapshot pairs in one launch: blockIdx.y picks the pair ----------------
+// Each stage kernel does everything of that stage that is independent per element (node or edge); the stages are
+// separated by the prefix sums, which turn per-element flags into output positions (so the outputs are ordered and
+// duplicate-free without any per-row counting).
+
+// stage 1a: cflags[v] = degree of v changed (SYM only: its normalised features change), else 0
+__global__ void steps_init_flags(const DiffStep *steps, int64_t n, int sym)
+{
+    const DiffStep &st = steps[blockIdx.y];
+    const int64_t v = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
+    if (v >= n) return;
+    st.cflags[v] = sym && (st.rp_a[v + 1] - st.rp_a[v]) != (st.rp_b[v + 1] - st.rp_b[v]);
+}
+
+// stage 1b: rows whose features were re-assigned (delta-mode loading keeps their list)
+__global__ void steps_flags_list(const DiffStep *steps)
+{
+    const DiffStep &st = steps[blockIdx.y];
+    const int64_t i = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
+    if (st.feat_rows && i < st.n_feat_rows) st.cflags[st.feat_rows[i]] = 1;
+}
+
+// stage 2: threads [0, na) take the edges of t-1, threads [na, na + nb) those of t
+__global__ void steps_edge_flags(const DiffStep *steps)
+{
+    const DiffStep &st = steps[blockIdx.y];
+    int64_t e = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
+    if (e < st.na) {
+        const int32_t v = st.rowid_a[e], u = st.col_a[e];
+        st.absent_a[e] = !row_find(st.col_b, st.rp_b[v], st.rp_b[v + 1], u);
+        return;
+    }
+    e -= st.na;
+    if (e >= st.nb) return;
+    const int32_t v = st.rowid_b[e], u = st.col_b[e];
+    st.absent_b[e] = !row_find(st.col_a, st.rp_a[v], st.rp_a[v + 1], u);
+    st.hit_b[e] = st.cflags[u] != 0;
+}
+
+// stage 3a: row pointers of the three outputs
+__global__ void steps_row_ptrs(const DiffStep *steps, int64_t n, int self_loop)
+{
+    const DiffStep &st = steps[blockIdx.y];
+    const int64_t v = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
+    if (v > n) return;
+    const int64_t i = st.pos_ins[st.rp_b[v]], d = st.pos_del[st.rp_a[v]];
+    st.ins_ptr[v] = i;
+    st.del_ptr[v] = d;
+    st.ent_ptr[v] = i + d + st.pos_hit[st.rp_b[v]] + (self_loop ? st.coffs[v] : 0);
+}
+
+// stage 3b: rows that change at all, rows with many entries
+__global__ void steps_row_flags(const DiffStep *steps, int64_t n)
+{
+    const DiffStep &st = steps[blockIdx.y];
+    const int64_t v = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
+    if (v >= n) return;
+    const int64_t len = st.ent_ptr[v + 1] - st.ent_ptr[v];
+    st.row_flag[v] = len > 0;
+    st.long_flag[v] = len > kLongRow;
+}
+
+// stage 4a: the three lists of nodes (changed nodes with their index, changed rows, long rows)
+__global__ void steps_compact(const DiffStep *steps, int64_t n)
+{
+    const DiffStep &st = steps[blockIdx.y];
+    const int64_t v = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
+    if (v >= n) return;
+    const bool c = st.cflags[v] != 0;
+    if (c) st.changed[st.coffs[v]] = int32_t(v);
+    st.cindex[v] = c ? int32_t(st.coffs[v]) : -1;
+    if (st.row_flag[v]) st.rows[st.roffs[v]] = int32_t(v);
+    if (st.long_flag[v]) st.long_rows[st.loffs[v]] = int32_t(v);
+}
+
+// stage 4b: dY rows of the changed nodes
+__global__ void steps_dy(const DiffStep *steps, int bf16, int32_t d)
+{
+    const DiffStep &st = steps[blockIdx.y];
+    const int64_t i = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
+    if (i >= st.n_changed * d) return;
+    const int64_t r = i / d;
+    const int32_t j = int32_t(i - r * d);
+    const int64_t u = st.changed[r];
+    float a, b;
+    if (bf16) {
+        a = bf16_to_f32(static_cast<const uint16_t *>(st.x_a)[u * d + j]);
+        b = bf16_to_f32(static_cast<const uint16_t *>(st.x_b)[u * d + j]);
+    } else {
+        a = static_cast<const float *>(st.x_a)[u * d + j];
+        b = static_cast<const float *>(st.x_b)[u * d + j];
+    }
+    const float pa = st.p_a ? st.p_a[u] : 1.0f, pb = st.p_b ? st.p_b[u] : 1.0f;
+    st.dY[i] = pb * b - pa * a;
+}
+
+// stage 4c: the entries.  Threads [0, nb): edges of t (inserted, changed source); [nb, nb + na): edges of t-1
+// (deleted); [nb + na, nb + na + n): the rows' own entries (self-loop of a changed node, last in its row).
+__global__ void steps_fill(const DiffStep *steps, int64_t n, int self_loop)
+{
+    const DiffStep &st = steps[blockIdx.y];
+    int64_t e = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
+    if (e < st.nb) {
+        const int32_t v = st.rowid_b[e], u = st.col_b[e];
+        if (st.absent_b[e]) {
+            const int64_t r = st.pos_ins[e];
+            st.ins_col[r] = u;
+            st.ent[st.ent_ptr[v] + (r - st.ins_ptr[v])] = uint32_t(u);
+        }
+        if (st.hit_b[e]) {
+            const int64_t base = st.ent_ptr[v] + (st.ins_ptr[v + 1] - st.ins_ptr[v]) + (st.del_ptr[v + 1] - st.del_ptr[v]);
+            st.ent[base + (st.pos_hit[e] - st.pos_hit[st.rp_b[v]])] = (2u << kKindShift) | uint32_t(st.cindex[u]);
+        }
+        return;
+    }
+    e -= st.nb;
+    if (e < st.na) {
+        if (!st.absent_a[e]) return;
+        const int32_t v = st.rowid_a[e], u = st.col_a[e];
+        const int64_t r = st.pos_del[e];
+        st.del_col[r] = u;
+        st.ent[st.ent_ptr[v] + (st.ins_ptr[v + 1] - st.ins_ptr[v]) + (r - st.del_ptr[v])] = (1u << kKindShift) | uint32_t(u);
+        return;
+    }
+    e -= st.na;
+    if (!self_loop || e >= n) return;
+    const int32_t ci = st.cindex[e];
+    if (ci >= 0) st.ent[st.ent_ptr[e + 1] - 1] = (2u << kKindShift) | uint32_t(ci);
+}
+
 }  // namespace
+
+void launch_diff_stage(int stage, const DiffStep *steps_dev, int count, int64_t n, int64_t max_a, int64_t max_b, int64_t max_list,
+                       int64_t max_changed, int sym, int self_loop, int bf16, int32_t d, hipStream_t s)
+{
+    if (count <= 0) return;
+    auto grid = [&](int64_t elems) { return dim3(std::max(1u, blocks_for(elems, 256)), unsigned(count)); };
+    switch (stage) {
+    case 0:
+        steps_init_flags<<<grid(n), 256, 0, s>>>(steps_dev, n, sym);
+        if (max_list > 0) steps_flags_list<<<grid(max_list), 256, 0, s>>>(steps_dev);
+        break;
+    case 1: steps_edge_flags<<<grid(max_a + max_b), 256, 0, s>>>(steps_dev); break;
+    case 2:
+        steps_row_ptrs<<<grid(n + 1), 256, 0, s>>>(steps_dev, n, self_loop);
+        steps_row_flags<<<grid(n), 256, 0, s>>>(steps_dev, n);
+        break;
+    case 3:
+        steps_compact<<<grid(n), 256, 0, s>>>(steps_dev, n);
+        if (max_changed > 0) steps_dy<<<grid(max_changed * d), 256, 0, s>>>(steps_dev, bf16, d);
+        steps_fill<<<grid(max_a + max_b + n), 256, 0, s>>>(steps_dev, n, self_loop);
+        break;
+    default: break;
+    }
+}
 
 uint64_t scan_tmp_bytes(int64_t n)
 {
@@ -486,17 +529,6 @@ void launch_feature_flags_compare(const void *x_prev, const void *x_cur, int64_t
                                                                static_cast<const uint4 *>(x_cur), chunks, cpr, flags);
 }
 
-void launch_feature_flags_list(const int32_t *rows, int64_t nrows, int64_t n, int32_t *flags, hipStream_t s)
-{
-    (void)n;
-    if (nrows > 0) flags_list<<<blocks_for(nrows, 256), 256, 0, s>>>(rows, nrows, flags);
-}
-
-void launch_degree_flags(const int64_t *rp_prev, const int64_t *rp_cur, int64_t n, int32_t *flags, hipStream_t s)
-{
-    if (n > 0) flags_degree<<<blocks_for(n, 256), 256, 0, s>>>(rp_prev, rp_cur, n, flags);
-}
-
 void launch_compact(const int32_t *flags, const int64_t *offsets, int64_t n, int32_t *list, int32_t *index_of,
                     hipStream_t s)
 {
@@ -545,43 +577,6 @@ void launch_long_flags(const int64_t *ptr, int64_t n, int32_t *flag, hipStream_t
     if (n > 0) long_flags<<<blocks_for(n, 256), 256, 0, s>>>(ptr, n, flag);
 }
 
-void launch_edge_flags(const int32_t *rowid, const int32_t *col, int64_t nnz, const int64_t *other_ptr,
-                       const int32_t *other_col, const int32_t *cflags, int32_t *absent, int32_t *hit, hipStream_t s)
-{
-    if (nnz > 0)
-        edge_flags<<<blocks_for(nnz, 256), 256, 0, s>>>(rowid, col, nnz, other_ptr, other_col, cflags, absent, hit);
-}
-
-void launch_delta_row_ptrs(const int64_t *rp_a, const int64_t *rp_b, const int64_t *pos_del, const int64_t *pos_ins,
-                           const int64_t *pos_hit, const int64_t *pos_self, int self_loop, int64_t n, int64_t *ins_ptr,
-                           int64_t *del_ptr, int64_t *ent_ptr, int32_t *row_flag, hipStream_t s)
-{
-    delta_row_ptrs<<<blocks_for(n + 1, 256), 256, 0, s>>>(rp_a, rp_b, pos_del, pos_ins, pos_hit, pos_self, self_loop, n,
-                                                          ins_ptr, del_ptr, ent_ptr);
-    if (n > 0) row_nonempty<<<blocks_for(n, 256), 256, 0, s>>>(ent_ptr, n, row_flag);
-}
-
-void launch_row_long_flags(const int64_t *ent_ptr, int64_t n, int32_t *flag, hipStream_t s)
-{
-    if (n > 0) row_long<<<blocks_for(n, 256), 256, 0, s>>>(ent_ptr, n, flag);
-}
-
-void launch_delta_fill(const int32_t *rowid_a, const int32_t *col_a, int64_t nnz_a, const int32_t *rowid_b,
-                       const int32_t *col_b, int64_t nnz_b, const int64_t *rp_b, const int32_t *absent_a,
-                       const int32_t *absent_b, const int32_t *hit_b, const int64_t *pos_del, const int64_t *pos_ins,
-                       const int64_t *pos_hit, const int32_t *cindex, int self_loop, int64_t n, const int64_t *ins_ptr,
-                       int32_t *ins_col, const int64_t *del_ptr, int32_t *del_col, const int64_t *ent_ptr, uint32_t *ent,
-                       hipStream_t s)
-{
-    if (nnz_b > 0)
-        fill_from_cur<<<blocks_for(nnz_b, 256), 256, 0, s>>>(rowid_b, col_b, nnz_b, rp_b, absent_b, hit_b, pos_ins, pos_hit,
-                                                             cindex, ins_ptr, del_ptr, ent_ptr, ins_col, ent);
-    if (nnz_a > 0)
-        fill_from_prev<<<blocks_for(nnz_a, 256), 256, 0, s>>>(rowid_a, col_a, nnz_a, absent_a, pos_del, ins_ptr, del_ptr,
-                                                              ent_ptr, del_col, ent);
-    if (self_loop && n > 0) fill_self<<<blocks_for(n, 256), 256, 0, s>>>(cindex, n, ent_ptr, ent);
-}
-
 void launch_scatter_rows(const void *vals, const int32_t *rows, int64_t nrows, int32_t row_bytes, void *x, hipStream_t s)
 {
     const int32_t chunks = row_bytes / 16;
@@ -589,14 +584,6 @@ void launch_scatter_rows(const void *vals, const int32_t *rows, int64_t nrows, i
     if (total > 0)
         scatter_rows<<<blocks_for(total, 256), 256, 0, s>>>(static_cast<const uint4 *>(vals), rows, nrows, chunks,
                                                             static_cast<uint4 *>(x));
-}
-
-void launch_dy(const void *x_prev, const void *x_cur, int bf16, const float *p_prev, const float *p_cur,
-               const int32_t *changed, int64_t n_changed, int32_t d, float *dY, hipStream_t s)
-{
-    int64_t total = n_changed * d;
-    if (total > 0)
-        dy_rows<<<blocks_for(total, 256), 256, 0, s>>>(x_prev, x_cur, bf16, p_prev, p_cur, changed, n_changed, d, dY);
 }
 
 }  // namespace reinc
