@@ -1506,6 +1506,22 @@ int launch_gemm_rows(const void *A, int a_bf16, int64_t n, int32_t K, int32_t M,
 {
     if (n <= 0) return 0;
     GemmArgs g{A, n, K, M, K, row_scale, W, ldw, w_transposed, bias, relu, mask, add, out};
+    // Deep products (K = 512: the gate gradients of an LSTM times W^T) whose three-plane slab fits for half of K only:
+    // two passes over the halves of K, the second adding to the first (out = A1 W1 + add, then out = A2 W2 + out).
+    // Without bias and ReLU the epilogue order (add, then mask) makes the two passes equal to the single product.
+    constexpr size_t kSlabMax = kLdsBytes - 1024;
+    if (dense_split_enabled() && !bias && !relu && K % 64 == 0 && size_t(K) * 64 * 6 > kSlabMax && size_t(K / 2) * 64 * 6 <= kSlabMax &&
+        M > 64) {
+        const int half = K / 2;
+        const char *A2 = static_cast<const char *>(A) + size_t(half) * (a_bf16 ? 2 : 4);
+        const float *W2 = w_transposed ? W + half : W + int64_t(half) * ldw;
+        GemmArgs g1{A, n, half, M, K, row_scale, W, ldw, w_transposed, nullptr, 0, nullptr, add, out};
+        GemmArgs g2{A2, n, half, M, K, row_scale, W2, ldw, w_transposed, nullptr, 0, mask, out, out};
+        if (gemm_rows_resident_dispatch(g1, a_bf16, s)) {
+            if (gemm_rows_resident_dispatch(g2, a_bf16, s)) return 0;
+            return -1;  // cannot happen: the second pass has the shape of the first
+        }
+    }
     // preferred: weight slab resident in LDS, as wide as fits
     if (gemm_rows_resident_dispatch(g, a_bf16, s)) return 0;
     // very deep products: stage the weights 32 k values at a time

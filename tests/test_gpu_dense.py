@@ -35,6 +35,9 @@ def _dev(a, dtype=None):
     (513, 100, 72, False, True, True),   # widths that are no multiple of the tile
     (129, 256, 512, True, False, True),
     (31, 8, 40, False, False, False),
+    (2077, 512, 128, False, True, False),   # deep product: two passes over the halves of K
+    (2077, 512, 128, True, False, True),    # the same depth with bias and ReLU: single pass
+    (1500, 384, 256, False, False, False),
 ])
 def test_gcn_transform(ctx, n, k, m, relu, scale, bias):
     rng = np.random.default_rng(n + k + m)
