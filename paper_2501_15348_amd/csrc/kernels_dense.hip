@@ -829,13 +829,20 @@ __global__ void __launch_bounds__(256) rnn_fused_kernel(RnnArgs g)
 // overall; a ring of three register buffers keeps the loads two chunks ahead of the matrix cores.  Needs
 // d_in % 32 == 0, H % 32 == 0 and 16-byte aligned rows.  SPLIT: the slab holds the three bfloat16 planes of the
 // weights and the products run on the bf16 matrix cores (see the note on fp32 products above).
-template <bool LSTM, int WN, int WAVES, bool SPLIT>
+//
+// PACK (LSTM, split only): a wave takes 16 hidden units instead of 32 and packs two gates into each 32-column tile
+// ([i | f] and [g | o]), so the slab is half as wide and fits the LDS where the unpacked one does not
+// (d_in + H = 256: 98 KB instead of 196 KB).  The four gates of a hidden unit then sit in two lanes 16 apart; in the
+// epilogue the two lanes swap half of their rows, after which each finishes its unit for 8 of the tile's 16 rows.
+template <bool LSTM, int WN, int WAVES, bool SPLIT, bool PACK = false>
 __global__ void __launch_bounds__(64 * WAVES) rnn_fused_resident_kernel(RnnArgs g)
 {
     extern __shared__ float Bs[];
+    static_assert(!PACK || (LSTM && SPLIT), "gate packing is for the split LSTM cell");
     constexpr int KG = LSTM ? 4 : 3;
     constexpr int WM = WAVES / WN;
-    constexpr int BH = 32 * WN;
+    constexpr int UW = PACK ? 16 : 32;  // hidden units per wave
+    constexpr int BH = UW * WN;
     constexpr int NC = KG * BH;
     constexpr int G = 4;  // B fragments are read four steps (12 or 16 registers) ahead
     static_assert(WAVES % WN == 0, "column groups must divide the block");
@@ -899,6 +906,10 @@ __global__ void __launch_bounds__(64 * WAVES) rnn_fused_resident_kernel(RnnArgs 
     const int plane = (g.d_in + H) / 8 * NC;  // records per plane of the split slab
     if (SPLIT) {
         auto col_of = [&](int c) {
+            if (PACK) {  // a wave's 64 columns: its 16 units of gate i, then f, g, o
+                const int wv = c / 64, r = c - wv * 64, gate = r / 16, unit = h0 + 16 * wv + (r & 15);
+                return unit < H ? gate * H + unit : -1;
+            }
             const int gate = c / BH, jj = c - gate * BH;
             return h0 + jj < H ? gate * H + h0 + jj : -1;
         };
@@ -918,7 +929,7 @@ __global__ void __launch_bounds__(64 * WAVES) rnn_fused_resident_kernel(RnnArgs 
     __syncthreads();
     // everything requested so far has landed by now; saying so keeps the waits inside the loops exact
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
-    const int j = h0 + wn * 32 + i;
+    const int j = PACK ? h0 + wn * 16 + (i & 15) : h0 + wn * 32 + i;
     float bsum[KG], bhn = 0.0f;  // gate biases: b_i + b_h, except that GRU keeps b_hn apart (the reset gate scales it)
 #pragma unroll
     for (int t = 0; t < KG; ++t) {
@@ -944,6 +955,57 @@ __global__ void __launch_bounds__(64 * WAVES) rnn_fused_resident_kernel(RnnArgs 
     auto epilogue = [&]() __attribute__((always_inline)) {  // rows rbase + 8*q + e of the finished tile, four at a time
         const int64_t rbase = int64_t(tile) * 32 + 4 * kk;
         const bool full = int64_t(tile) * 32 + 32 <= g.n;
+        if (PACK) {
+            // lanes 0..15 of a half hold gates i (acc[0]) and g (acc[1]) of their unit, lanes 16..31 gates f and o, for
+            // the same 16 rows.  The low lane keeps rows 0..7 (registers 0..7) and receives f, o for them; the high
+            // lane keeps rows 8..15 and receives i, g.
+            const bool low = i < 16;
+            float mine0[8], mine1[8], other0[8], other1[8];
+#pragma unroll
+            for (int r = 0; r < 8; ++r) {
+                mine0[r] = low ? acc[0][r] : acc[0][8 + r];
+                mine1[r] = low ? acc[1][r] : acc[1][8 + r];
+                other0[r] = __shfl_xor(low ? acc[0][8 + r] : acc[0][r], 16);
+                other1[r] = __shfl_xor(low ? acc[1][8 + r] : acc[1][r], 16);
+            }
+            if (j < H) {
+#pragma unroll
+                for (int q = 0; q < 2; ++q) {
+                    int64_t rr[4];
+                    float prev[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        rr[e] = min(rbase + 8 * (q + (low ? 0 : 2)) + e, g.n - 1);
+                        prev[e] = pstate ? pstate[rr[e] * H + j] : 0.0f;
+                    }
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        if (!(full || rbase + 8 * (q + (low ? 0 : 2)) + e < g.n)) continue;
+                        const int r = 4 * q + e;
+                        const int64_t o = rr[e] * H + j;
+                        const float gi = sigmoidf_((low ? mine0[r] : other0[r]) + bsum[0]);
+                        const float gf = sigmoidf_((low ? other0[r] : mine0[r]) + bsum[1]);
+                        const float gg = tanhf_((low ? mine1[r] : other1[r]) + bsum[2]);
+                        const float go = sigmoidf_((low ? other1[r] : mine1[r]) + bsum[LSTM ? 3 : 0]);
+                        const float cn = gf * prev[e] + gi * gg;
+                        g.c_out[o] = cn;
+                        g.h_out[o] = go * tanhf_(cn);
+                        if (g.saved) {
+                            float *sv = g.saved + rr[e] * 4 * H + j;
+                            sv[0] = gi;
+                            sv[H] = gf;
+                            sv[2 * H] = gg;
+                            sv[3 * H] = go;
+                        }
+                    }
+                }
+            }
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[t][r] = 0.0f;
+            return;
+        }
         if (j < H) {
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
@@ -1001,7 +1063,9 @@ __global__ void __launch_bounds__(64 * WAVES) rnn_fused_resident_kernel(RnnArgs 
         const float f = (has_xs && kc < kx) ? sc : 1.0f;
 #pragma unroll
         for (int e = 0; e < 16; ++e) cur[e] *= f;
-        if (SPLIT)
+        if (PACK)
+            mfma_chunk_split<2, 4>(cur, Bq + (4 * kc + 2 * kk) * NC + wn * 64 + i, NC, plane, 32, acc);
+        else if (SPLIT)
             mfma_chunk_split<KG, 4>(cur, Bq + (4 * kc + 2 * kk) * NC + wn * 32 + i, NC, plane, BH, acc);
         else
             mfma_chunk_map<KG, KG - 1, G>(cur, bp, NC, BH, acc, NoPrefetch());
@@ -1044,22 +1108,23 @@ __global__ void __launch_bounds__(64 * WAVES) rnn_fused_resident_kernel(RnnArgs 
     }
 }
 
-template <bool LSTM, int WN, int WAVES, bool SPLIT>
+template <bool LSTM, int WN, int WAVES, bool SPLIT, bool PACK = false>
 bool rnn_fused_resident_launch(const RnnArgs &g, hipStream_t s)
 {
     constexpr int KG = LSTM ? 4 : 3;
     constexpr int WM = WAVES / WN;
+    constexpr int UW = PACK ? 16 : 32;
     if (g.d_in % kBK != 0 || g.H % kBK != 0 || g.d_in % 4 != 0) return false;
-    const size_t lds = size_t(g.d_in + g.H) * KG * 32 * WN * (SPLIT ? 6 : sizeof(float));
+    const size_t lds = size_t(g.d_in + g.H) * KG * UW * WN * (SPLIT ? 6 : sizeof(float));
     if (lds > kLdsBytes - 1024) return false;
-    auto k = rnn_fused_resident_kernel<LSTM, WN, WAVES, SPLIT>;
+    auto k = rnn_fused_resident_kernel<LSTM, WN, WAVES, SPLIT, PACK>;
     if (lds > 48 * 1024 &&
         hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, int(lds)) != hipSuccess)
         return false;
     const int per_cu = resident_blocks(reinterpret_cast<const void *>(k), 64 * WAVES, lds);
     if (per_cu <= 0) return false;
     const int64_t ntiles = (g.n + 31) / 32;
-    const unsigned gy = unsigned((g.H + 32 * WN - 1) / (32 * WN));
+    const unsigned gy = unsigned((g.H + UW * WN - 1) / (UW * WN));
     dim3 grid(unsigned(std::min<int64_t>((ntiles + WM - 1) / WM, std::max<int64_t>(1, int64_t(kNumCU) * per_cu / gy))), gy);
     k<<<grid, 64 * WAVES, lds, s>>>(g);
     return true;
@@ -1068,6 +1133,7 @@ bool rnn_fused_resident_launch(const RnnArgs &g, hipStream_t s)
 constexpr int kRnnWaves = 12;  // three waves per SIMD: the kernel needs at most 168 registers
 
 constexpr int kRnnSplitWaves = 8;  // the split variant holds three planes of every fragment: two waves per SIMD
+constexpr int kRnnPackWaves = 8;   // (12 waves would leave 168 registers: the epilogue then spills)
 
 template <bool LSTM>
 bool rnn_fused_resident_dispatch(const RnnArgs &g, hipStream_t s)
@@ -1076,6 +1142,10 @@ bool rnn_fused_resident_dispatch(const RnnArgs &g, hipStream_t s)
         if (g.H % 128 == 0 && rnn_fused_resident_launch<LSTM, 4, kRnnSplitWaves, true>(g, s)) return true;
         if (g.H % 64 == 0 && rnn_fused_resident_launch<LSTM, 2, kRnnSplitWaves, true>(g, s)) return true;
         if (rnn_fused_resident_launch<LSTM, 1, kRnnSplitWaves, true>(g, s)) return true;
+        // LSTM whose unpacked three-plane slab does not fit: 16 units per wave, two gates per tile
+        if constexpr (LSTM) {
+            if (g.H % 16 == 0 && rnn_fused_resident_launch<true, 1, kRnnPackWaves, true, true>(g, s)) return true;
+        }
     }
     if (g.H % 128 == 0 && rnn_fused_resident_launch<LSTM, 4, kRnnWaves, false>(g, s)) return true;
     if (g.H % 64 == 0 && rnn_fused_resident_launch<LSTM, 2, kRnnWaves, false>(g, s)) return true;
