@@ -116,3 +116,19 @@ def test_zero_weights_closed_form(ctx):
     assert torch.allclose(out, 0.5 * hp, atol=1e-7)
     out, c = ctx.rnn_step("lstm", x, hp, cp, z(d, 4 * h), z(h, 4 * h), z(4 * h), z(4 * h))
     assert torch.allclose(c, 0.5 * cp, atol=1e-7) and torch.allclose(out, 0.5 * torch.tanh(0.5 * cp), atol=1e-6)
+
+
+def test_fp32_instruction_path_in_a_child_process():
+    """REINC_DENSE=fp32 keeps the dense kernels on the fp32 matrix instructions; the switch is read once per process,
+    so the cases above are run again in one child process with it set."""
+    import os
+    import subprocess
+    import sys
+
+    if os.environ.get("REINC_DENSE") == "fp32":
+        pytest.skip("this is the child")
+    env = dict(os.environ, REINC_DENSE="fp32")
+    here = os.path.abspath(__file__)
+    out = subprocess.run([sys.executable, "-m", "pytest", here, "-q", "-x", "-m", "gpu", "-p", "no:cacheprovider"], env=env,
+                         cwd=os.path.dirname(os.path.dirname(here)), capture_output=True, text=True, timeout=600)
+    assert out.returncode == 0, out.stdout[-3000:] + out.stderr[-2000:]
