@@ -347,10 +347,16 @@ incremental_rows(const int32_t *__restrict__ rows, int64_t n_rows, const int64_t
                 sc[j] = __shfl(my_sc, e & 63);
                 if (e < cnt) {
                     const int64_t u = en & kPayloadMask;
-                    if ((en >> kKindShift) == 2u)
+                    if constexpr (!BF16) {
+                        // both kinds of source are fp32 rows of the same width: one load from a selected base, not
+                        // two loads under complementary masks
+                        const float *src = (en >> kKindShift) == 2u ? dY : static_cast<const float *>(x_prev);
+                        load_f32<VEC>(src, u, D, li, r[j]);
+                    } else if ((en >> kKindShift) == 2u) {
                         load_f32<VEC>(dY, u, D, li, r[j]);
-                    else
+                    } else {
                         Row<BF16>::load(x_prev, u, D, li, r[j]);
+                    }
                 } else {
                     sc[j] = 0.0f;
 #pragma unroll
@@ -435,10 +441,16 @@ incremental_rows_grouped(const int32_t *__restrict__ rows, int64_t n_rows, const
                 const uint32_t en = __shfl(my_e, gbase + (e & (LPR - 1)));
                 if (e < cnt) {
                     const int64_t u = en & kPayloadMask;
-                    if ((en >> kKindShift) == 2u)
+                    if constexpr (!BF16) {
+                        // both kinds of source are fp32 rows of the same width: one load from a selected base, not
+                        // two loads under complementary masks
+                        const float *src = (en >> kKindShift) == 2u ? dY : static_cast<const float *>(x_prev);
+                        load_f32<VEC>(src, u, D, li, r[j]);
+                    } else if ((en >> kKindShift) == 2u) {
                         load_f32<VEC>(dY, u, D, li, r[j]);
-                    else
+                    } else {
                         Row<BF16>::load(x_prev, u, D, li, r[j]);
+                    }
                 } else {
 #pragma unroll
                     for (int i = 0; i < VEC; ++i) r[j][i] = 0.0f;
