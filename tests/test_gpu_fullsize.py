@@ -135,3 +135,76 @@ def torch_index(rows):
     import torch
 
     return torch.from_numpy(np.asarray(rows, dtype=np.int64)).cuda()
+
+
+def _sampled_rows(n, rng, count=600):
+    """Random rows plus the first and last rows of the matrix, of a 32-row tile and of a persistent block's range."""
+    edges = [0, 1, 31, 32, n // 2, n - 33, n - 32, n - 2, n - 1]
+    return np.unique(np.concatenate([rng.integers(0, n, count), np.asarray(edges)]))
+
+
+@pytest.mark.parametrize("n,k,m,relu,scale,bias", [
+    (800_000, 64, 64, True, True, True),      # a batch of 8 timesteps of workload c2: layer update
+    (800_000, 192, 64, False, False, False),  # c2: gate gradients back through W_i
+    (1_000_000, 128, 128, True, True, True),  # c3: layer update
+    (1_000_000, 512, 128, False, False, False),  # c3: LSTM gate gradients, two passes over K
+    (1_000_003, 256, 256, True, True, True),  # c4's first layer width, ragged last tile
+])
+def test_row_gemm_at_full_size(n, k, m, relu, scale, bias):
+    """The dense layer update at the row counts of the benchmark (persistent grid, one block per compute unit):
+    sampled output rows against the fp64 reference."""
+    import torch
+    from paper_2501_15348_amd import reinc
+
+    rng = np.random.default_rng(k + m)
+    ctx = reinc.Context(64, 1, (16, 16), "gru", 16, "sum", True, arena_bytes=1 << 20)
+    a = torch.randn(n, k, device="cuda")
+    w = (rng.standard_normal((k, m)) / np.sqrt(k)).astype(np.float32)
+    b = rng.standard_normal(m).astype(np.float32) if bias else None
+    rs = torch.rand(n, device="cuda") * 0.9 + 0.1 if scale else None
+    print(f"row gemm {n} x {k} -> {m}", flush=True)
+    out = ctx.gcn_transform(a, torch.from_numpy(w).cuda(), torch.from_numpy(b).cuda() if bias else None, rs, relu=relu)
+    rows = _sampled_rows(n, rng)
+    idx = torch_index(rows)
+    a_s = a[idx].cpu().numpy().astype(np.float64)
+    if scale:
+        a_s = a_s * rs[idx].cpu().numpy().astype(np.float64)[:, None]
+    ref = oracle.dense_layer(a_s, w, b, relu)
+    assert_close(out[idx].cpu().numpy(), ref, RTOL_FP32, f"rows of {n}x{k}x{m}")
+    ctx.close()
+
+
+@pytest.mark.parametrize("kind,n,d,h", [
+    ("gru", 100_000, 64, 64),       # c2
+    ("lstm", 1_000_000, 128, 128),  # c3: 16 hidden units per wave, two gates per tile
+    ("gru", 1_000_003, 128, 128),   # c4's cell, ragged last tile
+])
+def test_recurrent_step_at_full_size(kind, n, d, h):
+    """The fused recurrent step at the row counts of the benchmark: sampled rows against the fp64 cell."""
+    import torch
+    from paper_2501_15348_amd import reinc
+
+    rng = np.random.default_rng(n % 1000 + d + h)
+    ctx = reinc.Context(64, 1, (16, 16), "gru", 16, "sum", True, arena_bytes=1 << 20)
+    kg = 3 if kind == "gru" else 4
+    x, hp, cp = (torch.randn(n, w, device="cuda") for w in (d, h, h))
+    wi = (rng.standard_normal((d, kg * h)) / np.sqrt(d)).astype(np.float32)
+    wh = (rng.standard_normal((h, kg * h)) / np.sqrt(h)).astype(np.float32)
+    bi = (rng.standard_normal(kg * h) * 0.3).astype(np.float32)
+    bh = (rng.standard_normal(kg * h) * 0.3).astype(np.float32)
+    saved = torch.empty((n, 4 * h), device="cuda")
+    print(f"{kind} step {n} x {d} / {h}", flush=True)
+    dev = lambda v: torch.from_numpy(v).cuda()
+    h_out, c_out = ctx.rnn_step(kind, x, hp, cp if kind == "lstm" else None, dev(wi), dev(wh), dev(bi), dev(bh), saved)
+    rows = _sampled_rows(n, rng)
+    idx = torch_index(rows)
+    f = lambda t: t[idx].cpu().numpy().astype(np.float64)
+    g = lambda v: v.astype(np.float64)
+    if kind == "gru":
+        ref_h, gates = oracle.gru_cell(f(x), f(hp), g(wi), g(wh), g(bi), g(bh))
+    else:
+        ref_h, ref_c, gates = oracle.lstm_cell(f(x), f(hp), f(cp), g(wi), g(wh), g(bi), g(bh))
+        assert_close(c_out[idx].cpu().numpy(), ref_c, RTOL_FP32, "c")
+    assert_close(h_out[idx].cpu().numpy(), ref_h, RTOL_FP32, "h")
+    assert_close(saved[idx].cpu().numpy(), np.concatenate(gates, axis=1), RTOL_FP32, "saved gates")
+    ctx.close()
