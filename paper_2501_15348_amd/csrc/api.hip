@@ -422,9 +422,10 @@ static int build_group(reinc_ctx *ctx, const std::vector<int32_t> &steps, hipStr
         dl.del_col = static_cast<int32_t *>(take(tt[1], 4));
         dl.ent = static_cast<uint32_t *>(take(tt[2], 4));
         dl.rows = static_cast<int32_t *>(take(tt[3], 4));
+        dl.row_ent = static_cast<int64_t *>(take(tt[3] + 1, 8));
         dl.long_rows = static_cast<int32_t *>(take(tt[5], 4));
         dl.n_long_rows = tt[5];
-        if (!dl.changed || !dl.dY || !dl.ins_col || !dl.del_col || !dl.ent || !dl.rows || !dl.long_rows)
+        if (!dl.changed || !dl.dY || !dl.ins_col || !dl.del_col || !dl.ent || !dl.rows || !dl.row_ent || !dl.long_rows)
             return nomem("delta entries");
     }
     int64_t max_changed = 0;
@@ -432,7 +433,7 @@ static int build_group(reinc_ctx *ctx, const std::vector<int32_t> &steps, hipStr
         const Delta &dl = ctx->deltas[steps[g]];
         DiffStep &st = table[g];
         st.ins_col = dl.ins_col, st.del_col = dl.del_col, st.ent = dl.ent;
-        st.rows = dl.rows, st.long_rows = dl.long_rows, st.changed = dl.changed, st.dY = dl.dY;
+        st.rows = dl.rows, st.row_ent = dl.row_ent, st.long_rows = dl.long_rows, st.changed = dl.changed, st.dY = dl.dY;
         st.n_changed = totals[size_t(kTotals) * g + 4];
         max_changed = std::max(max_changed, st.n_changed);
     }
@@ -476,7 +477,7 @@ static int build_steps(reinc_ctx *ctx, const std::vector<int32_t> &todo, hipStre
         while (i + group.size() < todo.size()) {
             const int32_t t = todo[i + group.size()];
             const Snapshot &a = ctx->snaps[t - 1], &b = ctx->snaps[t];
-            const uint64_t persistent = 3 * uint64_t(n + 1) * 8 + uint64_t(2 * a.nnz + 3 * b.nnz + 4 * n) * 4 +
+            const uint64_t persistent = 4 * uint64_t(n + 1) * 8 + uint64_t(2 * a.nnz + 3 * b.nnz + 4 * n) * 4 +
                                         uint64_t(n) * ctx->cfg.dims[0] * 4 + 16 * 256;
             const uint64_t tables = uint64_t(a.nnz + 2 * b.nnz + 2 * n) / 256 + 4096;  // tile sums, job and pointer tables
             const uint64_t need = step_scratch_bytes(n, a.nnz, b.nnz) + persistent + tables;
@@ -616,7 +617,7 @@ int reinc_aggregate_incremental(reinc_ctx *ctx, int32_t t, const float *S_prev, 
     {
         // in place: the rows of R_t; to a new buffer: one pass over every row (rows without entries are copied)
         ProfScope prof(ctx, REINC_K_AGG_INC, as_stream(stream));
-        launch_incremental(in_place ? dl.rows : nullptr, in_place ? dl.info.n_rows : ctx->N(), dl.long_rows, dl.n_long_rows,
+        launch_incremental(in_place ? dl.rows : nullptr, dl.row_ent, in_place ? dl.info.n_rows : ctx->N(), dl.long_rows, dl.n_long_rows,
                            dl.ent_ptr, dl.ent, pv.x, ctx->cfg.feat_dtype == REINC_BF16, pv.p, dl.dY, d, S_prev, S_out, sn.q,
                            agg_out, as_stream(stream));
     }

@@ -59,6 +59,7 @@ struct Delta {
     int64_t *ent_ptr = nullptr;  // [N+1]
     uint32_t *ent = nullptr;     // [n_entries]
     int32_t *rows = nullptr;     // R_t [n_rows]
+    int64_t *row_ent = nullptr;    // [n_rows + 1]: ent_ptr of the listed rows (their entries are adjacent)
     int32_t *long_rows = nullptr;  // rows of R_t with more than kLongRow entries
     int64_t n_long_rows = 0;
     int32_t *changed = nullptr;  // C_t [n_changed]
@@ -250,6 +251,7 @@ struct DiffStep {
     int32_t *ins_col, *del_col;
     uint32_t *ent;
     int32_t *rows, *long_rows, *changed;
+    int64_t *row_ent;
     float *dY;
     int64_t n_changed;
 };
@@ -306,9 +308,9 @@ void launch_minmax_incremental(const int32_t *rows, int64_t n_rows, const int32_
                                const int32_t *idx, const void *x_cur, int bf16, int32_t d, int self_loop, int is_max,
                                const float *M_prev, const int32_t *C_prev, float *M_out, int32_t *C_out, int32_t *hub_flags,
                                int32_t *block_counts, int32_t *stat_out, hipStream_t s);
-// rows: every changed row (those of at most kLongRow entries are taken one per lane group); long_rows: the
-// changed rows with more entries (one wavefront each)
-void launch_incremental(const int32_t *rows, int64_t n_rows, const int32_t *long_rows, int64_t n_long,
+// rows: every changed row (those of at most kLongRow entries are taken one per lane group), row_ent: where the entries
+// of the i-th listed row begin ([n_rows + 1]; optional); long_rows: the changed rows with more entries (one wavefront each)
+void launch_incremental(const int32_t *rows, const int64_t *row_ent, int64_t n_rows, const int32_t *long_rows, int64_t n_long,
                         const int64_t *ent_ptr, const uint32_t *ent, const void *x_prev, int bf16, const float *p_prev,
                         const float *dY, int32_t d, const float *S_prev, float *S_out, const float *q, float *agg_out,
                         hipStream_t s);

@@ -388,8 +388,8 @@ incremental_rows(const int32_t *__restrict__ rows, int64_t n_rows, const int64_t
 // Changed rows with at most kLongRow entries, one row per group of LPR lanes (see aggregate_rows_grouped).
 template <int LPR, bool BF16>
 __global__ void __launch_bounds__(64 * kWavesPerBlock)
-incremental_rows_grouped(const int32_t *__restrict__ rows, int64_t n_rows, const int64_t *__restrict__ ent_ptr,
-                         const uint32_t *__restrict__ ent, const void *__restrict__ x_prev,
+incremental_rows_grouped(const int32_t *__restrict__ rows, const int64_t *__restrict__ row_ent, int64_t n_rows,
+                         const int64_t *__restrict__ ent_ptr, const uint32_t *__restrict__ ent, const void *__restrict__ x_prev,
                          const float *__restrict__ p_prev, const float *__restrict__ dY, const float *S_prev, float *S_out,
                          const float *__restrict__ q, float *__restrict__ agg_out)
 {
@@ -403,8 +403,15 @@ incremental_rows_grouped(const int32_t *__restrict__ rows, int64_t n_rows, const
     int64_t v = 0, beg = 0, end = 0;
     if (live) {
         v = rows ? rows[w] : w;  // no row list: every row, so that rows without entries are copied through
-        beg = ent_ptr[v];
-        end = ent_ptr[v + 1];
+        if (row_ent) {
+            // the listed rows are exactly those with entries, in ascending order: their entries are adjacent, and
+            // the bounds come from the list position, one dependent load earlier than through the row id
+            beg = row_ent[w];
+            end = row_ent[w + 1];
+        } else {
+            beg = ent_ptr[v];
+            end = ent_ptr[v + 1];
+        }
     }
     const bool mine = live && end - beg <= kLongRow;  // longer rows belong to the wave-per-row pass
     if (!mine) end = beg;
@@ -892,7 +899,7 @@ void aggregate_long_dispatch(int lpr, const AggBatch &batch, int32_t max_long, i
 }
 
 template <bool BF16>
-void incremental_dispatch(int lpr, const int32_t *rows, int64_t n_rows, const int32_t *long_rows, int64_t n_long,
+void incremental_dispatch(int lpr, const int32_t *rows, const int64_t *row_ent, int64_t n_rows, const int32_t *long_rows, int64_t n_long,
                           const int64_t *ent_ptr, const uint32_t *ent, const void *x_prev, const float *p_prev,
                           const float *dY, const float *S_prev, float *S_out, const float *q, float *agg_out,
                           hipStream_t s)
@@ -903,8 +910,8 @@ void incremental_dispatch(int lpr, const int32_t *rows, int64_t n_rows, const in
     case L: {                                                                                                       \
         const int64_t rows_per_block = int64_t(kWavesPerBlock) * (64 / L);                                          \
         const unsigned blocks = unsigned((n_rows + rows_per_block - 1) / rows_per_block);                           \
-        incremental_rows_grouped<L, BF16><<<blocks, th, 0, s>>>(rows, n_rows, ent_ptr, ent, x_prev, p_prev, dY, S_prev, \
-                                                                S_out, q, agg_out);                                 \
+        incremental_rows_grouped<L, BF16><<<blocks, th, 0, s>>>(rows, rows ? row_ent : nullptr, n_rows, ent_ptr, ent, x_prev, \
+                                                                p_prev, dY, S_prev, S_out, q, agg_out);             \
         if (n_long > 0)                                                                                             \
             incremental_rows<L, BF16><<<long_blocks, th, 0, s>>>(long_rows, n_long, ent_ptr, ent, x_prev, p_prev, dY, \
                                                                  S_prev, S_out, q, agg_out);                        \
@@ -1024,7 +1031,7 @@ void aggregate_full(reinc_ctx *ctx, const int64_t *ptr, const int32_t *idx, cons
     aggregate_full_batch(ctx, batch, bf16, d, self_loop, s);
 }
 
-void launch_incremental(const int32_t *rows, int64_t n_rows, const int32_t *long_rows, int64_t n_long,
+void launch_incremental(const int32_t *rows, const int64_t *row_ent, int64_t n_rows, const int32_t *long_rows, int64_t n_long,
                         const int64_t *ent_ptr, const uint32_t *ent, const void *x_prev, int bf16, const float *p_prev,
                         const float *dY, int32_t d, const float *S_prev, float *S_out, const float *q, float *agg_out,
                         hipStream_t s)
@@ -1032,10 +1039,10 @@ void launch_incremental(const int32_t *rows, int64_t n_rows, const int32_t *long
     if (n_rows <= 0) return;
     const int lpr = lanes_per_row(d, bf16);
     if (bf16)
-        incremental_dispatch<true>(lpr, rows, n_rows, long_rows, n_long, ent_ptr, ent, x_prev, p_prev, dY, S_prev, S_out, q,
+        incremental_dispatch<true>(lpr, rows, row_ent, n_rows, long_rows, n_long, ent_ptr, ent, x_prev, p_prev, dY, S_prev, S_out, q,
                                    agg_out, s);
     else
-        incremental_dispatch<false>(lpr, rows, n_rows, long_rows, n_long, ent_ptr, ent, x_prev, p_prev, dY, S_prev, S_out, q,
+        incremental_dispatch<false>(lpr, rows, row_ent, n_rows, long_rows, n_long, ent_ptr, ent, x_prev, p_prev, dY, S_prev, S_out, q,
                                     agg_out, s);
 }
 

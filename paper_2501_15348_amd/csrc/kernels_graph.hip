@@ -395,7 +395,11 @@ __global__ void steps_compact(const DiffStep *steps, int64_t n)
     const bool c = st.cflags[v] != 0;
     if (c) st.changed[st.coffs[v]] = int32_t(v);
     st.cindex[v] = c ? int32_t(st.coffs[v]) : -1;
-    if (st.row_flag[v]) st.rows[st.roffs[v]] = int32_t(v);
+    if (st.row_flag[v]) {
+        st.rows[st.roffs[v]] = int32_t(v);
+        st.row_ent[st.roffs[v]] = st.ent_ptr[v];
+    }
+    if (v == n - 1) st.row_ent[st.roffs[n]] = st.ent_ptr[n];
     if (st.long_flag[v]) st.long_rows[st.loffs[v]] = int32_t(v);
 }
 

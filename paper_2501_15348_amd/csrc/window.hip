@@ -305,7 +305,7 @@ int ensure_layer1(reinc_ctx *ctx, int32_t t, hipStream_t s)
         {
             // one pass over every row: changed rows get their delta, the others are copied into the new slot
             ProfScope prof(ctx, REINC_K_AGG_INC, s);
-            launch_incremental(nullptr, c.num_nodes, dl.long_rows, dl.n_long_rows, dl.ent_ptr, dl.ent, pv.x, bf16, pv.p, dl.dY,
+            launch_incremental(nullptr, nullptr, c.num_nodes, dl.long_rows, dl.n_long_rows, dl.ent_ptr, dl.ent, pv.x, bf16, pv.p, dl.dY,
                                d, ctx->gcache[t - 1], slot, nullptr, nullptr, s);
         }
         ++ctx->stats.steps_incremental;
