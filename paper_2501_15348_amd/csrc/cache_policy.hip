@@ -163,10 +163,14 @@ int reinc_policy_offer(reinc_policy *p, int64_t key, int64_t size, int64_t futur
                        int64_t *evicted, int32_t evicted_cap, int32_t *n_evicted)
 {
     if (!p || !admitted || size <= 0 || evicted_cap < 0 || (evicted_cap > 0 && !evicted)) return REINC_E_ARG;
-    std::vector<int64_t> gone;
-    *admitted = p->store.offer(key, size, future, imminence, &gone) ? 1 : 0;
-    if (n_evicted) *n_evicted = int32_t(gone.size());
-    for (size_t i = 0; i < gone.size() && i < size_t(evicted_cap); ++i) evicted[i] = gone[i];
+    try {
+        std::vector<int64_t> gone;
+        *admitted = p->store.offer(key, size, future, imminence, &gone) ? 1 : 0;
+        if (n_evicted) *n_evicted = int32_t(gone.size());
+        for (size_t i = 0; i < gone.size() && i < size_t(evicted_cap); ++i) evicted[i] = gone[i];
+    } catch (const std::bad_alloc &) {  // no exception crosses the C boundary
+        return REINC_E_NOMEM;
+    }
     return REINC_OK;
 }
 

@@ -7,6 +7,8 @@
 
 #include "ctx.h"
 
+#include <new>
+
 using namespace reinc;
 
 namespace {
@@ -821,7 +823,9 @@ int reinc_cache_configure(reinc_ctx *ctx, int32_t policy, int64_t budget_bytes, 
     ctx->budget_slots = std::min<int64_t>(budget_bytes / size, ctx->cfg.num_snapshots);  // more can never be held
     ctx->plan_window = window;
     ctx->plan_stride = stride;
-    ctx->gpolicy.reset(new CachePolicy(policy, ctx->budget_slots * size));
+    CachePolicy *store = new (std::nothrow) CachePolicy(policy, ctx->budget_slots * size);
+    if (!store) return ctx->fail(REINC_E_NOMEM, "out of host memory");
+    ctx->gpolicy.reset(store);
     ctx->pool_free = ctx->pool;  // buffers of an earlier budget are reused; more are taken at the next window if needed
     ctx->sync_policy_stats();
     return REINC_OK;
