@@ -896,10 +896,16 @@ __global__ void __launch_bounds__(64 * WAVES) rnn_fused_resident_kernel(RnnArgs 
         sc = *(const GlobalFloat *)lsp;
         advance(true);
     };
-    // the first two chunks are requested before the slabs are staged: the fetches overlap
-    float b0[16], b1[16], b2[16], s0 = 1.0f, s1 = 1.0f, s2 = 1.0f;
-    issue(b0, s0);
-    issue(b1, s1);
+    // A ring of RING register buffers keeps the loads RING - 1 chunks ahead of the matrix cores.  The split variants
+    // have registers to spare (two waves per SIMD) and take four: on small graphs a wave has a handful of tiles
+    // and its time is the chain of memory round trips, which a ring that holds a whole tile's chunks shortens.
+    // The first chunks are requested before the slabs are staged: the fetches overlap.
+    constexpr int RING = SPLIT ? 4 : 3;
+    float buf[RING][16], bsc[RING];
+#pragma unroll
+    for (int r = 0; r < RING; ++r) bsc[r] = 1.0f;
+#pragma unroll
+    for (int r = 0; r + 1 < RING; ++r) issue(buf[r], bsc[r]);
     const bool fast_stage = h0 + BH <= H && H % 4 == 0 && (reinterpret_cast<uintptr_t>(g.W_i) & 15) == 0 &&
                             (reinterpret_cast<uintptr_t>(g.W_h) & 15) == 0;
     u32x4 *Bq = reinterpret_cast<u32x4 *>(Bs);
@@ -1083,28 +1089,25 @@ __global__ void __launch_bounds__(64 * WAVES) rnn_fused_resident_kernel(RnnArgs 
     };
     // steady state (unconditional loads, exact waits), then the last chunks: see gemm_rows_resident_kernel
     const int my_tiles = first < ntiles ? (ntiles - first + stride - 1) / stride : 0;
-    const int steady = max(my_tiles * kch - 2, 0) / 3;
+    const int steady = max(my_tiles * kch - (RING - 1), 0) / RING;
     for (int it = 0; it < steady; ++it) {
-        issue_always(b2, s2);
-        __builtin_amdgcn_sched_barrier(0);
-        multiply(b0, s0);
-        issue_always(b0, s0);
-        __builtin_amdgcn_sched_barrier(0);
-        multiply(b1, s1);
-        issue_always(b1, s1);
-        __builtin_amdgcn_sched_barrier(0);
-        multiply(b2, s2);
+#pragma unroll
+        for (int r = 0; r < RING; ++r) {
+            issue_always(buf[(r + RING - 1) % RING], bsc[(r + RING - 1) % RING]);
+            __builtin_amdgcn_sched_barrier(0);
+            multiply(buf[r], bsc[r]);
+        }
     }
-    auto step = [&](float(&cur)[16], float &csc, float(&nxt)[16], float &nsc) __attribute__((always_inline)) {
-        const float sc = csc;
-        issue(nxt, nsc);
-        __builtin_amdgcn_sched_barrier(0);
-        multiply(cur, sc);
-    };
     while (tile < ntiles) {
-        step(b0, s0, b2, s2);
-        if (tile < ntiles) step(b1, s1, b0, s0);
-        if (tile < ntiles) step(b2, s2, b1, s1);
+#pragma unroll
+        for (int r = 0; r < RING; ++r) {
+            if (tile < ntiles) {
+                const float sc = bsc[r];
+                issue(buf[(r + RING - 1) % RING], bsc[(r + RING - 1) % RING]);
+                __builtin_amdgcn_sched_barrier(0);
+                multiply(buf[r], sc);
+            }
+        }
     }
 }
 
