@@ -181,7 +181,10 @@ def main():
         "config": {"workload": wl.name, "num_nodes": n, "num_edges": wl.num_edges, "snapshots": T, "window": L,
                    "windows_per_step": windows, "edge_churn": wl.edge_churn, "feat_churn": wl.feat_churn, "agg": wl.agg,
                    "dims": list(wl.dims), "rnn": wl.rnn, "hidden": wl.hidden, "fallback_ratio": 0.5,
-                   "step": "build deltas + cold epoch of forward/backward/SGD over all windows"},
+                   "step": "build deltas + cold epoch of forward/backward/SGD over all windows",
+                   "dense_products": ("fp32 matrix instructions" if os.environ.get("REINC_DENSE") == "fp32" else
+                                      "f32 operands as three bfloat16 terms each, six products on the bf16 matrix cores, "
+                                      "f32 accumulation (error as the fp32 instructions)")},
         "delta_edges_per_step": int(delta_edges), "snapshot_window_epoch_ms": round(ms_per_step, 3),
         "layer1_steps": {"incremental": (st1["steps_incremental"] - st0["steps_incremental"]) // args.steps,
                          "full": (st1["steps_full"] - st0["steps_full"]) // args.steps,
