@@ -146,6 +146,9 @@ class _EndpointSampler:
 
 def _draw_new_edges(rng, sampler: _EndpointSampler, need: int, existing_sorted: np.ndarray) -> np.ndarray:
     """`need` distinct edges, none a self-loop, none in `existing_sorted`; returned sorted."""
+    room = sampler.n * (sampler.n - 1) - existing_sorted.size
+    if need > room:
+        raise ValueError(f"{need} new edges requested, but only {room} distinct edges without self-loops are left on {sampler.n} nodes")
     got = np.empty(0, dtype=np.uint64)
     while got.size < need:
         m = int((need - got.size) * 1.25) + 64

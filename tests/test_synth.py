@@ -71,3 +71,11 @@ def test_params_layout():
     assert p["W1"].shape == (128, 128) and p["W_i"].shape == (128, 512) and p["b_h"].shape == (512,)
     assert abs(p["W1"]).max() <= 1 / np.sqrt(128)
     assert synth.make_target(wl.scaled(100)).shape == (100, 128)
+
+
+def test_impossible_edge_count_is_refused():
+    """More edges than distinct pairs exist: the generator says so instead of drawing for ever."""
+    import pytest
+
+    with pytest.raises(ValueError):
+        synth.make_sequence(synth.WORKLOADS["c5_10"].scaled(3, 2))
