@@ -32,6 +32,12 @@ Where the paper is silent this file decides: the tie-breaks above, that a refuse
 F and I are integers supplied by the caller (the paper derives them from the position of the snapshot in the
 sequence), and that LFU counts uses since entry (the count is lost on eviction).
 
+Pins (tests/test_oracle_cache_policy.py): a textbook page-replacement string (LRU 12 faults, optimum 9), exhaustive
+search for the optimal policy on small strings (no policy beats it; the score policy fed with true next-use distances
+reaches it), closed forms for cyclic access, hand-worked LFU, exact score comparison, and the shape of the paper's
+policy comparison on `encoder_decoder_flow`.  Parity unpinned: the hit rates the paper prints (52 % / 0 % at a 10 %
+cache, 78 % plateau, 100 % at 60 %) - the model and the cache-size normalisation behind them are not given.
+
 Access flows
 ------------
 `sliding_window_flow`   the flow of the library's window driver: window q covers snapshots qS .. qS+L-1, looks
