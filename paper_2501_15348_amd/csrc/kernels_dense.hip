@@ -14,6 +14,7 @@
 #include "ctx.h"
 
 #include <cstdlib>
+#include <type_traits>
 #include <cstring>
 
 namespace reinc {
@@ -1195,7 +1196,12 @@ __device__ inline void reduce_trip_split(const float (&a0)[8], const float (&a1)
     }
 }
 
-template <bool HAS_RS, bool SPLIT>
+// WIDE (outputs of four or more 64x64 slabs): the block's four waves take four different slabs (2 x 2, or 1 x 4 when
+// K <= 64) over the SAME rows instead of sharing one slab over different rows.  A row of A and of G is then fetched by
+// a quarter as many blocks -- with one slab per block every block re-read its 64 + 64 columns of every row, and on
+// outputs of 16 slabs (128 x 512: an LSTM's gate weights) the counters showed 2.6 times the algorithmic bytes coming
+// from HBM -- and no partial slabs have to be combined at the end.
+template <bool HAS_RS, bool SPLIT, bool WIDE>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) gemm_reduce_kernel(ReduceArgs g)
 {
     // wave w finishes accumulator tile w of the 2x2: the other waves park their share of it here (two tiles at
@@ -1207,11 +1213,17 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
     // 1-D grid; consecutive block ids go round the 8 XCDs, so id % 8 picks the XCD.  All slabs of one row chunk
     // are given to the same XCD (and to neighbouring ids), so that chunk's rows are fetched from HBM once and the
     // other slabs find them in that XCD's L2.
-    const int slabs_x = (g.K + 63) / 64, slabs = slabs_x * ((g.M + 63) / 64);
+    // WIDE: a block's slab is wx x wy wave slabs
+    const int wx = WIDE ? (g.K > 64 ? 2 : 1) : 1, wy = WIDE ? 4 / wx : 1;
+    const int slabs_x = (g.K + 64 * wx - 1) / (64 * wx), slabs = slabs_x * ((g.M + 64 * wy - 1) / (64 * wy));
     const int xcd = blockIdx.x % 8, qid = blockIdx.x / 8;
     const int slab = qid % slabs, chunk = (qid / slabs) * 8 + xcd;
     if (chunk >= g.chunks) return;
-    const int f0 = (slab % slabs_x) * 64, c0 = (slab / slabs_x) * 64;
+    const int f0 = (slab % slabs_x) * 64 * wx + (WIDE ? (w % wx) * 64 : 0);
+    const int c0 = (slab / slabs_x) * 64 * wy + (WIDE ? (w / wx) * 64 : 0);
+    if (WIDE && (f0 >= g.K || c0 >= g.M)) return;  // a wave slab outside the output (no barrier follows in this mode)
+    // rows of a trip: wave offset + rstep * u + half-wave, u = 0 .. 7; a block's trip covers `trip` rows
+    const int woff = WIDE ? 0 : 2 * w, rstep = WIDE ? 2 : 8, trip = WIDE ? 16 : 64;
     const int64_t r_begin = int64_t(chunk) * g.rows_per_chunk;
     const int64_t r_end = max(r_begin, min(g.n, r_begin + g.rows_per_chunk));  // a chunk past the last row is empty
     acc16 acc[2][2];
@@ -1233,25 +1245,25 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
     if (f0 + 64 <= g.K && c0 + 64 <= g.M) {
         // wave-uniform row pointers plus one fixed 32-bit lane offset per operand: the addresses of a trip cost
         // scalar arithmetic only
-        const int wu = __builtin_amdgcn_readfirstlane(w);
-        const float *ap = g.A + (base + 2 * wu) * g.lda + f0;
-        const float *gp = g.G + (base + 2 * wu) * g.ldg + c0;
-        const float *sp = HAS_RS ? g.row_scale + base + 2 * wu : nullptr;
+        const int wu = __builtin_amdgcn_readfirstlane(woff);
+        const float *ap = g.A + (base + wu) * g.lda + f0;
+        const float *gp = g.G + (base + wu) * g.ldg + c0;
+        const float *sp = HAS_RS ? g.row_scale + base + wu : nullptr;
         const unsigned aoff = unsigned(kk) * unsigned(g.lda) + i, goff = unsigned(kk) * unsigned(g.ldg) + i;
         // a trip's operands: [0] [1] = the two 32-column halves of the A rows, [2] [3] = of the G rows, [4] = row scale
         auto load = [&](float(&t)[5][kRU]) __attribute__((always_inline)) {
 #pragma unroll
             for (int u = 0; u < kRU; ++u) {
-                const float *au = ap + int64_t(8 * u) * g.lda, *gu = gp + int64_t(8 * u) * g.ldg;
+                const float *au = ap + int64_t(rstep * u) * g.lda, *gu = gp + int64_t(rstep * u) * g.ldg;
                 t[0][u] = au[aoff];
                 t[1][u] = au[aoff + 32];
                 t[2][u] = gu[goff];
                 t[3][u] = gu[goff + 32];
-                t[4][u] = HAS_RS ? sp[8 * u + kk] : 1.0f;
+                t[4][u] = HAS_RS ? sp[rstep * u + kk] : 1.0f;
             }
-            ap += int64_t(8 * kRU) * g.lda;
-            gp += int64_t(8 * kRU) * g.ldg;
-            if (HAS_RS) sp += 8 * kRU;
+            ap += int64_t(trip) * g.lda;
+            gp += int64_t(trip) * g.ldg;
+            if (HAS_RS) sp += trip;
         };
         auto multiply = [&](float(&t)[5][kRU]) __attribute__((always_inline)) {
             if (SPLIT) {
@@ -1282,11 +1294,17 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
                 bsum[1] += t[3][u];
             }
         };
-        const int trips = int((r_end - r_begin) / (8 * kRU));
+        const int trips = int((r_end - r_begin) / trip);
         float ta[5][kRU], tb[5][kRU];
         int t = 0;
         if (trips > 0) load(ta);
+        // WIDE: the four waves read the same rows (two of them the same columns of A, two the same columns of G).  While
+        // the whole block slab lies inside the output all four run this loop with the same trip count, and a barrier
+        // every other trip keeps them within two trips of each other, so that the second request for a line finds it in
+        // the compute unit's cache instead of going out again.
+        const bool lockstep = WIDE && (slab % slabs_x + 1) * 64 * wx <= g.K && (slab / slabs_x + 1) * 64 * wy <= g.M;
         for (; t + 2 < trips; t += 2) {
+            if (lockstep) __syncthreads();
             load(tb);
             __builtin_amdgcn_sched_barrier(0);  // the loads go out ahead of the arithmetic
             multiply(ta);
@@ -1302,15 +1320,15 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
         } else if (t < trips) {
             multiply(ta);
         }
-        base += int64_t(trips) * (8 * kRU);
+        base += int64_t(trips) * trip;
     }
     // ragged slabs and the last rows of the chunk: guarded loads
-    for (int64_t r0 = base + 2 * w + kk; r0 < r_end + kk; r0 += 8 * kRU) {
+    for (int64_t r0 = base + woff + kk; r0 < r_end + kk; r0 += trip) {
         // (the bound keeps both half-waves in step: a half that runs past r_end loads zeros)
         float a0[kRU], a1[kRU], b0[kRU], b1[kRU];
 #pragma unroll
         for (int u = 0; u < kRU; ++u) {
-            const int64_t r = r0 + 8 * u;
+            const int64_t r = r0 + rstep * u;
             a0[u] = a1[u] = b0[u] = b1[u] = 0.0f;
             if (r < r_end) {
                 const float sc = HAS_RS ? g.row_scale[r] : 1.0f;
@@ -1341,6 +1359,36 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
             bsum[1] += b1[u];
         }
     }
+    float *out = g.partial + int64_t(chunk) * (g.K + 1) * g.M;
+    if (WIDE) {
+        // every wave owns its four tiles: straight to the partial slab, four rows at a time
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
+#pragma unroll
+            for (int b = 0; b < 2; ++b) {
+                const int cc = c0 + 32 * b + i;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const int fr = f0 + 32 * a + 8 * q + 4 * kk + e;
+                        if (fr < g.K && cc < g.M) {
+                            float *o = out + int64_t(fr) * g.M + cc;
+                            *o = g.accumulate ? *o + acc[a][b][4 * q + e] : acc[a][b][4 * q + e];
+                        }
+                    }
+                }
+            }
+        if (f0 == 0) {  // the bias gradient: column sums of G, from the waves of the first row of slabs
+            const float s0 = bsum[0] + __shfl_xor(bsum[0], 32), s1 = bsum[1] + __shfl_xor(bsum[1], 32);
+            if (kk == 0) {
+                float *o = out + int64_t(g.K) * g.M + c0 + i;
+                if (c0 + i < g.M) o[0] = g.accumulate ? o[0] + s0 : s0;
+                if (c0 + 32 + i < g.M) o[32] = g.accumulate ? o[32] + s1 : s1;
+            }
+        }
+        return;
+    }
     // Combine the four waves.  Tile (a, b) is finished by wave 2a+b: the other three park their share in LDS
     // (slot = their rank among the other waves) and the owner adds the four shares in wave order, then adds
     // the result to the partial slab (or overwrites it).  Tiles (0, *) go first, then tiles (1, *).
@@ -1351,7 +1399,6 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
             bred[w][32 + i] = s1;
         }
     }
-    float *out = g.partial + int64_t(chunk) * (g.K + 1) * g.M;
     auto park = [&](const acc16 &t, int owner) __attribute__((always_inline)) {
         float *dst = red[owner & 1][w < owner ? w : w - 1];
 #pragma unroll
@@ -1633,17 +1680,32 @@ void launch_rnn_fused(int lstm, const float *x, const float *x_scale, int64_t n,
 #undef REINC_RNN_LAUNCH
 }
 
+// Outputs of four or more 64x64 slabs take the wide mode (a block = four slabs over the same rows).
+bool reduce_wide(int32_t K, int32_t M) { return ((K + 63) / 64) * ((M + 63) / 64) >= 4; }
+
+int reduce_block_slabs(int32_t K, int32_t M)
+{
+    if (!reduce_wide(K, M)) return ((K + 63) / 64) * ((M + 63) / 64);
+    const int wx = K > 64 ? 2 : 1, wy = 4 / wx;
+    return ((K + 64 * wx - 1) / (64 * wx)) * ((M + 64 * wy - 1) / (64 * wy));
+}
+
 int reduce_chunks(int64_t n, int32_t K, int32_t M)
 {
     // as many blocks as are resident at once (registers and LDS decide how many fit a compute unit), at least
     // 256 rows each
-    static const int per_cu =
-        dense_split_enabled()
-            ? std::max(1, std::min(resident_blocks(reinterpret_cast<const void *>(gemm_reduce_kernel<false, true>), 256, 0),
-                                   resident_blocks(reinterpret_cast<const void *>(gemm_reduce_kernel<true, true>), 256, 0)))
-            : std::max(1, std::min(resident_blocks(reinterpret_cast<const void *>(gemm_reduce_kernel<false, false>), 256, 0),
-                                   resident_blocks(reinterpret_cast<const void *>(gemm_reduce_kernel<true, false>), 256, 0)));
-    const int64_t slabs = int64_t((K + 63) / 64) * ((M + 63) / 64);
+    static const int per_cu = [] {
+        auto fit = [](const void *k) { return resident_blocks(k, 256, 0); };
+        const bool split = dense_split_enabled();
+        int m = 64;
+        for (const void *k : {reinterpret_cast<const void *>(split ? gemm_reduce_kernel<false, true, false> : gemm_reduce_kernel<false, false, false>),
+                              reinterpret_cast<const void *>(split ? gemm_reduce_kernel<true, true, false> : gemm_reduce_kernel<true, false, false>),
+                              reinterpret_cast<const void *>(split ? gemm_reduce_kernel<false, true, true> : gemm_reduce_kernel<false, false, true>),
+                              reinterpret_cast<const void *>(split ? gemm_reduce_kernel<true, true, true> : gemm_reduce_kernel<true, false, true>)})
+            m = std::min(m, fit(k));
+        return std::max(1, m);
+    }();
+    const int64_t slabs = reduce_block_slabs(K, M);
     int64_t chunks = std::max<int64_t>(1, int64_t(kNumCU) * per_cu / slabs);
     if (chunks >= 8) chunks &= ~int64_t(7);  // the grid is padded to whole groups of 8 chunks (one per XCD): stay resident
     chunks = std::min<int64_t>(chunks, (n + 255) / 256);
@@ -1665,13 +1727,18 @@ void launch_gemm_reduce(const float *A, int32_t lda, const float *row_scale, con
     int64_t rpc = (n_geom + chunks - 1) / chunks;
     rpc = (rpc + 63) & ~int64_t(63);  // whole 64-row trips; no row pair straddles two chunks
     ReduceArgs g{A, lda, row_scale, G, ldg, n, K, M, rpc, partial, chunks, accumulate};
-    const int slabs = ((K + 63) / 64) * ((M + 63) / 64);
+    const int slabs = reduce_block_slabs(K, M);
     const unsigned blocks = unsigned(slabs) * unsigned((chunks + 7) / 8) * 8u;
-    const bool split = dense_split_enabled();
+    const bool split = dense_split_enabled(), wide = reduce_wide(K, M);
+    auto pick = [&](auto has_rs) {
+        constexpr bool RS = decltype(has_rs)::value;
+        if (wide) return split ? gemm_reduce_kernel<RS, true, true> : gemm_reduce_kernel<RS, false, true>;
+        return split ? gemm_reduce_kernel<RS, true, false> : gemm_reduce_kernel<RS, false, false>;
+    };
     if (row_scale)
-        (split ? gemm_reduce_kernel<true, true> : gemm_reduce_kernel<true, false>)<<<blocks, 256, 0, s>>>(g);
+        pick(std::true_type{})<<<blocks, 256, 0, s>>>(g);
     else
-        (split ? gemm_reduce_kernel<false, true> : gemm_reduce_kernel<false, false>)<<<blocks, 256, 0, s>>>(g);
+        pick(std::false_type{})<<<blocks, 256, 0, s>>>(g);
 }
 
 void launch_reduce_partials(const float *partial, int64_t n, int32_t K, int32_t M, float *dW, float *db, hipStream_t s)
