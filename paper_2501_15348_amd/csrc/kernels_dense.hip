@@ -827,7 +827,7 @@ __global__ void __launch_bounds__(256) rnn_fused_kernel(RnnArgs g)
 // staged once per block (one block per compute unit), then every wave streams 32-row tiles for its 32 hidden
 // units without barriers.  Rows [0, d_in) of the slab hold W_i, rows [d_in, d_in + H) hold W_h, so the k
 // chunks of x and of h_prev form one stream per tile, and the chunks of all of a wave's tiles one stream
-// overall; a ring of three register buffers keeps the loads two chunks ahead of the matrix cores.  Needs
+// overall; a ring of register buffers (three, four in the split variants) keeps the loads ahead of the matrix cores.  Needs
 // d_in % 32 == 0, H % 32 == 0 and 16-byte aligned rows.  SPLIT: the slab holds the three bfloat16 planes of the
 // weights and the products run on the bf16 matrix cores (see the note on fp32 products above).
 //
