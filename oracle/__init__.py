@@ -21,6 +21,10 @@ LRU, LFU) is pinned to a textbook page-replacement example, exhaustive search fo
 for cyclic access and the shape of the paper's policy comparison; the paper's printed hit rates themselves are
 unpinned (the model and the cache-size normalisation behind them are not given).
 
+Node mini-batches (`oracle.minibatch`: the computational graphs of a set of nodes over the sequence, and the loss
+restricted to those nodes) are pinned to hand-worked graphs, dense matrix powers, the full-graph model itself
+(locality) and additivity over a partition of the nodes.
+
 Parity unpinned by the paper (pinned only to this package's own definition): the symmetric
 degree normalisation (absent from the paper), and the loss (mean squared error on a synthetic
 target instead of the paper's forecasting MAE on datasets that are not available).
@@ -29,3 +33,4 @@ from .dgnn import *  # noqa: F401,F403
 from . import incremental  # noqa: F401
 from . import minmax  # noqa: F401
 from . import cache_policy  # noqa: F401
+from . import minibatch  # noqa: F401

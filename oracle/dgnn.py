@@ -278,11 +278,14 @@ def forward_window(
     rnn: str,
     target: Optional[np.ndarray] = None,
     keep: bool = False,
+    loss_rows: Optional[np.ndarray] = None,
 ):
     """Forward over one window (Section 2.2: a sequence of consecutive snapshots is one sample and the
     recurrent state runs across it).  graphs[i], feats[i] are snapshot t0+i.  Every timestep recomputes
     H^l = ReLU(Agg(H^{l-1}; G_t) W_l + b_l) for l = 1..num_layers from H^0 = X_t, then steps the
-    recurrent cell from zero state.  loss = mean((h_last - target)^2).
+    recurrent cell from zero state.  loss = mean((h_last - target)^2), over all nodes or, for a node mini-batch
+    (Section 4.2: the sample is the sequence of computational graphs of the selected nodes), over the rows
+    `loss_rows` of h_last and target only.
     Returns (loss or None, h_last, saved) where saved feeds backward_window when keep is set."""
     p = _f64(params)
     n = graphs[0].n
@@ -309,7 +312,8 @@ def forward_window(
         h, c = h_new, c_new
     loss = None
     if target is not None:
-        loss = float(np.mean((h - np.asarray(target, dtype=np.float64)) ** 2))
+        diff = h - np.asarray(target, dtype=np.float64)
+        loss = float(np.mean((diff if loss_rows is None else diff[np.asarray(loss_rows)]) ** 2))
     return loss, h, saved
 
 
@@ -323,14 +327,20 @@ def backward_window(
     self_loop: bool,
     rnn: str,
     target: np.ndarray,
+    loss_rows: Optional[np.ndarray] = None,
 ) -> Dict[str, np.ndarray]:
-    """Back-propagation through time over the window (Section 2.2) for the loss of forward_window.
-    Gradients for every parameter; nothing is propagated to the input features."""
+    """Back-propagation through time over the window (Section 2.2) for the loss of forward_window (the same
+    `loss_rows`).  Gradients for every parameter; nothing is propagated to the input features."""
     p = _f64(params)
     hd = p["W_h"].shape[0]
     grads = {k: np.zeros_like(v) for k, v in p.items()}
     tgt = np.asarray(target, dtype=np.float64)
-    dh = 2.0 * (h_last - tgt) / tgt.size
+    if loss_rows is None:
+        dh = 2.0 * (h_last - tgt) / tgt.size
+    else:
+        rows = np.asarray(loss_rows)
+        dh = np.zeros_like(h_last)
+        dh[rows] = 2.0 * (h_last[rows] - tgt[rows]) / (rows.size * tgt.shape[1])
     dc = np.zeros_like(dh)
     for g, sv in zip(reversed(list(graphs)), reversed(saved)):
         x, h_prev = sv["x"], sv["h_prev"]
