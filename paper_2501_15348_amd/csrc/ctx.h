@@ -131,6 +131,12 @@ struct reinc_ctx {
     float *q_block = nullptr;     // [T, N] target-side degree scales of all snapshots (null for SUM)
     int max_batch = reinc::kMaxAggBatch;  // timesteps the window driver handles per launch (REINC_BATCH=1..8 lowers it)
     float *loss_partial = nullptr;
+    int64_t loss_rows = 0;  // rows [0, loss_rows) enter the loss (a node mini-batch, numbered first); 0 = every row
+    int64_t counted_rows() const { return loss_rows > 0 ? loss_rows : cfg.num_nodes; }
+    // node mini-batch plan made on this context (reinc_batch_plan): hop level and new id per node, the node list
+    int32_t *batch_level = nullptr, *batch_new_id = nullptr, *batch_nodes = nullptr;
+    int64_t batch_size = 0, batch_total = 0;  // batch nodes, nodes of the sub-sequence (0: no plan)
+    int32_t batch_hops = 0;
     reinc_stats stats{};
     // arena bookkeeping for reinc_reset_derived
     bool has_derived = false, load_after_derived = false;
@@ -339,7 +345,8 @@ void launch_rnn_backward_elem(int lstm, int64_t n, int32_t H, const float *dh, c
                               float *dh_carry, float *dc_prev, hipStream_t s);
 uint64_t loss_partial_bytes();
 void launch_mse(const float *h, const float *y, int64_t total, float *partial, float *loss, hipStream_t s);
-void launch_mse_grad(const float *h, const float *y, int64_t total, float *dh, hipStream_t s);
+// dh[i] = d mean((h - y)^2 over the first `counted` elements) / d h[i] for i < total (zero from `counted` on)
+void launch_mse_grad(const float *h, const float *y, int64_t counted, int64_t total, float *dh, hipStream_t s);
 void launch_fill_f32(float *p, int64_t n, float v, hipStream_t s);
 void launch_sgd(float *params, const float *grads, int64_t n, float lr, hipStream_t s);
 }  // namespace reinc

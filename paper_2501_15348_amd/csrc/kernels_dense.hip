@@ -1206,8 +1206,14 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
 {
     // wave w finishes accumulator tile w of the 2x2: the other waves park their share of it here (two tiles at
     // a time, to keep the block's LDS at 25 KB)
-    __shared__ float red[2][3][32 * 33];
-    __shared__ float bred[4][64];
+    // (wide mode with shared splitting uses the same storage for its staged planes: 2 buffers x 4 pieces x 3 planes x
+    // 64 columns x 2 half-waves of 16-byte records = 48 KB)
+    constexpr int kRedFloats = 2 * 3 * 32 * 33, kBredFloats = 4 * 64;
+    constexpr int kStageRecords = 2 * 4 * 3 * 64 * 2;
+    constexpr size_t kSharedBytes = (SPLIT && WIDE) ? size_t(kStageRecords) * 16 : size_t(kRedFloats + kBredFloats) * 4;
+    __shared__ __align__(16) unsigned char smem[kSharedBytes];
+    float(*red)[3][32 * 33] = reinterpret_cast<float(*)[3][32 * 33]>(smem);
+    float(*bred)[64] = reinterpret_cast<float(*)[64]>(smem + size_t(kRedFloats) * 4);
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int i = lane & 31, kk = lane >> 5;
     // 1-D grid; consecutive block ids go round the 8 XCDs, so id % 8 picks the XCD.  All slabs of one row chunk
@@ -1242,7 +1248,106 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
     // (a load that may or may not have been issued would force a wait for everything).
     constexpr int kRU = 8;
     int64_t base = r_begin;
-    if (f0 + 64 <= g.K && c0 + 64 <= g.M) {
+    // Wide 2 x 2 with the block slab inside the output: the four waves need the same 16 rows of 128 columns of A and
+    // of 128 columns of G, two waves each piece of 64 columns.  Each wave loads and splits ONE piece (waves 1, 3: the
+    // two pieces of A; waves 0, 2: the piece of G under their own slab, so the column sums for the bias gradient
+    // come out in the waves that write them), parks its three planes in LDS, and after a barrier every wave takes
+    // the fragments of the A piece and the G piece of its slab from there: half the loads and half the splitting per
+    // wave, and the waves cannot drift apart.  Two LDS buffers, one barrier per trip: a wave that writes buffer b
+    // again has passed the barrier of the trip between, which every wave reaches only after its reads of b.
+    bool shared_split = false;
+    if constexpr (SPLIT && WIDE) {
+        shared_split = wx == 2 && (slab % slabs_x + 1) * 128 <= g.K && (slab / slabs_x + 1) * 128 <= g.M;
+        if (shared_split) {
+            u32x4 *stage = reinterpret_cast<u32x4 *>(smem);  // [buffer][piece][plane][column][half]
+            const bool a_piece = (w & 1) != 0;
+            const int piece = w >> 1, slot = a_piece ? piece : 2 + piece;
+            const int pcol0 = (a_piece ? (slab % slabs_x) : (slab / slabs_x)) * 128 + 64 * piece;
+            const int ld = a_piece ? g.lda : g.ldg;
+            const float *pp = (a_piece ? g.A : g.G) + base * ld + pcol0;
+            const float *sp = (HAS_RS && a_piece) ? g.row_scale + base : nullptr;
+            const unsigned poff = unsigned(kk) * unsigned(ld) + i;
+            // a trip's piece: [0] [1] = its two 32-column halves, [2] = row scale (pieces of A)
+            auto load = [&](float(&t)[3][kRU]) __attribute__((always_inline)) {
+#pragma unroll
+                for (int u = 0; u < kRU; ++u) {
+                    const float *pu = pp + int64_t(2 * u) * ld;
+                    t[0][u] = pu[poff];
+                    t[1][u] = pu[poff + 32];
+                    t[2][u] = (HAS_RS && a_piece) ? sp[2 * u + kk] : 1.0f;
+                }
+                pp += int64_t(16) * ld;
+                if (HAS_RS && a_piece) sp += 16;
+            };
+            const int sx = w % 2, sy = w / 2;
+            auto process = [&](float(&t)[3][kRU], int buf) __attribute__((always_inline)) {
+                if (HAS_RS && a_piece) {
+#pragma unroll
+                    for (int u = 0; u < kRU; ++u) {
+                        t[0][u] *= t[2][u];
+                        t[1][u] *= t[2][u];
+                    }
+                }
+                if (!a_piece) {  // column sums of G: the bias gradient
+#pragma unroll
+                    for (int u = 0; u < kRU; ++u) {
+                        bsum[0] += t[0][u];
+                        bsum[1] += t[1][u];
+                    }
+                }
+                u32x4 p0[3], p1[3];
+                split8(t[0], p0[0], p0[1], p0[2]);
+                split8(t[1], p1[0], p1[1], p1[2]);
+                u32x4 *mine = stage + ((buf * 4 + slot) * 3) * 128;  // this wave's piece: [plane][column][half]
+#pragma unroll
+                for (int pl = 0; pl < 3; ++pl) {
+                    mine[pl * 128 + i * 2 + kk] = p0[pl];
+                    mine[pl * 128 + (32 + i) * 2 + kk] = p1[pl];
+                }
+                __syncthreads();
+                const u32x4 *pa = stage + ((buf * 4 + sx) * 3) * 128, *pg = stage + ((buf * 4 + 2 + sy) * 3) * 128;
+                u32x4 A0[3], A1[3], G0[3], G1[3];
+#pragma unroll
+                for (int pl = 0; pl < 3; ++pl) {
+                    A0[pl] = pa[pl * 128 + i * 2 + kk];
+                    A1[pl] = pa[pl * 128 + (32 + i) * 2 + kk];
+                    G0[pl] = pg[pl * 128 + i * 2 + kk];
+                    G1[pl] = pg[pl * 128 + (32 + i) * 2 + kk];
+                }
+                constexpr int order[6][2] = {{2, 0}, {1, 1}, {0, 2}, {1, 0}, {0, 1}, {0, 0}};
+#pragma unroll
+                for (int o = 0; o < 6; ++o) {
+                    const int p = order[o][0], q = order[o][1];
+                    acc[0][0] = mfma_bf16(A0[p], G0[q], acc[0][0]);
+                    acc[0][1] = mfma_bf16(A0[p], G1[q], acc[0][1]);
+                    acc[1][0] = mfma_bf16(A1[p], G0[q], acc[1][0]);
+                    acc[1][1] = mfma_bf16(A1[p], G1[q], acc[1][1]);
+                }
+            };
+            const int trips = int((r_end - r_begin) / 16);
+            float ta[3][kRU], tb[3][kRU];
+            int t = 0;
+            if (trips > 0) load(ta);
+            for (; t + 2 < trips; t += 2) {
+                load(tb);
+                __builtin_amdgcn_sched_barrier(0);
+                process(ta, 0);
+                load(ta);
+                __builtin_amdgcn_sched_barrier(0);
+                process(tb, 1);
+            }
+            if (t + 1 < trips) {
+                load(tb);
+                __builtin_amdgcn_sched_barrier(0);
+                process(ta, 0);
+                process(tb, 1);
+            } else if (t < trips) {
+                process(ta, 0);
+            }
+            base += int64_t(trips) * 16;
+        }
+    }
+    if (!shared_split && f0 + 64 <= g.K && c0 + 64 <= g.M) {
         // wave-uniform row pointers plus one fixed 32-bit lane offset per operand: the addresses of a trip cost
         // scalar arithmetic only
         const int wu = __builtin_amdgcn_readfirstlane(woff);
@@ -1600,10 +1705,11 @@ __global__ void __launch_bounds__(256) mse_final_kernel(const float *partial, in
     if (threadIdx.x == 0) *loss = total > 0 ? red[0] / float(total) : 0.0f;
 }
 
-__global__ void mse_grad_kernel(const float *h, const float *y, int64_t total, float *dh)
+// the loss covers the first `counted` elements; the gradient of the others (up to `total`) is zero
+__global__ void mse_grad_kernel(const float *h, const float *y, int64_t counted, int64_t total, float *dh)
 {
     const int64_t i = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
-    if (i < total) dh[i] = 2.0f * (h[i] - y[i]) / float(total);
+    if (i < total) dh[i] = i < counted ? 2.0f * (h[i] - y[i]) / float(counted) : 0.0f;
 }
 
 __global__ void sgd_kernel(float *p, const float *g, int64_t n, float lr)
@@ -1773,9 +1879,9 @@ void launch_mse(const float *h, const float *y, int64_t total, float *partial, f
     mse_final_kernel<<<1, 256, 0, s>>>(partial, kLossBlocks, total, loss);
 }
 
-void launch_mse_grad(const float *h, const float *y, int64_t total, float *dh, hipStream_t s)
+void launch_mse_grad(const float *h, const float *y, int64_t counted, int64_t total, float *dh, hipStream_t s)
 {
-    if (total > 0) mse_grad_kernel<<<unsigned((total + 255) / 256), 256, 0, s>>>(h, y, total, dh);
+    if (total > 0) mse_grad_kernel<<<unsigned((total + 255) / 256), 256, 0, s>>>(h, y, counted, total, dh);
 }
 
 void launch_sgd(float *params, const float *grads, int64_t n, float lr, hipStream_t s)

@@ -457,7 +457,7 @@ int reinc_forward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *par
         }
     }
     const LocalStep &last = ctx->local[L - 1];
-    if (target) launch_mse(last.h, target, n * H, ctx->loss_partial, loss_out, s);
+    if (target) launch_mse(last.h, target, ctx->counted_rows() * H, ctx->loss_partial, loss_out, s);
     if (h_last) REINC_HIP(ctx, hipMemcpyAsync(h_last, last.h, uint64_t(n) * H * 4, hipMemcpyDeviceToDevice, s));
     REINC_HIP(ctx, hipGetLastError());
     ctx->local_valid = true;
@@ -526,7 +526,7 @@ int reinc_backward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *pa
         return ctx->fail(REINC_E_NOMEM, "arena exhausted: no room for the backward scratch buffers");
     }
     launch_fill_f32(grads, p.count, 0.0f, s);
-    launch_mse_grad(ctx->local[L - 1].h, target, n * H, dh, s);
+    launch_mse_grad(ctx->local[L - 1].h, target, ctx->counted_rows() * H, n * H, dh, s);
     const float *dc_in = nullptr;  // zero at the last step
     const float *nof = nullptr;
     std::vector<const float *> s1(L), q(L), Ap(L), Mp(L);
@@ -657,7 +657,7 @@ int reinc_forward_window_integrated(reinc_ctx *ctx, int32_t t0, int32_t L, const
                   b_i, b_h, st.h, st.c, st.saved);
     }
     const LocalStep &last = ctx->local[L - 1];
-    if (target) launch_mse(last.h, target, n * H, ctx->loss_partial, loss_out, s);
+    if (target) launch_mse(last.h, target, ctx->counted_rows() * H, ctx->loss_partial, loss_out, s);
     if (h_last) REINC_HIP(ctx, hipMemcpyAsync(h_last, last.h, uint64_t(n) * H * 4, hipMemcpyDeviceToDevice, s));
     REINC_HIP(ctx, hipGetLastError());
     ctx->local_valid = true;
@@ -711,7 +711,7 @@ int reinc_backward_window_integrated(reinc_ctx *ctx, int32_t t0, int32_t L, cons
         return ctx->fail(REINC_E_NOMEM, "arena exhausted: no room for the backward scratch buffers");
     }
     launch_fill_f32(grads, count, 0.0f, s);
-    launch_mse_grad(ctx->local[L - 1].h, target, n * H, dh, s);
+    launch_mse_grad(ctx->local[L - 1].h, target, ctx->counted_rows() * H, n * H, dh, s);
     const float *dc_in = nullptr;
     const float *nof = nullptr;
     std::vector<const float *> s1(L), q(L), ah(L);

@@ -47,6 +47,7 @@ CASES = [
     ("c3", 1201, 4, dict(dims=(32, 64, 32, 16), hidden=32, agg="sym")),  # three GCN layers, LSTM
     ("c2", 2500, 6, dict(rnn="lstm", hidden=32)),  # a layer-1 pre-activation of this graph lies within fp32 rounding of zero
     ("c2", 40, 5, {}),                              # fewer rows than two tiles
+    ("c2", 1500, 4, dict(dims=(256, 128, 128), hidden=64)),  # weight gradients: block slabs of 128 x 128, whole (256 x 128) and ragged (128 x 192)
 ]
 
 
