@@ -259,6 +259,34 @@ int reinc_reset_derived(reinc_ctx *ctx);
  * the pointer is good until the next forward-window call (an aggregate the policy does not keep lives that long). */
 int reinc_cache_peek(reinc_ctx *ctx, int32_t t, const float **S_out);
 
+/* ---- node mini-batches (Section 4.2, "Rethinking Mini-batch Training") -------------------------------------
+ * A sample is the sequence of computational graphs of a set of selected nodes.  With F_0 = the batch and
+ * F_k = F_{k-1} plus the sources of every edge, of any snapshot, whose target is in F_{k-1}, the sub-sequence of a
+ * batch keeps the nodes F_hops and, of every snapshot, the edges whose target is in F_{hops-1}; its nodes are
+ * numbered batch first (in the order given), then the others by ascending id.  A stacked model of `hops`
+ * aggregation layers evaluated on the sub-sequence gives on the batch rows exactly what it gives on the whole
+ * graph (one hop more under the symmetric normalisation, whose source-side scale is a degree as well).
+ *
+ * The sub-sequence goes into a second context, which is then used like any other: sliding its windows over the
+ * whole sequence before the next batch is extracted (seq-first) lets its aggregate cache serve every window and
+ * hold the rows of this batch only.
+ *
+ * reinc_batch_plan: nodes = HOST array of n_batch distinct ids; hops <= 0 selects num_gcn_layers (+ 1 for
+ *   REINC_AGG_SYM).  Every snapshot's edges must be loaded.  Computes the node set on the device and keeps it in
+ *   `ctx` (3 ints per node of arena space, allocated by the first plan) until the next plan; returns the number of
+ *   nodes of the sub-sequence and |F_{hops-1}|.  REINC_E_ARG for ids out of range or listed twice.  SYNC.
+ * reinc_batch_node_list: old id of every node of the planned sub-sequence, to a HOST array of n_nodes int32.  SYNC.
+ * reinc_batch_load: fills `child` -- created by the caller with num_nodes = the planned count, the same
+ *   num_snapshots, dims[0], feat_dtype and device, no snapshots loaded -- with the extracted edges and the gathered
+ *   feature rows of every snapshot, and sets its loss rows to n_batch.  Errors are reported on `ctx`.  SYNC.
+ * reinc_set_loss_rows: the loss of the window calls becomes the mean over rows [0, rows) of h_last and target
+ *   (both stay [N, H]); the gradients are those of that loss.  rows = 0 or N: every row (the default). */
+int reinc_batch_plan(reinc_ctx *ctx, const int32_t *nodes, int64_t n_batch, int32_t hops, int64_t *n_nodes_out,
+                     int64_t *n_inner_out);
+int reinc_batch_node_list(reinc_ctx *ctx, int32_t *out);
+int reinc_batch_load(reinc_ctx *ctx, reinc_ctx *child);
+int reinc_set_loss_rows(reinc_ctx *ctx, int64_t rows);
+
 /* ---- cache budget and eviction policy (Section 3.3, "Eviction Policy"; compared with LRU / LFU in Section 5) ----
  * By default every layer-1 aggregate stays cached (REINC_POLICY_KEEP_ALL: T * N * dims[0] * 4 bytes in the end).
  * reinc_cache_configure limits what is RETAINED BETWEEN WINDOWS to budget_bytes and chooses who leaves:

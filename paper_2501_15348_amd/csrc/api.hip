@@ -115,6 +115,11 @@ int reinc_arena_free_bytes(const reinc_ctx *ctx, uint64_t *out)
 int reinc_load_edges(reinc_ctx *ctx, int32_t t, const int32_t *src, const int32_t *dst, int64_t nnz)
 {
     if (!ctx) return REINC_E_ARG;
+    return reinc::load_edges(ctx, t, src, dst, nnz, false);
+}
+
+extern "C++" int reinc::load_edges(reinc_ctx *ctx, int32_t t, const int32_t *src, const int32_t *dst, int64_t nnz, bool on_device)
+{
     REINC_TRY(check_t(ctx, t));
     if (nnz < 0 || (nnz > 0 && (!src || !dst))) return ctx->fail(REINC_E_ARG, "null edge arrays");
     Snapshot &sn = ctx->snaps[t];
@@ -143,8 +148,9 @@ int reinc_load_edges(reinc_ctx *ctx, int32_t t, const int32_t *src, const int32_
     void *scan_tmp = ctx->scratch(scan_tmp_bytes(std::max(m, n)));
     if (!d_src || !d_dst || !keys0 || !keys1 || !flag || !offs || !err || !sort_tmp || !scan_tmp) return fail_nomem("scratch");
     if (nnz > 0) {
-        REINC_HIP(ctx, hipMemcpy(d_src, src, size_t(nnz) * 4, hipMemcpyHostToDevice));
-        REINC_HIP(ctx, hipMemcpy(d_dst, dst, size_t(nnz) * 4, hipMemcpyHostToDevice));
+        const hipMemcpyKind kind = on_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice;
+        REINC_HIP(ctx, hipMemcpy(d_src, src, size_t(nnz) * 4, kind));
+        REINC_HIP(ctx, hipMemcpy(d_dst, dst, size_t(nnz) * 4, kind));
     }
     launch_fill_i32(err, 1, 0, s);
     unsigned node_bits = 1;
@@ -714,6 +720,8 @@ int reinc_reset_derived(reinc_ctx *ctx)
     ctx->local_reserved = 0;
     ctx->zero_state = nullptr;
     ctx->loss_partial = nullptr;
+    ctx->batch_level = ctx->batch_new_id = ctx->batch_nodes = nullptr;  // a mini-batch plan lived above the mark
+    ctx->batch_total = ctx->batch_size = 0;
     ctx->stats.local_bytes = 0;
     ctx->scratch_reset();
     return REINC_OK;

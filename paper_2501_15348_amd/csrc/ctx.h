@@ -228,6 +228,10 @@ struct ProfScope {
 
 namespace reinc {
 
+// ---- api.hip
+// reinc_load_edges with the raw list in host or in device memory
+int load_edges(reinc_ctx *ctx, int32_t t, const int32_t *src, const int32_t *dst, int64_t nnz, bool on_device);
+
 // ---- kernels_graph.hip
 // exclusive scan of int32 counts [n] into int64 offsets [n+1]; tmp: scratch of scan_tmp_bytes(n)
 uint64_t scan_tmp_bytes(int64_t n);

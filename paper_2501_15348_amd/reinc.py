@@ -107,6 +107,10 @@ def load_library() -> ctypes.CDLL:
         "reinc_cache_clear": [p],
         "reinc_cache_peek": [p, i32, ctypes.POINTER(p)],
         "reinc_cache_configure": [p, i32, i64, i32, i32],
+        "reinc_batch_plan": [p, p, i64, i32, p, p],
+        "reinc_batch_node_list": [p, p],
+        "reinc_batch_load": [p, p],
+        "reinc_set_loss_rows": [p, i64],
         "reinc_policy_create": [ctypes.POINTER(p), i32, i64],
         "reinc_policy_destroy": [p],
         "reinc_policy_access": [p, i64, ctypes.POINTER(i32)],
@@ -405,6 +409,43 @@ class Context:
     def cache_configure(self, policy: str, budget_bytes: int = 0, window: int = 1, stride: int = 1):
         """Limits what the layer-1 cache retains between windows; policy is one of POLICIES."""
         self._ck(self.lib.reinc_cache_configure(self.handle, POLICIES.index(policy), int(budget_bytes), window, stride))
+
+    # ---- node mini-batches
+    def set_loss_rows(self, rows: int):
+        self._ck(self.lib.reinc_set_loss_rows(self.handle, int(rows)))
+
+    def batch_plan(self, nodes, hops: int = 0):
+        """Plans the sub-sequence of a node batch; returns (nodes of the sub-sequence, inner nodes)."""
+        import numpy as np
+
+        nodes = np.ascontiguousarray(nodes, dtype=np.int32)
+        total, inner = ctypes.c_int64(), ctypes.c_int64()
+        self._ck(self.lib.reinc_batch_plan(self.handle, nodes.ctypes.data_as(ctypes.c_void_p), nodes.size, hops,
+                                           ctypes.byref(total), ctypes.byref(inner)))
+        return total.value, inner.value
+
+    def batch_node_list(self, total: int):
+        import numpy as np
+
+        out = np.empty(total, dtype=np.int32)
+        self._ck(self.lib.reinc_batch_node_list(self.handle, out.ctypes.data_as(ctypes.c_void_p)))
+        return out
+
+    def batch_context(self, nodes, arena_bytes: int, hops: int = 0, **kw) -> "Context":
+        """A new context holding the sub-sequence of `nodes` (same model configuration; keyword arguments override
+        constructor arguments such as fallback_ratio)."""
+        total, _ = self.batch_plan(nodes, hops)
+        args = dict(fallback_ratio=self.cfg.fallback_ratio, device=self.cfg.device)
+        args.update(kw)
+        agg = [k for k, v in AGG.items() if v == self.cfg.agg_kind][0]
+        child = Context(total, self.T, self.dims, self.rnn, self.hidden, agg, bool(self.cfg.self_loop), self.feat_dtype,
+                        arena_bytes=arena_bytes, **args)
+        try:
+            self._ck(self.lib.reinc_batch_load(self.handle, child.handle))
+        except Exception:
+            child.close()
+            raise
+        return child
 
     def aggregate_bytes(self) -> int:
         """Size of one cached layer-1 aggregate (the unit a budget is counted in)."""

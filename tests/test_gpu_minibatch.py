@@ -1,0 +1,161 @@
+"""GPU parity for node mini-batches (paper Section 4.2, "Rethinking Mini-batch Training"): the computational graphs
+of a node set extracted on the device (bit-exact against the set-based reference), and windows run on the
+extracted sub-sequence against the from-scratch reference of the WHOLE graph with the loss taken over the batch
+rows -- the extraction must lose nothing the batch depends on."""
+import numpy as np
+import pytest
+
+import oracle
+from oracle import minibatch
+from helpers import RTOL_FP32, assert_close, assert_gradients_close, oracle_feats, oracle_graphs
+from paper_2501_15348_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+def _dev(a):
+    import torch
+
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def _workload(mode, rnn, layers, n=3000, T=6, degree=2.5, seed=11, dist="uniform"):
+    dims = (16,) + (32,) * layers
+    return synth.Workload("mb", n, degree, T, dist, 2.1 if dist == "chunglu" else 0.0, 0.05, 0.02, "fp32", mode, True, dims, rnn,
+                          32, 4, seed)
+
+
+def _parent(wl, arena=1 << 28):
+    from paper_2501_15348_amd import reinc
+
+    seq = synth.make_sequence(wl)
+    ctx = reinc.Context.for_workload(wl, arena_bytes=arena)
+    ctx.load_sequence(seq)
+    return seq, ctx
+
+
+@pytest.mark.parametrize("mode,hops,dist", [("sum", 1, "uniform"), ("mean", 2, "uniform"), ("sym", 3, "uniform"), ("mean", 2, "chunglu")])
+def test_extraction_is_exact(mode, hops, dist):
+    wl = _workload(mode, "gru", 2, dist=dist)
+    seq, ctx = _parent(wl)
+    batch = np.random.default_rng(3).choice(wl.num_nodes, 40, replace=False).astype(np.int32)  # not sorted
+    ref_list, ref_sub, ref_inner = minibatch.extract(seq.edges, batch, hops)
+    total, inner = ctx.batch_plan(batch, hops)
+    assert (total, inner) == (len(ref_list), ref_inner)
+    assert np.array_equal(ctx.batch_node_list(total), ref_list)
+    child = ctx.batch_context(batch, 1 << 27, hops)
+    assert child.n == total
+    ref_graphs = oracle.graphs_of(ref_sub, total)
+    for t in range(wl.num_snapshots):
+        ptr, idx = child.get_snapshot_csr(t)
+        assert np.array_equal(ptr, ref_graphs[t].row_ptr) and np.array_equal(idx, ref_graphs[t].col), t
+    assert total < wl.num_nodes
+    child.close()
+    # a second plan on the same context replaces the first
+    other = np.arange(5, dtype=np.int32)
+    total2, _ = ctx.batch_plan(other, hops)
+    assert np.array_equal(ctx.batch_node_list(total2), minibatch.extract(seq.edges, other, hops)[0])
+    ctx.close()
+
+
+@pytest.mark.parametrize("mode,rnn,layers", [("sum", "gru", 1), ("mean", "lstm", 2), ("sym", "gru", 2)])
+def test_batch_windows_match_the_whole_graph_reference(mode, rnn, layers):
+    import torch
+
+    wl = _workload(mode, rnn, layers)
+    seq, ctx = _parent(wl)
+    n, T, L, H = wl.num_nodes, wl.num_snapshots, 4, wl.hidden
+    batch = np.random.default_rng(8).choice(n, 64, replace=False).astype(np.int32)
+    child = ctx.batch_context(batch, 1 << 28)  # default hop count
+    node_list = ctx.batch_node_list(child.n)
+    assert child.n < n
+    child.build_deltas(-1)
+    flat = synth.make_params(wl, bias_scale=0.2)
+    target = synth.make_target(wl)
+    params, tgt = _dev(flat), _dev(target[node_list])
+    loss = torch.zeros(1, device="cuda")
+    h_last = torch.empty((child.n, H), device="cuda")
+    grads = torch.empty_like(params)
+    graphs = oracle_graphs(seq)
+    p = synth.split_params(wl, flat.astype(np.float64))
+    names = [name for name, _ in synth.param_shapes(wl)]
+    for t0 in (0, 1, T - L):  # seq-first: the windows of one batch slide over the sequence
+        print(f"[{wl.name} {mode} {rnn}] window t0={t0}", flush=True)
+        child.forward_window(t0, L, params, tgt, loss, h_last)
+        child.backward_window(t0, L, params, tgt, grads)
+        torch.cuda.synchronize()
+        g = graphs[t0:t0 + L]
+        feats = [oracle_feats(seq, t) for t in range(t0, t0 + L)]
+        ref_loss, ref_h, saved = oracle.forward_window(g, feats, p, layers, wl.agg, wl.self_loop, wl.rnn, target, keep=True,
+                                                       loss_rows=batch)
+        assert_close(h_last.cpu().numpy()[:len(batch)], ref_h[batch], RTOL_FP32, "h_last on the batch rows")
+        assert abs(loss.item() - ref_loss) <= RTOL_FP32 * abs(ref_loss), (loss.item(), ref_loss)
+        assert_gradients_close(
+            synth.split_params(wl, grads.cpu().numpy()), saved,
+            lambda sv: oracle.backward_window(g, sv, ref_h, p, layers, wl.agg, wl.self_loop, wl.rnn, target, loss_rows=batch),
+            names, 5 * RTOL_FP32)
+    st = child.get_stats()
+    assert st["global_hits"] == 3 + 3 and st["global_misses"] == 4 + 1 + 1  # the batch's cache serves its later windows
+    child.close()
+    ctx.close()
+
+
+def test_loss_rows_on_an_ordinary_context():
+    import torch
+
+    wl = _workload("mean", "gru", 1, n=500, T=4)
+    seq, ctx = _parent(wl)
+    ctx.build_deltas(-1)
+    flat, target = synth.make_params(wl, bias_scale=0.2), synth.make_target(wl)
+    params, tgt = _dev(flat), _dev(target)
+    loss = torch.zeros(1, device="cuda")
+    grads = torch.empty_like(params)
+    graphs = oracle_graphs(seq)
+    feats = [oracle_feats(seq, t) for t in range(4)]
+    p = synth.split_params(wl, flat.astype(np.float64))
+    for rows in (123, 0):
+        ctx.set_loss_rows(rows)
+        ctx.forward_window(0, 4, params, tgt, loss)
+        ctx.backward_window(0, 4, params, tgt, grads)
+        torch.cuda.synchronize()
+        sel = np.arange(rows) if rows else None
+        ref_loss, ref_h, saved = oracle.forward_window(graphs, feats, p, 1, wl.agg, wl.self_loop, wl.rnn, target, keep=True, loss_rows=sel)
+        assert abs(loss.item() - ref_loss) <= RTOL_FP32 * abs(ref_loss)
+        assert_gradients_close(
+            synth.split_params(wl, grads.cpu().numpy()), saved,
+            lambda sv: oracle.backward_window(graphs, sv, ref_h, p, 1, wl.agg, wl.self_loop, wl.rnn, target, loss_rows=sel),
+            [name for name, _ in synth.param_shapes(wl)], 5 * RTOL_FP32)
+    ctx.close()
+
+
+def test_error_paths():
+    from paper_2501_15348_amd import reinc
+
+    wl = _workload("mean", "gru", 1, n=400, T=3)
+    seq, ctx = _parent(wl, arena=1 << 26)
+    with pytest.raises(reinc.ReincError, match="twice"):
+        ctx.batch_plan(np.array([5, 9, 5], dtype=np.int32))
+    with pytest.raises(reinc.ReincError, match="out of range"):
+        ctx.batch_plan(np.array([5, 400], dtype=np.int32))
+    with pytest.raises(reinc.ReincError, match="between 1 and"):
+        ctx.batch_plan(np.array([], dtype=np.int32))
+    with pytest.raises(reinc.ReincError, match="no node batch"):
+        ctx.batch_node_list(1)  # the failed plans left nothing behind
+    with pytest.raises(reinc.ReincError, match="loss rows"):
+        ctx.set_loss_rows(401)
+    total, _ = ctx.batch_plan(np.array([7, 3], dtype=np.int32))
+    wrong = reinc.Context(total + 1, wl.num_snapshots, wl.dims, wl.rnn, wl.hidden, wl.agg, wl.self_loop, arena_bytes=1 << 24)
+    rc = ctx.lib.reinc_batch_load(ctx.handle, wrong.handle)
+    assert rc == reinc.E_ARG and b"needs" in ctx.lib.reinc_last_error(ctx.handle)
+    wrong.close()
+    # the whole graph as a batch: every node is a batch node, the loss covers every row
+    everyone = np.random.default_rng(0).permutation(400).astype(np.int32)
+    child = ctx.batch_context(everyone, 1 << 26)
+    assert child.n == 400 and np.array_equal(ctx.batch_node_list(400), everyone)
+    child.close()
+    # a context without its snapshots cannot plan
+    empty = reinc.Context.for_workload(wl, arena_bytes=1 << 24)
+    with pytest.raises(reinc.ReincError, match="must be loaded"):
+        empty.batch_plan(np.array([1], dtype=np.int32))
+    empty.close()
+    ctx.close()
