@@ -356,7 +356,95 @@ def extras(ctx, wl, seq, infos, params, target, step, step_s):
                      "retained_peak_MB": round((T * size if policy == "keep_all" else st1["global_peak_bytes"]) / 1e6, 1)})
     ctx.cache_configure("keep_all")
     res["cache_budget"] = rows
+    res["node_minibatch"] = minibatch_rows(ctx, wl, seq, params, target, L, "bench workload")
+    # the same model on a road-network-like graph (uniform, mean degree 3, mean aggregation: the paper's forecasting
+    # data sets are sensor networks of that sparsity), where the computational graphs of a batch stay small
+    from paper_2501_15348_amd import reinc
+
+    wl2 = dataclasses.replace(wl, name="sparse", mean_degree=3.0, structure="uniform", gamma=0.0, agg="mean")
+    seq2 = synth.make_sequence(wl2)
+    ctx2 = reinc.Context.for_workload(wl2, arena_bytes=int(ctx.cfg.arena_bytes))
+    ctx2.load_sequence(seq2)
+    res["node_minibatch"] += minibatch_rows(ctx2, wl2, seq2, params, target, L, "uniform degree 3, mean")
+    ctx2.close()
     return res
+
+
+def minibatch_rows(ctx, wl, seq, params, target, L, label):
+    """Seq-first node mini-batches: for a few batch sizes, the first batches of a seeded partition of the nodes are
+    extracted into their own context and every window of the sequence is trained on each (forward, backward, SGD)
+    before the next batch is taken; node-first order is imitated by dropping the batch's aggregate cache before every
+    window.  Times are per batch."""
+    import numpy as np
+    import torch
+
+    from paper_2501_15348_amd import synth
+
+    n, T = wl.num_nodes, wl.num_snapshots
+    perm = np.random.default_rng(wl.seed + 77).permutation(n).astype(np.int32)
+    full_edges = float(sum(len(s_) for s_, _ in seq.edges))
+    rows = []
+    for parts, take in ((8, 2), (64, 3)):
+        size = n // parts
+        acc = {"extract_ms": [], "deltas_ms": [], "seq_first_epoch_ms": [], "node_first_epoch_ms": [], "nodes": [], "edges": [],
+               "cache_MB": [], "hits": [], "misses": [], "hits_node_first": []}
+        for b in range(take):
+            batch = perm[b * size:(b + 1) * size]
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            total, _ = ctx.batch_plan(batch)
+            frac = total / n
+            child_arena = int(frac * ctx.cfg.arena_bytes) + (512 << 20)
+            child = ctx.batch_context(batch, child_arena)
+            torch.cuda.synchronize()
+            acc["extract_ms"].append((time.perf_counter() - t0) * 1e3)
+            t0 = time.perf_counter()
+            child.build_deltas(-1)
+            torch.cuda.synchronize()
+            acc["deltas_ms"].append((time.perf_counter() - t0) * 1e3)
+            node_list = torch.from_numpy(ctx.batch_node_list(total).astype(np.int64)).cuda()
+            tgt = target[node_list].contiguous()
+            p = params.clone()
+            grads = torch.empty_like(p)
+            loss = torch.zeros(1, device="cuda")
+
+            def epoch(node_first):
+                for t0_ in range(T - L + 1):
+                    if node_first:
+                        child.cache_clear()
+                    child.forward_window(t0_, L, p, tgt, loss)
+                    child.backward_window(t0_, L, p, tgt, grads)
+                    child.sgd_step(p, grads, 1e-2)
+
+            for node_first in (False, True):
+                child.cache_clear()
+                st0 = child.get_stats()
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                epoch(node_first)
+                torch.cuda.synchronize()
+                ms = (time.perf_counter() - t0) * 1e3
+                st1 = child.get_stats()
+                if node_first:
+                    acc["node_first_epoch_ms"].append(ms)
+                    acc["hits_node_first"].append(st1["global_hits"] - st0["global_hits"])
+                else:
+                    acc["seq_first_epoch_ms"].append(ms)
+                    acc["hits"].append(st1["global_hits"] - st0["global_hits"])
+                    acc["misses"].append(st1["global_misses"] - st0["global_misses"])
+            acc["nodes"].append(total)
+            acc["edges"].append(sum(child.get_snapshot_csr(t)[1].size for t in range(T)) / full_edges)
+            acc["cache_MB"].append(T * child.aggregate_bytes() / 1e6)
+            child.close()
+            del child
+        mean = lambda k: float(np.mean(acc[k]))
+        rows.append({"graph": label, "batch_nodes": size, "batches_timed": take, "batches_per_pass": parts,
+                     "sub_sequence_nodes": round(mean("nodes")), "edges_kept_frac": round(mean("edges"), 4),
+                     "extract_ms": round(mean("extract_ms"), 3), "build_deltas_ms": round(mean("deltas_ms"), 3),
+                     "seq_first_epoch_ms": round(mean("seq_first_epoch_ms"), 3), "node_first_epoch_ms": round(mean("node_first_epoch_ms"), 3),
+                     "layer1_cache_MB": round(mean("cache_MB"), 1), "hits": round(mean("hits")), "misses": round(mean("misses")),
+                     "hits_node_first": round(mean("hits_node_first"))})
+    return rows
 
 
 def reinc_kinds():

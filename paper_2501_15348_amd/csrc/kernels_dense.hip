@@ -1206,10 +1206,10 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
 {
     // wave w finishes accumulator tile w of the 2x2: the other waves park their share of it here (two tiles at
     // a time, to keep the block's LDS at 25 KB)
-    // (wide mode with shared splitting uses the same storage for its staged planes: 2 buffers x 4 pieces x 3 planes x
-    // 64 columns x 2 half-waves of 16-byte records = 48 KB)
+    // (wide mode with shared splitting uses the same storage for its staged planes: 3 buffers x 4 pieces x 3 planes x
+    // 64 columns x 2 half-waves of 16-byte records = 72 KB; two blocks per compute unit still fit)
     constexpr int kRedFloats = 2 * 3 * 32 * 33, kBredFloats = 4 * 64;
-    constexpr int kStageRecords = 2 * 4 * 3 * 64 * 2;
+    constexpr int kStageRecords = 3 * 4 * 3 * 64 * 2;
     constexpr size_t kSharedBytes = (SPLIT && WIDE) ? size_t(kStageRecords) * 16 : size_t(kRedFloats + kBredFloats) * 4;
     __shared__ __align__(16) unsigned char smem[kSharedBytes];
     float(*red)[3][32 * 33] = reinterpret_cast<float(*)[3][32 * 33]>(smem);
@@ -1253,13 +1253,17 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
     // two pieces of A; waves 0, 2: the piece of G under their own slab, so the column sums for the bias gradient
     // come out in the waves that write them), parks its three planes in LDS, and after a barrier every wave takes
     // the fragments of the A piece and the G piece of its slab from there: half the loads and half the splitting per
-    // wave, and the waves cannot drift apart.  Two LDS buffers, one barrier per trip: a wave that writes buffer b
-    // again has passed the barrier of the trip between, which every wave reaches only after its reads of b.
+    // wave, and the waves cannot drift apart.  One barrier per trip and a ring of three LDS buffers: a wave that
+    // writes buffer b again has passed the barriers of the two trips between, which every wave reaches only after
+    // its reads of b.  The loads run two trips ahead of the arithmetic (three register sets): with one trip in
+    // flight the bytes outstanding per compute unit, not the arithmetic, bounded the rate.
     bool shared_split = false;
     if constexpr (SPLIT && WIDE) {
         shared_split = wx == 2 && (slab % slabs_x + 1) * 128 <= g.K && (slab / slabs_x + 1) * 128 <= g.M;
         if (shared_split) {
-            u32x4 *stage = reinterpret_cast<u32x4 *>(smem);  // [buffer][piece][plane][column][half]
+            // [buffer][piece][plane][32-column half][lane]: a lane's record sits at its lane index, so that the lanes
+            // of a 128-bit LDS access cover consecutive 16-byte records (records two apart cost every access twice)
+            u32x4 *stage = reinterpret_cast<u32x4 *>(smem);
             const bool a_piece = (w & 1) != 0;
             const int piece = w >> 1, slot = a_piece ? piece : 2 + piece;
             const int pcol0 = (a_piece ? (slab % slabs_x) : (slab / slabs_x)) * 128 + 64 * piece;
@@ -1298,21 +1302,21 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
                 u32x4 p0[3], p1[3];
                 split8(t[0], p0[0], p0[1], p0[2]);
                 split8(t[1], p1[0], p1[1], p1[2]);
-                u32x4 *mine = stage + ((buf * 4 + slot) * 3) * 128;  // this wave's piece: [plane][column][half]
+                u32x4 *mine = stage + ((buf * 4 + slot) * 3) * 128;  // this wave's piece
 #pragma unroll
                 for (int pl = 0; pl < 3; ++pl) {
-                    mine[pl * 128 + i * 2 + kk] = p0[pl];
-                    mine[pl * 128 + (32 + i) * 2 + kk] = p1[pl];
+                    mine[pl * 128 + lane] = p0[pl];
+                    mine[pl * 128 + 64 + lane] = p1[pl];
                 }
                 __syncthreads();
                 const u32x4 *pa = stage + ((buf * 4 + sx) * 3) * 128, *pg = stage + ((buf * 4 + 2 + sy) * 3) * 128;
                 u32x4 A0[3], A1[3], G0[3], G1[3];
 #pragma unroll
                 for (int pl = 0; pl < 3; ++pl) {
-                    A0[pl] = pa[pl * 128 + i * 2 + kk];
-                    A1[pl] = pa[pl * 128 + (32 + i) * 2 + kk];
-                    G0[pl] = pg[pl * 128 + i * 2 + kk];
-                    G1[pl] = pg[pl * 128 + (32 + i) * 2 + kk];
+                    A0[pl] = pa[pl * 128 + lane];
+                    A1[pl] = pa[pl * 128 + 64 + lane];
+                    G0[pl] = pg[pl * 128 + lane];
+                    G1[pl] = pg[pl * 128 + 64 + lane];
                 }
                 constexpr int order[6][2] = {{2, 0}, {1, 1}, {0, 2}, {1, 0}, {0, 1}, {0, 0}};
 #pragma unroll
@@ -1325,24 +1329,33 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
                 }
             };
             const int trips = int((r_end - r_begin) / 16);
-            float ta[3][kRU], tb[3][kRU];
+            float ta[3][kRU], tb[3][kRU], tc[3][kRU];
             int t = 0;
             if (trips > 0) load(ta);
-            for (; t + 2 < trips; t += 2) {
-                load(tb);
+            if (trips > 1) load(tb);
+            // invariant at the top: trips t and t+1 are loaded (ta, tb), at least three more trips follow trip t-1
+            for (; t + 5 <= trips; t += 3) {
+                load(tc);
                 __builtin_amdgcn_sched_barrier(0);
                 process(ta, 0);
                 load(ta);
                 __builtin_amdgcn_sched_barrier(0);
                 process(tb, 1);
-            }
-            if (t + 1 < trips) {
                 load(tb);
                 __builtin_amdgcn_sched_barrier(0);
+                process(tc, 2);
+            }
+            // two to four trips are left (or all of fewer than two): ta and tb are loaded, the others follow
+            if (t < trips) {
+                const int left = trips - t;
+                if (left > 2) load(tc);
+                __builtin_amdgcn_sched_barrier(0);
                 process(ta, 0);
-                process(tb, 1);
-            } else if (t < trips) {
-                process(ta, 0);
+                if (left > 3) load(ta);
+                __builtin_amdgcn_sched_barrier(0);
+                if (left > 1) process(tb, 1);
+                if (left > 2) process(tc, 2);
+                if (left > 3) process(ta, 0);
             }
             base += int64_t(trips) * 16;
         }
