@@ -1259,30 +1259,65 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
     // flight the bytes outstanding per compute unit, not the arithmetic, bounded the rate.
     bool shared_split = false;
     if constexpr (SPLIT && WIDE) {
-        shared_split = wx == 2 && (slab % slabs_x + 1) * 128 <= g.K && (slab / slabs_x + 1) * 128 <= g.M;
+        // (chunks of fewer than five trips take the per-wave path below: the pipeline here starts with two trips
+        // in flight and its loop runs at least once)
+        shared_split = wx == 2 && (slab % slabs_x + 1) * 128 <= g.K && (slab / slabs_x + 1) * 128 <= g.M && r_end - r_begin >= 5 * 16;
         if (shared_split) {
             // [buffer][piece][plane][32-column half][lane]: a lane's record sits at its lane index, so that the lanes
             // of a 128-bit LDS access cover consecutive 16-byte records (records two apart cost every access twice)
             u32x4 *stage = reinterpret_cast<u32x4 *>(smem);
-            const bool a_piece = (w & 1) != 0;
-            const int piece = w >> 1, slot = a_piece ? piece : 2 + piece;
+            const int wu = __builtin_amdgcn_readfirstlane(w);  // (known to be the same in every lane: scalar addresses)
+            const bool a_piece = (wu & 1) != 0;
+            const int piece = wu >> 1, slot = a_piece ? piece : 2 + piece;
             const int pcol0 = (a_piece ? (slab % slabs_x) : (slab / slabs_x)) * 128 + 64 * piece;
             const int ld = a_piece ? g.lda : g.ldg;
+            // The loads are written as instructions with the waits placed by hand.  The compiler's own wait
+            // insertion loses count of loads that cross the loop's back edge: it made the first trip of every
+            // iteration wait for all loads but the newest group, which left one trip in flight instead of two.
+            // Addresses: a wave-uniform base (scalar registers, advanced once per trip) plus one fixed 32-bit
+            // lane offset per row pair; the second 32 columns ride on the instruction's offset field.
             const float *pp = (a_piece ? g.A : g.G) + base * ld + pcol0;
-            const float *sp = (HAS_RS && a_piece) ? g.row_scale + base : nullptr;
-            const unsigned poff = unsigned(kk) * unsigned(ld) + i;
-            // a trip's piece: [0] [1] = its two 32-column halves, [2] = row scale (pieces of A)
+            const float *sp = HAS_RS ? g.row_scale + base : nullptr;  // (every wave loads the scales: equal load counts)
+            unsigned voff[kRU], soff[kRU];
+#pragma unroll
+            for (int u = 0; u < kRU; ++u) {
+                voff[u] = (unsigned(2 * u + kk) * unsigned(ld) + unsigned(i)) * 4u;
+                soff[u] = unsigned(2 * u + kk) * 4u;
+            }
+            // a trip's piece: [0] [1] = its two 32-column halves, [2] = row scale
+            constexpr int kGroup = HAS_RS ? 3 * kRU : 2 * kRU;  // loads per trip and wave
+            static_assert(2 * kGroup <= 63, "the counter of outstanding loads holds 63");
             auto load = [&](float(&t)[3][kRU]) __attribute__((always_inline)) {
 #pragma unroll
                 for (int u = 0; u < kRU; ++u) {
-                    const float *pu = pp + int64_t(2 * u) * ld;
-                    t[0][u] = pu[poff];
-                    t[1][u] = pu[poff + 32];
-                    t[2][u] = (HAS_RS && a_piece) ? sp[2 * u + kk] : 1.0f;
+                    asm volatile("global_load_dword %0, %1, %2" : "=&v"(t[0][u]) : "v"(voff[u]), "s"(pp) : "memory");
+                    asm volatile("global_load_dword %0, %1, %2 offset:128" : "=&v"(t[1][u]) : "v"(voff[u]), "s"(pp) : "memory");
+                    if (HAS_RS)
+                        asm volatile("global_load_dword %0, %1, %2" : "=&v"(t[2][u]) : "v"(soff[u]), "s"(sp) : "memory");
+                    else
+                        t[2][u] = 1.0f;
                 }
                 pp += int64_t(16) * ld;
-                if (HAS_RS && a_piece) sp += 16;
+                if (HAS_RS) sp += 16;
             };
+            // waits until at most NEWER * kGroup loads are outstanding: the group in `t` has arrived when NEWER
+            // groups were issued after it.  The values pass through the statements, so nothing that uses them can
+            // be placed ahead of the wait.  Between a load and its wait the compiler takes the destination registers
+            // for ready values: the control flow below is shaped so that it has no reason to copy them there (loads
+            // and waits are never separated by a branch that is taken only sometimes, except the loop's back edge,
+            // where the three register sets keep their roles).
+            auto arrive8 = [](float(&r)[kRU]) __attribute__((always_inline)) {
+                asm volatile("" : "+v"(r[0]), "+v"(r[1]), "+v"(r[2]), "+v"(r[3]), "+v"(r[4]), "+v"(r[5]), "+v"(r[6]), "+v"(r[7])::"memory");
+            };
+            auto wait_for = [&](float(&t)[3][kRU], auto newer) __attribute__((always_inline)) {
+                constexpr int kLeft = decltype(newer)::value * kGroup;
+                asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kLeft) : "memory");
+                arrive8(t[0]);
+                arrive8(t[1]);
+                if (HAS_RS) arrive8(t[2]);
+            };
+            using Newer0 = std::integral_constant<int, 0>;
+            using Newer2 = std::integral_constant<int, 2>;
             const int sx = w % 2, sy = w / 2;
             auto process = [&](float(&t)[3][kRU], int buf) __attribute__((always_inline)) {
                 if (HAS_RS && a_piece) {
@@ -1328,34 +1363,39 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
                     acc[1][1] = mfma_bf16(A1[p], G1[q], acc[1][1]);
                 }
             };
-            const int trips = int((r_end - r_begin) / 16);
+            const int trips = int((r_end - r_begin) / 16);  // at least 5
             float ta[3][kRU], tb[3][kRU], tc[3][kRU];
             int t = 0;
-            if (trips > 0) load(ta);
-            if (trips > 1) load(tb);
-            // invariant at the top: trips t and t+1 are loaded (ta, tb), at least three more trips follow trip t-1
-            for (; t + 5 <= trips; t += 3) {
+            load(ta);
+            load(tb);
+            // invariant at the top: trips t and t+1 are loaded (ta, tb) and at least three more trips follow them
+            do {
                 load(tc);
-                __builtin_amdgcn_sched_barrier(0);
+                wait_for(ta, Newer2());
                 process(ta, 0);
                 load(ta);
-                __builtin_amdgcn_sched_barrier(0);
+                wait_for(tb, Newer2());
                 process(tb, 1);
                 load(tb);
-                __builtin_amdgcn_sched_barrier(0);
+                wait_for(tc, Newer2());
+                process(tc, 2);
+                t += 3;
+            } while (t + 5 <= trips);
+            // two to four trips are left, the first two of them loaded: they wait for everything outstanding
+            const int left = trips - t;
+            wait_for(ta, Newer0());
+            wait_for(tb, Newer0());
+            process(ta, 0);
+            process(tb, 1);
+            if (left > 2) {
+                load(tc);
+                wait_for(tc, Newer0());
                 process(tc, 2);
             }
-            // two to four trips are left (or all of fewer than two): ta and tb are loaded, the others follow
-            if (t < trips) {
-                const int left = trips - t;
-                if (left > 2) load(tc);
-                __builtin_amdgcn_sched_barrier(0);
+            if (left > 3) {
+                load(ta);
+                wait_for(ta, Newer0());
                 process(ta, 0);
-                if (left > 3) load(ta);
-                __builtin_amdgcn_sched_barrier(0);
-                if (left > 1) process(tb, 1);
-                if (left > 2) process(tc, 2);
-                if (left > 3) process(ta, 0);
             }
             base += int64_t(trips) * 16;
         }
