@@ -100,6 +100,41 @@ def test_batch_windows_match_the_whole_graph_reference(mode, rnn, layers):
     ctx.close()
 
 
+def test_bf16_features_and_a_cache_budget_in_the_batch_context():
+    """bfloat16 feature rows are gathered as bit patterns; the batch context takes a cache budget like any other."""
+    import dataclasses
+
+    import torch
+
+    from helpers import RTOL_BF16
+
+    wl = dataclasses.replace(_workload("mean", "gru", 2), feat_dtype="bf16")
+    seq, ctx = _parent(wl)
+    n, T, L, H = wl.num_nodes, wl.num_snapshots, 4, wl.hidden
+    batch = np.random.default_rng(2).choice(n, 48, replace=False).astype(np.int32)
+    child = ctx.batch_context(batch, 1 << 28)
+    node_list = ctx.batch_node_list(child.n)
+    child.build_deltas(-1)
+    child.cache_configure("score", 2 * child.aggregate_bytes(), window=L, stride=1)
+    flat, target = synth.make_params(wl, bias_scale=0.2), synth.make_target(wl)
+    params, tgt = _dev(flat), _dev(target[node_list])
+    loss = torch.zeros(1, device="cuda")
+    h_last = torch.empty((child.n, H), device="cuda")
+    graphs = oracle_graphs(seq)
+    p = synth.split_params(wl, flat.astype(np.float64))
+    for t0 in range(T - L + 1):
+        child.forward_window(t0, L, params, tgt, loss, h_last)
+        torch.cuda.synchronize()
+        feats = [oracle_feats(seq, t) for t in range(t0, t0 + L)]
+        ref_loss, ref_h, _ = oracle.forward_window(graphs[t0:t0 + L], feats, p, 2, wl.agg, wl.self_loop, wl.rnn, target, loss_rows=batch)
+        assert_close(h_last.cpu().numpy()[:len(batch)], ref_h[batch], RTOL_BF16, f"h_last on the batch rows, window {t0}")
+        assert abs(loss.item() - ref_loss) <= RTOL_BF16 * abs(ref_loss)
+    st = child.get_stats()
+    assert 0 < st["global_hits"] <= 2 * (T - L) and st["global_peak_bytes"] <= 2 * child.aggregate_bytes()
+    child.close()
+    ctx.close()
+
+
 def test_loss_rows_on_an_ordinary_context():
     import torch
 
