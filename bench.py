@@ -356,6 +356,11 @@ def extras(ctx, wl, seq, infos, params, target, step, step_s):
                      "retained_peak_MB": round((T * size if policy == "keep_all" else st1["global_peak_bytes"]) / 1e6, 1)})
     ctx.cache_configure("keep_all")
     res["cache_budget"] = rows
+    # (both parts need a second context of up to the size of the first: skipped where the card has no room for it)
+    free_bytes, _ = torch.cuda.mem_get_info()
+    if free_bytes < 2.2 * int(ctx.cfg.arena_bytes) + (2 << 30):
+        res["node_minibatch"] = "skipped: no room for a second context of this workload's size"
+        return res
     res["node_minibatch"] = minibatch_rows(ctx, wl, seq, params, target, L, "bench workload")
     # the same model on a road-network-like graph (uniform, mean degree 3, mean aggregation: the paper's forecasting
     # data sets are sensor networks of that sparsity), where the computational graphs of a batch stay small
