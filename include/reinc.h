@@ -278,9 +278,12 @@ int reinc_cache_peek(reinc_ctx *ctx, int32_t t, const float **S_out);
  * reinc_batch_node_list: old id of every node of the planned sub-sequence, to a HOST array of n_nodes int32.  SYNC.
  * reinc_batch_load: fills `child` -- created by the caller with num_nodes = the planned count, the same
  *   num_snapshots, dims[0], feat_dtype and device, no snapshots loaded -- with the extracted edges and the gathered
- *   feature rows of every snapshot, and sets its loss rows to n_batch.  Errors are reported on `ctx`.  SYNC.
+ *   feature rows of every snapshot, and sets its loss rows to n_batch.  Errors are reported on `ctx`; after a
+ *   failure `child` may hold some of the snapshots and is good for reinc_destroy only.  Both contexts stay
+ *   independent afterwards (the child holds copies).  SYNC.
  * reinc_set_loss_rows: the loss of the window calls becomes the mean over rows [0, rows) of h_last and target
- *   (both stay [N, H]); the gradients are those of that loss.  rows = 0 or N: every row (the default). */
+ *   (both stay [N, H]); the gradients are those of that loss.  rows = 0 or N: every row (the default).  Takes
+ *   effect with the next call; set it before the forward call of a window, not between forward and backward. */
 int reinc_batch_plan(reinc_ctx *ctx, const int32_t *nodes, int64_t n_batch, int32_t hops, int64_t *n_nodes_out,
                      int64_t *n_inner_out);
 int reinc_batch_node_list(reinc_ctx *ctx, int32_t *out);

@@ -186,7 +186,7 @@ int reinc_batch_load(reinc_ctx *ctx, reinc_ctx *child)
         if (sn.edges_loaded || sn.feats_loaded) return ctx->fail(REINC_E_STATE, "the batch context already holds snapshots");
     REINC_HIP(ctx, hipSetDevice(a.device));
     hipStream_t s = nullptr;
-    const int64_t n = ctx->N(), nu = ctx->batch_total;
+    const int64_t nu = ctx->batch_total;
     const int32_t row_bytes = int32_t(a.dims[0] * ctx->elem_bytes());
     if (row_bytes % 16 != 0) return ctx->fail(REINC_E_UNSUPPORTED, "feature rows of %d bytes", row_bytes);
     int64_t max_e = 1;
@@ -201,7 +201,6 @@ int reinc_batch_load(reinc_ctx *ctx, reinc_ctx *child)
         ctx->scratch_reset();
         return ctx->fail(REINC_E_NOMEM, "arena exhausted while extracting a node batch");
     }
-    (void)n;
     int rc = REINC_OK;
     for (int32_t t = 0; t < a.num_snapshots && rc == REINC_OK; ++t) {
         const Snapshot &sn = ctx->snaps[t];
