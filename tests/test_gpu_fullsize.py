@@ -72,6 +72,28 @@ def test_bench_workload_c2_full():
     got = synth.split_params(wl, grads.cpu().numpy())
     for name, _ in synth.param_shapes(wl):
         assert_close(got[name], ref_g[name], 5 * RTOL_FP32, f"grad {name}")
+    # a node mini-batch extracted at this size (Section 4.2): the same window on the batch's computational graphs
+    # against the whole-graph reference with the loss over the batch rows
+    batch = np.random.default_rng(4).choice(wl.num_nodes, 2000, replace=False).astype(np.int32)
+    print(f"[{wl.name}] node mini-batch of {batch.size}", flush=True)
+    child = ctx.batch_context(batch, 2 << 30)
+    node_list = ctx.batch_node_list(child.n)
+    rest = node_list[batch.size:]
+    assert np.array_equal(node_list[:batch.size], batch) and np.all(np.diff(rest) > 0)
+    assert np.intersect1d(rest, batch).size == 0 and child.n <= wl.num_nodes
+    child.build_deltas(-1)
+    tgt_b = torch.from_numpy(target[node_list]).cuda()
+    hb = torch.empty((child.n, wl.hidden), device="cuda")
+    child.forward_window(1, 3, params, tgt_b, loss, hb)
+    child.backward_window(1, 3, params, tgt_b, grads)
+    assert_close(hb.cpu().numpy()[:batch.size], ref_h[batch], RTOL_FP32, "mini-batch h_last")
+    ref_loss_b = float(np.mean((ref_h[batch] - target[batch].astype(np.float64)) ** 2))
+    assert abs(loss.item() - ref_loss_b) <= RTOL_FP32 * abs(ref_loss_b)
+    ref_gb = oracle.backward_window(graphs[1:4], saved, ref_h, p, 2, wl.agg, wl.self_loop, wl.rnn, target, loss_rows=batch)
+    got = synth.split_params(wl, grads.cpu().numpy())
+    for name, _ in synth.param_shapes(wl):
+        assert_close(got[name], ref_gb[name], 5 * RTOL_FP32, f"mini-batch grad {name}")
+    child.close()
     ctx.close()
 
 
