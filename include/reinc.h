@@ -282,8 +282,10 @@ int reinc_cache_peek(reinc_ctx *ctx, int32_t t, const float **S_out);
  *   failure `child` may hold some of the snapshots and is good for reinc_destroy only.  Both contexts stay
  *   independent afterwards (the child holds copies).  SYNC.
  * reinc_set_loss_rows: the loss of the window calls becomes the mean over rows [0, rows) of h_last and target
- *   (both stay [N, H]); the gradients are those of that loss.  rows = 0 or N: every row (the default).  Takes
- *   effect with the next call; set it before the forward call of a window, not between forward and backward. */
+ *   (both stay [N, H]); the gradients are those of that loss.  The stacked model then computes its last GCN layer
+ *   and the recurrent cell on those rows only (nothing else depends on the others), and reinc_forward_window writes
+ *   rows [0, rows) of h_last only.  rows = 0 or N: every row (the default).  A backward call needs a forward call
+ *   made with the same rows (REINC_E_STATE otherwise). */
 int reinc_batch_plan(reinc_ctx *ctx, const int32_t *nodes, int64_t n_batch, int32_t hops, int64_t *n_nodes_out,
                      int64_t *n_inner_out);
 int reinc_batch_node_list(reinc_ctx *ctx, int32_t *out);

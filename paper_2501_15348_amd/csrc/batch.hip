@@ -97,6 +97,7 @@ int reinc_set_loss_rows(reinc_ctx *ctx, int64_t rows)
     if (!ctx) return REINC_E_ARG;
     if (rows < 0 || rows > ctx->N()) return ctx->fail(REINC_E_ARG, "loss rows %lld outside [0, %lld]", (long long)rows, (long long)ctx->N());
     ctx->loss_rows = rows == ctx->N() ? 0 : rows;
+    ctx->local_valid = false;  // a backward call needs a forward call with these rows first
     return REINC_OK;
 }
 
@@ -239,6 +240,7 @@ int reinc_batch_load(reinc_ctx *ctx, reinc_ctx *child)
     ctx->scratch_reset();
     if (rc != REINC_OK) return rc;
     child->loss_rows = ctx->batch_size == nu ? 0 : ctx->batch_size;
+    child->local_valid = false;
     return REINC_OK;
 }
 

@@ -78,6 +78,7 @@ struct AggItem {
     float *out;
     const int32_t *long_rows;
     int32_t n_long;
+    int64_t row_limit = 0;  // > 0: listed long rows from this row on are skipped (their output rows do not exist)
 };
 struct AggBatch {
     int count = 0;
@@ -125,6 +126,7 @@ struct reinc_ctx {
     std::vector<reinc::LocalStep> local;
     uint64_t local_reserved = 0;  // bytes at the top of the arena held by the local cache
     bool local_valid = false;
+    int64_t local_top = -1;  // row count the top quantities of the local cache are placed for (see place_top)
     int32_t local_t0 = -1, local_L = 0;
     int local_kind = 0;  // which model carved the local cache: 0 = stacked (GCN layers, then the cell), 1 = integrated
     float *zero_state = nullptr;  // [N, H] zeros: the recurrent state before the first timestep of a window
@@ -133,6 +135,9 @@ struct reinc_ctx {
     float *loss_partial = nullptr;
     int64_t loss_rows = 0;  // rows [0, loss_rows) enter the loss (a node mini-batch, numbered first); 0 = every row
     int64_t counted_rows() const { return loss_rows > 0 ? loss_rows : cfg.num_nodes; }
+    // The stacked model computes its last GCN layer and the recurrent cell on the loss rows only (nothing else reads
+    // them: the layers below need every row, because the batch's neighbours feed the aggregation of the last layer).
+    int64_t top_rows() const { return counted_rows(); }
     // node mini-batch plan made on this context (reinc_batch_plan): hop level and new id per node, the node list
     int32_t *batch_level = nullptr, *batch_new_id = nullptr, *batch_nodes = nullptr;
     int64_t batch_size = 0, batch_total = 0;  // batch nodes, nodes of the sub-sequence (0: no plan)
@@ -303,8 +308,10 @@ bool agg_width_supported(int32_t d, int bf16);
 void launch_aggregate_batch(const AggBatch &batch, int bf16, int32_t d, int64_t n, int self_loop, hipStream_t s,
                             hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr);
 void launch_aggregate_long_batch(const AggBatch &batch, int bf16, int32_t d, int self_loop, hipStream_t s);
-// both, with the main kernel timed as REINC_K_AGG_FULL
-void aggregate_full_batch(reinc_ctx *ctx, const AggBatch &batch, int bf16, int32_t d, int self_loop, hipStream_t s);
+// both, with the main kernel timed as REINC_K_AGG_FULL; n_rows >= 0: only rows [0, n_rows) of the short-row kernel
+// (listed long rows beyond it are still computed)
+void aggregate_full_batch(reinc_ctx *ctx, const AggBatch &batch, int bf16, int32_t d, int self_loop, hipStream_t s,
+                          int64_t n_rows = -1);
 void aggregate_full(reinc_ctx *ctx, const int64_t *ptr, const int32_t *idx, const int32_t *long_rows, int32_t n_long,
                     const void *X, int bf16, int32_t d, int self_loop, const float *in_scale, const float *out_scale,
                     const float *mask, float *out, hipStream_t s);

@@ -258,6 +258,7 @@ aggregate_long_rows(AggBatch batch, int self_loop)
     float *__restrict__ out = it.out;
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int64_t v = it.long_rows[blockIdx.x];
+    if (it.row_limit > 0 && v >= it.row_limit) return;  // (the same for the whole block)
     const int64_t beg = ptr[v], end = ptr[v + 1];
     float acc[VEC];
 #pragma unroll
@@ -1011,12 +1012,12 @@ void launch_aggregate_long_batch(const AggBatch &batch, int bf16, int32_t d, int
         aggregate_long_dispatch<false>(lpr, batch, max_long, self_loop, s);
 }
 
-void aggregate_full_batch(reinc_ctx *ctx, const AggBatch &batch, int bf16, int32_t d, int self_loop, hipStream_t s)
+void aggregate_full_batch(reinc_ctx *ctx, const AggBatch &batch, int bf16, int32_t d, int self_loop, hipStream_t s, int64_t n_rows)
 {
     {
         // the timing events ride on the launch itself, so they carry the kernel's own begin and end
         ProfScope prof(ctx, REINC_K_AGG_FULL, s, true);
-        launch_aggregate_batch(batch, bf16, d, ctx->cfg.num_nodes, self_loop, s, prof.start(), prof.stop());
+        launch_aggregate_batch(batch, bf16, d, n_rows >= 0 ? n_rows : ctx->cfg.num_nodes, self_loop, s, prof.start(), prof.stop());
     }
     launch_aggregate_long_batch(batch, bf16, d, self_loop, s);
 }

@@ -140,9 +140,33 @@ int ensure_local(reinc_ctx *ctx, int32_t L, hipStream_t s)
     ctx->local_L = L;
     ctx->local_kind = 0;
     ctx->local_valid = false;
+    ctx->local_top = int64_t(n);
     ctx->stats.local_bytes = int64_t(need);
     launch_fill_f32(ctx->zero_state, int64_t(n) * c.rnn_hidden, 0.0f, s);
     return REINC_OK;
+}
+
+// With loss rows set (a node mini-batch, numbered first) the last GCN layer and the recurrent cell are computed on
+// those `nt` rows only.  Their per-timestep slices are then placed nt rows apart inside the same allocations, so that
+// consecutive timesteps stay adjacent rows of one tall matrix.  nt = N gives the layout ensure_local made.
+void place_top(reinc_ctx *ctx, int64_t nt, hipStream_t s)
+{
+    const reinc_config &c = ctx->cfg;
+    const int Lg = c.num_gcn_layers;
+    const uint64_t H = uint64_t(c.rnn_hidden), rows = uint64_t(nt);
+    float *bH = ctx->local[0].H[Lg], *bS = Lg >= 2 ? ctx->local[0].S[Lg] : nullptr, *bc = ctx->local[0].c, *bsv = ctx->local[0].saved;
+    for (size_t i = 0; i < ctx->local.size(); ++i) {
+        reinc::LocalStep &st = ctx->local[i];
+        st.H[Lg] = bH + i * slice_floats(rows, c.dims[Lg]);
+        if (bS) st.S[Lg] = bS + i * slice_floats(rows, c.dims[Lg - 1]);
+        st.h = ctx->zero_state + (i + 1) * slice_floats(rows, H);
+        if (bc) st.c = bc + i * slice_floats(rows, H);
+        st.saved = bsv + i * slice_floats(rows, 4 * H);
+    }
+    if (ctx->local_top != nt) {  // another placement wrote states where the zero state of this one lies
+        launch_fill_f32(ctx->zero_state, nt * c.rnn_hidden, 0.0f, s);
+        ctx->local_top = nt;
+    }
 }
 
 // Local cache of the integrated model: per timestep the aggregated hidden state Agg(h_{t-1}) (kept in LocalStep::S[1];
@@ -411,6 +435,10 @@ int reinc_forward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *par
     const int Lg = c.num_gcn_layers, H = c.rnn_hidden;
     const int lstm = c.rnn_kind == REINC_RNN_LSTM;
     const float *nof = nullptr;
+    // With loss rows set (a node mini-batch, numbered first) the last GCN layer and the recurrent cell are computed
+    // on those rows only (see place_top).
+    const int64_t nt = ctx->top_rows();
+    place_top(ctx, nt, s);
     // Layer by layer over batches of timesteps: the dense steps see all timesteps of a batch as one tall matrix
     // (one launch instead of one per timestep), the aggregation of a layer takes the batch's snapshots in one
     // launch; only the layer-1 sums (a chain over snapshots) and the recurrent cell (a chain over time) go
@@ -432,18 +460,22 @@ int reinc_forward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *par
                     LocalStep &st = ctx->local[i];
                     batch.item[i - lo] = AggItem{sn.row_ptr, sn.col, st.H[l - 1], sn.p, nullptr, nullptr, nullptr, st.S[l], sn.long_rows,
                                                  sn.n_long_rows};
+                    if (l == Lg && nt < n) batch.item[i - lo].row_limit = nt;  // S of the last layer has nt rows per timestep
                 }
-                aggregate_full_batch(ctx, batch, 0, c.dims[l - 1], c.self_loop, s);
+                aggregate_full_batch(ctx, batch, 0, c.dims[l - 1], c.self_loop, s, l == Lg ? nt : n);
             }
             for (int32_t i = lo; i <= hi; ++i) {
                 Sp[i] = l == 1 ? s1[i] : ctx->local[i].S[l];
                 Hout[i] = ctx->local[i].H[l];
             }
             const bool has_q = q[lo] != nullptr;
-            REINC_TRY(for_runs(lo, hi, n, {Strip{Sp.data(), c.dims[l - 1]}, Strip{Hout.data(), c.dims[l]},
-                                           Strip{has_q ? q.data() : nullptr, 1}},
+            // (the last layer works on the top rows; with Lg == 1 its input, the cached sums, and the degree scales
+            // keep the full height, so a batch's timesteps are not adjacent there and go one by one)
+            const int64_t nl = l == Lg ? nt : n;
+            REINC_TRY(for_runs(lo, hi, nl, {Strip{Sp.data(), c.dims[l - 1]}, Strip{Hout.data(), c.dims[l]},
+                                            Strip{has_q ? q.data() : nullptr, 1}},
                                [&](int i0, int len) {
-                                   gemm_rows(ctx, s, (const void *)Sp[i0], 0, n * len, c.dims[l - 1], c.dims[l], q[i0], p.W[l], 0,
+                                   gemm_rows(ctx, s, (const void *)Sp[i0], 0, nl * len, c.dims[l - 1], c.dims[l], q[i0], p.W[l], 0,
                                              c.dims[l], p.b[l], 1, nof, nof, const_cast<float *>(Hout[i0]));
                                    return REINC_OK;
                                }));
@@ -452,13 +484,13 @@ int reinc_forward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *par
             LocalStep &st = ctx->local[i];
             const LocalStep *pv = i ? &ctx->local[i - 1] : nullptr;
             const float *hp = pv ? (const float *)pv->h : nof;
-            rnn_fused(ctx, s, lstm, (const float *)st.H[Lg], nof, n, c.dims[Lg], H, hp, hp, pv ? (const float *)pv->c : nof,
+            rnn_fused(ctx, s, lstm, (const float *)st.H[Lg], nof, nt, c.dims[Lg], H, hp, hp, pv ? (const float *)pv->c : nof,
                       p.W_i, p.W_h, p.b_i, p.b_h, st.h, st.c, st.saved);
         }
     }
     const LocalStep &last = ctx->local[L - 1];
     if (target) launch_mse(last.h, target, ctx->counted_rows() * H, ctx->loss_partial, loss_out, s);
-    if (h_last) REINC_HIP(ctx, hipMemcpyAsync(h_last, last.h, uint64_t(n) * H * 4, hipMemcpyDeviceToDevice, s));
+    if (h_last) REINC_HIP(ctx, hipMemcpyAsync(h_last, last.h, uint64_t(nt) * H * 4, hipMemcpyDeviceToDevice, s));
     REINC_HIP(ctx, hipGetLastError());
     ctx->local_valid = true;
     ctx->local_t0 = t0;
@@ -479,6 +511,9 @@ int reinc_backward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *pa
     const Params p = split_params(c, params);
     Params gp = split_params(c, grads);
     const int64_t n = c.num_nodes;
+    const int64_t nt = ctx->top_rows();  // rows of the last GCN layer and of the recurrent cell (see place_top)
+    const bool top = nt < n;
+    if (ctx->local_top != nt) return ctx->fail(REINC_E_STATE, "the loss rows changed since the forward pass of this window");
     const int Lg = c.num_gcn_layers, H = c.rnn_hidden;
     const int lstm = c.rnn_kind == REINC_RNN_LSTM;
     const int KH = (lstm ? 4 : 3) * H;
@@ -509,16 +544,17 @@ int reinc_backward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *pa
         return ctx->fail(REINC_E_NOMEM, "arena exhausted: no room for the backward scratch buffers");
     }
     const int64_t rowsB = int64_t(B) * n;
+    const int64_t rowsT = int64_t(B) * nt;  // rows of a batch of timesteps in the top quantities
     float *dgi = f32(uint64_t(rowsB) * KH);
     float *dgh = lstm ? dgi : f32(uint64_t(rowsB) * KH);
     float *dz = f32(uint64_t(rowsB) * maxd), *dz2 = f32(uint64_t(rowsB) * maxd), *dagg = f32(uint64_t(rowsB) * maxd);
     // one set of partial slabs per weight matrix: they collect all batches and are reduced once at the end
-    float *part_wi = static_cast<float *>(ctx->scratch(reduce_partial_bytes(rowsB, c.dims[Lg], KH)));
-    float *part_wh = static_cast<float *>(ctx->scratch(reduce_partial_bytes(rowsB, H, KH)));
+    float *part_wi = static_cast<float *>(ctx->scratch(reduce_partial_bytes(rowsT, c.dims[Lg], KH)));
+    float *part_wh = static_cast<float *>(ctx->scratch(reduce_partial_bytes(rowsT, H, KH)));
     float *part_w[REINC_MAX_GCN_LAYERS + 1] = {};
     bool part_ok = part_wi && part_wh;
     for (int l = 1; l <= Lg; ++l) {
-        part_w[l] = static_cast<float *>(ctx->scratch(reduce_partial_bytes(rowsB, c.dims[l - 1], c.dims[l])));
+        part_w[l] = static_cast<float *>(ctx->scratch(reduce_partial_bytes(l == Lg ? rowsT : rowsB, c.dims[l - 1], c.dims[l])));
         part_ok = part_ok && part_w[l];
     }
     if (!dgi || !dgh || !dz || !dz2 || !dagg || !part_ok) {
@@ -526,14 +562,14 @@ int reinc_backward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *pa
         return ctx->fail(REINC_E_NOMEM, "arena exhausted: no room for the backward scratch buffers");
     }
     launch_fill_f32(grads, p.count, 0.0f, s);
-    launch_mse_grad(ctx->local[L - 1].h, target, ctx->counted_rows() * H, n * H, dh, s);
+    launch_mse_grad(ctx->local[L - 1].h, target, ctx->counted_rows() * H, nt * H, dh, s);
     const float *dc_in = nullptr;  // zero at the last step
     const float *nof = nullptr;
     std::vector<const float *> s1(L), q(L), Ap(L), Mp(L);
     // The partial slabs of a weight always belong to the same number of rows (B timesteps): a shorter last batch
     // uses the chunk geometry of a full one, so that every batch adds into the same slabs.
-    auto reduce = [&](const float *A, int lda, const float *rs, const float *G, int ldg, int64_t rows, int K, int M, float *part,
-                      int accumulate) { gemm_reduce(ctx, s, A, lda, rs, G, ldg, rows, rowsB, K, M, part, accumulate); };
+    auto reduce = [&](const float *A, int lda, const float *rs, const float *G, int ldg, int64_t rows, int64_t rows_geom, int K, int M,
+                      float *part, int accumulate) { gemm_reduce(ctx, s, A, lda, rs, G, ldg, rows, rows_geom, K, M, part, accumulate); };
     bool first_batch = true;
     for (int32_t hi = L - 1; hi >= 0;) {
         const int32_t lo = std::max(0, hi - B + 1);
@@ -542,12 +578,12 @@ int reinc_backward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *pa
         for (int32_t i = hi; i >= lo; --i) {
             const LocalStep &st = ctx->local[i];
             const LocalStep *pv = i ? &ctx->local[i - 1] : nullptr;
-            float *dgi_i = dgi + int64_t(i - lo) * n * KH, *dgh_i = dgh + int64_t(i - lo) * n * KH;
-            rnn_backward_elem(ctx, s, lstm, n, H, (const float *)dh, dc_in, (const float *)st.saved,
+            float *dgi_i = dgi + int64_t(i - lo) * nt * KH, *dgh_i = dgh + int64_t(i - lo) * nt * KH;
+            rnn_backward_elem(ctx, s, lstm, nt, H, (const float *)dh, dc_in, (const float *)st.saved,
                               pv ? (const float *)pv->h : nof, pv ? (const float *)pv->c : nof, (const float *)st.c, dgi_i, dgh_i,
                               dh2, dc2);
             if (i > 0) {  // gradient w.r.t. h_{t-1}
-                gemm_rows(ctx, s, (const void *)dgh_i, 0, n, KH, H, nof, p.W_h, 1, KH, nof, 0, lstm ? nof : (const float *)dh2,
+                gemm_rows(ctx, s, (const void *)dgh_i, 0, nt, KH, H, nof, p.W_h, 1, KH, nof, 0, lstm ? nof : (const float *)dh2,
                           nof, dh);
                 if (lstm) {
                     std::swap(dc, dc2);  // dc now holds the gradient w.r.t. c_{t-1}; dc2 is free for the next step
@@ -568,33 +604,44 @@ int reinc_backward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *pa
             Mp[i] = i ? ctx->local[i - 1].h : ctx->zero_state;
         }
         int calls = 0;
-        REINC_TRY(for_runs(lo, hi, n, {Strip{Ap.data(), dl}}, [&](int i0, int len) {
-            reduce(Ap[i0], dl, nof, dgi + int64_t(i0 - lo) * n * KH, KH, n * len, dl, KH, part_wi, acc0 | (calls++ > 0));
+        REINC_TRY(for_runs(lo, hi, nt, {Strip{Ap.data(), dl}}, [&](int i0, int len) {
+            reduce(Ap[i0], dl, nof, dgi + int64_t(i0 - lo) * nt * KH, KH, nt * len, rowsT, dl, KH, part_wi, acc0 | (calls++ > 0));
             return REINC_OK;
         }));
         calls = 0;
-        REINC_TRY(for_runs(lo, hi, n, {Strip{Mp.data(), H}}, [&](int i0, int len) {
-            reduce(Mp[i0], H, nof, dgh + int64_t(i0 - lo) * n * KH, KH, n * len, H, KH, part_wh, acc0 | (calls++ > 0));
+        REINC_TRY(for_runs(lo, hi, nt, {Strip{Mp.data(), H}}, [&](int i0, int len) {
+            reduce(Mp[i0], H, nof, dgh + int64_t(i0 - lo) * nt * KH, KH, nt * len, rowsT, H, KH, part_wh, acc0 | (calls++ > 0));
             return REINC_OK;
         }));
         // gradient w.r.t. the last GCN layer's pre-activation, all timesteps of the batch
-        REINC_TRY(for_runs(lo, hi, n, {Strip{Ap.data(), dl}}, [&](int i0, int len) {
-            gemm_rows(ctx, s, (const void *)(dgi + int64_t(i0 - lo) * n * KH), 0, n * len, KH, dl, nof, p.W_i, 1, KH, nof, 0, nof,
-                      Ap[i0], dz + int64_t(i0 - lo) * n * dl);
+        REINC_TRY(for_runs(lo, hi, nt, {Strip{Ap.data(), dl}}, [&](int i0, int len) {
+            gemm_rows(ctx, s, (const void *)(dgi + int64_t(i0 - lo) * nt * KH), 0, nt * len, KH, dl, nof, p.W_i, 1, KH, nof, 0, nof,
+                      Ap[i0], dz + int64_t(i0 - lo) * nt * dl);
             return REINC_OK;
         }));
         for (int l = Lg; l >= 1; --l) {
             const int din = c.dims[l - 1], dout = c.dims[l];
             for (int32_t i = lo; i <= hi; ++i) Ap[i] = l == 1 ? s1[i] : ctx->local[i].S[l];
             calls = 0;
-            REINC_TRY(for_runs(lo, hi, n, {Strip{Ap.data(), din}, Strip{has_q ? q.data() : nullptr, 1}},
+            // dz holds the gradients of layer l's pre-activations: nl rows per timestep (the top rows for the last layer)
+            const bool top_l = top && l == Lg;
+            const int64_t nl = l == Lg ? nt : n;
+            REINC_TRY(for_runs(lo, hi, nl, {Strip{Ap.data(), din}, Strip{has_q ? q.data() : nullptr, 1}},
                                [&](int i0, int len) {
-                                   reduce(Ap[i0], din, q[i0], dz + int64_t(i0 - lo) * n * dout, dout, n * len, din, dout, part_w[l],
-                                          acc0 | (calls++ > 0));
+                                   reduce(Ap[i0], din, q[i0], dz + int64_t(i0 - lo) * nl * dout, dout, nl * len, l == Lg ? rowsT : rowsB,
+                                          din, dout, part_w[l], acc0 | (calls++ > 0));
                                    return REINC_OK;
                                }));
             if (l > 1) {
-                gemm_rows(ctx, s, (const void *)dz, 0, n * nb, dout, din, nof, p.W[l], 1, dout, nof, 0, nof, nof, dagg);
+                if (top_l) {
+                    // the adjoint aggregation below reads every row of dagg (full height): the rows that are not computed
+                    // are zero
+                    launch_fill_f32(dagg, int64_t(nb) * n * din, 0.0f, s);
+                    for (int32_t i = lo; i <= hi; ++i)
+                        gemm_rows(ctx, s, (const void *)(dz + int64_t(i - lo) * nt * dout), 0, nt, dout, din, nof, p.W[l], 1, dout, nof, 0,
+                                  nof, nof, dagg + int64_t(i - lo) * n * din);
+                } else
+                    gemm_rows(ctx, s, (const void *)dz, 0, n * nb, dout, din, nof, p.W[l], 1, dout, nof, 0, nof, nof, dagg);
                 AggBatch batch;
                 batch.count = nb;
                 for (int32_t i = lo; i <= hi; ++i) {
@@ -610,10 +657,10 @@ int reinc_backward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *pa
         first_batch = false;
         hi = lo - 1;
     }
-    launch_reduce_partials(part_wi, rowsB, c.dims[Lg], KH, const_cast<float *>(gp.W_i), const_cast<float *>(gp.b_i), s);
-    launch_reduce_partials(part_wh, rowsB, H, KH, const_cast<float *>(gp.W_h), const_cast<float *>(gp.b_h), s);
+    launch_reduce_partials(part_wi, rowsT, c.dims[Lg], KH, const_cast<float *>(gp.W_i), const_cast<float *>(gp.b_i), s);
+    launch_reduce_partials(part_wh, rowsT, H, KH, const_cast<float *>(gp.W_h), const_cast<float *>(gp.b_h), s);
     for (int l = 1; l <= Lg; ++l)
-        launch_reduce_partials(part_w[l], rowsB, c.dims[l - 1], c.dims[l], const_cast<float *>(gp.W[l]),
+        launch_reduce_partials(part_w[l], l == Lg ? rowsT : rowsB, c.dims[l - 1], c.dims[l], const_cast<float *>(gp.W[l]),
                                const_cast<float *>(gp.b[l]), s);
     REINC_HIP(ctx, hipGetLastError());
     return REINC_OK;
