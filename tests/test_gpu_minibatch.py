@@ -148,8 +148,13 @@ def test_loss_rows_on_an_ordinary_context():
     graphs = oracle_graphs(seq)
     feats = [oracle_feats(seq, t) for t in range(4)]
     p = synth.split_params(wl, flat.astype(np.float64))
-    for rows in (123, 0):
+    from paper_2501_15348_amd import reinc
+
+    # growing and shrinking row counts: the compact slices of the recurrent state move, the zero state must stay zero
+    for rows in (123, 0, 300, 50):
         ctx.set_loss_rows(rows)
+        with pytest.raises(reinc.ReincError, match="forward pass"):
+            ctx.backward_window(0, 4, params, tgt, grads)  # the rows changed: the last forward pass does not count
         ctx.forward_window(0, 4, params, tgt, loss)
         ctx.backward_window(0, 4, params, tgt, grads)
         torch.cuda.synchronize()
