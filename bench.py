@@ -27,7 +27,7 @@ MAX_BATCH = 8  # timesteps of a window that the driver hands to one launch
 
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
 # command (profiles/bench_c2_hbm_traffic_pmc.txt), scaled by the copy-kernel calibration; None = not measured.
-MEASURED_TRAFFIC = {"c2": 827.0e6}
+MEASURED_TRAFFIC = {"c2": 872.0e6}
 
 
 def parse_args():

@@ -138,12 +138,13 @@ extern "C++" int reinc::load_edges(reinc_ctx *ctx, int32_t t, const int32_t *src
     const int64_t m = std::max<int64_t>(nnz, 1);
     int32_t *d_src = static_cast<int32_t *>(ctx->scratch(uint64_t(m) * 4));
     int32_t *d_dst = static_cast<int32_t *>(ctx->scratch(uint64_t(m) * 4));
-    uint64_t *keys0 = static_cast<uint64_t *>(ctx->scratch(uint64_t(m) * 8));
-    uint64_t *keys1 = static_cast<uint64_t *>(ctx->scratch(uint64_t(m) * 8));
+    const int64_t mm = std::max(m, n);  // (the key arrays also serve the per-node sort by row length below)
+    uint64_t *keys0 = static_cast<uint64_t *>(ctx->scratch(uint64_t(mm) * 8));
+    uint64_t *keys1 = static_cast<uint64_t *>(ctx->scratch(uint64_t(mm) * 8));
     int32_t *flag = static_cast<int32_t *>(ctx->scratch(uint64_t(std::max(m, n)) * 4));
     int64_t *offs = static_cast<int64_t *>(ctx->scratch(uint64_t(std::max(m, n) + 1) * 8));
     int32_t *err = static_cast<int32_t *>(ctx->scratch(256));
-    const size_t sort_bytes = sort_keys_tmp_bytes(m);
+    const size_t sort_bytes = sort_keys_tmp_bytes(mm);
     void *sort_tmp = ctx->scratch(sort_bytes);
     void *scan_tmp = ctx->scratch(scan_tmp_bytes(std::max(m, n)));
     if (!d_src || !d_dst || !keys0 || !keys1 || !flag || !offs || !err || !sort_tmp || !scan_tmp) return fail_nomem("scratch");
@@ -186,6 +187,15 @@ extern "C++" int reinc::load_edges(reinc_ctx *ctx, int32_t t, const int32_t *src
         sn.q = ctx->q_block + int64_t(t) * n;  // one [T, N] block: the scales of consecutive snapshots are adjacent
         launch_degree_scales(sn.row_ptr, n, agg == REINC_AGG_SYM, ctx->cfg.self_loop, sn.q, s);
         if (agg == REINC_AGG_SYM) sn.p = sn.q;  // same numbers on both sides
+    }
+    // rows and columns by falling length: the order in which the group-per-row aggregation kernel takes them
+    sn.row_order = static_cast<int32_t *>(ctx->alloc(uint64_t(n) * 4));
+    sn.col_order = static_cast<int32_t *>(ctx->alloc(uint64_t(n) * 4));
+    if (!sn.row_order || !sn.col_order) return fail_nomem("row order lists");
+    for (int side = 0; side < 2; ++side) {
+        launch_length_keys(side == 0 ? sn.row_ptr : sn.col_ptr, n, keys0, s);
+        REINC_HIP(ctx, sort_keys(sort_tmp, sort_bytes, keys0, keys1, n, 32 + 7, s));  // lengths are capped at kLongRow + 1 < 128
+        launch_low_halves(keys1, n, side == 0 ? sn.row_order : sn.col_order, s);
     }
     // rows / columns that take the block-per-row aggregation path
     for (int side = 0; side < 2; ++side) {
@@ -595,10 +605,10 @@ int reinc_aggregate_full(reinc_ctx *ctx, int32_t t, int transpose, const void *X
     const int bf16 = x_dtype == REINC_BF16;
     if (!transpose)
         aggregate_full(ctx, sn.row_ptr, sn.col, sn.long_rows, sn.n_long_rows, X, bf16, d, ctx->cfg.self_loop, sn.p,
-                       apply_q ? sn.q : nullptr, nullptr, out, as_stream(stream));
+                       apply_q ? sn.q : nullptr, nullptr, out, as_stream(stream), sn.row_order);
     else
         aggregate_full(ctx, sn.col_ptr, sn.row, sn.long_cols, sn.n_long_cols, X, bf16, d, ctx->cfg.self_loop,
-                       apply_q ? sn.q : nullptr, sn.p, nullptr, out, as_stream(stream));
+                       apply_q ? sn.q : nullptr, sn.p, nullptr, out, as_stream(stream), sn.col_order);
     REINC_HIP(ctx, hipGetLastError());
     return REINC_OK;
 }

@@ -36,6 +36,9 @@ struct Snapshot {
     // degree scalings: p (source side), q (target side), fp32 [N]
     float *p = nullptr;
     float *q = nullptr;
+    // rows (columns) ordered by falling length: the order in which the group-per-row aggregation kernel takes them, so
+    // that the rows a wavefront works on together are equally long (a wavefront lasts as long as its longest row)
+    int32_t *row_order = nullptr, *col_order = nullptr;
     // rows / columns longer than kLongRow (ascending)
     int32_t *long_rows = nullptr;
     int32_t n_long_rows = 0;
@@ -79,6 +82,7 @@ struct AggItem {
     const int32_t *long_rows;
     int32_t n_long;
     int64_t row_limit = 0;  // > 0: listed long rows from this row on are skipped (their output rows do not exist)
+    const int32_t *order = nullptr;  // [n] or null: the row the i-th lane group of the short-row kernel takes
 };
 struct AggBatch {
     int count = 0;
@@ -295,6 +299,8 @@ void launch_ptr_from_sorted(const uint64_t *keys, int64_t e, int64_t n, int64_t 
 void launch_ptr_from_rowid(const int32_t *rowid, int64_t e, int64_t n, int64_t *ptr, hipStream_t s);
 void launch_degree_scales(const int64_t *ptr, int64_t n, int sym, int self_loop, float *q, hipStream_t s);
 void launch_long_flags(const int64_t *ptr, int64_t n, int32_t *flag, hipStream_t s);
+// keys[v] = (kLongRow + 1 - min(length of row v, kLongRow + 1)) << 32 | v: ascending keys = falling row length
+void launch_length_keys(const int64_t *ptr, int64_t n, uint64_t *keys, hipStream_t s);
 void launch_scatter_rows(const void *vals, const int32_t *rows, int64_t nrows, int32_t row_bytes, void *x, hipStream_t s);
 
 // ---- kernels_agg.hip
@@ -314,7 +320,7 @@ void aggregate_full_batch(reinc_ctx *ctx, const AggBatch &batch, int bf16, int32
                           int64_t n_rows = -1);
 void aggregate_full(reinc_ctx *ctx, const int64_t *ptr, const int32_t *idx, const int32_t *long_rows, int32_t n_long,
                     const void *X, int bf16, int32_t d, int self_loop, const float *in_scale, const float *out_scale,
-                    const float *mask, float *out, hipStream_t s);
+                    const float *mask, float *out, hipStream_t s, const int32_t *order = nullptr);
 // max / min aggregation with contributing source ids (Section 3.2): from scratch, and the incremental step whose
 // hub rows with a lost contributor are marked in hub_flags [N] (zeroed by the caller) for the block-per-row kernel;
 // block_counts needs one int per 4 rows; *stat_out receives the number of rows aggregated from scratch

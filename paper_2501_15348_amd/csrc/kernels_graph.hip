@@ -312,6 +312,14 @@ __device__ inline bool row_find(const int32_t *col, int64_t beg, int64_t end, in
 }
 
 // X[rows[r]] = vals[r], rows of `chunks` 16-byte pieces
+__global__ void length_keys(const int64_t *ptr, int64_t n, uint64_t *keys)
+{
+    const int64_t v = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
+    if (v >= n) return;
+    const int64_t len = min(ptr[v + 1] - ptr[v], int64_t(kLongRow + 1));
+    keys[v] = (uint64_t(kLongRow + 1 - len) << 32) | uint64_t(v);
+}
+
 __global__ void scatter_rows(const uint4 *vals, const int32_t *rows, int64_t nrows, int32_t chunks, uint4 *x)
 {
     int64_t i = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
@@ -574,6 +582,11 @@ void launch_ptr_from_rowid(const int32_t *rowid, int64_t e, int64_t n, int64_t *
 void launch_degree_scales(const int64_t *ptr, int64_t n, int sym, int self_loop, float *q, hipStream_t s)
 {
     if (n > 0) degree_scales<<<blocks_for(n, 256), 256, 0, s>>>(ptr, n, sym, self_loop, q);
+}
+
+void launch_length_keys(const int64_t *ptr, int64_t n, uint64_t *keys, hipStream_t s)
+{
+    if (n > 0) length_keys<<<blocks_for(n, 256), 256, 0, s>>>(ptr, n, keys);
 }
 
 void launch_long_flags(const int64_t *ptr, int64_t n, int32_t *flag, hipStream_t s)

@@ -338,7 +338,7 @@ int ensure_layer1(reinc_ctx *ctx, int32_t t, hipStream_t s)
         ctx->stats.delta_entries_processed += dl.info.n_entries;
     } else {
         aggregate_full(ctx, sn.row_ptr, sn.col, sn.long_rows, sn.n_long_rows, sn.x, bf16, d, c.self_loop, sn.p, nullptr,
-                       nullptr, slot, s);
+                       nullptr, slot, s, sn.row_order);
         ++ctx->stats.steps_full;
     }
     REINC_HIP(ctx, hipGetLastError());
@@ -460,7 +460,10 @@ int reinc_forward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *par
                     LocalStep &st = ctx->local[i];
                     batch.item[i - lo] = AggItem{sn.row_ptr, sn.col, st.H[l - 1], sn.p, nullptr, nullptr, nullptr, st.S[l], sn.long_rows,
                                                  sn.n_long_rows};
-                    if (l == Lg && nt < n) batch.item[i - lo].row_limit = nt;  // S of the last layer has nt rows per timestep
+                    if (l == Lg && nt < n)
+                        batch.item[i - lo].row_limit = nt;  // S of the last layer has nt rows per timestep: rows [0, nt) as they come
+                    else
+                        batch.item[i - lo].order = sn.row_order;
                 }
                 aggregate_full_batch(ctx, batch, 0, c.dims[l - 1], c.self_loop, s, l == Lg ? nt : n);
             }
@@ -649,6 +652,7 @@ int reinc_backward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *pa
                     batch.item[i - lo] = AggItem{sn.col_ptr, sn.row, dagg + int64_t(i - lo) * n * din, sn.q, sn.p,
                                                  ctx->local[i].H[l - 1], nullptr, dz2 + int64_t(i - lo) * n * din, sn.long_cols,
                                                  sn.n_long_cols};
+                    batch.item[i - lo].order = sn.col_order;
                 }
                 aggregate_full_batch(ctx, batch, 0, din, c.self_loop, s);
                 std::swap(dz, dz2);
@@ -698,7 +702,7 @@ int reinc_forward_window_integrated(reinc_ctx *ctx, int32_t t0, int32_t L, const
         const LocalStep *pv = i ? &ctx->local[i - 1] : nullptr;
         if (pv)  // Agg(h_{t-1}) over snapshot t; at the first timestep the state, and with it the aggregate, is zero
             aggregate_full(ctx, sn.row_ptr, sn.col, sn.long_rows, sn.n_long_rows, pv->h, 0, H, c.self_loop, sn.p, sn.q, nullptr,
-                           st.S[1], s);
+                           st.S[1], s, sn.row_order);
         rnn_fused(ctx, s, lstm, (const float *)ctx->gcache[t], (const float *)sn.q, n, c.dims[0], H,
                   pv ? (const float *)st.S[1] : nof, pv ? (const float *)pv->h : nof, pv ? (const float *)pv->c : nof, W_i, W_h,
                   b_i, b_h, st.h, st.c, st.saved);
@@ -780,6 +784,7 @@ int reinc_backward_window_integrated(reinc_ctx *ctx, int32_t t0, int32_t L, cons
                 batch.count = 1;
                 batch.item[0] = AggItem{sn.col_ptr, sn.row, dah, sn.q, sn.p, nullptr, lstm ? nof : (const float *)dh2, dh,
                                         sn.long_cols, sn.n_long_cols};
+                batch.item[0].order = sn.col_order;
                 aggregate_full_batch(ctx, batch, 0, H, c.self_loop, s);
                 if (lstm) {
                     std::swap(dc, dc2);
