@@ -60,6 +60,18 @@ def test_extraction_is_exact(mode, hops, dist):
 
 @pytest.mark.parametrize("mode,rnn,layers", [("sum", "gru", 1), ("mean", "lstm", 2), ("sym", "gru", 2)])
 def test_batch_windows_match_the_whole_graph_reference(mode, rnn, layers):
+    _check_batch_windows(mode, rnn, layers)
+
+
+def test_batch_windows_with_three_timesteps_per_launch(monkeypatch):
+    """A window of four timesteps in launches of three and one: the compact slices of the last layer and of the cell
+    are adjacent within a launch's timesteps only."""
+    monkeypatch.setenv("REINC_BATCH", "3")
+    _check_batch_windows("mean", "lstm", 2)
+    _check_batch_windows("sum", "gru", 2)
+
+
+def _check_batch_windows(mode, rnn, layers):
     import torch
 
     wl = _workload(mode, rnn, layers)
