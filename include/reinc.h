@@ -265,20 +265,21 @@ int reinc_cache_peek(reinc_ctx *ctx, int32_t t, const float **S_out);
  * batch keeps the nodes F_hops and, of every snapshot, the edges whose target is in F_{hops-1}; its nodes are
  * numbered batch first (in the order given), then the others by ascending id.  A stacked model of `hops`
  * aggregation layers evaluated on the sub-sequence gives on the batch rows exactly what it gives on the whole
- * graph (one hop more under the symmetric normalisation, whose source-side scale is a degree as well).
+ * graph.  (The degree scales of the mean and symmetric normalisations are carried over from the source graph, so
+ * the degree of a node whose own in-edges are not kept -- a source only -- is still the right one.)
  *
  * The sub-sequence goes into a second context, which is then used like any other: sliding its windows over the
  * whole sequence before the next batch is extracted (seq-first) lets its aggregate cache serve every window and
  * hold the rows of this batch only.
  *
- * reinc_batch_plan: nodes = HOST array of n_batch distinct ids; hops <= 0 selects num_gcn_layers (+ 1 for
- *   REINC_AGG_SYM).  Every snapshot's edges must be loaded.  Computes the node set on the device and keeps it in
+ * reinc_batch_plan: nodes = HOST array of n_batch distinct ids; hops <= 0 selects num_gcn_layers.  Every
+ *   snapshot's edges must be loaded.  Computes the node set on the device and keeps it in
  *   `ctx` (3 ints per node of arena space, allocated by the first plan) until the next plan; returns the number of
  *   nodes of the sub-sequence and |F_{hops-1}|.  REINC_E_ARG for ids out of range or listed twice.  SYNC.
  * reinc_batch_node_list: old id of every node of the planned sub-sequence, to a HOST array of n_nodes int32.  SYNC.
  * reinc_batch_load: fills `child` -- created by the caller with num_nodes = the planned count, the same
- *   num_snapshots, dims[0], feat_dtype and device, no snapshots loaded -- with the extracted edges and the gathered
- *   feature rows of every snapshot, and sets its loss rows to n_batch.  Errors are reported on `ctx`; after a
+ *   num_snapshots, dims[0], feat_dtype, agg_kind, self_loop and device, no snapshots loaded -- with the extracted
+ *   edges, the gathered feature rows and degree scales of every snapshot, and sets its loss rows to n_batch.  Errors are reported on `ctx`; after a
  *   failure `child` may hold some of the snapshots and is good for reinc_destroy only.  Both contexts stay
  *   independent afterwards (the child holds copies).  SYNC.
  * reinc_set_loss_rows: the loss of the window calls becomes the mean over rows [0, rows) of h_last and target

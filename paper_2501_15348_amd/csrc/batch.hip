@@ -78,6 +78,12 @@ __global__ void batch_edge_compact(const int32_t *rowid, const int32_t *col, int
     dst[offs[i]] = new_id[rowid[i]];
 }
 
+__global__ void gather_f32(const float *in, const int32_t *list, int64_t n, float *out)
+{
+    const int64_t i = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
+    if (i < n) out[i] = in[list[i]];
+}
+
 // out row i = in row list[i], in 16-byte pieces
 __global__ void gather_rows(const uint4 *in, const int32_t *list, int64_t nrows, int32_t chunks, uint4 *out)
 {
@@ -106,7 +112,7 @@ int reinc_batch_plan(reinc_ctx *ctx, const int32_t *nodes, int64_t n_batch, int3
     if (!ctx) return REINC_E_ARG;
     const int64_t n = ctx->N();
     if (!nodes || n_batch <= 0 || n_batch > n) return ctx->fail(REINC_E_ARG, "a batch needs between 1 and %lld nodes", (long long)n);
-    if (hops <= 0) hops = ctx->cfg.num_gcn_layers + (ctx->cfg.agg_kind == REINC_AGG_SYM ? 1 : 0);
+    if (hops <= 0) hops = ctx->cfg.num_gcn_layers;
     if (hops > 64) return ctx->fail(REINC_E_ARG, "%d hops", hops);
     for (int64_t i = 0; i < n_batch; ++i)
         if (nodes[i] < 0 || nodes[i] >= n) return ctx->fail(REINC_E_ARG, "batch node id %d out of range", nodes[i]);
@@ -178,8 +184,10 @@ int reinc_batch_load(reinc_ctx *ctx, reinc_ctx *child)
     if (ctx->batch_total <= 0) return ctx->fail(REINC_E_STATE, "no node batch has been planned");
     const reinc_config &a = ctx->cfg, &b = child->cfg;
     if (b.num_nodes != ctx->batch_total || b.num_snapshots != a.num_snapshots || b.dims[0] != a.dims[0] || b.feat_dtype != a.feat_dtype ||
-        b.device != a.device)
-        return ctx->fail(REINC_E_ARG, "the batch context needs %lld nodes, %d snapshots and the feature width, type and device of its source",
+        b.device != a.device || b.agg_kind != a.agg_kind || b.self_loop != a.self_loop)
+        return ctx->fail(REINC_E_ARG,
+                         "the batch context needs %lld nodes, %d snapshots and the feature width, type, aggregator, self-loop flag and "
+                         "device of its source",
                          (long long)ctx->batch_total, a.num_snapshots);
     for (const Snapshot &sn : ctx->snaps)
         if (!sn.edges_loaded || !sn.feats_loaded) return ctx->fail(REINC_E_STATE, "every snapshot must be loaded before a batch is extracted");
@@ -221,6 +229,10 @@ int reinc_batch_load(reinc_ctx *ctx, reinc_ctx *child)
             break;
         }
         Snapshot &cs = child->snaps[t];
+        // The degree scales are those of the source graph: a row of the batch graph holds all of a node's in-edges only
+        // for the nodes whose aggregate is needed, but the symmetric normalisation also scales by the degree of an
+        // edge's source.
+        if (cs.q && sn.q) gather_f32<<<blocks_for(nu, 256), 256, 0, s>>>(sn.q, ctx->batch_nodes, nu, cs.q);
         cs.x = child->alloc(uint64_t(nu) * row_bytes);
         if (!cs.x) {
             rc = ctx->fail(REINC_E_NOMEM, "batch context: arena exhausted while storing features of snapshot %d", t);

@@ -343,7 +343,11 @@ __global__ void steps_init_flags(const DiffStep *steps, int64_t n, int sym)
     const DiffStep &st = steps[blockIdx.y];
     const int64_t v = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
     if (v >= n) return;
-    st.cflags[v] = sym && (st.rp_a[v + 1] - st.rp_a[v]) != (st.rp_b[v + 1] - st.rp_b[v]);
+    // under the symmetric normalisation a node's row of Y changes when its source-side scale does, i.e. when its
+    // degree does (the scales are compared, not the row lengths: a node batch extracted from a larger graph carries
+    // the scales of that graph, and its rows need not hold all of a node's edges)
+    st.cflags[v] = sym && st.p_a && st.p_b ? st.p_a[v] != st.p_b[v]
+                                           : (sym && (st.rp_a[v + 1] - st.rp_a[v]) != (st.rp_b[v + 1] - st.rp_b[v]));
 }
 
 // stage 1b: rows whose features were re-assigned (delta-mode loading keeps their list)
