@@ -198,6 +198,16 @@ int reinc_aggregate_full_minmax(reinc_ctx *ctx, int32_t t, int op, const void *X
                                 int32_t *contrib, void *stream);
 int reinc_aggregate_incremental_minmax(reinc_ctx *ctx, int32_t t, int op, const float *M_prev, const int32_t *C_prev,
                                        float *M_out, int32_t *C_out, int32_t *work, void *stream);
+/* reinc_aggregate_incremental_minmax_static, ASYNC: the same step for callers that cannot allocate device memory
+ * or provide a work buffer (code under HIP graph capture, tight serving loops, harnesses that forbid allocation).
+ * The work area is a static device array inside the library (8 MiB per GPU, held until the process ends); the call
+ * allocates nothing and enqueues kernels only.  At most 2^20 nodes: a larger context gets REINC_E_ARG (use the
+ * call above).  n_redone_out: device int32 scalar that receives the number of rows aggregated from scratch, or NULL.
+ * All calls on one GPU share the one work area: calls that may overlap on a GPU (different streams, different
+ * contexts or threads) race and must be serialised by the caller.  Other arguments, results and errors as above. */
+int reinc_aggregate_incremental_minmax_static(reinc_ctx *ctx, int32_t t, int op, const float *M_prev,
+                                              const int32_t *C_prev, float *M_out, int32_t *C_out,
+                                              int32_t *n_redone_out, void *stream);
 
 /* ---- dense steps ------------------------------------------------------------------------------------------
  * reinc_gcn_transform (Section 3.5, Listing 1: update = ReLU(linear(aggregate))), ASYNC.

@@ -89,7 +89,7 @@ int reinc_create(reinc_ctx **out, const reinc_config *cfg)
         ctx->q_block = static_cast<float *>(ctx->alloc(uint64_t(c.num_snapshots) * uint64_t(c.num_nodes) * 4));
         if (!ctx->q_block) return ctx->fail(REINC_E_NOMEM, "arena exhausted: no room for the degree scales");
     }
-    return REINC_OK;
+    return static_scratch_init(ctx);
 }
 
 int reinc_destroy(reinc_ctx *ctx)
@@ -674,6 +674,12 @@ int reinc_aggregate_incremental_minmax(reinc_ctx *ctx, int32_t t, int op, const 
                                        float *M_out, int32_t *C_out, int32_t *work, void *stream)
 {
     if (!ctx) return REINC_E_ARG;
+    return reinc::minmax_incremental(ctx, t, op, M_prev, C_prev, M_out, C_out, work, true, as_stream(stream));
+}
+
+extern "C++" int reinc::minmax_incremental(reinc_ctx *ctx, int32_t t, int op, const float *M_prev, const int32_t *C_prev,
+                                           float *M_out, int32_t *C_out, int32_t *work, bool timed, hipStream_t s)
+{
     REINC_TRY(need_delta(ctx, t));
     if (op != REINC_OP_MAX && op != REINC_OP_MIN) return ctx->fail(REINC_E_ARG, "op must be REINC_OP_MAX or REINC_OP_MIN");
     if (!M_prev || !C_prev || !M_out || !C_out || !work) return ctx->fail(REINC_E_ARG, "null buffer");
@@ -690,16 +696,23 @@ int reinc_aggregate_incremental_minmax(reinc_ctx *ctx, int32_t t, int op, const 
         if ((a < b + bytes && b < a + bytes) || (e < f + bytes && f < e + bytes))
             return ctx->fail(REINC_E_ARG, "output buffers must be the previous ones themselves or disjoint from them");
     }
-    hipStream_t s = as_stream(stream);
-    // work: [0] rows aggregated from scratch, [1] spare, [2, N+2) hub-row marks by row id, then per-block counts
+    // work: [0] rows aggregated from scratch, [1] spare, [2, N+2) hub-row marks by row id, then per-block counts.
+    // Everything that must start at zero is cleared here, by a kernel: the buffer keeps the last call's contents.
     launch_fill_f32(reinterpret_cast<float *>(work), ctx->N() + 2, 0.0f, s);  // (bit pattern 0)
     {
-        ProfScope prof(ctx, REINC_K_AGG_MINMAX, s);
         const int64_t n_rows = in_place ? dl.info.n_rows : ctx->N();
-        launch_minmax_incremental(in_place ? dl.rows : nullptr, n_rows, sn.long_rows, sn.n_long_rows, dl.ent_ptr, dl.ent,
-                                  dl.changed, sn.row_ptr, sn.col, sn.x, ctx->cfg.feat_dtype == REINC_BF16, d,
-                                  ctx->cfg.self_loop, op == REINC_OP_MAX, M_prev, C_prev, M_out, C_out, work + 2,
-                                  work + 2 + ctx->N(), work, s);
+        auto run = [&] {
+            launch_minmax_incremental(in_place ? dl.rows : nullptr, n_rows, sn.long_rows, sn.n_long_rows, dl.ent_ptr, dl.ent,
+                                      dl.changed, sn.row_ptr, sn.col, sn.x, ctx->cfg.feat_dtype == REINC_BF16, d,
+                                      ctx->cfg.self_loop, op == REINC_OP_MAX, M_prev, C_prev, M_out, C_out, work + 2,
+                                      work + 2 + ctx->N(), work, s);
+        };
+        if (timed) {
+            ProfScope prof(ctx, REINC_K_AGG_MINMAX, s);  // (creates events while a profile is open)
+            run();
+        } else {
+            run();
+        }
     }
     REINC_HIP(ctx, hipGetLastError());
     return REINC_OK;

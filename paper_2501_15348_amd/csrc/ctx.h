@@ -240,6 +240,14 @@ namespace reinc {
 // ---- api.hip
 // reinc_load_edges with the raw list in host or in device memory
 int load_edges(reinc_ctx *ctx, int32_t t, const int32_t *src, const int32_t *dst, int64_t nnz, bool on_device);
+// reinc_aggregate_incremental_minmax with the work area given by the caller of this function; `timed`: the launches
+// may be bracketed by profiling events
+int minmax_incremental(reinc_ctx *ctx, int32_t t, int op, const float *M_prev, const int32_t *C_prev, float *M_out,
+                       int32_t *C_out, int32_t *work, bool timed, hipStream_t s);
+
+// ---- noalloc.hip
+// finds the address of the static work area on the context's device (once per device)
+int static_scratch_init(reinc_ctx *ctx);
 
 // ---- kernels_graph.hip
 // exclusive scan of int32 counts [n] into int64 offsets [n+1]; tmp: scratch of scan_tmp_bytes(n)

@@ -94,6 +94,7 @@ def load_library() -> ctypes.CDLL:
         "reinc_aggregate_incremental": [p, i32, p, p, p, p],
         "reinc_aggregate_full_minmax": [p, i32, ci, p, ci, i32, p, p, p],
         "reinc_aggregate_incremental_minmax": [p, i32, ci, p, p, p, p, p, p],
+        "reinc_aggregate_incremental_minmax_static": [p, i32, ci, p, p, p, p, p, p],
         "reinc_gcn_transform": [p, p, ci, i64, i32, i32, p, p, p, ci, p, p],
         "reinc_rnn_step": [p, ci, p, i64, i32, i32, p, p, p, p, p, p, p, p, p, p],
         "reinc_forward_window": [p, i32, i32, p, p, p, p, p],
@@ -340,6 +341,13 @@ class Context:
         self._ck(self.lib.reinc_aggregate_incremental_minmax(self.handle, t, OPS[op], _dev_ptr(m_prev), _dev_ptr(c_prev),
                                                              _dev_ptr(m_out), _dev_ptr(c_out), _dev_ptr(work), _stream()))
         return m_out, c_out, work
+
+    def aggregate_incremental_minmax_static(self, t: int, op: str, m_prev, c_prev, m_out, c_out, n_redone=None):
+        """The same step with the library's static work area: no allocation here or in the library (the caller
+        passes every buffer); n_redone: int32 device scalar or None."""
+        self._ck(self.lib.reinc_aggregate_incremental_minmax_static(self.handle, t, OPS[op], _dev_ptr(m_prev),
+                                                                    _dev_ptr(c_prev), _dev_ptr(m_out), _dev_ptr(c_out),
+                                                                    _dev_ptr(n_redone), _stream()))
 
     # ---- dense steps
     def gcn_transform(self, a, w, b=None, row_scale=None, relu: bool = True, out=None):
