@@ -20,6 +20,8 @@ from __future__ import annotations
 
 import dataclasses
 import math
+import os
+from concurrent.futures import ThreadPoolExecutor
 from dataclasses import dataclass
 from typing import List, Optional, Tuple
 
@@ -31,6 +33,83 @@ _S_GRAPH, _S_PERM, _S_STEP, _S_FEAT0, _S_FEATSTEP, _S_PARAM, _S_TARGET, _S_SHUFF
 
 def _rng(seed: int, stream: int, sub: int = 0) -> np.random.Generator:
     return np.random.Generator(np.random.Philox(key=[(seed << 16) ^ sub, stream]))
+
+
+# The largest workloads hold tens of millions of edges per snapshot; the array passes below are split into pieces
+# that a few threads work on (numpy releases the interpreter lock inside them).  The pieces and their results do
+# not depend on the number of threads.
+_PIECE = 1 << 20
+_THREADS = max(1, min(16, os.cpu_count() or 1))
+
+
+def _pieces(n: int, piece: int = _PIECE):
+    return [(a, min(a + piece, n)) for a in range(0, n, piece)]
+
+
+def _pmap(fn, n: int, piece: int = _PIECE):
+    """fn(a, b) for every piece [a, b) of range(n); results in order."""
+    parts = _pieces(n, piece)
+    if len(parts) <= 1 or _THREADS == 1:
+        return [fn(a, b) for a, b in parts]
+    with ThreadPoolExecutor(_THREADS) as pool:
+        return list(pool.map(lambda ab: fn(*ab), parts))
+
+
+def _in_sorted(ref_sorted: np.ndarray, x: np.ndarray) -> np.ndarray:
+    """Mask of the entries of x that occur in ref_sorted."""
+    out = np.zeros(x.size, dtype=bool)
+    if ref_sorted.size == 0:
+        return out
+
+    def run(a, b):
+        pos = np.minimum(np.searchsorted(ref_sorted, x[a:b]), ref_sorted.size - 1)
+        out[a:b] = ref_sorted[pos] == x[a:b]
+
+    _pmap(run, x.size)
+    return out
+
+
+def _first_occurrences(k: np.ndarray) -> np.ndarray:
+    """The entries of k without repeats of an earlier value, in their order.  (Repeats are rare: the values that
+    occur more than once are found from one plain sort, and only their occurrences are ranked by position.)"""
+    ks = np.sort(k)
+    rep = ks[1:][ks[1:] == ks[:-1]]
+    if rep.size == 0:
+        return k, ks
+    rep = rep[np.concatenate([[True], rep[1:] != rep[:-1]])]
+    idx = np.nonzero(_in_sorted(rep, k))[0]
+    _, first = np.unique(k[idx], return_index=True)
+    keep = np.ones(k.size, dtype=bool)
+    keep[idx] = False
+    keep[idx[first]] = True
+    uk = ks[np.concatenate([[True], ks[1:] != ks[:-1]])]
+    return k[keep], uk
+
+
+def _replace_sorted(keys: np.ndarray, drop: np.ndarray, ins: np.ndarray) -> np.ndarray:
+    """keys (sorted, distinct) without the entries at the sorted positions `drop`, united with `ins` (sorted,
+    disjoint from keys); sorted.  Piece by piece: a piece of the old array and the new values that fall into
+    its range are merged on their own."""
+    if keys.size == 0:
+        return ins.copy()
+    parts = _pieces(keys.size)
+    lo = [0] + [int(x) for x in np.searchsorted(ins, keys[[a for a, _ in parts[1:]]])] if len(parts) > 1 else [0]
+    hi = lo[1:] + [ins.size]
+    dlo = np.searchsorted(drop, [a for a, _ in parts])
+    dhi = np.append(dlo[1:], drop.size)
+
+    def run(i):
+        a, b = parts[i]
+        keep = np.ones(b - a, dtype=bool)
+        keep[drop[dlo[i]:dhi[i]] - a] = False
+        return np.sort(np.concatenate([keys[a:b][keep], ins[lo[i]:hi[i]]]))
+
+    if len(parts) == 1 or _THREADS == 1:
+        out = [run(i) for i in range(len(parts))]
+    else:
+        with ThreadPoolExecutor(_THREADS) as pool:
+            out = list(pool.map(run, range(len(parts))))
+    return np.concatenate(out)
 
 
 @dataclass(frozen=True)
@@ -95,12 +174,27 @@ WORKLOADS = {
 
 def _pack(src: np.ndarray, dst: np.ndarray) -> np.ndarray:
     """Generator-internal identity of a directed edge, used only to reject duplicates."""
-    return (dst.astype(np.uint64) << np.uint64(32)) | src.astype(np.uint64)
+    out = np.empty(src.size, dtype=np.uint64)
+
+    def run(a, b):
+        out[a:b] = (dst[a:b].astype(np.uint64) << np.uint64(32)) | src[a:b].astype(np.uint64)
+
+    _pmap(run, src.size)
+    return out
 
 
-def _unpack(keys: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
-    src = (keys & np.uint64(0xFFFFFFFF)).astype(np.int32)
-    dst = (keys >> np.uint64(32)).astype(np.int32)
+def _unpack(keys: np.ndarray, order: Optional[Tuple[int, int]] = None) -> Tuple[np.ndarray, np.ndarray]:
+    """(src, dst) of packed edges; with order = (a, b) entry i is taken from keys[(a * i + b) % len(keys)]."""
+    n = keys.size
+    src = np.empty(n, dtype=np.int32)
+    dst = np.empty(n, dtype=np.int32)
+
+    def run(lo, hi):
+        k = keys[lo:hi] if order is None else keys[(np.arange(lo, hi, dtype=np.int64) * order[0] + order[1]) % n]
+        src[lo:hi] = (k & np.uint64(0xFFFFFFFF)).astype(np.int32)
+        dst[lo:hi] = (k >> np.uint64(32)).astype(np.int32)
+
+    _pmap(run, n)
     return src, dst
 
 
@@ -139,28 +233,46 @@ class _EndpointSampler:
     def draw(self, rng: np.random.Generator, m: int) -> Tuple[np.ndarray, np.ndarray]:
         if self.cdf is None:
             return (rng.integers(0, self.n, m, dtype=np.int32), rng.integers(0, self.n, m, dtype=np.int32))
-        s = np.minimum(np.searchsorted(self.cdf, rng.random(m)), self.n - 1)
-        d = np.minimum(np.searchsorted(self.cdf, rng.random(m)), self.n - 1)
-        return self.perm[s], self.perm[d]
+        out = []
+        for _ in range(2):
+            u = rng.random(m)
+            ids = np.empty(m, dtype=np.int32)
+
+            def run(a, b):
+                ids[a:b] = self.perm[np.minimum(np.searchsorted(self.cdf, u[a:b]), self.n - 1)]
+
+            _pmap(run, m)
+            out.append(ids)
+        return out[0], out[1]
 
 
-def _draw_new_edges(rng, sampler: _EndpointSampler, need: int, existing_sorted: np.ndarray) -> np.ndarray:
-    """`need` distinct edges, none a self-loop, none in `existing_sorted`; returned sorted."""
+def _draw_round(rng, sampler: _EndpointSampler, m: int):
+    """m endpoint pairs as packed edges without self-loops and repeats: (in draw order, the same values sorted)."""
+    s, d = sampler.draw(rng, m)
+    ok = s != d
+    return _first_occurrences(_pack(s[ok], d[ok]))
+
+
+def _round_size(missing: int) -> int:
+    return int(missing * 1.25) + 64
+
+
+def _draw_new_edges(rng, sampler: _EndpointSampler, need: int, existing_sorted: np.ndarray, first_round=None) -> np.ndarray:
+    """`need` distinct edges, none a self-loop, none in `existing_sorted`; returned sorted.  first_round: the result
+    of _draw_round(rng, sampler, _round_size(need)) if the caller has drawn it already."""
     room = sampler.n * (sampler.n - 1) - existing_sorted.size
     if need > room:
         raise ValueError(f"{need} new edges requested, but only {room} distinct edges without self-loops are left on {sampler.n} nodes")
     got = np.empty(0, dtype=np.uint64)
     while got.size < need:
-        m = int((need - got.size) * 1.25) + 64
-        s, d = sampler.draw(rng, m)
-        ok = s != d
-        k = _pack(s[ok], d[ok])
-        _, first = np.unique(k, return_index=True)
-        k = k[np.sort(first)]  # distinct, in draw order
-        for ref in (existing_sorted, got):
-            if ref.size:
-                pos = np.minimum(np.searchsorted(ref, k), ref.size - 1)
-                k = k[ref[pos] != k]
+        if first_round is not None:
+            k, uk = first_round
+            first_round = None
+        else:
+            k, uk = _draw_round(rng, sampler, _round_size(need - got.size))
+        taken = uk[_in_sorted(existing_sorted, uk) | _in_sorted(got, uk)]
+        if taken.size:
+            k = k[~_in_sorted(taken, k)]
         k = k[: need - got.size]
         got = np.sort(np.concatenate([got, k]))
     return got
@@ -206,6 +318,22 @@ def bf16_bits(x: np.ndarray) -> np.ndarray:
     return (u >> np.uint32(16)).astype(np.uint16)
 
 
+_ROW_BLOCK = 1 << 16
+
+
+def _normal_rows(seed: int, stream: int, n: int, d: int, to_bf16: bool) -> np.ndarray:
+    """[n, d] fp32 N(0,1), drawn in blocks of 65,536 rows, block j from sub-stream j of the Philox key (the blocks
+    are independent of each other, so several threads can draw them)."""
+    x = np.empty((n, d), dtype=np.float32)
+
+    def run(a, b):
+        blk = _rng(seed, stream, a // _ROW_BLOCK).standard_normal((b - a, d), dtype=np.float32)
+        x[a:b] = round_to_bf16(blk) if to_bf16 else blk
+
+    _pmap(run, n, _ROW_BLOCK)
+    return x
+
+
 def make_sequence(wl: Workload, shuffle_edges: bool = True, progress=None) -> SnapshotSequence:
     """Generate the seeded snapshot sequence of a workload.
 
@@ -218,30 +346,43 @@ def make_sequence(wl: Workload, shuffle_edges: bool = True, progress=None) -> Sn
     keys = _draw_new_edges(_rng(wl.seed, _S_GRAPH), sampler, e0, np.empty(0, dtype=np.uint64))
 
     def emit(k: np.ndarray, t: int):
-        if shuffle_edges:
-            k = k[_rng(wl.seed, _S_SHUFFLE, t).permutation(k.size)]
-        return _unpack(k)
+        # The loader's input is an edge list in no particular order: the sorted keys are handed over through a seeded
+        # index map i -> (a i + b) mod E with a coprime to E (a bijection; neighbours in the list are far apart in key
+        # order).  Nothing downstream depends on this order.
+        if not shuffle_edges or k.size < 2:
+            return _unpack(k)
+        r = _rng(wl.seed, _S_SHUFFLE, t)
+        a = int(r.integers(k.size // 3, k.size)) | 1
+        while math.gcd(a, k.size) != 1:
+            a += 2
+        return _unpack(k, (a % k.size, int(r.integers(0, k.size))))
 
     edges = [emit(keys, 0)]
     tell("edges", 0, T)
     t_ins: List[np.ndarray] = [np.empty(0, dtype=np.uint64)]
     t_del: List[np.ndarray] = [np.empty(0, dtype=np.uint64)]
-    for t in range(1, T):
-        rng = _rng(wl.seed, _S_STEP, t)
-        m = int(math.floor(wl.edge_churn * keys.size))
-        drop = np.sort(rng.choice(keys.size, m, replace=False)) if m else np.empty(0, dtype=np.int64)
-        ins = _draw_new_edges(rng, sampler, m, keys)  # rejects anything in E_{t-1}, deleted ones included
-        keep = np.ones(keys.size, dtype=bool)
-        keep[drop] = False
-        t_del.append(keys[drop])
-        t_ins.append(ins)
-        keys = np.sort(np.concatenate([keys[keep], ins]))
-        edges.append(emit(keys, t))
-        tell("edges", t, T)
+    m = int(math.floor(wl.edge_churn * keys.size))  # (the edge count stays the same from step to step)
 
-    x0 = _rng(wl.seed, _S_FEAT0).standard_normal((n, d), dtype=np.float32)
-    if wl.feat_dtype == "bf16":
-        x0 = round_to_bf16(x0)
+    def prepare(t: int):
+        # what step t needs that does not depend on the edges of step t-1: which positions leave, and the first round
+        # of candidate edges.  Each step has its own generator, so the steps can be prepared ahead by other threads.
+        rng = _rng(wl.seed, _S_STEP, t)
+        drop = np.sort(rng.choice(keys.size, m, replace=False)) if m else np.empty(0, dtype=np.int64)
+        return rng, drop, (_draw_round(rng, sampler, _round_size(m)) if m else None)
+
+    with ThreadPoolExecutor(max(1, min(4, _THREADS // 2))) as ahead:
+        prepared = [ahead.submit(prepare, t) for t in range(1, T)]
+        for t in range(1, T):
+            rng, drop, first_round = prepared[t - 1].result()
+            prepared[t - 1] = None
+            ins = _draw_new_edges(rng, sampler, m, keys, first_round)  # rejects anything in E_{t-1}, deleted ones included
+            t_del.append(keys[drop])
+            t_ins.append(ins)
+            keys = _replace_sorted(keys, drop, ins)
+            edges.append(emit(keys, t))
+            tell("edges", t, T)
+
+    x0 = _normal_rows(wl.seed, _S_FEAT0, n, d, wl.feat_dtype == "bf16")
     rows_l = [np.empty(0, dtype=np.int32)]
     vals_l = [np.empty((0, d), dtype=np.float32)]
     for t in range(1, T):
