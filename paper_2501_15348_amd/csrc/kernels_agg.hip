@@ -5,10 +5,10 @@
 //       read and hands them round with lane shuffles; a row of d values is read by LPR = d*sizeof(elem)/16
 //       lanes as one 16-byte load each, so 64/LPR source rows are in flight per load instruction and U of
 //       those instructions are issued back to back.
-//   aggregate_rows_grouped / incremental_rows_grouped : the same sums with one row per group of LPR lanes, for
-//       rows of at most kLongRow entries (the bulk of a power-law graph): more independent chains per wave.
-//   incremental_rows : Eq. 2 in the form  S_t[r] = S_{t-1}[r] + sum_ins Y_{t-1}[u] - sum_del Y_{t-1}[u]
-//       + sum_changed dY[u]  over the rows of R_t only, same lane layout, signed tagged entries.
+//   aggregate_rows_grouped : the same sums with one row per group of LPR lanes, for rows of at most kLongRow
+//       entries (the bulk of a power-law graph): more independent chains per wave.
+//   incremental_segmented : Eq. 2 in the form  S_t[r] = S_{t-1}[r] + sum_ins Y_{t-1}[u] - sum_del Y_{t-1}[u]
+//       + sum_changed dY[u]  over signed tagged entries, the work of a block of rows split by entries.
 //
 // No atomics anywhere: every output row has one writer and a fixed summation order, so results are
 // bit-reproducible from run to run.
@@ -307,186 +307,191 @@ aggregate_long_rows(AggBatch batch, int self_loop)
     }
 }
 
-template <int LPR, bool BF16>
-__global__ void __launch_bounds__(64 * kWavesPerBlock)
-incremental_rows(const int32_t *__restrict__ rows, int64_t n_rows, const int64_t *__restrict__ ent_ptr,
-                 const uint32_t *__restrict__ ent, const void *__restrict__ x_prev, const float *__restrict__ p_prev,
-                 const float *__restrict__ dY, const float *S_prev, float *S_out, const float *__restrict__ q,
-                 float *__restrict__ agg_out)
-{
-    constexpr int VEC = Row<BF16>::kVec;
-    constexpr int D = LPR * VEC;
-    constexpr int G = 64 / LPR;
-    const int lane = threadIdx.x & 63;
-    const int g = lane / LPR, li = lane % LPR;
-    const int64_t w = int64_t(blockIdx.x) * kWavesPerBlock + (threadIdx.x >> 6);
-    if (w >= n_rows) return;
-    const int64_t v = rows[w];
-    const int64_t beg = ent_ptr[v], end = ent_ptr[v + 1];
-    float acc[VEC];
-#pragma unroll
-    for (int i = 0; i < VEC; ++i) acc[i] = 0.0f;
-    for (int64_t base = beg; base < end; base += 64) {
-        const int cnt = int(min(int64_t(64), end - base));
-        uint32_t my_e = 0;
-        float my_sc = 0.0f;
-        if (lane < cnt) {
-            my_e = ent[base + lane];
-            const uint32_t kind = my_e >> kKindShift;
-            if (kind == 2u) {
-                my_sc = 1.0f;
-            } else {
-                my_sc = p_prev ? p_prev[my_e & kPayloadMask] : 1.0f;
-                if (kind == 1u) my_sc = -my_sc;
-            }
-        }
-        for (int k = 0; k < cnt; k += G * kUnroll) {
-            float r[kUnroll][VEC];
-            float sc[kUnroll];
-#pragma unroll
-            for (int j = 0; j < kUnroll; ++j) {
-                const int e = k + j * G + g;
-                const uint32_t en = __shfl(my_e, e & 63);
-                sc[j] = __shfl(my_sc, e & 63);
-                if (e < cnt) {
-                    const int64_t u = en & kPayloadMask;
-                    if constexpr (!BF16) {
-                        // both kinds of source are fp32 rows of the same width: one load from a selected base, not
-                        // two loads under complementary masks
-                        const float *src = (en >> kKindShift) == 2u ? dY : static_cast<const float *>(x_prev);
-                        load_f32<VEC>(src, u, D, li, r[j]);
-                    } else if ((en >> kKindShift) == 2u) {
-                        load_f32<VEC>(dY, u, D, li, r[j]);
-                    } else {
-                        Row<BF16>::load(x_prev, u, D, li, r[j]);
-                    }
-                } else {
-                    sc[j] = 0.0f;
-#pragma unroll
-                    for (int i = 0; i < VEC; ++i) r[j][i] = 0.0f;
-                }
-            }
-#pragma unroll
-            for (int j = 0; j < kUnroll; ++j)
-#pragma unroll
-                for (int i = 0; i < VEC; ++i) acc[i] += sc[j] * r[j][i];
-        }
-    }
-    reduce_groups<LPR, VEC>(acc);
-    if (lane < LPR) {
-        float s[VEC];
-        load_f32<VEC>(S_prev, v, D, lane, s);
-#pragma unroll
-        for (int i = 0; i < VEC; ++i) s[i] += acc[i];
-        store_f32<VEC>(S_out, v, D, lane, s);
-        if (agg_out) {
-            const float qq = q ? q[v] : 1.0f;
-#pragma unroll
-            for (int i = 0; i < VEC; ++i) s[i] *= qq;
-            store_f32<VEC>(agg_out, v, D, lane, s);
-        }
-    }
-}
+// Rows of S a block of incremental_segmented works on: as many as make a 16 KB tile of fp32 sums (16 rows of 256
+// values, 64 rows of 64).  Measured on 2.5e6 rows of 256 bf16 values with 1e7 entries: 8 rows 2.63 ms, 16 rows 2.22 ms,
+// 32 rows 2.47 ms; the smaller tile lets more blocks share a compute unit while they wait in different phases.
+constexpr int inc_rows_per_block(int d) { return 4096 / d < 8 ? 8 : (4096 / d > 256 ? 256 : 4096 / d); }
 
-// Changed rows with at most kLongRow entries, one row per group of LPR lanes (see aggregate_rows_grouped).
+// Eq. 2 in the form  S_t[r] = S_{t-1}[r] + sum_ins Y_{t-1}[u] - sum_del Y_{t-1}[u] + sum_changed dY[u].
+//
+// A block takes RB consecutive rows -- of the whole matrix (rows == null: a new buffer is written, rows without
+// entries are copied through) or of the list R_t (in place) -- whose delta entries are adjacent in `ent`.  The work
+// is split by ENTRIES, not by rows: every group of LPR lanes gets an equal share of the block's entries and walks it
+// eight gathers at a time, whatever rows they belong to, so that a hub row with a thousand entries and a run of rows
+// with one entry each cost the same per entry, and no row pointer -> entry -> source row chain is waited for more
+// than once per block.  A row that ends inside a group's share is summed in registers and put into the block's LDS
+// tile; a row that a share cuts leaves a partial sum in LDS, and the group in whose share the row begins adds the
+// pieces in ascending order (fixed order, no atomics: results are bit-reproducible).  Then all threads stream the
+// block's rows: S_out = S_prev + tile, coalesced.
 template <int LPR, bool BF16>
 __global__ void __launch_bounds__(64 * kWavesPerBlock)
-incremental_rows_grouped(const int32_t *__restrict__ rows, const int64_t *__restrict__ row_ent, int64_t n_rows,
-                         const int64_t *__restrict__ ent_ptr, const uint32_t *__restrict__ ent, const void *__restrict__ x_prev,
-                         const float *__restrict__ p_prev, const float *__restrict__ dY, const float *S_prev, float *S_out,
-                         const float *__restrict__ q, float *__restrict__ agg_out)
+incremental_segmented(const int32_t *__restrict__ rows, const int64_t *__restrict__ ptr, int64_t n_rows,
+                      const uint32_t *__restrict__ ent, const void *__restrict__ x_prev, const float *__restrict__ p_prev,
+                      const float *__restrict__ dY, const float *S_prev, float *S_out, const float *__restrict__ q,
+                      float *__restrict__ agg_out, int copy_unchanged)
 {
     constexpr int VEC = Row<BF16>::kVec;
     constexpr int D = LPR * VEC;
     constexpr int G = 64 / LPR;
-    const int lane = threadIdx.x & 63;
+    constexpr int NG = kWavesPerBlock * G;  // lane groups per block
+    constexpr int RB = inc_rows_per_block(D);
+    constexpr int kThreads = 64 * kWavesPerBlock;
+    constexpr int kU = kUnrollGrouped;  // gathers a lane has in flight (16 spills at 512-byte bf16 rows: 1.5x slower)
+    __shared__ __align__(16) float tile[RB * D];      // delta sums of the block's rows
+    __shared__ __align__(16) float part[NG * D];      // per group: its piece of a row that began in an earlier share
+    __shared__ int32_t part_row[2 * NG];              // [2 g]: the row of that piece; [2 g + 1]: the row that begins in
+                                                      // share g and goes on into later ones (block-local, -1: none)
+    __shared__ int32_t lptr[RB + 1];                  // entry offsets of the block's rows, relative to the first
+    __shared__ int32_t lrow[RB];                      // their row ids
+    const int tid = threadIdx.x, lane = tid & 63;
     const int g = lane / LPR, li = lane % LPR, gbase = g * LPR;
-    const int64_t w = (int64_t(blockIdx.x) * kWavesPerBlock + (threadIdx.x >> 6)) * G + g;
-    const bool live = w < n_rows;
-    int64_t v = 0, beg = 0, end = 0;
-    if (live) {
-        v = rows ? rows[w] : w;  // no row list: every row, so that rows without entries are copied through
-        if (row_ent) {
-            // the listed rows are exactly those with entries, in ascending order: their entries are adjacent, and
-            // the bounds come from the list position, one dependent load earlier than through the row id
-            beg = row_ent[w];
-            end = row_ent[w + 1];
-        } else {
-            beg = ent_ptr[v];
-            end = ent_ptr[v + 1];
+    const int gid = (tid >> 6) * G + g;
+    const int64_t w0 = int64_t(blockIdx.x) * RB;
+    const int nr = int(min(int64_t(RB), n_rows - w0));
+    const int64_t e0 = ptr[w0];
+    for (int i = tid; i <= nr; i += kThreads) lptr[i] = int32_t(ptr[w0 + i] - e0);
+    for (int i = tid; i < nr; i += kThreads) lrow[i] = rows ? rows[w0 + i] : int32_t(w0 + i);
+    for (int i = tid; i < 2 * NG; i += kThreads) part_row[i] = -1;
+    for (int i = tid; i < nr * D / 4; i += kThreads) reinterpret_cast<float4 *>(tile)[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    __syncthreads();
+    const int ne = lptr[nr];
+    const int share = (ne + NG - 1) / NG;
+    const int a = min(gid * share, ne), b = min(a + share, ne);
+    if (a < b) {
+        // the row that holds entry a: lptr[row] <= a < lptr[row + 1]
+        int lo = 0, hi = nr;
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (lptr[mid] <= a)
+                lo = mid;
+            else
+                hi = mid;
         }
-    }
-    const bool mine = live && end - beg <= kLongRow;  // longer rows belong to the wave-per-row pass
-    if (!mine) end = beg;
-    float s_old[VEC];
-    if (mine) load_f32<VEC>(S_prev, v, D, li, s_old);  // issued early: independent of the entry chain
-    float acc[VEC];
+        int row = lo;
+        int row_end = lptr[row + 1];
+        bool began_earlier = lptr[row] < a;
+        float acc[VEC];
 #pragma unroll
-    for (int i = 0; i < VEC; ++i) acc[i] = 0.0f;
-    const int len = int(end - beg);
-    int maxlen = len;
+        for (int i = 0; i < VEC; ++i) acc[i] = 0.0f;
+        auto put = [&](float *dst) {
 #pragma unroll
-    for (int off = LPR; off < 64; off <<= 1) maxlen = max(maxlen, __shfl_xor(maxlen, off));
-    for (int base = 0; base < maxlen; base += LPR) {
-        const int cnt = min(LPR, max(len - base, 0));
-        uint32_t my_e = 0;
-        float my_sc = 0.0f;
-        if (li < cnt) {
-            my_e = ent[beg + base + li];
-            const uint32_t kind = my_e >> kKindShift;
-            if (kind == 2u) {
-                my_sc = 1.0f;
-            } else {
-                my_sc = p_prev ? p_prev[my_e & kPayloadMask] : 1.0f;
-                if (kind == 1u) my_sc = -my_sc;
-            }
-        }
-        const int cmax = min(LPR, maxlen - base);
-        for (int k = 0; k < cmax; k += kUnrollGrouped) {
-            float r[kUnrollGrouped][VEC];
-            float sc[kUnrollGrouped];
-#pragma unroll
-            for (int j = 0; j < kUnrollGrouped; ++j) {
-                const int e = k + j;
-                const uint32_t en = __shfl(my_e, gbase + (e & (LPR - 1)));
-                if (e < cnt) {
-                    const int64_t u = en & kPayloadMask;
-                    if constexpr (!BF16) {
-                        // both kinds of source are fp32 rows of the same width: one load from a selected base, not
-                        // two loads under complementary masks
-                        const float *src = (en >> kKindShift) == 2u ? dY : static_cast<const float *>(x_prev);
-                        load_f32<VEC>(src, u, D, li, r[j]);
-                    } else if ((en >> kKindShift) == 2u) {
-                        load_f32<VEC>(dY, u, D, li, r[j]);
-                    } else {
-                        Row<BF16>::load(x_prev, u, D, li, r[j]);
-                    }
+            for (int i = 0; i < VEC; i += 4)
+                *reinterpret_cast<float4 *>(dst + li * VEC + i) = make_float4(acc[i], acc[i + 1], acc[i + 2], acc[i + 3]);
+        };
+        for (int base = a; base < b; base += LPR) {
+            const int cnt = min(LPR, b - base);
+            uint32_t my_e = 0;
+            float my_sc = 0.0f;
+            if (li < cnt) {
+                my_e = ent[e0 + base + li];
+                const uint32_t kind = my_e >> kKindShift;
+                if (kind == 2u) {
+                    my_sc = 1.0f;
                 } else {
-#pragma unroll
-                    for (int i = 0; i < VEC; ++i) r[j][i] = 0.0f;
+                    my_sc = p_prev ? p_prev[my_e & kPayloadMask] : 1.0f;
+                    if (kind == 1u) my_sc = -my_sc;
                 }
             }
+            for (int k = 0; k < cnt; k += kU) {
+                float r[kU][VEC];
+                float sc[kU];
 #pragma unroll
-            for (int j = 0; j < kUnrollGrouped; ++j) {
-                const int e = k + j;
-                sc[j] = __shfl(my_sc, gbase + (e & (LPR - 1)));
-                if (e >= cnt) sc[j] = 0.0f;
+                for (int j = 0; j < kU; ++j) {
+                    const int e = k + j;
+                    const uint32_t en = __shfl(my_e, gbase + (e & (LPR - 1)));
+                    if (e < cnt) {
+                        const int64_t u = en & kPayloadMask;
+                        if constexpr (!BF16) {
+                            // both kinds of source are fp32 rows of the same width: one load from a selected base
+                            const float *src = (en >> kKindShift) == 2u ? dY : static_cast<const float *>(x_prev);
+                            load_f32<VEC>(src, u, D, li, r[j]);
+                        } else if ((en >> kKindShift) == 2u) {
+                            load_f32<VEC>(dY, u, D, li, r[j]);
+                        } else {
+                            Row<BF16>::load(x_prev, u, D, li, r[j]);
+                        }
+                    }
+                }
+#pragma unroll
+                for (int j = 0; j < kU; ++j) sc[j] = __shfl(my_sc, gbase + ((k + j) & (LPR - 1)));
+#pragma unroll
+                for (int j = 0; j < kU; ++j) {
+                    const int e = k + j;
+                    if (e < cnt) {
+                        if (base + e >= row_end) {  // the current row ended inside this share
+                            if (began_earlier) {
+                                put(part + gid * D);
+                                if (li == 0) part_row[2 * gid] = row;
+                                began_earlier = false;
+                            } else {
+                                put(tile + row * D);
+                            }
+#pragma unroll
+                            for (int i = 0; i < VEC; ++i) acc[i] = 0.0f;
+                            do {
+                                ++row;
+                                row_end = lptr[row + 1];
+                            } while (base + e >= row_end);
+                        }
+#pragma unroll
+                        for (int i = 0; i < VEC; ++i) acc[i] += sc[j] * r[j][i];
+                    }
+                }
             }
-#pragma unroll
-            for (int j = 0; j < kUnrollGrouped; ++j)
-#pragma unroll
-                for (int i = 0; i < VEC; ++i) acc[i] += sc[j] * r[j][i];
+        }
+        // the last row of the share
+        if (began_earlier) {
+            put(part + gid * D);
+            if (li == 0) part_row[2 * gid] = row;
+        } else {
+            put(tile + row * D);  // complete, or the first piece of a row that goes on: only this group writes it
+            if (row_end > b && li == 0) part_row[2 * gid + 1] = row;
         }
     }
-    if (mine) {
+    __syncthreads();
+    {
+        // a row cut by share boundaries: the group it began in adds the pieces, in ascending order
+        const int r = part_row[2 * gid + 1];
+        if (r >= 0) {
+            float sum[VEC];
 #pragma unroll
-        for (int i = 0; i < VEC; ++i) s_old[i] += acc[i];
-        store_f32<VEC>(S_out, v, D, li, s_old);
-        if (agg_out) {
-            const float qq = q ? q[v] : 1.0f;
+            for (int i = 0; i < VEC; ++i) sum[i] = tile[r * D + li * VEC + i];
+            for (int g2 = gid + 1; g2 < NG && part_row[2 * g2] == r; ++g2)
 #pragma unroll
-            for (int i = 0; i < VEC; ++i) s_old[i] *= qq;
-            store_f32<VEC>(agg_out, v, D, li, s_old);
+                for (int i = 0; i < VEC; ++i) sum[i] += part[g2 * D + li * VEC + i];
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) tile[r * D + li * VEC + i] = sum[i];
+        }
+    }
+    __syncthreads();
+    // stream the block's rows: four rows per group in flight
+    constexpr int kRowsInFlight = 4;
+    for (int i0 = gid; i0 < nr; i0 += kRowsInFlight * NG) {
+        float s[kRowsInFlight][VEC];
+        bool act[kRowsInFlight], has[kRowsInFlight];
+#pragma unroll
+        for (int u = 0; u < kRowsInFlight; ++u) {
+            const int i = i0 + u * NG;
+            has[u] = i < nr && lptr[i + 1] > lptr[i];
+            act[u] = i < nr && (copy_unchanged || has[u]);
+            if (act[u]) load_f32<VEC>(S_prev, lrow[i], D, li, s[u]);
+        }
+#pragma unroll
+        for (int u = 0; u < kRowsInFlight; ++u) {
+            const int i = i0 + u * NG;
+            if (!act[u]) continue;
+            const int64_t v = lrow[i];
+            if (has[u]) {  // (a row without entries is copied as it is: bitwise, -0 included)
+#pragma unroll
+                for (int k = 0; k < VEC; ++k) s[u][k] += tile[i * D + li * VEC + k];
+            }
+            store_f32<VEC>(S_out, v, D, li, s[u]);
+            if (agg_out && has[u]) {
+                const float qq = q ? q[v] : 1.0f;
+#pragma unroll
+                for (int k = 0; k < VEC; ++k) s[u][k] *= qq;
+                store_f32<VEC>(agg_out, v, D, li, s[u]);
+            }
         }
     }
 }
@@ -902,23 +907,19 @@ void aggregate_long_dispatch(int lpr, const AggBatch &batch, int32_t max_long, i
 }
 
 template <bool BF16>
-void incremental_dispatch(int lpr, const int32_t *rows, const int64_t *row_ent, int64_t n_rows, const int32_t *long_rows, int64_t n_long,
-                          const int64_t *ent_ptr, const uint32_t *ent, const void *x_prev, const float *p_prev,
-                          const float *dY, const float *S_prev, float *S_out, const float *q, float *agg_out,
-                          hipStream_t s)
+void incremental_dispatch(int lpr, const int32_t *rows, const int64_t *ptr, int64_t n_rows, const uint32_t *ent,
+                          const void *x_prev, const float *p_prev, const float *dY, const float *S_prev, float *S_out,
+                          const float *q, float *agg_out, int copy_unchanged, hipStream_t s, hipEvent_t ev_start,
+                          hipEvent_t ev_stop)
 {
     const dim3 th(64 * kWavesPerBlock);
-    const unsigned long_blocks = unsigned((n_long + kWavesPerBlock - 1) / kWavesPerBlock);
-#define REINC_INC_CASE(L)                                                                                           \
-    case L: {                                                                                                       \
-        const int64_t rows_per_block = int64_t(kWavesPerBlock) * (64 / L);                                          \
-        const unsigned blocks = unsigned((n_rows + rows_per_block - 1) / rows_per_block);                           \
-        incremental_rows_grouped<L, BF16><<<blocks, th, 0, s>>>(rows, rows ? row_ent : nullptr, n_rows, ent_ptr, ent, x_prev, \
-                                                                p_prev, dY, S_prev, S_out, q, agg_out);             \
-        if (n_long > 0)                                                                                             \
-            incremental_rows<L, BF16><<<long_blocks, th, 0, s>>>(long_rows, n_long, ent_ptr, ent, x_prev, p_prev, dY, \
-                                                                 S_prev, S_out, q, agg_out);                        \
-        break;                                                                                                      \
+#define REINC_INC_CASE(L)                                                                                              \
+    case L: {                                                                                                          \
+        constexpr int rb = inc_rows_per_block(L * Row<BF16>::kVec);                                                    \
+        const unsigned blocks = unsigned((n_rows + rb - 1) / rb);                                                      \
+        hipExtLaunchKernelGGL((incremental_segmented<L, BF16>), dim3(blocks), th, 0, s, ev_start, ev_stop, 0, rows,    \
+                              ptr, n_rows, ent, x_prev, p_prev, dY, S_prev, S_out, q, agg_out, copy_unchanged);        \
+        break;                                                                                                         \
     }
     switch (lpr) {
         REINC_INC_CASE(1)
@@ -1048,19 +1049,22 @@ void aggregate_full(reinc_ctx *ctx, const int64_t *ptr, const int32_t *idx, cons
     aggregate_full_batch(ctx, batch, bf16, d, self_loop, s);
 }
 
-void launch_incremental(const int32_t *rows, const int64_t *row_ent, int64_t n_rows, const int32_t *long_rows, int64_t n_long,
-                        const int64_t *ent_ptr, const uint32_t *ent, const void *x_prev, int bf16, const float *p_prev,
-                        const float *dY, int32_t d, const float *S_prev, float *S_out, const float *q, float *agg_out,
-                        hipStream_t s)
+void launch_incremental(const int32_t *rows, const int64_t *row_ent, int64_t n_rows, const int64_t *ent_ptr,
+                        const uint32_t *ent, const void *x_prev, int bf16, const float *p_prev, const float *dY, int32_t d,
+                        const float *S_prev, float *S_out, const float *q, float *agg_out, hipStream_t s, hipEvent_t ev_start,
+                        hipEvent_t ev_stop)
 {
     if (n_rows <= 0) return;
     const int lpr = lanes_per_row(d, bf16);
+    // listed rows: their entries are adjacent, row_ent holds the offsets by list position; every row: ent_ptr by row id
+    const int64_t *ptr = rows ? row_ent : ent_ptr;
+    const int copy_unchanged = rows == nullptr;
     if (bf16)
-        incremental_dispatch<true>(lpr, rows, row_ent, n_rows, long_rows, n_long, ent_ptr, ent, x_prev, p_prev, dY, S_prev, S_out, q,
-                                   agg_out, s);
+        incremental_dispatch<true>(lpr, rows, ptr, n_rows, ent, x_prev, p_prev, dY, S_prev, S_out, q, agg_out, copy_unchanged, s,
+                                   ev_start, ev_stop);
     else
-        incremental_dispatch<false>(lpr, rows, row_ent, n_rows, long_rows, n_long, ent_ptr, ent, x_prev, p_prev, dY, S_prev, S_out, q,
-                                    agg_out, s);
+        incremental_dispatch<false>(lpr, rows, ptr, n_rows, ent, x_prev, p_prev, dY, S_prev, S_out, q, agg_out, copy_unchanged, s,
+                                    ev_start, ev_stop);
 }
 
 void launch_minmax_full(const int64_t *ptr, const int32_t *idx, const int32_t *long_rows, int32_t n_long, const void *X,
