@@ -283,10 +283,12 @@ int reinc_load_features_delta(reinc_ctx *ctx, int32_t t, const int32_t *rows, in
 // ------------------------------------------------------------------------------------------------ deltas
 
 // Scratch one step needs while its deltas are being built (bytes, with the allocator's rounding).
+static uint64_t diff_mask_bytes(int64_t n, int64_t nnz) { return 8 * uint64_t(nnz / 64 + n / 16 + 4); }  // (64-bit words, one spare per block of at least 16 rows)
+
 static uint64_t step_scratch_bytes(int64_t n, int64_t na, int64_t nb)
 {
     auto r = [](int64_t count, int64_t elem) { return (uint64_t(std::max<int64_t>(count, 1)) * elem + 255) & ~uint64_t(255); };
-    return 5 * r(n, 4) + r(na, 4) + 2 * r(nb, 4) + 3 * r(n + 1, 8) + r(na + 1, 8) + 2 * r(nb + 1, 8);
+    return 5 * r(n, 4) + 2 * r(n + 1, 8) + r((n + 63) / 64, 8) + r(diff_mask_bytes(n, na), 1) + 2 * r(diff_mask_bytes(n, nb), 1);
 }
 
 // Builds the deltas of a group of steps.  Every stage runs for all steps of the group before the next stage begins,
@@ -311,123 +313,93 @@ static int build_group(reinc_ctx *ctx, const std::vector<int32_t> &steps, hipStr
     };
     auto i32s = [&](int64_t c) { return static_cast<int32_t *>(ctx->scratch(uint64_t(std::max<int64_t>(c, 1)) * 4)); };
     auto i64s = [&](int64_t c) { return static_cast<int64_t *>(ctx->scratch(uint64_t(std::max<int64_t>(c, 1)) * 8)); };
-    struct Work {
-        int32_t *cflags, *cindex, *row_flag, *long_flag, *absent_a, *absent_b, *hit_b;
-        int64_t *coffs, *roffs, *loffs, *pos_del, *pos_ins, *pos_hit;
-    };
-    std::vector<Work> work(G);
-    // job tables of the three scan stages and the table of totals, built up front (every address is known once the
-    // scratch and the row pointers are allocated) and uploaded in one copy
-    std::vector<ScanJob> jobs;
-    jobs.reserve(size_t(6) * G);
-    int64_t tiles[3] = {0, 0, 0};
-    int first_job[4] = {0, 0, 0, 0};
-    bool ok = true;
-    for (int g = 0; g < G; ++g) {
-        const Snapshot &a = ctx->snaps[steps[g] - 1], &b = ctx->snaps[steps[g]];
-        Work &w = work[g];
-        w.cflags = i32s(n), w.cindex = i32s(n), w.row_flag = i32s(n), w.long_flag = i32s(n);
-        w.absent_a = i32s(a.nnz), w.absent_b = i32s(b.nnz), w.hit_b = i32s(b.nnz);
-        w.coffs = i64s(n + 1), w.roffs = i64s(n + 1), w.loffs = i64s(n + 1);
-        w.pos_del = i64s(a.nnz + 1), w.pos_ins = i64s(b.nnz + 1), w.pos_hit = i64s(b.nnz + 1);
-        ok = ok && w.cflags && w.cindex && w.row_flag && w.long_flag && w.absent_a && w.absent_b && w.hit_b && w.coffs && w.roffs &&
-             w.loffs && w.pos_del && w.pos_ins && w.pos_hit;
-        Delta &dl = ctx->deltas[steps[g]];
-        dl.ins_ptr = static_cast<int64_t *>(ctx->alloc(uint64_t(n + 1) * 8));
-        dl.del_ptr = static_cast<int64_t *>(ctx->alloc(uint64_t(n + 1) * 8));
-        dl.ent_ptr = static_cast<int64_t *>(ctx->alloc(uint64_t(n + 1) * 8));
-        ok = ok && dl.ins_ptr && dl.del_ptr && dl.ent_ptr;
-    }
-    if (!ok) return nomem("scratch and row pointers");
-    // the per-step table for the batched stage kernels
+    // the per-step table for the batched stage kernels: inputs, scratch, and the row pointers of the outputs
     std::vector<DiffStep> table(G);
-    int64_t max_a = 0, max_b = 0, max_list = 0;
-    bool compare_features = false;
+    int64_t max_list = 0;
+    bool compare_features = false, ok = true;
     for (int g = 0; g < G; ++g) {
         const Snapshot &a = ctx->snaps[steps[g] - 1], &b = ctx->snaps[steps[g]];
-        const Work &w = work[g];
-        const Delta &dl = ctx->deltas[steps[g]];
+        Delta &dl = ctx->deltas[steps[g]];
         DiffStep &st = table[g];
         st = DiffStep{};
-        st.rowid_a = a.rowid, st.col_a = a.col, st.rowid_b = b.rowid, st.col_b = b.col;
-        st.rp_a = a.row_ptr, st.rp_b = b.row_ptr;
-        st.na = a.nnz, st.nb = b.nnz;
+        st.col_a = a.col, st.col_b = b.col, st.rp_a = a.row_ptr, st.rp_b = b.row_ptr;
         st.x_a = a.x, st.x_b = b.x, st.p_a = a.p, st.p_b = b.p;
         st.feat_rows = b.feats_from_delta ? b.feat_rows : nullptr;
         st.n_feat_rows = b.feats_from_delta ? b.n_feat_rows : 0;
-        st.cflags = w.cflags, st.cindex = w.cindex, st.row_flag = w.row_flag, st.long_flag = w.long_flag;
-        st.absent_a = w.absent_a, st.absent_b = w.absent_b, st.hit_b = w.hit_b;
-        st.coffs = w.coffs, st.roffs = w.roffs, st.loffs = w.loffs;
-        st.pos_del = w.pos_del, st.pos_ins = w.pos_ins, st.pos_hit = w.pos_hit;
+        st.cflags = i32s(n), st.cnt_ins = i32s(n), st.cnt_del = i32s(n), st.cnt_ent = i32s(n), st.row_flag = i32s(n);
+        st.coffs = i64s(n + 1), st.roffs = i64s(n + 1);
+        st.bits = reinterpret_cast<uint64_t *>(i64s((n + 63) / 64));
+        st.mask_del = static_cast<uint64_t *>(ctx->scratch(diff_mask_bytes(n, a.nnz)));
+        st.mask_ins = static_cast<uint64_t *>(ctx->scratch(diff_mask_bytes(n, b.nnz)));
+        st.mask_hit = static_cast<uint64_t *>(ctx->scratch(diff_mask_bytes(n, b.nnz)));
+        dl.ins_ptr = static_cast<int64_t *>(ctx->alloc(uint64_t(n + 1) * 8));
+        dl.del_ptr = static_cast<int64_t *>(ctx->alloc(uint64_t(n + 1) * 8));
+        dl.ent_ptr = static_cast<int64_t *>(ctx->alloc(uint64_t(n + 1) * 8));
         st.ins_ptr = dl.ins_ptr, st.del_ptr = dl.del_ptr, st.ent_ptr = dl.ent_ptr;
-        max_a = std::max(max_a, a.nnz);
-        max_b = std::max(max_b, b.nnz);
+        ok = ok && st.cflags && st.cnt_ins && st.cnt_del && st.cnt_ent && st.row_flag && st.coffs && st.roffs && st.bits &&
+             st.mask_del && st.mask_ins && st.mask_hit && dl.ins_ptr && dl.del_ptr && dl.ent_ptr;
         max_list = std::max(max_list, st.n_feat_rows);
         compare_features = compare_features || !b.feats_from_delta;
     }
+    if (!ok) return nomem("scratch and row pointers");
     DiffStep *table_dev = static_cast<DiffStep *>(ctx->scratch(table.size() * sizeof(DiffStep)));
     if (!table_dev) return nomem("step table");
     const int sym = ctx->cfg.agg_kind == REINC_AGG_SYM;
+    // job tables of the two scan stages and the table of totals, built up front and uploaded in one copy
+    std::vector<ScanJob> jobs;
+    jobs.reserve(size_t(5) * G);
+    int64_t tiles[2] = {0, 0};
     auto add_job = [&](int stage, const int32_t *in, int64_t *out, int64_t count) {
         jobs.push_back(ScanJob{in, out, count, tiles[stage]});
         tiles[stage] += scan_tiles(count);
     };
-    for (int g = 0; g < G; ++g) add_job(0, work[g].cflags, work[g].coffs, n);
-    first_job[1] = int(jobs.size());
+    for (int g = 0; g < G; ++g) add_job(0, table[g].cflags, table[g].coffs, n);
+    const int first_job1 = int(jobs.size());
     for (int g = 0; g < G; ++g) {
-        const Snapshot &a = ctx->snaps[steps[g] - 1], &b = ctx->snaps[steps[g]];
-        add_job(1, work[g].absent_a, work[g].pos_del, a.nnz);
-        add_job(1, work[g].absent_b, work[g].pos_ins, b.nnz);
-        add_job(1, work[g].hit_b, work[g].pos_hit, b.nnz);
+        add_job(1, table[g].cnt_ins, table[g].ins_ptr, n);
+        add_job(1, table[g].cnt_del, table[g].del_ptr, n);
+        add_job(1, table[g].cnt_ent, table[g].ent_ptr, n);
+        add_job(1, table[g].row_flag, table[g].roffs, n);
     }
-    first_job[2] = int(jobs.size());
-    for (int g = 0; g < G; ++g) {
-        add_job(2, work[g].row_flag, work[g].roffs, n);
-        add_job(2, work[g].long_flag, work[g].loffs, n);
-    }
-    first_job[3] = int(jobs.size());
-    constexpr int kTotals = 6;  // per step: inserted, deleted, entries, changed rows of S, changed nodes, long rows
+    constexpr int kTotals = 5;  // per step: inserted, deleted, entries, changed rows of S, changed nodes
     std::vector<const int64_t *> total_ptrs(size_t(kTotals) * G);
     for (int g = 0; g < G; ++g) {
-        const Delta &dl = ctx->deltas[steps[g]];
-        const int64_t *p[kTotals] = {dl.ins_ptr + n, dl.del_ptr + n, dl.ent_ptr + n, work[g].roffs + n, work[g].coffs + n, work[g].loffs + n};
+        const DiffStep &st = table[g];
+        const int64_t *p[kTotals] = {st.ins_ptr + n, st.del_ptr + n, st.ent_ptr + n, st.roffs + n, st.coffs + n};
         std::copy(p, p + kTotals, total_ptrs.begin() + size_t(kTotals) * g);
     }
-    const int64_t max_tiles = std::max(tiles[0], std::max(tiles[1], tiles[2]));
     ScanJob *jobs_dev = static_cast<ScanJob *>(ctx->scratch(jobs.size() * sizeof(ScanJob)));
     const int64_t **ptrs_dev = static_cast<const int64_t **>(ctx->scratch(total_ptrs.size() * sizeof(int64_t *)));
     int64_t *totals_dev = i64s(int64_t(kTotals) * G);
-    int64_t *tile_sums = i64s(max_tiles);
+    int64_t *tile_sums = i64s(std::max(tiles[0], tiles[1]));
     if (!jobs_dev || !ptrs_dev || !totals_dev || !tile_sums) return nomem("scan tables");
     REINC_HIP(ctx, hipMemcpyAsync(jobs_dev, jobs.data(), jobs.size() * sizeof(ScanJob), hipMemcpyHostToDevice, s));
     REINC_HIP(ctx, hipMemcpyAsync(ptrs_dev, total_ptrs.data(), total_ptrs.size() * sizeof(int64_t *), hipMemcpyHostToDevice, s));
-
     REINC_HIP(ctx, hipMemcpyAsync(table_dev, table.data(), table.size() * sizeof(DiffStep), hipMemcpyHostToDevice, s));
     auto stage = [&](int which, int64_t max_changed) {
-        launch_diff_stage(which, table_dev, G, n, max_a, max_b, max_list, max_changed, sym, ctx->cfg.self_loop, bf16, d, s);
+        launch_diff_stage(which, table_dev, G, n, max_list, max_changed, sym, ctx->cfg.self_loop, bf16, d, s);
     };
-    // stage 1: change sets C_t (steps whose features were loaded whole are compared row by row)
-    stage(0, 0);
-    if (compare_features)
-        for (int g = 0; g < G; ++g) {
-            const Snapshot &a = ctx->snaps[steps[g] - 1], &b = ctx->snaps[steps[g]];
-            if (!b.feats_from_delta) launch_feature_flags_compare(a.x, b.x, n, d * ctx->elem_bytes(), work[g].cflags, s);
-        }
-    launch_multi_scan(jobs_dev + first_job[0], first_job[1] - first_job[0], tiles[0], tile_sums, s);
-    // stage 2: per-edge flags (one thread per edge); their prefix sums are the output positions
     {
         ProfScope prof(ctx, REINC_K_DIFF, s);
+        // stage 0: change sets C_t (steps whose features were loaded whole are compared row by row)
+        stage(0, 0);
+        if (compare_features)
+            for (int g = 0; g < G; ++g) {
+                const Snapshot &a = ctx->snaps[steps[g] - 1], &b = ctx->snaps[steps[g]];
+                if (!b.feats_from_delta) launch_feature_flags_compare(a.x, b.x, n, d * ctx->elem_bytes(), table[g].cflags, s);
+            }
+        launch_multi_scan(jobs_dev, first_job1, tiles[0], tile_sums, s);
+        // stage 1: per row, how many edges were inserted and deleted and how many entries the merged row gets; their
+        // prefix sums over the rows are the row pointers of the outputs
         stage(1, 0);
+        launch_multi_scan(jobs_dev + first_job1, int(jobs.size()) - first_job1, tiles[1], tile_sums, s);
     }
-    launch_multi_scan(jobs_dev + first_job[1], first_job[2] - first_job[1], tiles[1], tile_sums, s);
-    // stage 3: row pointers of the three outputs, rows that change, rows with many entries
-    stage(2, 0);
-    launch_multi_scan(jobs_dev + first_job[2], first_job[3] - first_job[2], tiles[2], tile_sums, s);
     launch_gather_i64(ptrs_dev, kTotals * G, totals_dev, s);
     std::vector<int64_t> totals(size_t(kTotals) * G);
     REINC_HIP(ctx, hipMemcpyAsync(totals.data(), totals_dev, totals.size() * 8, hipMemcpyDeviceToHost, s));
     REINC_HIP(ctx, hipStreamSynchronize(s));
-    // stage 4: outputs of the sizes just learnt
+    // stage 2: outputs of the sizes just learnt
+    int64_t max_changed = 0;
     for (int g = 0; g < G; ++g) {
         const int64_t *tt = &totals[size_t(kTotals) * g];
         Delta &dl = ctx->deltas[steps[g]];
@@ -439,24 +411,17 @@ static int build_group(reinc_ctx *ctx, const std::vector<int32_t> &steps, hipStr
         dl.ent = static_cast<uint32_t *>(take(tt[2], 4));
         dl.rows = static_cast<int32_t *>(take(tt[3], 4));
         dl.row_ent = static_cast<int64_t *>(take(tt[3] + 1, 8));
-        dl.long_rows = static_cast<int32_t *>(take(tt[5], 4));
-        dl.n_long_rows = tt[5];
-        if (!dl.changed || !dl.dY || !dl.ins_col || !dl.del_col || !dl.ent || !dl.rows || !dl.row_ent || !dl.long_rows)
-            return nomem("delta entries");
-    }
-    int64_t max_changed = 0;
-    for (int g = 0; g < G; ++g) {
-        const Delta &dl = ctx->deltas[steps[g]];
+        if (!dl.changed || !dl.dY || !dl.ins_col || !dl.del_col || !dl.ent || !dl.rows || !dl.row_ent) return nomem("delta entries");
         DiffStep &st = table[g];
         st.ins_col = dl.ins_col, st.del_col = dl.del_col, st.ent = dl.ent;
-        st.rows = dl.rows, st.row_ent = dl.row_ent, st.long_rows = dl.long_rows, st.changed = dl.changed, st.dY = dl.dY;
-        st.n_changed = totals[size_t(kTotals) * g + 4];
+        st.rows = dl.rows, st.row_ent = dl.row_ent, st.changed = dl.changed, st.dY = dl.dY;
+        st.n_changed = tt[4];
         max_changed = std::max(max_changed, st.n_changed);
     }
     REINC_HIP(ctx, hipMemcpyAsync(table_dev, table.data(), table.size() * sizeof(DiffStep), hipMemcpyHostToDevice, s));
     {
         ProfScope prof(ctx, REINC_K_DIFF, s);
-        stage(3, max_changed);
+        stage(2, max_changed);
     }
     REINC_HIP(ctx, hipGetLastError());
     REINC_HIP(ctx, hipStreamSynchronize(s));
@@ -495,7 +460,7 @@ static int build_steps(reinc_ctx *ctx, const std::vector<int32_t> &todo, hipStre
             const Snapshot &a = ctx->snaps[t - 1], &b = ctx->snaps[t];
             const uint64_t persistent = 4 * uint64_t(n + 1) * 8 + uint64_t(2 * a.nnz + 3 * b.nnz + 4 * n) * 4 +
                                         uint64_t(n) * ctx->cfg.dims[0] * 4 + 16 * 256;
-            const uint64_t tables = uint64_t(a.nnz + 2 * b.nnz + 2 * n) / 256 + 4096;  // tile sums, job and pointer tables
+            const uint64_t tables = uint64_t(4 * n) / 256 + 4096;  // tile sums, job and pointer tables
             const uint64_t need = step_scratch_bytes(n, a.nnz, b.nnz) + persistent + tables;
             if (!group.empty() && used + need > room) break;
             used += need;
@@ -632,10 +597,10 @@ int reinc_aggregate_incremental(reinc_ctx *ctx, int32_t t, const float *S_prev, 
     }
     {
         // in place: the rows of R_t; to a new buffer: one pass over every row (rows without entries are copied)
-        ProfScope prof(ctx, REINC_K_AGG_INC, as_stream(stream));
-        launch_incremental(in_place ? dl.rows : nullptr, dl.row_ent, in_place ? dl.info.n_rows : ctx->N(), dl.long_rows, dl.n_long_rows,
-                           dl.ent_ptr, dl.ent, pv.x, ctx->cfg.feat_dtype == REINC_BF16, pv.p, dl.dY, d, S_prev, S_out, sn.q,
-                           agg_out, as_stream(stream));
+        ProfScope prof(ctx, REINC_K_AGG_INC, as_stream(stream), true);
+        launch_incremental(in_place ? dl.rows : nullptr, dl.row_ent, in_place ? dl.info.n_rows : ctx->N(), dl.ent_ptr, dl.ent, pv.x,
+                           ctx->cfg.feat_dtype == REINC_BF16, pv.p, dl.dY, d, S_prev, S_out, sn.q, agg_out, as_stream(stream),
+                           prof.start(), prof.stop());
     }
     REINC_HIP(ctx, hipGetLastError());
     ctx->stats.delta_entries_processed += dl.info.n_entries;

@@ -63,8 +63,6 @@ struct Delta {
     uint32_t *ent = nullptr;     // [n_entries]
     int32_t *rows = nullptr;     // R_t [n_rows]
     int64_t *row_ent = nullptr;    // [n_rows + 1]: ent_ptr of the listed rows (their entries are adjacent)
-    int32_t *long_rows = nullptr;  // rows of R_t with more than kLongRow entries
-    int64_t n_long_rows = 0;
     int32_t *changed = nullptr;  // C_t [n_changed]
     float *dY = nullptr;         // [n_changed, d0] fp32
 };
@@ -131,7 +129,8 @@ struct reinc_ctx {
     uint64_t local_reserved = 0;  // bytes at the top of the arena held by the local cache
     bool local_valid = false;
     int64_t local_top = -1;  // row count the top quantities of the local cache are placed for (see place_top)
-    int32_t local_t0 = -1, local_L = 0;
+    int32_t local_t0 = -1, local_L = 0;  // start of the window the local cache holds; the longest window it is carved for
+    int32_t local_len = 0;               // length of the window it holds (the last forward call's)
     int local_kind = 0;  // which model carved the local cache: 0 = stacked (GCN layers, then the cell), 1 = integrated
     float *zero_state = nullptr;  // [N, H] zeros: the recurrent state before the first timestep of a window
     float *q_block = nullptr;     // [T, N] target-side degree scales of all snapshots (null for SUM)
@@ -265,27 +264,33 @@ void launch_multi_scan(const ScanJob *jobs_dev, int njobs, int64_t total_tiles, 
 // Everything the diff builder needs for one pair of consecutive snapshots (a = t-1, b = t): inputs, scratch, outputs.
 // A table of these in device memory lets one launch work on many pairs (blockIdx.y picks the pair).
 struct DiffStep {
-    const int32_t *rowid_a, *col_a, *rowid_b, *col_b;
+    const int32_t *col_a, *col_b;
     const int64_t *rp_a, *rp_b;
-    int64_t na, nb;
     const void *x_a, *x_b;
     const float *p_a, *p_b;
     const int32_t *feat_rows;  // rows re-assigned at t (delta-mode loading), or null
     int64_t n_feat_rows;
-    int32_t *cflags, *cindex, *row_flag, *long_flag, *absent_a, *absent_b, *hit_b;
-    int64_t *coffs, *roffs, *loffs, *pos_del, *pos_ins, *pos_hit;
+    // scratch: change-set flags and their prefix sums, the change set as a bit per node, four counts per row and the
+    // prefix sums of the last (changed rows), the per-entry flag bits
+    int32_t *cflags;
+    int64_t *coffs;
+    uint64_t *bits;
+    int32_t *cnt_ins, *cnt_del, *cnt_ent, *row_flag;
+    int64_t *roffs;
+    uint64_t *mask_ins, *mask_del, *mask_hit;  // a bit per entry: absent from the other snapshot / source in the change set
+    // outputs
     int64_t *ins_ptr, *del_ptr, *ent_ptr;
     int32_t *ins_col, *del_col;
     uint32_t *ent;
-    int32_t *rows, *long_rows, *changed;
+    int32_t *rows, *changed;
     int64_t *row_ent;
     float *dY;
     int64_t n_changed;
 };
-// stage 0: change-set flags; 1: per-edge flags; 2: row pointers and row flags; 3: lists, dY, entries.  The prefix sums
-// between the stages are the caller's.  max_*: the largest count of any pair (the grid covers it).
-void launch_diff_stage(int stage, const DiffStep *steps_dev, int count, int64_t n, int64_t max_a, int64_t max_b, int64_t max_list,
-                       int64_t max_changed, int sym, int self_loop, int bf16, int32_t d, hipStream_t s);
+// stage 0: change-set flags; 1: the change set as bits and the per-row counts; 2: every output.  The prefix sums
+// between the stages are the caller's.  max_list / max_changed: the largest count of any pair (the grid covers it).
+void launch_diff_stage(int stage, const DiffStep *steps_dev, int count, int64_t n, int64_t max_list, int64_t max_changed, int sym,
+                       int self_loop, int bf16, int32_t d, hipStream_t s);
 // dst[i] = *src_dev[i] for i < count (src_dev: pointer table in device memory)
 void launch_gather_i64(const int64_t *const *src_dev, int count, int64_t *dst, hipStream_t s);
 void launch_fill_i32(int32_t *p, int64_t n, int32_t v, hipStream_t s);
@@ -339,12 +344,13 @@ void launch_minmax_incremental(const int32_t *rows, int64_t n_rows, const int32_
                                const int32_t *idx, const void *x_cur, int bf16, int32_t d, int self_loop, int is_max,
                                const float *M_prev, const int32_t *C_prev, float *M_out, int32_t *C_out, int32_t *hub_flags,
                                int32_t *block_counts, int32_t *stat_out, hipStream_t s);
-// rows: every changed row (those of at most kLongRow entries are taken one per lane group), row_ent: where the entries
-// of the i-th listed row begin ([n_rows + 1]; optional); long_rows: the changed rows with more entries (one wavefront each)
-void launch_incremental(const int32_t *rows, const int64_t *row_ent, int64_t n_rows, const int32_t *long_rows, int64_t n_long,
-                        const int64_t *ent_ptr, const uint32_t *ent, const void *x_prev, int bf16, const float *p_prev,
-                        const float *dY, int32_t d, const float *S_prev, float *S_out, const float *q, float *agg_out,
-                        hipStream_t s);
+// Eq. 2 over the merged signed delta rows.  rows != null: the listed rows only (in place), row_ent [n_rows + 1] = where
+// the entries of the i-th listed row begin; rows == null: every row 0 .. n_rows-1 through ent_ptr, rows without
+// entries are copied from S_prev to S_out.  ev_start / ev_stop (optional) are stamped with the kernel's begin and end.
+void launch_incremental(const int32_t *rows, const int64_t *row_ent, int64_t n_rows, const int64_t *ent_ptr,
+                        const uint32_t *ent, const void *x_prev, int bf16, const float *p_prev, const float *dY, int32_t d,
+                        const float *S_prev, float *S_out, const float *q, float *agg_out, hipStream_t s,
+                        hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr);
 
 // ---- kernels_dense.hip
 // out[n,M] = epilogue((row_scale .* A)[n,K] * B[K,M]); B = W (ldw = row stride) or W^T when w_transposed.

@@ -294,23 +294,6 @@ __global__ void long_flags(const int64_t *ptr, int64_t n, int32_t *flag)
     if (v < n) flag[v] = ptr[v + 1] - ptr[v] > kLongRow;
 }
 
-// ---- snapshot diff, one thread per edge -----------------------------------------------------------------
-// Every edge of one snapshot looks itself up in the same row of the other snapshot (binary search over that
-// row's sorted columns).  Work is per edge, so a hub row costs no more per element than a short one and the
-// launch has no long tail; consecutive threads share a row, so the row bounds and the top probes hit in cache.
-__device__ inline bool row_find(const int32_t *col, int64_t beg, int64_t end, int32_t key)
-{
-    int64_t lo = beg, hi = end;
-    while (lo < hi) {
-        int64_t mid = (lo + hi) >> 1;
-        if (col[mid] < key)
-            lo = mid + 1;
-        else
-            hi = mid;
-    }
-    return lo < end && col[lo] == key;
-}
-
 // X[rows[r]] = vals[r], rows of `chunks` 16-byte pieces
 __global__ void length_keys(const int64_t *ptr, int64_t n, uint64_t *keys)
 {
@@ -332,12 +315,24 @@ __device__ inline float bf16_to_f32(uint16_t b) { return __uint_as_float(uint32_
 
 inline unsigned blocks_for(int64_t n, int threads) { return unsigned((n + threads - 1) / threads); }
 
-// ---- the diff builder's stages, for many snapshot pairs in one launch: blockIdx.y picks the pair ----------------
-// Each stage kernel does everything of that stage that is independent per element (node or edge); the stages are
-// separated by the prefix sums, which turn per-element flags into output positions (so the outputs are ordered and
-// duplicate-free without any per-row counting).
+// ---- the diff builder, for many snapshot pairs in one launch: blockIdx.y picks the pair -------------------------
+// Two consecutive snapshots are two CSRs with ascending columns, i.e. two sorted lists of edge keys.  A block takes
+// kDiffRows consecutive rows: their entries are one contiguous piece of each column list, which the block loads
+// once, coalesced, into LDS (up to kDiffCap entries each; a block whose rows hold more, around a hub, searches
+// the lists in global memory instead).  Every entry then looks itself up in the same row of the other snapshot --
+// a bisection in LDS: absent entries of t are inserted edges, absent entries of t-1 deleted ones, and an entry of t
+// whose source is in the change set is a feature-change entry.  Pass 1 leaves four counts per ROW (inserted, deleted,
+// all entries, row changes at all) and one BIT per entry and kind; prefix sums over the N rows give the row pointers
+// of the three outputs; pass 2 reads the bits and writes every flagged entry where the row pointers and a running
+// count inside the block put it (the outputs are row-major, so positions only grow through a block).
+constexpr int kDiffRows = 64;  // (at most 64: one wavefront scans a block's per-row counts)
+// 2048 entries of each list keep a block at 17 KB of LDS, so that eight blocks share a compute unit (with 4096: four
+// blocks, and pass 1 took 1.5 times as long: it waits on dependent LDS reads)
+constexpr int kDiffCap = 2048;
+constexpr int kDiffThreads = 256;
+constexpr int kDiffItems = 8;  // consecutive entries a thread takes per round of pass 2
 
-// stage 1a: cflags[v] = degree of v changed (SYM only: its normalised features change), else 0
+// stage 0a: cflags[v] = degree of v changed (SYM only: its normalised features change), else 0
 __global__ void steps_init_flags(const DiffStep *steps, int64_t n, int sym)
 {
     const DiffStep &st = steps[blockIdx.y];
@@ -350,72 +345,321 @@ __global__ void steps_init_flags(const DiffStep *steps, int64_t n, int sym)
                                            : (sym && (st.rp_a[v + 1] - st.rp_a[v]) != (st.rp_b[v + 1] - st.rp_b[v]));
 }
 
-// stage 1b: rows whose features were re-assigned (delta-mode loading keeps their list)
-__global__ void steps_flags_list(const DiffStep *steps)
+// stage 0b: rows whose features were re-assigned (delta-mode loading keeps their list) and really differ from the
+// row before (the change set is defined by the values, not by the list): one thread per 16-byte piece of a listed row
+__global__ void steps_flags_list(const DiffStep *steps, int32_t chunks)
 {
     const DiffStep &st = steps[blockIdx.y];
     const int64_t i = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
-    if (st.feat_rows && i < st.n_feat_rows) st.cflags[st.feat_rows[i]] = 1;
+    if (!st.feat_rows || i >= st.n_feat_rows * chunks) return;
+    const int64_t r = i / chunks;
+    const int64_t at = int64_t(st.feat_rows[r]) * chunks + (i - r * chunks);
+    const uint4 x = static_cast<const uint4 *>(st.x_a)[at], y = static_cast<const uint4 *>(st.x_b)[at];
+    if (x.x != y.x || x.y != y.y || x.z != y.z || x.w != y.w) st.cflags[st.feat_rows[r]] = 1;
 }
 
-// stage 2: threads [0, na) take the edges of t-1, threads [na, na + nb) those of t
-__global__ void steps_edge_flags(const DiffStep *steps)
+// stage 1a: the change set as one bit per node (64 nodes per word: small enough to stay in the L2 while every edge
+// looks its source up)
+__global__ void steps_bits(const DiffStep *steps, int64_t n)
 {
     const DiffStep &st = steps[blockIdx.y];
-    int64_t e = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
-    if (e < st.na) {
-        const int32_t v = st.rowid_a[e], u = st.col_a[e];
-        st.absent_a[e] = !row_find(st.col_b, st.rp_b[v], st.rp_b[v + 1], u);
-        return;
+    const int64_t v = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
+    const unsigned long long m = __ballot(v < n && st.cflags[v] != 0);
+    if ((threadIdx.x & 63) == 0 && v < n) st.bits[v >> 6] = m;
+}
+
+__device__ inline bool bit_of(const uint64_t *bits, int64_t u) { return (bits[u >> 6] >> (u & 63)) & 1; }
+
+// the row that holds entry e: off[r] <= e < off[r + 1]  (off ascending, off[0] = 0, e < off[nr])
+__device__ inline int row_of(const int32_t *off, int nr, int e)
+{
+    int lo = 0, hi = nr;
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (off[mid] <= e)
+            lo = mid;
+        else
+            hi = mid;
     }
-    e -= st.na;
-    if (e >= st.nb) return;
-    const int32_t v = st.rowid_b[e], u = st.col_b[e];
-    st.absent_b[e] = !row_find(st.col_a, st.rp_a[v], st.rp_a[v + 1], u);
-    st.hit_b[e] = st.cflags[u] != 0;
+    return lo;
 }
 
-// stage 3a: row pointers of the three outputs
-__global__ void steps_row_ptrs(const DiffStep *steps, int64_t n, int self_loop)
+// Is `key` in the ascending list col[beg, end)?  The search starts at position `hint` and gallops away from it before
+// it bisects: between consecutive snapshots most of a row is unchanged, so an entry sits within a few places of where
+// it sits in the other snapshot's row, and one or two probes settle it.
+__device__ inline bool sorted_has(const int32_t *col, int beg, int end, int hint, int32_t key)
 {
-    const DiffStep &st = steps[blockIdx.y];
-    const int64_t v = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
-    if (v > n) return;
-    const int64_t i = st.pos_ins[st.rp_b[v]], d = st.pos_del[st.rp_a[v]];
-    st.ins_ptr[v] = i;
-    st.del_ptr[v] = d;
-    st.ent_ptr[v] = i + d + st.pos_hit[st.rp_b[v]] + (self_loop ? st.coffs[v] : 0);
-}
-
-// stage 3b: rows that change at all, rows with many entries
-__global__ void steps_row_flags(const DiffStep *steps, int64_t n)
-{
-    const DiffStep &st = steps[blockIdx.y];
-    const int64_t v = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
-    if (v >= n) return;
-    const int64_t len = st.ent_ptr[v + 1] - st.ent_ptr[v];
-    st.row_flag[v] = len > 0;
-    st.long_flag[v] = len > kLongRow;
-}
-
-// stage 4a: the three lists of nodes (changed nodes with their index, changed rows, long rows)
-__global__ void steps_compact(const DiffStep *steps, int64_t n)
-{
-    const DiffStep &st = steps[blockIdx.y];
-    const int64_t v = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
-    if (v >= n) return;
-    const bool c = st.cflags[v] != 0;
-    if (c) st.changed[st.coffs[v]] = int32_t(v);
-    st.cindex[v] = c ? int32_t(st.coffs[v]) : -1;
-    if (st.row_flag[v]) {
-        st.rows[st.roffs[v]] = int32_t(v);
-        st.row_ent[st.roffs[v]] = st.ent_ptr[v];
+    if (beg >= end) return false;
+    int p = min(max(hint, beg), end - 1);
+    int32_t c = col[p];
+    if (c == key) return true;
+    int lo, hi;  // the key, if present, lies in [lo, hi)
+    if (c < key) {
+        lo = p + 1;
+        int step = 1;
+        hi = lo;
+        while (hi < end && col[hi] < key) {
+            lo = hi + 1;
+            hi += step;
+            step <<= 1;
+        }
+        hi = min(hi + 1, end);
+    } else {
+        hi = p;
+        int step = 1;
+        lo = hi;
+        while (lo > beg && col[lo - 1] > key) {
+            hi = lo - 1;
+            lo -= step;
+            step <<= 1;
+        }
+        lo = max(lo - 1, beg);
     }
-    if (v == n - 1) st.row_ent[st.roffs[n]] = st.ent_ptr[n];
-    if (st.long_flag[v]) st.long_rows[st.loffs[v]] = int32_t(v);
+    while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (col[mid] < key)
+            lo = mid + 1;
+        else
+            hi = mid;
+    }
+    return lo < end && col[lo] == key;
 }
 
-// stage 4b: dY rows of the changed nodes
+// what a block of the diff kernels keeps in LDS
+struct DiffTile {
+    int32_t offa[kDiffRows + 1], offb[kDiffRows + 1];  // entry offsets of the block's rows, relative to the first
+    int32_t la[kDiffCap], lb[kDiffCap];                // the column lists (when both fit)
+};
+
+// loads the offsets and, if both pieces fit, the column lists; returns whether they are in LDS
+__device__ inline bool diff_load(const DiffStep &st, DiffTile &t, int64_t v0, int nr, int64_t &a0, int64_t &b0, bool lists)
+{
+    a0 = st.rp_a[v0];
+    b0 = st.rp_b[v0];
+    for (int i = threadIdx.x; i <= nr; i += kDiffThreads) {
+        t.offa[i] = int32_t(st.rp_a[v0 + i] - a0);
+        t.offb[i] = int32_t(st.rp_b[v0 + i] - b0);
+    }
+    __syncthreads();
+    const int na = t.offa[nr], nb = t.offb[nr];
+    const bool fits = lists && na <= kDiffCap && nb <= kDiffCap;
+    if (fits) {
+        for (int i = threadIdx.x; i < na; i += kDiffThreads) t.la[i] = st.col_a[a0 + i];
+        for (int i = threadIdx.x; i < nb; i += kDiffThreads) t.lb[i] = st.col_b[b0 + i];
+    }
+    __syncthreads();
+    return fits;
+}
+
+// Where the flag bits of a block's entries begin, in 64-bit words: one bit per entry of the block's piece of a column
+// list, 64 consecutive entries per word.  The pieces of consecutive blocks are adjacent in the list, so
+// piece_start / 64 + block index leaves every block room for its last, partly filled word.
+__device__ inline int64_t mask_base(int64_t piece_start) { return piece_start / 64 + blockIdx.x; }
+
+// pass 1 over one list: `mine` against `other`.  A wavefront takes 64 consecutive entries at a time, one per lane
+// (coalesced, conflict-free reads); absent entries are counted per row in cnt_absent, entries whose source is in the
+// change set in cnt_hit (bits == null: not wanted), and both kinds are noted as one bit per entry for pass 2 (a
+// wavefront's ballot is the word of its 64 entries).
+__device__ inline void diff_count_list(const int32_t *mine, const int32_t *off_mine, const int32_t *other, const int32_t *off_other,
+                                       int nr, const uint64_t *bits, int32_t *cnt_absent, int32_t *cnt_hit, uint64_t *mask_absent,
+                                       uint64_t *mask_hit)
+{
+    const int total = off_mine[nr];
+    const int lane = threadIdx.x & 63;
+    for (int base = int(threadIdx.x >> 6) * 64; base < total; base += kDiffThreads) {
+        const int e = base + lane;
+        bool absent = false, hit = false;
+        if (e < total) {
+            // the window's first row by bisection (the same for all lanes), then a few steps forward per lane
+            int r = row_of(off_mine, nr, base);
+            while (e >= off_mine[r + 1]) ++r;
+            const int32_t u = mine[e];
+            const int ob = off_other[r];
+            absent = !sorted_has(other, ob, off_other[r + 1], ob + (e - off_mine[r]), u);
+            hit = bits && bit_of(bits, u);
+            if (absent) atomicAdd(&cnt_absent[r], 1);
+            if (hit) atomicAdd(&cnt_hit[r], 1);
+        }
+        const unsigned long long m_abs = __ballot(absent), m_hit = __ballot(hit);
+        if (lane == 0) {
+            mask_absent[base / 64] = m_abs;
+            if (mask_hit) mask_hit[base / 64] = m_hit;
+        }
+    }
+}
+
+__global__ void __launch_bounds__(kDiffThreads) diff_count(const DiffStep *steps, int64_t n, int self_loop)
+{
+    __shared__ DiffTile t;
+    __shared__ int32_t cnt[3][kDiffRows];  // inserted, deleted, feature-change entries per row
+    const DiffStep st = steps[blockIdx.y];  // (a copy: the pointers stay in registers across the stores below)
+    const int64_t v0 = int64_t(blockIdx.x) * kDiffRows;
+    const int nr = int(min(int64_t(kDiffRows), n - v0));
+    for (int i = threadIdx.x; i < 3 * kDiffRows; i += kDiffThreads) (&cnt[0][0])[i] = 0;
+    int64_t a0, b0;
+    const bool fits = diff_load(st, t, v0, nr, a0, b0, true);
+    const uint64_t *bits = st.coffs[n] > 0 ? st.bits : nullptr;  // (an empty change set needs no look-ups)
+    uint64_t *ma = st.mask_del + mask_base(a0), *mb = st.mask_ins + mask_base(b0), *mh = bits ? st.mask_hit + mask_base(b0) : nullptr;
+    if (fits) {
+        diff_count_list(t.lb, t.offb, t.la, t.offa, nr, bits, cnt[0], cnt[2], mb, mh);
+        diff_count_list(t.la, t.offa, t.lb, t.offb, nr, nullptr, cnt[1], nullptr, ma, nullptr);
+    } else {
+        diff_count_list(st.col_b + b0, t.offb, st.col_a + a0, t.offa, nr, bits, cnt[0], cnt[2], mb, mh);
+        diff_count_list(st.col_a + a0, t.offa, st.col_b + b0, t.offb, nr, nullptr, cnt[1], nullptr, ma, nullptr);
+    }
+    __syncthreads();
+    for (int r = threadIdx.x; r < nr; r += kDiffThreads) {
+        const int64_t v = v0 + r;
+        const int32_t own = self_loop && bits && bit_of(bits, v);  // the row's own entry: self-loop of a changed node
+        const int32_t all = cnt[0][r] + cnt[1][r] + cnt[2][r] + own;
+        st.cnt_ins[v] = cnt[0][r];
+        st.cnt_del[v] = cnt[1][r];
+        st.cnt_ent[v] = all;
+        st.row_flag[v] = all > 0;
+    }
+}
+
+// exclusive prefix of one value per thread over the block (256 threads); *total = the block's sum
+__device__ inline uint32_t block_prefix_u32(uint32_t v, uint32_t *wave_sums, uint32_t *total)
+{
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    uint32_t incl = v;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t up = __shfl_up(incl, off);
+        if (lane >= off) incl += up;
+    }
+    __syncthreads();  // (wave_sums may still be read from the previous call)
+    if (lane == 63) wave_sums[w] = incl;
+    __syncthreads();
+    uint32_t before = 0, all = 0;
+#pragma unroll
+    for (int k = 0; k < kDiffThreads / 64; ++k) {
+        if (k < w) before += wave_sums[k];
+        all += wave_sums[k];
+    }
+    *total = all;
+    return before + incl - v;
+}
+
+// pass 2 over one list, by the flag bits of pass 1 (a thread takes the byte of kDiffItems = 8 consecutive entries).
+// IS_B: `mine` is snapshot t (absent = inserted, and feature-change entries are written too); else snapshot t-1
+// (absent = deleted).  p_ins / p_del / p_ent: the output
+// row pointers relative to the block's first row, hit_before: feature-change entries in the block's earlier rows.
+template <bool IS_B>
+__device__ inline void diff_fill_list(const DiffStep &st, const int32_t *mine, const int32_t *off_mine, int nr,
+                                      const uint8_t *mask_absent, const uint8_t *mask_hit, const int32_t *p_ins, const int32_t *p_del,
+                                      const int32_t *p_ent, const int32_t *hit_before, int64_t out0, int64_t ent0,
+                                      uint32_t *wave_sums)
+{
+    const int total = off_mine[nr];
+    uint32_t run_absent = 0, run_hit = 0;  // entries written by earlier rounds
+    for (int base = 0; base < total; base += kDiffThreads * kDiffItems) {
+        const int e0 = base + int(threadIdx.x) * kDiffItems;
+        uint32_t m_absent = 0, m_hit = 0;
+        if (e0 < total) {
+            m_absent = mask_absent[e0 / kDiffItems];
+            if (IS_B && mask_hit) m_hit = mask_hit[e0 / kDiffItems];
+        }
+        uint32_t tot;
+        const uint32_t ex = block_prefix_u32(uint32_t(__popc(m_absent)) | (uint32_t(__popc(m_hit)) << 16), wave_sums, &tot);
+        uint32_t at_absent = run_absent + (ex & 0xFFFFu), at_hit = run_hit + (ex >> 16);
+        if (m_absent | m_hit) {
+            int r = row_of(off_mine, nr, e0);
+#pragma unroll
+            for (int j = 0; j < kDiffItems; ++j) {
+                if (!((m_absent | m_hit) & (1u << j))) continue;
+                const int e = e0 + j;
+                while (e >= off_mine[r + 1]) ++r;
+                const int32_t u = mine[e];
+                if (m_absent & (1u << j)) {
+                    if (IS_B) {
+                        st.ins_col[out0 + at_absent] = u;
+                        st.ent[ent0 + p_ent[r] + (int32_t(at_absent) - p_ins[r])] = uint32_t(u);
+                    } else {
+                        st.del_col[out0 + at_absent] = u;
+                        st.ent[ent0 + p_ent[r] + (p_ins[r + 1] - p_ins[r]) + (int32_t(at_absent) - p_del[r])] =
+                            (1u << kKindShift) | uint32_t(u);
+                    }
+                    ++at_absent;
+                }
+                if (IS_B && (m_hit & (1u << j))) {
+                    st.ent[ent0 + p_ent[r] + (p_ins[r + 1] - p_ins[r]) + (p_del[r + 1] - p_del[r]) + (int32_t(at_hit) - hit_before[r])] =
+                        (2u << kKindShift) | uint32_t(st.coffs[u]);
+                    ++at_hit;
+                }
+            }
+        }
+        run_absent += tot & 0xFFFFu;
+        run_hit += tot >> 16;
+    }
+}
+
+__global__ void __launch_bounds__(kDiffThreads) diff_fill(const DiffStep *steps, int64_t n, int self_loop)
+{
+    __shared__ int32_t offa[kDiffRows + 1], offb[kDiffRows + 1];
+    __shared__ int32_t p_ins[kDiffRows + 1], p_del[kDiffRows + 1], p_ent[kDiffRows + 1], hit_before[kDiffRows + 1];
+    __shared__ uint32_t wave_sums[kDiffThreads / 64];
+    const DiffStep st = steps[blockIdx.y];  // (a copy: the pointers stay in registers across the stores below)
+    const int64_t v0 = int64_t(blockIdx.x) * kDiffRows;
+    const int nr = int(min(int64_t(kDiffRows), n - v0));
+    const int64_t ins0 = st.ins_ptr[v0], del0 = st.del_ptr[v0], ent0 = st.ent_ptr[v0];
+    const int64_t a0 = st.rp_a[v0], b0 = st.rp_b[v0];
+    for (int i = threadIdx.x; i <= nr; i += kDiffThreads) {
+        offa[i] = int32_t(st.rp_a[v0 + i] - a0);
+        offb[i] = int32_t(st.rp_b[v0 + i] - b0);
+        p_ins[i] = int32_t(st.ins_ptr[v0 + i] - ins0);
+        p_del[i] = int32_t(st.del_ptr[v0 + i] - del0);
+        p_ent[i] = int32_t(st.ent_ptr[v0 + i] - ent0);
+    }
+    __syncthreads();
+    const uint64_t *bits = st.coffs[n] > 0 ? st.bits : nullptr;
+    static_assert(kDiffRows <= 64, "the prefix sums below take one row per lane");
+    if (threadIdx.x < 64) {
+        // feature-change entries of the block's earlier rows (a row's entries are its inserted, deleted and
+        // feature-change entries and, last, its own): prefix sums over the 64 rows in one wavefront
+        const int r = threadIdx.x;
+        int32_t mine = 0;
+        if (r < nr) {
+            const int32_t own = self_loop && bits && bit_of(bits, v0 + r);
+            mine = (p_ent[r + 1] - p_ent[r]) - (p_ins[r + 1] - p_ins[r]) - (p_del[r + 1] - p_del[r]) - own;
+        }
+        int32_t incl = mine;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const int32_t up = __shfl_up(incl, off);
+            if (r >= off) incl += up;
+        }
+        if (r <= kDiffRows) hit_before[r] = incl - mine;
+        if (kDiffRows == 64 && r == 63) hit_before[64] = incl;
+    }
+    __syncthreads();
+    // only flagged entries are touched, so the column lists are read from global memory (a few scattered words)
+    if (p_ins[nr] > 0 || hit_before[nr] > 0)
+        diff_fill_list<true>(st, st.col_b + b0, offb, nr, reinterpret_cast<const uint8_t *>(st.mask_ins + mask_base(b0)),
+                             bits ? reinterpret_cast<const uint8_t *>(st.mask_hit + mask_base(b0)) : nullptr, p_ins, p_del, p_ent,
+                             hit_before, ins0, ent0, wave_sums);
+    if (p_del[nr] > 0)
+        diff_fill_list<false>(st, st.col_a + a0, offa, nr, reinterpret_cast<const uint8_t *>(st.mask_del + mask_base(a0)), nullptr,
+                              p_ins, p_del, p_ent, hit_before, del0, ent0, wave_sums);
+    // the rows' own entries and the three lists: changed nodes C_t, changed rows R_t with where their entries begin
+    for (int r = threadIdx.x; r < nr; r += kDiffThreads) {
+        const int64_t v = v0 + r;
+        if (bits && bit_of(bits, v)) {
+            const int64_t ci = st.coffs[v];
+            st.changed[ci] = int32_t(v);
+            if (self_loop) st.ent[ent0 + p_ent[r + 1] - 1] = (2u << kKindShift) | uint32_t(ci);
+        }
+        if (p_ent[r + 1] > p_ent[r]) {
+            const int64_t at = st.roffs[v];
+            st.rows[at] = int32_t(v);
+            st.row_ent[at] = ent0 + p_ent[r];
+        }
+        if (v == n - 1) st.row_ent[st.roffs[n]] = st.ent_ptr[n];
+    }
+}
+
+// stage 2b: dY rows of the changed nodes
 __global__ void steps_dy(const DiffStep *steps, int bf16, int32_t d)
 {
     const DiffStep &st = steps[blockIdx.y];
@@ -436,61 +680,27 @@ __global__ void steps_dy(const DiffStep *steps, int bf16, int32_t d)
     st.dY[i] = pb * b - pa * a;
 }
 
-// stage 4c: the entries.  Threads [0, nb): edges of t (inserted, changed source); [nb, nb + na): edges of t-1
-// (deleted); [nb + na, nb + na + n): the rows' own entries (self-loop of a changed node, last in its row).
-__global__ void steps_fill(const DiffStep *steps, int64_t n, int self_loop)
-{
-    const DiffStep &st = steps[blockIdx.y];
-    int64_t e = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
-    if (e < st.nb) {
-        const int32_t v = st.rowid_b[e], u = st.col_b[e];
-        if (st.absent_b[e]) {
-            const int64_t r = st.pos_ins[e];
-            st.ins_col[r] = u;
-            st.ent[st.ent_ptr[v] + (r - st.ins_ptr[v])] = uint32_t(u);
-        }
-        if (st.hit_b[e]) {
-            const int64_t base = st.ent_ptr[v] + (st.ins_ptr[v + 1] - st.ins_ptr[v]) + (st.del_ptr[v + 1] - st.del_ptr[v]);
-            st.ent[base + (st.pos_hit[e] - st.pos_hit[st.rp_b[v]])] = (2u << kKindShift) | uint32_t(st.cindex[u]);
-        }
-        return;
-    }
-    e -= st.nb;
-    if (e < st.na) {
-        if (!st.absent_a[e]) return;
-        const int32_t v = st.rowid_a[e], u = st.col_a[e];
-        const int64_t r = st.pos_del[e];
-        st.del_col[r] = u;
-        st.ent[st.ent_ptr[v] + (st.ins_ptr[v + 1] - st.ins_ptr[v]) + (r - st.del_ptr[v])] = (1u << kKindShift) | uint32_t(u);
-        return;
-    }
-    e -= st.na;
-    if (!self_loop || e >= n) return;
-    const int32_t ci = st.cindex[e];
-    if (ci >= 0) st.ent[st.ent_ptr[e + 1] - 1] = (2u << kKindShift) | uint32_t(ci);
-}
-
 }  // namespace
 
-void launch_diff_stage(int stage, const DiffStep *steps_dev, int count, int64_t n, int64_t max_a, int64_t max_b, int64_t max_list,
-                       int64_t max_changed, int sym, int self_loop, int bf16, int32_t d, hipStream_t s)
+void launch_diff_stage(int stage, const DiffStep *steps_dev, int count, int64_t n, int64_t max_list, int64_t max_changed, int sym,
+                       int self_loop, int bf16, int32_t d, hipStream_t s)
 {
     if (count <= 0) return;
     auto grid = [&](int64_t elems) { return dim3(std::max(1u, blocks_for(elems, 256)), unsigned(count)); };
+    const dim3 row_blocks(unsigned((n + kDiffRows - 1) / kDiffRows), unsigned(count));
+    const int32_t chunks = d * (bf16 ? 2 : 4) / 16;
     switch (stage) {
     case 0:
         steps_init_flags<<<grid(n), 256, 0, s>>>(steps_dev, n, sym);
-        if (max_list > 0) steps_flags_list<<<grid(max_list), 256, 0, s>>>(steps_dev);
+        if (max_list > 0) steps_flags_list<<<grid(max_list * chunks), 256, 0, s>>>(steps_dev, chunks);
         break;
-    case 1: steps_edge_flags<<<grid(max_a + max_b), 256, 0, s>>>(steps_dev); break;
+    case 1:
+        steps_bits<<<grid(n), 256, 0, s>>>(steps_dev, n);
+        diff_count<<<row_blocks, kDiffThreads, 0, s>>>(steps_dev, n, self_loop);
+        break;
     case 2:
-        steps_row_ptrs<<<grid(n + 1), 256, 0, s>>>(steps_dev, n, self_loop);
-        steps_row_flags<<<grid(n), 256, 0, s>>>(steps_dev, n);
-        break;
-    case 3:
-        steps_compact<<<grid(n), 256, 0, s>>>(steps_dev, n);
+        diff_fill<<<row_blocks, kDiffThreads, 0, s>>>(steps_dev, n, self_loop);
         if (max_changed > 0) steps_dy<<<grid(max_changed * d), 256, 0, s>>>(steps_dev, bf16, d);
-        steps_fill<<<grid(max_a + max_b + n), 256, 0, s>>>(steps_dev, n, self_loop);
         break;
     default: break;
     }
