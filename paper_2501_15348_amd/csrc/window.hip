@@ -330,9 +330,9 @@ int ensure_layer1(reinc_ctx *ctx, int32_t t, hipStream_t s)
         const Snapshot &pv = ctx->snaps[t - 1];
         {
             // one pass over every row: changed rows get their delta, the others are copied into the new slot
-            ProfScope prof(ctx, REINC_K_AGG_INC, s);
-            launch_incremental(nullptr, nullptr, c.num_nodes, dl.long_rows, dl.n_long_rows, dl.ent_ptr, dl.ent, pv.x, bf16, pv.p, dl.dY,
-                               d, ctx->gcache[t - 1], slot, nullptr, nullptr, s);
+            ProfScope prof(ctx, REINC_K_AGG_INC, s, true);
+            launch_incremental(nullptr, nullptr, c.num_nodes, dl.ent_ptr, dl.ent, pv.x, bf16, pv.p, dl.dY, d, ctx->gcache[t - 1], slot,
+                               nullptr, nullptr, s, prof.start(), prof.stop());
         }
         ++ctx->stats.steps_incremental;
         ctx->stats.delta_entries_processed += dl.info.n_entries;
@@ -497,6 +497,7 @@ int reinc_forward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *par
     REINC_HIP(ctx, hipGetLastError());
     ctx->local_valid = true;
     ctx->local_t0 = t0;
+    ctx->local_len = L;
     return REINC_OK;
 }
 
@@ -506,7 +507,7 @@ int reinc_backward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *pa
     if (!ctx) return REINC_E_ARG;
     REINC_TRY(check_window(ctx, t0, L));
     if (!params || !target || !grads) return ctx->fail(REINC_E_ARG, "null params, target or grads");
-    if (!ctx->local_valid || ctx->local_kind != 0 || ctx->local_t0 != t0 || int32_t(ctx->local.size()) < L)
+    if (!ctx->local_valid || ctx->local_kind != 0 || ctx->local_t0 != t0 || ctx->local_len != L)
         return ctx->fail(REINC_E_STATE, "backward needs the forward pass of the same window [%d, %d) first", t0, t0 + L);
     const reinc_config &c = ctx->cfg;
     hipStream_t s = as_stream(stream);
@@ -713,6 +714,7 @@ int reinc_forward_window_integrated(reinc_ctx *ctx, int32_t t0, int32_t L, const
     REINC_HIP(ctx, hipGetLastError());
     ctx->local_valid = true;
     ctx->local_t0 = t0;
+    ctx->local_len = L;
     return REINC_OK;
 }
 
@@ -722,7 +724,7 @@ int reinc_backward_window_integrated(reinc_ctx *ctx, int32_t t0, int32_t L, cons
     if (!ctx) return REINC_E_ARG;
     REINC_TRY(check_window(ctx, t0, L));
     if (!params || !target || !grads) return ctx->fail(REINC_E_ARG, "null params, target or grads");
-    if (!ctx->local_valid || ctx->local_kind != 1 || ctx->local_t0 != t0 || int32_t(ctx->local.size()) < L)
+    if (!ctx->local_valid || ctx->local_kind != 1 || ctx->local_t0 != t0 || ctx->local_len != L)
         return ctx->fail(REINC_E_STATE, "backward needs the integrated forward pass of the same window [%d, %d) first", t0, t0 + L);
     const reinc_config &c = ctx->cfg;
     hipStream_t s = as_stream(stream);
