@@ -1,10 +1,30 @@
 """Shared by the GPU parity tests: tolerance rule and oracle-side expectations."""
+import json
+import os
+
 import numpy as np
 
 import oracle
 
 RTOL_FP32 = 1e-4  # fp32 path
 RTOL_BF16 = 2e-2  # bf16 inputs, fp32 accumulation
+GRAD_RTOL_FP32 = 1e-4  # gradients of the fp32 path: the same bound as the outputs
+
+_ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+_ERROR_LOG = os.path.join(_ROOT, "gpurun_out", "parity_errors.jsonl")
+
+
+def record(what, worst, rtol):
+    """Notes the measured worst error of one comparison (in the units of the tolerance rule: the rtol that would just
+    pass) next to the tolerance it was held to, one JSON line per comparison, where a results folder exists."""
+    if not os.path.isdir(os.path.dirname(_ERROR_LOG)):
+        return
+    try:
+        with open(_ERROR_LOG, "a") as f:
+            f.write(json.dumps({"test": os.environ.get("PYTEST_CURRENT_TEST", "").split(" ")[0], "what": what,
+                                "worst": float(worst), "rtol": float(rtol)}) + "\n")
+    except OSError:
+        pass
 
 
 def assert_close(got, ref, rtol, what=""):
@@ -19,6 +39,9 @@ def assert_close(got, ref, rtol, what=""):
     rms = float(np.sqrt(np.mean(ref * ref)))
     err = np.abs(got - ref)
     bound = rtol * np.abs(ref) + rtol * rms
+    denom = np.abs(ref) + rms
+    if what:
+        record(what, float(np.max(np.where(denom > 0, err / np.where(denom > 0, denom, 1.0), np.where(err > 0, np.inf, 0.0)))), rtol)
     bad = err > bound
     if bad.any():
         i = np.unravel_index(np.argmax(err - bound), err.shape)

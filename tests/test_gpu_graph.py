@@ -74,6 +74,34 @@ def test_full_feature_loads_find_the_same_change_set():
     _check_all_steps(synth.make_sequence(wl), delta_features=False)
 
 
+def test_a_listed_row_with_unchanged_values_is_not_in_the_change_set():
+    """Delta-mode loading ships (row, values) pairs; the change set is defined by the values: a row that is sent again
+    with the values it already had belongs to it as little as it would after a full load."""
+    import copy
+
+    wl = synth.WORKLOADS["c2"].scaled(900, 3, agg="mean")
+    seq = copy.deepcopy(synth.make_sequence(wl))
+    t = 2
+    x_prev = oracle_feats(seq, t - 1).astype(np.float32)
+    extra = np.setdiff1d(np.arange(0, wl.num_nodes, 37, dtype=np.int32), seq.feat_rows[t])
+    rows = np.concatenate([seq.feat_rows[t], extra])
+    vals = np.concatenate([seq.feat_vals[t], x_prev[extra]])
+    order = np.argsort(rows)
+    seq.feat_rows[t], seq.feat_vals[t] = rows[order].astype(np.int32), vals[order]
+    ctx = _ctx(wl)
+    ctx.load_sequence(seq)
+    ctx.build_deltas(-1)
+    graphs = oracle_graphs(seq)
+    counts = oracle.change_counts(graphs[t - 1], graphs[t], oracle_feats(seq, t - 1), oracle_feats(seq, t), wl.agg, wl.self_loop)
+    info = ctx.get_delta_info(t)
+    for k in ("n_changed", "n_fchg_entries", "n_entries", "n_rows"):
+        assert info[k] == counts[k], (k, info[k], counts[k])
+    _, _, _, changed = ctx.get_merged_delta(t)
+    assert np.intersect1d(changed, extra).size == 0 and extra.size > 10
+    ctx.close()
+    _check_all_steps(seq)
+
+
 def _manual_seq(n, steps, d=4, sl=True, agg="sum"):
     """steps: list of (src list, dst list, rows to re-draw)"""
     wl = synth.Workload("manual", n, 1.0, len(steps), "uniform", 0, 0, 0, "fp32", agg, sl, (d, d), "gru", d, len(steps))

@@ -9,7 +9,7 @@ import numpy as np
 import pytest
 
 import oracle
-from helpers import RTOL_FP32, assert_close, assert_gradients_close, oracle_feats, oracle_graphs
+from helpers import GRAD_RTOL_FP32, RTOL_FP32, assert_close, assert_gradients_close, oracle_feats, oracle_graphs
 from paper_2501_15348_amd import synth
 
 pytestmark = pytest.mark.gpu
@@ -21,9 +21,7 @@ def _config(case):
     T = rng.randint(3, 6)
     L = rng.randint(1, min(T, 4))
     agg = rng.choice(["sum", "mean", "sym"])
-    # three un-normalised sum layers multiply the activations by the degree three times (rms ~ 80 into the cell): the
-    # fp32 noise of the gate pre-activations then exceeds a tolerance that is relative to the outputs
-    layers = rng.choice([1, 2, 2] if agg == "sum" else [1, 2, 2, 3])
+    layers = rng.choice([1, 2, 2, 3])
     kw = dict(dims=tuple(rng.choice([16, 32, 64, 128, 256]) for _ in range(layers + 1)), hidden=rng.choice([16, 32, 64, 128]),
               agg=agg, rnn=rng.choice(["gru", "lstm"]), self_loop=rng.choice([True, True, False]))
     wl = synth.WORKLOADS[rng.choice(["c2", "c3", "c5_10"])].scaled(n, T, **kw)
@@ -47,6 +45,12 @@ def test_random_configuration(case):
     if budget:
         ctx.cache_configure(budget[0], budget[1] * ctx.aggregate_bytes(), window=L, stride=1)
     flat = synth.make_params(wl, bias_scale=0.2)
+    if wl.agg == "sum":
+        # an un-normalised sum multiplies the activations by about the degree at every layer: the layer weights are drawn
+        # that much smaller, as trained weights of such a model would be, so that every layer's output stays of order one
+        views = synth.split_params(wl, flat)
+        for l in range(1, len(wl.dims)):
+            views[f"W{l}"] *= np.float32(1.0 / (1.0 + wl.mean_degree))
     target = synth.make_target(wl)
     params, tgt = torch.from_numpy(flat).cuda(), torch.from_numpy(target).cuda()
     loss = torch.zeros(1, device="cuda")
@@ -67,7 +71,7 @@ def test_random_configuration(case):
         assert_gradients_close(
             synth.split_params(wl, grads.cpu().numpy()), saved,
             lambda sv: oracle.backward_window(graphs, sv, ref_h, p, layers, wl.agg, wl.self_loop, wl.rnn, target),
-            [name for name, _ in synth.param_shapes(wl)], 5 * RTOL_FP32)
+            [name for name, _ in synth.param_shapes(wl)], GRAD_RTOL_FP32)
     # the integrated model (graph operations inside the gates) on the first window of the same sequence
     wli = dataclasses.replace(wl, dims=(wl.dims[0],))
     flat_i = synth.make_params(wli, bias_scale=0.2)
@@ -83,5 +87,5 @@ def test_random_configuration(case):
     ref_g = oracle.backward_window_integrated(graphs_all[:L], saved, ref_h, pi, wl.agg, wl.self_loop, wl.rnn, target)
     got = synth.split_params(wli, grads_i.cpu().numpy())
     for name, _ in synth.param_shapes(wli):
-        assert_close(got[name], ref_g[name], 5 * RTOL_FP32, f"integrated grad {name}")
+        assert_close(got[name], ref_g[name], GRAD_RTOL_FP32, f"integrated grad {name}")
     ctx.close()

@@ -6,7 +6,7 @@ import numpy as np
 import pytest
 
 import oracle
-from helpers import RTOL_BF16, RTOL_FP32, assert_close, assert_gradients_close, oracle_feats, oracle_graphs
+from helpers import GRAD_RTOL_FP32, RTOL_BF16, RTOL_FP32, assert_close, assert_gradients_close, oracle_feats, oracle_graphs
 from paper_2501_15348_amd import synth
 
 pytestmark = pytest.mark.gpu
@@ -48,6 +48,8 @@ CASES = [
     ("c2", 2500, 6, dict(rnn="lstm", hidden=32)),  # a layer-1 pre-activation of this graph lies within fp32 rounding of zero
     ("c2", 40, 5, {}),                              # fewer rows than two tiles
     ("c2", 1500, 4, dict(dims=(256, 128, 128), hidden=64)),  # weight gradients: block slabs of 128 x 128, whole (256 x 128) and ragged (128 x 192)
+    ("c4", 1200, 4, {}),                            # the largest workload's model: bf16 features, 256 -> 256 -> 128, GRU 128
+    ("c4", 4099, 5, dict(edge_churn=0.03)),         # the same with steps under the fallback threshold at this small size
 ]
 
 
@@ -61,7 +63,9 @@ def test_forward_and_backward_match_reference(name, n, T, kw):
     seq, ctx, flat, target = _setup(wl)
     T = wl.num_snapshots
     L = min(T, 4)
-    rtol = RTOL_FP32
+    bf16 = wl.feat_dtype == "bf16"
+    rtol = RTOL_BF16 if bf16 else RTOL_FP32
+    grad_rtol = RTOL_BF16 if bf16 else GRAD_RTOL_FP32
     params, tgt = _dev(flat), _dev(target)
     loss = torch.zeros(1, device="cuda")
     h_last = torch.empty((wl.num_nodes, wl.hidden), device="cuda")
@@ -78,7 +82,7 @@ def test_forward_and_backward_match_reference(name, n, T, kw):
         assert_gradients_close(
             got, saved,
             lambda sv: oracle.backward_window(graphs, sv, ref_h, p, len(wl.dims) - 1, wl.agg, wl.self_loop, wl.rnn, target),
-            [name_ for name_, _ in synth.param_shapes(wl)], 5 * rtol)
+            [name_ for name_, _ in synth.param_shapes(wl)], grad_rtol)
     st = ctx.get_stats()
     assert st["global_misses"] == min(T, 2 * L) if T - L >= L else True
     assert st["global_hits"] + st["global_misses"] == 2 * L
@@ -160,6 +164,21 @@ def test_window_errors():
     with pytest.raises(reinc.ReincError) as e:
         ctx.backward_window(1, 3, params, tgt, grads)
     assert e.value.code == reinc.E_STATE
+    # a shorter window from the same start after a longer one: the local cache is large enough for the longer one,
+    # but it holds the activations of the shorter one only
+    ctx.forward_window(0, 2, params, tgt, loss)
+    for length in (4, 3, 1):
+        with pytest.raises(reinc.ReincError) as e:
+            ctx.backward_window(0, length, params, tgt, grads)
+        assert e.value.code == reinc.E_STATE
+    ctx.backward_window(0, 2, params, tgt, grads)
+    pi = torch.zeros((16 + 16 + 2) * 48, device="cuda")
+    gi = torch.empty_like(pi)
+    ctx.forward_window_integrated(0, 2, pi, tgt, loss)
+    with pytest.raises(reinc.ReincError) as e:
+        ctx.backward_window_integrated(0, 3, pi, tgt, gi)
+    assert e.value.code == reinc.E_STATE
+    ctx.backward_window_integrated(0, 2, pi, tgt, gi)
     ctx.close()
     small = reinc.Context.for_workload(wl, arena_bytes=200 << 10)
     small.load_sequence(seq)
@@ -200,4 +219,4 @@ def test_batch_depth_does_not_change_the_answer(monkeypatch):
     ref_g = oracle.backward_window(graphs, saved, ref_h, p, len(wl.dims) - 1, wl.agg, wl.self_loop, wl.rnn, target)
     got = synth.split_params(wl, outs[-1][1])
     for name_, _ in synth.param_shapes(wl):
-        assert_close(got[name_], ref_g[name_], 5 * RTOL_FP32, f"grad {name_}")
+        assert_close(got[name_], ref_g[name_], GRAD_RTOL_FP32, f"grad {name_}")
