@@ -238,8 +238,10 @@ def main():
     for t0_ in range(windows):
         for l in range(2, layers + 1):  # forward aggregate and backward adjoint of layer l
             count += 2 * batches
+            # a layer that narrows its input applies its linear map first and gathers rows of its own width
+            width = wl.dims[l] if wl.dims[l] < wl.dims[l - 1] else wl.dims[l - 1]
             for t in range(t0_, t0_ + L):
-                total_bytes += short_bytes(t, "fwd", wl.dims[l - 1], 4) + short_bytes(t, "adj", wl.dims[l - 1], 4)
+                total_bytes += short_bytes(t, "fwd", width, 4) + short_bytes(t, "adj", width, 4)
     # (a launch covers one snapshot at layer 1 and up to MAX_BATCH snapshots above it -- fewer where the arena leaves
     # less scratch -- so the bytes of all launches are set against their total duration)
     bytes_per_launch = total_bytes * args.steps / max(launches, 1)

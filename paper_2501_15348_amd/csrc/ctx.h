@@ -81,6 +81,8 @@ struct AggItem {
     int32_t n_long;
     int64_t row_limit = 0;  // > 0: listed long rows from this row on are skipped (their output rows do not exist)
     const int32_t *order = nullptr;  // [n] or null: the row the i-th lane group of the short-row kernel takes
+    const float *bias = nullptr;     // [d] or null: added to the scaled row (before relu, mask and add)
+    int relu = 0;                    // clamp at zero after the bias
 };
 struct AggBatch {
     int count = 0;
@@ -319,7 +321,8 @@ void launch_scatter_rows(const void *vals, const int32_t *rows, int64_t nrows, i
 // ---- kernels_agg.hip
 bool agg_width_supported(int32_t d, int bf16);
 // out[v] = out_scale[v] * ( self_loop * in_scale[v] X[v] + sum_{e in [ptr[v], ptr[v+1])} in_scale[idx[e]] X[idx[e]] )
-// in_scale / out_scale may be null (factor 1); mask [n,d] (may be null) zeroes the output where mask <= 0.
+// in_scale / out_scale may be null (factor 1); then + bias and relu (AggItem); mask [n,d] (may be null) zeroes the
+// output where mask <= 0.
 // One launch serves a batch of up to kMaxAggBatch snapshots (blockIdx.y picks the item): the layers above the
 // first aggregate every timestep of a window in one go.  launch_aggregate_batch takes every row of at most kLongRow
 // entries (all rows of an item with n_long == 0); launch_aggregate_long_batch takes the listed long rows with one
@@ -358,6 +361,9 @@ void launch_incremental(const int32_t *rows, const int64_t *row_ent, int64_t n_r
 int launch_gemm_rows(const void *A, int a_bf16, int64_t n, int32_t K, int32_t M, const float *row_scale, const float *W,
                      int w_transposed, int32_t ldw, const float *bias, int relu, const float *add, const float *mask,
                      float *out, hipStream_t s);
+// db[j] (+)= sum over the n rows of G[., j]; partial: scratch of column_sums_bytes(M); fixed summation order
+uint64_t column_sums_bytes(int32_t M);
+void launch_column_sums(const float *G, int64_t n, int32_t M, float *partial, float *db, int accumulate, hipStream_t s);
 // x_scale [n] (or null) multiplies the rows of x; h_prev is the recurrent GEMM operand, h_carry the state of the GRU
 // carry term z .* h (the stacked model passes the same pointer for both)
 void launch_rnn_fused(int lstm, const float *x, const float *x_scale, int64_t n, int32_t d_in, int32_t H, const float *h_prev,

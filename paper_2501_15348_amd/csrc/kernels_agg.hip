@@ -223,6 +223,16 @@ aggregate_rows_grouped(AggBatch batch, int64_t n, int self_loop)
 #pragma unroll
             for (int i = 0; i < VEC; ++i) acc[i] *= q;
         }
+        if (it.bias) {
+            float b[VEC];
+            load_f32<VEC>(it.bias, 0, D, li, b);
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) acc[i] += b[i];
+        }
+        if (it.relu) {
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) acc[i] = fmaxf(acc[i], 0.0f);
+        }
         if (mask) {
             float m[VEC];
             load_f32<VEC>(mask, v, D, li, m);
@@ -289,6 +299,16 @@ aggregate_long_rows(AggBatch batch, int self_loop)
             const float q = out_scale[v];
 #pragma unroll
             for (int i = 0; i < VEC; ++i) acc[i] *= q;
+        }
+        if (it.bias) {
+            float b[VEC];
+            load_f32<VEC>(it.bias, 0, D, lane, b);
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) acc[i] += b[i];
+        }
+        if (it.relu) {
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) acc[i] = fmaxf(acc[i], 0.0f);
         }
         if (mask) {
             float m[VEC];

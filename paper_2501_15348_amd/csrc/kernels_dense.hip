@@ -1638,6 +1638,36 @@ reduce_partials_kernel(const float *partial, int chunks, int K, int M, float *ds
         dst_b[idx - K * M] += v;
 }
 
+// ---- column sums of a tall matrix (bias gradient of a layer whose linear map runs before its aggregation) -------
+// Block b adds the rows b, b + blocks, ... (thread j of 256 takes the columns j, j + 256, ...: coalesced rows); the
+// second kernel adds the blocks' sums in block order: a fixed summation order.
+constexpr int kColumnSumBlocks = 1024;
+
+__global__ void __launch_bounds__(256) column_sums_partial(const float *__restrict__ G, int64_t n, int M, float *__restrict__ partial)
+{
+    for (int j = threadIdx.x; j < M; j += 256) {
+        float s0 = 0.0f, s1 = 0.0f, s2 = 0.0f, s3 = 0.0f;
+        int64_t r = blockIdx.x;
+        for (; r + 3 * int64_t(kColumnSumBlocks) < n; r += 4 * int64_t(kColumnSumBlocks)) {
+            s0 += G[r * M + j];
+            s1 += G[(r + kColumnSumBlocks) * M + j];
+            s2 += G[(r + 2 * int64_t(kColumnSumBlocks)) * M + j];
+            s3 += G[(r + 3 * int64_t(kColumnSumBlocks)) * M + j];
+        }
+        for (; r < n; r += kColumnSumBlocks) s0 += G[r * M + j];
+        partial[int64_t(blockIdx.x) * M + j] = (s0 + s1) + (s2 + s3);
+    }
+}
+
+__global__ void __launch_bounds__(256) column_sums_finish(const float *__restrict__ partial, int M, float *db, int accumulate)
+{
+    const int j = blockIdx.x * 256 + threadIdx.x;
+    if (j >= M) return;
+    float s = 0.0f;
+    for (int b = 0; b < kColumnSumBlocks; ++b) s += partial[int64_t(b) * M + j];
+    db[j] = accumulate ? db[j] + s : s;
+}
+
 // ---- recurrent backward, elementwise part ------------------------------------------------------------------
 // GRU : dgi = [dr, dz, dn], dgh = [dr, dz, dn .* r], dh_carry = dh .* z
 // LSTM: dgi = dgh = [di, df, dg, do], dc_prev = dc_total .* f, dh_carry = 0
@@ -1898,6 +1928,15 @@ void launch_gemm_reduce(const float *A, int32_t lda, const float *row_scale, con
         pick(std::true_type{})<<<blocks, 256, 0, s>>>(g);
     else
         pick(std::false_type{})<<<blocks, 256, 0, s>>>(g);
+}
+
+uint64_t column_sums_bytes(int32_t M) { return uint64_t(kColumnSumBlocks) * uint64_t(M) * sizeof(float); }
+
+void launch_column_sums(const float *G, int64_t n, int32_t M, float *partial, float *db, int accumulate, hipStream_t s)
+{
+    if (n <= 0 || M <= 0) return;
+    column_sums_partial<<<kColumnSumBlocks, 256, 0, s>>>(G, n, M, partial);
+    column_sums_finish<<<(M + 255) / 256, 256, 0, s>>>(partial, M, db, accumulate);
 }
 
 void launch_reduce_partials(const float *partial, int64_t n, int32_t K, int32_t M, float *dW, float *db, hipStream_t s)

@@ -74,6 +74,15 @@ Params split_params(const reinc_config &c, const float *flat)
 
 uint64_t align256(uint64_t b) { return (b + 255) & ~uint64_t(255); }
 
+// Layers above the first whose output is narrower than their input apply the linear map BEFORE the aggregation:
+// A (H W) = (A H) W, the same layer within rounding, but every edge then gathers a row of dims[l] values instead of
+// dims[l-1] (the gathers of these layers are the largest share of a step when the widths shrink).  Z = H W stays in
+// fp32: kept in bfloat16 (tried for bfloat16 node features) it halves the gathered bytes again, but the rounding moves
+// enough ReLU decisions of the layer that single weight-gradient entries of a 1200-node graph miss the 2e-2 bound.
+bool transform_first(const reinc_config &c, int l) { return l >= 2 && c.dims[l] < c.dims[l - 1]; }
+// floats a timestep's rows of LocalStep::S[l] take: the sums feeding layer l, or Z of a transform-first layer
+uint64_t s_width_floats(const reinc_config &c, int l) { return uint64_t(transform_first(c, l) ? c.dims[l] : c.dims[l - 1]); }
+
 // The local cache keeps every quantity as one array over the window's timesteps, so that the rows of consecutive
 // timesteps are adjacent and the dense kernels can take a whole batch of timesteps as one tall matrix.  A
 // timestep's slice is exactly n*d floats when that keeps slices 16-byte aligned, else it is padded (and the
@@ -86,7 +95,7 @@ uint64_t local_bytes(const reinc_config &c, int32_t L)
     uint64_t b = 0;
     for (int l = 1; l <= c.num_gcn_layers; ++l) {
         b += align256(uint64_t(L) * slice_floats(n, c.dims[l]) * 4);
-        if (l >= 2) b += align256(uint64_t(L) * slice_floats(n, c.dims[l - 1]) * 4);
+        if (l >= 2) b += align256(uint64_t(L) * slice_floats(n, s_width_floats(c, l)) * 4);
     }
     b += align256(uint64_t(L + 1) * slice_floats(n, H) * 4);                                  // h, with the zero state in front
     if (c.rnn_kind == REINC_RNN_LSTM) b += align256(uint64_t(L) * slice_floats(n, H) * 4);    // c
@@ -119,7 +128,7 @@ int ensure_local(reinc_ctx *ctx, int32_t L, hipStream_t s)
         float *Hl = take(uint64_t(L) * sh * 4);
         for (int32_t i = 0; i < L; ++i) ctx->local[i].H[l] = Hl + i * sh;
         if (l >= 2) {
-            const uint64_t ss = slice_floats(n, c.dims[l - 1]);
+            const uint64_t ss = slice_floats(n, s_width_floats(c, l));
             float *Sl = take(uint64_t(L) * ss * 4);
             for (int32_t i = 0; i < L; ++i) ctx->local[i].S[l] = Sl + i * ss;
         }
@@ -154,7 +163,9 @@ void place_top(reinc_ctx *ctx, int64_t nt, hipStream_t s)
     const reinc_config &c = ctx->cfg;
     const int Lg = c.num_gcn_layers;
     const uint64_t H = uint64_t(c.rnn_hidden), rows = uint64_t(nt);
-    float *bH = ctx->local[0].H[Lg], *bS = Lg >= 2 ? ctx->local[0].S[Lg] : nullptr, *bc = ctx->local[0].c, *bsv = ctx->local[0].saved;
+    // (Z of a transform-first last layer is needed on every row -- the sources -- and stays where ensure_local put it)
+    float *bH = ctx->local[0].H[Lg], *bS = Lg >= 2 && !transform_first(c, Lg) ? ctx->local[0].S[Lg] : nullptr, *bc = ctx->local[0].c,
+          *bsv = ctx->local[0].saved;
     for (size_t i = 0; i < ctx->local.size(); ++i) {
         reinc::LocalStep &st = ctx->local[i];
         st.H[Lg] = bH + i * slice_floats(rows, c.dims[Lg]);
@@ -421,9 +432,12 @@ int reinc_forward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *par
     if (!params) return ctx->fail(REINC_E_ARG, "null parameter vector");
     if (target && !loss_out) return ctx->fail(REINC_E_ARG, "a target needs loss_out");
     const reinc_config &c = ctx->cfg;
-    for (int l = 1; l < c.num_gcn_layers; ++l)
-        if (!agg_width_supported(c.dims[l], 0))
-            return ctx->fail(REINC_E_UNSUPPORTED, "layer width %d: row bytes must be a power of two in [16, 1024]", c.dims[l]);
+    for (int l = 2; l <= c.num_gcn_layers; ++l) {  // what layer l aggregates: its input rows, or Z = H W of its own width
+        const bool tf = transform_first(c, l);
+        if (!agg_width_supported(tf ? c.dims[l] : c.dims[l - 1], 0))
+            return ctx->fail(REINC_E_UNSUPPORTED, "layer %d aggregates rows of %d values: row bytes must be a power of two in [16, 1024]",
+                             l, tf ? c.dims[l] : c.dims[l - 1]);
+    }
     hipStream_t s = as_stream(stream);
     REINC_HIP(ctx, hipSetDevice(c.device));
     ctx->local_valid = false;
@@ -452,6 +466,36 @@ int reinc_forward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *par
             q[i] = ctx->snaps[t0 + i].q;
         }
         for (int l = 1; l <= Lg; ++l) {
+            if (transform_first(c, l)) {
+                // Z = H^{l-1} W_l for all timesteps of the batch as one tall matrix (every row: the rows are sources),
+                // then H^l = ReLU(Q (A + sI) P Z + b_l) straight out of the aggregation kernel
+                for (int32_t i = lo; i <= hi; ++i) {
+                    Sp[i] = ctx->local[i].H[l - 1];
+                    Hout[i] = ctx->local[i].S[l];
+                }
+                REINC_TRY(for_runs(lo, hi, n, {Strip{Sp.data(), c.dims[l - 1]}, Strip{Hout.data(), int64_t(s_width_floats(c, l))}},
+                                   [&](int i0, int len) {
+                                       gemm_rows(ctx, s, (const void *)Sp[i0], 0, n * len, c.dims[l - 1], c.dims[l], nof, p.W[l], 0,
+                                                 c.dims[l], nof, 0, nof, nof, const_cast<float *>(Hout[i0]));
+                                       return REINC_OK;
+                                   }));
+                AggBatch batch;
+                batch.count = hi - lo + 1;
+                for (int32_t i = lo; i <= hi; ++i) {
+                    const Snapshot &sn = ctx->snaps[t0 + i];
+                    LocalStep &st = ctx->local[i];
+                    AggItem &it = batch.item[i - lo];
+                    it = AggItem{sn.row_ptr, sn.col, st.S[l], sn.p, sn.q, nullptr, nullptr, st.H[l], sn.long_rows, sn.n_long_rows};
+                    it.bias = p.b[l];
+                    it.relu = 1;
+                    if (l == Lg && nt < n)
+                        it.row_limit = nt;  // H of the last layer has nt rows per timestep: rows [0, nt) as they come
+                    else
+                        it.order = sn.row_order;
+                }
+                aggregate_full_batch(ctx, batch, 0, c.dims[l], c.self_loop, s, l == Lg ? nt : n);
+                continue;
+            }
             if (l >= 2) {
                 AggBatch batch;
                 batch.count = hi - lo + 1;
@@ -539,7 +583,7 @@ int reinc_backward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *pa
         uint64_t b = align256(rows * KH * 4) * (lstm ? 1 : 2) + 3 * align256(rows * maxd * 4);
         b += align256(reduce_partial_bytes(int64_t(rows), c.dims[Lg], KH)) + align256(reduce_partial_bytes(int64_t(rows), H, KH));
         for (int l = 1; l <= Lg; ++l) b += align256(reduce_partial_bytes(int64_t(rows), c.dims[l - 1], c.dims[l]));
-        return b;
+        return b + align256(column_sums_bytes(maxd));
     };
     int B = std::min<int>(L, ctx->max_batch);
     while (B > 1 && batch_bytes(B) > free_bytes) --B;
@@ -557,10 +601,13 @@ int reinc_backward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *pa
     float *part_wh = static_cast<float *>(ctx->scratch(reduce_partial_bytes(rowsT, H, KH)));
     float *part_w[REINC_MAX_GCN_LAYERS + 1] = {};
     bool part_ok = part_wi && part_wh;
+    auto layer_rows = [&](int l) { return l == Lg && !transform_first(c, l) ? rowsT : rowsB; };  // rows its weight gradient sums over
     for (int l = 1; l <= Lg; ++l) {
-        part_w[l] = static_cast<float *>(ctx->scratch(reduce_partial_bytes(l == Lg ? rowsT : rowsB, c.dims[l - 1], c.dims[l])));
+        part_w[l] = static_cast<float *>(ctx->scratch(reduce_partial_bytes(layer_rows(l), c.dims[l - 1], c.dims[l])));
         part_ok = part_ok && part_w[l];
     }
+    float *colsum = static_cast<float *>(ctx->scratch(column_sums_bytes(maxd)));
+    part_ok = part_ok && colsum;
     if (!dgi || !dgh || !dz || !dz2 || !dagg || !part_ok) {
         ctx->scratch_reset();
         return ctx->fail(REINC_E_NOMEM, "arena exhausted: no room for the backward scratch buffers");
@@ -625,11 +672,43 @@ int reinc_backward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *pa
         }));
         for (int l = Lg; l >= 1; --l) {
             const int din = c.dims[l - 1], dout = c.dims[l];
-            for (int32_t i = lo; i <= hi; ++i) Ap[i] = l == 1 ? s1[i] : ctx->local[i].S[l];
             calls = 0;
             // dz holds the gradients of layer l's pre-activations: nl rows per timestep (the top rows for the last layer)
             const bool top_l = top && l == Lg;
             const int64_t nl = l == Lg ? nt : n;
+            if (transform_first(c, l)) {
+                // H^l = ReLU(Q (A + sI) P Z + b_l), Z = H^{l-1} W_l:  db_l = column sums of dz;  dZ = P (A + sI)^T Q dz (the
+                // adjoint gather, dout wide);  dW_l = H^{l-1}^T dZ;  dz of layer l-1 = (dZ W_l^T) masked by H^{l-1} > 0
+                launch_column_sums(dz, nl * nb, dout, colsum, const_cast<float *>(gp.b[l]), 1, s);
+                const float *dz_full = dz;
+                if (top_l) {  // the adjoint reads every row: the rows that are not computed are zero
+                    launch_fill_f32(dagg, int64_t(nb) * n * dout, 0.0f, s);
+                    for (int32_t i = lo; i <= hi; ++i)
+                        REINC_HIP(ctx, hipMemcpyAsync(dagg + int64_t(i - lo) * n * dout, dz + int64_t(i - lo) * nt * dout,
+                                                      uint64_t(nt) * dout * 4, hipMemcpyDeviceToDevice, s));
+                    dz_full = dagg;
+                }
+                AggBatch batch;
+                batch.count = nb;
+                for (int32_t i = lo; i <= hi; ++i) {
+                    const Snapshot &sn = ctx->snaps[t0 + i];
+                    batch.item[i - lo] = AggItem{sn.col_ptr, sn.row, dz_full + int64_t(i - lo) * n * dout, sn.q, sn.p, nullptr, nullptr,
+                                                 dz2 + int64_t(i - lo) * n * dout, sn.long_cols, sn.n_long_cols};
+                    batch.item[i - lo].order = sn.col_order;
+                }
+                aggregate_full_batch(ctx, batch, 0, dout, c.self_loop, s);
+                for (int32_t i = lo; i <= hi; ++i) Ap[i] = ctx->local[i].H[l - 1];
+                REINC_TRY(for_runs(lo, hi, n, {Strip{Ap.data(), din}}, [&](int i0, int len) {
+                    reduce(Ap[i0], din, nof, dz2 + int64_t(i0 - lo) * n * dout, dout, n * len, rowsB, din, dout, part_w[l],
+                           acc0 | (calls++ > 0));
+                    gemm_rows(ctx, s, (const void *)(dz2 + int64_t(i0 - lo) * n * dout), 0, n * len, dout, din, nof, p.W[l], 1, dout, nof,
+                              0, nof, Ap[i0], (top_l ? dz : dagg) + int64_t(i0 - lo) * n * din);
+                    return REINC_OK;
+                }));
+                if (!top_l) std::swap(dz, dagg);  // (with top rows dz itself received the full-height result)
+                continue;
+            }
+            for (int32_t i = lo; i <= hi; ++i) Ap[i] = l == 1 ? s1[i] : ctx->local[i].S[l];
             REINC_TRY(for_runs(lo, hi, nl, {Strip{Ap.data(), din}, Strip{has_q ? q.data() : nullptr, 1}},
                                [&](int i0, int len) {
                                    reduce(Ap[i0], din, q[i0], dz + int64_t(i0 - lo) * nl * dout, dout, nl * len, l == Lg ? rowsT : rowsB,
@@ -664,9 +743,9 @@ int reinc_backward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *pa
     }
     launch_reduce_partials(part_wi, rowsT, c.dims[Lg], KH, const_cast<float *>(gp.W_i), const_cast<float *>(gp.b_i), s);
     launch_reduce_partials(part_wh, rowsT, H, KH, const_cast<float *>(gp.W_h), const_cast<float *>(gp.b_h), s);
-    for (int l = 1; l <= Lg; ++l)
-        launch_reduce_partials(part_w[l], l == Lg ? rowsT : rowsB, c.dims[l - 1], c.dims[l], const_cast<float *>(gp.W[l]),
-                               const_cast<float *>(gp.b[l]), s);
+    for (int l = 1; l <= Lg; ++l)  // (the bias gradient of a transform-first layer is not the slabs' column sum: see above)
+        launch_reduce_partials(part_w[l], layer_rows(l), c.dims[l - 1], c.dims[l], const_cast<float *>(gp.W[l]),
+                               transform_first(c, l) ? nullptr : const_cast<float *>(gp.b[l]), s);
     REINC_HIP(ctx, hipGetLastError());
     return REINC_OK;
 }
