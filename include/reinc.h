@@ -115,11 +115,11 @@ const char *reinc_last_error(const reinc_ctx *ctx);
 int reinc_arena_free_bytes(const reinc_ctx *ctx, uint64_t *out);
 
 /* ---- load the snapshot sequence (Section 2.1: snapshots G_t with features F_t) --------------------------
- * reinc_load_edges: src/dst are HOST arrays of nnz int32 endpoints in any order.  Duplicates and
- * self-loops are removed; ids outside [0, N) give REINC_E_ARG.  The list is copied to the device, where the
- * canonical CSR (by destination) and CSC (by source) of snapshot t are built (key sort, de-duplication).  SYNC.
- * Each snapshot is loaded once. */
-int reinc_load_edges(reinc_ctx *ctx, int32_t t, const int32_t *src, const int32_t *dst, int64_t nnz);
+ * reinc_load_edges: src/dst are arrays of nnz int32 endpoints in any order, in HOST memory (on_device = 0) or in
+ * DEVICE memory (on_device = 1).  Duplicates and self-loops are removed; ids outside [0, N) give REINC_E_ARG.  The
+ * list is copied into the arena, where the canonical CSR (by destination) and CSC (by source) of snapshot t are
+ * built (key sort, de-duplication); the caller's arrays are not kept.  SYNC.  Each snapshot is loaded once. */
+int reinc_load_edges(reinc_ctx *ctx, int32_t t, const int32_t *src, const int32_t *dst, int64_t nnz, int on_device);
 /* X_t = the given [N, dims[0]] matrix (fp32, or bf16 bit patterns when feat_dtype is bf16).
  * on_device selects whether X is a device or a host pointer.  SYNC. */
 int reinc_load_features_full(reinc_ctx *ctx, int32_t t, const void *X, int on_device);

@@ -112,10 +112,10 @@ int reinc_arena_free_bytes(const reinc_ctx *ctx, uint64_t *out)
 
 // ------------------------------------------------------------------------------------------------ loading
 
-int reinc_load_edges(reinc_ctx *ctx, int32_t t, const int32_t *src, const int32_t *dst, int64_t nnz)
+int reinc_load_edges(reinc_ctx *ctx, int32_t t, const int32_t *src, const int32_t *dst, int64_t nnz, int on_device)
 {
     if (!ctx) return REINC_E_ARG;
-    return reinc::load_edges(ctx, t, src, dst, nnz, false);
+    return reinc::load_edges(ctx, t, src, dst, nnz, on_device != 0);
 }
 
 extern "C++" int reinc::load_edges(reinc_ctx *ctx, int32_t t, const int32_t *src, const int32_t *dst, int64_t nnz, bool on_device)

@@ -82,7 +82,7 @@ def load_library() -> ctypes.CDLL:
         "reinc_create": [ctypes.POINTER(p), ctypes.POINTER(Config)],
         "reinc_destroy": [p],
         "reinc_arena_free_bytes": [p, ctypes.POINTER(ctypes.c_uint64)],
-        "reinc_load_edges": [p, i32, p, p, i64],
+        "reinc_load_edges": [p, i32, p, p, i64, ci],
         "reinc_load_features_full": [p, i32, p, ci],
         "reinc_load_features_delta": [p, i32, p, i64, p],
         "reinc_build_deltas": [p, i32, p],
@@ -214,12 +214,22 @@ class Context:
             raise ReincError(rc, self.lib.reinc_last_error(self.handle).decode())
 
     # ---- loading
-    def load_edges(self, t: int, src: np.ndarray, dst: np.ndarray):
+    def load_edges(self, t: int, src, dst):
+        """src, dst: int32 endpoint arrays, numpy (host) or torch tensors on this context's device."""
+        import torch
+
+        if isinstance(src, torch.Tensor) or isinstance(dst, torch.Tensor):
+            if not (isinstance(src, torch.Tensor) and isinstance(dst, torch.Tensor)) or src.dtype != torch.int32 or dst.dtype != torch.int32:
+                raise ValueError("device edge lists are two int32 tensors")
+            if src.shape != dst.shape or src.dim() != 1:
+                raise ValueError("src and dst differ in length")
+            self._ck(self.lib.reinc_load_edges(self.handle, t, _dev_ptr(src), _dev_ptr(dst), src.numel(), 1))
+            return
         src = np.ascontiguousarray(src, dtype=np.int32)
         dst = np.ascontiguousarray(dst, dtype=np.int32)
         if src.shape != dst.shape:
             raise ValueError("src and dst differ in length")
-        self._ck(self.lib.reinc_load_edges(self.handle, t, _np_ptr(src), _np_ptr(dst), src.size))
+        self._ck(self.lib.reinc_load_edges(self.handle, t, _np_ptr(src), _np_ptr(dst), src.size, 0))
 
     def _host_feats(self, x: np.ndarray) -> np.ndarray:
         if self.feat_dtype == "bf16":

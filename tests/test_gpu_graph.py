@@ -74,6 +74,23 @@ def test_full_feature_loads_find_the_same_change_set():
     _check_all_steps(synth.make_sequence(wl), delta_features=False)
 
 
+def test_edge_lists_in_device_memory_give_the_same_snapshots(tiny_seq):
+    """The raw edge list may already sit in device memory (on_device = 1): same canonical CSR and CSC."""
+    import torch
+
+    wl = tiny_seq.workload
+    host, dev = _ctx(wl), _ctx(wl)
+    for t in (0, 3):
+        src, dst = tiny_seq.edges[t]
+        host.load_edges(t, src, dst)
+        dev.load_edges(t, torch.from_numpy(src).cuda(), torch.from_numpy(dst).cuda())
+        for transpose in (False, True):
+            a, b = host.get_snapshot_csr(t, transpose), dev.get_snapshot_csr(t, transpose)
+            assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+    host.close()
+    dev.close()
+
+
 def test_a_listed_row_with_unchanged_values_is_not_in_the_change_set():
     """Delta-mode loading ships (row, values) pairs; the change set is defined by the values: a row that is sent again
     with the values it already had belongs to it as little as it would after a full load."""
