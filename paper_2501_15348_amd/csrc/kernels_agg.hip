@@ -21,8 +21,13 @@ namespace reinc {
 namespace {
 
 constexpr int kWavesPerBlock = 4;
-constexpr int kUnroll = 8;        // source rows in flight per lane in the wave-per-row kernels
+constexpr int kUnroll = 8;         // source rows in flight per lane in the wave-per-row kernels
 constexpr int kUnrollGrouped = 8;  // in the group-per-row kernels (16 lowers occupancy and measured slower)
+// The sum aggregation of bfloat16 rows keeps eight values per gathered row and lane, twice the registers of fp32 rows:
+// four rows in flight leave room for more wavefronts per SIMD, which pays (2.5e6 rows of 512 bytes, 5e7 edges: both
+// kernels together 6.92 -> 4.73 ms); on fp32 rows four in flight is 1-4 % slower than eight.
+template <bool BF16>
+constexpr int kSumUnroll = BF16 ? 4 : 8;
 
 template <bool BF16>
 struct Row;
@@ -92,12 +97,12 @@ __device__ inline void gather_segment(const int32_t *idx, int64_t beg, int64_t e
             my_u = idx[base + lane];
             if (in_scale) my_sc = in_scale[my_u];
         }
-        for (int k = 0; k < cnt; k += G * kUnroll) {
-            float r[kUnroll][VEC];
-            float sc[kUnroll];
+        for (int k = 0; k < cnt; k += G * kSumUnroll<BF16>) {
+            float r[kSumUnroll<BF16>][VEC];
+            float sc[kSumUnroll<BF16>];
             // the row gathers depend only on the column ids: issue them before touching the gathered scales
 #pragma unroll
-            for (int j = 0; j < kUnroll; ++j) {
+            for (int j = 0; j < kSumUnroll<BF16>; ++j) {
                 const int e = k + j * G + g;
                 const int32_t u = __shfl(my_u, e & 63);
                 if (e < cnt) {
@@ -108,13 +113,13 @@ __device__ inline void gather_segment(const int32_t *idx, int64_t beg, int64_t e
                 }
             }
 #pragma unroll
-            for (int j = 0; j < kUnroll; ++j) {
+            for (int j = 0; j < kSumUnroll<BF16>; ++j) {
                 const int e = k + j * G + g;
                 sc[j] = __shfl(my_sc, e & 63);
                 if (e >= cnt) sc[j] = 0.0f;
             }
 #pragma unroll
-            for (int j = 0; j < kUnroll; ++j)
+            for (int j = 0; j < kSumUnroll<BF16>; ++j)
 #pragma unroll
                 for (int i = 0; i < VEC; ++i) acc[i] += sc[j] * r[j][i];
         }
@@ -184,11 +189,11 @@ aggregate_rows_grouped(AggBatch batch, int64_t n, int self_loop)
             if (in_scale) my_sc = in_scale[my_u];
         }
         const int cmax = min(LPR, maxlen - base);
-        for (int k = 0; k < cmax; k += kUnrollGrouped) {
-            float r[kUnrollGrouped][VEC];
-            float sc[kUnrollGrouped];
+        for (int k = 0; k < cmax; k += kSumUnroll<BF16>) {
+            float r[kSumUnroll<BF16>][VEC];
+            float sc[kSumUnroll<BF16>];
 #pragma unroll
-            for (int j = 0; j < kUnrollGrouped; ++j) {
+            for (int j = 0; j < kSumUnroll<BF16>; ++j) {
                 const int e = k + j;
                 const int32_t u = __shfl(my_u, gbase + (e & (LPR - 1)));
                 if (e < cnt) {
@@ -199,13 +204,13 @@ aggregate_rows_grouped(AggBatch batch, int64_t n, int self_loop)
                 }
             }
 #pragma unroll
-            for (int j = 0; j < kUnrollGrouped; ++j) {
+            for (int j = 0; j < kSumUnroll<BF16>; ++j) {
                 const int e = k + j;
                 sc[j] = __shfl(my_sc, gbase + (e & (LPR - 1)));
                 if (e >= cnt) sc[j] = 0.0f;
             }
 #pragma unroll
-            for (int j = 0; j < kUnrollGrouped; ++j)
+            for (int j = 0; j < kSumUnroll<BF16>; ++j)
 #pragma unroll
                 for (int i = 0; i < VEC; ++i) acc[i] += sc[j] * r[j][i];
         }
@@ -328,8 +333,9 @@ aggregate_long_rows(AggBatch batch, int self_loop)
 }
 
 // Rows of S a block of incremental_segmented works on: as many as make a 16 KB tile of fp32 sums (16 rows of 256
-// values, 64 rows of 64).  Measured on 2.5e6 rows of 256 bf16 values with 1e7 entries: 8 rows 2.63 ms, 16 rows 2.22 ms,
-// 32 rows 2.47 ms; the smaller tile lets more blocks share a compute unit while they wait in different phases.
+// values, 64 rows of 64).  Measured on 2.5e6 rows of 256 bf16 values with 1e7 entries (four gathers in flight): 4 rows
+// 2.23 ms, 8 rows 1.78, 16 rows 1.73, 32 rows 2.46; a small tile lets more blocks share a compute unit while they wait
+// in different phases.
 constexpr int inc_rows_per_block(int d) { return 4096 / d < 8 ? 8 : (4096 / d > 256 ? 256 : 4096 / d); }
 
 // Eq. 2 in the form  S_t[r] = S_{t-1}[r] + sum_ins Y_{t-1}[u] - sum_del Y_{t-1}[u] + sum_changed dY[u].
@@ -356,7 +362,10 @@ incremental_segmented(const int32_t *__restrict__ rows, const int64_t *__restric
     constexpr int NG = kWavesPerBlock * G;  // lane groups per block
     constexpr int RB = inc_rows_per_block(D);
     constexpr int kThreads = 64 * kWavesPerBlock;
-    constexpr int kU = kUnrollGrouped;  // gathers a lane has in flight (16 spills at 512-byte bf16 rows: 1.5x slower)
+    // gathers a lane has in flight.  Four: the registers of eight (103 at 512-byte bf16 rows) leave four wavefronts per
+    // SIMD, and the kernel gains more from the blocks that then share a compute unit than from deeper gathers
+    // (2.5e6 rows, 1e7 entries: 2, 3, 4 in flight 1.73 ms, 6: 1.92, 8: 2.22, 12: 2.77, 16: 3.3)
+    constexpr int kU = 4;
     __shared__ __align__(16) float tile[RB * D];      // delta sums of the block's rows
     __shared__ __align__(16) float part[NG * D];      // per group: its piece of a row that began in an earlier share
     __shared__ int32_t part_row[2 * NG];              // [2 g]: the row of that piece; [2 g + 1]: the row that begins in

@@ -80,7 +80,7 @@ def test_unsupported_width_is_an_error():
 
 
 def test_hub_rows_take_the_block_path():
-    """Rows beyond 512 entries are reduced by a whole block; both CSR and CSC sides."""
+    """Rows of more than 64 entries are reduced by a whole block; both CSR and CSC sides."""
     n, d = 5000, 64
     rng = np.random.default_rng(3)
     src = np.concatenate([rng.choice(np.arange(1, n), 3000, replace=False), np.full(2500, 1), rng.integers(0, n, 20000)])
