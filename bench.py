@@ -520,7 +520,7 @@ def minibatch_rows(ctx, wl, seq, params, target, L, label):
             total, _ = ctx.batch_plan(batch)
             frac = total / n
             child_arena = int(frac * ctx.cfg.arena_bytes) + (512 << 20)
-            child = ctx.batch_context(batch, child_arena)
+            child = ctx.batch_context(batch, child_arena, planned_total=total)
             torch.cuda.synchronize()
             acc["extract_ms"].append((time.perf_counter() - t0) * 1e3)
             t0 = time.perf_counter()

@@ -118,6 +118,124 @@ int reinc_load_edges(reinc_ctx *ctx, int32_t t, const int32_t *src, const int32_
     return reinc::load_edges(ctx, t, src, dst, nnz, on_device != 0);
 }
 
+// Scratch of the device-side canonicalisation of one snapshot of at most m raw edges (n nodes).
+struct LoadScratch {
+    int32_t *d_src, *d_dst;
+    uint64_t *keys0, *keys1;
+    int32_t *flag, *flag2;
+    int64_t *offs, *offs2;
+    int64_t *counts;  // small: totals gathered for one copy to the host
+    void *sort_tmp, *scan_tmp;
+    size_t sort_bytes;
+    bool ok;
+};
+
+static LoadScratch load_scratch(reinc_ctx *ctx, int64_t m, int64_t n, bool raw_lists)
+{
+    LoadScratch w{};
+    const int64_t mm = std::max(std::max<int64_t>(m, 1), n);  // (the key arrays also serve the per-node sort by row length)
+    if (raw_lists) {
+        w.d_src = static_cast<int32_t *>(ctx->scratch(uint64_t(std::max<int64_t>(m, 1)) * 4));
+        w.d_dst = static_cast<int32_t *>(ctx->scratch(uint64_t(std::max<int64_t>(m, 1)) * 4));
+    }
+    w.keys0 = static_cast<uint64_t *>(ctx->scratch(uint64_t(mm) * 8));
+    w.keys1 = static_cast<uint64_t *>(ctx->scratch(uint64_t(mm) * 8));
+    w.flag = static_cast<int32_t *>(ctx->scratch(uint64_t(mm) * 4));
+    w.offs = static_cast<int64_t *>(ctx->scratch(uint64_t(mm + 1) * 8));
+    w.flag2 = static_cast<int32_t *>(ctx->scratch(uint64_t(n) * 4));
+    w.offs2 = static_cast<int64_t *>(ctx->scratch(uint64_t(n + 1) * 8));
+    w.counts = static_cast<int64_t *>(ctx->scratch(256));
+    w.sort_bytes = sort_keys_tmp_bytes(mm);
+    w.sort_tmp = ctx->scratch(w.sort_bytes);
+    w.scan_tmp = ctx->scratch(2 * scan_tmp_bytes(mm));
+    w.ok = (!raw_lists || (w.d_src && w.d_dst)) && w.keys0 && w.keys1 && w.flag && w.offs && w.flag2 && w.offs2 && w.counts &&
+           w.sort_tmp && w.scan_tmp;
+    return w;
+}
+
+static unsigned node_bits_of(int64_t n)
+{
+    unsigned bits = 1;
+    while ((int64_t(1) << bits) <= n) ++bits;  // the sentinel row id n must sort correctly too
+    return bits;
+}
+
+extern "C++" unsigned reinc::node_key_bits(int64_t n) { return node_bits_of(n); }
+
+// The rest of a snapshot once its e canonical edges are known: sn.col / sn.rowid hold the CSR entries (allocated and
+// filled by the caller), w.keys0 the same edges in the same order keyed by source (source << 32 | target).  Builds
+// the row pointers, the CSC, the degree scales, the row / column orders by falling length and the lists of long rows /
+// columns.  Waits for the device.
+static int finish_snapshot(reinc_ctx *ctx, int32_t t, int64_t e, const LoadScratch &w, uint64_t mark, hipStream_t s)
+{
+    Snapshot &sn = ctx->snaps[t];
+    const int64_t n = ctx->N();
+    const unsigned node_bits = node_bits_of(n);
+    auto fail_nomem = [&](const char *what) {
+        ctx->bottom = mark;
+        ctx->scratch_reset();
+        sn = Snapshot();
+        return ctx->fail(REINC_E_NOMEM, "arena exhausted while canonicalising snapshot %d: %s", t, what);
+    };
+    launch_ptr_from_rowid(sn.rowid, e, n, sn.row_ptr, s);
+    // (w.keys0 is in the CSR's order, ascending by target within a source, and the sort is stable: the source bits suffice)
+    REINC_HIP(ctx, sort_keys(w.sort_tmp, w.sort_bytes, w.keys0, w.keys1, e, 32, 32 + node_bits, s));
+    launch_low_halves(w.keys1, e, sn.row, s);
+    launch_ptr_from_sorted(w.keys1, e, n, sn.col_ptr, s);
+    const int agg = ctx->cfg.agg_kind;
+    if (agg != REINC_AGG_SUM) {
+        sn.q = ctx->q_block + int64_t(t) * n;  // one [T, N] block: the scales of consecutive snapshots are adjacent
+        launch_degree_scales(sn.row_ptr, n, agg == REINC_AGG_SYM, ctx->cfg.self_loop, sn.q, s);
+        if (agg == REINC_AGG_SYM) sn.p = sn.q;  // same numbers on both sides
+    }
+    // rows and columns by falling length: the order in which the group-per-row aggregation kernel takes them
+    sn.row_order = static_cast<int32_t *>(ctx->alloc(uint64_t(n) * 4));
+    sn.col_order = static_cast<int32_t *>(ctx->alloc(uint64_t(n) * 4));
+    if (!sn.row_order || !sn.col_order) return fail_nomem("row order lists");
+    for (int side = 0; side < 2; ++side) {
+        launch_length_keys(side == 0 ? sn.row_ptr : sn.col_ptr, n, w.keys0, s);
+        // (the keys are ascending in their low halves, the node ids, and the sort is stable: only the seven bits of the
+        // capped length need sorting)
+        REINC_HIP(ctx, sort_keys(w.sort_tmp, w.sort_bytes, w.keys0, w.keys1, n, 32, 32 + 7, s));
+        launch_low_halves(w.keys1, n, side == 0 ? sn.row_order : sn.col_order, s);
+    }
+    // rows / columns that take the block-per-row aggregation path: both lists are sized by one copy to the host
+    char *scan_tmp2 = static_cast<char *>(w.scan_tmp) + scan_tmp_bytes(n);
+    launch_long_flags(sn.row_ptr, n, w.flag, s);
+    launch_scan(w.flag, w.offs, n, w.scan_tmp, s);
+    launch_long_flags(sn.col_ptr, n, w.flag2, s);
+    launch_scan(w.flag2, w.offs2, n, scan_tmp2, s);
+    int64_t cnt[2] = {0, 0};
+    REINC_HIP(ctx, hipMemcpyAsync(&cnt[0], w.offs + n, 8, hipMemcpyDeviceToHost, s));
+    REINC_HIP(ctx, hipMemcpyAsync(&cnt[1], w.offs2 + n, 8, hipMemcpyDeviceToHost, s));
+    REINC_HIP(ctx, hipStreamSynchronize(s));
+    sn.long_rows = static_cast<int32_t *>(ctx->alloc(uint64_t(std::max<int64_t>(cnt[0], 1)) * 4));
+    sn.long_cols = static_cast<int32_t *>(ctx->alloc(uint64_t(std::max<int64_t>(cnt[1], 1)) * 4));
+    if (!sn.long_rows || !sn.long_cols) return fail_nomem("long row lists");
+    launch_compact(w.flag, w.offs, n, sn.long_rows, nullptr, s);
+    launch_compact(w.flag2, w.offs2, n, sn.long_cols, nullptr, s);
+    sn.n_long_rows = int32_t(cnt[0]);
+    sn.n_long_cols = int32_t(cnt[1]);
+    REINC_HIP(ctx, hipGetLastError());
+    REINC_HIP(ctx, hipStreamSynchronize(s));
+    sn.nnz = e;
+    sn.edges_loaded = true;
+    if (ctx->has_derived) ctx->load_after_derived = true;
+    return REINC_OK;
+}
+
+static int alloc_snapshot_arrays(reinc_ctx *ctx, Snapshot &sn, int64_t e)
+{
+    const int64_t n = ctx->N();
+    const uint64_t ee = uint64_t(std::max<int64_t>(e, 1));
+    sn.row_ptr = static_cast<int64_t *>(ctx->alloc(uint64_t(n + 1) * 8));
+    sn.col = static_cast<int32_t *>(ctx->alloc(ee * 4));
+    sn.rowid = static_cast<int32_t *>(ctx->alloc(ee * 4));
+    sn.col_ptr = static_cast<int64_t *>(ctx->alloc(uint64_t(n + 1) * 8));
+    sn.row = static_cast<int32_t *>(ctx->alloc(ee * 4));
+    return sn.row_ptr && sn.col && sn.rowid && sn.col_ptr && sn.row;
+}
+
 extern "C++" int reinc::load_edges(reinc_ctx *ctx, int32_t t, const int32_t *src, const int32_t *dst, int64_t nnz, bool on_device)
 {
     REINC_TRY(check_t(ctx, t));
@@ -133,93 +251,35 @@ extern "C++" int reinc::load_edges(reinc_ctx *ctx, int32_t t, const int32_t *src
     auto fail_nomem = [&](const char *what) {
         ctx->bottom = mark;
         ctx->scratch_reset();
+        sn = Snapshot();
         return ctx->fail(REINC_E_NOMEM, "arena exhausted while canonicalising snapshot %d: %s", t, what);
     };
-    const int64_t m = std::max<int64_t>(nnz, 1);
-    int32_t *d_src = static_cast<int32_t *>(ctx->scratch(uint64_t(m) * 4));
-    int32_t *d_dst = static_cast<int32_t *>(ctx->scratch(uint64_t(m) * 4));
-    const int64_t mm = std::max(m, n);  // (the key arrays also serve the per-node sort by row length below)
-    uint64_t *keys0 = static_cast<uint64_t *>(ctx->scratch(uint64_t(mm) * 8));
-    uint64_t *keys1 = static_cast<uint64_t *>(ctx->scratch(uint64_t(mm) * 8));
-    int32_t *flag = static_cast<int32_t *>(ctx->scratch(uint64_t(std::max(m, n)) * 4));
-    int64_t *offs = static_cast<int64_t *>(ctx->scratch(uint64_t(std::max(m, n) + 1) * 8));
-    int32_t *err = static_cast<int32_t *>(ctx->scratch(256));
-    const size_t sort_bytes = sort_keys_tmp_bytes(mm);
-    void *sort_tmp = ctx->scratch(sort_bytes);
-    void *scan_tmp = ctx->scratch(scan_tmp_bytes(std::max(m, n)));
-    if (!d_src || !d_dst || !keys0 || !keys1 || !flag || !offs || !err || !sort_tmp || !scan_tmp) return fail_nomem("scratch");
+    const LoadScratch w = load_scratch(ctx, nnz, n, true);
+    int32_t *err = reinterpret_cast<int32_t *>(w.counts);
+    if (!w.ok) return fail_nomem("scratch");
     if (nnz > 0) {
         const hipMemcpyKind kind = on_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice;
-        REINC_HIP(ctx, hipMemcpy(d_src, src, size_t(nnz) * 4, kind));
-        REINC_HIP(ctx, hipMemcpy(d_dst, dst, size_t(nnz) * 4, kind));
+        REINC_HIP(ctx, hipMemcpy(w.d_src, src, size_t(nnz) * 4, kind));
+        REINC_HIP(ctx, hipMemcpy(w.d_dst, dst, size_t(nnz) * 4, kind));
     }
     launch_fill_i32(err, 1, 0, s);
-    unsigned node_bits = 1;
-    while ((int64_t(1) << node_bits) <= n) ++node_bits;  // the sentinel row id n must sort correctly too
-    launch_make_keys(d_src, d_dst, nnz, n, keys0, err, s);
-    REINC_HIP(ctx, sort_keys(sort_tmp, sort_bytes, keys0, keys1, nnz, 32 + node_bits, s));
-    launch_unique_flags(keys1, nnz, n, flag, s);
-    launch_scan(flag, offs, nnz, scan_tmp, s);
+    launch_make_keys(w.d_src, w.d_dst, nnz, n, w.keys0, err, s);
+    REINC_HIP(ctx, sort_keys(w.sort_tmp, w.sort_bytes, w.keys0, w.keys1, nnz, 0, 32 + node_bits_of(n), s));
+    launch_unique_flags(w.keys1, nnz, n, w.flag, s);
+    launch_scan(w.flag, w.offs, nnz, w.scan_tmp, s);
     int64_t e = 0;
     int32_t bad = 0;
-    REINC_HIP(ctx, hipMemcpy(&e, offs + std::max<int64_t>(nnz, 0), 8, hipMemcpyDeviceToHost));
+    REINC_HIP(ctx, hipMemcpy(&e, w.offs + std::max<int64_t>(nnz, 0), 8, hipMemcpyDeviceToHost));
     REINC_HIP(ctx, hipMemcpy(&bad, err, 4, hipMemcpyDeviceToHost));
     if (bad) {
         ctx->scratch_reset();
         return ctx->fail(REINC_E_ARG, "snapshot %d: an edge endpoint is outside [0, %lld)", t, (long long)n);
     }
-    sn.nnz = e;
-    const uint64_t ee = uint64_t(std::max<int64_t>(e, 1));
-    sn.row_ptr = static_cast<int64_t *>(ctx->alloc(uint64_t(n + 1) * 8));
-    sn.col = static_cast<int32_t *>(ctx->alloc(ee * 4));
-    sn.rowid = static_cast<int32_t *>(ctx->alloc(ee * 4));
-    sn.col_ptr = static_cast<int64_t *>(ctx->alloc(uint64_t(n + 1) * 8));
-    sn.row = static_cast<int32_t *>(ctx->alloc(ee * 4));
-    if (!sn.row_ptr || !sn.col || !sn.rowid || !sn.col_ptr || !sn.row) return fail_nomem("CSR / CSC");
+    if (!alloc_snapshot_arrays(ctx, sn, e)) return fail_nomem("CSR / CSC");
     // CSR by destination from the sorted unique keys; the same edges keyed by source give the CSC
-    launch_scatter_unique(keys1, flag, offs, nnz, sn.col, sn.rowid, keys0, s);
-    launch_ptr_from_rowid(sn.rowid, e, n, sn.row_ptr, s);
-    REINC_HIP(ctx, sort_keys(sort_tmp, sort_bytes, keys0, keys1, e, 32 + node_bits, s));
-    launch_low_halves(keys1, e, sn.row, s);
-    launch_ptr_from_sorted(keys1, e, n, sn.col_ptr, s);
-    const int agg = ctx->cfg.agg_kind;
-    if (agg != REINC_AGG_SUM) {
-        sn.q = ctx->q_block + int64_t(t) * n;  // one [T, N] block: the scales of consecutive snapshots are adjacent
-        launch_degree_scales(sn.row_ptr, n, agg == REINC_AGG_SYM, ctx->cfg.self_loop, sn.q, s);
-        if (agg == REINC_AGG_SYM) sn.p = sn.q;  // same numbers on both sides
-    }
-    // rows and columns by falling length: the order in which the group-per-row aggregation kernel takes them
-    sn.row_order = static_cast<int32_t *>(ctx->alloc(uint64_t(n) * 4));
-    sn.col_order = static_cast<int32_t *>(ctx->alloc(uint64_t(n) * 4));
-    if (!sn.row_order || !sn.col_order) return fail_nomem("row order lists");
-    for (int side = 0; side < 2; ++side) {
-        launch_length_keys(side == 0 ? sn.row_ptr : sn.col_ptr, n, keys0, s);
-        REINC_HIP(ctx, sort_keys(sort_tmp, sort_bytes, keys0, keys1, n, 32 + 7, s));  // lengths are capped at kLongRow + 1 < 128
-        launch_low_halves(keys1, n, side == 0 ? sn.row_order : sn.col_order, s);
-    }
-    // rows / columns that take the block-per-row aggregation path
-    for (int side = 0; side < 2; ++side) {
-        const int64_t *ptr = side == 0 ? sn.row_ptr : sn.col_ptr;
-        launch_long_flags(ptr, n, flag, s);
-        launch_scan(flag, offs, n, scan_tmp, s);
-        int64_t cnt = 0;
-        REINC_HIP(ctx, hipMemcpy(&cnt, offs + n, 8, hipMemcpyDeviceToHost));
-        int32_t *list = static_cast<int32_t *>(ctx->alloc(uint64_t(std::max<int64_t>(cnt, 1)) * 4));
-        if (!list) return fail_nomem("long row list");
-        launch_compact(flag, offs, n, list, nullptr, s);
-        if (side == 0) {
-            sn.long_rows = list;
-            sn.n_long_rows = int32_t(cnt);
-        } else {
-            sn.long_cols = list;
-            sn.n_long_cols = int32_t(cnt);
-        }
-    }
-    REINC_HIP(ctx, hipGetLastError());
-    REINC_HIP(ctx, hipDeviceSynchronize());
+    launch_scatter_unique(w.keys1, w.flag, w.offs, nnz, sn.col, sn.rowid, w.keys0, s);
+    REINC_TRY(finish_snapshot(ctx, t, e, w, mark, s));
     ctx->scratch_reset();
-    sn.edges_loaded = true;
-    if (ctx->has_derived) ctx->load_after_derived = true;
     return REINC_OK;
 }
 

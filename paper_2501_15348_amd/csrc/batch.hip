@@ -34,16 +34,6 @@ __global__ void batch_seed(const int32_t *nodes, int64_t nb, int32_t *level, int
     node_list[i] = v;
 }
 
-// hop k: the source of an edge whose target was reached in fewer than k hops is reached in at most k.  Levels
-// below k are final and levels of k are only ever written as k during this launch, so the order of the threads
-// does not matter.
-__global__ void batch_expand(const int32_t *rowid, const int32_t *col, int64_t e, int32_t *level, int32_t k)
-{
-    const int64_t i = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
-    if (i >= e) return;
-    if (level[rowid[i]] < k) atomicMin(&level[col[i]], k);
-}
-
 // flags of the nodes that join the batch nodes in the sub-sequence, and the count of inner nodes (targets kept)
 __global__ void batch_member_flags(const int32_t *level, int64_t n, int32_t hops, int32_t *flag, unsigned long long *inner)
 {
@@ -63,34 +53,179 @@ __global__ void batch_number(const int32_t *flag, const int64_t *offs, int64_t n
     node_list[id] = int32_t(v);
 }
 
-__global__ void batch_edge_flags(const int32_t *rowid, int64_t e, const int32_t *level, int32_t hops, int32_t *flag)
+// ---- extraction of all snapshots of the sub-sequence in one pass: blockIdx.y (or a key's top bits) picks the snapshot ----
+// A batch graph is small (thousands of rows), so one snapshot at a time would be a few dozen launches of almost
+// empty kernels per snapshot.  Here every step handles the T snapshots together; the source and the batch context
+// are described to the kernels by one table each.
+struct MbSrc {
+    const int64_t *row_ptr;
+    const int32_t *rowid, *col;
+    const float *q;
+    const void *x;
+    int64_t nnz;
+};
+struct MbDst {
+    int64_t *row_ptr, *col_ptr;
+    int32_t *col, *rowid, *row, *row_order, *col_order, *long_rows, *long_cols;
+    float *q;
+    void *x;
+};
+
+// hop k: the source of an edge whose target was reached in fewer than k hops is reached in at most k.  Levels
+// below k are final and levels of k are only ever written as k during this launch, so the order of the threads
+// does not matter.
+__global__ void mb_expand(const MbSrc *src, int32_t *level, int32_t k)
 {
+    const MbSrc sn = src[blockIdx.y];
     const int64_t i = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
-    if (i < e) flag[i] = level[rowid[i]] < hops;
+    if (i >= sn.nnz) return;
+    if (level[sn.rowid[i]] < k) atomicMin(&level[sn.col[i]], k);
 }
 
-__global__ void batch_edge_compact(const int32_t *rowid, const int32_t *col, int64_t e, const int32_t *flag, const int64_t *offs,
-                                   const int32_t *new_id, int32_t *src, int32_t *dst)
+// counts[t * nu + i] = in-edges that row i of the batch graph keeps in snapshot t: all of them if the node's aggregate
+// is needed (it was reached in fewer than `hops` hops), none otherwise
+__global__ void mb_row_counts(const MbSrc *src, const int32_t *nodes, const int32_t *level, int32_t hops, int64_t nu, int32_t *counts)
 {
     const int64_t i = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
-    if (i >= e || !flag[i]) return;
-    src[offs[i]] = new_id[col[i]];
-    dst[offs[i]] = new_id[rowid[i]];
+    if (i >= nu) return;
+    const int32_t v = nodes[i];
+    const int64_t *ptr = src[blockIdx.y].row_ptr;
+    counts[blockIdx.y * nu + i] = level[v] < hops ? int32_t(ptr[v + 1] - ptr[v]) : 0;
 }
 
-__global__ void gather_f32(const float *in, const int32_t *list, int64_t n, float *out)
+// the rows are emitted in the order of their new ids, so the scanned counts are the row pointers already
+__global__ void mb_row_ptrs(const MbDst *dst, const int64_t *offs, int64_t nu, int64_t *kbase)
 {
     const int64_t i = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
-    if (i < n) out[i] = in[list[i]];
+    if (i > nu) return;
+    const int64_t t = blockIdx.y, base = offs[t * nu];
+    dst[t].row_ptr[i] = offs[t * nu + i] - base;
+    if (i == 0) kbase[t] = base;
+    if (i == nu && t + 1 == gridDim.y) kbase[t + 1] = offs[t * nu + nu];
 }
 
-// out row i = in row list[i], in 16-byte pieces
-__global__ void gather_rows(const uint4 *in, const int32_t *list, int64_t nrows, int32_t chunks, uint4 *out)
+// keys of the kept edges, snapshot << 2 shift | new target << shift | new source: 16 lanes copy one row
+__global__ void mb_edge_keys(const MbSrc *src, const int32_t *nodes, const int32_t *level, const int32_t *new_id, int32_t hops, int64_t nu,
+                             int64_t rows_total, const int64_t *offs, unsigned shift, uint64_t *keys)
+{
+    const int64_t r = (blockIdx.x * int64_t(blockDim.x) + threadIdx.x) >> 4;
+    const int lane = threadIdx.x & 15;
+    if (r >= rows_total) return;
+    const int64_t t = r / nu, i = r - t * nu;
+    const int32_t v = nodes[i];
+    if (level[v] >= hops) return;
+    const MbSrc sn = src[t];
+    const int64_t b = sn.row_ptr[v], len = sn.row_ptr[v + 1] - b, out = offs[r];
+    const uint64_t high = (uint64_t(t) << (2 * shift)) | (uint64_t(i) << shift);
+    for (int64_t e = lane; e < len; e += 16) keys[out + e] = high | uint64_t(uint32_t(new_id[sn.col[b + e]]));
+}
+
+// sorted keys -> the CSR entries of every snapshot, and the same edges keyed by source for the CSC
+__global__ void mb_split(const uint64_t *keys, int64_t total, unsigned shift, const int64_t *kbase, const MbDst *dst, uint64_t *swapped)
+{
+    const int64_t j = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
+    if (j >= total) return;
+    const uint64_t k = keys[j], mask = (uint64_t(1) << shift) - 1, t = k >> (2 * shift), lo = k & mask, hi = (k >> shift) & mask;
+    const int64_t local = j - kbase[t];
+    dst[t].col[local] = int32_t(lo);
+    dst[t].rowid[local] = int32_t(hi);
+    swapped[j] = (t << (2 * shift)) | (lo << shift) | hi;
+}
+
+__global__ void mb_csc_rows(const uint64_t *keys, int64_t total, unsigned shift, const int64_t *kbase, const MbDst *dst)
+{
+    const int64_t j = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
+    if (j >= total) return;
+    const uint64_t k = keys[j], t = k >> (2 * shift);
+    dst[t].row[j - kbase[t]] = int32_t(k & ((uint64_t(1) << shift) - 1));
+}
+
+__global__ void mb_col_ptrs(const uint64_t *keys, unsigned shift, const int64_t *kbase, const MbDst *dst, int64_t nu)
+{
+    const int64_t v = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
+    if (v > nu) return;
+    const int64_t t = blockIdx.y, begin = kbase[t];
+    const uint64_t mask = (uint64_t(1) << shift) - 1;
+    int64_t lo = begin, hi = kbase[t + 1];
+    while (lo < hi) {
+        const int64_t mid = (lo + hi) >> 1;
+        if (int64_t((keys[mid] >> shift) & mask) < v)
+            lo = mid + 1;
+        else
+            hi = mid;
+    }
+    dst[t].col_ptr[v] = lo - begin;
+}
+
+// Degree scales and features of the batch rows.  The scales are those of the source graph: a row of the batch graph
+// holds all of a node's in-edges only for the nodes whose aggregate is needed, but the symmetric normalisation also
+// scales by the degree of an edge's source.
+__global__ void mb_gather_scales(const MbSrc *src, const MbDst *dst, const int32_t *nodes, int64_t nu)
 {
     const int64_t i = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
-    if (i >= nrows * chunks) return;
+    if (i < nu) dst[blockIdx.y].q[i] = src[blockIdx.y].q[nodes[i]];
+}
+
+// out row i = in row nodes[i], in 16-byte pieces
+__global__ void mb_gather_rows(const MbSrc *src, const MbDst *dst, const int32_t *nodes, int64_t nu, int32_t chunks)
+{
+    const int64_t i = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
+    if (i >= nu * chunks) return;
     const int64_t r = i / chunks;
-    out[i] = in[int64_t(list[r]) * chunks + (i - r * chunks)];
+    static_cast<uint4 *>(dst[blockIdx.y].x)[i] = static_cast<const uint4 *>(src[blockIdx.y].x)[int64_t(nodes[r]) * chunks + (i - r * chunks)];
+}
+
+// per row (y < T) and per column (y >= T) of every snapshot: the key that orders it by falling length, and whether
+// it takes the block-per-row path
+__global__ void mb_length_keys(const MbDst *dst, int64_t nu, int32_t T, uint64_t *keys, int32_t *flag)
+{
+    const int64_t v = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
+    if (v >= nu) return;
+    const int64_t y = blockIdx.y;
+    const int64_t *ptr = y < T ? dst[y].row_ptr : dst[y - T].col_ptr;
+    const int64_t full = ptr[v + 1] - ptr[v], len = min(full, int64_t(kLongRow + 1));
+    keys[y * nu + v] = (uint64_t(y) << 39) | (uint64_t(kLongRow + 1 - len) << 32) | uint64_t(v);
+    flag[y * nu + v] = full > kLongRow;
+}
+
+__global__ void mb_orders(const uint64_t *keys, const MbDst *dst, int64_t nu, int32_t T)
+{
+    const int64_t v = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
+    if (v >= nu) return;
+    const int64_t y = blockIdx.y;
+    int32_t *out = y < T ? dst[y].row_order : dst[y - T].col_order;
+    out[v] = int32_t(keys[y * nu + v] & 0xFFFFFFFFu);
+}
+
+__global__ void mb_long_lists(const int32_t *flag, const int64_t *offs, const MbDst *dst, int64_t nu, int32_t T, int64_t *n_long)
+{
+    const int64_t v = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
+    if (v >= nu) return;
+    const int64_t y = blockIdx.y, base = offs[y * nu];
+    int32_t *list = y < T ? dst[y].long_rows : dst[y - T].long_cols;
+    if (flag[y * nu + v]) list[offs[y * nu + v] - base] = int32_t(v);
+    if (v == nu - 1) n_long[y] = offs[y * nu + nu] - base;
+}
+
+// the table of the source snapshots, in scratch memory of ctx (null: no room or the copy failed)
+const MbSrc *source_table(reinc_ctx *ctx, int64_t *max_e)
+{
+    std::vector<MbSrc> host;
+    *max_e = 0;
+    for (const Snapshot &sn : ctx->snaps) {
+        host.push_back(MbSrc{sn.row_ptr, sn.rowid, sn.col, sn.q, sn.x, sn.nnz});
+        *max_e = std::max(*max_e, sn.nnz);
+    }
+    void *dev = ctx->scratch(host.size() * sizeof(MbSrc));
+    if (!dev || hipMemcpy(dev, host.data(), host.size() * sizeof(MbSrc), hipMemcpyHostToDevice) != hipSuccess) return nullptr;
+    return static_cast<const MbSrc *>(dev);
+}
+
+unsigned bits_for(int64_t values)  // bits that hold any number in [0, values)
+{
+    unsigned bits = 1;
+    while ((int64_t(1) << bits) < values) ++bits;
+    return bits;
 }
 
 }  // namespace
@@ -137,7 +272,9 @@ int reinc_batch_plan(reinc_ctx *ctx, const int32_t *nodes, int64_t n_batch, int3
     int64_t *offs = static_cast<int64_t *>(ctx->scratch(uint64_t(n + 1) * 8));
     void *scan_tmp = ctx->scratch(scan_tmp_bytes(n));
     int64_t *counters = static_cast<int64_t *>(ctx->scratch(256));  // [0] inner nodes, [1] (as int32) duplicate flag
-    if (!d_nodes || !flag || !offs || !scan_tmp || !counters) {
+    int64_t max_e = 0;
+    const MbSrc *src = source_table(ctx, &max_e);
+    if (!d_nodes || !flag || !offs || !scan_tmp || !counters || !src) {
         ctx->scratch_reset();
         return ctx->fail(REINC_E_NOMEM, "arena exhausted while planning a node batch");
     }
@@ -147,9 +284,9 @@ int reinc_batch_plan(reinc_ctx *ctx, const int32_t *nodes, int64_t n_batch, int3
     launch_fill_i32(ctx->batch_new_id, n, -1, s);
     launch_fill_i32(reinterpret_cast<int32_t *>(counters), 4, 0, s);
     batch_seed<<<blocks_for(n_batch, 256), 256, 0, s>>>(d_nodes, n_batch, ctx->batch_level, ctx->batch_new_id, ctx->batch_nodes, err);
-    for (int32_t k = 1; k <= hops; ++k)
-        for (const Snapshot &sn : ctx->snaps)
-            if (sn.nnz > 0) batch_expand<<<blocks_for(sn.nnz, 256), 256, 0, s>>>(sn.rowid, sn.col, sn.nnz, ctx->batch_level, k);
+    if (max_e > 0)
+        for (int32_t k = 1; k <= hops; ++k)
+            mb_expand<<<dim3(blocks_for(max_e, 256), unsigned(ctx->snaps.size())), 256, 0, s>>>(src, ctx->batch_level, k);
     batch_member_flags<<<blocks_for(n, 256), 256, 0, s>>>(ctx->batch_level, n, hops, flag, reinterpret_cast<unsigned long long *>(counters));
     launch_scan(flag, offs, n, scan_tmp, s);
     batch_number<<<blocks_for(n, 256), 256, 0, s>>>(flag, offs, n, n_batch, ctx->batch_new_id, ctx->batch_nodes);
@@ -196,61 +333,115 @@ int reinc_batch_load(reinc_ctx *ctx, reinc_ctx *child)
     REINC_HIP(ctx, hipSetDevice(a.device));
     hipStream_t s = nullptr;
     const int64_t nu = ctx->batch_total;
+    const int32_t T = a.num_snapshots;
     const int32_t row_bytes = int32_t(a.dims[0] * ctx->elem_bytes());
     if (row_bytes % 16 != 0) return ctx->fail(REINC_E_UNSUPPORTED, "feature rows of %d bytes", row_bytes);
-    int64_t max_e = 1;
-    for (const Snapshot &sn : ctx->snaps) max_e = std::max(max_e, sn.nnz);
-    ctx->scratch_reset();
-    int32_t *flag = static_cast<int32_t *>(ctx->scratch(uint64_t(max_e) * 4));
-    int64_t *offs = static_cast<int64_t *>(ctx->scratch(uint64_t(max_e + 1) * 8));
-    int32_t *src = static_cast<int32_t *>(ctx->scratch(uint64_t(max_e) * 4));
-    int32_t *dst = static_cast<int32_t *>(ctx->scratch(uint64_t(max_e) * 4));
-    void *scan_tmp = ctx->scratch(scan_tmp_bytes(max_e));
-    if (!flag || !offs || !src || !dst || !scan_tmp) {
+    const unsigned shift = node_key_bits(nu), tbits = bits_for(T);
+    if (2 * shift + tbits > 64 || 2 * T > 65535)
+        return ctx->fail(REINC_E_UNSUPPORTED, "a batch of %lld nodes over %d snapshots", (long long)nu, T);
+    const bool scaled = a.agg_kind != REINC_AGG_SUM;
+    auto fail = [&](int code, const char *what) {
         ctx->scratch_reset();
-        return ctx->fail(REINC_E_NOMEM, "arena exhausted while extracting a node batch");
-    }
-    int rc = REINC_OK;
-    for (int32_t t = 0; t < a.num_snapshots && rc == REINC_OK; ++t) {
-        const Snapshot &sn = ctx->snaps[t];
-        int64_t kept = 0;
-        if (sn.nnz > 0) {
-            batch_edge_flags<<<blocks_for(sn.nnz, 256), 256, 0, s>>>(sn.rowid, sn.nnz, ctx->batch_level, ctx->batch_hops, flag);
-            launch_scan(flag, offs, sn.nnz, scan_tmp, s);
-            batch_edge_compact<<<blocks_for(sn.nnz, 256), 256, 0, s>>>(sn.rowid, sn.col, sn.nnz, flag, offs, ctx->batch_new_id, src, dst);
-            if (hipGetLastError() != hipSuccess || hipMemcpy(&kept, offs + sn.nnz, 8, hipMemcpyDeviceToHost) != hipSuccess) {
-                rc = ctx->fail(REINC_E_HIP, "extracting the edges of snapshot %d failed", t);
-                break;
-            }
-        }
-        rc = load_edges(child, t, src, dst, kept, true);
-        if (rc != REINC_OK) {
-            ctx->fail(rc, "batch context: %s", child->err.c_str());
-            break;
-        }
+        return ctx->fail(code, "extracting a node batch: %s", what);
+    };
+
+    // what does not depend on the number of kept edges
+    std::vector<MbDst> host_dst(size_t(T), MbDst{});
+    for (int32_t t = 0; t < T; ++t) {
         Snapshot &cs = child->snaps[t];
-        // The degree scales are those of the source graph: a row of the batch graph holds all of a node's in-edges only
-        // for the nodes whose aggregate is needed, but the symmetric normalisation also scales by the degree of an
-        // edge's source.
-        if (cs.q && sn.q) gather_f32<<<blocks_for(nu, 256), 256, 0, s>>>(sn.q, ctx->batch_nodes, nu, cs.q);
+        cs.row_ptr = static_cast<int64_t *>(child->alloc(uint64_t(nu + 1) * 8));
+        cs.col_ptr = static_cast<int64_t *>(child->alloc(uint64_t(nu + 1) * 8));
+        cs.row_order = static_cast<int32_t *>(child->alloc(uint64_t(nu) * 4));
+        cs.col_order = static_cast<int32_t *>(child->alloc(uint64_t(nu) * 4));
         cs.x = child->alloc(uint64_t(nu) * row_bytes);
-        if (!cs.x) {
-            rc = ctx->fail(REINC_E_NOMEM, "batch context: arena exhausted while storing features of snapshot %d", t);
-            break;
+        if (!cs.row_ptr || !cs.col_ptr || !cs.row_order || !cs.col_order || !cs.x) return fail(REINC_E_NOMEM, "batch context: arena exhausted");
+        if (scaled) {
+            cs.q = child->q_block + int64_t(t) * nu;
+            if (a.agg_kind == REINC_AGG_SYM) cs.p = cs.q;
         }
-        const int32_t chunks = row_bytes / 16;
-        gather_rows<<<blocks_for(nu * chunks, 256), 256, 0, s>>>(static_cast<const uint4 *>(sn.x), ctx->batch_nodes, nu, chunks,
-                                                                static_cast<uint4 *>(cs.x));
-        if (hipGetLastError() != hipSuccess || hipDeviceSynchronize() != hipSuccess) {
-            rc = ctx->fail(REINC_E_HIP, "gathering the features of snapshot %d failed", t);
-            break;
-        }
+        host_dst[t] = MbDst{cs.row_ptr, cs.col_ptr, nullptr, nullptr, nullptr, cs.row_order, cs.col_order, nullptr, nullptr, cs.q, cs.x};
+    }
+    ctx->scratch_reset();
+    int64_t max_e = 0;
+    const MbSrc *src = source_table(ctx, &max_e);
+    MbDst *dst = static_cast<MbDst *>(ctx->scratch(uint64_t(T) * sizeof(MbDst)));
+    const int64_t rows_total = int64_t(T) * nu;
+    int32_t *counts = static_cast<int32_t *>(ctx->scratch(uint64_t(2 * rows_total) * 4));  // later: the long row / column flags
+    int64_t *offs = static_cast<int64_t *>(ctx->scratch(uint64_t(2 * rows_total + 1) * 8));
+    void *scan_tmp = ctx->scratch(scan_tmp_bytes(2 * rows_total));
+    int64_t *kbase = static_cast<int64_t *>(ctx->scratch(uint64_t(T + 1) * 8));
+    int64_t *n_long = static_cast<int64_t *>(ctx->scratch(uint64_t(2 * T) * 8));
+    if (!src || !dst || !counts || !offs || !scan_tmp || !kbase || !n_long) return fail(REINC_E_NOMEM, "arena exhausted");
+    REINC_HIP(ctx, hipMemcpy(dst, host_dst.data(), size_t(T) * sizeof(MbDst), hipMemcpyHostToDevice));
+    const dim3 per_row(blocks_for(nu, 256), unsigned(T)), per_ptr(blocks_for(nu + 1, 256), unsigned(T));
+    mb_row_counts<<<per_row, 256, 0, s>>>(src, ctx->batch_nodes, ctx->batch_level, ctx->batch_hops, nu, counts);
+    launch_scan(counts, offs, rows_total, scan_tmp, s);
+    mb_row_ptrs<<<per_ptr, 256, 0, s>>>(dst, offs, nu, kbase);
+    if (scaled) mb_gather_scales<<<per_row, 256, 0, s>>>(src, dst, ctx->batch_nodes, nu);
+    const int32_t chunks = row_bytes / 16;
+    mb_gather_rows<<<dim3(blocks_for(nu * chunks, 256), unsigned(T)), 256, 0, s>>>(src, dst, ctx->batch_nodes, nu, chunks);
+    REINC_HIP(ctx, hipGetLastError());
+    std::vector<int64_t> host_kbase(size_t(T) + 1, 0);
+    REINC_HIP(ctx, hipMemcpy(host_kbase.data(), kbase, size_t(T + 1) * 8, hipMemcpyDeviceToHost));  // (waits for the device)
+
+    // the edge arrays, now that their sizes are known; a list of long rows cannot be longer than edges / (kLongRow + 1)
+    const int64_t total = host_kbase[T];
+    for (int32_t t = 0; t < T; ++t) {
+        Snapshot &cs = child->snaps[t];
+        const int64_t kept = host_kbase[t + 1] - host_kbase[t];
+        const uint64_t ee = uint64_t(std::max<int64_t>(kept, 1)), longs = uint64_t(kept / (kLongRow + 1) + 1);
+        cs.col = static_cast<int32_t *>(child->alloc(ee * 4));
+        cs.rowid = static_cast<int32_t *>(child->alloc(ee * 4));
+        cs.row = static_cast<int32_t *>(child->alloc(ee * 4));
+        cs.long_rows = static_cast<int32_t *>(child->alloc(longs * 4));
+        cs.long_cols = static_cast<int32_t *>(child->alloc(longs * 4));
+        if (!cs.col || !cs.rowid || !cs.row || !cs.long_rows || !cs.long_cols) return fail(REINC_E_NOMEM, "batch context: arena exhausted");
+        cs.nnz = kept;
+        host_dst[t].col = cs.col;
+        host_dst[t].rowid = cs.rowid;
+        host_dst[t].row = cs.row;
+        host_dst[t].long_rows = cs.long_rows;
+        host_dst[t].long_cols = cs.long_cols;
+    }
+    const int64_t n_keys = std::max<int64_t>(std::max(total, 2 * rows_total), 1);
+    uint64_t *keys0 = static_cast<uint64_t *>(ctx->scratch(uint64_t(n_keys) * 8));
+    uint64_t *keys1 = static_cast<uint64_t *>(ctx->scratch(uint64_t(n_keys) * 8));
+    const size_t sort_bytes = sort_keys_tmp_bytes(n_keys);
+    void *sort_tmp = ctx->scratch(sort_bytes);
+    if (!keys0 || !keys1 || !sort_tmp) return fail(REINC_E_NOMEM, "arena exhausted");
+    REINC_HIP(ctx, hipMemcpy(dst, host_dst.data(), size_t(T) * sizeof(MbDst), hipMemcpyHostToDevice));
+    if (total > 0) {
+        mb_edge_keys<<<blocks_for(rows_total * 16, 256), 256, 0, s>>>(src, ctx->batch_nodes, ctx->batch_level, ctx->batch_new_id, ctx->batch_hops,
+                                                                      nu, rows_total, offs, shift, keys0);
+        // CSR: by snapshot, target, source.  CSC: the same list re-keyed, where a stable sort by snapshot and source
+        // leaves the targets of a column ascending.
+        REINC_HIP(ctx, sort_keys(sort_tmp, sort_bytes, keys0, keys1, total, 0, 2 * shift + tbits, s));
+        mb_split<<<blocks_for(total, 256), 256, 0, s>>>(keys1, total, shift, kbase, dst, keys0);
+        REINC_HIP(ctx, sort_keys(sort_tmp, sort_bytes, keys0, keys1, total, shift, 2 * shift + tbits, s));
+        mb_csc_rows<<<blocks_for(total, 256), 256, 0, s>>>(keys1, total, shift, kbase, dst);
+    }
+    mb_col_ptrs<<<per_ptr, 256, 0, s>>>(keys1, shift, kbase, dst, nu);
+    // rows and columns by falling length (the keys are written in ascending order of snapshot and node and the sort
+    // is stable: the length bits and the snapshot bits suffice), and the lists of long rows and columns
+    const dim3 per_side(blocks_for(nu, 256), unsigned(2 * T));
+    mb_length_keys<<<per_side, 256, 0, s>>>(dst, nu, T, keys0, counts);
+    REINC_HIP(ctx, sort_keys(sort_tmp, sort_bytes, keys0, keys1, 2 * rows_total, 32, 39 + bits_for(2 * T), s));
+    mb_orders<<<per_side, 256, 0, s>>>(keys1, dst, nu, T);
+    launch_scan(counts, offs, 2 * rows_total, scan_tmp, s);
+    mb_long_lists<<<per_side, 256, 0, s>>>(counts, offs, dst, nu, T, n_long);
+    REINC_HIP(ctx, hipGetLastError());
+    std::vector<int64_t> host_long(size_t(2 * T), 0);
+    REINC_HIP(ctx, hipMemcpy(host_long.data(), n_long, size_t(2 * T) * 8, hipMemcpyDeviceToHost));  // (waits for the device)
+    ctx->scratch_reset();
+    for (int32_t t = 0; t < T; ++t) {
+        Snapshot &cs = child->snaps[t];
+        cs.n_long_rows = int32_t(host_long[t]);
+        cs.n_long_cols = int32_t(host_long[T + t]);
+        cs.edges_loaded = true;
         cs.feats_loaded = true;
         cs.feats_from_delta = false;
-        if (child->has_derived) child->load_after_derived = true;
     }
-    ctx->scratch_reset();
-    if (rc != REINC_OK) return rc;
+    if (child->has_derived) child->load_after_derived = true;
     child->loss_rows = ctx->batch_size == nu ? 0 : ctx->batch_size;
     child->local_valid = false;
     return REINC_OK;

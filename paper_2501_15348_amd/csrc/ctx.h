@@ -241,6 +241,7 @@ namespace reinc {
 // ---- api.hip
 // reinc_load_edges with the raw list in host or in device memory
 int load_edges(reinc_ctx *ctx, int32_t t, const int32_t *src, const int32_t *dst, int64_t nnz, bool on_device);
+unsigned node_key_bits(int64_t n);  // bits that hold any id in [0, n]
 // reinc_aggregate_incremental_minmax with the work area given by the caller of this function; `timed`: the launches
 // may be bracketed by profiling events
 int minmax_incremental(reinc_ctx *ctx, int32_t t, int op, const float *M_prev, const int32_t *C_prev, float *M_out,
@@ -302,7 +303,8 @@ void launch_compact(const int32_t *flags, const int64_t *offsets, int64_t n, int
                     hipStream_t s);
 // canonicalisation of a raw edge list
 size_t sort_keys_tmp_bytes(int64_t n);
-hipError_t sort_keys(void *tmp, size_t tmp_bytes, const uint64_t *in, uint64_t *out, int64_t n, unsigned end_bit,
+// stable sort by the key bits [begin_bit, end_bit)
+hipError_t sort_keys(void *tmp, size_t tmp_bytes, const uint64_t *in, uint64_t *out, int64_t n, unsigned begin_bit, unsigned end_bit,
                      hipStream_t s);
 void launch_make_keys(const int32_t *src, const int32_t *dst, int64_t nnz, int64_t n, uint64_t *keys, int32_t *err,
                       hipStream_t s);

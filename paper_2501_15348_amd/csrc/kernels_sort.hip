@@ -15,11 +15,11 @@ size_t sort_keys_tmp_bytes(int64_t n)
     return bytes;
 }
 
-hipError_t sort_keys(void *tmp, size_t tmp_bytes, const uint64_t *in, uint64_t *out, int64_t n, unsigned end_bit,
+hipError_t sort_keys(void *tmp, size_t tmp_bytes, const uint64_t *in, uint64_t *out, int64_t n, unsigned begin_bit, unsigned end_bit,
                      hipStream_t s)
 {
     if (n <= 0) return hipSuccess;
-    return rocprim::radix_sort_keys(tmp, tmp_bytes, in, out, size_t(n), 0u, end_bit, s);
+    return rocprim::radix_sort_keys(tmp, tmp_bytes, in, out, size_t(n), begin_bit, end_bit, s);
 }
 
 }  // namespace reinc

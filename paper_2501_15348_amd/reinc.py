@@ -449,10 +449,11 @@ class Context:
         self._ck(self.lib.reinc_batch_node_list(self.handle, out.ctypes.data_as(ctypes.c_void_p)))
         return out
 
-    def batch_context(self, nodes, arena_bytes: int, hops: int = 0, **kw) -> "Context":
+    def batch_context(self, nodes, arena_bytes: int, hops: int = 0, planned_total: Optional[int] = None, **kw) -> "Context":
         """A new context holding the sub-sequence of `nodes` (same model configuration; keyword arguments override
-        constructor arguments such as fallback_ratio)."""
-        total, _ = self.batch_plan(nodes, hops)
+        constructor arguments such as fallback_ratio).  planned_total: the node count batch_plan returned for these
+        nodes and hops, if the caller has just planned them (say, to size the arena); the plan is then not repeated."""
+        total = planned_total if planned_total is not None else self.batch_plan(nodes, hops)[0]
         args = dict(fallback_ratio=self.cfg.fallback_ratio, device=self.cfg.device)
         args.update(kw)
         agg = [k for k, v in AGG.items() if v == self.cfg.agg_kind][0]

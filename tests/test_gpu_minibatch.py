@@ -73,16 +73,28 @@ def test_batch_windows_with_three_timesteps_per_launch(monkeypatch):
     _check_batch_windows("sum", "gru", 2)
 
 
-def _check_batch_windows(mode, rnn, layers):
+def test_batch_windows_with_hub_rows_and_columns():
+    """A power-law graph: the batch graph has rows and columns beyond the length at which the aggregation kernels
+    switch to a block per row, in the forward pass (rows) and in the backward pass (columns)."""
+    _check_batch_windows("sym", "gru", 2, dist="chunglu", degree=12.0, hubs=True)
+
+
+def _check_batch_windows(mode, rnn, layers, dist="uniform", degree=2.5, hubs=False):
     import torch
 
-    wl = _workload(mode, rnn, layers)
+    wl = _workload(mode, rnn, layers, dist=dist, degree=degree)
     seq, ctx = _parent(wl)
     n, T, L, H = wl.num_nodes, wl.num_snapshots, 4, wl.hidden
     batch = np.random.default_rng(8).choice(n, 64, replace=False).astype(np.int32)
+    if hubs:  # the node with the most in-edges joins the batch
+        batch[0] = np.argmax(np.bincount(seq.edges[0][1], minlength=n))
+        batch = np.unique(batch).astype(np.int32)
     child = ctx.batch_context(batch, 1 << 28)  # default hop count
     node_list = ctx.batch_node_list(child.n)
-    assert child.n < n
+    assert child.n < n or hubs
+    if hubs:
+        ptr, idx = child.get_snapshot_csr(0)
+        assert np.diff(ptr).max() > 64 and np.bincount(idx).max() > 64
     child.build_deltas(-1)
     flat = synth.make_params(wl, bias_scale=0.2)
     target = synth.make_target(wl)
