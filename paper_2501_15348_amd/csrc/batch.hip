@@ -71,15 +71,19 @@ struct MbDst {
     void *x;
 };
 
-// hop k: the source of an edge whose target was reached in fewer than k hops is reached in at most k.  Levels
-// below k are final and levels of k are only ever written as k during this launch, so the order of the threads
-// does not matter.
-__global__ void mb_expand(const MbSrc *src, int32_t *level, int32_t k)
+// hop k: the sources of the rows reached in exactly k - 1 hops are reached in at most k (the rows reached earlier
+// were expanded in an earlier hop).  Levels of k - 1 are final and levels are only ever lowered to k during this
+// launch, so the order of the threads does not matter.  16 lanes walk one row.
+__global__ void mb_expand(const MbSrc *src, int32_t *level, int32_t k, int64_t n)
 {
+    const int64_t v = (blockIdx.x * int64_t(blockDim.x) + threadIdx.x) >> 4;
+    if (v >= n || level[v] != k - 1) return;
     const MbSrc sn = src[blockIdx.y];
-    const int64_t i = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
-    if (i >= sn.nnz) return;
-    if (level[sn.rowid[i]] < k) atomicMin(&level[sn.col[i]], k);
+    const int64_t end = sn.row_ptr[v + 1];
+    for (int64_t i = sn.row_ptr[v] + (threadIdx.x & 15); i < end; i += 16) {
+        const int32_t u = sn.col[i];
+        if (level[u] > k) atomicMin(&level[u], k);
+    }
 }
 
 // counts[t * nu + i] = in-edges that row i of the batch graph keeps in snapshot t: all of them if the node's aggregate
@@ -104,7 +108,8 @@ __global__ void mb_row_ptrs(const MbDst *dst, const int64_t *offs, int64_t nu, i
     if (i == nu && t + 1 == gridDim.y) kbase[t + 1] = offs[t * nu + nu];
 }
 
-// keys of the kept edges, snapshot << 2 shift | new target << shift | new source: 16 lanes copy one row
+// keys of the kept edges, snapshot << 2 shift | new source << shift | new target, written in ascending order of
+// snapshot and target: 16 lanes copy one row
 __global__ void mb_edge_keys(const MbSrc *src, const int32_t *nodes, const int32_t *level, const int32_t *new_id, int32_t hops, int64_t nu,
                              int64_t rows_total, const int64_t *offs, unsigned shift, uint64_t *keys)
 {
@@ -116,30 +121,33 @@ __global__ void mb_edge_keys(const MbSrc *src, const int32_t *nodes, const int32
     if (level[v] >= hops) return;
     const MbSrc sn = src[t];
     const int64_t b = sn.row_ptr[v], len = sn.row_ptr[v + 1] - b, out = offs[r];
-    const uint64_t high = (uint64_t(t) << (2 * shift)) | (uint64_t(i) << shift);
-    for (int64_t e = lane; e < len; e += 16) keys[out + e] = high | uint64_t(uint32_t(new_id[sn.col[b + e]]));
+    const uint64_t rest = (uint64_t(t) << (2 * shift)) | uint64_t(i);
+    for (int64_t e = lane; e < len; e += 16) keys[out + e] = rest | (uint64_t(uint32_t(new_id[sn.col[b + e]])) << shift);
 }
 
-// sorted keys -> the CSR entries of every snapshot, and the same edges keyed by source for the CSC
-__global__ void mb_split(const uint64_t *keys, int64_t total, unsigned shift, const int64_t *kbase, const MbDst *dst, uint64_t *swapped)
+// keys in the order of snapshot, source, target -> the row ids of every snapshot's CSC, and the same edges keyed
+// snapshot << 2 shift | target << shift | source
+__global__ void mb_csc_entries(const uint64_t *keys, int64_t total, unsigned shift, const int64_t *kbase, const MbDst *dst, uint64_t *swapped)
 {
     const int64_t j = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
     if (j >= total) return;
     const uint64_t k = keys[j], mask = (uint64_t(1) << shift) - 1, t = k >> (2 * shift), lo = k & mask, hi = (k >> shift) & mask;
-    const int64_t local = j - kbase[t];
-    dst[t].col[local] = int32_t(lo);
-    dst[t].rowid[local] = int32_t(hi);
+    dst[t].row[j - kbase[t]] = int32_t(lo);
     swapped[j] = (t << (2 * shift)) | (lo << shift) | hi;
 }
 
-__global__ void mb_csc_rows(const uint64_t *keys, int64_t total, unsigned shift, const int64_t *kbase, const MbDst *dst)
+// keys in the order of snapshot, target, source -> the entries of every snapshot's CSR
+__global__ void mb_csr_entries(const uint64_t *keys, int64_t total, unsigned shift, const int64_t *kbase, const MbDst *dst)
 {
     const int64_t j = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
     if (j >= total) return;
-    const uint64_t k = keys[j], t = k >> (2 * shift);
-    dst[t].row[j - kbase[t]] = int32_t(k & ((uint64_t(1) << shift) - 1));
+    const uint64_t k = keys[j], mask = (uint64_t(1) << shift) - 1, t = k >> (2 * shift);
+    const int64_t local = j - kbase[t];
+    dst[t].col[local] = int32_t(k & mask);
+    dst[t].rowid[local] = int32_t((k >> shift) & mask);
 }
 
+// the column pointers, from the keys in the order of snapshot, source, target
 __global__ void mb_col_ptrs(const uint64_t *keys, unsigned shift, const int64_t *kbase, const MbDst *dst, int64_t nu)
 {
     const int64_t v = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
@@ -286,7 +294,7 @@ int reinc_batch_plan(reinc_ctx *ctx, const int32_t *nodes, int64_t n_batch, int3
     batch_seed<<<blocks_for(n_batch, 256), 256, 0, s>>>(d_nodes, n_batch, ctx->batch_level, ctx->batch_new_id, ctx->batch_nodes, err);
     if (max_e > 0)
         for (int32_t k = 1; k <= hops; ++k)
-            mb_expand<<<dim3(blocks_for(max_e, 256), unsigned(ctx->snaps.size())), 256, 0, s>>>(src, ctx->batch_level, k);
+            mb_expand<<<dim3(blocks_for(n * 16, 256), unsigned(ctx->snaps.size())), 256, 0, s>>>(src, ctx->batch_level, k, n);
     batch_member_flags<<<blocks_for(n, 256), 256, 0, s>>>(ctx->batch_level, n, hops, flag, reinterpret_cast<unsigned long long *>(counters));
     launch_scan(flag, offs, n, scan_tmp, s);
     batch_number<<<blocks_for(n, 256), 256, 0, s>>>(flag, offs, n, n_batch, ctx->batch_new_id, ctx->batch_nodes);
@@ -413,14 +421,17 @@ int reinc_batch_load(reinc_ctx *ctx, reinc_ctx *child)
     if (total > 0) {
         mb_edge_keys<<<blocks_for(rows_total * 16, 256), 256, 0, s>>>(src, ctx->batch_nodes, ctx->batch_level, ctx->batch_new_id, ctx->batch_hops,
                                                                       nu, rows_total, offs, shift, keys0);
-        // CSR: by snapshot, target, source.  CSC: the same list re-keyed, where a stable sort by snapshot and source
-        // leaves the targets of a column ascending.
-        REINC_HIP(ctx, sort_keys(sort_tmp, sort_bytes, keys0, keys1, total, 0, 2 * shift + tbits, s));
-        mb_split<<<blocks_for(total, 256), 256, 0, s>>>(keys1, total, shift, kbase, dst, keys0);
+        // Two stable sorts by the snapshot and one endpoint each.  The keys are written in the order of snapshot and
+        // target; sorted by snapshot and source they are the CSC, with the targets of a column ascending; re-keyed
+        // and sorted by snapshot and target they are the CSR, with the sources of a row ascending.
         REINC_HIP(ctx, sort_keys(sort_tmp, sort_bytes, keys0, keys1, total, shift, 2 * shift + tbits, s));
-        mb_csc_rows<<<blocks_for(total, 256), 256, 0, s>>>(keys1, total, shift, kbase, dst);
     }
     mb_col_ptrs<<<per_ptr, 256, 0, s>>>(keys1, shift, kbase, dst, nu);
+    if (total > 0) {
+        mb_csc_entries<<<blocks_for(total, 256), 256, 0, s>>>(keys1, total, shift, kbase, dst, keys0);
+        REINC_HIP(ctx, sort_keys(sort_tmp, sort_bytes, keys0, keys1, total, shift, 2 * shift + tbits, s));
+        mb_csr_entries<<<blocks_for(total, 256), 256, 0, s>>>(keys1, total, shift, kbase, dst);
+    }
     // rows and columns by falling length (the keys are written in ascending order of snapshot and node and the sort
     // is stable: the length bits and the snapshot bits suffice), and the lists of long rows and columns
     const dim3 per_side(blocks_for(nu, 256), unsigned(2 * T));
