@@ -854,7 +854,17 @@ __global__ void __launch_bounds__(64 * WAVES) rnn_fused_resident_kernel(RnnArgs 
     const int H = g.H, ldw = KG * H;
     const int ntiles = int((g.n + 31) / 32);
     const int first = __builtin_amdgcn_readfirstlane(int(blockIdx.x) * WM + wm), stride = int(gridDim.x) * WM;
-    const int kx = g.d_in / kBK, kh = g.h_prev ? H / kBK : 0, kch = kx + kh;
+    // PACK: the previous state c_prev that the epilogue needs comes in as one more chunk of the tile's stream and is
+    // moved into accumulator layout by the matrix cores (a product with an identity matrix, exact term by term).
+    // Loads issued by the epilogue itself are waited for on the spot, once per tile, together with every load of the
+    // ring.  (The unpacked variants have no registers left for a fifth accumulator: with it they spilled and took
+    // half as long again.)
+    const float *pstate = LSTM ? g.c_prev : g.h_carry;
+    const int ks = (PACK && pstate) ? 1 : 0;
+    const int kx = g.d_in / kBK, kh = g.h_prev ? H / kBK : 0, kch = kx + kh + ks;
+    auto s_ptr = [&](int t) __attribute__((always_inline)) {  // the wave's 16 units, in both halves of the wave
+        return reinterpret_cast<const char *>(pstate) + (min(int64_t(t) * 32 + i, g.n - 1) * H + h0 + wn * 16) * 4;
+    };
     auto x_ptr = [&](int t) __attribute__((always_inline)) {
         return reinterpret_cast<const char *>(g.x) + (min(int64_t(t) * 32 + i, g.n - 1) * g.d_in + 16 * kk) * 4;
     };
@@ -874,6 +884,7 @@ __global__ void __launch_bounds__(64 * WAVES) rnn_fused_resident_kernel(RnnArgs 
         lptr += kBK * 4;
         ++lk;
         if (lk == kx && kh > 0) lptr = h_ptr(ltile);
+        if (PACK && ks && lk == kx + kh) lptr = s_ptr(ltile);
         if (lk == kch) {
             lk = 0;
             ltile += stride;
@@ -950,14 +961,22 @@ __global__ void __launch_bounds__(64 * WAVES) rnn_fused_resident_kernel(RnnArgs 
         }
     }
     const float *bp0 = Bs + (16 * kk) * NC + wn * 32 + i;
-    const float *pstate = LSTM ? g.c_prev : g.h_carry;
-    // compute cursor; accumulators: LSTM i, f, g, o (x and h parts summed); GRU r, z (summed), h part of n, x part of n
+    // compute cursor; accumulators: LSTM i, f, g, o (x and h parts summed); GRU r, z (summed), h part of n, x part of n;
+    // PACK: [i | f], [g | o], the previous state
     int tile = first, kc = 0;
     acc16 acc[4];
 #pragma unroll
     for (int t = 0; t < 4; ++t)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[t][r] = 0.0f;
+    // identity fragment for the state chunk: the lane's eight k slots are the units 8 * kk + s of the wave, s = 0 .. 7,
+    // and its column is unit i % 16, in both halves of the tile
+    u32x4 ident;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const int s1 = (i & 15) - 8 * kk;
+        ident[e] = s1 == 2 * e ? 0x00003F80u : s1 == 2 * e + 1 ? 0x3F800000u : 0u;
+    }
 
     auto epilogue = [&]() __attribute__((always_inline)) {  // rows rbase + 8*q + e of the finished tile, four at a time
         const int64_t rbase = int64_t(tile) * 32 + 4 * kk;
@@ -966,14 +985,20 @@ __global__ void __launch_bounds__(64 * WAVES) rnn_fused_resident_kernel(RnnArgs 
             // lanes 0..15 of a half hold gates i (acc[0]) and g (acc[1]) of their unit, lanes 16..31 gates f and o, for
             // the same 16 rows.  The low lane keeps rows 0..7 (registers 0..7) and receives f, o for them; the high
             // lane keeps rows 8..15 and receives i, g.
+            // (The registers are made opaque first: a select between two elements of an accumulator would otherwise be
+            // turned into one element at a selected index, which costs a chain of 15 selects per value, and the
+            // exchange would be moved out of this once-per-tile path into every chunk.)
             const bool low = i < 16;
-            float mine0[8], mine1[8], other0[8], other1[8];
+            float mine0[8], mine1[8], other0[8], other1[8], state[8];
 #pragma unroll
             for (int r = 0; r < 8; ++r) {
-                mine0[r] = low ? acc[0][r] : acc[0][8 + r];
-                mine1[r] = low ? acc[1][r] : acc[1][8 + r];
-                other0[r] = __shfl_xor(low ? acc[0][8 + r] : acc[0][r], 16);
-                other1[r] = __shfl_xor(low ? acc[1][8 + r] : acc[1][r], 16);
+                float a0 = acc[0][r], b0 = acc[0][8 + r], a1 = acc[1][r], b1 = acc[1][8 + r], a2 = acc[2][r], b2 = acc[2][8 + r];
+                asm volatile("" : "+v"(a0), "+v"(b0), "+v"(a1), "+v"(b1), "+v"(a2), "+v"(b2));
+                mine0[r] = low ? a0 : b0;
+                mine1[r] = low ? a1 : b1;
+                state[r] = low ? a2 : b2;
+                other0[r] = __shfl_xor(low ? b0 : a0, 16);
+                other1[r] = __shfl_xor(low ? b1 : a1, 16);
             }
             if (j < H) {
 #pragma unroll
@@ -983,7 +1008,7 @@ __global__ void __launch_bounds__(64 * WAVES) rnn_fused_resident_kernel(RnnArgs 
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
                         rr[e] = min(rbase + 8 * (q + (low ? 0 : 2)) + e, g.n - 1);
-                        prev[e] = pstate ? pstate[rr[e] * H + j] : 0.0f;
+                        prev[e] = state[4 * q + e];  // (zero without a previous state)
                     }
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
@@ -1008,7 +1033,7 @@ __global__ void __launch_bounds__(64 * WAVES) rnn_fused_resident_kernel(RnnArgs 
                 }
             }
 #pragma unroll
-            for (int t = 0; t < 2; ++t)
+            for (int t = 0; t < 3; ++t)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[t][r] = 0.0f;
             return;
@@ -1065,17 +1090,35 @@ __global__ void __launch_bounds__(64 * WAVES) rnn_fused_resident_kernel(RnnArgs 
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[t][r] = 0.0f;
     };
+    auto state_chunk = [&](float(&cur)[16]) __attribute__((always_inline)) {
+        float v[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {  // both halves hold the wave's 16 units: the upper half takes the last eight
+            float lo8 = cur[e], hi8 = cur[8 + e];
+            asm volatile("" : "+v"(lo8), "+v"(hi8));
+            v[e] = kk ? hi8 : lo8;
+        }
+        u32x4 sh, sm, sl;
+        split8(v, sh, sm, sl);
+        acc[2] = mfma_bf16(sl, ident, acc[2]);
+        acc[2] = mfma_bf16(sm, ident, acc[2]);
+        acc[2] = mfma_bf16(sh, ident, acc[2]);
+    };
     auto multiply = [&](float(&cur)[16], float sc) __attribute__((always_inline)) {
         const float *bp = bp0 + kc * kBK * NC;
-        const float f = (has_xs && kc < kx) ? sc : 1.0f;
+        if (PACK && ks && kc == kx + kh) {
+            state_chunk(cur);
+        } else {
+            const float f = (has_xs && kc < kx) ? sc : 1.0f;
 #pragma unroll
-        for (int e = 0; e < 16; ++e) cur[e] *= f;
-        if (PACK)
-            mfma_chunk_split<2, 4>(cur, Bq + (4 * kc + 2 * kk) * NC + wn * 64 + i, NC, plane, 32, acc);
-        else if (SPLIT)
-            mfma_chunk_split<KG, 4>(cur, Bq + (4 * kc + 2 * kk) * NC + wn * 32 + i, NC, plane, BH, acc);
-        else
-            mfma_chunk_map<KG, KG - 1, G>(cur, bp, NC, BH, acc, NoPrefetch());
+            for (int e = 0; e < 16; ++e) cur[e] *= f;
+            if (PACK)
+                mfma_chunk_split<2, 4>(cur, Bq + (4 * kc + 2 * kk) * NC + wn * 64 + i, NC, plane, 32, acc);
+            else if (SPLIT)
+                mfma_chunk_split<KG, 4>(cur, Bq + (4 * kc + 2 * kk) * NC + wn * 32 + i, NC, plane, BH, acc);
+            else
+                mfma_chunk_map<KG, KG - 1, G>(cur, bp, NC, BH, acc, NoPrefetch());
+        }
         ++kc;
         if (!LSTM && kc == kx) {  // GRU: the x part of the n gate is complete; the h part starts from zero
             acc[3] = acc[2];
@@ -1119,6 +1162,7 @@ bool rnn_fused_resident_launch(const RnnArgs &g, hipStream_t s)
     constexpr int WM = WAVES / WN;
     constexpr int UW = PACK ? 16 : 32;
     if (g.d_in % kBK != 0 || g.H % kBK != 0 || g.d_in % 4 != 0) return false;
+    if (PACK && (reinterpret_cast<uintptr_t>(g.c_prev) & 15) != 0) return false;  // (the state chunk is read in 16-byte pieces)
     const size_t lds = size_t(g.d_in + g.H) * KG * UW * WN * (SPLIT ? 6 : sizeof(float));
     if (lds > kLdsBytes - 1024) return false;
     auto k = rnn_fused_resident_kernel<LSTM, WN, WAVES, SPLIT, PACK>;
