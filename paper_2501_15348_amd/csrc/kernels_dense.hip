@@ -986,8 +986,7 @@ __global__ void __launch_bounds__(64 * WAVES) rnn_fused_resident_kernel(RnnArgs 
             // the same 16 rows.  The low lane keeps rows 0..7 (registers 0..7) and receives f, o for them; the high
             // lane keeps rows 8..15 and receives i, g.
             // (The registers are made opaque first: a select between two elements of an accumulator would otherwise be
-            // turned into one element at a selected index, which costs a chain of 15 selects per value, and the
-            // exchange would be moved out of this once-per-tile path into every chunk.)
+            // turned into one element at a selected index, which costs a chain of 15 selects per value.)
             const bool low = i < 16;
             float mine0[8], mine1[8], other0[8], other1[8], state[8];
 #pragma unroll

@@ -120,3 +120,35 @@ def test_the_walk_finds_a_planted_copy(assembly):
     body.insert(k + 2, f"\tv_mov_b32_e32 v255, {reg}")
     violations, _ = _walk(*_blocks(body))
     assert any(reg[1:] == str(h) for _, _, hit in violations for h in hit)
+
+
+def _loop_blocks(blocks, order):
+    """Labels of the blocks between the first block that holds matrix instructions and the last block that branches
+    back to it or before it: the kernel's loops over chunks."""
+    index = {b: k for k, b in enumerate(order)}
+    first = next(k for k, b in enumerate(order) if any(t.startswith("v_mfma") for t, _ in blocks[b]))
+    last = first
+    for k, b in enumerate(order):
+        for t, _ in blocks[b]:
+            m = re.match(r"s_c?branch\w*\s+(\.LBB\d+_\d+)", t)
+            if m and first <= index[m.group(1)] <= k:
+                last = max(last, k)
+    return order[first:last + 1]
+
+
+def test_packed_lstm_cell_keeps_its_loads_in_flight_and_its_epilogue_short(assembly):
+    """Two properties of the compiled packed LSTM step that the source cannot state.  (1) Inside the steady loop no
+    wait drains the ring of row loads: the epilogue issues no loads of its own (the previous cell state arrives as a
+    chunk), so every vmcnt wait there leaves the newest chunks in flight.  (2) The exchange between the two lanes of a
+    hidden unit is one select per value: once it had been compiled into an element at a selected index, a chain of 15
+    selects per value (1860 selects in the loop instead of 275)."""
+    body = _function(assembly, "rnn_fused_resident_kernelILb1ELi1ELi8ELb1ELb1E")
+    blocks, order = _blocks(body)
+    loop = _loop_blocks(blocks, order)
+    chunk_blocks = [b for b in loop if sum(t.startswith("v_mfma") for t, _ in blocks[b]) >= 24]
+    assert len(chunk_blocks) >= 4, "the unrolled chunk steps were not found: has the kernel changed?"
+    steady = loop[:loop.index(chunk_blocks[3]) + 1]  # the first loop: one step per ring buffer, loads unconditional
+    waits = [int(n) for b in steady for t, _ in blocks[b] for n in re.findall(r"vmcnt\((\d+)\)", t)]
+    assert waits and min(waits) >= 10, sorted(set(waits))
+    selects = sum(t.startswith("v_cndmask") for b in steady for t, _ in blocks[b])
+    assert selects <= 600, selects
