@@ -51,6 +51,26 @@ def test_extraction_is_exact(mode, hops, dist):
     for t in range(wl.num_snapshots):
         ptr, idx = child.get_snapshot_csr(t)
         assert np.array_equal(ptr, ref_graphs[t].row_ptr) and np.array_equal(idx, ref_graphs[t].col), t
+        # the transpose (by source, targets ascending): counting sort of the reference rows
+        src, dst = ref_graphs[t].col, np.repeat(np.arange(total), np.diff(ref_graphs[t].row_ptr))
+        order = np.lexsort((dst, src))
+        tptr, tidx = child.get_snapshot_csr(t, transpose=True)
+        assert np.array_equal(tptr, np.concatenate(([0], np.cumsum(np.bincount(src, minlength=total))))), t
+        assert np.array_equal(tidx, dst[order]), t
+        # aggregation over the extracted structure (row order lists, long-row lists, both directions) against the
+        # dense definition on the same graph
+        x = np.random.default_rng(t).standard_normal((total, 16)).astype(np.float32)
+        dense = np.zeros((total, total))
+        dense[dst, src] = 1.0
+        # (source-side scales under the symmetric normalisation: the degrees of the WHOLE graph, carried over)
+        scale = np.ones(total)
+        if mode == "sym":
+            scale = (1.0 + np.bincount(seq.edges[t][1], minlength=wl.num_nodes))[ref_list] ** -0.5
+        a = dense + np.eye(total)
+        for transpose in (False, True):
+            got = child.aggregate_full(t, _dev(x), transpose=transpose).cpu().numpy()
+            want = scale[:, None] * (a.T @ x) if transpose else a @ (scale[:, None] * x)
+            assert_close(got, want, RTOL_FP32, f"aggregate over the extracted snapshot {t}, transpose {transpose}")
     assert total < wl.num_nodes
     child.close()
     # a second plan on the same context replaces the first
