@@ -12,8 +12,9 @@ A model of `hops` aggregation layers evaluated on the sub-sequence gives, on the
 whole graph: row v of layer l needs layer l-1 on v and on the sources of v's edges only.  (With the symmetric
 normalisation the scale of a SOURCE is a degree too, so one more hop is needed for the same statement.)
 
-The numbering of the sub-sequence: the batch nodes first, in the order given, then the other nodes in ascending
-order of their ids.
+The numbering of the sub-sequence: the batch nodes first, in the order given, then the nodes first reached in one
+hop, in ascending order of their ids, then those first reached in two hops, and so on: F_k is the first |F_k| ids
+for every k, and layer l of an L-layer model is needed on the first |F_{L-l}| rows only.
 
 Pins (tests/test_oracle_minibatch.py): hand-worked chains and stars; the closure equals the breadth-first ball in
 the union graph found by matrix powers of a dense adjacency; the model restricted to the sub-sequence reproduces
@@ -43,15 +44,15 @@ def closure(edges: Sequence[Tuple[np.ndarray, np.ndarray]], batch: Sequence[int]
 
 
 def extract(edges: Sequence[Tuple[np.ndarray, np.ndarray]], batch: Sequence[int], hops: int):
-    """Returns (node_list, sub_edges, n_inner): node_list[new id] = old id (batch first, then ascending),
-    sub_edges[t] = (src, dst) in new ids of the edges of snapshot t whose target lies in F_{hops-1}, in the order
-    of the input list, and n_inner = |F_{hops-1}|."""
+    """Returns (node_list, sub_edges, n_inner): node_list[new id] = old id (batch first, then by the number of hops
+    at which a node is first reached, ascending ids within one number), sub_edges[t] = (src, dst) in new ids of the
+    edges of snapshot t whose target lies in F_{hops-1}, in the order of the input list, and n_inner = |F_{hops-1}|."""
     batch = [int(v) for v in batch]
     if len(set(batch)) != len(batch):
         raise ValueError("batch nodes must be distinct")
     levels = closure(edges, batch, hops)
-    inner, outer = levels[hops - 1] if hops > 0 else set(), levels[hops]
-    rest = sorted(outer - set(batch))
+    inner = levels[hops - 1] if hops > 0 else set()
+    rest = [v for k in range(1, hops + 1) for v in sorted(levels[k] - levels[k - 1])]
     node_list = np.array(batch + rest, dtype=np.int64)
     new_id = {old: i for i, old in enumerate(node_list.tolist())}
     sub = []

@@ -22,20 +22,36 @@ def test_chain_by_hand():
     levels = minibatch.closure(edges, [4], 2)
     assert levels == [{4}, {4, 3}, {4, 3, 2, 5}]
     node_list, sub, n_inner = minibatch.extract(edges, [4], 2)
-    assert node_list.tolist() == [4, 2, 3, 5] and n_inner == 2
-    # kept: edges into 3 or 4.  new ids: 4 -> 0, 2 -> 1, 3 -> 2, 5 -> 3
-    assert list(zip(*[a.tolist() for a in sub[0]])) == [(1, 2), (2, 0)]
-    assert list(zip(*[a.tolist() for a in sub[1]])) == [(1, 2), (2, 0), (3, 2)]
+    assert node_list.tolist() == [4, 3, 2, 5] and n_inner == 2  # the batch, then one hop (3), then two hops (2, 5)
+    # kept: edges into 3 or 4.  new ids: 4 -> 0, 3 -> 1, 2 -> 2, 5 -> 3
+    assert list(zip(*[a.tolist() for a in sub[0]])) == [(2, 1), (1, 0)]
+    assert list(zip(*[a.tolist() for a in sub[1]])) == [(2, 1), (1, 0), (3, 1)]
 
 
 def test_star_and_batch_order():
-    # leaves 1..4 point at the hub 0; the batch keeps its given order, the others ascend
+    # leaves 1..4 point at the hub 0; the batch keeps its given order, the others ascend within their hop count
     edges = [_arr([(1, 0), (2, 0), (3, 0), (4, 0)])]
     node_list, sub, n_inner = minibatch.extract(edges, [3, 0], 1)
     assert node_list.tolist() == [3, 0, 1, 2, 4] and n_inner == 2
     assert sorted(zip(*[a.tolist() for a in sub[0]])) == [(0, 1), (2, 1), (3, 1), (4, 1)]
     with pytest.raises(ValueError):
         minibatch.extract(edges, [1, 1], 1)
+
+
+def test_every_hop_set_is_a_prefix_of_the_numbering():
+    rng = np.random.default_rng(5)
+    edges = [(rng.integers(0, 60, 90).astype(np.int32), rng.integers(0, 60, 90).astype(np.int32)) for _ in range(3)]
+    batch = [17, 3, 41]
+    levels = minibatch.closure(edges, batch, 3)
+    node_list, _, n_inner = minibatch.extract(edges, batch, 3)
+    assert node_list[:3].tolist() == batch and n_inner == len(levels[2])
+    for k in range(4):
+        first = node_list[:len(levels[k])].tolist()
+        assert set(first) == levels[k]
+        if k:  # ascending ids among the nodes first reached in k hops
+            new = first[len(levels[k - 1]):]
+            assert new == sorted(new)
+    assert len(levels[1]) < len(levels[2]) < len(levels[3]) < 60  # (the case does separate the sets)
 
 
 def test_zero_hops_is_the_batch_alone():
