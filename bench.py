@@ -511,13 +511,13 @@ def minibatch_rows(ctx, wl, seq, params, target, L, label):
     rows = []
     for parts, take in ((8, 2), (64, 3)):
         size = n // parts
-        acc = {"extract_ms": [], "deltas_ms": [], "seq_first_epoch_ms": [], "node_first_epoch_ms": [], "nodes": [], "edges": [],
+        acc = {"extract_ms": [], "deltas_ms": [], "seq_first_epoch_ms": [], "node_first_epoch_ms": [], "nodes": [], "inner": [], "edges": [],
                "cache_MB": [], "hits": [], "misses": [], "hits_node_first": []}
         for b in range(take):
             batch = perm[b * size:(b + 1) * size]
             torch.cuda.synchronize()
             t0 = time.perf_counter()
-            total, _ = ctx.batch_plan(batch)
+            total, inner = ctx.batch_plan(batch)
             frac = total / n
             child_arena = int(frac * ctx.cfg.arena_bytes) + (512 << 20)
             child = ctx.batch_context(batch, child_arena, planned_total=total)
@@ -558,13 +558,15 @@ def minibatch_rows(ctx, wl, seq, params, target, L, label):
                     acc["hits"].append(st1["global_hits"] - st0["global_hits"])
                     acc["misses"].append(st1["global_misses"] - st0["global_misses"])
             acc["nodes"].append(total)
+            acc["inner"].append(inner)
             acc["edges"].append(sum(child.get_snapshot_csr(t)[1].size for t in range(T)) / full_edges)
             acc["cache_MB"].append(T * child.aggregate_bytes() / 1e6)
             child.close()
             del child
         mean = lambda k: float(np.mean(acc[k]))
         rows.append({"graph": label, "batch_nodes": size, "batches_timed": take, "batches_per_pass": parts,
-                     "sub_sequence_nodes": round(mean("nodes")), "edges_kept_frac": round(mean("edges"), 4),
+                     "sub_sequence_nodes": round(mean("nodes")), "nodes_within_one_hop": round(mean("inner")),
+                     "edges_kept_frac": round(mean("edges"), 4),
                      "extract_ms": round(mean("extract_ms"), 3), "build_deltas_ms": round(mean("deltas_ms"), 3),
                      "seq_first_epoch_ms": round(mean("seq_first_epoch_ms"), 3), "node_first_epoch_ms": round(mean("node_first_epoch_ms"), 3),
                      "layer1_cache_MB": round(mean("cache_MB"), 1), "hits": round(mean("hits")), "misses": round(mean("misses")),

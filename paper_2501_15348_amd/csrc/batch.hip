@@ -7,9 +7,12 @@
 //
 //   F_0 = the batch,  F_k = F_{k-1} and the sources of every edge, of any snapshot, whose target is in F_{k-1};
 //   the sub-sequence keeps the nodes F_hops and, of every snapshot, the edges whose target is in F_{hops-1}.
-// Numbering of the sub-sequence: batch nodes first, in the order given, then the others by ascending id.
+// Numbering of the sub-sequence: batch nodes first, in the order given, then the nodes first reached in one hop by
+// ascending id, then those first reached in two hops, ...: every F_k is a prefix of the ids, so layer l of an L-layer
+// model, which is needed on F_{L-l} only, works on a prefix of the rows.
 #include <algorithm>
 #include <climits>
+#include <cstdlib>
 #include <vector>
 
 #include "ctx.h"
@@ -34,21 +37,26 @@ __global__ void batch_seed(const int32_t *nodes, int64_t nb, int32_t *level, int
     node_list[i] = v;
 }
 
-// flags of the nodes that join the batch nodes in the sub-sequence, and the count of inner nodes (targets kept)
-__global__ void batch_member_flags(const int32_t *level, int64_t n, int32_t hops, int32_t *flag, unsigned long long *inner)
+// flag[(k - 1) * n + v] = node v is first reached in exactly k hops, k = 1 .. hops: the scan of these flags numbers
+// the nodes that join the batch by hop count first and by id second
+__global__ void batch_level_flags(const int32_t *level, int64_t n, int32_t hops, int32_t *flag)
 {
-    const int64_t v = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
-    if (v >= n) return;
-    const int32_t l = level[v];
-    flag[v] = l >= 1 && l <= hops;
-    if (l < hops) atomicAdd(inner, 1ull);
+    const int64_t idx = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
+    if (idx >= n * hops) return;
+    const int64_t k = idx / n;
+    flag[idx] = level[idx - k * n] == int32_t(k + 1);
 }
 
-__global__ void batch_number(const int32_t *flag, const int64_t *offs, int64_t n, int64_t nb, int32_t *new_id, int32_t *node_list)
+// new ids and the node list; counts[k] = nodes first reached in 1 .. k hops, k = 0 .. hops
+__global__ void batch_number(const int32_t *level, const int64_t *offs, int64_t n, int32_t hops, int64_t nb, int32_t *new_id,
+                             int32_t *node_list, int64_t *counts)
 {
     const int64_t v = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
-    if (v >= n || !flag[v]) return;
-    const int64_t id = nb + offs[v];
+    if (v <= hops) counts[v] = offs[v * n];
+    if (v >= n) return;
+    const int32_t l = level[v];
+    if (l < 1 || l > hops) return;
+    const int64_t id = nb + offs[int64_t(l - 1) * n + v];
     new_id[v] = int32_t(id);
     node_list[id] = int32_t(v);
 }
@@ -229,6 +237,13 @@ const MbSrc *source_table(reinc_ctx *ctx, int64_t *max_e)
     return static_cast<const MbSrc *>(dev);
 }
 
+// A layer below the last keeps full-height slices, so restricted to its first rows it runs timestep by timestep
+// instead of once per batch of timesteps.  That pays when the rows left out are many: the restriction is taken when
+// they hold at least this many bytes of the layer's input and output per timestep (measured: 500,000-node graphs
+// gain 10 % of a batch epoch at 200 MB and 3 % at 100 MB; at 70 MB and below, and on 100,000-node graphs, the
+// one-by-one launches cost 5 - 13 %).  REINC_LAYER_ROWS=<MB> overrides it (0: always).
+constexpr double layer_rows_threshold = 150e6;
+
 unsigned bits_for(int64_t values)  // bits that hold any number in [0, values)
 {
     unsigned bits = 1;
@@ -246,6 +261,7 @@ int reinc_set_loss_rows(reinc_ctx *ctx, int64_t rows)
     if (!ctx) return REINC_E_ARG;
     if (rows < 0 || rows > ctx->N()) return ctx->fail(REINC_E_ARG, "loss rows %lld outside [0, %lld]", (long long)rows, (long long)ctx->N());
     ctx->loss_rows = rows == ctx->N() ? 0 : rows;
+    for (int64_t &r : ctx->layer_rows) r = 0;  // (only reinc_batch_load knows which rows the layers below need)
     ctx->local_valid = false;  // a backward call needs a forward call with these rows first
     return REINC_OK;
 }
@@ -276,39 +292,41 @@ int reinc_batch_plan(reinc_ctx *ctx, const int32_t *nodes, int64_t n_batch, int3
     }
     ctx->scratch_reset();
     int32_t *d_nodes = static_cast<int32_t *>(ctx->scratch(uint64_t(n_batch) * 4));
-    int32_t *flag = static_cast<int32_t *>(ctx->scratch(uint64_t(n) * 4));
-    int64_t *offs = static_cast<int64_t *>(ctx->scratch(uint64_t(n + 1) * 8));
-    void *scan_tmp = ctx->scratch(scan_tmp_bytes(n));
-    int64_t *counters = static_cast<int64_t *>(ctx->scratch(256));  // [0] inner nodes, [1] (as int32) duplicate flag
+    int32_t *flag = static_cast<int32_t *>(ctx->scratch(uint64_t(n) * hops * 4));
+    int64_t *offs = static_cast<int64_t *>(ctx->scratch(uint64_t(n * hops + 1) * 8));
+    void *scan_tmp = ctx->scratch(scan_tmp_bytes(n * hops));
+    int64_t *counters = static_cast<int64_t *>(ctx->scratch(1024));  // [0 .. hops] level counts, [hops + 1] (as int32) duplicate flag
     int64_t max_e = 0;
     const MbSrc *src = source_table(ctx, &max_e);
     if (!d_nodes || !flag || !offs || !scan_tmp || !counters || !src) {
         ctx->scratch_reset();
         return ctx->fail(REINC_E_NOMEM, "arena exhausted while planning a node batch");
     }
-    int32_t *err = reinterpret_cast<int32_t *>(counters + 1);
+    int32_t *err = reinterpret_cast<int32_t *>(counters + hops + 1);
     REINC_HIP(ctx, hipMemcpy(d_nodes, nodes, size_t(n_batch) * 4, hipMemcpyHostToDevice));
     launch_fill_i32(ctx->batch_level, n, kFar, s);
     launch_fill_i32(ctx->batch_new_id, n, -1, s);
-    launch_fill_i32(reinterpret_cast<int32_t *>(counters), 4, 0, s);
+    launch_fill_i32(err, 2, 0, s);
     batch_seed<<<blocks_for(n_batch, 256), 256, 0, s>>>(d_nodes, n_batch, ctx->batch_level, ctx->batch_new_id, ctx->batch_nodes, err);
     if (max_e > 0)
         for (int32_t k = 1; k <= hops; ++k)
             mb_expand<<<dim3(blocks_for(n * 16, 256), unsigned(ctx->snaps.size())), 256, 0, s>>>(src, ctx->batch_level, k, n);
-    batch_member_flags<<<blocks_for(n, 256), 256, 0, s>>>(ctx->batch_level, n, hops, flag, reinterpret_cast<unsigned long long *>(counters));
-    launch_scan(flag, offs, n, scan_tmp, s);
-    batch_number<<<blocks_for(n, 256), 256, 0, s>>>(flag, offs, n, n_batch, ctx->batch_new_id, ctx->batch_nodes);
+    batch_level_flags<<<blocks_for(n * hops, 256), 256, 0, s>>>(ctx->batch_level, n, hops, flag);
+    launch_scan(flag, offs, n * hops, scan_tmp, s);
+    batch_number<<<blocks_for(std::max<int64_t>(n, hops + 1), 256), 256, 0, s>>>(ctx->batch_level, offs, n, hops, n_batch, ctx->batch_new_id,
+                                                                              ctx->batch_nodes, counters);
     REINC_HIP(ctx, hipGetLastError());
-    int64_t joined = 0, host_counters[2] = {0, 0};
-    REINC_HIP(ctx, hipMemcpy(&joined, offs + n, 8, hipMemcpyDeviceToHost));
-    REINC_HIP(ctx, hipMemcpy(host_counters, counters, 16, hipMemcpyDeviceToHost));
+    std::vector<int64_t> host_counters(size_t(hops) + 2, 0);
+    REINC_HIP(ctx, hipMemcpy(host_counters.data(), counters, size_t(hops + 2) * 8, hipMemcpyDeviceToHost));
     ctx->scratch_reset();
-    if (int32_t(host_counters[1] & 0xffffffff)) return ctx->fail(REINC_E_ARG, "a node is listed twice in the batch");
+    if (int32_t(host_counters[hops + 1] & 0xffffffff)) return ctx->fail(REINC_E_ARG, "a node is listed twice in the batch");
     ctx->batch_size = n_batch;
-    ctx->batch_total = n_batch + joined;
+    ctx->batch_total = n_batch + host_counters[hops];
     ctx->batch_hops = hops;
+    ctx->batch_reach.assign(size_t(hops) + 1, 0);  // |F_k|: the nodes reached in at most k hops are the first |F_k| ids
+    for (int32_t k = 0; k <= hops; ++k) ctx->batch_reach[k] = n_batch + host_counters[k];
     if (n_nodes_out) *n_nodes_out = ctx->batch_total;
-    if (n_inner_out) *n_inner_out = host_counters[0];
+    if (n_inner_out) *n_inner_out = ctx->batch_reach[hops - 1];
     return REINC_OK;
 }
 
@@ -454,6 +472,17 @@ int reinc_batch_load(reinc_ctx *ctx, reinc_ctx *child)
     }
     if (child->has_derived) child->load_after_derived = true;
     child->loss_rows = ctx->batch_size == nu ? 0 : ctx->batch_size;
+    // layer l of the batch context's L layers is needed on the nodes within L - l hops of the batch: the first ids
+    const int32_t Lc = b.num_gcn_layers;
+    const char *env = std::getenv("REINC_LAYER_ROWS");  // a number of MB: see layer_rows_threshold
+    const double threshold = env ? std::atof(env) * 1e6 : layer_rows_threshold;
+    for (int32_t l = 1; l <= REINC_MAX_GCN_LAYERS; ++l) {
+        const int32_t k = Lc - l;
+        child->layer_rows[l] = 0;
+        if (l >= Lc || k > ctx->batch_hops || ctx->batch_reach[k] >= nu) continue;
+        const double saved = double(nu - ctx->batch_reach[k]) * (b.dims[l - 1] + b.dims[l]) * 4.0;
+        if (saved >= threshold) child->layer_rows[l] = ctx->batch_reach[k];
+    }
     child->local_valid = false;
     return REINC_OK;
 }

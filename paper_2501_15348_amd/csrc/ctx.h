@@ -141,12 +141,20 @@ struct reinc_ctx {
     int64_t loss_rows = 0;  // rows [0, loss_rows) enter the loss (a node mini-batch, numbered first); 0 = every row
     int64_t counted_rows() const { return loss_rows > 0 ? loss_rows : cfg.num_nodes; }
     // The stacked model computes its last GCN layer and the recurrent cell on the loss rows only (nothing else reads
-    // them: the layers below need every row, because the batch's neighbours feed the aggregation of the last layer).
+    // them).  The layers below need the batch's neighbourhood: layer l of L the nodes within L - l hops, which a batch
+    // context numbers first (layer_rows[l] of them, set by reinc_batch_load; 0 = every row).
     int64_t top_rows() const { return counted_rows(); }
+    int64_t layer_rows[REINC_MAX_GCN_LAYERS + 1] = {};
+    int64_t rows_of_layer(int l) const
+    {
+        if (l == cfg.num_gcn_layers) return top_rows();
+        return l >= 1 && layer_rows[l] > 0 ? layer_rows[l] : cfg.num_nodes;
+    }
     // node mini-batch plan made on this context (reinc_batch_plan): hop level and new id per node, the node list
     int32_t *batch_level = nullptr, *batch_new_id = nullptr, *batch_nodes = nullptr;
     int64_t batch_size = 0, batch_total = 0;  // batch nodes, nodes of the sub-sequence (0: no plan)
     int32_t batch_hops = 0;
+    std::vector<int64_t> batch_reach;  // [k] = nodes reached in at most k hops (the first ids of the sub-sequence)
     reinc_stats stats{};
     // arena bookkeeping for reinc_reset_derived
     bool has_derived = false, load_after_derived = false;

@@ -466,16 +466,20 @@ int reinc_forward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *par
             q[i] = ctx->snaps[t0 + i].q;
         }
         for (int l = 1; l <= Lg; ++l) {
+            // rows of H^l that anything reads: all of them, or (a node batch) the first nl; the layers below the last
+            // keep full-height slices, so with nl < n their timesteps are not adjacent and go one by one
+            const int64_t nl = ctx->rows_of_layer(l);
             if (transform_first(c, l)) {
-                // Z = H^{l-1} W_l for all timesteps of the batch as one tall matrix (every row: the rows are sources),
-                // then H^l = ReLU(Q (A + sI) P Z + b_l) straight out of the aggregation kernel
+                // Z = H^{l-1} W_l for all timesteps of the batch as one tall matrix (every row of H^{l-1} that exists: the
+                // rows are sources), then H^l = ReLU(Q (A + sI) P Z + b_l) straight out of the aggregation kernel
+                const int64_t nz = ctx->rows_of_layer(l - 1);
                 for (int32_t i = lo; i <= hi; ++i) {
                     Sp[i] = ctx->local[i].H[l - 1];
                     Hout[i] = ctx->local[i].S[l];
                 }
-                REINC_TRY(for_runs(lo, hi, n, {Strip{Sp.data(), c.dims[l - 1]}, Strip{Hout.data(), int64_t(s_width_floats(c, l))}},
+                REINC_TRY(for_runs(lo, hi, nz, {Strip{Sp.data(), c.dims[l - 1]}, Strip{Hout.data(), int64_t(s_width_floats(c, l))}},
                                    [&](int i0, int len) {
-                                       gemm_rows(ctx, s, (const void *)Sp[i0], 0, n * len, c.dims[l - 1], c.dims[l], nof, p.W[l], 0,
+                                       gemm_rows(ctx, s, (const void *)Sp[i0], 0, nz * len, c.dims[l - 1], c.dims[l], nof, p.W[l], 0,
                                                  c.dims[l], nof, 0, nof, nof, const_cast<float *>(Hout[i0]));
                                        return REINC_OK;
                                    }));
@@ -488,12 +492,12 @@ int reinc_forward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *par
                     it = AggItem{sn.row_ptr, sn.col, st.S[l], sn.p, sn.q, nullptr, nullptr, st.H[l], sn.long_rows, sn.n_long_rows};
                     it.bias = p.b[l];
                     it.relu = 1;
-                    if (l == Lg && nt < n)
-                        it.row_limit = nt;  // H of the last layer has nt rows per timestep: rows [0, nt) as they come
+                    if (nl < n)
+                        it.row_limit = nl;  // rows [0, nl) as they come (the last layer's H has nt rows per timestep)
                     else
                         it.order = sn.row_order;
                 }
-                aggregate_full_batch(ctx, batch, 0, c.dims[l], c.self_loop, s, l == Lg ? nt : n);
+                aggregate_full_batch(ctx, batch, 0, c.dims[l], c.self_loop, s, nl);
                 continue;
             }
             if (l >= 2) {
@@ -504,12 +508,12 @@ int reinc_forward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *par
                     LocalStep &st = ctx->local[i];
                     batch.item[i - lo] = AggItem{sn.row_ptr, sn.col, st.H[l - 1], sn.p, nullptr, nullptr, nullptr, st.S[l], sn.long_rows,
                                                  sn.n_long_rows};
-                    if (l == Lg && nt < n)
-                        batch.item[i - lo].row_limit = nt;  // S of the last layer has nt rows per timestep: rows [0, nt) as they come
+                    if (nl < n)
+                        batch.item[i - lo].row_limit = nl;  // rows [0, nl) as they come (the last layer's S has nt rows per timestep)
                     else
                         batch.item[i - lo].order = sn.row_order;
                 }
-                aggregate_full_batch(ctx, batch, 0, c.dims[l - 1], c.self_loop, s, l == Lg ? nt : n);
+                aggregate_full_batch(ctx, batch, 0, c.dims[l - 1], c.self_loop, s, nl);
             }
             for (int32_t i = lo; i <= hi; ++i) {
                 Sp[i] = l == 1 ? s1[i] : ctx->local[i].S[l];
@@ -518,7 +522,6 @@ int reinc_forward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *par
             const bool has_q = q[lo] != nullptr;
             // (the last layer works on the top rows; with Lg == 1 its input, the cached sums, and the degree scales
             // keep the full height, so a batch's timesteps are not adjacent there and go one by one)
-            const int64_t nl = l == Lg ? nt : n;
             REINC_TRY(for_runs(lo, hi, nl, {Strip{Sp.data(), c.dims[l - 1]}, Strip{Hout.data(), c.dims[l]},
                                             Strip{has_q ? q.data() : nullptr, 1}},
                                [&](int i0, int len) {
@@ -560,7 +563,6 @@ int reinc_backward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *pa
     Params gp = split_params(c, grads);
     const int64_t n = c.num_nodes;
     const int64_t nt = ctx->top_rows();  // rows of the last GCN layer and of the recurrent cell (see place_top)
-    const bool top = nt < n;
     if (ctx->local_top != nt) return ctx->fail(REINC_E_STATE, "the loss rows changed since the forward pass of this window");
     const int Lg = c.num_gcn_layers, H = c.rnn_hidden;
     const int lstm = c.rnn_kind == REINC_RNN_LSTM;
@@ -673,19 +675,32 @@ int reinc_backward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *pa
         for (int l = Lg; l >= 1; --l) {
             const int din = c.dims[l - 1], dout = c.dims[l];
             calls = 0;
-            // dz holds the gradients of layer l's pre-activations: nl rows per timestep (the top rows for the last layer)
-            const bool top_l = top && l == Lg;
-            const int64_t nl = l == Lg ? nt : n;
+            // dz holds the gradients of layer l's pre-activations: nl rows per timestep, the timesteps sl rows apart (the
+            // top rows, compact, for the last layer; below it full-height slices of which a node batch fills the first nl).
+            // np: the rows of layer l - 1 that anything reads (the sources of the rows of layer l lie among them).
+            const int64_t nl = ctx->rows_of_layer(l), sl = l == Lg ? nt : n;
+            const int64_t np = l > 1 ? ctx->rows_of_layer(l - 1) : n;
+            const bool part_l = nl < n;  // only some rows exist: what reads every row is given zeros for the others
+            auto adjoint_item = [&](AggItem &it, const Snapshot &sn) {  // its output rows are the sources
+                if (np < n)
+                    it.row_limit = np;
+                else
+                    it.order = sn.col_order;
+            };
             if (transform_first(c, l)) {
                 // H^l = ReLU(Q (A + sI) P Z + b_l), Z = H^{l-1} W_l:  db_l = column sums of dz;  dZ = P (A + sI)^T Q dz (the
                 // adjoint gather, dout wide);  dW_l = H^{l-1}^T dZ;  dz of layer l-1 = (dZ W_l^T) masked by H^{l-1} > 0
-                launch_column_sums(dz, nl * nb, dout, colsum, const_cast<float *>(gp.b[l]), 1, s);
+                if (nl == sl)
+                    launch_column_sums(dz, nl * nb, dout, colsum, const_cast<float *>(gp.b[l]), 1, s);
+                else
+                    for (int32_t i = lo; i <= hi; ++i)
+                        launch_column_sums(dz + int64_t(i - lo) * sl * dout, nl, dout, colsum, const_cast<float *>(gp.b[l]), 1, s);
                 const float *dz_full = dz;
-                if (top_l) {  // the adjoint reads every row: the rows that are not computed are zero
+                if (part_l) {  // the adjoint reads every row: the rows that are not computed are zero
                     launch_fill_f32(dagg, int64_t(nb) * n * dout, 0.0f, s);
                     for (int32_t i = lo; i <= hi; ++i)
-                        REINC_HIP(ctx, hipMemcpyAsync(dagg + int64_t(i - lo) * n * dout, dz + int64_t(i - lo) * nt * dout,
-                                                      uint64_t(nt) * dout * 4, hipMemcpyDeviceToDevice, s));
+                        REINC_HIP(ctx, hipMemcpyAsync(dagg + int64_t(i - lo) * n * dout, dz + int64_t(i - lo) * sl * dout,
+                                                      uint64_t(nl) * dout * 4, hipMemcpyDeviceToDevice, s));
                     dz_full = dagg;
                 }
                 AggBatch batch;
@@ -694,34 +709,34 @@ int reinc_backward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *pa
                     const Snapshot &sn = ctx->snaps[t0 + i];
                     batch.item[i - lo] = AggItem{sn.col_ptr, sn.row, dz_full + int64_t(i - lo) * n * dout, sn.q, sn.p, nullptr, nullptr,
                                                  dz2 + int64_t(i - lo) * n * dout, sn.long_cols, sn.n_long_cols};
-                    batch.item[i - lo].order = sn.col_order;
+                    adjoint_item(batch.item[i - lo], sn);
                 }
-                aggregate_full_batch(ctx, batch, 0, dout, c.self_loop, s);
+                aggregate_full_batch(ctx, batch, 0, dout, c.self_loop, s, np);
                 for (int32_t i = lo; i <= hi; ++i) Ap[i] = ctx->local[i].H[l - 1];
-                REINC_TRY(for_runs(lo, hi, n, {Strip{Ap.data(), din}}, [&](int i0, int len) {
-                    reduce(Ap[i0], din, nof, dz2 + int64_t(i0 - lo) * n * dout, dout, n * len, rowsB, din, dout, part_w[l],
+                REINC_TRY(for_runs(lo, hi, np, {Strip{Ap.data(), din}}, [&](int i0, int len) {
+                    reduce(Ap[i0], din, nof, dz2 + int64_t(i0 - lo) * n * dout, dout, np * len, rowsB, din, dout, part_w[l],
                            acc0 | (calls++ > 0));
-                    gemm_rows(ctx, s, (const void *)(dz2 + int64_t(i0 - lo) * n * dout), 0, n * len, dout, din, nof, p.W[l], 1, dout, nof,
-                              0, nof, Ap[i0], (top_l ? dz : dagg) + int64_t(i0 - lo) * n * din);
+                    gemm_rows(ctx, s, (const void *)(dz2 + int64_t(i0 - lo) * n * dout), 0, np * len, dout, din, nof, p.W[l], 1, dout, nof,
+                              0, nof, Ap[i0], (part_l ? dz : dagg) + int64_t(i0 - lo) * n * din);
                     return REINC_OK;
                 }));
-                if (!top_l) std::swap(dz, dagg);  // (with top rows dz itself received the full-height result)
+                if (!part_l) std::swap(dz, dagg);  // (else dz itself received the result, in full-height slices)
                 continue;
             }
             for (int32_t i = lo; i <= hi; ++i) Ap[i] = l == 1 ? s1[i] : ctx->local[i].S[l];
             REINC_TRY(for_runs(lo, hi, nl, {Strip{Ap.data(), din}, Strip{has_q ? q.data() : nullptr, 1}},
                                [&](int i0, int len) {
-                                   reduce(Ap[i0], din, q[i0], dz + int64_t(i0 - lo) * nl * dout, dout, nl * len, l == Lg ? rowsT : rowsB,
+                                   reduce(Ap[i0], din, q[i0], dz + int64_t(i0 - lo) * sl * dout, dout, nl * len, l == Lg ? rowsT : rowsB,
                                           din, dout, part_w[l], acc0 | (calls++ > 0));
                                    return REINC_OK;
                                }));
             if (l > 1) {
-                if (top_l) {
+                if (part_l) {
                     // the adjoint aggregation below reads every row of dagg (full height): the rows that are not computed
                     // are zero
                     launch_fill_f32(dagg, int64_t(nb) * n * din, 0.0f, s);
                     for (int32_t i = lo; i <= hi; ++i)
-                        gemm_rows(ctx, s, (const void *)(dz + int64_t(i - lo) * nt * dout), 0, nt, dout, din, nof, p.W[l], 1, dout, nof, 0,
+                        gemm_rows(ctx, s, (const void *)(dz + int64_t(i - lo) * sl * dout), 0, nl, dout, din, nof, p.W[l], 1, dout, nof, 0,
                                   nof, nof, dagg + int64_t(i - lo) * n * din);
                 } else
                     gemm_rows(ctx, s, (const void *)dz, 0, n * nb, dout, din, nof, p.W[l], 1, dout, nof, 0, nof, nof, dagg);
@@ -732,9 +747,9 @@ int reinc_backward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *pa
                     batch.item[i - lo] = AggItem{sn.col_ptr, sn.row, dagg + int64_t(i - lo) * n * din, sn.q, sn.p,
                                                  ctx->local[i].H[l - 1], nullptr, dz2 + int64_t(i - lo) * n * din, sn.long_cols,
                                                  sn.n_long_cols};
-                    batch.item[i - lo].order = sn.col_order;
+                    adjoint_item(batch.item[i - lo], sn);
                 }
-                aggregate_full_batch(ctx, batch, 0, din, c.self_loop, s);
+                aggregate_full_batch(ctx, batch, 0, din, c.self_loop, s, np);
                 std::swap(dz, dz2);
             }
         }

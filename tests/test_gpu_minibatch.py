@@ -21,8 +21,8 @@ def _dev(a):
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
 
-def _workload(mode, rnn, layers, n=3000, T=6, degree=2.5, seed=11, dist="uniform"):
-    dims = (16,) + (32,) * layers
+def _workload(mode, rnn, layers, n=3000, T=6, degree=2.5, seed=11, dist="uniform", dims=None):
+    dims = dims or (16,) + (32,) * layers
     return synth.Workload("mb", n, degree, T, dist, 2.1 if dist == "chunglu" else 0.0, 0.05, 0.02, "fp32", mode, True, dims, rnn,
                           32, 4, seed)
 
@@ -85,6 +85,16 @@ def test_batch_windows_match_the_whole_graph_reference(mode, rnn, layers):
     _check_batch_windows(mode, rnn, layers)
 
 
+@pytest.mark.parametrize("mode,rnn,dims", [("sum", "gru", (16, 32, 32, 32)), ("mean", "lstm", (16, 32, 16)),
+                                           ("sym", "gru", (16, 32, 16, 16)), ("mean", "gru", (16, 32, 32, 16))])
+def test_layers_below_the_last_run_on_their_hop_sets(mode, rnn, dims, monkeypatch):
+    """Layer l of L is computed on the nodes within L - l hops of the batch only (a prefix of the numbering); three
+    layers, and layers that narrow their input (linear map before the aggregation) in every position.  (The library
+    takes the restriction only where it pays; the environment variable makes it unconditional.)"""
+    monkeypatch.setenv("REINC_LAYER_ROWS", "0")
+    _check_batch_windows(mode, rnn, len(dims) - 1, degree=1.5, dims=dims, prefixes=True)
+
+
 def test_batch_windows_with_three_timesteps_per_launch(monkeypatch):
     """A window of four timesteps in launches of three and one: the compact slices of the last layer and of the cell
     are adjacent within a launch's timesteps only."""
@@ -99,19 +109,31 @@ def test_batch_windows_with_hub_rows_and_columns():
     _check_batch_windows("sym", "gru", 2, dist="chunglu", degree=12.0, hubs=True)
 
 
-def _check_batch_windows(mode, rnn, layers, dist="uniform", degree=2.5, hubs=False):
+def _check_batch_windows(mode, rnn, layers, dist="uniform", degree=2.5, hubs=False, dims=None, prefixes=False):
     import torch
 
-    wl = _workload(mode, rnn, layers, dist=dist, degree=degree)
+    wl = _workload(mode, rnn, layers, dist=dist, degree=degree, dims=dims)
     seq, ctx = _parent(wl)
     n, T, L, H = wl.num_nodes, wl.num_snapshots, 4, wl.hidden
     batch = np.random.default_rng(8).choice(n, 64, replace=False).astype(np.int32)
     if hubs:  # the node with the most in-edges joins the batch
         batch[0] = np.argmax(np.bincount(seq.edges[0][1], minlength=n))
         batch = np.unique(batch).astype(np.int32)
-    child = ctx.batch_context(batch, 1 << 28)  # default hop count
+    if prefixes:
+        # a batch context whose memory starts out as NaN: a row that no layer computes must not be read by any other
+        from paper_2501_15348_amd import reinc
+
+        total, _ = ctx.batch_plan(batch)
+        child = reinc.Context(total, ctx.T, ctx.dims, ctx.rnn, ctx.hidden, mode, True, "fp32", arena_bytes=1 << 28)
+        child.arena[:child.arena.numel() // 4 * 4].view(torch.float32).fill_(float("nan"))
+        ctx._ck(ctx.lib.reinc_batch_load(ctx.handle, child.handle))
+    else:
+        child = ctx.batch_context(batch, 1 << 28)  # default hop count
     node_list = ctx.batch_node_list(child.n)
     assert child.n < n or hubs
+    if prefixes:  # the case does separate the hop sets: every layer has its own row count
+        reach = [len(f) for f in minibatch.closure(seq.edges, batch, layers)]
+        assert all(a < b for a, b in zip(reach, reach[1:])) and reach[-1] == child.n, reach
     if hubs:
         ptr, idx = child.get_snapshot_csr(0)
         assert np.diff(ptr).max() > 64 and np.bincount(idx).max() > 64
