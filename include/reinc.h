@@ -273,7 +273,8 @@ int reinc_cache_peek(reinc_ctx *ctx, int32_t t, const float **S_out);
  * A sample is the sequence of computational graphs of a set of selected nodes.  With F_0 = the batch and
  * F_k = F_{k-1} plus the sources of every edge, of any snapshot, whose target is in F_{k-1}, the sub-sequence of a
  * batch keeps the nodes F_hops and, of every snapshot, the edges whose target is in F_{hops-1}; its nodes are
- * numbered batch first (in the order given), then the others by ascending id.  A stacked model of `hops`
+ * numbered batch first (in the order given), then the nodes first reached in one hop by ascending id, then those
+ * first reached in two hops, and so on: every F_k is the first |F_k| ids.  A stacked model of `hops`
  * aggregation layers evaluated on the sub-sequence gives on the batch rows exactly what it gives on the whole
  * graph.  (The degree scales of the mean and symmetric normalisations are carried over from the source graph, so
  * the degree of a node whose own in-edges are not kept -- a source only -- is still the right one.)
@@ -289,14 +290,17 @@ int reinc_cache_peek(reinc_ctx *ctx, int32_t t, const float **S_out);
  * reinc_batch_node_list: old id of every node of the planned sub-sequence, to a HOST array of n_nodes int32.  SYNC.
  * reinc_batch_load: fills `child` -- created by the caller with num_nodes = the planned count, the same
  *   num_snapshots, dims[0], feat_dtype, agg_kind, self_loop and device, no snapshots loaded -- with the extracted
- *   edges, the gathered feature rows and degree scales of every snapshot, and sets its loss rows to n_batch.  Errors are reported on `ctx`; after a
- *   failure `child` may hold some of the snapshots and is good for reinc_destroy only.  Both contexts stay
- *   independent afterwards (the child holds copies).  SYNC.
+ *   edges, the gathered feature rows and degree scales of every snapshot, and sets its loss rows to n_batch.  It
+ *   also tells `child` on how many of its first rows each layer below the last is needed (layer l of L: |F_{L-l}|),
+ *   and the window calls compute a layer on those rows only where that leaves out enough rows to pay for itself
+ *   (environment variable REINC_LAYER_ROWS = megabytes left out per timestep from which on; 0: always).  Errors are
+ *   reported on `ctx`; after a failure `child` may hold some of the snapshots and is good for reinc_destroy only.
+ *   Both contexts stay independent afterwards (the child holds copies).  SYNC.
  * reinc_set_loss_rows: the loss of the window calls becomes the mean over rows [0, rows) of h_last and target
  *   (both stay [N, H]); the gradients are those of that loss.  The stacked model then computes its last GCN layer
  *   and the recurrent cell on those rows only (nothing else depends on the others), and reinc_forward_window writes
  *   rows [0, rows) of h_last only.  rows = 0 or N: every row (the default).  A backward call needs a forward call
- *   made with the same rows (REINC_E_STATE otherwise). */
+ *   made with the same rows (REINC_E_STATE otherwise).  Forgets what reinc_batch_load said about the layers below. */
 int reinc_batch_plan(reinc_ctx *ctx, const int32_t *nodes, int64_t n_batch, int32_t hops, int64_t *n_nodes_out,
                      int64_t *n_inner_out);
 int reinc_batch_node_list(reinc_ctx *ctx, int32_t *out);
