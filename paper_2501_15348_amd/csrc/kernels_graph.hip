@@ -2,6 +2,8 @@
 // consecutive canonical CSRs (sorted edge keys) into the insert / delete CSRs and the merged signed delta rows
 // (paper Section 3.2: delta graphs of edge deletions and insertions, with a node's feature change
 // folded in through its out-edges).  All outputs are unique, so they can be compared bit for bit.
+#include <climits>
+
 #include "ctx.h"
 
 #include <algorithm>
@@ -466,13 +468,22 @@ __device__ inline void diff_count_list(const int32_t *mine, const int32_t *off_m
 {
     const int total = off_mine[nr];
     const int lane = threadIdx.x & 63;
+    static_assert(kDiffRows <= 64, "a lane holds the first entry of one row");
+    const int my_start = lane < nr ? off_mine[lane] : INT_MAX;  // (row `lane` begins here)
     for (int base = int(threadIdx.x >> 6) * 64; base < total; base += kDiffThreads) {
         const int e = base + lane;
         bool absent = false, hit = false;
+        // The row of every entry of the window: the row that holds its first entry is a count over the lanes' row
+        // starts (the same for all lanes); the rows that begin inside the window are few, and each is handed, as a
+        // scalar, to the lanes at or behind its first entry.
+        const int r0 = __popcll(__ballot(my_start <= base)) - 1;
+        int r = r0;
+        for (int k = r0 + 1; k < nr; ++k) {
+            const int start = __builtin_amdgcn_readlane(my_start, k);
+            if (start > base + 63) break;
+            if (e >= start) r = k;
+        }
         if (e < total) {
-            // the window's first row by bisection (the same for all lanes), then a few steps forward per lane
-            int r = row_of(off_mine, nr, base);
-            while (e >= off_mine[r + 1]) ++r;
             const int32_t u = mine[e];
             const int ob = off_other[r];
             absent = !sorted_has(other, ob, off_other[r + 1], ob + (e - off_mine[r]), u);
