@@ -560,7 +560,8 @@ def minibatch_rows(ctx, wl, seq, params, target, L, label):
             acc["nodes"].append(total)
             acc["inner"].append(inner)
             acc["edges"].append(sum(child.get_snapshot_csr(t)[1].size for t in range(T)) / full_edges)
-            acc["cache_MB"].append(T * child.aggregate_bytes() / 1e6)
+            cached_rows = inner if len(wl.dims) > 2 else batch.size  # the rows that layer 1 is needed on
+            acc["cache_MB"].append(T * cached_rows * wl.dims[0] * 4 / 1e6)
             child.close()
             del child
         mean = lambda k: float(np.mean(acc[k]))

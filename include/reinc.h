@@ -291,16 +291,18 @@ int reinc_cache_peek(reinc_ctx *ctx, int32_t t, const float **S_out);
  * reinc_batch_load: fills `child` -- created by the caller with num_nodes = the planned count, the same
  *   num_snapshots, dims[0], feat_dtype, agg_kind, self_loop and device, no snapshots loaded -- with the extracted
  *   edges, the gathered feature rows and degree scales of every snapshot, and sets its loss rows to n_batch.  It
- *   also tells `child` on how many of its first rows each layer below the last is needed (layer l of L: |F_{L-l}|),
- *   and the window calls compute a layer on those rows only where that leaves out enough rows to pay for itself
- *   (environment variable REINC_LAYER_ROWS = megabytes left out per timestep from which on; 0: always).  Errors are
+ *   also tells `child` on how many of its first rows each layer below the last is needed (layer l of L: |F_{L-l}|):
+ *   the window calls compute a layer on those rows only, and the cached layer-1 sums of `child` hold the rows that
+ *   layer 1 is needed on only (reinc_cache_peek then returns that many rows).  Environment variable
+ *   REINC_LAYER_ROWS = megabytes a restriction must leave out per timestep to be taken (default 0).  Errors are
  *   reported on `ctx`; after a failure `child` may hold some of the snapshots and is good for reinc_destroy only.
  *   Both contexts stay independent afterwards (the child holds copies).  SYNC.
  * reinc_set_loss_rows: the loss of the window calls becomes the mean over rows [0, rows) of h_last and target
  *   (both stay [N, H]); the gradients are those of that loss.  The stacked model then computes its last GCN layer
  *   and the recurrent cell on those rows only (nothing else depends on the others), and reinc_forward_window writes
  *   rows [0, rows) of h_last only.  rows = 0 or N: every row (the default).  A backward call needs a forward call
- *   made with the same rows (REINC_E_STATE otherwise).  Forgets what reinc_batch_load said about the layers below. */
+ *   made with the same rows (REINC_E_STATE otherwise).  Forgets what reinc_batch_load said about the layers below
+ *   (and with it the cached sums of a batch context, which hold some rows only). */
 int reinc_batch_plan(reinc_ctx *ctx, const int32_t *nodes, int64_t n_batch, int32_t hops, int64_t *n_nodes_out,
                      int64_t *n_inner_out);
 int reinc_batch_node_list(reinc_ctx *ctx, int32_t *out);

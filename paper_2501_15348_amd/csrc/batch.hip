@@ -237,12 +237,11 @@ const MbSrc *source_table(reinc_ctx *ctx, int64_t *max_e)
     return static_cast<const MbSrc *>(dev);
 }
 
-// A layer below the last keeps full-height slices, so restricted to its first rows it runs timestep by timestep
-// instead of once per batch of timesteps.  That pays when the rows left out are many: the restriction is taken when
-// they hold at least this many bytes of the layer's input and output per timestep (measured: 500,000-node graphs
-// gain 10 % of a batch epoch at 200 MB and 3 % at 100 MB; at 70 MB and below, and on 100,000-node graphs, the
-// one-by-one launches cost 5 - 13 %).  REINC_LAYER_ROWS=<MB> overrides it (0: always).
-constexpr double layer_rows_threshold = 150e6;
+// A layer below the last is restricted to the rows it is needed on when they leave out at least this many bytes of
+// its input and output per timestep.  (A first version kept full-height slices for such a layer and ran it timestep
+// by timestep, which paid from 150 MB on only; with the slices placed next to each other it always pays.)
+// REINC_LAYER_ROWS=<MB> overrides it; a huge value switches the restriction off.
+constexpr double layer_rows_threshold = 0.0;
 
 unsigned bits_for(int64_t values)  // bits that hold any number in [0, values)
 {
@@ -262,6 +261,11 @@ int reinc_set_loss_rows(reinc_ctx *ctx, int64_t rows)
     if (rows < 0 || rows > ctx->N()) return ctx->fail(REINC_E_ARG, "loss rows %lld outside [0, %lld]", (long long)rows, (long long)ctx->N());
     ctx->loss_rows = rows == ctx->N() ? 0 : rows;
     for (int64_t &r : ctx->layer_rows) r = 0;  // (only reinc_batch_load knows which rows the layers below need)
+    if (ctx->cache_rows > 0) {                 // cached sums that hold some of the rows only are of no use any more
+        const int rc = reinc_cache_clear(ctx);
+        if (rc != REINC_OK) return rc;
+        ctx->cache_rows = 0;
+    }
     ctx->local_valid = false;  // a backward call needs a forward call with these rows first
     return REINC_OK;
 }
@@ -483,6 +487,7 @@ int reinc_batch_load(reinc_ctx *ctx, reinc_ctx *child)
         const double saved = double(nu - ctx->batch_reach[k]) * (b.dims[l - 1] + b.dims[l]) * 4.0;
         if (saved >= threshold) child->layer_rows[l] = ctx->batch_reach[k];
     }
+    child->cache_rows = child->rows_of_layer(1) < nu ? child->rows_of_layer(1) : 0;  // (its cache is still empty)
     child->local_valid = false;
     return REINC_OK;
 }

@@ -130,7 +130,7 @@ struct reinc_ctx {
     std::vector<reinc::LocalStep> local;
     uint64_t local_reserved = 0;  // bytes at the top of the arena held by the local cache
     bool local_valid = false;
-    int64_t local_top = -1;  // row count the top quantities of the local cache are placed for (see place_top)
+    int64_t local_top = -1;  // row count the top quantities of the local cache are placed for (see place_rows)
     int32_t local_t0 = -1, local_L = 0;  // start of the window the local cache holds; the longest window it is carved for
     int32_t local_len = 0;               // length of the window it holds (the last forward call's)
     int local_kind = 0;  // which model carved the local cache: 0 = stacked (GCN layers, then the cell), 1 = integrated
@@ -150,6 +150,11 @@ struct reinc_ctx {
         if (l == cfg.num_gcn_layers) return top_rows();
         return l >= 1 && layer_rows[l] > 0 ? layer_rows[l] : cfg.num_nodes;
     }
+    // rows of the cached layer-1 sums that are computed and kept (a batch context: those layer 1 is needed on; the
+    // buffers of the global cache are then that short); 0 = every row
+    int64_t cache_rows = 0;
+    int64_t cached_rows() const { return cache_rows > 0 ? cache_rows : cfg.num_nodes; }
+    int64_t local_rows[REINC_MAX_GCN_LAYERS + 1] = {};  // rows_of_layer(l) the local cache is placed for (see place_rows)
     // node mini-batch plan made on this context (reinc_batch_plan): hop level and new id per node, the node list
     int32_t *batch_level = nullptr, *batch_new_id = nullptr, *batch_nodes = nullptr;
     int64_t batch_size = 0, batch_total = 0;  // batch nodes, nodes of the sub-sequence (0: no plan)

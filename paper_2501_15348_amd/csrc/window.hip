@@ -155,21 +155,31 @@ int ensure_local(reinc_ctx *ctx, int32_t L, hipStream_t s)
     return REINC_OK;
 }
 
-// With loss rows set (a node mini-batch, numbered first) the last GCN layer and the recurrent cell are computed on
-// those `nt` rows only.  Their per-timestep slices are then placed nt rows apart inside the same allocations, so that
-// consecutive timesteps stay adjacent rows of one tall matrix.  nt = N gives the layout ensure_local made.
-void place_top(reinc_ctx *ctx, int64_t nt, hipStream_t s)
+// Not every layer is computed on every row: with loss rows set (a node mini-batch, numbered first) the last GCN layer
+// and the recurrent cell work on those `nt` rows only, and a batch context may know that a layer below is needed on
+// its first rows only (reinc_ctx::rows_of_layer).  The per-timestep slices of a quantity are placed as many rows apart
+// as it has, inside the allocations ensure_local made for N rows, so that consecutive timesteps stay adjacent rows of
+// one tall matrix.  Z = H W of a layer that narrows its input has the rows of the layer below (they are sources).
+void place_rows(reinc_ctx *ctx, hipStream_t s)
 {
     const reinc_config &c = ctx->cfg;
     const int Lg = c.num_gcn_layers;
+    const int64_t nt = ctx->top_rows();
     const uint64_t H = uint64_t(c.rnn_hidden), rows = uint64_t(nt);
-    // (Z of a transform-first last layer is needed on every row -- the sources -- and stays where ensure_local put it)
-    float *bH = ctx->local[0].H[Lg], *bS = Lg >= 2 && !transform_first(c, Lg) ? ctx->local[0].S[Lg] : nullptr, *bc = ctx->local[0].c,
-          *bsv = ctx->local[0].saved;
+    float *bH[REINC_MAX_GCN_LAYERS + 1] = {}, *bS[REINC_MAX_GCN_LAYERS + 1] = {};
+    for (int l = 1; l <= Lg; ++l) {
+        bH[l] = ctx->local[0].H[l];
+        bS[l] = l >= 2 ? ctx->local[0].S[l] : nullptr;
+        ctx->local_rows[l] = ctx->rows_of_layer(l);
+    }
+    float *bc = ctx->local[0].c, *bsv = ctx->local[0].saved;
     for (size_t i = 0; i < ctx->local.size(); ++i) {
         reinc::LocalStep &st = ctx->local[i];
-        st.H[Lg] = bH + i * slice_floats(rows, c.dims[Lg]);
-        if (bS) st.S[Lg] = bS + i * slice_floats(rows, c.dims[Lg - 1]);
+        for (int l = 1; l <= Lg; ++l) {
+            const uint64_t rl = uint64_t(ctx->rows_of_layer(l));
+            st.H[l] = bH[l] + i * slice_floats(rl, c.dims[l]);
+            if (l >= 2) st.S[l] = bS[l] + i * slice_floats(transform_first(c, l) ? uint64_t(ctx->rows_of_layer(l - 1)) : rl, s_width_floats(c, l));
+        }
         st.h = ctx->zero_state + (i + 1) * slice_floats(rows, H);
         if (bc) st.c = bc + i * slice_floats(rows, H);
         st.saved = bsv + i * slice_floats(rows, 4 * H);
@@ -178,6 +188,17 @@ void place_top(reinc_ctx *ctx, int64_t nt, hipStream_t s)
         launch_fill_f32(ctx->zero_state, nt * c.rnn_hidden, 0.0f, s);
         ctx->local_top = nt;
     }
+}
+
+// dst[i * rows + r] = src_i[r] for the timesteps i of a batch: the degree scales of a layer that works on its first
+// rows only, next to each other like the layer's other per-timestep quantities
+struct ScaleTable {
+    const float *src[kMaxAggBatch];
+};
+__global__ void gather_scales(ScaleTable t, int64_t rows, float *dst)
+{
+    const int64_t r = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
+    if (r < rows) dst[int64_t(blockIdx.y) * rows + r] = t.src[blockIdx.y][r];
 }
 
 // Local cache of the integrated model: per timestep the aggregated hidden state Agg(h_{t-1}) (kept in LocalStep::S[1];
@@ -303,7 +324,8 @@ int ensure_layer1(reinc_ctx *ctx, int32_t t, hipStream_t s)
         return ctx->fail(REINC_E_STATE, "snapshot %d needs its edges and features loaded", t);
     const int32_t d = c.dims[0];
     const int bf16 = c.feat_dtype == REINC_BF16;
-    const uint64_t bytes = uint64_t(c.num_nodes) * d * 4;
+    const int64_t rows = ctx->cached_rows();  // (a batch context: the rows layer 1 is needed on; the buffer is that short)
+    const uint64_t bytes = uint64_t(rows) * d * 4;
     float *slot = nullptr;
     if (ctx->gpolicy) {
         if (ctx->pool_free.empty()) return ctx->fail(REINC_E_STATE, "cache buffers exhausted (window longer than configured?)");
@@ -342,14 +364,20 @@ int ensure_layer1(reinc_ctx *ctx, int32_t t, hipStream_t s)
         {
             // one pass over every row: changed rows get their delta, the others are copied into the new slot
             ProfScope prof(ctx, REINC_K_AGG_INC, s, true);
-            launch_incremental(nullptr, nullptr, c.num_nodes, dl.ent_ptr, dl.ent, pv.x, bf16, pv.p, dl.dY, d, ctx->gcache[t - 1], slot,
+            launch_incremental(nullptr, nullptr, rows, dl.ent_ptr, dl.ent, pv.x, bf16, pv.p, dl.dY, d, ctx->gcache[t - 1], slot,
                                nullptr, nullptr, s, prof.start(), prof.stop());
         }
         ++ctx->stats.steps_incremental;
         ctx->stats.delta_entries_processed += dl.info.n_entries;
     } else {
-        aggregate_full(ctx, sn.row_ptr, sn.col, sn.long_rows, sn.n_long_rows, sn.x, bf16, d, c.self_loop, sn.p, nullptr,
-                       nullptr, slot, s, sn.row_order);
+        AggBatch batch;
+        batch.count = 1;
+        batch.item[0] = AggItem{sn.row_ptr, sn.col, sn.x, sn.p, nullptr, nullptr, nullptr, slot, sn.long_rows, sn.n_long_rows};
+        if (rows < c.num_nodes)
+            batch.item[0].row_limit = rows;
+        else
+            batch.item[0].order = sn.row_order;
+        aggregate_full_batch(ctx, batch, bf16, d, c.self_loop, s, rows);
         ++ctx->stats.steps_full;
     }
     REINC_HIP(ctx, hipGetLastError());
@@ -452,12 +480,23 @@ int reinc_forward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *par
     // With loss rows set (a node mini-batch, numbered first) the last GCN layer and the recurrent cell are computed
     // on those rows only (see place_top).
     const int64_t nt = ctx->top_rows();
-    place_top(ctx, nt, s);
+    place_rows(ctx, s);
+    // the degree scales of a batch of timesteps, next to each other, for a layer that works on its first rows only
+    float *q_rows = nullptr;
+    if (c.agg_kind != REINC_AGG_SUM) {
+        int64_t most = 0;
+        for (int l = 1; l <= Lg; ++l)
+            if (ctx->rows_of_layer(l) < n && !transform_first(c, l)) most = std::max(most, ctx->rows_of_layer(l));
+        if (most > 0) {
+            q_rows = static_cast<float *>(ctx->scratch(uint64_t(std::min<int32_t>(L, ctx->max_batch)) * most * 4));
+            if (!q_rows) return ctx->fail(REINC_E_NOMEM, "arena exhausted: no room for a batch's degree scales");
+        }
+    }
     // Layer by layer over batches of timesteps: the dense steps see all timesteps of a batch as one tall matrix
     // (one launch instead of one per timestep), the aggregation of a layer takes the batch's snapshots in one
     // launch; only the layer-1 sums (a chain over snapshots) and the recurrent cell (a chain over time) go
     // timestep by timestep.
-    std::vector<const float *> s1(L), q(L), Hp(L), Sp(L), Hout(L);
+    std::vector<const float *> s1(L), q(L), ql(L), Hp(L), Sp(L), Hout(L);
     for (int32_t lo = 0; lo < L; lo += ctx->max_batch) {
         const int32_t hi = std::min(L, lo + ctx->max_batch) - 1;
         for (int32_t i = lo; i <= hi; ++i) {
@@ -518,14 +557,23 @@ int reinc_forward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *par
             for (int32_t i = lo; i <= hi; ++i) {
                 Sp[i] = l == 1 ? s1[i] : ctx->local[i].S[l];
                 Hout[i] = ctx->local[i].H[l];
+                ql[i] = q[i];
             }
             const bool has_q = q[lo] != nullptr;
+            if (has_q && nl < n && q_rows) {
+                ScaleTable tab{};
+                for (int32_t i = lo; i <= hi; ++i) {
+                    tab.src[i - lo] = q[i];
+                    ql[i] = q_rows + int64_t(i - lo) * nl;
+                }
+                gather_scales<<<dim3(unsigned((nl + 255) / 256), unsigned(hi - lo + 1)), 256, 0, s>>>(tab, nl, q_rows);
+            }
             // (the last layer works on the top rows; with Lg == 1 its input, the cached sums, and the degree scales
             // keep the full height, so a batch's timesteps are not adjacent there and go one by one)
             REINC_TRY(for_runs(lo, hi, nl, {Strip{Sp.data(), c.dims[l - 1]}, Strip{Hout.data(), c.dims[l]},
-                                            Strip{has_q ? q.data() : nullptr, 1}},
+                                            Strip{has_q ? ql.data() : nullptr, 1}},
                                [&](int i0, int len) {
-                                   gemm_rows(ctx, s, (const void *)Sp[i0], 0, nl * len, c.dims[l - 1], c.dims[l], q[i0], p.W[l], 0,
+                                   gemm_rows(ctx, s, (const void *)Sp[i0], 0, nl * len, c.dims[l - 1], c.dims[l], ql[i0], p.W[l], 0,
                                              c.dims[l], p.b[l], 1, nof, nof, const_cast<float *>(Hout[i0]));
                                    return REINC_OK;
                                }));
@@ -564,6 +612,9 @@ int reinc_backward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *pa
     const int64_t n = c.num_nodes;
     const int64_t nt = ctx->top_rows();  // rows of the last GCN layer and of the recurrent cell (see place_top)
     if (ctx->local_top != nt) return ctx->fail(REINC_E_STATE, "the loss rows changed since the forward pass of this window");
+    for (int l = 1; l <= c.num_gcn_layers; ++l)
+        if (ctx->local_rows[l] != ctx->rows_of_layer(l))
+            return ctx->fail(REINC_E_STATE, "the rows of layer %d changed since the forward pass of this window", l);
     const int Lg = c.num_gcn_layers, H = c.rnn_hidden;
     const int lstm = c.rnn_kind == REINC_RNN_LSTM;
     const int KH = (lstm ? 4 : 3) * H;
@@ -610,6 +661,17 @@ int reinc_backward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *pa
     }
     float *colsum = static_cast<float *>(ctx->scratch(column_sums_bytes(maxd)));
     part_ok = part_ok && colsum;
+    // the degree scales of a batch of timesteps, next to each other, for a layer that works on its first rows only
+    float *q_rows = nullptr;
+    if (c.agg_kind != REINC_AGG_SUM) {
+        int64_t most = 0;
+        for (int l = 1; l <= Lg; ++l)
+            if (ctx->rows_of_layer(l) < n && !transform_first(c, l)) most = std::max(most, ctx->rows_of_layer(l));
+        if (most > 0) {
+            q_rows = static_cast<float *>(ctx->scratch(uint64_t(B) * most * 4));
+            part_ok = part_ok && q_rows;
+        }
+    }
     if (!dgi || !dgh || !dz || !dz2 || !dagg || !part_ok) {
         ctx->scratch_reset();
         return ctx->fail(REINC_E_NOMEM, "arena exhausted: no room for the backward scratch buffers");
@@ -618,7 +680,7 @@ int reinc_backward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *pa
     launch_mse_grad(ctx->local[L - 1].h, target, ctx->counted_rows() * H, nt * H, dh, s);
     const float *dc_in = nullptr;  // zero at the last step
     const float *nof = nullptr;
-    std::vector<const float *> s1(L), q(L), Ap(L), Mp(L);
+    std::vector<const float *> s1(L), q(L), ql(L), Ap(L), Mp(L);
     // The partial slabs of a weight always belong to the same number of rows (B timesteps): a shorter last batch
     // uses the chunk geometry of a full one, so that every batch adds into the same slabs.
     auto reduce = [&](const float *A, int lda, const float *rs, const float *G, int ldg, int64_t rows, int64_t rows_geom, int K, int M,
@@ -675,10 +737,9 @@ int reinc_backward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *pa
         for (int l = Lg; l >= 1; --l) {
             const int din = c.dims[l - 1], dout = c.dims[l];
             calls = 0;
-            // dz holds the gradients of layer l's pre-activations: nl rows per timestep, the timesteps sl rows apart (the
-            // top rows, compact, for the last layer; below it full-height slices of which a node batch fills the first nl).
+            // dz holds the gradients of layer l's pre-activations: nl rows per timestep, the timesteps next to each other.
             // np: the rows of layer l - 1 that anything reads (the sources of the rows of layer l lie among them).
-            const int64_t nl = ctx->rows_of_layer(l), sl = l == Lg ? nt : n;
+            const int64_t nl = ctx->rows_of_layer(l);
             const int64_t np = l > 1 ? ctx->rows_of_layer(l - 1) : n;
             const bool part_l = nl < n;  // only some rows exist: what reads every row is given zeros for the others
             auto adjoint_item = [&](AggItem &it, const Snapshot &sn) {  // its output rows are the sources
@@ -690,16 +751,12 @@ int reinc_backward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *pa
             if (transform_first(c, l)) {
                 // H^l = ReLU(Q (A + sI) P Z + b_l), Z = H^{l-1} W_l:  db_l = column sums of dz;  dZ = P (A + sI)^T Q dz (the
                 // adjoint gather, dout wide);  dW_l = H^{l-1}^T dZ;  dz of layer l-1 = (dZ W_l^T) masked by H^{l-1} > 0
-                if (nl == sl)
-                    launch_column_sums(dz, nl * nb, dout, colsum, const_cast<float *>(gp.b[l]), 1, s);
-                else
-                    for (int32_t i = lo; i <= hi; ++i)
-                        launch_column_sums(dz + int64_t(i - lo) * sl * dout, nl, dout, colsum, const_cast<float *>(gp.b[l]), 1, s);
+                launch_column_sums(dz, nl * nb, dout, colsum, const_cast<float *>(gp.b[l]), 1, s);
                 const float *dz_full = dz;
                 if (part_l) {  // the adjoint reads every row: the rows that are not computed are zero
                     launch_fill_f32(dagg, int64_t(nb) * n * dout, 0.0f, s);
                     for (int32_t i = lo; i <= hi; ++i)
-                        REINC_HIP(ctx, hipMemcpyAsync(dagg + int64_t(i - lo) * n * dout, dz + int64_t(i - lo) * sl * dout,
+                        REINC_HIP(ctx, hipMemcpyAsync(dagg + int64_t(i - lo) * n * dout, dz + int64_t(i - lo) * nl * dout,
                                                       uint64_t(nl) * dout * 4, hipMemcpyDeviceToDevice, s));
                     dz_full = dagg;
                 }
@@ -708,25 +765,36 @@ int reinc_backward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *pa
                 for (int32_t i = lo; i <= hi; ++i) {
                     const Snapshot &sn = ctx->snaps[t0 + i];
                     batch.item[i - lo] = AggItem{sn.col_ptr, sn.row, dz_full + int64_t(i - lo) * n * dout, sn.q, sn.p, nullptr, nullptr,
-                                                 dz2 + int64_t(i - lo) * n * dout, sn.long_cols, sn.n_long_cols};
+                                                 dz2 + int64_t(i - lo) * np * dout, sn.long_cols, sn.n_long_cols};
                     adjoint_item(batch.item[i - lo], sn);
                 }
                 aggregate_full_batch(ctx, batch, 0, dout, c.self_loop, s, np);
                 for (int32_t i = lo; i <= hi; ++i) Ap[i] = ctx->local[i].H[l - 1];
                 REINC_TRY(for_runs(lo, hi, np, {Strip{Ap.data(), din}}, [&](int i0, int len) {
-                    reduce(Ap[i0], din, nof, dz2 + int64_t(i0 - lo) * n * dout, dout, np * len, rowsB, din, dout, part_w[l],
+                    reduce(Ap[i0], din, nof, dz2 + int64_t(i0 - lo) * np * dout, dout, np * len, rowsB, din, dout, part_w[l],
                            acc0 | (calls++ > 0));
-                    gemm_rows(ctx, s, (const void *)(dz2 + int64_t(i0 - lo) * n * dout), 0, np * len, dout, din, nof, p.W[l], 1, dout, nof,
-                              0, nof, Ap[i0], (part_l ? dz : dagg) + int64_t(i0 - lo) * n * din);
+                    gemm_rows(ctx, s, (const void *)(dz2 + int64_t(i0 - lo) * np * dout), 0, np * len, dout, din, nof, p.W[l], 1, dout, nof,
+                              0, nof, Ap[i0], (part_l ? dz : dagg) + int64_t(i0 - lo) * np * din);
                     return REINC_OK;
                 }));
-                if (!part_l) std::swap(dz, dagg);  // (else dz itself received the result, in full-height slices)
+                if (!part_l) std::swap(dz, dagg);  // (else dz itself received the result: dagg held its zero-padded copy)
                 continue;
             }
-            for (int32_t i = lo; i <= hi; ++i) Ap[i] = l == 1 ? s1[i] : ctx->local[i].S[l];
-            REINC_TRY(for_runs(lo, hi, nl, {Strip{Ap.data(), din}, Strip{has_q ? q.data() : nullptr, 1}},
+            for (int32_t i = lo; i <= hi; ++i) {
+                Ap[i] = l == 1 ? s1[i] : ctx->local[i].S[l];
+                ql[i] = q[i];
+            }
+            if (has_q && part_l && q_rows) {
+                ScaleTable tab{};
+                for (int32_t i = lo; i <= hi; ++i) {
+                    tab.src[i - lo] = q[i];
+                    ql[i] = q_rows + int64_t(i - lo) * nl;
+                }
+                gather_scales<<<dim3(unsigned((nl + 255) / 256), unsigned(nb)), 256, 0, s>>>(tab, nl, q_rows);
+            }
+            REINC_TRY(for_runs(lo, hi, nl, {Strip{Ap.data(), din}, Strip{has_q ? ql.data() : nullptr, 1}},
                                [&](int i0, int len) {
-                                   reduce(Ap[i0], din, q[i0], dz + int64_t(i0 - lo) * sl * dout, dout, nl * len, l == Lg ? rowsT : rowsB,
+                                   reduce(Ap[i0], din, ql[i0], dz + int64_t(i0 - lo) * nl * dout, dout, nl * len, l == Lg ? rowsT : rowsB,
                                           din, dout, part_w[l], acc0 | (calls++ > 0));
                                    return REINC_OK;
                                }));
@@ -736,7 +804,7 @@ int reinc_backward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *pa
                     // are zero
                     launch_fill_f32(dagg, int64_t(nb) * n * din, 0.0f, s);
                     for (int32_t i = lo; i <= hi; ++i)
-                        gemm_rows(ctx, s, (const void *)(dz + int64_t(i - lo) * sl * dout), 0, nl, dout, din, nof, p.W[l], 1, dout, nof, 0,
+                        gemm_rows(ctx, s, (const void *)(dz + int64_t(i - lo) * nl * dout), 0, nl, dout, din, nof, p.W[l], 1, dout, nof, 0,
                                   nof, nof, dagg + int64_t(i - lo) * n * din);
                 } else
                     gemm_rows(ctx, s, (const void *)dz, 0, n * nb, dout, din, nof, p.W[l], 1, dout, nof, 0, nof, nof, dagg);
@@ -745,7 +813,7 @@ int reinc_backward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *pa
                 for (int32_t i = lo; i <= hi; ++i) {
                     const Snapshot &sn = ctx->snaps[t0 + i];
                     batch.item[i - lo] = AggItem{sn.col_ptr, sn.row, dagg + int64_t(i - lo) * n * din, sn.q, sn.p,
-                                                 ctx->local[i].H[l - 1], nullptr, dz2 + int64_t(i - lo) * n * din, sn.long_cols,
+                                                 ctx->local[i].H[l - 1], nullptr, dz2 + int64_t(i - lo) * np * din, sn.long_cols,
                                                  sn.n_long_cols};
                     adjoint_item(batch.item[i - lo], sn);
                 }
@@ -772,6 +840,10 @@ int reinc_forward_window_integrated(reinc_ctx *ctx, int32_t t0, int32_t L, const
 {
     if (!ctx) return REINC_E_ARG;
     REINC_TRY(check_window(ctx, t0, L));
+    if (ctx->cache_rows > 0) {  // a batch context cached the rows its stacked layers need; this model reads every row
+        REINC_TRY(reinc_cache_clear(ctx));
+        ctx->cache_rows = 0;
+    }
     if (!params) return ctx->fail(REINC_E_ARG, "null parameter vector");
     if (target && !loss_out) return ctx->fail(REINC_E_ARG, "a target needs loss_out");
     const reinc_config &c = ctx->cfg;
@@ -941,7 +1013,7 @@ int reinc_cache_clear(reinc_ctx *ctx)
         }
     if (any) {
         // release the tail of the persistent region when nothing else was allocated after the first slot
-        const uint64_t slot = (uint64_t(ctx->cfg.num_nodes) * ctx->cfg.dims[0] * 4 + 255) & ~uint64_t(255);
+        const uint64_t slot = (uint64_t(ctx->cached_rows()) * ctx->cfg.dims[0] * 4 + 255) & ~uint64_t(255);
         uint64_t count = 0;
         for (float *p : ctx->gcache) count += p != nullptr;
         if (lowest + count * slot == ctx->bottom) ctx->bottom = lowest;

@@ -87,7 +87,7 @@ def say(capsys):
     return emit
 
 
-def test_bench_workload_c2_full(monkeypatch):
+def test_bench_workload_c2_full():
     """100k nodes, 1M edges, sym normalisation: deltas, both aggregation paths, and a 3-snapshot window."""
     import torch
 
@@ -122,7 +122,6 @@ def test_bench_workload_c2_full(monkeypatch):
     # against the whole-graph reference with the loss over the batch rows
     batch = np.random.default_rng(4).choice(wl.num_nodes, 2000, replace=False).astype(np.int32)
     print(f"[{wl.name}] node mini-batch of {batch.size}", flush=True)
-    monkeypatch.setenv("REINC_LAYER_ROWS", "0")  # layer 1 on the nodes within one hop only, whatever that saves
     child = ctx.batch_context(batch, 2 << 30)
     node_list = ctx.batch_node_list(child.n)
     rest = node_list[batch.size:]

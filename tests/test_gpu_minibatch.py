@@ -87,12 +87,18 @@ def test_batch_windows_match_the_whole_graph_reference(mode, rnn, layers):
 
 @pytest.mark.parametrize("mode,rnn,dims", [("sum", "gru", (16, 32, 32, 32)), ("mean", "lstm", (16, 32, 16)),
                                            ("sym", "gru", (16, 32, 16, 16)), ("mean", "gru", (16, 32, 32, 16))])
-def test_layers_below_the_last_run_on_their_hop_sets(mode, rnn, dims, monkeypatch):
+def test_layers_below_the_last_run_on_their_hop_sets(mode, rnn, dims):
     """Layer l of L is computed on the nodes within L - l hops of the batch only (a prefix of the numbering); three
-    layers, and layers that narrow their input (linear map before the aggregation) in every position.  (The library
-    takes the restriction only where it pays; the environment variable makes it unconditional.)"""
-    monkeypatch.setenv("REINC_LAYER_ROWS", "0")
+    layers, and layers that narrow their input (linear map before the aggregation) in every position."""
     _check_batch_windows(mode, rnn, len(dims) - 1, degree=1.5, dims=dims, prefixes=True)
+
+
+@pytest.mark.parametrize("mode,rnn,dims", [("mean", "lstm", (16, 32, 32)), ("sym", "gru", (16, 32, 16, 16))])
+def test_batch_windows_with_every_row_of_the_layers_below(mode, rnn, dims, monkeypatch):
+    """The same with the restriction of the layers below the last switched off: only the last layer and the cell work
+    on the batch rows."""
+    monkeypatch.setenv("REINC_LAYER_ROWS", "1e12")
+    _check_batch_windows(mode, rnn, len(dims) - 1, dims=dims)
 
 
 def test_batch_windows_with_three_timesteps_per_launch(monkeypatch):
@@ -266,4 +272,36 @@ def test_error_paths():
     with pytest.raises(reinc.ReincError, match="must be loaded"):
         empty.batch_plan(np.array([1], dtype=np.int32))
     empty.close()
+    ctx.close()
+
+
+def test_integrated_model_on_a_batch_context_reads_every_row():
+    """After a stacked window the cached layer-1 sums of a batch context hold the rows that layer 1 needs; the integrated
+    model aggregates the hidden state of every node of the sub-sequence, so its window drops them and computes whole
+    ones: h on every row against the reference model run on the extracted graphs (sum aggregation: no scales carried
+    over from the whole graph)."""
+    import dataclasses
+    import torch
+
+    wl = _workload("sum", "gru", 2)
+    seq, ctx = _parent(wl)
+    batch = np.random.default_rng(5).choice(wl.num_nodes, 50, replace=False).astype(np.int32)
+    node_list, sub, _ = minibatch.extract(seq.edges, batch, 2)
+    child = ctx.batch_context(batch, 1 << 28)
+    assert child.n == len(node_list)
+    child.build_deltas(-1)
+    L, H = 3, wl.hidden
+    flat = _dev(synth.make_params(wl, bias_scale=0.2))
+    child.forward_window(0, L, flat)  # fills the cache with short buffers
+    wli = dataclasses.replace(wl, dims=(wl.dims[0],))
+    flat_i = synth.make_params(wli, bias_scale=0.2)
+    h_last = torch.empty((child.n, H), device="cuda")
+    child.forward_window_integrated(0, L, _dev(flat_i), h_last=h_last)
+    torch.cuda.synchronize()
+    graphs = oracle.graphs_of(sub, child.n)
+    feats = [oracle_feats(seq, t)[node_list] for t in range(L)]
+    p = synth.split_params(wli, flat_i.astype(np.float64))
+    _, ref_h, _ = oracle.forward_window_integrated(graphs[:L], feats, p, wl.agg, wl.self_loop, wl.rnn, None)
+    assert_close(h_last.cpu().numpy(), ref_h, RTOL_FP32, "integrated h_last on a batch context")
+    child.close()
     ctx.close()
