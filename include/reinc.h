@@ -265,8 +265,9 @@ int reinc_cache_clear(reinc_ctx *ctx);
  * their arena space, so that the next reinc_build_deltas / window calls start cold.  Fails with REINC_E_STATE
  * if a snapshot was loaded after the first derived structure was built.  SYNC. */
 int reinc_reset_derived(reinc_ctx *ctx);
-/* Device pointer of the cached layer-1 sums S_t ([N, dims[0]] fp32) or NULL if not cached.  With a cache budget
- * the pointer is good until the next forward-window call (an aggregate the policy does not keep lives that long). */
+/* Device pointer of the cached layer-1 sums S_t ([N, dims[0]] fp32; in a context filled by reinc_batch_load only the
+ * first rows, see there) or NULL if not cached.  With a cache budget the pointer is good until the next forward-window
+ * call (an aggregate the policy does not keep lives that long). */
 int reinc_cache_peek(reinc_ctx *ctx, int32_t t, const float **S_out);
 
 /* ---- node mini-batches (Section 4.2, "Rethinking Mini-batch Training") -------------------------------------
