@@ -392,6 +392,7 @@ def forward_window_integrated(
     rnn: str,
     target: Optional[np.ndarray] = None,
     keep: bool = False,
+    loss_rows: Optional[np.ndarray] = None,
 ):
     """Forward over one window of the integrated model (Section 2.1: a GraphRNN replaces the matrix products of
     the recurrent gates by graph operations on x_t and h_{t-1}; Section 3.1, reuse across gates: the inputs are
@@ -399,7 +400,8 @@ def forward_window_integrated(
         ax = Agg(X_t; G_t),   ah = Agg(h_{t-1}; G_t),
         h_t = cell(x = ax, h = ah)  with the carry term taken from the un-aggregated state:
         GRU:  h_t = (1 - z) * n + z * h_{t-1};    LSTM:  c_t = f * c_{t-1} + i * g,  h_t = o * tanh(c_t).
-    params: W_i [d0, K*H], W_h [H, K*H], b_i, b_h.  Zero initial state; loss = mean((h_last - target)^2)."""
+    params: W_i [d0, K*H], W_h [H, K*H], b_i, b_h.  Zero initial state; loss = mean((h_last - target)^2), over the
+    rows `loss_rows` of h_last and target only if given (a node mini-batch, Section 4.2)."""
     p = _f64(params)
     n = graphs[0].n
     hd = p["W_h"].shape[0]
@@ -421,7 +423,8 @@ def forward_window_integrated(
         h, c = h_new, c_new
     loss = None
     if target is not None:
-        loss = float(np.mean((h - np.asarray(target, dtype=np.float64)) ** 2))
+        diff = h - np.asarray(target, dtype=np.float64)
+        loss = float(np.mean((diff if loss_rows is None else diff[np.asarray(loss_rows)]) ** 2))
     return loss, h, saved
 
 
@@ -434,13 +437,19 @@ def backward_window_integrated(
     self_loop: bool,
     rnn: str,
     target: np.ndarray,
+    loss_rows: Optional[np.ndarray] = None,
 ) -> Dict[str, np.ndarray]:
-    """Back-propagation through time for forward_window_integrated.  The gradient reaches h_{t-1} over two paths:
-    the carry term, and the aggregate ah through the adjoint of the aggregation."""
+    """Back-propagation through time for forward_window_integrated (the same `loss_rows`).  The gradient reaches
+    h_{t-1} over two paths: the carry term, and the aggregate ah through the adjoint of the aggregation."""
     p = _f64(params)
     grads = {k: np.zeros_like(v) for k, v in p.items()}
     tgt = np.asarray(target, dtype=np.float64)
-    dh = 2.0 * (h_last - tgt) / tgt.size
+    if loss_rows is None:
+        dh = 2.0 * (h_last - tgt) / tgt.size
+    else:
+        rows = np.asarray(loss_rows)
+        dh = np.zeros_like(h_last)
+        dh[rows] = 2.0 * (h_last[rows] - tgt[rows]) / (rows.size * tgt.shape[1])
     dc = np.zeros_like(dh)
     for g, sv in zip(reversed(list(graphs)), reversed(saved)):
         ax, ah, h_prev = sv["ax"], sv["ah"], sv["h_prev"]

@@ -167,3 +167,69 @@ def test_the_batch_loss_ignores_features_outside_its_computational_graph():
     for x in moved:
         x[list(inside)[-1]] += 10.0
     assert _run(wl, graphs, moved, flat, target, batch)[0] != base
+
+
+# ---- the integrated model (graph operations inside the gates): its receptive field grows by one hop per timestep,
+# so a window of L timesteps needs the batch's neighbourhood of L hops (one more under the symmetric normalisation)
+
+def _model_integrated(mode, rnn, n=300, T=3, degree=2.0, seed=4):
+    import dataclasses
+
+    wl = synth.Workload("mbi", n, degree, T, "uniform", 0.0, 0.2, 0.2, "fp32", mode, True, (4, 5), rnn, 3, T, seed)
+    wli = dataclasses.replace(wl, dims=(4,))  # parameter shapes: the cell only
+    seq = synth.make_sequence(wl)
+    feats = [oracle.features_at(seq.x0, seq.feat_rows, seq.feat_vals, t) for t in range(T)]
+    flat = synth.make_params(wli, bias_scale=0.3).astype(np.float64)
+    target = synth.make_target(wl).astype(np.float64)
+    return wl, wli, seq, feats, flat, target
+
+
+def _run_integrated(wl, wli, graphs, feats, flat, target, rows):
+    p = synth.split_params(wli, flat)
+    loss, h, saved = oracle.forward_window_integrated(graphs, feats, p, wl.agg, wl.self_loop, wl.rnn, target, keep=True,
+                                                      loss_rows=rows)
+    g = oracle.backward_window_integrated(graphs, saved, h, p, wl.agg, wl.self_loop, wl.rnn, target, loss_rows=rows)
+    return loss, h, np.concatenate([g[name].ravel() for name, _ in synth.param_shapes(wli)])
+
+
+@pytest.mark.parametrize("mode,rnn", [("sum", "gru"), ("mean", "lstm"), ("sym", "gru")])
+def test_integrated_model_on_extracted_graphs_needs_one_hop_per_timestep(mode, rnn):
+    wl, wli, seq, feats, flat, target = _model_integrated(mode, rnn)
+    n, T = wl.num_nodes, wl.num_snapshots
+    graphs = oracle.graphs_of(seq.edges, n)
+    batch = np.random.default_rng(2).choice(n, 4, replace=False)
+    full_loss, full_h, full_g = _run_integrated(wl, wli, graphs, feats, flat, target, batch)
+    hops = T + (1 if mode == "sym" else 0)
+    node_list, sub, _ = minibatch.extract(seq.edges, batch, hops)
+    reach = [len(f) for f in minibatch.closure(seq.edges, batch, hops)]
+    assert all(a < b for a, b in zip(reach, reach[1:])) and reach[-1] < n, reach  # every hop adds nodes, and not all
+    rows = np.arange(len(batch))
+    loss, h, g = _run_integrated(wl, wli, oracle.graphs_of(sub, len(node_list)), [x[node_list] for x in feats], flat,
+                                 target[node_list], rows)
+    assert loss == pytest.approx(full_loss, rel=1e-12)
+    np.testing.assert_allclose(h[:len(batch)], full_h[batch], rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(g, full_g, rtol=1e-10, atol=1e-14)
+    short_list, short_sub, _ = minibatch.extract(seq.edges, batch, hops - 1)
+    _, h_short, _ = _run_integrated(wl, wli, oracle.graphs_of(short_sub, len(short_list)), [x[short_list] for x in feats], flat,
+                                    target[short_list], rows)
+    assert not np.allclose(h_short[:len(batch)], full_h[batch], rtol=1e-9, atol=1e-12)
+
+
+def test_integrated_batch_losses_add_up_and_match_finite_differences():
+    wl, wli, seq, feats, flat, target = _model_integrated("mean", "gru", n=30, degree=2.0)
+    n = wl.num_nodes
+    graphs = oracle.graphs_of(seq.edges, n)
+    full_loss, _, full_g = _run_integrated(wl, wli, graphs, feats, flat, target, None)
+    perm = np.random.default_rng(1).permutation(n)
+    parts = [perm[:7], perm[7:19], perm[19:]]
+    runs = [_run_integrated(wl, wli, graphs, feats, flat, target, b) for b in parts]
+    assert sum(len(b) / n * r[0] for b, r in zip(parts, runs)) == pytest.approx(full_loss, rel=1e-12)
+    np.testing.assert_allclose(sum(len(b) / n * r[2] for b, r in zip(parts, runs)), full_g, rtol=1e-10, atol=1e-15)
+    batch, grad, eps = parts[0], runs[0][2], 1e-6
+    for i in np.random.default_rng(0).choice(flat.size, 20, replace=False):
+        fp, fm = flat.copy(), flat.copy()
+        fp[i] += eps
+        fm[i] -= eps
+        num = (_run_integrated(wl, wli, graphs, feats, fp, target, batch)[0] -
+               _run_integrated(wl, wli, graphs, feats, fm, target, batch)[0]) / (2 * eps)
+        assert abs(num - grad[i]) <= 1e-6 * max(1.0, abs(num)) + 1e-9, (i, num, grad[i])
