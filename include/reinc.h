@@ -278,7 +278,9 @@ int reinc_cache_peek(reinc_ctx *ctx, int32_t t, const float **S_out);
  * first reached in two hops, and so on: every F_k is the first |F_k| ids.  A stacked model of `hops`
  * aggregation layers evaluated on the sub-sequence gives on the batch rows exactly what it gives on the whole
  * graph.  (The degree scales of the mean and symmetric normalisations are carried over from the source graph, so
- * the degree of a node whose own in-edges are not kept -- a source only -- is still the right one.)
+ * the degree of a node whose own in-edges are not kept -- a source only -- is still the right one.)  The integrated
+ * model (Section 2.1) aggregates the hidden state inside the gates, so a batch row depends on one hop more per
+ * timestep: a window of L timesteps is exact on a sub-sequence planned with hops >= L.
  *
  * The sub-sequence goes into a second context, which is then used like any other: sliding its windows over the
  * whole sequence before the next batch is extracted (seq-first) lets its aggregate cache serve every window and

@@ -478,7 +478,7 @@ int reinc_forward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *par
     const int lstm = c.rnn_kind == REINC_RNN_LSTM;
     const float *nof = nullptr;
     // With loss rows set (a node mini-batch, numbered first) the last GCN layer and the recurrent cell are computed
-    // on those rows only (see place_top).
+    // on those rows only (see place_rows).
     const int64_t nt = ctx->top_rows();
     place_rows(ctx, s);
     // the degree scales of a batch of timesteps, next to each other, for a layer that works on its first rows only
@@ -610,7 +610,7 @@ int reinc_backward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *pa
     const Params p = split_params(c, params);
     Params gp = split_params(c, grads);
     const int64_t n = c.num_nodes;
-    const int64_t nt = ctx->top_rows();  // rows of the last GCN layer and of the recurrent cell (see place_top)
+    const int64_t nt = ctx->top_rows();  // rows of the last GCN layer and of the recurrent cell (see place_rows)
     if (ctx->local_top != nt) return ctx->fail(REINC_E_STATE, "the loss rows changed since the forward pass of this window");
     for (int l = 1; l <= c.num_gcn_layers; ++l)
         if (ctx->local_rows[l] != ctx->rows_of_layer(l))

@@ -305,3 +305,48 @@ def test_integrated_model_on_a_batch_context_reads_every_row():
     assert_close(h_last.cpu().numpy(), ref_h, RTOL_FP32, "integrated h_last on a batch context")
     child.close()
     ctx.close()
+
+
+@pytest.mark.parametrize("mode,rnn", [("sum", "gru"), ("mean", "lstm"), ("sym", "gru")])
+def test_integrated_model_on_a_batch_of_one_hop_per_timestep(mode, rnn):
+    """The integrated model aggregates the hidden state inside the gates (Section 2.1), so what a batch row depends on
+    grows by one hop per timestep: a sub-sequence extracted with as many hops as the window is long gives the batch rows,
+    the batch loss and the gradients of the whole graph (Section 4.2: the loss of a batch is taken over its nodes)."""
+    import dataclasses
+    import torch
+
+    wl = _workload(mode, rnn, 1, n=6000, T=5, degree=2.0)
+    wli = dataclasses.replace(wl, dims=(wl.dims[0],))
+    seq, ctx = _parent(wl)
+    n, T, L, H = wl.num_nodes, wl.num_snapshots, 3, wl.hidden
+    batch = np.random.default_rng(3).choice(n, 24, replace=False).astype(np.int32)
+    child = ctx.batch_context(batch, 1 << 28, hops=L)
+    node_list = ctx.batch_node_list(child.n)
+    reach = [len(f) for f in minibatch.closure(seq.edges, batch, L)]
+    assert all(a < b for a, b in zip(reach, reach[1:])) and reach[-1] == child.n < n, reach
+    child.build_deltas(-1)
+    flat = synth.make_params(wli, bias_scale=0.2)
+    target = synth.make_target(wl)
+    params, tgt = _dev(flat), _dev(target[node_list])
+    loss = torch.zeros(1, device="cuda")
+    h_last = torch.empty((child.n, H), device="cuda")
+    grads = torch.empty_like(params)
+    graphs = oracle_graphs(seq)
+    p = synth.split_params(wli, flat.astype(np.float64))
+    for t0 in (0, T - L):
+        print(f"[{wl.name} {mode} {rnn}] integrated batch window t0={t0}", flush=True)
+        child.forward_window_integrated(t0, L, params, tgt, loss, h_last)
+        child.backward_window_integrated(t0, L, params, tgt, grads)
+        torch.cuda.synchronize()
+        g = graphs[t0:t0 + L]
+        feats = [oracle_feats(seq, t) for t in range(t0, t0 + L)]
+        ref_loss, ref_h, saved = oracle.forward_window_integrated(g, feats, p, wl.agg, wl.self_loop, wl.rnn, target, keep=True,
+                                                                  loss_rows=batch)
+        assert_close(h_last.cpu().numpy()[:len(batch)], ref_h[batch], RTOL_FP32, "integrated h_last on the batch rows")
+        assert abs(loss.item() - ref_loss) <= RTOL_FP32 * abs(ref_loss), (loss.item(), ref_loss)
+        ref_g = oracle.backward_window_integrated(g, saved, ref_h, p, wl.agg, wl.self_loop, wl.rnn, target, loss_rows=batch)
+        got = synth.split_params(wli, grads.cpu().numpy())
+        for name, _ in synth.param_shapes(wli):
+            assert_close(got[name], ref_g[name], GRAD_RTOL_FP32, f"grad {name} (t0={t0})")
+    child.close()
+    ctx.close()
