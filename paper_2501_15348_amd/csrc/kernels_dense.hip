@@ -344,9 +344,11 @@ __device__ inline void split8(const float *v, u32x4 &hi, u32x4 &mid, u32x4 &lo)
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         const float a0 = v[2 * j], a1 = v[2 * j + 1];
-        const uint32_t h = pack_bf16(a0, a1);
+        uint32_t h = pack_bf16(a0, a1);
+        asm volatile("" : "+v"(h));  // both halves come out of this one conversion (left alone, the low half gets a second one)
         const float r0 = a0 - __uint_as_float(h << 16), r1 = a1 - __uint_as_float(h & 0xFFFF0000u);
-        const uint32_t m = pack_bf16(r0, r1);
+        uint32_t m = pack_bf16(r0, r1);
+        asm volatile("" : "+v"(m));
         const float q0 = r0 - __uint_as_float(m << 16), q1 = r1 - __uint_as_float(m & 0xFFFF0000u);
         hi[j] = h;
         mid[j] = m;
@@ -552,6 +554,48 @@ __global__ void __launch_bounds__(64 * WAVES) gemm_rows_resident_kernel(GemmArgs
     auto epilogue = [&]() __attribute__((always_inline)) {  // rows rbase + 8*q + e (q, e in 0..3) of the finished tile, four rows at a time
         const int64_t rbase = int64_t(tile) * 32 + 4 * kk;
         const bool full = int64_t(tile) * 32 + 32 <= g.n;
+        if (full) {
+            // a whole tile: an element's address is a wave-uniform part (tile and row inside it: scalar arithmetic) plus
+            // a lane part that never changes (row half and column), so no vector instruction goes into addressing
+            const uint32_t row_bytes = uint32_t(g.M) * 4u;
+            const int64_t tile_off = int64_t(tile) * 32 * row_bytes;
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                const int c = wcol0 + 32 * t + i;
+                if (c < g.M) {
+                    const uint32_t lane_off = uint32_t(4 * kk) * row_bytes + uint32_t(c) * 4u;
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        float v[4];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            v[e] = acc[t][4 * q + e] + bias[t];
+                            if (g.relu) v[e] = fmaxf(v[e], 0.0f);
+                        }
+                        if (g.add) {
+#pragma unroll
+                            for (int e = 0; e < 4; ++e)
+                                v[e] += *reinterpret_cast<const float *>(reinterpret_cast<const char *>(g.add) + tile_off +
+                                                                         uint32_t(8 * q + e) * row_bytes + lane_off);
+                        }
+                        if (g.mask) {
+#pragma unroll
+                            for (int e = 0; e < 4; ++e)
+                                if (!(*reinterpret_cast<const float *>(reinterpret_cast<const char *>(g.mask) + tile_off +
+                                                                       uint32_t(8 * q + e) * row_bytes + lane_off) > 0.0f))
+                                    v[e] = 0.0f;
+                        }
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            *reinterpret_cast<float *>(reinterpret_cast<char *>(g.out) + tile_off + uint32_t(8 * q + e) * row_bytes +
+                                                       lane_off) = v[e];
+                    }
+                }
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[t][r] = 0.0f;
+            }
+            return;
+        }
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
             const int c = wcol0 + 32 * t + i;
