@@ -370,6 +370,7 @@ def extras(ctx, wl, seq, infos, params, target, step, step_s, full):
                            "edges_per_s": round(sum(i["num_edges_prev"] + i["num_edges_cur"] for i in infos) / dt, 1),
                            "algorithmic_GBps": round(db / dt / 1e9, 1), "hbm_frac": round(db / dt / 1e9 / HBM_PEAK_GBS, 4),
                            "note": "wall time of reinc_build_deltas for all steps (every kernel and both host waits)"}
+    res["gcn_transform"], res["rnn_step"] = dense_rows(ctx, wl, timed)
     # warm epoch: every layer-1 sum comes from the global cache
     L = min(wl.window, T)
     loss = torch.zeros(1, device="cuda")
@@ -447,6 +448,57 @@ def extras(ctx, wl, seq, infos, params, target, step, step_s, full):
     res["node_minibatch"] += minibatch_rows(ctx2, wl2, seq2, params, target, L, "uniform degree 3, mean")
     ctx2.close()
     return res
+
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 matrix-core peak of MI355X
+MFMA_F32_PEAK_TFLOPS = 157.3
+
+
+def dense_rows(ctx, wl, timed):
+    """K5 per GCN layer and K6 at the workload's row count, one timestep per call (inside a window the driver hands
+    them up to MAX_BATCH timesteps as one taller matrix): algorithmic bytes against the HBM peak, and the matrix-core
+    rate -- fp32-equivalent flops, and the six bf16 products per fp32 product that the three-term split really
+    issues, against the bf16 peak.  With REINC_DENSE=fp32 the products run on the fp32 matrix instructions instead."""
+    import torch
+
+    n = wl.num_nodes
+    split = os.environ.get("REINC_DENSE") != "fp32"
+    g = torch.Generator(device="cuda").manual_seed(3)
+
+    def row(ms, nbytes, flops):
+        r = {"us": round(ms * 1e3, 1), "algorithmic_GBps": round(nbytes / ms / 1e6, 1),
+             "hbm_frac": round(nbytes / ms / 1e6 / HBM_PEAK_GBS, 4), "f32_equivalent_TFLOPs": round(flops / ms / 1e9, 1)}
+        if split:
+            r["bf16_products_TFLOPs"] = round(6 * flops / ms / 1e9, 1)
+            r["mfma_frac"] = round(6 * flops / ms / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4)
+        else:
+            r["mfma_frac"] = round(flops / ms / 1e9 / MFMA_F32_PEAK_TFLOPS, 4)
+        return r
+
+    layers = []
+    for l in range(1, len(wl.dims)):
+        k, m = wl.dims[l - 1], wl.dims[l]
+        a = torch.randn(n, k, device="cuda", generator=g)
+        w = torch.randn(k, m, device="cuda", generator=g) / k ** 0.5
+        b = torch.zeros(m, device="cuda")
+        out = torch.empty(n, m, device="cuda")
+        ms = timed(lambda: ctx.gcn_transform(a, w, b, None, True, out))
+        layers.append({"rows": n, "d_in": k, "d_out": m, **row(ms, n * (k + m) * 4 + k * m * 4, 2.0 * n * k * m)})
+        del a, out
+    d, h = wl.dims[-1], wl.hidden
+    kg = 4 if wl.rnn == "lstm" else 3
+    x = torch.randn(n, d, device="cuda", generator=g)
+    hp = 0.5 * torch.randn(n, h, device="cuda", generator=g)
+    cp = 0.5 * torch.randn(n, h, device="cuda", generator=g) if wl.rnn == "lstm" else None
+    wi = torch.randn(d, kg * h, device="cuda", generator=g) / d ** 0.5
+    wh = torch.randn(h, kg * h, device="cuda", generator=g) / h ** 0.5
+    bi, bh = torch.zeros(kg * h, device="cuda"), torch.zeros(kg * h, device="cuda")
+    saved = torch.empty(n, 4 * h, device="cuda")
+    ms = timed(lambda: ctx.rnn_step(wl.rnn, x, hp, cp, wi, wh, bi, bh, saved))
+    # x, h (and c) read; h (and c) and the four saved gate rows written
+    nbytes = n * 4 * (d + h * (2 if cp is not None else 1) * 2 + 4 * h)
+    cell = {"rows": n, "d_in": d, "hidden": h, "kind": wl.rnn, **row(ms, nbytes, 2.0 * n * (d + h) * kg * h)}
+    return layers, cell
 
 
 def max_rows(ctx, wl, seq, infos, timed):
