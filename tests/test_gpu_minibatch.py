@@ -292,7 +292,11 @@ def test_integrated_model_on_a_batch_context_reads_every_row():
     child.build_deltas(-1)
     L, H = 3, wl.hidden
     flat = _dev(synth.make_params(wl, bias_scale=0.2))
-    child.forward_window(0, L, flat)  # fills the cache with short buffers
+    nb = len(batch)
+    h_stacked = torch.empty((child.n, H), device="cuda")
+    child.forward_window(0, L, flat, h_last=h_stacked)  # fills the cache with short buffers
+    torch.cuda.synchronize()
+    first = h_stacked[:nb].clone()
     wli = dataclasses.replace(wl, dims=(wl.dims[0],))
     flat_i = synth.make_params(wli, bias_scale=0.2)
     h_last = torch.empty((child.n, H), device="cuda")
@@ -303,6 +307,10 @@ def test_integrated_model_on_a_batch_context_reads_every_row():
     p = synth.split_params(wli, flat_i.astype(np.float64))
     _, ref_h, _ = oracle.forward_window_integrated(graphs[:L], feats, p, wl.agg, wl.self_loop, wl.rnn, None)
     assert_close(h_last.cpu().numpy(), ref_h, RTOL_FP32, "integrated h_last on a batch context")
+    # and the stacked model afterwards finds whole cached sums, of which it reads its rows: the same batch rows as before
+    child.forward_window(0, L, flat, h_last=h_stacked)
+    torch.cuda.synchronize()
+    assert_close(h_stacked[:nb].cpu().numpy(), first.cpu().numpy(), 1e-6, "stacked h_last after the integrated window")
     child.close()
     ctx.close()
 
