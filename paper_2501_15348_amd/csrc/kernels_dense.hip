@@ -1043,35 +1043,49 @@ __global__ void __launch_bounds__(64 * WAVES) rnn_fused_resident_kernel(RnnArgs 
                 other0[r] = __shfl_xor(low ? b0 : a0, 16);
                 other1[r] = __shfl_xor(low ? b1 : a1, 16);
             }
-            if (j < H) {
+            // the cell of row r (register index) from the exchanged gates; at(base, w) is this lane's element of its row
+            // in a matrix of w * H columns
+            auto packed_cell = [&](int r, float prev, auto at) __attribute__((always_inline)) {
+                const float gi = sigmoidf_((low ? mine0[r] : other0[r]) + bsum[0]);
+                const float gf = sigmoidf_((low ? other0[r] : mine0[r]) + bsum[1]);
+                const float gg = tanhf_((low ? mine1[r] : other1[r]) + bsum[2]);
+                const float go = sigmoidf_((low ? other1[r] : mine1[r]) + bsum[LSTM ? 3 : 0]);
+                const float cn = gf * prev + gi * gg;
+                *at(g.c_out, 1) = cn;
+                *at(g.h_out, 1) = go * tanhf_(cn);
+                if (g.saved) {
+                    float *sv = at(g.saved, 4);
+                    sv[0] = gi;
+                    sv[H] = gf;
+                    sv[2 * H] = gg;
+                    sv[3 * H] = go;
+                }
+            };
+            if (j < H && full) {
+                // a whole tile: an element's address is a wave-uniform part (tile, row inside it) plus a lane part that
+                // never changes (row half, lane half, unit), so addressing costs scalar arithmetic only
+                const uint32_t hrow = uint32_t(H) * 4u;
+                const int64_t tile_h = int64_t(tile) * 32 * hrow;
+                const uint32_t lane_rows = uint32_t(4 * kk + (low ? 0 : 16));
+                const uint32_t lane_h = lane_rows * hrow + uint32_t(j) * 4u, lane_s = lane_rows * 4u * hrow + uint32_t(j) * 4u;
+#pragma unroll
+                for (int q = 0; q < 2; ++q)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const int64_t oh = tile_h + uint32_t(8 * q + e) * hrow;
+                        packed_cell(4 * q + e, state[4 * q + e], [&](float *base, int w) __attribute__((always_inline)) {
+                            return reinterpret_cast<float *>(reinterpret_cast<char *>(base) + w * oh + (w == 4 ? lane_s : lane_h));
+                        });
+                    }
+            } else if (j < H) {
 #pragma unroll
                 for (int q = 0; q < 2; ++q) {
-                    int64_t rr[4];
-                    float prev[4];
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
-                        rr[e] = min(rbase + 8 * (q + (low ? 0 : 2)) + e, g.n - 1);
-                        prev[e] = state[4 * q + e];  // (zero without a previous state)
-                    }
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        if (!(full || rbase + 8 * (q + (low ? 0 : 2)) + e < g.n)) continue;
-                        const int r = 4 * q + e;
-                        const int64_t o = rr[e] * H + j;
-                        const float gi = sigmoidf_((low ? mine0[r] : other0[r]) + bsum[0]);
-                        const float gf = sigmoidf_((low ? other0[r] : mine0[r]) + bsum[1]);
-                        const float gg = tanhf_((low ? mine1[r] : other1[r]) + bsum[2]);
-                        const float go = sigmoidf_((low ? other1[r] : mine1[r]) + bsum[LSTM ? 3 : 0]);
-                        const float cn = gf * prev[e] + gi * gg;
-                        g.c_out[o] = cn;
-                        g.h_out[o] = go * tanhf_(cn);
-                        if (g.saved) {
-                            float *sv = g.saved + rr[e] * 4 * H + j;
-                            sv[0] = gi;
-                            sv[H] = gf;
-                            sv[2 * H] = gg;
-                            sv[3 * H] = go;
-                        }
+                        if (!(rbase + 8 * (q + (low ? 0 : 2)) + e < g.n)) continue;
+                        const int64_t row = rbase + 8 * (q + (low ? 0 : 2)) + e;
+                        packed_cell(4 * q + e, state[4 * q + e],
+                                    [&](float *base, int w) __attribute__((always_inline)) { return base + row * w * H + j; });
                     }
                 }
             }
@@ -1081,7 +1095,61 @@ __global__ void __launch_bounds__(64 * WAVES) rnn_fused_resident_kernel(RnnArgs 
                 for (int r = 0; r < 16; ++r) acc[t][r] = 0.0f;
             return;
         }
-        if (j < H) {
+        // the cell of row r (register index); at(base, w) is this lane's element of its row in a matrix of w * H columns
+        auto cell = [&](int r, float prev, auto at) __attribute__((always_inline)) {
+            if (LSTM) {
+                const float gi = sigmoidf_(acc[0][r] + bsum[0]);
+                const float gf = sigmoidf_(acc[1][r] + bsum[1]);
+                const float gg = tanhf_(acc[2][r] + bsum[2]);
+                const float go = sigmoidf_(acc[3][r] + bsum[LSTM ? 3 : 0]);
+                const float cn = gf * prev + gi * gg;
+                *at(g.c_out, 1) = cn;
+                *at(g.h_out, 1) = go * tanhf_(cn);
+                if (g.saved) {
+                    float *sv = at(g.saved, 4);
+                    sv[0] = gi;
+                    sv[H] = gf;
+                    sv[2 * H] = gg;
+                    sv[3 * H] = go;
+                }
+            } else {
+                const float gr = sigmoidf_(acc[0][r] + bsum[0]);
+                const float gz = sigmoidf_(acc[1][r] + bsum[1]);
+                const float ghn = acc[2][r] + bhn;
+                const float gn = tanhf_(acc[3][r] + bsum[2] + gr * ghn);
+                *at(g.h_out, 1) = (1.0f - gz) * gn + gz * prev;
+                if (g.saved) {
+                    float *sv = at(g.saved, 4);
+                    sv[0] = gr;
+                    sv[H] = gz;
+                    sv[2 * H] = gn;
+                    sv[3 * H] = ghn;
+                }
+            }
+        };
+        if (SPLIT && j < H && full) {
+            // a whole tile: addresses from a wave-uniform part (tile, row inside it) and a constant lane part
+            // (the 12-wave variants on the fp32 instructions have no registers to spare for it)
+            const uint32_t hrow = uint32_t(H) * 4u;
+            const int64_t tile_h = int64_t(tile) * 32 * hrow;
+            const uint32_t lane_h = uint32_t(4 * kk) * hrow + uint32_t(j) * 4u, lane_s = uint32_t(16 * kk) * hrow + uint32_t(j) * 4u;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                float prev[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    prev[e] = pstate ? *reinterpret_cast<const float *>(reinterpret_cast<const char *>(pstate) + tile_h +
+                                                                        uint32_t(8 * q + e) * hrow + lane_h)
+                                     : 0.0f;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int64_t oh = tile_h + uint32_t(8 * q + e) * hrow;
+                    cell(4 * q + e, prev[e], [&](float *base, int w) __attribute__((always_inline)) {
+                        return reinterpret_cast<float *>(reinterpret_cast<char *>(base) + w * oh + (w == 4 ? lane_s : lane_h));
+                    });
+                }
+            }
+        } else if (j < H) {
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 int64_t rr[4];
@@ -1094,37 +1162,9 @@ __global__ void __launch_bounds__(64 * WAVES) rnn_fused_resident_kernel(RnnArgs 
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     if (!(full || rbase + 8 * q + e < g.n)) continue;
-                    const int r = 4 * q + e;
                     const int64_t o = rr[e] * H + j;
-                    if (LSTM) {
-                        const float gi = sigmoidf_(acc[0][r] + bsum[0]);
-                        const float gf = sigmoidf_(acc[1][r] + bsum[1]);
-                        const float gg = tanhf_(acc[2][r] + bsum[2]);
-                        const float go = sigmoidf_(acc[3][r] + bsum[LSTM ? 3 : 0]);
-                        const float cn = gf * prev[e] + gi * gg;
-                        g.c_out[o] = cn;
-                        g.h_out[o] = go * tanhf_(cn);
-                        if (g.saved) {
-                            float *sv = g.saved + rr[e] * 4 * H + j;
-                            sv[0] = gi;
-                            sv[H] = gf;
-                            sv[2 * H] = gg;
-                            sv[3 * H] = go;
-                        }
-                    } else {
-                        const float gr = sigmoidf_(acc[0][r] + bsum[0]);
-                        const float gz = sigmoidf_(acc[1][r] + bsum[1]);
-                        const float ghn = acc[2][r] + bhn;
-                        const float gn = tanhf_(acc[3][r] + bsum[2] + gr * ghn);
-                        g.h_out[o] = (1.0f - gz) * gn + gz * prev[e];
-                        if (g.saved) {
-                            float *sv = g.saved + rr[e] * 4 * H + j;
-                            sv[0] = gr;
-                            sv[H] = gz;
-                            sv[2 * H] = gn;
-                            sv[3 * H] = ghn;
-                        }
-                    }
+                    cell(4 * q + e, prev[e],
+                         [&](float *base, int w) __attribute__((always_inline)) { return w == 1 ? base + o : base + rr[e] * 4 * H + j; });
                 }
             }
         }
