@@ -1133,18 +1133,21 @@ __global__ void __launch_bounds__(64 * WAVES) rnn_fused_resident_kernel(RnnArgs 
             const uint32_t hrow = uint32_t(H) * 4u;
             const int64_t tile_h = int64_t(tile) * 32 * hrow;
             const uint32_t lane_h = uint32_t(4 * kk) * hrow + uint32_t(j) * 4u, lane_s = uint32_t(16 * kk) * hrow + uint32_t(j) * 4u;
+            // the tile's sixteen state values are requested together: one wait per tile instead of one per four rows
+            float prev[16];
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                float prev[4];
+            for (int q = 0; q < 4; ++q)
 #pragma unroll
                 for (int e = 0; e < 4; ++e)
-                    prev[e] = pstate ? *reinterpret_cast<const float *>(reinterpret_cast<const char *>(pstate) + tile_h +
-                                                                        uint32_t(8 * q + e) * hrow + lane_h)
-                                     : 0.0f;
+                    prev[4 * q + e] = pstate ? *reinterpret_cast<const float *>(reinterpret_cast<const char *>(pstate) + tile_h +
+                                                                                uint32_t(8 * q + e) * hrow + lane_h)
+                                             : 0.0f;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const int64_t oh = tile_h + uint32_t(8 * q + e) * hrow;
-                    cell(4 * q + e, prev[e], [&](float *base, int w) __attribute__((always_inline)) {
+                    cell(4 * q + e, prev[4 * q + e], [&](float *base, int w) __attribute__((always_inline)) {
                         return reinterpret_cast<float *>(reinterpret_cast<char *>(base) + w * oh + (w == 4 ? lane_s : lane_h));
                     });
                 }
