@@ -280,7 +280,10 @@ int reinc_cache_peek(reinc_ctx *ctx, int32_t t, const float **S_out);
  * graph.  (The degree scales of the mean and symmetric normalisations are carried over from the source graph, so
  * the degree of a node whose own in-edges are not kept -- a source only -- is still the right one.)  The integrated
  * model (Section 2.1) aggregates the hidden state inside the gates, so a batch row depends on one hop more per
- * timestep: a window of L timesteps is exact on a sub-sequence planned with hops >= L.
+ * timestep: a window of L timesteps is exact on a sub-sequence planned with hops >= L.  On a batch context its window
+ * calls compute timestep i of L on the nodes within L - 1 - i hops of the batch (the last one on the batch rows),
+ * reinc_forward_window_integrated writes rows [0, n_batch) of h_last only, and the cached input sums hold the rows of
+ * the first timestep (sums cached with fewer rows, by the stacked model or a shorter window, are recomputed).
  *
  * The sub-sequence goes into a second context, which is then used like any other: sliding its windows over the
  * whole sequence before the next batch is extracted (seq-first) lets its aggregate cache serve every window and
@@ -304,8 +307,9 @@ int reinc_cache_peek(reinc_ctx *ctx, int32_t t, const float **S_out);
  *   (both stay [N, H]); the gradients are those of that loss.  The stacked model then computes its last GCN layer
  *   and the recurrent cell on those rows only (nothing else depends on the others), and reinc_forward_window writes
  *   rows [0, rows) of h_last only.  rows = 0 or N: every row (the default).  A backward call needs a forward call
- *   made with the same rows (REINC_E_STATE otherwise).  Forgets what reinc_batch_load said about the layers below
- *   (and with it the cached sums of a batch context, which hold some rows only). */
+ *   made with the same rows (REINC_E_STATE otherwise).  Forgets what reinc_batch_load said about the layers below and
+ *   about the timesteps of the integrated model (and with it the cached sums of a batch context, which hold some
+ *   rows only). */
 int reinc_batch_plan(reinc_ctx *ctx, const int32_t *nodes, int64_t n_batch, int32_t hops, int64_t *n_nodes_out,
                      int64_t *n_inner_out);
 int reinc_batch_node_list(reinc_ctx *ctx, int32_t *out);

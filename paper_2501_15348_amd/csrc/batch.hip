@@ -261,6 +261,7 @@ int reinc_set_loss_rows(reinc_ctx *ctx, int64_t rows)
     if (rows < 0 || rows > ctx->N()) return ctx->fail(REINC_E_ARG, "loss rows %lld outside [0, %lld]", (long long)rows, (long long)ctx->N());
     ctx->loss_rows = rows == ctx->N() ? 0 : rows;
     for (int64_t &r : ctx->layer_rows) r = 0;  // (only reinc_batch_load knows which rows the layers below need)
+    ctx->hop_rows.clear();
     if (ctx->cache_rows > 0) {                 // cached sums that hold some of the rows only are of no use any more
         const int rc = reinc_cache_clear(ctx);
         if (rc != REINC_OK) return rc;
@@ -488,6 +489,10 @@ int reinc_batch_load(reinc_ctx *ctx, reinc_ctx *child)
         if (saved >= threshold) child->layer_rows[l] = ctx->batch_reach[k];
     }
     child->cache_rows = child->rows_of_layer(1) < nu ? child->rows_of_layer(1) : 0;  // (its cache is still empty)
+    child->hop_rows.clear();
+    // (the integrated model's rows per timestep, under the same threshold: its last timestep leaves out all but the batch)
+    if (child->loss_rows > 0 && double(nu - ctx->batch_size) * (b.dims[0] + b.rnn_hidden) * 4.0 >= threshold)
+        child->hop_rows = ctx->batch_reach;
     child->local_valid = false;
     return REINC_OK;
 }

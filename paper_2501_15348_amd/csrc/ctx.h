@@ -155,6 +155,17 @@ struct reinc_ctx {
     int64_t cache_rows = 0;
     int64_t cached_rows() const { return cache_rows > 0 ? cache_rows : cfg.num_nodes; }
     int64_t local_rows[REINC_MAX_GCN_LAYERS + 1] = {};  // rows_of_layer(l) the local cache is placed for (see place_rows)
+    // A batch context: hop_rows[k] = nodes within k hops of the batch (its first ids), set by reinc_batch_load; empty =
+    // unknown.  The integrated model, whose hidden state is aggregated once per timestep, needs timestep i of an
+    // L-step window on the nodes within L - 1 - i hops only.
+    std::vector<int64_t> hop_rows;
+    int64_t integrated_rows(int32_t L, int32_t i) const
+    {
+        const int64_t k = int64_t(L) - 1 - i;
+        if (loss_rows <= 0 || hop_rows.empty() || k >= int64_t(hop_rows.size())) return cfg.num_nodes;
+        return hop_rows[size_t(k)];
+    }
+    std::vector<int64_t> step_rows;  // rows the last integrated forward pass computed per timestep (for its backward pass)
     // node mini-batch plan made on this context (reinc_batch_plan): hop level and new id per node, the node list
     int32_t *batch_level = nullptr, *batch_new_id = nullptr, *batch_nodes = nullptr;
     int64_t batch_size = 0, batch_total = 0;  // batch nodes, nodes of the sub-sequence (0: no plan)

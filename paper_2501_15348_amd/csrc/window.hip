@@ -469,6 +469,11 @@ int reinc_forward_window(reinc_ctx *ctx, int32_t t0, int32_t L, const float *par
     hipStream_t s = as_stream(stream);
     REINC_HIP(ctx, hipSetDevice(c.device));
     ctx->local_valid = false;
+    if (ctx->cache_rows > 0 && ctx->cache_rows < ctx->rows_of_layer(1)) {
+        // (a batch context whose cached sums were made for a short window of the integrated model: too few rows)
+        REINC_TRY(reinc_cache_clear(ctx));
+        ctx->cache_rows = ctx->rows_of_layer(1) < c.num_nodes ? ctx->rows_of_layer(1) : 0;
+    }
     REINC_TRY(begin_budgeted_window(ctx, t0, L));
     REINC_TRY(ensure_local(ctx, L, s));
     ctx->scratch_reset();
@@ -840,9 +845,13 @@ int reinc_forward_window_integrated(reinc_ctx *ctx, int32_t t0, int32_t L, const
 {
     if (!ctx) return REINC_E_ARG;
     REINC_TRY(check_window(ctx, t0, L));
-    if (ctx->cache_rows > 0) {  // a batch context cached the rows its stacked layers need; this model reads every row
+    // A batch context computes timestep i on the nodes within L - 1 - i hops of the batch (nothing else reaches the
+    // batch rows by the window's end); its cached input sums must hold the rows of the first timestep.  Sums cached with
+    // fewer rows (by the stacked model, or by a shorter window) are dropped.
+    const int64_t need_rows = ctx->integrated_rows(L, 0);
+    if (ctx->cache_rows > 0 && ctx->cache_rows < need_rows) {
         REINC_TRY(reinc_cache_clear(ctx));
-        ctx->cache_rows = 0;
+        ctx->cache_rows = need_rows < ctx->cfg.num_nodes ? need_rows : 0;
     }
     if (!params) return ctx->fail(REINC_E_ARG, "null parameter vector");
     if (target && !loss_out) return ctx->fail(REINC_E_ARG, "a target needs loss_out");
@@ -861,22 +870,33 @@ int reinc_forward_window_integrated(reinc_ctx *ctx, int32_t t0, int32_t L, const
     const int64_t KH = int64_t(lstm ? 4 : 3) * H;
     const float *W_i = params, *W_h = W_i + int64_t(c.dims[0]) * KH, *b_i = W_h + int64_t(H) * KH, *b_h = b_i + KH;
     const float *nof = nullptr;
+    ctx->step_rows.assign(size_t(L), n);
     for (int32_t i = 0; i < L; ++i) {
         const int32_t t = t0 + i;
         REINC_TRY(ensure_layer1(ctx, t, s));  // Agg(X_t): from the global cache, by Eq. 2, or from scratch
         const Snapshot &sn = ctx->snaps[t];
         LocalStep &st = ctx->local[i];
         const LocalStep *pv = i ? &ctx->local[i - 1] : nullptr;
-        if (pv)  // Agg(h_{t-1}) over snapshot t; at the first timestep the state, and with it the aggregate, is zero
-            aggregate_full(ctx, sn.row_ptr, sn.col, sn.long_rows, sn.n_long_rows, pv->h, 0, H, c.self_loop, sn.p, sn.q, nullptr,
-                           st.S[1], s, sn.row_order);
-        rnn_fused(ctx, s, lstm, (const float *)ctx->gcache[t], (const float *)sn.q, n, c.dims[0], H,
+        const int64_t ni = ctx->integrated_rows(L, i);  // (the sources of these rows lie among the rows of timestep i - 1)
+        ctx->step_rows[size_t(i)] = ni;
+        if (pv) {  // Agg(h_{t-1}) over snapshot t; at the first timestep the state, and with it the aggregate, is zero
+            AggBatch batch;
+            batch.count = 1;
+            batch.item[0] = AggItem{sn.row_ptr, sn.col, pv->h, sn.p, sn.q, nullptr, nullptr, st.S[1], sn.long_rows, sn.n_long_rows};
+            if (ni < n)
+                batch.item[0].row_limit = ni;
+            else
+                batch.item[0].order = sn.row_order;
+            aggregate_full_batch(ctx, batch, 0, H, c.self_loop, s, ni);
+        }
+        rnn_fused(ctx, s, lstm, (const float *)ctx->gcache[t], (const float *)sn.q, ni, c.dims[0], H,
                   pv ? (const float *)st.S[1] : nof, pv ? (const float *)pv->h : nof, pv ? (const float *)pv->c : nof, W_i, W_h,
                   b_i, b_h, st.h, st.c, st.saved);
     }
     const LocalStep &last = ctx->local[L - 1];
+    const int64_t n_last = ctx->step_rows[size_t(L - 1)];  // (a batch context: the loss rows)
     if (target) launch_mse(last.h, target, ctx->counted_rows() * H, ctx->loss_partial, loss_out, s);
-    if (h_last) REINC_HIP(ctx, hipMemcpyAsync(h_last, last.h, uint64_t(n) * H * 4, hipMemcpyDeviceToDevice, s));
+    if (h_last) REINC_HIP(ctx, hipMemcpyAsync(h_last, last.h, uint64_t(n_last) * H * 4, hipMemcpyDeviceToDevice, s));
     REINC_HIP(ctx, hipGetLastError());
     ctx->local_valid = true;
     ctx->local_t0 = t0;
@@ -931,6 +951,20 @@ int reinc_backward_window_integrated(reinc_ctx *ctx, int32_t t0, int32_t L, cons
     }
     launch_fill_f32(grads, count, 0.0f, s);
     launch_mse_grad(ctx->local[L - 1].h, target, ctx->counted_rows() * H, n * H, dh, s);
+    // A batch context computed timestep i on its first step_rows[i] rows (non-increasing in i).  Going back in time the
+    // row count only grows, so whatever a step leaves beyond its rows -- the gradient w.r.t. the aggregated state, the
+    // carried state gradients -- is still the zero it starts as: what reads every row finds zeros there.
+    const std::vector<int64_t> &rows_of = ctx->step_rows;
+    if (int32_t(rows_of.size()) != L) return ctx->fail(REINC_E_STATE, "the forward pass left no row counts for this window");
+    const bool part = rows_of[size_t(L - 1)] < n;
+    if (part) {
+        launch_fill_f32(dah, n * H, 0.0f, s);
+        launch_fill_f32(dh2, n * H, 0.0f, s);
+        if (lstm) {
+            launch_fill_f32(dc, n * H, 0.0f, s);
+            launch_fill_f32(dc2, n * H, 0.0f, s);
+        }
+    }
     const float *dc_in = nullptr;
     const float *nof = nullptr;
     std::vector<const float *> s1(L), q(L), ah(L);
@@ -941,19 +975,24 @@ int reinc_backward_window_integrated(reinc_ctx *ctx, int32_t t0, int32_t L, cons
             const Snapshot &sn = ctx->snaps[t0 + i];
             const LocalStep &st = ctx->local[i];
             const LocalStep *pv = i ? &ctx->local[i - 1] : nullptr;
+            const int64_t ni = rows_of[size_t(i)];
             float *dgi_i = dgi + int64_t(i - lo) * n * KH, *dgh_i = dgh + int64_t(i - lo) * n * KH;
-            rnn_backward_elem(ctx, s, lstm, n, H, (const float *)dh, dc_in, (const float *)st.saved,
+            rnn_backward_elem(ctx, s, lstm, ni, H, (const float *)dh, dc_in, (const float *)st.saved,
                               pv ? (const float *)pv->h : nof, pv ? (const float *)pv->c : nof, (const float *)st.c, dgi_i, dgh_i,
                               dh2, dc2);
             if (i > 0) {
                 // gradient w.r.t. Agg(h_{t-1}), then through the adjoint of the aggregation, plus the carry path
-                gemm_rows(ctx, s, (const void *)dgh_i, 0, n, KH, H, nof, W_h, 1, KH, nof, 0, nof, nof, dah);
+                const int64_t np = rows_of[size_t(i - 1)];  // rows of h_{t-1} that exist: the output rows of the adjoint
+                gemm_rows(ctx, s, (const void *)dgh_i, 0, ni, KH, H, nof, W_h, 1, KH, nof, 0, nof, nof, dah);
                 AggBatch batch;
                 batch.count = 1;
                 batch.item[0] = AggItem{sn.col_ptr, sn.row, dah, sn.q, sn.p, nullptr, lstm ? nof : (const float *)dh2, dh,
                                         sn.long_cols, sn.n_long_cols};
-                batch.item[0].order = sn.col_order;
-                aggregate_full_batch(ctx, batch, 0, H, c.self_loop, s);
+                if (np < n)
+                    batch.item[0].row_limit = np;
+                else
+                    batch.item[0].order = sn.col_order;
+                aggregate_full_batch(ctx, batch, 0, H, c.self_loop, s, np);
                 if (lstm) {
                     std::swap(dc, dc2);
                     dc_in = dc;
@@ -968,6 +1007,19 @@ int reinc_backward_window_integrated(reinc_ctx *ctx, int32_t t0, int32_t L, cons
         const bool has_q = q[lo] != nullptr;
         const int acc0 = first_batch ? 0 : 1;
         int calls = 0;
+        if (part) {
+            // every timestep has its own row count: one reduction each, over the rows that exist
+            for (int32_t i = lo; i <= hi; ++i, ++calls) {
+                const int64_t ni = rows_of[size_t(i)];
+                gemm_reduce(ctx, s, s1[i], d0, q[i], (const float *)(dgi + int64_t(i - lo) * n * KH), KH, ni, rowsB, d0, KH, part_wi,
+                            acc0 | (calls > 0));
+                gemm_reduce(ctx, s, ah[i], H, nof, (const float *)(dgh + int64_t(i - lo) * n * KH), KH, ni, rowsB, H, KH, part_wh,
+                            acc0 | (calls > 0));
+            }
+            first_batch = false;
+            hi = lo - 1;
+            continue;
+        }
         REINC_TRY(for_runs(lo, hi, n, {Strip{s1.data(), d0}, Strip{has_q ? q.data() : nullptr, 1}}, [&](int i0, int len) {
             gemm_reduce(ctx, s, s1[i0], d0, q[i0], (const float *)(dgi + int64_t(i0 - lo) * n * KH), KH, n * len, rowsB, d0, KH,
                         part_wi, acc0 | (calls++ > 0));

@@ -277,9 +277,10 @@ def test_error_paths():
 
 def test_integrated_model_on_a_batch_context_reads_every_row():
     """After a stacked window the cached layer-1 sums of a batch context hold the rows that layer 1 needs; the integrated
-    model aggregates the hidden state of every node of the sub-sequence, so its window drops them and computes whole
-    ones: h on every row against the reference model run on the extracted graphs (sum aggregation: no scales carried
-    over from the whole graph)."""
+    model's first timestep needs more of them (here every row: three timesteps on a two-hop sub-sequence), so its window
+    drops the short sums and computes longer ones: h against the reference model run on the extracted graphs (sum
+    aggregation: no scales carried over from the whole graph), on the batch rows, and on every row once the loss rows
+    are taken back."""
     import dataclasses
     import torch
 
@@ -306,11 +307,16 @@ def test_integrated_model_on_a_batch_context_reads_every_row():
     feats = [oracle_feats(seq, t)[node_list] for t in range(L)]
     p = synth.split_params(wli, flat_i.astype(np.float64))
     _, ref_h, _ = oracle.forward_window_integrated(graphs[:L], feats, p, wl.agg, wl.self_loop, wl.rnn, None)
-    assert_close(h_last.cpu().numpy(), ref_h, RTOL_FP32, "integrated h_last on a batch context")
+    # (the last timestep exists on the batch rows only; with the loss rows taken back every row is computed)
+    assert_close(h_last.cpu().numpy()[:nb], ref_h[:nb], RTOL_FP32, "integrated h_last on a batch context")
     # and the stacked model afterwards finds whole cached sums, of which it reads its rows: the same batch rows as before
     child.forward_window(0, L, flat, h_last=h_stacked)
     torch.cuda.synchronize()
     assert_close(h_stacked[:nb].cpu().numpy(), first.cpu().numpy(), 1e-6, "stacked h_last after the integrated window")
+    child.set_loss_rows(0)
+    child.forward_window_integrated(0, L, _dev(flat_i), h_last=h_last)
+    torch.cuda.synchronize()
+    assert_close(h_last.cpu().numpy(), ref_h, RTOL_FP32, "integrated h_last on every row of the sub-sequence")
     child.close()
     ctx.close()
 
@@ -328,7 +334,14 @@ def test_integrated_model_on_a_batch_of_one_hop_per_timestep(mode, rnn):
     seq, ctx = _parent(wl)
     n, T, L, H = wl.num_nodes, wl.num_snapshots, 3, wl.hidden
     batch = np.random.default_rng(3).choice(n, 24, replace=False).astype(np.int32)
-    child = ctx.batch_context(batch, 1 << 28, hops=L)
+    # (the library computes timestep i of the window on the nodes within L - 1 - i hops of the batch only: the batch
+    # context's memory starts out as NaN, so that a read of a row that no timestep computes shows)
+    from paper_2501_15348_amd import reinc
+
+    total, _ = ctx.batch_plan(batch, hops=L)
+    child = reinc.Context(total, ctx.T, ctx.dims, ctx.rnn, ctx.hidden, mode, True, "fp32", arena_bytes=1 << 28)
+    child.arena[:child.arena.numel() // 4 * 4].view(torch.float32).fill_(float("nan"))
+    ctx._ck(ctx.lib.reinc_batch_load(ctx.handle, child.handle))
     node_list = ctx.batch_node_list(child.n)
     reach = [len(f) for f in minibatch.closure(seq.edges, batch, L)]
     assert all(a < b for a, b in zip(reach, reach[1:])) and reach[-1] == child.n < n, reach
