@@ -141,6 +141,31 @@ def test_bench_workload_c2_full():
     for name, _ in synth.param_shapes(wl):
         assert_close(got[name], ref_gb[name], GRAD_RTOL_FP32, f"mini-batch grad {name}")
     child.close()
+    # the integrated model on a batch planned with one hop per timestep of its window (Section 2.1, Section 4.2)
+    import dataclasses
+
+    wli = dataclasses.replace(wl, dims=(wl.dims[0],))
+    flat_i = synth.make_params(wli, bias_scale=0.1)
+    pi = synth.split_params(wli, flat_i.astype(np.float64))
+    small = batch[:200]
+    print(f"[{wl.name}] integrated model on a node mini-batch of {small.size}, two hops", flush=True)
+    child = ctx.batch_context(small, 2 << 30, hops=2)
+    node_list = ctx.batch_node_list(child.n)
+    child.build_deltas(-1)
+    params_i, grads_i = torch.from_numpy(flat_i).cuda(), torch.empty(flat_i.size, device="cuda")
+    tgt_b = torch.from_numpy(target[node_list]).cuda()
+    hb = torch.empty((child.n, wl.hidden), device="cuda")
+    child.forward_window_integrated(1, 2, params_i, tgt_b, loss, hb)
+    child.backward_window_integrated(1, 2, params_i, tgt_b, grads_i)
+    ref_loss_i, ref_hi, saved_i = oracle.forward_window_integrated(graphs[1:3], feats[:2], pi, wl.agg, wl.self_loop, wl.rnn, target,
+                                                                   keep=True, loss_rows=small)
+    assert_close(hb.cpu().numpy()[:small.size], ref_hi[small], RTOL_FP32, "integrated mini-batch h_last")
+    assert abs(loss.item() - ref_loss_i) <= RTOL_FP32 * abs(ref_loss_i)
+    ref_gi = oracle.backward_window_integrated(graphs[1:3], saved_i, ref_hi, pi, wl.agg, wl.self_loop, wl.rnn, target, loss_rows=small)
+    got = synth.split_params(wli, grads_i.cpu().numpy())
+    for name, _ in synth.param_shapes(wli):
+        assert_close(got[name], ref_gi[name], GRAD_RTOL_FP32, f"integrated mini-batch grad {name}")
+    child.close()
     ctx.close()
 
 
